@@ -1,0 +1,333 @@
+/*
+ * lutkan_oracle.c -- plain CPU oracle for LUT-KAN (arxiv 2601.03332).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, obviously-correct statement of what the
+ * layer forward computes.  It is compiled on its own (gcc -O2 -ffp-contract=off), shares no
+ * header, table, helper or constant with the HIP library, and is only ever called by the
+ * tests, the smoke check and the CPU-baseline leg of the benchmark.  The product path never
+ * routes through it.
+ *
+ * Every function follows the paper's equations in the paper's order and notation:
+ *   - B-spline basis by the Cox--de Boor recursion        (Sec. 3.2, Eq. 4-5), in fp64
+ *   - per-segment half-open sampling                      (Sec. 4.2, Eq. 7)
+ *   - symmetric int8 / asymmetric uint8 quantisation      (Sec. 4.4, Eq. 11-12), in fp32
+ *   - affine dequantisation                               (Sec. 4.4, Eq. 10)
+ *   - the five inference steps                            (Sec. 4.5, Eq. 13-17), in fp32
+ *   - boundary_mode and oob_policy                        (Sec. 5.2-5.4)
+ *   - the dense layer sum y_j = sum_i phi_ij(x_i)         (Sec. 3.1, Eq. 1), accumulated in fp64
+ *
+ * Readings taken where the paper is silent (each one is also a unit test):
+ *   - the edge function is the pure spline branch, phi_ij == s_ij (value_repr = phi, no base branch);
+ *   - the LUT knots are the G+1 domain breakpoints tau[p..p+G] of the extended knot vector, K = G;
+ *   - the spline is sampled in fp64 and rounded once to fp32; quantisation runs in fp32 with one
+ *     rounding per operation and round-half-to-even for the code;
+ *   - a segment with zero range stores alpha = 1 and all codes 0;
+ *   - a NaN input is out of domain, is indexed like t_0, and makes every output of its row NaN
+ *     under either oob_policy;
+ *   - the B-spline layer applies the same boundary_mode / oob_policy to x before evaluating.
+ *
+ * Parity pins: all functions here are pinned by closed forms, invariants, a library routine
+ * (scipy.interpolate.BSpline, numpy.searchsorted) and brute force in tests/test_oracle_*.py.
+ * The paper's absolute error / latency tables depend on a PyKAN initialisation that is not
+ * available: parity with those numbers is unpinned (only their trend in L is checked).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { LKO_SYM_INT8 = 0, LKO_ASYM_UINT8 = 1 };
+enum { LKO_HALF_OPEN = 0, LKO_CLOSED = 1 };
+enum { LKO_CLIP_X = 0, LKO_ZERO_SPLINE = 1 };
+
+/* ------------------------------------------------------------------------------------------
+ * Cox--de Boor recursion (Eq. 4-5).  tau[0..n-1] is the knot vector, N has room for n-1 values.
+ * On return N[r] = B_{r,p}(x) for r = 0..n-2-p.  Degree 0 is the half-open indicator; a term
+ * whose knot span has zero length is 0 (the 0/0 = 0 convention); left term first, then right.
+ * ---------------------------------------------------------------------------------------- */
+void lko_bspline_basis(const double *tau, int n, int p, double x, double *N)
+{
+    for (int r = 0; r < n - 1; ++r)
+        N[r] = (tau[r] <= x && x < tau[r + 1]) ? 1.0 : 0.0;
+    for (int q = 1; q <= p; ++q) {
+        for (int r = 0; r < n - 1 - q; ++r) {
+            double dl = tau[r + q] - tau[r];
+            double dr = tau[r + q + 1] - tau[r + 1];
+            double left = (dl != 0.0) ? (x - tau[r]) / dl * N[r] : 0.0;
+            double right = (dr != 0.0) ? (tau[r + q + 1] - x) / dr * N[r + 1] : 0.0;
+            N[r] = left + right;
+        }
+    }
+}
+
+/* Spline branch s(x) = sum_{r=0}^{R-1} c_r B_{r,p}(x) (Eq. 3), r ascending, fp64. */
+double lko_spline_value(const float *tau_f, int G, int p, const float *coef, double x)
+{
+    int n = G + 2 * p + 1, R = G + p;
+    double tau[n], N[n];
+    for (int r = 0; r < n; ++r) tau[r] = (double)tau_f[r];
+    lko_bspline_basis(tau, n, p, x, N);
+    double s = 0.0;
+    for (int r = 0; r < R; ++r) s += (double)coef[r] * N[r];
+    return s;
+}
+
+/* Sampling position x_{k,l} = t_k + l * Delta_k, Delta_k = (t_{k+1}-t_k)/L (Eq. 7), fp64 from fp32 knots. */
+double lko_sample_x(const float *T, int L, int k, int l)
+{
+    double delta = ((double)T[k + 1] - (double)T[k]) / (double)L;
+    return (double)T[k] + (double)l * delta;
+}
+
+/* Quantise one segment's L float samples (Eq. 11-12).  q is int8_t[L] or uint8_t[L]. */
+void lko_quantize_segment(const float *v, int L, int scheme, void *q, float *alpha, float *y_min)
+{
+    if (scheme == LKO_SYM_INT8) {
+        int8_t *qs = (int8_t *)q;
+        float amax = 0.0f;
+        for (int l = 0; l < L; ++l) { float a = fabsf(v[l]); if (a > amax) amax = a; }
+        *y_min = 0.0f;
+        if (amax == 0.0f) { *alpha = 1.0f; for (int l = 0; l < L; ++l) qs[l] = 0; return; }
+        float a = amax / 127.0f;
+        *alpha = a;
+        for (int l = 0; l < L; ++l) {
+            float r = rintf(v[l] / a);
+            if (r > 127.0f) r = 127.0f;
+            if (r < -127.0f) r = -127.0f;
+            qs[l] = (int8_t)r;
+        }
+    } else {
+        uint8_t *qu = (uint8_t *)q;
+        float lo = v[0], hi = v[0];
+        for (int l = 1; l < L; ++l) { if (v[l] < lo) lo = v[l]; if (v[l] > hi) hi = v[l]; }
+        *y_min = lo;
+        if (hi == lo) { *alpha = 1.0f; for (int l = 0; l < L; ++l) qu[l] = 0; return; }
+        float range = hi - lo;
+        float a = range / 255.0f;
+        *alpha = a;
+        for (int l = 0; l < L; ++l) {
+            float t = v[l] - lo;
+            float r = rintf(t / a);
+            if (r > 255.0f) r = 255.0f;
+            if (r < 0.0f) r = 0.0f;
+            qu[l] = (uint8_t)r;
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Compile one dense layer into the artifact arrays of Sec. 4.6:
+ *   knots[K+1], q[E][K][L] (e = i*m + j), scale[E][K], y_min[E][K];  v_out (nullable) gets the
+ *   unquantised fp32 samples v_{e,k,l}.
+ * The basis values at the K*L sampling positions depend only on the shared knot vector, so they
+ * are evaluated once and reused by every edge; each edge value is still the sum of Eq. 3.
+ * ---------------------------------------------------------------------------------------- */
+int lko_compile(int d, int m, int G, int p, const float *tau_f, const float *coef, int L, int scheme,
+                void *q, float *scale, float *y_min, float *knots, float *v_out, int nthreads)
+{
+    if (d < 1 || m < 1 || G < 1 || p < 0 || L < 2) return -1;
+    int n = G + 2 * p + 1, R = G + p, K = G;
+    for (int r = 0; r + 1 < n; ++r) if (!(tau_f[r] < tau_f[r + 1])) return -2;
+    for (int k = 0; k <= K; ++k) knots[k] = tau_f[p + k];
+    double *tau = (double *)malloc(sizeof(double) * n);
+    double *Bs = (double *)malloc(sizeof(double) * (size_t)K * L * n);
+    if (!tau || !Bs) { free(tau); free(Bs); return -3; }
+    for (int r = 0; r < n; ++r) tau[r] = (double)tau_f[r];
+    for (int k = 0; k < K; ++k)
+        for (int l = 0; l < L; ++l)
+            lko_bspline_basis(tau, n, p, lko_sample_x(knots, L, k, l), Bs + ((size_t)k * L + l) * n);
+    long E = (long)d * m;
+    (void)nthreads;
+#pragma omp parallel for num_threads(nthreads > 0 ? nthreads : 1) schedule(static)
+    for (long e = 0; e < E; ++e) {
+        float v[L];
+        const float *c = coef + (size_t)e * R;
+        for (int k = 0; k < K; ++k) {
+            for (int l = 0; l < L; ++l) {
+                const double *N = Bs + ((size_t)k * L + l) * n;
+                double s = 0.0;
+                for (int r = 0; r < R; ++r) s += (double)c[r] * N[r];
+                v[l] = (float)s;
+            }
+            if (v_out) memcpy(v_out + ((size_t)e * K + k) * L, v, sizeof(float) * L);
+            lko_quantize_segment(v, L, scheme, (char *)q + ((size_t)e * K + k) * L,
+                                 scale + (size_t)e * K + k, y_min + (size_t)e * K + k);
+        }
+    }
+    free(tau);
+    free(Bs);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Steps 1-4 of Sec. 4.5 plus the domain predicate of Sec. 5.2 for one scalar input, all fp32.
+ * ---------------------------------------------------------------------------------------- */
+typedef struct { int32_t k, l0, l1; float w, xc; uint8_t in; uint8_t is_nan; } lko_index;
+
+void lko_locate(const float *T, int K, int L, int boundary, float x, lko_index *o)
+{
+    float t0 = T[0], tK = T[K];
+    o->is_nan = (x != x);
+    /* In(x): half_open t_0 <= x < t_K ; closed t_0 <= x <= t_K */
+    o->in = (boundary == LKO_CLOSED) ? (uint8_t)(x >= t0 && x <= tK) : (uint8_t)(x >= t0 && x < tK);
+    /* Step 1: x' = min(max(x, t_0), t_K*) */
+    float tKs = (boundary == LKO_CLOSED) ? tK : nextafterf(tK, -INFINITY);
+    float xc = x;
+    if (o->is_nan) xc = t0;
+    if (xc < t0) xc = t0;
+    if (xc > tKs) xc = tKs;
+    o->xc = xc;
+    /* Step 2: k = searchsorted(T, x', right) - 1 = #{kappa : T[kappa] <= x'} - 1, clipped to [0, K-1] */
+    int cnt = 0;
+    for (int kappa = 0; kappa <= K; ++kappa) if (T[kappa] <= xc) ++cnt;
+    int k = cnt - 1;
+    if (k < 0) k = 0;
+    if (k > K - 1) k = K - 1;
+    o->k = k;
+    /* Step 3: u = (x' - t_k) / (t_{k+1} - t_k) */
+    float num = xc - T[k];
+    float den = T[k + 1] - T[k];
+    float u = num / den;
+    /* Step 4: z = u (L-1), l0 = floor(z), l1 = min(l0+1, L-1), w = z - l0 */
+    float z = u * (float)(L - 1);
+    int l0 = (int)floorf(z);
+    if (l0 > L - 1) l0 = L - 1;
+    if (l0 < 0) l0 = 0;
+    o->l0 = l0;
+    o->l1 = (l0 + 1 < L - 1) ? l0 + 1 : L - 1;
+    o->w = z - (float)l0;
+}
+
+static inline float lko_code(const void *q, int scheme, size_t idx)
+{
+    return (scheme == LKO_SYM_INT8) ? (float)((const int8_t *)q)[idx] : (float)((const uint8_t *)q)[idx];
+}
+
+/* Step 5 (Eq. 17) with Eq. 10 for both neighbours; fp32, one rounding per operation. */
+float lko_edge_value(const void *q, int scheme, size_t seg_base, int l0, int l1, float w, float alpha, float y_min)
+{
+    float q0 = lko_code(q, scheme, seg_base + (size_t)l0);
+    float q1 = lko_code(q, scheme, seg_base + (size_t)l1);
+    float a0 = alpha * q0;
+    float v0 = y_min + a0;
+    float a1 = alpha * q1;
+    float v1 = y_min + a1;
+    float omw = 1.0f - w;
+    float p0 = omw * v0;
+    float p1 = w * v1;
+    return p0 + p1;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * LUT layer forward (Sec. 3.1 Eq. 1 over Sec. 4.5 and Sec. 5).
+ *   x[B][d] fp32 -> y[B][m] fp32 (fp64 accumulation over i, ascending, one final rounding).
+ * Optional outputs (nullable): A[B][m] = sum_i |phi_ij| (fp64, the tolerance denominator),
+ *   k_out/l0_out/in_out/w_out [B][d], q01_out[B][d][m][2] (the two gathered codes per edge),
+ *   stats[2] = { number of (row,input) pairs out of domain, number of rows with any such input }.
+ * ---------------------------------------------------------------------------------------- */
+int lko_lut_forward(int d, int m, int K, int L, int scheme, int boundary, int oob,
+                    const float *knots, const void *q, const float *scale, const float *y_min,
+                    const float *x, long B, float *y, double *A,
+                    int32_t *k_out, int32_t *l0_out, uint8_t *in_out, float *w_out, int16_t *q01_out,
+                    uint64_t *stats, int nthreads)
+{
+    if (d < 1 || m < 1 || K < 1 || L < 2 || B < 0) return -1;
+    uint64_t oob_count = 0, oob_rows = 0;
+    (void)nthreads;
+#pragma omp parallel for num_threads(nthreads > 0 ? nthreads : 1) schedule(static) reduction(+ : oob_count, oob_rows)
+    for (long b = 0; b < B; ++b) {
+        double acc[m], absacc[m];
+        for (int j = 0; j < m; ++j) { acc[j] = 0.0; absacc[j] = 0.0; }
+        int any = 0;
+        for (int i = 0; i < d; ++i) {
+            lko_index ix;
+            lko_locate(knots, K, L, boundary, x[(size_t)b * d + i], &ix);
+            if (!ix.in) { ++oob_count; any = 1; }
+            if (k_out) k_out[(size_t)b * d + i] = ix.k;
+            if (l0_out) l0_out[(size_t)b * d + i] = ix.l0;
+            if (in_out) in_out[(size_t)b * d + i] = ix.in;
+            if (w_out) w_out[(size_t)b * d + i] = ix.w;
+            for (int j = 0; j < m; ++j) {
+                size_t e = (size_t)i * m + j;
+                size_t seg = (e * K + (size_t)ix.k) * L;
+                float v = lko_edge_value(q, scheme, seg, ix.l0, ix.l1, ix.w, scale[e * K + ix.k], y_min[e * K + ix.k]);
+                if (q01_out) {
+                    size_t o = (((size_t)b * d + i) * m + j) * 2;
+                    q01_out[o] = (int16_t)lko_code(q, scheme, seg + ix.l0);
+                    q01_out[o + 1] = (int16_t)lko_code(q, scheme, seg + ix.l1);
+                }
+                float phi = (oob == LKO_ZERO_SPLINE && !ix.in) ? 0.0f : v;   /* Sec. 5.4 */
+                if (ix.is_nan) phi = NAN;
+                acc[j] += (double)phi;
+                absacc[j] += fabs((double)phi);
+            }
+        }
+        oob_rows += (uint64_t)any;
+        for (int j = 0; j < m; ++j) {
+            y[(size_t)b * m + j] = (float)acc[j];
+            if (A) A[(size_t)b * m + j] = absacc[j];
+        }
+    }
+    if (stats) { stats[0] = oob_count; stats[1] = oob_rows; }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * B-spline layer forward (the same-backend baseline of Sec. 3.3 / 6.4): the exact spline of
+ * Eq. 3 in fp64 at the safely clipped input x', masked by the same oob_policy, summed over i.
+ * A[B][m] (nullable) = sum_i sum_r |c_r| B_{r,p}(x'_i) over unmasked inputs.
+ * ---------------------------------------------------------------------------------------- */
+int lko_bspline_forward(int d, int m, int G, int p, const float *tau_f, const float *coef,
+                        int boundary, int oob, const float *x, long B, float *y, double *A, int nthreads)
+{
+    if (d < 1 || m < 1 || G < 1 || p < 0 || B < 0) return -1;
+    int n = G + 2 * p + 1, R = G + p, K = G;
+    double tau[n];
+    float T[K + 1];
+    for (int r = 0; r < n; ++r) tau[r] = (double)tau_f[r];
+    for (int k = 0; k <= K; ++k) T[k] = tau_f[p + k];
+    (void)nthreads;
+#pragma omp parallel for num_threads(nthreads > 0 ? nthreads : 1) schedule(static)
+    for (long b = 0; b < B; ++b) {
+        double acc[m], absacc[m], N[n];
+        for (int j = 0; j < m; ++j) { acc[j] = 0.0; absacc[j] = 0.0; }
+        for (int i = 0; i < d; ++i) {
+            lko_index ix;
+            lko_locate(T, K, 2, boundary, x[(size_t)b * d + i], &ix);
+            lko_bspline_basis(tau, n, p, (double)ix.xc, N);
+            int masked = (oob == LKO_ZERO_SPLINE && !ix.in);
+            for (int j = 0; j < m; ++j) {
+                const float *c = coef + ((size_t)i * m + j) * R;
+                double s = 0.0, sa = 0.0;
+                for (int r = 0; r < R; ++r) { s += (double)c[r] * N[r]; sa += fabs((double)c[r]) * N[r]; }
+                if (masked) { s = 0.0; sa = 0.0; }
+                if (ix.is_nan) { s = NAN; sa = NAN; }
+                acc[j] += s;
+                absacc[j] += sa;
+            }
+        }
+        for (int j = 0; j < m; ++j) {
+            y[(size_t)b * m + j] = (float)acc[j];
+            if (A) A[(size_t)b * m + j] = absacc[j];
+        }
+    }
+    return 0;
+}
+
+/* Bytes of the artifact arrays of Sec. 4.6 for E edges: codes + dequantisation parameters + knots. */
+long lko_artifact_bytes(long E, int K, int L, int param_bytes_per_segment)
+{
+    return E * ((long)K * L + (long)param_bytes_per_segment * K) + 4L * (K + 1);
+}
+
+int lko_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

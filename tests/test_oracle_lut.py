@@ -1,0 +1,384 @@
+"""Pins for the oracle's LUT compile + forward (Sec. 4.2-4.5, Sec. 5) against facts the paper and
+the arithmetic fix: sampling positions, code-range invariants, the boundary special cases stated in
+the text, numpy.searchsorted, closed forms for constant and linear edge functions, brute force on a
+tiny layer, and the trend in L of Table 1.
+"""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import ASYM_UINT8, CLIP_X, CLOSED, HALF_OPEN, SYM_INT8, ZERO_SPLINE
+from lutkan_inputs import cfg1, nonuniform_ext_knots, random_layer, uniform_ext_knots
+
+P = 3
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _greville(tau):
+    t = tau.astype(np.float64)
+    return np.array([(t[r + 1] + t[r + 2] + t[r + 3]) / 3.0 for r in range(tau.size - P - 1)])
+
+
+def _compile_spec(s, want_v=False):
+    return oracle.compile_layer(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, want_v=want_v)
+
+
+# ---------------------------------------------------------------- sampling (Eq. 7)
+def test_sampling_positions():
+    T = uniform_ext_knots(-1.0, 1.0, 5)[P:P + 6]
+    for L in (2, 16, 64):
+        for k in range(5):
+            assert oracle.sample_x(T, L, k, 0) == float(T[k])                      # x_{k,0} = t_k exactly
+            delta = (float(T[k + 1]) - float(T[k])) / L
+            last = oracle.sample_x(T, L, k, L - 1)
+            assert abs(last - (float(T[k + 1]) - delta)) <= 1e-15                  # x_{k,L-1} = t_{k+1} - Delta_k
+            assert last < float(T[k + 1])                                          # right end never sampled
+
+
+def test_compiled_samples_are_the_spline_at_the_sampling_positions():
+    w = random_layer(3, 2, 3, 6, 8, SYM_INT8, CLOSED, CLIP_X, B=4, uniform=False)
+    s = w.layers[0]
+    art = _compile_spec(s, want_v=True)
+    np.testing.assert_array_equal(art.knots, s.ext_knots[P:P + s.G + 1])
+    for e in range(s.d * s.m):
+        i, j = divmod(e, s.m)
+        for k in range(s.G):
+            for l in range(s.L):
+                xs = oracle.sample_x(art.knots, s.L, k, l)
+                assert art.v[e, k, l] == np.float32(oracle.spline_value(s.ext_knots, P, s.coef[i, j], xs))
+
+
+# ---------------------------------------------------------------- quantisation (Eq. 10-12)
+@pytest.mark.parametrize("scheme", [SYM_INT8, ASYM_UINT8])
+def test_quantisation_invariants(scheme):
+    rng = np.random.Generator(np.random.PCG64(21))
+    for trial in range(200):
+        L = int(rng.choice([2, 3, 16, 64, 128]))
+        v = (rng.normal(size=L) * 10.0 ** rng.uniform(-3, 2) + rng.normal() * (trial % 3)).astype(np.float32)
+        q, a, y0 = oracle.quantize_segment(v, scheme)
+        deq = (np.float32(y0) + np.float32(a) * q.astype(np.float32)).astype(np.float32)
+        assert a > 0
+        # each dequantised sample is within half a step (plus a rounding) of the float sample
+        assert np.all(np.abs(deq.astype(np.float64) - v) <= 0.5 * float(a) * (1 + 1e-5) + 1e-30)
+        if scheme == SYM_INT8:
+            assert y0 == 0.0 and q.dtype == np.int8
+            assert q.min() >= -127 and q.max() <= 127                       # -128 is never produced
+            assert abs(int(q[np.argmax(np.abs(v))])) == 127                 # the arg-max |v| sample saturates
+            np.testing.assert_allclose(float(a), float(np.abs(v).max()) / 127.0, rtol=1e-6)
+        else:
+            assert q.dtype == np.uint8
+            assert y0 == v.min()                                            # y_min = min_l v exactly
+            assert q[np.argmin(v)] == 0 and q[np.argmax(v)] == 255
+            np.testing.assert_allclose(float(a), (float(v.max()) - float(v.min())) / 255.0, rtol=1e-6)
+
+
+def test_symmetric_codes_negate_with_the_values():
+    rng = np.random.Generator(np.random.PCG64(22))
+    v = rng.normal(size=64).astype(np.float32)
+    q, a, _ = oracle.quantize_segment(v, SYM_INT8)
+    qn, an, _ = oracle.quantize_segment(-v, SYM_INT8)
+    np.testing.assert_array_equal(qn, -q)
+    assert a == an
+
+
+@pytest.mark.parametrize("scheme", [SYM_INT8, ASYM_UINT8])
+def test_zero_range_segment(scheme):
+    for c in (0.0, 1.25, -3.0):
+        v = np.full(16, c, dtype=np.float32)
+        q, a, y0 = oracle.quantize_segment(v, scheme)
+        deq = np.float32(y0) + np.float32(a) * q.astype(np.float32)
+        if scheme == ASYM_UINT8 or c == 0.0:
+            assert a == 1.0 and np.all(q == 0)                              # degenerate range: alpha = 1, codes 0
+            assert np.all(deq == np.float32(c))
+        else:
+            assert np.all(np.abs(q) == 127)                                 # symmetric constant: +-127 * (|c|/127)
+            assert np.all(np.abs(deq - np.float32(c)) <= np.spacing(np.float32(abs(c))))
+
+
+def test_round_half_to_even():
+    # values at exactly k + 0.5 steps of alpha = 1 (max = 255): codes go to the even neighbour
+    v = np.array([0.0, 0.5, 1.5, 2.5, 3.5, 255.0], dtype=np.float32)
+    q, a, y0 = oracle.quantize_segment(v, ASYM_UINT8)
+    assert a == 1.0 and y0 == 0.0
+    np.testing.assert_array_equal(q, [0, 0, 2, 2, 4, 255])
+    v = np.array([0.5, -0.5, 1.5, -2.5, 127.0], dtype=np.float32)
+    q, a, _ = oracle.quantize_segment(v, SYM_INT8)
+    assert a == 1.0
+    np.testing.assert_array_equal(q, [0, 0, 2, -2, 127])
+
+
+def test_artifact_bytes_matches_table9():
+    rows = [l.split() for l in open(os.path.join(GOLD, "table9_artifact_bytes.txt")) if l[0] != "#"]
+    total = 0
+    for E, K, L, nbytes in rows:
+        got = oracle.artifact_bytes(int(E), int(K), int(L), 4)
+        assert got == int(nbytes)
+        total += got
+    assert total == 2262096                                                   # "LUT Total" row of Table 9
+    art = _compile_spec(cfg1().layers[0])
+    assert art.q.nbytes + art.scale.nbytes + art.y_min.nbytes + art.knots.nbytes == oracle.artifact_bytes(12, 5, 16, 8)
+
+
+# ---------------------------------------------------------------- indexing (Eq. 13-16, Sec. 5.2-5.3)
+def _one_edge_art(tau, L, scheme, coef=None):
+    G = tau.size - 2 * P - 1
+    if coef is None:
+        coef = np.random.Generator(np.random.PCG64(31)).normal(size=G + P)
+    return oracle.compile_layer(1, 1, G, P, tau, np.asarray(coef, dtype=np.float32), L, scheme)
+
+
+@pytest.mark.parametrize("uniform", [True, False])
+@pytest.mark.parametrize("L", [2, 16, 33, 64])
+def test_special_points(uniform, L):
+    rng = np.random.Generator(np.random.PCG64(5))
+    tau = uniform_ext_knots(-1.0, 1.0, 5) if uniform else nonuniform_ext_knots(rng, -1.0, 1.0, 5)
+    art = _one_edge_art(tau, L, SYM_INT8)
+    T, K = art.knots, art.K
+    for boundary in (HALF_OPEN, CLOSED):
+        x = T[:K].reshape(-1, 1)
+        r = oracle.lut_forward(art, boundary, CLIP_X, x, trace=True)
+        np.testing.assert_array_equal(r.k[:, 0], np.arange(K))                 # x = t_k -> (k, 0, w=0)
+        assert np.all(r.l0 == 0) and np.all(r.w == 0) and np.all(r.inside == 1)
+        lo = np.array([[T[0] - 1.0], [np.nextafter(T[0], np.float32(-np.inf))], [-np.inf]], dtype=np.float32)
+        r = oracle.lut_forward(art, boundary, CLIP_X, lo, trace=True)
+        assert np.all(r.k == 0) and np.all(r.l0 == 0) and np.all(r.w == 0) and np.all(r.inside == 0)
+    tK = np.array([[T[K]]], dtype=np.float32)
+    r = oracle.lut_forward(art, CLOSED, CLIP_X, tK, trace=True)                  # Sec. 4.2: last index, last segment
+    assert (r.k[0, 0], r.l0[0, 0], r.w[0, 0], r.inside[0, 0]) == (K - 1, L - 1, 0.0, 1)
+    r = oracle.lut_forward(art, HALF_OPEN, CLIP_X, tK, trace=True)               # Sec. 5.5: OOB yet safely indexed
+    assert r.inside[0, 0] == 0 and r.k[0, 0] == K - 1 and r.l0[0, 0] <= L - 1 and r.oob_count == 1
+    below = np.nextafter(T[K], np.float32(-np.inf)).reshape(1, 1)
+    r2 = oracle.lut_forward(art, HALF_OPEN, CLIP_X, below, trace=True)
+    assert r2.inside[0, 0] == 1 and r2.y[0, 0] == r.y[0, 0] and r2.l0[0, 0] == r.l0[0, 0] and r2.w[0, 0] == r.w[0, 0]
+    hi = np.array([[T[K] + 0.5], [np.inf]], dtype=np.float32)
+    for boundary in (HALF_OPEN, CLOSED):
+        r = oracle.lut_forward(art, boundary, CLIP_X, hi, trace=True)
+        assert np.all(r.k == K - 1) and np.all(r.inside == 0)
+
+
+def _neighbourhood(v, n):
+    out = [np.float32(v)]
+    a = b = np.float32(v)
+    for _ in range(n):
+        a = np.nextafter(a, np.float32(-np.inf))
+        b = np.nextafter(b, np.float32(np.inf))
+        out += [a, b]
+    return np.array(sorted(out), dtype=np.float32)
+
+
+@pytest.mark.parametrize("uniform", [True, False])
+def test_segment_index_every_float_near_every_knot_vs_numpy_searchsorted(uniform):
+    rng = np.random.Generator(np.random.PCG64(6))
+    tau = uniform_ext_knots(-1.0, 1.0, 10) if uniform else nonuniform_ext_knots(rng, -2.0, 3.0, 7)
+    L = 64
+    art = _one_edge_art(tau, L, ASYM_UINT8)
+    T, K = art.knots, art.K
+    xs = np.concatenate([_neighbourhood(t, 300) for t in T] + [rng.uniform(T[0] - 1, T[K] + 1, 5000).astype(np.float32)])
+    for boundary in (HALF_OPEN, CLOSED):
+        r = oracle.lut_forward(art, boundary, CLIP_X, xs.reshape(-1, 1), trace=True)
+        tKs = T[K] if boundary == CLOSED else np.nextafter(T[K], np.float32(-np.inf))
+        xc = np.minimum(np.maximum(xs, T[0]), tKs)
+        k_ref = np.clip(np.searchsorted(T, xc, side="right") - 1, 0, K - 1)       # Eq. 14 via the library routine
+        np.testing.assert_array_equal(r.k[:, 0], k_ref)
+        inside_ref = (xs >= T[0]) & ((xs <= T[K]) if boundary == CLOSED else (xs < T[K]))
+        np.testing.assert_array_equal(r.inside[:, 0].astype(bool), inside_ref)
+        # the located segment really contains x' and (l0, w) reassemble z = u (L-1) within [0, L-1]
+        assert np.all(T[r.k[:, 0]] <= xc) and np.all((xc < T[r.k[:, 0] + 1]) | ((xc == T[K]) & (r.k[:, 0] == K - 1)))
+        z = r.l0[:, 0] + r.w[:, 0].astype(np.float64)
+        u = (xc.astype(np.float64) - T[r.k[:, 0]]) / (T[r.k[:, 0] + 1].astype(np.float64) - T[r.k[:, 0]])
+        assert np.all(np.abs(z - u * (L - 1)) <= 1e-4)
+        assert np.all((r.l0 >= 0) & (r.l0 <= L - 1) & (r.w >= 0) & (r.w < 1))
+        assert r.oob_count == int((~inside_ref).sum())
+
+
+def test_boundary_modes_differ_only_at_tK():
+    w = random_layer(9, 3, 2, 5, 16, SYM_INT8, CLOSED, CLIP_X, B=4096)
+    art = _compile_spec(w.layers[0])
+    tK = art.knots[-1]
+    a = oracle.lut_forward(art, CLOSED, CLIP_X, w.x, trace=True)
+    b = oracle.lut_forward(art, HALF_OPEN, CLIP_X, w.x, trace=True)
+    differs = a.inside != b.inside
+    assert differs.any()                                   # the generator plants exact t_K values
+    assert np.all(w.x[differs] == tK) and np.all((w.x == tK) == differs)
+
+
+# ---------------------------------------------------------------- interpolation + dequantisation (Eq. 10, 17)
+@pytest.mark.parametrize("scheme", [SYM_INT8, ASYM_UINT8])
+def test_w_zero_returns_the_dequantised_code_exactly(scheme):
+    tau = uniform_ext_knots(-1.0, 1.0, 4)            # h = 0.5: sample lookups with w = 0 are exact in fp32
+    L = 17                                            # L-1 = 16 so that u = l/16 is exact
+    art = _one_edge_art(tau, L, scheme)
+    T = art.knots
+    for k in range(4):
+        for l in range(L - 1):
+            x = np.float32(T[k] + np.float32(0.5) * np.float32(l / 16.0)).reshape(1, 1)
+            r = oracle.lut_forward(art, CLOSED, CLIP_X, x, trace=True, codes=True)
+            assert (r.k[0, 0], r.l0[0, 0], r.w[0, 0]) == (k, l, 0.0)
+            code = art.q[0, k, l]
+            assert r.q01[0, 0, 0, 0] == int(code)
+            assert r.y[0, 0] == np.float32(art.y_min[0, k] + np.float32(art.scale[0, k] * np.float32(code)))
+
+
+@pytest.mark.parametrize("scheme", [SYM_INT8, ASYM_UINT8])
+def test_output_lies_between_the_two_dequantised_neighbours(scheme):
+    w = random_layer(12, 1, 1, 6, 32, scheme, CLOSED, CLIP_X, B=3000, uniform=False)
+    art = _compile_spec(w.layers[0])
+    r = oracle.lut_forward(art, CLOSED, CLIP_X, w.x, trace=True, codes=True)
+    k = r.k[:, 0]
+    v0 = art.y_min[0, k] + art.scale[0, k] * r.q01[:, 0, 0, 0].astype(np.float32)
+    v1 = art.y_min[0, k] + art.scale[0, k] * r.q01[:, 0, 0, 1].astype(np.float32)
+    lo, hi = np.minimum(v0, v1), np.maximum(v0, v1)
+    tol = 2 * np.spacing(np.maximum(np.abs(lo), np.abs(hi)).astype(np.float32))
+    assert np.all(r.y[:, 0] >= lo - tol) and np.all(r.y[:, 0] <= hi + tol)
+    l1 = np.minimum(r.l0[:, 0] + 1, 31)
+    np.testing.assert_array_equal(r.q01[:, 0, 0, 0], art.q[0, k, r.l0[:, 0]].astype(np.int16))
+    np.testing.assert_array_equal(r.q01[:, 0, 0, 1], art.q[0, k, l1].astype(np.int16))
+
+
+@pytest.mark.parametrize("scheme", [SYM_INT8, ASYM_UINT8])
+def test_constant_edge_function(scheme):
+    tau = uniform_ext_knots(-1.0, 1.0, 5)
+    art = _one_edge_art(tau, 16, scheme, coef=np.full(8, 0.7))
+    x = np.linspace(-1.3, 1.3, 777, dtype=np.float32).reshape(-1, 1)
+    r = oracle.lut_forward(art, CLOSED, CLIP_X, x)
+    if scheme == ASYM_UINT8:
+        # partition of unity in fp64 may leave the samples a few ulp apart; the LUT is then exact to one code step
+        assert np.all(np.abs(r.y - np.float32(0.7)) <= 2 * np.spacing(np.float32(0.7)))
+    else:
+        assert np.all(np.abs(r.y - np.float32(0.7)) <= 4 * np.spacing(np.float32(0.7)))
+
+
+@pytest.mark.parametrize("uniform", [True, False])
+@pytest.mark.parametrize("L", [16, 64])
+def test_linear_edge_function_closed_form(uniform, L):
+    """Samples sit at u = l/L (Eq. 7) but are looked up at u = l/(L-1) (Eq. 16): on a linear edge function
+    f(x) = a x + c the table therefore returns f(t_k + u h_k (L-1)/L), up to the quantisation step."""
+    rng = np.random.Generator(np.random.PCG64(8))
+    tau = uniform_ext_knots(-1.0, 1.0, 5) if uniform else nonuniform_ext_knots(rng, -1.0, 1.0, 5)
+    a_, c_ = 1.75, -0.25
+    art = _one_edge_art(tau, L, ASYM_UINT8, coef=a_ * _greville(tau) + c_)
+    T = art.knots.astype(np.float64)
+    x = rng.uniform(-1.0, 1.0, 4000).astype(np.float32)
+    r = oracle.lut_forward(art, CLOSED, CLIP_X, x.reshape(-1, 1), trace=True)
+    k = r.k[:, 0]
+    h = T[k + 1] - T[k]
+    u = (x.astype(np.float64) - T[k]) / h
+    want = a_ * (T[k] + u * h * (L - 1) / L) + c_
+    step = art.scale[0, k].astype(np.float64)
+    assert np.all(np.abs(r.y[:, 0] - want) <= 0.5 * step + 1e-6)
+    # ... which is NOT f(x): the deviation is a u h_k / L (zero at the left knot, one sampling step at the right)
+    dev = np.abs(r.y[:, 0] - (a_ * x.astype(np.float64) + c_))
+    assert np.all(np.abs(dev - a_ * u * h / L) <= 0.5 * step + 1e-6)
+    assert dev.max() > 0.5 * a_ * h.min() / L
+
+
+def test_error_halves_per_doubling_of_L_like_table1():
+    w = random_layer(2, 10, 8, 8, 16, ASYM_UINT8, CLOSED, CLIP_X, B=4096, oob_frac=0.0)
+    s = w.layers[0]
+    x = np.clip(w.x, -1.0, 1.0)
+    exact = oracle.bspline_forward(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, CLOSED, CLIP_X, x).y.astype(np.float64)
+    for scheme, name in ((ASYM_UINT8, "asym"), (SYM_INT8, "sym")):
+        mae = []
+        for L in (16, 32, 64, 128):
+            art = oracle.compile_layer(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, L, scheme)
+            mae.append(np.abs(oracle.lut_forward(art, CLOSED, CLIP_X, x).y - exact).mean())
+        ours = np.array(mae[:-1]) / np.array(mae[1:])
+        rows = [l.split() for l in open(os.path.join(GOLD, "table1_mae_vs_L.txt")) if l[0] != "#" and l.startswith(name)]
+        paper = np.array([float(r[2]) for r in rows])
+        paper_ratio = paper[:-1] / paper[1:]
+        assert np.all(np.abs(paper_ratio - 2.0) < 0.15)                        # Table 1: ~2x per doubling
+        assert np.all(ours[:2] > 1.7) and np.all(ours[:2] < 2.3), ours          # same O(1/L) trend here
+        assert ours[2] > 1.4                                                    # quantisation floor starts to show
+
+
+# ---------------------------------------------------------------- OOB policies (Sec. 5.4)
+@pytest.mark.parametrize("scheme", [SYM_INT8, ASYM_UINT8])
+def test_oob_policies(scheme):
+    w = random_layer(4, 3, 4, 5, 16, scheme, CLOSED, CLIP_X, B=2000, oob_frac=0.3)
+    s = w.layers[0]
+    art = _compile_spec(s)
+    res = {(b, o): oracle.lut_forward(art, b, o, w.x, trace=True) for b in (HALF_OPEN, CLOSED) for o in (CLIP_X, ZERO_SPLINE)}
+    # rows whose inputs are all strictly inside: identical outputs under all four contracts
+    inside_all = np.all((w.x >= art.knots[0]) & (w.x < art.knots[-1]), axis=1)
+    assert inside_all.sum() > 50
+    base = res[(CLOSED, CLIP_X)].y[inside_all]
+    for r in res.values():
+        np.testing.assert_array_equal(r.y[inside_all], base)
+    # zero_spline: an OOB input contributes exactly 0; clip_x: x < t_0 contributes the dequantised code [k=0][l=0]
+    for b in (HALF_OPEN, CLOSED):
+        r = res[(b, ZERO_SPLINE)]
+        all_out = np.all(r.inside == 0, axis=1)
+        x_out = np.full((3, s.d), 7.5, dtype=np.float32)
+        x_out[1] = -7.5
+        x_out[2, ::2] = -np.inf
+        rz = oracle.lut_forward(art, b, ZERO_SPLINE, x_out)
+        assert np.all(rz.y == 0.0) and np.all(rz.A == 0.0) and rz.oob_any_rows == 3 and rz.oob_count == 3 * s.d
+        rc = oracle.lut_forward(art, b, CLIP_X, x_out[1:2])
+        want = np.zeros(s.m)
+        for i in range(s.d):
+            for j in range(s.m):
+                e = i * s.m + j
+                want[j] += float(np.float32(art.y_min[e, 0] + np.float32(art.scale[e, 0] * np.float32(art.q[e, 0, 0]))))
+        np.testing.assert_allclose(rc.y[0], want.astype(np.float32), rtol=1e-6)
+        assert r.oob_any_rows == int(np.any(r.inside == 0, axis=1).sum()) and all_out.sum() >= 0
+
+
+def test_nan_input_poisons_its_row_only():
+    w = random_layer(4, 3, 2, 5, 16, ASYM_UINT8, CLOSED, ZERO_SPLINE, B=8, oob_frac=0.0)
+    art = _compile_spec(w.layers[0])
+    x = w.x.copy()
+    x[2, 1] = np.nan
+    for oob in (CLIP_X, ZERO_SPLINE):
+        r = oracle.lut_forward(art, CLOSED, oob, x, trace=True)
+        assert np.isnan(r.y[2]).all() and np.isfinite(np.delete(r.y, 2, axis=0)).all()
+        assert (r.inside[2, 1], r.k[2, 1], r.l0[2, 1]) == (0, 0, 0)
+
+
+# ---------------------------------------------------------------- layer sum (Eq. 1)
+def test_tiny_layer_brute_force_from_single_edges():
+    """cfg-1-sized layer: y[b][j] must equal the fp64 sum over i of the single-edge (d=m=1) outputs."""
+    w = cfg1(seed=0, B=64)
+    s = w.layers[0]
+    art = _compile_spec(s)
+    full = oracle.lut_forward(art, s.boundary, s.oob, w.x)
+    want = np.zeros((64, s.m))
+    wantA = np.zeros((64, s.m))
+    for i in range(s.d):
+        for j in range(s.m):
+            e = i * s.m + j
+            one = oracle.compile_layer(1, 1, s.G, s.p, s.ext_knots, s.coef[i, j], s.L, s.scheme)
+            np.testing.assert_array_equal(one.q[0], art.q[e])
+            assert np.array_equal(one.scale[0], art.scale[e]) and np.array_equal(one.y_min[0], art.y_min[e])
+            ye = oracle.lut_forward(one, s.boundary, s.oob, w.x[:, i:i + 1]).y[:, 0].astype(np.float64)
+            want[:, j] += ye
+            wantA[:, j] += np.abs(ye)
+    np.testing.assert_array_equal(full.y, want.astype(np.float32))
+    np.testing.assert_allclose(full.A, wantA, rtol=1e-15)
+
+
+def test_rows_are_independent_and_threads_do_not_matter():
+    w = random_layer(15, 5, 7, 6, 32, ASYM_UINT8, HALF_OPEN, ZERO_SPLINE, B=257)
+    art = _compile_spec(w.layers[0])
+    a = oracle.lut_forward(art, HALF_OPEN, ZERO_SPLINE, w.x, nthreads=1)
+    perm = np.random.Generator(np.random.PCG64(1)).permutation(257)
+    b = oracle.lut_forward(art, HALF_OPEN, ZERO_SPLINE, w.x[perm], nthreads=4)
+    np.testing.assert_array_equal(a.y[perm], b.y)
+    assert a.oob_count == b.oob_count and a.oob_any_rows == b.oob_any_rows
+
+
+def test_lut_tracks_the_exact_spline_layer():
+    """End-to-end sanity: LUT layer vs the fp64 B-spline layer differ by O(h |f'| / L) + quantisation only."""
+    w = random_layer(17, 6, 5, 8, 128, ASYM_UINT8, CLOSED, CLIP_X, B=512, oob_frac=0.1)
+    s = w.layers[0]
+    art = _compile_spec(s)
+    lut = oracle.lut_forward(art, CLOSED, CLIP_X, w.x)
+    ref = oracle.bspline_forward(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, CLOSED, CLIP_X, w.x)
+    assert np.abs(lut.y - ref.y).max() < 6 * 0.02 and np.abs(lut.y - ref.y).mean() < 0.01
+    # zero_spline on the B-spline layer masks the same inputs
+    z_lut = oracle.lut_forward(art, CLOSED, ZERO_SPLINE, w.x)
+    z_ref = oracle.bspline_forward(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, CLOSED, ZERO_SPLINE, w.x)
+    assert np.abs(z_lut.y - z_ref.y).max() < 6 * 0.02
+    far = np.full((2, s.d), 9.0, dtype=np.float32)
+    assert np.all(oracle.bspline_forward(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, CLOSED, ZERO_SPLINE, far).y == 0)

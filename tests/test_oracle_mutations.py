@@ -1,0 +1,51 @@
+"""The pins must be able to fail: each planted mistake in a *copy* of the oracle's C source (never in
+the HIP path) has to be rejected by the CPU pin tests.  Runs on the CPU only."""
+import os
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = os.path.join(ROOT, "oracle", "lutkan_oracle.c")
+
+MUTATIONS = {
+    "lerp_weights_swapped": ("float p0 = omw * v0;\n    float p1 = w * v1;", "float p0 = w * v0;\n    float p1 = omw * v1;"),
+    "dequant_drops_y_min": ("float v0 = y_min + a0;", "float v0 = a0;"),
+    "searchsorted_left": ("if (T[kappa] <= xc) ++cnt;", "if (T[kappa] < xc) ++cnt;"),
+    "lookup_uses_L_not_L_minus_1": ("float z = u * (float)(L - 1);", "float z = u * (float)(L);"),
+    "sampling_closed_grid": ("/ (double)L;", "/ (double)(L - 1);"),
+    "symmetric_uses_128": ("float a = amax / 127.0f;", "float a = amax / 128.0f;"),
+    "recursion_wrong_right_denominator": ("double dr = tau[r + q + 1] - tau[r + 1];", "double dr = tau[r + q + 1] - tau[r];"),
+    "recursion_wrong_left_numerator": ("(x - tau[r]) / dl * N[r]", "(x - tau[r + 1]) / dl * N[r]"),
+    "closed_mode_excludes_tK": ("(uint8_t)(x >= t0 && x <= tK)", "(uint8_t)(x >= t0 && x < tK)"),
+    "half_open_includes_tK": (": (uint8_t)(x >= t0 && x < tK);", ": (uint8_t)(x >= t0 && x <= tK);"),
+    "zero_spline_ignored": ("(oob == LKO_ZERO_SPLINE && !ix.in) ? 0.0f : v;", "v;"),
+    "edge_index_transposed": ("size_t e = (size_t)i * m + j;\n                size_t seg", "size_t e = (size_t)j * d + i;\n                size_t seg"),
+    "round_half_away": ("float r = rintf(t / a);", "float r = roundf(t / a);"),
+    "no_nextafter": ("nextafterf(tK, -INFINITY)", "tK"),
+    "l1_not_clamped_to_l0_plus_1": ("o->l1 = (l0 + 1 < L - 1) ? l0 + 1 : L - 1;", "o->l1 = l0;"),
+    "asym_min_is_zero": ("*y_min = lo;", "*y_min = 0.0f;"),
+    "degree0_closed_indicator": ("(tau[r] <= x && x < tau[r + 1])", "(tau[r] <= x && x <= tau[r + 1])"),
+    "layer_sum_skips_first_input": ("for (int i = 0; i < d; ++i) {\n            lko_index ix;\n            lko_locate(knots", "for (int i = (d > 1); i < d; ++i) {\n            lko_index ix;\n            lko_locate(knots"),
+}
+
+
+def test_every_mutation_text_is_present_once():
+    src = open(SRC).read()
+    for name, (old, _) in MUTATIONS.items():
+        assert src.count(old) == 1, name
+
+
+@pytest.mark.parametrize("name", sorted(MUTATIONS))
+def test_pins_reject_planted_mistake(name, tmp_path):
+    old, new = MUTATIONS[name]
+    src = open(SRC).read().replace(old, new)
+    msrc = tmp_path / "mutant.c"
+    msrc.write_text(src)
+    env = dict(os.environ, LUTKAN_ORACLE_SRC=str(msrc), LUTKAN_ORACLE_LIB=str(tmp_path / "libmutant.so"))
+    r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
+                        os.path.join(ROOT, "tests", "test_oracle_bspline.py"),
+                        os.path.join(ROOT, "tests", "test_oracle_lut.py")],
+                       cwd=ROOT, env=env, capture_output=True, text=True, timeout=600)
+    assert r.returncode == 1, f"mutation {name} survived the pins:\n{r.stdout[-2000:]}"
