@@ -1,0 +1,190 @@
+/*
+ * lutkan.h -- C ABI of the MI355X (gfx950) LUT-KAN layer-forward library.
+ *
+ * The library computes the forward pass of a dense Kolmogorov-Arnold layer
+ *     y_j = sum_i phi_ij(x_i)                                            (Sec. 3.1, Eq. 1)
+ * in which every edge function is a segment-wise int8/uint8 lookup table (Sec. 4), together
+ * with a same-backend cubic B-spline layer (Sec. 3.2-3.3) that serves as the honest baseline.
+ *
+ * Conventions
+ *   - Every function returns 0 (LUTKAN_OK) or a negative lutkan_status.  No exception crosses the
+ *     ABI.  lutkan_last_error() gives a thread-local, human readable reason for the last failure.
+ *   - "host" pointers are ordinary CPU memory; "device" pointers are HIP device memory that the
+ *     CALLER owns (allocated by any allocator, e.g. a torch tensor).  The library never allocates
+ *     or frees device memory and never synchronises: forward calls only enqueue kernels on the
+ *     stream handed in (a hipStream_t passed as void*; NULL = the default stream).
+ *   - Host artifacts returned by lutkan_compile are owned by the library until lutkan_artifact_free.
+ *   - Row-major everywhere.  x is [B][d] fp32, y is [B][m] fp32; x and y must not alias.
+ *   - B == 0 is a no-op that returns LUTKAN_OK.
+ */
+#ifndef LUTKAN_H
+#define LUTKAN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  LUTKAN_OK = 0,
+  LUTKAN_EINVAL = -1,        /* null pointer, bad enum, L < 2, knots not strictly increasing, non-finite coef */
+  LUTKAN_ESHAPE = -2,        /* sizes that do not fit together (workspace too small, d/m mismatch in a chain) */
+  LUTKAN_ENOMEM = -3,        /* host allocation failed */
+  LUTKAN_EHIP = -4,          /* a HIP runtime call failed */
+  LUTKAN_EUNSUPPORTED = -5   /* degree != 3, K > LUTKAN_MAX_K, K*L > LUTKAN_MAX_ROWS */
+} lutkan_status;
+
+typedef enum { LUTKAN_SYM_INT8 = 0, LUTKAN_ASYM_UINT8 = 1 } lutkan_scheme;        /* Sec. 4.4, Eq. 11-12 */
+typedef enum { LUTKAN_HALF_OPEN = 0, LUTKAN_CLOSED = 1 } lutkan_boundary;          /* Sec. 5.2 */
+typedef enum { LUTKAN_CLIP_X = 0, LUTKAN_ZERO_SPLINE = 1 } lutkan_oob;             /* Sec. 5.4 */
+typedef enum { LUTKAN_ALGO_AUTO = 0, LUTKAN_ALGO_GATHER = 1, LUTKAN_ALGO_TILED = 2 } lutkan_algo;
+
+#define LUTKAN_MAX_K 64            /* segments per layer (the knot vector travels in the kernel arguments) */
+#define LUTKAN_MAX_ROWS 65536      /* K * L, table rows per input */
+#define LUTKAN_MAX_LAYERS 16
+
+const char *lutkan_last_error(void);
+const char *lutkan_version(void);
+
+/* ------------------------------------------------------------------------------------------------
+ * Host side: compile a B-spline KAN layer into a LUT artifact (Sec. 4.2-4.6, Sec. 6.3).
+ * ---------------------------------------------------------------------------------------------- */
+
+/* One dense layer with pure-spline edges phi_ij = s_ij (value_repr = phi, Sec. 4.3).  All pointers are host. */
+typedef struct {
+  int32_t d, m;              /* inputs, outputs */
+  int32_t G;                 /* grid intervals; the LUT has K = G segments on the domain grid (Sec. 4.2) */
+  int32_t degree;            /* spline degree p; must be 3 */
+  const float *ext_knots;    /* [G + 2*degree + 1] strictly increasing; domain = [ext_knots[p], ext_knots[p+G]] */
+  const float *coef;         /* [d][m][G + degree] B-spline coefficients c_r of Eq. 3 */
+  int32_t L;                 /* samples per segment, >= 2 (Eq. 7) */
+  int32_t scheme;            /* lutkan_scheme */
+  int32_t boundary;          /* lutkan_boundary */
+  int32_t oob;               /* lutkan_oob */
+} lutkan_layer_desc;
+
+typedef struct lutkan_artifact lutkan_artifact;     /* opaque, host memory */
+
+typedef struct {
+  int32_t d, m, K, L, G, degree, scheme, boundary, oob;
+  int32_t jt;                /* column-tile width of the device tables (a power of two <= 128, or 128) */
+  int32_t n_tiles;           /* ceil(m / jt) */
+  int32_t blob_bytes;        /* bytes of one (tile, input) slice of the LUT device table */
+  int32_t coef_blob_bytes;   /* bytes of one (tile, input) slice of the B-spline device table */
+  float t0, tK, tK_star;     /* domain ends and the safe upper clip value of Eq. 13 */
+  size_t q_canonical_bytes;  /* d*m*K*L */
+  size_t params_canonical_bytes; /* d*m*K*4, for scale and for y_min each */
+  size_t table_bytes;        /* whole LUT device table = n_tiles*d*blob_bytes */
+  size_t coef_table_bytes;   /* whole B-spline device table = n_tiles*d*coef_blob_bytes */
+  size_t artifact_bytes;     /* Sec. 4.6 arrays: q + scale + y_min + knots (what Sec. 6.6 "LUT artifact bytes" counts) */
+} lutkan_info;
+
+/* Samples every edge on every segment in fp64 (Eq. 3-5, Eq. 7), quantises in fp32 (Eq. 11-12) and lays the
+ * result out twice: the canonical arrays of Sec. 4.6 and the device tables described below.
+ * n_threads <= 0 picks the number of host cores.  *out is set only on success. */
+int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, lutkan_artifact **out);
+void lutkan_artifact_free(lutkan_artifact *a);
+int lutkan_artifact_info(const lutkan_artifact *a, lutkan_info *out);
+
+/* Read-only host views, valid until lutkan_artifact_free.  Canonical arrays (Sec. 4.6), edge e = i*m + j: */
+const void *lutkan_artifact_q(const lutkan_artifact *a);          /* int8 or uint8 [E][K][L] */
+const float *lutkan_artifact_scale(const lutkan_artifact *a);     /* alpha  [E][K] */
+const float *lutkan_artifact_ymin(const lutkan_artifact *a);      /* y_min  [E][K] (zeros for symmetric) */
+const float *lutkan_artifact_knots(const lutkan_artifact *a);     /* [K+1] */
+const float *lutkan_artifact_ext_knots(const lutkan_artifact *a); /* [G+2p+1] */
+
+/* Device tables (host copies to upload verbatim).  Columns are cut into n_tiles tiles of jt outputs; the
+ * last tile is zero padded.  LUT table: for tile t and input i one contiguous slice of blob_bytes bytes
+ *     float   alpha [K][jt]
+ *     float   y_min [K][jt]                    (asymmetric scheme only; elided when y_min == 0, Sec. 7.5)
+ *     code    q     [K][L][jt]                 (int8 / uint8, i.e. the [i][segment][sample][j] order per tile)
+ *     zero padding up to a multiple of 16 bytes
+ * slices ordered [t][i].  B-spline table: slices of float c[R = G+p][jt], ordered [t][i]. */
+const void *lutkan_artifact_table(const lutkan_artifact *a);
+const void *lutkan_artifact_coef_table(const lutkan_artifact *a);
+
+/* ------------------------------------------------------------------------------------------------
+ * Device side.  The structs are plain host structs; the pointers inside are DEVICE pointers.
+ * ---------------------------------------------------------------------------------------------- */
+typedef struct {
+  int32_t d, m, K, L, scheme, boundary, oob;
+  int32_t jt, n_tiles, blob_bytes;
+  int32_t algo;                       /* lutkan_algo; AUTO picks by shape */
+  float knots[LUTKAN_MAX_K + 1];      /* host copy of T, entries 0..K used */
+  const void *table;                  /* device, lutkan_info.table_bytes bytes, 16-byte aligned */
+} lutkan_dev_layer;
+
+typedef struct {
+  int32_t d, m, G, degree, boundary, oob;
+  int32_t jt, n_tiles, coef_blob_bytes;
+  int32_t algo;
+  float ext_knots[LUTKAN_MAX_K + 7];  /* host copy, entries 0..G+6 used */
+  const float *coef_table;            /* device, lutkan_info.coef_table_bytes bytes, 16-byte aligned */
+} bspline_dev_layer;
+
+/* Fills every field of the device structs from an artifact except the device pointer (set to NULL). */
+int lutkan_dev_layer_init(const lutkan_artifact *a, lutkan_dev_layer *out);
+int bspline_dev_layer_init(const lutkan_artifact *a, bspline_dev_layer *out);
+
+/* Sec. 5.5 / 5.6 counters: inputs (b,i) with In(x) = 0, and rows with at least one such input. */
+typedef struct { unsigned long long oob_count, oob_any_rows; } lutkan_oob_stats;
+
+/* Scratch needed by one forward call for B rows (per-(row,input) lookup records); 256-byte aligned use. */
+size_t lutkan_forward_workspace_bytes(const lutkan_dev_layer *layer, int64_t B);
+size_t bspline_forward_workspace_bytes(const bspline_dev_layer *layer, int64_t B);
+
+/* LUT layer forward (Sec. 4.5 steps 1-5, Sec. 5.2-5.4, Eq. 1).  Per (row, input): the domain test on the raw
+ * x, the safe clip x', the segment k, the local coordinate u and (l0, w) are computed once in IEEE fp32 and
+ * reused for all m outputs; per edge two adjacent codes are gathered, dequantised with the segment's
+ * (alpha, y_min), interpolated and summed over i in fp32.
+ *   x          device [B][d] fp32          y   device [B][m] fp32 (overwritten)
+ *   stats      device, nullable; the two counters are ADDED to (the caller zeroes them)
+ *   workspace  device, >= lutkan_forward_workspace_bytes(layer, B), 256-byte aligned, contents undefined after
+ * Errors: EINVAL for null/ill-formed arguments, ESHAPE for a short workspace, EHIP if a launch fails. */
+int lutkan_forward(const lutkan_dev_layer *layer, const float *x, int64_t B, float *y,
+                   lutkan_oob_stats *stats, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* The two phases of lutkan_forward as separate calls, for callers that time or overlap them:
+ *   lutkan_forward_locate   steps 1-4 of Sec. 4.5 and the domain test of Sec. 5.2 for every (row, input);
+ *                           fills the workspace with the lookup records (and adds to stats, nullable)
+ *   lutkan_forward_edges    step 5 (Eq. 10, 17), Sec. 5.4 and the sum of Eq. 1 from the records in the workspace
+ * Calling locate then edges on one stream with the same layer, B and workspace equals lutkan_forward. */
+int lutkan_forward_locate(const lutkan_dev_layer *layer, const float *x, int64_t B, lutkan_oob_stats *stats,
+                          void *workspace, size_t workspace_bytes, void *hip_stream);
+int lutkan_forward_edges(const lutkan_dev_layer *layer, int64_t B, float *y,
+                         void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Same computation, additionally writing what the paper's contract fixes bit-exactly, for parity checks:
+ *   k_out, l0_out  device int32 [B][d]  segment index (Eq. 14) and lower LUT index (Eq. 16)
+ *   in_out         device uint8 [B][d]  In(x) of Sec. 5.2
+ *   w_out          device fp32  [B][d]  interpolation weight (Eq. 16)
+ *   q01_out        device int16 [B][d][m][2], nullable: the two gathered codes per edge (small layers only) */
+int lutkan_forward_trace(const lutkan_dev_layer *layer, const float *x, int64_t B, float *y,
+                         int32_t *k_out, int32_t *l0_out, uint8_t *in_out, float *w_out, int16_t *q01_out,
+                         void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* B-spline layer forward (Eq. 1 over Eq. 3-5): per (row, input) the span and the four non-zero cubic basis
+ * values are computed once by the Cox-de Boor recursion in fp32; per edge four coefficient FMAs; the same
+ * boundary_mode / oob_policy as the LUT layer is applied to x first. */
+int bspline_kan_forward(const bspline_dev_layer *layer, const float *x, int64_t B, float *y,
+                        void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* The two phases of bspline_kan_forward (span + basis values per (row, input); coefficient FMAs + sum). */
+int bspline_forward_locate(const bspline_dev_layer *layer, const float *x, int64_t B,
+                           void *workspace, size_t workspace_bytes, void *hip_stream);
+int bspline_forward_edges(const bspline_dev_layer *layer, int64_t B, float *y,
+                          void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Per-layer chaining (Sec. 5.1: intermediate activations feed the next layer and may leave its domain):
+ * y of layer l is x of layer l+1.  The workspace holds two ping-pong activation buffers plus the largest
+ * per-layer scratch.  layers[l].m must equal layers[l+1].d.  stats (nullable) points to n_layers entries. */
+size_t lutkan_model_workspace_bytes(const lutkan_dev_layer *layers, int32_t n_layers, int64_t B);
+int lutkan_model_forward(const lutkan_dev_layer *layers, int32_t n_layers, const float *x, int64_t B, float *y,
+                         lutkan_oob_stats *stats, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LUTKAN_H */

@@ -1,0 +1,361 @@
+"""ctypes binding of include/lutkan.h.  Same entry-point names as the C ABI; argument marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+from . import build as _build
+
+SYM_INT8, ASYM_UINT8 = 0, 1
+HALF_OPEN, CLOSED = 0, 1
+CLIP_X, ZERO_SPLINE = 0, 1
+ALGO_AUTO, ALGO_GATHER, ALGO_TILED = 0, 1, 2
+MAX_K = 64
+
+
+class LutKanError(RuntimeError):
+    pass
+
+
+class _LayerDesc(C.Structure):
+    _fields_ = [("d", C.c_int32), ("m", C.c_int32), ("G", C.c_int32), ("degree", C.c_int32),
+                ("ext_knots", C.c_void_p), ("coef", C.c_void_p),
+                ("L", C.c_int32), ("scheme", C.c_int32), ("boundary", C.c_int32), ("oob", C.c_int32)]
+
+
+class _Info(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("d", "m", "K", "L", "G", "degree", "scheme", "boundary", "oob",
+                                         "jt", "n_tiles", "blob_bytes", "coef_blob_bytes")] + \
+               [("t0", C.c_float), ("tK", C.c_float), ("tK_star", C.c_float)] + \
+               [(n, C.c_size_t) for n in ("q_canonical_bytes", "params_canonical_bytes", "table_bytes",
+                                          "coef_table_bytes", "artifact_bytes")]
+
+
+class _DevLayer(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("d", "m", "K", "L", "scheme", "boundary", "oob", "jt", "n_tiles",
+                                         "blob_bytes", "algo")] + \
+               [("knots", C.c_float * (MAX_K + 1)), ("table", C.c_void_p)]
+
+
+class _SplineDevLayer(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("d", "m", "G", "degree", "boundary", "oob", "jt", "n_tiles",
+                                         "coef_blob_bytes", "algo")] + \
+               [("ext_knots", C.c_float * (MAX_K + 7)), ("coef_table", C.c_void_p)]
+
+
+EXPORTS = [
+    "lutkan_last_error", "lutkan_version", "lutkan_compile", "lutkan_artifact_free", "lutkan_artifact_info",
+    "lutkan_artifact_q", "lutkan_artifact_scale", "lutkan_artifact_ymin", "lutkan_artifact_knots",
+    "lutkan_artifact_ext_knots", "lutkan_artifact_table", "lutkan_artifact_coef_table",
+    "lutkan_dev_layer_init", "bspline_dev_layer_init", "lutkan_forward_workspace_bytes",
+    "bspline_forward_workspace_bytes", "lutkan_forward", "lutkan_forward_trace", "bspline_kan_forward",
+    "lutkan_model_workspace_bytes", "lutkan_model_forward", "lutkan_forward_locate", "lutkan_forward_edges",
+    "bspline_forward_locate", "bspline_forward_edges",
+]
+
+_lib = None
+
+
+def library_path() -> str:
+    return _build.LIB
+
+
+def load_library():
+    """Loads liblutkan.so, building it first only when no built library exists."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        _build.build()
+    lib = C.CDLL(_build.LIB)
+    vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+    lib.lutkan_last_error.restype = C.c_char_p
+    lib.lutkan_version.restype = C.c_char_p
+    lib.lutkan_compile.argtypes = [C.POINTER(_LayerDesc), i32, C.POINTER(vp)]
+    lib.lutkan_artifact_free.argtypes = [vp]
+    lib.lutkan_artifact_free.restype = None
+    lib.lutkan_artifact_info.argtypes = [vp, C.POINTER(_Info)]
+    for n in ("q", "scale", "ymin", "knots", "ext_knots", "table", "coef_table"):
+        f = getattr(lib, "lutkan_artifact_" + n)
+        f.argtypes = [vp]
+        f.restype = vp
+    lib.lutkan_dev_layer_init.argtypes = [vp, C.POINTER(_DevLayer)]
+    lib.bspline_dev_layer_init.argtypes = [vp, C.POINTER(_SplineDevLayer)]
+    lib.lutkan_forward_workspace_bytes.argtypes = [C.POINTER(_DevLayer), i64]
+    lib.lutkan_forward_workspace_bytes.restype = sz
+    lib.bspline_forward_workspace_bytes.argtypes = [C.POINTER(_SplineDevLayer), i64]
+    lib.bspline_forward_workspace_bytes.restype = sz
+    lib.lutkan_forward.argtypes = [C.POINTER(_DevLayer), vp, i64, vp, vp, vp, sz, vp]
+    lib.lutkan_forward_trace.argtypes = [C.POINTER(_DevLayer), vp, i64, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.bspline_kan_forward.argtypes = [C.POINTER(_SplineDevLayer), vp, i64, vp, vp, sz, vp]
+    lib.lutkan_forward_locate.argtypes = [C.POINTER(_DevLayer), vp, i64, vp, vp, sz, vp]
+    lib.lutkan_forward_edges.argtypes = [C.POINTER(_DevLayer), i64, vp, vp, sz, vp]
+    lib.bspline_forward_locate.argtypes = [C.POINTER(_SplineDevLayer), vp, i64, vp, sz, vp]
+    lib.bspline_forward_edges.argtypes = [C.POINTER(_SplineDevLayer), i64, vp, vp, sz, vp]
+    lib.lutkan_model_workspace_bytes.argtypes = [C.POINTER(_DevLayer), i32, i64]
+    lib.lutkan_model_workspace_bytes.restype = sz
+    lib.lutkan_model_forward.argtypes = [C.POINTER(_DevLayer), i32, vp, i64, vp, vp, vp, sz, vp]
+    _lib = lib
+    return lib
+
+
+def lutkan_last_error() -> str:
+    return load_library().lutkan_last_error().decode()
+
+
+def lutkan_version() -> str:
+    return load_library().lutkan_version().decode()
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise LutKanError(f"[{rc}] {lutkan_last_error()}")
+
+
+def _view(ptr, nbytes, dtype, shape):
+    buf = (C.c_char * nbytes).from_address(ptr)
+    return np.frombuffer(buf, dtype=dtype).reshape(shape)
+
+
+class Artifact:
+    """Host LUT artifact (Sec. 4.6) owned by the library; numpy views stay valid while this object lives."""
+
+    def __init__(self, handle):
+        self._h = handle
+        lib = load_library()
+        info = _Info()
+        _check(lib.lutkan_artifact_info(handle, C.byref(info)))
+        self.info = info
+        E, K, L = info.d * info.m, info.K, info.L
+        qdt = np.int8 if info.scheme == SYM_INT8 else np.uint8
+        self.q = _view(lib.lutkan_artifact_q(handle), E * K * L, qdt, (E, K, L))
+        self.scale = _view(lib.lutkan_artifact_scale(handle), E * K * 4, np.float32, (E, K))
+        self.y_min = _view(lib.lutkan_artifact_ymin(handle), E * K * 4, np.float32, (E, K))
+        self.knots = _view(lib.lutkan_artifact_knots(handle), (K + 1) * 4, np.float32, (K + 1,))
+        self.ext_knots = _view(lib.lutkan_artifact_ext_knots(handle), (info.G + 7) * 4, np.float32, (info.G + 7,))
+        self.table = _view(lib.lutkan_artifact_table(handle), info.table_bytes, np.uint8, (info.table_bytes,))
+        self.coef_table = _view(lib.lutkan_artifact_coef_table(handle), info.coef_table_bytes, np.float32,
+                                (info.coef_table_bytes // 4,))
+
+    def __del__(self):
+        h, self._h = getattr(self, "_h", None), None
+        if h and _lib is not None:
+            self.q = self.scale = self.y_min = self.knots = self.ext_knots = self.table = self.coef_table = None
+            _lib.lutkan_artifact_free(h)
+
+    def to_device(self, device="cuda:0", algo: int = ALGO_AUTO) -> "LutLayer":
+        return LutLayer(self, device, algo)
+
+    def bspline_to_device(self, device="cuda:0", algo: int = ALGO_AUTO) -> "BsplineLayer":
+        return BsplineLayer(self, device, algo)
+
+
+def lutkan_compile(d: int, m: int, G: int, degree: int, ext_knots, coef, L: int, scheme: int, boundary: int,
+                   oob: int, n_threads: int = 0) -> Artifact:
+    """Host-only LUT compilation of one dense B-spline KAN layer (Sec. 4.2-4.6)."""
+    lib = load_library()
+    tau = np.ascontiguousarray(ext_knots, dtype=np.float32)
+    cf = np.ascontiguousarray(coef, dtype=np.float32)
+    if tau.size != G + 2 * degree + 1 or cf.size != d * m * (G + degree):
+        raise LutKanError("lutkan_compile: ext_knots / coef have the wrong number of elements")
+    desc = _LayerDesc(d, m, G, degree, tau.ctypes.data, cf.ctypes.data, L, scheme, boundary, oob)
+    out = C.c_void_p()
+    _check(lib.lutkan_compile(C.byref(desc), n_threads, C.byref(out)))
+    return Artifact(out.value)
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _upload(arr: np.ndarray, device):
+    torch = _torch()
+    return torch.from_numpy(arr).to(device)
+
+
+class LutLayer:
+    """Device-side LUT layer: the lutkan_dev_layer struct plus the torch tensor that owns its table."""
+
+    def __init__(self, art: Artifact, device, algo: int = ALGO_AUTO):
+        self.c = _DevLayer()
+        _check(load_library().lutkan_dev_layer_init(art._h, C.byref(self.c)))
+        self.c.algo = algo
+        self.table = _upload(art.table, device)
+        self.c.table = self.table.data_ptr()
+        self.device = self.table.device
+        self.d, self.m = self.c.d, self.c.m
+
+    def with_contract(self, boundary: int, oob: int, algo: Optional[int] = None) -> "LutLayer":
+        """Same tables under another boundary_mode / oob_policy (the contract is not baked into the codes)."""
+        other = object.__new__(LutLayer)
+        other.c = _DevLayer.from_buffer_copy(self.c)
+        other.c.boundary, other.c.oob = boundary, oob
+        if algo is not None:
+            other.c.algo = algo
+        other.table, other.device, other.d, other.m = self.table, self.device, self.d, self.m
+        return other
+
+
+class BsplineLayer:
+    def __init__(self, art: Artifact, device, algo: int = ALGO_AUTO):
+        self.c = _SplineDevLayer()
+        _check(load_library().bspline_dev_layer_init(art._h, C.byref(self.c)))
+        self.c.algo = algo
+        self.coef_table = _upload(art.coef_table, device)
+        self.c.coef_table = self.coef_table.data_ptr()
+        self.device = self.coef_table.device
+        self.d, self.m = self.c.d, self.c.m
+
+    def with_contract(self, boundary: int, oob: int, algo: Optional[int] = None) -> "BsplineLayer":
+        other = object.__new__(BsplineLayer)
+        other.c = _SplineDevLayer.from_buffer_copy(self.c)
+        other.c.boundary, other.c.oob = boundary, oob
+        if algo is not None:
+            other.c.algo = algo
+        other.coef_table, other.device, other.d, other.m = self.coef_table, self.device, self.d, self.m
+        return other
+
+
+def _stream(device) -> int:
+    return _torch().cuda.current_stream(device).cuda_stream
+
+
+def _require(t, dtype, what):
+    torch = _torch()
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous() and t.dtype == dtype):
+        raise LutKanError(f"{what} must be a contiguous CUDA tensor of dtype {dtype}")
+
+
+def lutkan_forward_workspace_bytes(layer: LutLayer, B: int) -> int:
+    return int(load_library().lutkan_forward_workspace_bytes(C.byref(layer.c), B))
+
+
+def bspline_forward_workspace_bytes(layer: BsplineLayer, B: int) -> int:
+    return int(load_library().bspline_forward_workspace_bytes(C.byref(layer.c), B))
+
+
+def lutkan_model_workspace_bytes(layers: Sequence[LutLayer], B: int) -> int:
+    arr = (_DevLayer * len(layers))(*[l.c for l in layers])
+    return int(load_library().lutkan_model_workspace_bytes(arr, len(layers), B))
+
+
+def _workspace(nbytes, device, workspace):
+    torch = _torch()
+    if workspace is None:
+        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+    _require(workspace, torch.uint8, "workspace")
+    return workspace
+
+
+def lutkan_forward(layer: LutLayer, x, y=None, stats=None, workspace=None):
+    """y[B,m] = LUT layer forward of x[B,d] on the current stream.  stats: optional int64[2] CUDA tensor (added to)."""
+    torch = _torch()
+    _require(x, torch.float32, "x")
+    B = x.shape[0]
+    if x.dim() != 2 or x.shape[1] != layer.d:
+        raise LutKanError(f"x must be [B,{layer.d}]")
+    if y is None:
+        y = torch.empty((B, layer.m), dtype=torch.float32, device=x.device)
+    _require(y, torch.float32, "y")
+    if stats is not None:
+        _require(stats, torch.int64, "stats")
+    ws = _workspace(lutkan_forward_workspace_bytes(layer, B), x.device, workspace)
+    _check(load_library().lutkan_forward(C.byref(layer.c), x.data_ptr(), B, y.data_ptr(),
+                                         stats.data_ptr() if stats is not None else None,
+                                         ws.data_ptr(), ws.numel(), _stream(x.device)))
+    return y
+
+
+def lutkan_forward_locate(layer: LutLayer, x, workspace, stats=None):
+    """Phase 1 of lutkan_forward: fills `workspace` with the per-(row,input) lookup records."""
+    torch = _torch()
+    _require(x, torch.float32, "x")
+    _require(workspace, torch.uint8, "workspace")
+    _check(load_library().lutkan_forward_locate(C.byref(layer.c), x.data_ptr(), x.shape[0],
+                                                stats.data_ptr() if stats is not None else None,
+                                                workspace.data_ptr(), workspace.numel(), _stream(x.device)))
+
+
+def lutkan_forward_edges(layer: LutLayer, B: int, y, workspace):
+    """Phase 2 of lutkan_forward: gathers, dequantises, interpolates and sums from the records in `workspace`."""
+    torch = _torch()
+    _require(y, torch.float32, "y")
+    _require(workspace, torch.uint8, "workspace")
+    _check(load_library().lutkan_forward_edges(C.byref(layer.c), B, y.data_ptr(), workspace.data_ptr(),
+                                               workspace.numel(), _stream(y.device)))
+    return y
+
+
+def bspline_forward_locate(layer: "BsplineLayer", x, workspace):
+    torch = _torch()
+    _require(x, torch.float32, "x")
+    _require(workspace, torch.uint8, "workspace")
+    _check(load_library().bspline_forward_locate(C.byref(layer.c), x.data_ptr(), x.shape[0], workspace.data_ptr(),
+                                                 workspace.numel(), _stream(x.device)))
+
+
+def bspline_forward_edges(layer: "BsplineLayer", B: int, y, workspace):
+    torch = _torch()
+    _require(y, torch.float32, "y")
+    _require(workspace, torch.uint8, "workspace")
+    _check(load_library().bspline_forward_edges(C.byref(layer.c), B, y.data_ptr(), workspace.data_ptr(),
+                                                workspace.numel(), _stream(y.device)))
+    return y
+
+
+def lutkan_forward_trace(layer: LutLayer, x, codes: bool = False, workspace=None):
+    """Forward plus the bit-exact quantities of the contract: (y, k, l0, inside, w, q01 or None)."""
+    torch = _torch()
+    _require(x, torch.float32, "x")
+    B, d, m = x.shape[0], layer.d, layer.m
+    dev = x.device
+    y = torch.empty((B, m), dtype=torch.float32, device=dev)
+    k = torch.empty((B, d), dtype=torch.int32, device=dev)
+    l0 = torch.empty((B, d), dtype=torch.int32, device=dev)
+    inside = torch.empty((B, d), dtype=torch.uint8, device=dev)
+    w = torch.empty((B, d), dtype=torch.float32, device=dev)
+    q01 = torch.empty((B, d, m, 2), dtype=torch.int16, device=dev) if codes else None
+    ws = _workspace(lutkan_forward_workspace_bytes(layer, B), dev, workspace)
+    _check(load_library().lutkan_forward_trace(C.byref(layer.c), x.data_ptr(), B, y.data_ptr(), k.data_ptr(),
+                                               l0.data_ptr(), inside.data_ptr(), w.data_ptr(),
+                                               q01.data_ptr() if codes else None, ws.data_ptr(), ws.numel(),
+                                               _stream(dev)))
+    return y, k, l0, inside, w, q01
+
+
+def bspline_kan_forward(layer: BsplineLayer, x, y=None, workspace=None):
+    torch = _torch()
+    _require(x, torch.float32, "x")
+    B = x.shape[0]
+    if x.dim() != 2 or x.shape[1] != layer.d:
+        raise LutKanError(f"x must be [B,{layer.d}]")
+    if y is None:
+        y = torch.empty((B, layer.m), dtype=torch.float32, device=x.device)
+    _require(y, torch.float32, "y")
+    ws = _workspace(bspline_forward_workspace_bytes(layer, B), x.device, workspace)
+    _check(load_library().bspline_kan_forward(C.byref(layer.c), x.data_ptr(), B, y.data_ptr(), ws.data_ptr(),
+                                              ws.numel(), _stream(x.device)))
+    return y
+
+
+def lutkan_model_forward(layers: List[LutLayer], x, y=None, stats=None, workspace=None):
+    """Chained forward: layer l's output is layer l+1's input.  stats: optional int64[n_layers,2] CUDA tensor."""
+    torch = _torch()
+    _require(x, torch.float32, "x")
+    B = x.shape[0]
+    arr = (_DevLayer * len(layers))(*[l.c for l in layers])
+    if y is None:
+        y = torch.empty((B, layers[-1].m), dtype=torch.float32, device=x.device)
+    _require(y, torch.float32, "y")
+    if stats is not None:
+        _require(stats, torch.int64, "stats")
+    need = int(load_library().lutkan_model_workspace_bytes(arr, len(layers), B))
+    ws = _workspace(need, x.device, workspace)
+    _check(load_library().lutkan_model_forward(arr, len(layers), x.data_ptr(), B, y.data_ptr(),
+                                               stats.data_ptr() if stats is not None else None,
+                                               ws.data_ptr(), ws.numel(), _stream(x.device)))
+    return y

@@ -1,0 +1,278 @@
+// Host-side LUT compiler of liblutkan: B-spline KAN layer -> segment-wise int8/uint8 tables.
+//
+// Follows Sec. 4.2 (half-open per-segment sampling, Eq. 7), Sec. 3.2 (Cox-de Boor, Eq. 3-5),
+// Sec. 4.4 (symmetric int8 / asymmetric uint8 affine quantisation, Eq. 10-12) and Sec. 4.6 (artifact
+// arrays), then re-lays the tables out for the gfx950 kernels: column tiles of jt outputs, one
+// contiguous slice per (tile, input) holding that input's dequantisation parameters and its
+// [segment][sample][column] codes.
+//
+// Numerics: the spline is evaluated in double from the fp32 knots and coefficients and rounded once to
+// fp32; quantisation is fp32 with one rounding per operation and round-half-to-even.  This file must be
+// compiled without FMA contraction.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <thread>
+
+#include "lutkan_internal.h"
+
+namespace lutkan {
+
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+int choose_jt(int m, int K, int L, int scheme) {
+  if (m > 64) {
+    if (blob_layout(K, L, 128, scheme).bytes <= kLdsSliceBudget) return 128;
+    return 64;
+  }
+  int jt = 4;
+  while (jt < m) jt *= 2;
+  return jt;
+}
+
+namespace {
+
+constexpr int P = 3;  // cubic
+
+// The four cubic B-spline basis functions that are non-zero on the span [tau[mu], tau[mu+1]), by the
+// Cox-de Boor recursion restricted to its non-zero entries.  out[a] = B_{mu-3+a, 3}(x).
+// Each term is (numerator / knot difference) * lower-degree value, left term plus right term, and a
+// zero-length knot difference contributes 0.
+void nonzero_cubic_basis(const double *tau, int mu, double x, double out[4]) {
+  double lower[5] = {0.0, 0.0, 0.0, 1.0, 0.0};  // lower[a] = B_{mu-3+a, q-1}(x); slot 4 is always 0
+  for (int q = 1; q <= P; ++q) {
+    double next[5] = {0.0, 0.0, 0.0, 0.0, 0.0};
+    for (int a = P - q; a <= P; ++a) {
+      const int r = mu - P + a;
+      double acc = 0.0;
+      bool have = false;
+      if (lower[a] != 0.0) {
+        const double span = tau[r + q] - tau[r];
+        if (span != 0.0) { acc = (x - tau[r]) / span * lower[a]; have = true; }
+      }
+      if (lower[a + 1] != 0.0) {
+        const double span = tau[r + q + 1] - tau[r + 1];
+        if (span != 0.0) {
+          const double term = (tau[r + q + 1] - x) / span * lower[a + 1];
+          acc = have ? acc + term : term;
+        }
+      }
+      next[a] = acc;
+    }
+    std::memcpy(lower, next, sizeof(lower));
+  }
+  for (int a = 0; a < 4; ++a) out[a] = lower[a];
+}
+
+struct SegmentCodes {
+  float alpha, ymin;
+};
+
+// Eq. 11: q in [-127,127], y_min = 0, alpha = max|v| / 127.  A zero segment stores alpha = 1, q = 0.
+SegmentCodes quantise_symmetric(const float *v, int L, int8_t *q) {
+  float peak = 0.0f;
+  for (int l = 0; l < L; ++l) peak = std::max(peak, std::fabs(v[l]));
+  if (peak == 0.0f) {
+    std::memset(q, 0, (size_t)L);
+    return {1.0f, 0.0f};
+  }
+  const float alpha = peak / 127.0f;
+  for (int l = 0; l < L; ++l) {
+    const float code = std::nearbyintf(v[l] / alpha);
+    q[l] = (int8_t)std::min(127.0f, std::max(-127.0f, code));
+  }
+  return {alpha, 0.0f};
+}
+
+// Eq. 12: q in [0,255], y_min = min v, alpha = (max v - y_min) / 255.  A flat segment stores alpha = 1, q = 0.
+SegmentCodes quantise_asymmetric(const float *v, int L, uint8_t *q) {
+  const float lo = *std::min_element(v, v + L);
+  const float hi = *std::max_element(v, v + L);
+  if (hi == lo) {
+    std::memset(q, 0, (size_t)L);
+    return {1.0f, lo};
+  }
+  const float width = hi - lo;
+  const float alpha = width / 255.0f;
+  for (int l = 0; l < L; ++l) {
+    const float shifted = v[l] - lo;
+    const float code = std::nearbyintf(shifted / alpha);
+    q[l] = (uint8_t)std::min(255.0f, std::max(0.0f, code));
+  }
+  return {alpha, lo};
+}
+
+}  // namespace
+}  // namespace lutkan
+
+using namespace lutkan;
+
+extern "C" const char *lutkan_last_error(void) { return g_err; }
+extern "C" const char *lutkan_version(void) { return "lutkan-gfx950 0.1"; }
+
+extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, lutkan_artifact **out) {
+  if (!desc || !out) return fail(LUTKAN_EINVAL, "lutkan_compile: null argument");
+  if (!desc->ext_knots || !desc->coef) return fail(LUTKAN_EINVAL, "lutkan_compile: null knots/coef");
+  const int d = desc->d, m = desc->m, G = desc->G, L = desc->L;
+  if (d < 1 || m < 1 || G < 1) return fail(LUTKAN_EINVAL, "lutkan_compile: d, m, G must be >= 1");
+  if (L < 2) return fail(LUTKAN_EINVAL, "lutkan_compile: L must be >= 2 (got %d)", L);
+  if (desc->degree != P) return fail(LUTKAN_EUNSUPPORTED, "lutkan_compile: only cubic splines (degree 3), got %d", desc->degree);
+  if (desc->scheme != LUTKAN_SYM_INT8 && desc->scheme != LUTKAN_ASYM_UINT8) return fail(LUTKAN_EINVAL, "lutkan_compile: bad scheme %d", desc->scheme);
+  if (desc->boundary != LUTKAN_HALF_OPEN && desc->boundary != LUTKAN_CLOSED) return fail(LUTKAN_EINVAL, "lutkan_compile: bad boundary_mode %d", desc->boundary);
+  if (desc->oob != LUTKAN_CLIP_X && desc->oob != LUTKAN_ZERO_SPLINE) return fail(LUTKAN_EINVAL, "lutkan_compile: bad oob_policy %d", desc->oob);
+  const int K = G, R = G + P, n_knots = G + 2 * P + 1;
+  if (K > LUTKAN_MAX_K) return fail(LUTKAN_EUNSUPPORTED, "lutkan_compile: K=%d exceeds LUTKAN_MAX_K=%d", K, LUTKAN_MAX_K);
+  if ((int64_t)K * L > LUTKAN_MAX_ROWS) return fail(LUTKAN_EUNSUPPORTED, "lutkan_compile: K*L=%lld exceeds %d", (long long)K * L, LUTKAN_MAX_ROWS);
+  for (int r = 0; r < n_knots; ++r)
+    if (!std::isfinite(desc->ext_knots[r])) return fail(LUTKAN_EINVAL, "lutkan_compile: knot %d is not finite", r);
+  for (int r = 0; r + 1 < n_knots; ++r)
+    if (!(desc->ext_knots[r] < desc->ext_knots[r + 1])) return fail(LUTKAN_EINVAL, "lutkan_compile: knots not strictly increasing at %d", r);
+  const size_t E = (size_t)d * m;
+  for (size_t n = 0; n < E * R; ++n)
+    if (!std::isfinite(desc->coef[n])) return fail(LUTKAN_EINVAL, "lutkan_compile: coefficient %zu is not finite", n);
+
+  lutkan_artifact *a = new (std::nothrow) lutkan_artifact();
+  if (!a) return fail(LUTKAN_ENOMEM, "lutkan_compile: out of host memory");
+  const int scheme = desc->scheme;
+  const int jt = choose_jt(m, K, L, scheme);
+  const int n_tiles = (m + jt - 1) / jt;
+  const BlobLayout lay = blob_layout(K, L, jt, scheme);
+  const int coef_blob = R * jt * 4;
+  try {
+    a->ext_knots.assign(desc->ext_knots, desc->ext_knots + n_knots);
+    a->knots.assign(desc->ext_knots + P, desc->ext_knots + P + K + 1);
+    a->q.resize(E * K * L);
+    a->scale.resize(E * K);
+    a->ymin.resize(E * K);
+    a->table.assign((size_t)n_tiles * d * lay.bytes, 0);
+    a->coef_table.assign((size_t)n_tiles * d * R * jt, 0.0f);
+  } catch (const std::bad_alloc &) {
+    delete a;
+    return fail(LUTKAN_ENOMEM, "lutkan_compile: out of host memory for %zu edges", E);
+  }
+
+  // Basis values at the K*L sampling positions x_{k,l} = t_k + l*(t_{k+1}-t_k)/L (Eq. 7).  The knot vector is
+  // shared by all edges of the layer, so this small table is built once: basis[(k*L+l)*4 + a] multiplies
+  // coefficient c_{k+a} (span mu = k+3, first non-zero function r = mu-3 = k).
+  std::vector<double> tau(a->ext_knots.begin(), a->ext_knots.end());
+  std::vector<double> basis((size_t)K * L * 4);
+  for (int k = 0; k < K; ++k) {
+    const double left = (double)a->knots[k];
+    const double step = ((double)a->knots[k + 1] - left) / (double)L;
+    for (int l = 0; l < L; ++l) nonzero_cubic_basis(tau.data(), k + P, left + (double)l * step, &basis[((size_t)k * L + l) * 4]);
+  }
+
+  int nt = n_threads > 0 ? n_threads : (int)std::thread::hardware_concurrency();
+  nt = std::max(1, std::min(nt, 64));
+  nt = (int)std::min<size_t>((size_t)nt, (size_t)d);
+  auto work = [&](int tid) {
+    std::vector<float> v((size_t)L);
+    for (int i = tid; i < d; i += nt) {
+      for (int j = 0; j < m; ++j) {
+        const size_t e = (size_t)i * m + j;
+        const float *c = desc->coef + e * R;
+        const int t = j / jt, jj = j % jt;
+        uint8_t *slice = a->table.data() + ((size_t)t * d + i) * lay.bytes;
+        float *slice_alpha = reinterpret_cast<float *>(slice + lay.alpha_off);
+        float *slice_ymin = reinterpret_cast<float *>(slice + lay.ymin_off);
+        uint8_t *slice_codes = slice + lay.codes_off;
+        float *cslice = a->coef_table.data() + ((size_t)t * d + i) * R * jt;
+        for (int r = 0; r < R; ++r) cslice[(size_t)r * jt + jj] = c[r];
+        for (int k = 0; k < K; ++k) {
+          const double c0 = c[k], c1 = c[k + 1], c2 = c[k + 2], c3 = c[k + 3];
+          for (int l = 0; l < L; ++l) {
+            const double *N = &basis[((size_t)k * L + l) * 4];
+            double s = 0.0;
+            s += c0 * N[0];
+            s += c1 * N[1];
+            s += c2 * N[2];
+            s += c3 * N[3];
+            v[l] = (float)s;
+          }
+          uint8_t *qc = a->q.data() + (e * K + k) * L;
+          const SegmentCodes sc = (scheme == LUTKAN_SYM_INT8)
+                                      ? quantise_symmetric(v.data(), L, reinterpret_cast<int8_t *>(qc))
+                                      : quantise_asymmetric(v.data(), L, qc);
+          a->scale[e * K + k] = sc.alpha;
+          a->ymin[e * K + k] = sc.ymin;
+          slice_alpha[(size_t)k * jt + jj] = sc.alpha;
+          if (scheme == LUTKAN_ASYM_UINT8) slice_ymin[(size_t)k * jt + jj] = sc.ymin;
+          for (int l = 0; l < L; ++l) slice_codes[((size_t)k * L + l) * jt + jj] = qc[l];
+        }
+      }
+    }
+  };
+  if (nt == 1) {
+    work(0);
+  } else {
+    std::vector<std::thread> pool;
+    for (int t = 0; t < nt; ++t) pool.emplace_back(work, t);
+    for (auto &th : pool) th.join();
+  }
+
+  lutkan_info &I = a->info;
+  std::memset(&I, 0, sizeof(I));
+  I.d = d; I.m = m; I.K = K; I.L = L; I.G = G; I.degree = P;
+  I.scheme = scheme; I.boundary = desc->boundary; I.oob = desc->oob;
+  I.jt = jt; I.n_tiles = n_tiles; I.blob_bytes = lay.bytes; I.coef_blob_bytes = coef_blob;
+  I.t0 = a->knots[0]; I.tK = a->knots[K];
+  I.tK_star = (desc->boundary == LUTKAN_CLOSED) ? I.tK : std::nextafterf(I.tK, -INFINITY);  // Eq. 13
+  I.q_canonical_bytes = E * K * L;
+  I.params_canonical_bytes = E * K * 4;
+  I.table_bytes = a->table.size();
+  I.coef_table_bytes = a->coef_table.size() * 4;
+  I.artifact_bytes = I.q_canonical_bytes + 2 * I.params_canonical_bytes + 4 * (size_t)(K + 1);
+  *out = a;
+  return LUTKAN_OK;
+}
+
+extern "C" void lutkan_artifact_free(lutkan_artifact *a) { delete a; }
+
+extern "C" int lutkan_artifact_info(const lutkan_artifact *a, lutkan_info *out) {
+  if (!a || !out) return fail(LUTKAN_EINVAL, "lutkan_artifact_info: null argument");
+  *out = a->info;
+  return LUTKAN_OK;
+}
+
+extern "C" const void *lutkan_artifact_q(const lutkan_artifact *a) { return a ? a->q.data() : nullptr; }
+extern "C" const float *lutkan_artifact_scale(const lutkan_artifact *a) { return a ? a->scale.data() : nullptr; }
+extern "C" const float *lutkan_artifact_ymin(const lutkan_artifact *a) { return a ? a->ymin.data() : nullptr; }
+extern "C" const float *lutkan_artifact_knots(const lutkan_artifact *a) { return a ? a->knots.data() : nullptr; }
+extern "C" const float *lutkan_artifact_ext_knots(const lutkan_artifact *a) { return a ? a->ext_knots.data() : nullptr; }
+extern "C" const void *lutkan_artifact_table(const lutkan_artifact *a) { return a ? a->table.data() : nullptr; }
+extern "C" const void *lutkan_artifact_coef_table(const lutkan_artifact *a) { return a ? a->coef_table.data() : nullptr; }
+
+extern "C" int lutkan_dev_layer_init(const lutkan_artifact *a, lutkan_dev_layer *out) {
+  if (!a || !out) return fail(LUTKAN_EINVAL, "lutkan_dev_layer_init: null argument");
+  std::memset(out, 0, sizeof(*out));
+  const lutkan_info &I = a->info;
+  out->d = I.d; out->m = I.m; out->K = I.K; out->L = I.L;
+  out->scheme = I.scheme; out->boundary = I.boundary; out->oob = I.oob;
+  out->jt = I.jt; out->n_tiles = I.n_tiles; out->blob_bytes = I.blob_bytes;
+  out->algo = LUTKAN_ALGO_AUTO;
+  for (int k = 0; k <= I.K; ++k) out->knots[k] = a->knots[k];
+  out->table = nullptr;
+  return LUTKAN_OK;
+}
+
+extern "C" int bspline_dev_layer_init(const lutkan_artifact *a, bspline_dev_layer *out) {
+  if (!a || !out) return fail(LUTKAN_EINVAL, "bspline_dev_layer_init: null argument");
+  std::memset(out, 0, sizeof(*out));
+  const lutkan_info &I = a->info;
+  out->d = I.d; out->m = I.m; out->G = I.G; out->degree = I.degree;
+  out->boundary = I.boundary; out->oob = I.oob;
+  out->jt = I.jt; out->n_tiles = I.n_tiles; out->coef_blob_bytes = I.coef_blob_bytes;
+  out->algo = LUTKAN_ALGO_AUTO;
+  for (int r = 0; r < I.G + 2 * P + 1; ++r) out->ext_knots[r] = a->ext_knots[r];
+  out->coef_table = nullptr;
+  return LUTKAN_OK;
+}

@@ -1,0 +1,52 @@
+// Internal declarations shared by the host compiler and the HIP launchers of liblutkan.
+// Nothing here is part of the C ABI (see include/lutkan.h).
+#pragma once
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <vector>
+
+#include "lutkan.h"
+
+namespace lutkan {
+
+// Thread-local error text behind lutkan_last_error().
+int fail(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+
+// Byte offsets inside one (tile, input) slice of the LUT device table:
+//   [alpha K*jt f32][y_min K*jt f32 (asymmetric only)][codes K*L*jt bytes][zero pad to 16 B]
+struct BlobLayout {
+  int32_t alpha_off, ymin_off, codes_off, bytes;
+};
+
+inline BlobLayout blob_layout(int K, int L, int jt, int scheme) {
+  BlobLayout b;
+  b.alpha_off = 0;
+  b.ymin_off = K * jt * 4;
+  b.codes_off = (scheme == LUTKAN_ASYM_UINT8) ? 2 * K * jt * 4 : K * jt * 4;
+  int raw = b.codes_off + K * L * jt;
+  b.bytes = (raw + 15) & ~15;
+  return b;
+}
+
+// Largest table slice the tiled kernels stage in LDS: 96 KiB, i.e. six 16-byte vectors per thread of a
+// 1024-thread work-group while the slice is in flight between global memory and LDS.
+constexpr int kLdsSliceBudget = 96 * 1024;
+
+// Column-tile width for a layer: 128 columns (two per lane of a wave) when the slice fits the LDS
+// budget, 64 when only that fits, and for narrow layers the next power of two >= m (at least 4).
+int choose_jt(int m, int K, int L, int scheme);
+
+}  // namespace lutkan
+
+struct lutkan_artifact {
+  lutkan_info info;
+  std::vector<float> ext_knots;   // [G+2p+1]
+  std::vector<float> knots;       // [K+1]
+  std::vector<uint8_t> q;         // canonical [E][K][L]
+  std::vector<float> scale;       // [E][K]
+  std::vector<float> ymin;        // [E][K]
+  std::vector<uint8_t> table;     // device LUT table, [t][i] slices
+  std::vector<float> coef_table;  // device B-spline table, [t][i][R][jt]
+};

@@ -1,0 +1,866 @@
+// gfx950 kernels and launchers of liblutkan: LUT-KAN layer forward and the B-spline baseline layer.
+//
+// Work split (Sec. 4.5, Sec. 5):
+//   1. locate kernel   per (row, input): domain test on the raw x (Sec. 5.2), safe clip (Eq. 13), segment
+//                      (Eq. 14), local coordinate (Eq. 15), (l0, w) (Eq. 16), all in IEEE fp32 with one
+//                      rounding per operation, written as a 8-byte "record" [input][row] so that it is
+//                      computed once and reused by all m outputs.
+//   2. edge kernel     per (row, output): for every input gather the two adjacent codes, dequantise (Eq. 10),
+//                      interpolate (Eq. 17), apply the oob_policy (Sec. 5.4) and accumulate (Eq. 1).
+//                      "gather" variant: codes straight from global memory (any shape, used for narrow layers
+//                      and for the trace);  "tiled" variant: a work-group owns (row tile) x (column tile),
+//                      walks the inputs, and stages each input's table slice in LDS.
+// The file is compiled with -ffp-contract=off; every fused multiply-add below is written out as fmaf().
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+
+#include "lutkan_internal.h"
+
+using lutkan::fail;
+
+namespace {
+
+constexpr int kWave = 64;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte load/store
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+constexpr int kMaskedBit = (int)0x80000000u;   // record: contribution is exactly zero (zero_spline, or padding row)
+constexpr int kRowBits = 20;                   // record: bits 0..19 = k*L + l0, bits 20..26 = k
+
+// ------------------------------------------------------------------------------------------------
+// Locate kernel (steps 1-4 of Sec. 4.5 + Sec. 5.2).
+// ------------------------------------------------------------------------------------------------
+struct LocateArgs {
+  const float *x;        // [B][d]
+  int32_t *rec_pk;       // [d][Bp]
+  float *rec_w;          // [d][Bp]
+  int64_t B, Bp;
+  int32_t d, K, L;
+  int32_t closed, zero_spline;
+  float tKs;             // safe upper clip value
+  float knots[LUTKAN_MAX_K + 1];
+  unsigned long long *stats;   // nullable: {oob_count, oob_any_rows}
+  int32_t *k_out, *l0_out;     // nullable trace outputs, [B][d]
+  uint8_t *in_out;
+  float *w_out;
+};
+
+struct Located {
+  int k, l0;
+  float w;
+  bool inside, is_nan;
+};
+
+__device__ __forceinline__ Located locate_one(const LocateArgs &a, float x) {
+  Located o;
+  const float t0 = a.knots[0];
+  const float tK = a.knots[a.K];
+  o.is_nan = (x != x);
+  o.inside = a.closed ? (x >= t0 && x <= tK) : (x >= t0 && x < tK);
+  float xc = o.is_nan ? t0 : x;
+  xc = (xc < t0) ? t0 : xc;
+  xc = (xc > a.tKs) ? a.tKs : xc;
+  // k = #{kappa in 1..K-1 : T[kappa] <= x'}; T[0] <= x' always holds and T[K] is clipped away (Eq. 14).
+  int k = 0;
+  float tk = t0, tk1 = a.knots[1];
+  for (int kappa = 1; kappa < a.K; ++kappa) {
+    const float t = a.knots[kappa];
+    const bool ge = (t <= xc);
+    k += ge ? 1 : 0;
+    tk = ge ? t : tk;
+    tk1 = ge ? a.knots[kappa + 1] : tk1;
+  }
+  const float num = __fsub_rn(xc, tk);
+  const float den = __fsub_rn(tk1, tk);
+  const float u = __fdiv_rn(num, den);                       // Eq. 15, correctly rounded
+  const float z = __fmul_rn(u, (float)(a.L - 1));            // Eq. 16
+  int l0 = (int)floorf(z);
+  l0 = min(max(l0, 0), a.L - 1);
+  o.k = k;
+  o.l0 = l0;
+  o.w = __fsub_rn(z, (float)l0);
+  return o;
+}
+
+constexpr int kLocRows = 32;    // rows per block
+constexpr int kLocCols = 64;    // inputs per pass
+
+__global__ __launch_bounds__(256) void lutkan_locate_kernel(const LocateArgs a) {
+  __shared__ int32_t s_pk[kLocCols][kLocRows + 1];
+  __shared__ float s_w[kLocCols][kLocRows + 1];
+  __shared__ int s_row_oob[kLocRows];
+  const int tid = threadIdx.x;
+  const int64_t b0 = (int64_t)blockIdx.x * kLocRows;
+  if (tid < kLocRows) s_row_oob[tid] = 0;
+  __syncthreads();
+  unsigned my_oob = 0;
+  for (int i0 = 0; i0 < a.d; i0 += kLocCols) {
+    // phase 1: read x along inputs (coalesced), locate, park the record in LDS
+    const int il = tid & (kLocCols - 1);
+    const int i = i0 + il;
+#pragma unroll
+    for (int p = 0; p < kLocRows / 4; ++p) {
+      const int bl = p * 4 + (tid >> 6);
+      const int64_t b = b0 + bl;
+      int pk = kMaskedBit;
+      float w = 0.0f;
+      if (b < a.B && i < a.d) {
+        const float x = a.x[b * a.d + i];
+        const Located o = locate_one(a, x);
+        const bool masked = a.zero_spline && !o.inside && !o.is_nan;
+        w = o.is_nan ? __builtin_nanf("") : o.w;
+        pk = (o.k * a.L + o.l0) | (o.k << kRowBits) | (masked ? kMaskedBit : 0);
+        if (!o.inside) { ++my_oob; s_row_oob[bl] = 1; }
+        if (a.k_out) {
+          a.k_out[b * a.d + i] = o.k;
+          a.l0_out[b * a.d + i] = o.l0;
+          a.in_out[b * a.d + i] = o.inside ? 1 : 0;
+          a.w_out[b * a.d + i] = o.w;
+        }
+      }
+      s_pk[il][bl] = pk;
+      s_w[il][bl] = w;
+    }
+    __syncthreads();
+    // phase 2: write records along rows (coalesced)
+    const int bl2 = tid & (kLocRows - 1);
+#pragma unroll
+    for (int p = 0; p < kLocCols / 8; ++p) {
+      const int il2 = p * 8 + (tid >> 5);
+      const int i2 = i0 + il2;
+      if (i2 < a.d && b0 + bl2 < a.Bp) {
+        a.rec_pk[(int64_t)i2 * a.Bp + b0 + bl2] = s_pk[il2][bl2];
+        a.rec_w[(int64_t)i2 * a.Bp + b0 + bl2] = s_w[il2][bl2];
+      }
+    }
+    __syncthreads();
+  }
+  if (a.stats) {
+    // one atomic per wave for the input counter, one per block for the row counter
+    unsigned v = my_oob;
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, kWave);
+    if ((tid & 63) == 0 && v) atomicAdd(&a.stats[0], (unsigned long long)v);
+    if (tid < kLocRows) {
+      unsigned r = (unsigned)s_row_oob[tid];
+      for (int off = 16; off > 0; off >>= 1) r += __shfl_down(r, off, kWave);
+      if (tid == 0 && r) atomicAdd(&a.stats[1], (unsigned long long)r);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Edge kernels.
+// ------------------------------------------------------------------------------------------------
+struct EdgeArgs {
+  const unsigned char *table;
+  const int32_t *rec_pk;
+  const float *rec_w;
+  float *y;
+  int16_t *q01_out;      // nullable, [B][d][m][2]
+  int64_t B, Bp;
+  int32_t d, m, K, L;
+  int32_t jt, n_tiles, blob_bytes;
+  int32_t alpha_off, ymin_off, codes_off;
+};
+
+template <int SCHEME>
+__device__ __forceinline__ float code_to_float(unsigned byte) {
+  if (SCHEME == LUTKAN_SYM_INT8) return (float)(int)(int8_t)byte;
+  return (float)(byte & 0xffu);
+}
+
+// Gather variant: one thread per (row, output column); consecutive threads take consecutive columns so the
+// two code rows and the parameter row are read as contiguous runs.
+template <int SCHEME, bool TRACE>
+__global__ __launch_bounds__(256) void lutkan_gather_kernel(const EdgeArgs a, const int jx_log2) {
+  const int jx = 1 << jx_log2;
+  const int tx = threadIdx.x & (jx - 1);
+  const int ty = threadIdx.x >> jx_log2;
+  const int j = blockIdx.y * jx + tx;
+  const int64_t b = (int64_t)blockIdx.x * (256 >> jx_log2) + ty;
+  if (j >= a.m || b >= a.B) return;
+  const int t = j / a.jt, jj = j - t * a.jt;
+  const unsigned char *slice = a.table + (size_t)t * a.d * a.blob_bytes;
+  float acc = 0.0f;
+  for (int i = 0; i < a.d; ++i, slice += a.blob_bytes) {
+    const int pk = a.rec_pk[(int64_t)i * a.Bp + b];
+    const float w = a.rec_w[(int64_t)i * a.Bp + b];
+    const int row = pk & ((1 << kRowBits) - 1);
+    const int k = (pk >> kRowBits) & 0x7f;
+    const int l0 = row - k * a.L;
+    const int row1 = (l0 + 1 < a.L) ? row + 1 : row;                       // l1 = min(l0+1, L-1)
+    const unsigned char *codes = slice + a.codes_off;
+    const unsigned c0 = codes[(size_t)row * a.jt + jj];
+    const unsigned c1 = codes[(size_t)row1 * a.jt + jj];
+    if (TRACE && a.q01_out) {
+      int16_t *o = a.q01_out + ((b * a.d + i) * a.m + j) * 2;
+      o[0] = (int16_t)code_to_float<SCHEME>(c0);
+      o[1] = (int16_t)code_to_float<SCHEME>(c1);
+    }
+    if (pk < 0) continue;                                                  // oob_policy zero_spline: exactly 0
+    const float alpha = reinterpret_cast<const float *>(slice + a.alpha_off)[k * a.jt + jj];
+    const float f0 = code_to_float<SCHEME>(c0), f1 = code_to_float<SCHEME>(c1);
+    const float tq = fmaf(w, f1 - f0, f0);                                 // interpolate the codes ...
+    acc = fmaf(alpha, tq, acc);                                            // ... then one scale per edge
+    if (SCHEME == LUTKAN_ASYM_UINT8) acc += reinterpret_cast<const float *>(slice + a.ymin_off)[k * a.jt + jj];
+  }
+  a.y[b * a.m + j] = acc;
+}
+
+// Tiled variant.  A work-group of NW waves owns NW*RW rows and one column tile of JT = 64*CPL outputs; each
+// wave owns RW rows, each lane CPL adjacent columns, so a lane keeps RW*CPL running sums in registers for the
+// whole walk over the d inputs.  Per input the (tile, input) table slice is copied global -> registers while
+// the previous input is being processed, then registers -> LDS between two barriers.  A wave handles one row
+// at a time: the row's record is wave-uniform (broadcast from the lane that loaded it), the 64 lanes read
+// one contiguous run of codes for l0, one for l0+1 and one run of scales, without bank conflicts.
+// l0+1 is read even when l0 = L-1: then w = 0 exactly, the neighbour is the next segment's first row (or the
+// zeroed padding row after the last segment) and does not change the result.
+template <int SCHEME, int CPL, int RW, int NW, int PF>
+__global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  constexpr int JT = 64 * CPL;
+  constexpr int NT = NW * 64;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int t = blockIdx.x % a.n_tiles;
+  const int64_t rt = blockIdx.x / a.n_tiles;
+  const int64_t b0 = rt * (NW * RW) + (int64_t)wave * RW;
+  const int nvec = a.blob_bytes >> 4;
+
+  for (int o = a.blob_bytes + tid * 4; o < a.blob_bytes + JT + 16; o += NT * 4) *reinterpret_cast<uint32_t *>(lds + o) = 0u;
+
+  float acc[RW][CPL];
+#pragma unroll
+  for (int r = 0; r < RW; ++r)
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) acc[r][c] = 0.0f;
+
+  const u32x4 *src = reinterpret_cast<const u32x4 *>(a.table + (size_t)t * a.d * a.blob_bytes);
+  u32x4 pf[PF];
+#pragma unroll
+  for (int p = 0; p < PF; ++p) {
+    const int v = p * NT + tid;
+    if (v < nvec) pf[p] = src[v];
+  }
+  const int rl = (lane < RW) ? lane : 0;
+  int cur_pk = a.rec_pk[b0 + rl];
+  float cur_w = a.rec_w[b0 + rl];
+
+  const unsigned char *codes_lds = lds + a.codes_off + lane * CPL;
+  const unsigned char *alpha_lds = lds + a.alpha_off + lane * CPL * 4;
+  const unsigned char *ymin_lds = lds + a.ymin_off + lane * CPL * 4;
+
+  for (int i = 0; i < a.d; ++i) {
+    __syncthreads();                                   // everyone is done with the previous slice
+#pragma unroll
+    for (int p = 0; p < PF; ++p) {
+      const int v = p * NT + tid;
+      if (v < nvec) reinterpret_cast<u32x4 *>(lds)[v] = pf[p];
+    }
+    __syncthreads();
+    int nxt_pk = 0;
+    float nxt_w = 0.0f;
+    if (i + 1 < a.d) {
+      const u32x4 *nsrc = src + (size_t)(i + 1) * nvec;
+#pragma unroll
+      for (int p = 0; p < PF; ++p) {
+        const int v = p * NT + tid;
+        if (v < nvec) pf[p] = nsrc[v];
+      }
+      nxt_pk = a.rec_pk[(int64_t)(i + 1) * a.Bp + b0 + rl];
+      nxt_w = a.rec_w[(int64_t)(i + 1) * a.Bp + b0 + rl];
+    }
+#pragma unroll
+    for (int r = 0; r < RW; ++r) {
+      const int pk = __builtin_amdgcn_readlane(cur_pk, r);
+      const float w = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(cur_w), r));
+      if (pk >= 0) {
+        const int row = pk & ((1 << kRowBits) - 1);
+        const int k = (pk >> kRowBits) & 0x7f;
+        const unsigned char *cp = codes_lds + row * JT;
+        const unsigned char *ap = alpha_lds + k * (JT * 4);
+        if (CPL == 2) {
+          const unsigned c0 = *reinterpret_cast<const uint16_t *>(cp);
+          const unsigned c1 = *reinterpret_cast<const uint16_t *>(cp + JT);
+          const f32x2 al = *reinterpret_cast<const f32x2 *>(ap);
+          const float f00 = code_to_float<SCHEME>(c0), f01 = code_to_float<SCHEME>(c0 >> 8);
+          const float f10 = code_to_float<SCHEME>(c1), f11 = code_to_float<SCHEME>(c1 >> 8);
+          const float t0 = fmaf(w, f10 - f00, f00);
+          const float t1 = fmaf(w, f11 - f01, f01);
+          acc[r][0] = fmaf(al.x, t0, acc[r][0]);
+          acc[r][CPL - 1] = fmaf(al.y, t1, acc[r][CPL - 1]);
+          if (SCHEME == LUTKAN_ASYM_UINT8) {
+            const f32x2 ym = *reinterpret_cast<const f32x2 *>(ymin_lds + k * (JT * 4));
+            acc[r][0] += ym.x;
+            acc[r][CPL - 1] += ym.y;
+          }
+        } else {
+          const unsigned c0 = *cp;
+          const unsigned c1 = *(cp + JT);
+          const float al = *reinterpret_cast<const float *>(ap);
+          const float f0 = code_to_float<SCHEME>(c0), f1 = code_to_float<SCHEME>(c1);
+          const float t0 = fmaf(w, f1 - f0, f0);
+          acc[r][0] = fmaf(al, t0, acc[r][0]);
+          if (SCHEME == LUTKAN_ASYM_UINT8) acc[r][0] += *reinterpret_cast<const float *>(ymin_lds + k * (JT * 4));
+        }
+      }
+    }
+    cur_pk = nxt_pk;
+    cur_w = nxt_w;
+  }
+
+  const int j = t * JT + lane * CPL;
+#pragma unroll
+  for (int r = 0; r < RW; ++r) {
+    const int64_t b = b0 + r;
+    if (b < a.B) {
+#pragma unroll
+      for (int c = 0; c < CPL; ++c)
+        if (j + c < a.m) a.y[b * a.m + j + c] = acc[r][c];
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// B-spline baseline (Sec. 3.2-3.3).
+// ------------------------------------------------------------------------------------------------
+struct SplineLocateArgs {
+  const float *x;
+  int32_t *rec_pk;       // [d][Bp]: first coefficient row r0 = k, or masked
+  float *rec_n;          // [4][d][Bp]: the four non-zero cubic basis values
+  int64_t B, Bp;
+  int32_t d, G;
+  int32_t closed, zero_spline;
+  float tKs;
+  float ext_knots[LUTKAN_MAX_K + 7];
+};
+
+__global__ __launch_bounds__(256) void bspline_locate_kernel(const SplineLocateArgs a) {
+  __shared__ int32_t s_pk[kLocCols][kLocRows + 1];
+  __shared__ float s_n[4][kLocCols][kLocRows + 1];
+  __shared__ float s_tau[LUTKAN_MAX_K + 7];
+  const int tid = threadIdx.x;
+  const int64_t b0 = (int64_t)blockIdx.x * kLocRows;
+  for (int r = tid; r < a.G + 7; r += 256) s_tau[r] = a.ext_knots[r];
+  __syncthreads();
+  const float t0 = s_tau[3], tK = s_tau[3 + a.G];
+  for (int i0 = 0; i0 < a.d; i0 += kLocCols) {
+    const int il = tid & (kLocCols - 1);
+    const int i = i0 + il;
+#pragma unroll 1
+    for (int p = 0; p < kLocRows / 4; ++p) {
+      const int bl = p * 4 + (tid >> 6);
+      const int64_t b = b0 + bl;
+      int pk = kMaskedBit;
+      float n0 = 0.f, n1 = 0.f, n2 = 0.f, n3 = 0.f;
+      if (b < a.B && i < a.d) {
+        const float x = a.x[b * a.d + i];
+        const bool is_nan = (x != x);
+        const bool inside = a.closed ? (x >= t0 && x <= tK) : (x >= t0 && x < tK);
+        float xc = is_nan ? t0 : x;
+        xc = (xc < t0) ? t0 : xc;
+        xc = (xc > a.tKs) ? a.tKs : xc;
+        int k = 0;
+        for (int kappa = 1; kappa < a.G; ++kappa) k += (s_tau[3 + kappa] <= xc) ? 1 : 0;
+        // Cox-de Boor on the span mu = k+3, non-zero entries only (Eq. 4-5); knots are distinct.
+        const float *tau = s_tau + k;               // tau[0..7] = ext_knots[mu-3 .. mu+4]
+        float lower[5] = {0.f, 0.f, 0.f, 1.f, 0.f};
+#pragma unroll
+        for (int q = 1; q <= 3; ++q) {
+          float next[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int s = 3 - q; s <= 3; ++s) {
+            const float left = (xc - tau[s]) / (tau[s + q] - tau[s]) * lower[s];
+            const float right = (tau[s + q + 1] - xc) / (tau[s + q + 1] - tau[s + 1]) * lower[s + 1];
+            next[s] = left + right;
+          }
+#pragma unroll
+          for (int s = 0; s < 5; ++s) lower[s] = next[s];
+        }
+        const bool masked = a.zero_spline && !inside && !is_nan;
+        const float poison = is_nan ? __builtin_nanf("") : 1.0f;
+        n0 = lower[0] * poison; n1 = lower[1] * poison; n2 = lower[2] * poison; n3 = lower[3] * poison;
+        pk = k | (masked ? kMaskedBit : 0);
+      }
+      s_pk[il][bl] = pk;
+      s_n[0][il][bl] = n0; s_n[1][il][bl] = n1; s_n[2][il][bl] = n2; s_n[3][il][bl] = n3;
+    }
+    __syncthreads();
+    const int bl2 = tid & (kLocRows - 1);
+    const int64_t plane = (int64_t)a.d * a.Bp;
+#pragma unroll 1
+    for (int p = 0; p < kLocCols / 8; ++p) {
+      const int il2 = p * 8 + (tid >> 5);
+      const int i2 = i0 + il2;
+      if (i2 < a.d && b0 + bl2 < a.Bp) {
+        const int64_t o = (int64_t)i2 * a.Bp + b0 + bl2;
+        a.rec_pk[o] = s_pk[il2][bl2];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) a.rec_n[c * plane + o] = s_n[c][il2][bl2];
+      }
+    }
+    __syncthreads();
+  }
+}
+
+struct SplineEdgeArgs {
+  const float *coef_table;   // [t][i][R][jt]
+  const int32_t *rec_pk;
+  const float *rec_n;
+  float *y;
+  int64_t B, Bp;
+  int32_t d, m, R;
+  int32_t jt, n_tiles;
+};
+
+__global__ __launch_bounds__(256) void bspline_gather_kernel(const SplineEdgeArgs a, const int jx_log2) {
+  const int jx = 1 << jx_log2;
+  const int tx = threadIdx.x & (jx - 1);
+  const int ty = threadIdx.x >> jx_log2;
+  const int j = blockIdx.y * jx + tx;
+  const int64_t b = (int64_t)blockIdx.x * (256 >> jx_log2) + ty;
+  if (j >= a.m || b >= a.B) return;
+  const int t = j / a.jt, jj = j - t * a.jt;
+  const int64_t plane = (int64_t)a.d * a.Bp;
+  const float *slice = a.coef_table + (size_t)t * a.d * a.R * a.jt;
+  float acc = 0.0f;
+  for (int i = 0; i < a.d; ++i, slice += (size_t)a.R * a.jt) {
+    const int64_t o = (int64_t)i * a.Bp + b;
+    const int pk = a.rec_pk[o];
+    if (pk < 0) continue;
+    const float *c = slice + (size_t)pk * a.jt + jj;
+    acc = fmaf(a.rec_n[o], c[0], acc);
+    acc = fmaf(a.rec_n[plane + o], c[a.jt], acc);
+    acc = fmaf(a.rec_n[2 * plane + o], c[2 * a.jt], acc);
+    acc = fmaf(a.rec_n[3 * plane + o], c[3 * a.jt], acc);
+  }
+  a.y[b * a.m + j] = acc;
+}
+
+// Tiled B-spline kernel: same ownership as the LUT tiled kernel; the staged slice is the input's coefficient
+// matrix c[R][JT]; per row four contiguous coefficient runs (r0..r0+3) are read and weighted by the row's
+// four basis values.
+template <int CPL, int RW, int NW, int PF>
+__global__ __launch_bounds__(NW * 64) void bspline_tiled_kernel(const SplineEdgeArgs a) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  constexpr int JT = 64 * CPL;
+  constexpr int NT = NW * 64;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int t = blockIdx.x % a.n_tiles;
+  const int64_t rt = blockIdx.x / a.n_tiles;
+  const int64_t b0 = rt * (NW * RW) + (int64_t)wave * RW;
+  const int nvec = (a.R * JT * 4) >> 4;
+  const int64_t plane = (int64_t)a.d * a.Bp;
+
+  float acc[RW][CPL];
+#pragma unroll
+  for (int r = 0; r < RW; ++r)
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) acc[r][c] = 0.0f;
+
+  const u32x4 *src = reinterpret_cast<const u32x4 *>(a.coef_table + (size_t)t * a.d * a.R * JT);
+  u32x4 pf[PF];
+#pragma unroll
+  for (int p = 0; p < PF; ++p) {
+    const int v = p * NT + tid;
+    if (v < nvec) pf[p] = src[v];
+  }
+  const int rl = (lane < RW) ? lane : 0;
+  int cur_pk = a.rec_pk[b0 + rl];
+  float cur_n[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) cur_n[c] = a.rec_n[c * plane + b0 + rl];
+  const unsigned char *coef_lds = lds + lane * CPL * 4;
+
+  for (int i = 0; i < a.d; ++i) {
+    __syncthreads();
+#pragma unroll
+    for (int p = 0; p < PF; ++p) {
+      const int v = p * NT + tid;
+      if (v < nvec) reinterpret_cast<u32x4 *>(lds)[v] = pf[p];
+    }
+    __syncthreads();
+    int nxt_pk = 0;
+    float nxt_n[4] = {0.f, 0.f, 0.f, 0.f};
+    if (i + 1 < a.d) {
+      const u32x4 *nsrc = src + (size_t)(i + 1) * nvec;
+#pragma unroll
+      for (int p = 0; p < PF; ++p) {
+        const int v = p * NT + tid;
+        if (v < nvec) pf[p] = nsrc[v];
+      }
+      const int64_t o = (int64_t)(i + 1) * a.Bp + b0 + rl;
+      nxt_pk = a.rec_pk[o];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) nxt_n[c] = a.rec_n[c * plane + o];
+    }
+#pragma unroll
+    for (int r = 0; r < RW; ++r) {
+      const int pk = __builtin_amdgcn_readlane(cur_pk, r);
+      if (pk >= 0) {
+        const unsigned char *cp = coef_lds + pk * (JT * 4);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const float n = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(cur_n[c]), r));
+          if (CPL == 2) {
+            const f32x2 cf = *reinterpret_cast<const f32x2 *>(cp + c * (JT * 4));
+            acc[r][0] = fmaf(n, cf.x, acc[r][0]);
+            acc[r][CPL - 1] = fmaf(n, cf.y, acc[r][CPL - 1]);
+          } else {
+            acc[r][0] = fmaf(n, *reinterpret_cast<const float *>(cp + c * (JT * 4)), acc[r][0]);
+          }
+        }
+      }
+    }
+    cur_pk = nxt_pk;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) cur_n[c] = nxt_n[c];
+  }
+
+  const int j = t * JT + lane * CPL;
+#pragma unroll
+  for (int r = 0; r < RW; ++r) {
+    const int64_t b = b0 + r;
+    if (b < a.B) {
+#pragma unroll
+      for (int c = 0; c < CPL; ++c)
+        if (j + c < a.m) a.y[b * a.m + j + c] = acc[r][c];
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Host launchers.
+// ------------------------------------------------------------------------------------------------
+constexpr int kTileWaves = 16;          // waves per tiled work-group (1024 threads, one work-group per CU)
+constexpr int kMaxRowTile = kTileWaves * 32;
+
+inline int64_t round_up(int64_t v, int64_t q) { return (v + q - 1) / q * q; }
+inline int64_t padded_rows(int64_t B) { return round_up(B, kMaxRowTile); }
+
+int check_launch(const char *what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(LUTKAN_EHIP, "%s: %s", what, hipGetErrorString(e));
+  return LUTKAN_OK;
+}
+
+int validate_layer(const lutkan_dev_layer *l, const char *who) {
+  if (!l) return fail(LUTKAN_EINVAL, "%s: null layer", who);
+  if (!l->table) return fail(LUTKAN_EINVAL, "%s: layer.table is null", who);
+  if (l->d < 1 || l->m < 1 || l->K < 1 || l->L < 2) return fail(LUTKAN_EINVAL, "%s: bad d/m/K/L (%d,%d,%d,%d)", who, l->d, l->m, l->K, l->L);
+  if (l->K > LUTKAN_MAX_K || (int64_t)l->K * l->L > LUTKAN_MAX_ROWS) return fail(LUTKAN_EUNSUPPORTED, "%s: K or K*L too large", who);
+  if (l->scheme != LUTKAN_SYM_INT8 && l->scheme != LUTKAN_ASYM_UINT8) return fail(LUTKAN_EINVAL, "%s: bad scheme %d", who, l->scheme);
+  if (l->boundary != LUTKAN_HALF_OPEN && l->boundary != LUTKAN_CLOSED) return fail(LUTKAN_EINVAL, "%s: bad boundary_mode %d", who, l->boundary);
+  if (l->oob != LUTKAN_CLIP_X && l->oob != LUTKAN_ZERO_SPLINE) return fail(LUTKAN_EINVAL, "%s: bad oob_policy %d", who, l->oob);
+  if (l->algo < LUTKAN_ALGO_AUTO || l->algo > LUTKAN_ALGO_TILED) return fail(LUTKAN_EINVAL, "%s: bad algo %d", who, l->algo);
+  for (int k = 0; k < l->K; ++k)
+    if (!(l->knots[k] < l->knots[k + 1])) return fail(LUTKAN_EINVAL, "%s: knots not strictly increasing at %d", who, k);
+  if (l->jt < 4 || l->jt > 128 || (l->jt & (l->jt - 1))) return fail(LUTKAN_EINVAL, "%s: jt=%d is not a power of two in [4,128]", who, l->jt);
+  if (l->n_tiles != (l->m + l->jt - 1) / l->jt) return fail(LUTKAN_ESHAPE, "%s: n_tiles does not match m and jt", who);
+  if (l->blob_bytes != lutkan::blob_layout(l->K, l->L, l->jt, l->scheme).bytes) return fail(LUTKAN_ESHAPE, "%s: blob_bytes does not match K, L, jt, scheme", who);
+  if ((reinterpret_cast<uintptr_t>(l->table) & 15) != 0) return fail(LUTKAN_EINVAL, "%s: table must be 16-byte aligned", who);
+  return LUTKAN_OK;
+}
+
+int gather_jx_log2(int m) {
+  int lg = 2;
+  while ((1 << lg) < m && lg < 8) ++lg;
+  return lg;
+}
+
+template <int SCHEME, int CPL, int RW>
+int launch_tiled_pf(const EdgeArgs &ea, hipStream_t s) {
+  constexpr int NW = kTileWaves;
+  const int nvec = ea.blob_bytes >> 4;
+  const int pf = (nvec + NW * 64 - 1) / (NW * 64);
+  const int64_t row_tiles = (ea.B + NW * RW - 1) / (NW * RW);
+  const dim3 grid((unsigned)(row_tiles * ea.n_tiles));
+  const size_t lds = (size_t)ea.blob_bytes + 64 * CPL + 16;
+#define LUTKAN_TILED_CASE(N)                                                                                          \
+  case N: {                                                                                                           \
+    auto kern = lutkan_tiled_kernel<SCHEME, CPL, RW, NW, N>;                                                          \
+    static bool lds_raised = false; /* the default cap on dynamic LDS is below the 160 KiB a gfx950 CU has */         \
+    if (!lds_raised) {                                                                                                \
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 120 * 1024); \
+      if (e != hipSuccess) return fail(LUTKAN_EHIP, "hipFuncSetAttribute(LDS): %s", hipGetErrorString(e));            \
+      lds_raised = true;                                                                                              \
+    }                                                                                                                 \
+    hipLaunchKernelGGL(kern, grid, dim3(NW * 64), lds, s, ea);                                                        \
+    break;                                                                                                            \
+  }
+  switch (pf) {
+    LUTKAN_TILED_CASE(1)
+    LUTKAN_TILED_CASE(2)
+    LUTKAN_TILED_CASE(3)
+    LUTKAN_TILED_CASE(4)
+    LUTKAN_TILED_CASE(5)
+    LUTKAN_TILED_CASE(6)
+    default:
+      return fail(LUTKAN_EUNSUPPORTED, "tiled kernel: table slice of %d bytes is too large to stage", ea.blob_bytes);
+  }
+#undef LUTKAN_TILED_CASE
+  return check_launch("lutkan_tiled_kernel");
+}
+
+template <int SCHEME, int CPL>
+int launch_tiled(const EdgeArgs &ea, int rw, hipStream_t s) {
+  switch (rw) {
+    case 32: return launch_tiled_pf<SCHEME, CPL, 32>(ea, s);
+    case 16: return launch_tiled_pf<SCHEME, CPL, 16>(ea, s);
+    case 8: return launch_tiled_pf<SCHEME, CPL, 8>(ea, s);
+    default: return launch_tiled_pf<SCHEME, CPL, 4>(ea, s);
+  }
+}
+
+// Rows per wave: the largest of 32/16/8/4 that still gives every CU a work-group.
+int choose_rw(int64_t B, int n_tiles) {
+  for (int rw = 32; rw > 4; rw >>= 1) {
+    const int64_t groups = (B + kTileWaves * rw - 1) / (kTileWaves * rw) * n_tiles;
+    if (groups >= 256) return rw;
+  }
+  return 4;
+}
+
+bool tiled_supported(int jt, int blob_bytes) {
+  return (jt == 64 || jt == 128) && blob_bytes <= 6 * kTileWaves * 64 * 16;
+}
+
+enum { kLocate = 1, kEdges = 2 };
+
+int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y, lutkan_oob_stats *stats,
+                 int32_t *k_out, int32_t *l0_out, uint8_t *in_out, float *w_out, int16_t *q01_out, bool trace,
+                 void *workspace, size_t workspace_bytes, void *hip_stream, const char *who, int phases = kLocate | kEdges) {
+  if (int rc = validate_layer(l, who)) return rc;
+  if (B < 0) return fail(LUTKAN_EINVAL, "%s: B < 0", who);
+  if (B == 0) return LUTKAN_OK;
+  if (((phases & kLocate) && !x) || ((phases & kEdges) && !y)) return fail(LUTKAN_EINVAL, "%s: null x or y", who);
+  if (x == y) return fail(LUTKAN_EINVAL, "%s: x and y alias", who);
+  if (trace && (!k_out || !l0_out || !in_out || !w_out)) return fail(LUTKAN_EINVAL, "%s: null trace output", who);
+  const size_t need = lutkan_forward_workspace_bytes(l, B);
+  if (!workspace || workspace_bytes < need) return fail(LUTKAN_ESHAPE, "%s: workspace of %zu bytes, need %zu", who, workspace_bytes, need);
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return fail(LUTKAN_EINVAL, "%s: workspace must be 256-byte aligned", who);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const int64_t Bp = padded_rows(B);
+
+  LocateArgs la;
+  la.x = x;
+  la.rec_pk = static_cast<int32_t *>(workspace);
+  la.rec_w = reinterpret_cast<float *>(static_cast<char *>(workspace) + (size_t)l->d * Bp * 4);
+  la.B = B; la.Bp = Bp; la.d = l->d; la.K = l->K; la.L = l->L;
+  la.closed = (l->boundary == LUTKAN_CLOSED);
+  la.zero_spline = (l->oob == LUTKAN_ZERO_SPLINE);
+  la.tKs = la.closed ? l->knots[l->K] : std::nextafterf(l->knots[l->K], -INFINITY);
+  for (int k = 0; k <= l->K; ++k) la.knots[k] = l->knots[k];
+  la.stats = reinterpret_cast<unsigned long long *>(stats);
+  la.k_out = trace ? k_out : nullptr; la.l0_out = l0_out; la.in_out = in_out; la.w_out = w_out;
+  if (phases & kLocate) {
+    hipLaunchKernelGGL(lutkan_locate_kernel, dim3((unsigned)(Bp / kLocRows)), dim3(256), 0, s, la);
+    if (int rc = check_launch("lutkan_locate_kernel")) return rc;
+  }
+  if (!(phases & kEdges)) return LUTKAN_OK;
+
+  const lutkan::BlobLayout lay = lutkan::blob_layout(l->K, l->L, l->jt, l->scheme);
+  EdgeArgs ea;
+  ea.table = static_cast<const unsigned char *>(l->table);
+  ea.rec_pk = la.rec_pk; ea.rec_w = la.rec_w; ea.y = y; ea.q01_out = q01_out;
+  ea.B = B; ea.Bp = Bp; ea.d = l->d; ea.m = l->m; ea.K = l->K; ea.L = l->L;
+  ea.jt = l->jt; ea.n_tiles = l->n_tiles; ea.blob_bytes = l->blob_bytes;
+  ea.alpha_off = lay.alpha_off; ea.ymin_off = lay.ymin_off; ea.codes_off = lay.codes_off;
+
+  bool tiled = tiled_supported(l->jt, l->blob_bytes) && !q01_out;
+  if (l->algo == LUTKAN_ALGO_GATHER) tiled = false;
+  if (l->algo == LUTKAN_ALGO_TILED && !tiled) return fail(LUTKAN_EUNSUPPORTED, "%s: tiled kernel needs jt in {64,128} and a slice <= 96 KiB", who);
+  if (tiled) {
+    const int rw = choose_rw(B, l->n_tiles);
+    if (l->scheme == LUTKAN_SYM_INT8)
+      return (l->jt == 128) ? launch_tiled<LUTKAN_SYM_INT8, 2>(ea, rw, s) : launch_tiled<LUTKAN_SYM_INT8, 1>(ea, rw, s);
+    return (l->jt == 128) ? launch_tiled<LUTKAN_ASYM_UINT8, 2>(ea, rw, s) : launch_tiled<LUTKAN_ASYM_UINT8, 1>(ea, rw, s);
+  }
+  const int lg = gather_jx_log2(l->m);
+  const dim3 grid((unsigned)((B + (256 >> lg) - 1) / (256 >> lg)), (unsigned)((l->m + (1 << lg) - 1) >> lg));
+  if (grid.y > 65535u) return fail(LUTKAN_EUNSUPPORTED, "%s: m too large for the gather kernel", who);
+  if (l->scheme == LUTKAN_SYM_INT8) {
+    if (q01_out) hipLaunchKernelGGL((lutkan_gather_kernel<LUTKAN_SYM_INT8, true>), grid, dim3(256), 0, s, ea, lg);
+    else hipLaunchKernelGGL((lutkan_gather_kernel<LUTKAN_SYM_INT8, false>), grid, dim3(256), 0, s, ea, lg);
+  } else {
+    if (q01_out) hipLaunchKernelGGL((lutkan_gather_kernel<LUTKAN_ASYM_UINT8, true>), grid, dim3(256), 0, s, ea, lg);
+    else hipLaunchKernelGGL((lutkan_gather_kernel<LUTKAN_ASYM_UINT8, false>), grid, dim3(256), 0, s, ea, lg);
+  }
+  return check_launch("lutkan_gather_kernel");
+}
+
+template <int CPL, int RW>
+int launch_spline_tiled_rw(const SplineEdgeArgs &ea, hipStream_t s) {
+  constexpr int NW = kTileWaves;
+  const int bytes = ea.R * 64 * CPL * 4;
+  const int pf = ((bytes >> 4) + NW * 64 - 1) / (NW * 64);
+  const int64_t row_tiles = (ea.B + NW * RW - 1) / (NW * RW);
+  const dim3 grid((unsigned)(row_tiles * ea.n_tiles));
+  if (pf == 1) hipLaunchKernelGGL((bspline_tiled_kernel<CPL, RW, NW, 1>), grid, dim3(NW * 64), (size_t)bytes, s, ea);
+  else if (pf == 2) hipLaunchKernelGGL((bspline_tiled_kernel<CPL, RW, NW, 2>), grid, dim3(NW * 64), (size_t)bytes, s, ea);
+  else if (pf == 3) hipLaunchKernelGGL((bspline_tiled_kernel<CPL, RW, NW, 3>), grid, dim3(NW * 64), (size_t)bytes, s, ea);
+  else return fail(LUTKAN_EUNSUPPORTED, "bspline tiled kernel: coefficient slice of %d bytes too large", bytes);
+  return check_launch("bspline_tiled_kernel");
+}
+
+template <int CPL>
+int launch_spline_tiled(const SplineEdgeArgs &ea, int rw, hipStream_t s) {
+  switch (rw) {
+    case 32: return launch_spline_tiled_rw<CPL, 32>(ea, s);
+    case 16: return launch_spline_tiled_rw<CPL, 16>(ea, s);
+    case 8: return launch_spline_tiled_rw<CPL, 8>(ea, s);
+    default: return launch_spline_tiled_rw<CPL, 4>(ea, s);
+  }
+}
+
+}  // namespace
+
+extern "C" size_t lutkan_forward_workspace_bytes(const lutkan_dev_layer *layer, int64_t B) {
+  if (!layer || B <= 0) return 0;
+  return (size_t)layer->d * (size_t)padded_rows(B) * 8;
+}
+
+extern "C" size_t bspline_forward_workspace_bytes(const bspline_dev_layer *layer, int64_t B) {
+  if (!layer || B <= 0) return 0;
+  return (size_t)layer->d * (size_t)padded_rows(B) * 20;
+}
+
+extern "C" int lutkan_forward(const lutkan_dev_layer *layer, const float *x, int64_t B, float *y,
+                              lutkan_oob_stats *stats, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  return forward_impl(layer, x, B, y, stats, nullptr, nullptr, nullptr, nullptr, nullptr, false, workspace,
+                      workspace_bytes, hip_stream, "lutkan_forward");
+}
+
+extern "C" int lutkan_forward_locate(const lutkan_dev_layer *layer, const float *x, int64_t B, lutkan_oob_stats *stats,
+                                     void *workspace, size_t workspace_bytes, void *hip_stream) {
+  return forward_impl(layer, x, B, nullptr, stats, nullptr, nullptr, nullptr, nullptr, nullptr, false, workspace,
+                      workspace_bytes, hip_stream, "lutkan_forward_locate", kLocate);
+}
+
+extern "C" int lutkan_forward_edges(const lutkan_dev_layer *layer, int64_t B, float *y, void *workspace,
+                                    size_t workspace_bytes, void *hip_stream) {
+  return forward_impl(layer, nullptr, B, y, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, false, workspace,
+                      workspace_bytes, hip_stream, "lutkan_forward_edges", kEdges);
+}
+
+extern "C" int lutkan_forward_trace(const lutkan_dev_layer *layer, const float *x, int64_t B, float *y,
+                                    int32_t *k_out, int32_t *l0_out, uint8_t *in_out, float *w_out, int16_t *q01_out,
+                                    void *workspace, size_t workspace_bytes, void *hip_stream) {
+  return forward_impl(layer, x, B, y, nullptr, k_out, l0_out, in_out, w_out, q01_out, true, workspace,
+                      workspace_bytes, hip_stream, "lutkan_forward_trace");
+}
+
+namespace {
+int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y, void *workspace,
+                 size_t workspace_bytes, void *hip_stream, const char *who, int phases) {
+  if (!l) return fail(LUTKAN_EINVAL, "%s: null layer", who);
+  if (!l->coef_table) return fail(LUTKAN_EINVAL, "%s: layer.coef_table is null", who);
+  if (l->d < 1 || l->m < 1 || l->G < 1 || l->G > LUTKAN_MAX_K) return fail(LUTKAN_EINVAL, "%s: bad d/m/G", who);
+  if (l->degree != 3) return fail(LUTKAN_EUNSUPPORTED, "%s: only cubic splines", who);
+  if (l->boundary != LUTKAN_HALF_OPEN && l->boundary != LUTKAN_CLOSED) return fail(LUTKAN_EINVAL, "%s: bad boundary_mode", who);
+  if (l->oob != LUTKAN_CLIP_X && l->oob != LUTKAN_ZERO_SPLINE) return fail(LUTKAN_EINVAL, "%s: bad oob_policy", who);
+  if (l->algo < LUTKAN_ALGO_AUTO || l->algo > LUTKAN_ALGO_TILED) return fail(LUTKAN_EINVAL, "%s: bad algo", who);
+  for (int r = 0; r < l->G + 6; ++r)
+    if (!(l->ext_knots[r] < l->ext_knots[r + 1])) return fail(LUTKAN_EINVAL, "%s: knots not strictly increasing at %d", who, r);
+  if (l->jt < 4 || l->jt > 128 || (l->jt & (l->jt - 1))) return fail(LUTKAN_EINVAL, "%s: bad jt", who);
+  if (l->n_tiles != (l->m + l->jt - 1) / l->jt) return fail(LUTKAN_ESHAPE, "%s: n_tiles does not match m and jt", who);
+  if ((reinterpret_cast<uintptr_t>(l->coef_table) & 15) != 0) return fail(LUTKAN_EINVAL, "%s: coef_table must be 16-byte aligned", who);
+  if (B < 0) return fail(LUTKAN_EINVAL, "%s: B < 0", who);
+  if (B == 0) return LUTKAN_OK;
+  if (((phases & kLocate) && !x) || ((phases & kEdges) && !y) || x == y) return fail(LUTKAN_EINVAL, "%s: null or aliased x / y", who);
+  const size_t need = bspline_forward_workspace_bytes(l, B);
+  if (!workspace || workspace_bytes < need) return fail(LUTKAN_ESHAPE, "%s: workspace of %zu bytes, need %zu", who, workspace_bytes, need);
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return fail(LUTKAN_EINVAL, "%s: workspace must be 256-byte aligned", who);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const int64_t Bp = padded_rows(B);
+  const int G = l->G;
+
+  SplineLocateArgs la;
+  la.x = x;
+  la.rec_pk = static_cast<int32_t *>(workspace);
+  la.rec_n = reinterpret_cast<float *>(static_cast<char *>(workspace) + (size_t)l->d * Bp * 4);
+  la.B = B; la.Bp = Bp; la.d = l->d; la.G = G;
+  la.closed = (l->boundary == LUTKAN_CLOSED);
+  la.zero_spline = (l->oob == LUTKAN_ZERO_SPLINE);
+  la.tKs = la.closed ? l->ext_knots[3 + G] : std::nextafterf(l->ext_knots[3 + G], -INFINITY);
+  for (int r = 0; r < G + 7; ++r) la.ext_knots[r] = l->ext_knots[r];
+  if (phases & kLocate) {
+    hipLaunchKernelGGL(bspline_locate_kernel, dim3((unsigned)(Bp / kLocRows)), dim3(256), 0, s, la);
+    if (int rc = check_launch("bspline_locate_kernel")) return rc;
+  }
+  if (!(phases & kEdges)) return LUTKAN_OK;
+
+  SplineEdgeArgs ea;
+  ea.coef_table = l->coef_table; ea.rec_pk = la.rec_pk; ea.rec_n = la.rec_n; ea.y = y;
+  ea.B = B; ea.Bp = Bp; ea.d = l->d; ea.m = l->m; ea.R = G + 3; ea.jt = l->jt; ea.n_tiles = l->n_tiles;
+  bool tiled = (l->jt == 64 || l->jt == 128) && (ea.R * l->jt * 4) <= 3 * kTileWaves * 64 * 16;
+  if (l->algo == LUTKAN_ALGO_GATHER) tiled = false;
+  if (l->algo == LUTKAN_ALGO_TILED && !tiled) return fail(LUTKAN_EUNSUPPORTED, "%s: tiled kernel needs jt in {64,128}", who);
+  if (tiled) {
+    const int rw = choose_rw(B, l->n_tiles);
+    return (l->jt == 128) ? launch_spline_tiled<2>(ea, rw, s) : launch_spline_tiled<1>(ea, rw, s);
+  }
+  const int lg = gather_jx_log2(l->m);
+  const dim3 grid((unsigned)((B + (256 >> lg) - 1) / (256 >> lg)), (unsigned)((l->m + (1 << lg) - 1) >> lg));
+  hipLaunchKernelGGL(bspline_gather_kernel, grid, dim3(256), 0, s, ea, lg);
+  return check_launch("bspline_gather_kernel");
+}
+}  // namespace
+
+extern "C" int bspline_kan_forward(const bspline_dev_layer *l, const float *x, int64_t B, float *y,
+                                   void *workspace, size_t workspace_bytes, void *hip_stream) {
+  return bspline_impl(l, x, B, y, workspace, workspace_bytes, hip_stream, "bspline_kan_forward", kLocate | kEdges);
+}
+
+extern "C" int bspline_forward_locate(const bspline_dev_layer *l, const float *x, int64_t B, void *workspace,
+                                      size_t workspace_bytes, void *hip_stream) {
+  return bspline_impl(l, x, B, nullptr, workspace, workspace_bytes, hip_stream, "bspline_forward_locate", kLocate);
+}
+
+extern "C" int bspline_forward_edges(const bspline_dev_layer *l, int64_t B, float *y, void *workspace,
+                                     size_t workspace_bytes, void *hip_stream) {
+  return bspline_impl(l, nullptr, B, y, workspace, workspace_bytes, hip_stream, "bspline_forward_edges", kEdges);
+}
+
+extern "C" size_t lutkan_model_workspace_bytes(const lutkan_dev_layer *layers, int32_t n_layers, int64_t B) {
+  if (!layers || n_layers < 1 || B <= 0) return 0;
+  size_t act = 0, scratch = 0;
+  for (int l = 0; l < n_layers; ++l) {
+    if (l + 1 < n_layers) act = std::max(act, (size_t)round_up((int64_t)layers[l].m * B * 4, 256));
+    scratch = std::max(scratch, lutkan_forward_workspace_bytes(&layers[l], B));
+  }
+  return 2 * act + scratch;
+}
+
+extern "C" int lutkan_model_forward(const lutkan_dev_layer *layers, int32_t n_layers, const float *x, int64_t B, float *y,
+                                    lutkan_oob_stats *stats, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  const char *who = "lutkan_model_forward";
+  if (!layers || n_layers < 1 || n_layers > LUTKAN_MAX_LAYERS) return fail(LUTKAN_EINVAL, "%s: need 1..%d layers", who, LUTKAN_MAX_LAYERS);
+  for (int l = 0; l + 1 < n_layers; ++l)
+    if (layers[l].m != layers[l + 1].d) return fail(LUTKAN_ESHAPE, "%s: layer %d has m=%d but layer %d has d=%d", who, l, layers[l].m, l + 1, layers[l + 1].d);
+  if (B < 0) return fail(LUTKAN_EINVAL, "%s: B < 0", who);
+  if (B == 0) return LUTKAN_OK;
+  const size_t need = lutkan_model_workspace_bytes(layers, n_layers, B);
+  if (!workspace || workspace_bytes < need) return fail(LUTKAN_ESHAPE, "%s: workspace of %zu bytes, need %zu", who, workspace_bytes, need);
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return fail(LUTKAN_EINVAL, "%s: workspace must be 256-byte aligned", who);
+  size_t act = 0, scratch = 0;
+  for (int l = 0; l < n_layers; ++l) {
+    if (l + 1 < n_layers) act = std::max(act, (size_t)round_up((int64_t)layers[l].m * B * 4, 256));
+    scratch = std::max(scratch, lutkan_forward_workspace_bytes(&layers[l], B));
+  }
+  char *base = static_cast<char *>(workspace);
+  float *ping[2] = {reinterpret_cast<float *>(base), reinterpret_cast<float *>(base + act)};
+  void *rec = base + 2 * act;
+  const float *in = x;
+  for (int l = 0; l < n_layers; ++l) {
+    float *out = (l + 1 == n_layers) ? y : ping[l & 1];
+    int rc = lutkan_forward(&layers[l], in, B, out, stats ? stats + l : nullptr, rec, scratch, hip_stream);
+    if (rc) return rc;
+    in = out;
+  }
+  return LUTKAN_OK;
+}
