@@ -1,0 +1,177 @@
+#!/usr/bin/env python3
+"""Benchmark of the LUT-KAN layer forward on one MI355X.
+
+One "step" is one pass of the whole hot path (locate kernel + edge kernel, i.e. lutkan_forward) over one batch of
+seeded synthetic input that is already resident in HBM.  The workload is the largest single-GPU configuration:
+one dense layer 1024 -> 1024, G = 10 segments on [-1,1], cubic splines with N(0,1) coefficients compiled to
+L = 64 symmetric int8 tables, batch 32768 rows of x ~ N(0, 0.5) clipped to [-1.2, 1.2], closed + clip_x.
+
+Prints ONE JSON line: edge-evaluations/s (batch*d*m per second), the roofline record of the dominant kernel
+(the edge kernel) measured with HIP events on the launch stream, the B-spline baseline ratio, and the CPU
+oracle timed on a bounded sample of the same rows.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# fp32 vector rate without the packed-fp32 forms (this library is built with them disabled):
+# 256 CUs x 4 SIMDs x 16 lanes x 2 flop (FMA) x 2.4 GHz.  The published packed figure is 157.3 TFLOP/s.
+PEAK_FP32_TFLOPS = 256 * 4 * 16 * 2 * 2.4e9 / 1e12
+PEAK_FP32_PACKED_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+# Algorithmic fp32 operations per edge evaluation (Eq. 10 twice: 2 mul + 2 add; Eq. 17: 2 mul + 1 add;
+# Eq. 1: 1 add).  Integer->float conversions, address arithmetic and the 1-w subtraction are not counted.
+FLOP_PER_EDGE = 8
+# HBM traffic of one edge-kernel launch measured with rocprofv3 --pmc (see profiles/); None until measured.
+MEASURED_TRAFFIC_BYTES = None
+
+
+def log(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--batch", type=int, default=32768)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-bspline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build is single-GPU by design (rows are independent: more GPUs would each run the "
+                 "same kernel on B/N rows with replicated tables); run with --gpus 1")
+
+    import numpy as np
+    import torch
+
+    import paper_2601_03332_amd as lk
+    from lutkan_inputs import cfg4
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    t0 = time.time()
+    w = cfg4(seed=0, B=args.batch)
+    s = w.layers[0]
+    B, d, m = w.x.shape[0], s.d, s.m
+    log(f"[bench] inputs generated in {time.time() - t0:.1f}s: {w.name}")
+    t0 = time.time()
+    art = lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, s.boundary, s.oob)
+    log(f"[bench] lutkan_compile: {time.time() - t0:.1f}s, table {art.info.table_bytes / 2**20:.0f} MiB, jt={art.info.jt}")
+    layer = art.to_device(dev)
+    nbuf = 3                                            # rotate buffers so no step re-reads a cache-warm x / y
+    xs = [torch.from_numpy(w.x).to(dev)]
+    for r in range(1, nbuf):
+        xs.append(xs[0].roll(r * 977, dims=0).contiguous())
+    ys = [torch.empty((B, m), dtype=torch.float32, device=dev) for _ in range(nbuf)]
+    ws = torch.empty(lk.lutkan_forward_workspace_bytes(layer, B), dtype=torch.uint8, device=dev)
+    edges = B * d * m
+
+    def step(n):
+        lk.lutkan_forward(layer, xs[n % nbuf], ys[n % nbuf], workspace=ws)
+
+    for n in range(args.warmup):
+        step(n)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for n in range(args.steps):
+        step(n)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    value = edges / (dt / args.steps)
+    log(f"[bench] lutkan_forward: {ms_per_step:.3f} ms/step, {value:.4g} edge-evals/s")
+
+    # Per-kernel durations with HIP events on the stream the kernels are launched on (torch's current stream).
+    def time_phases(locate, edge_fn, steps):
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+        for n in range(steps):
+            ev[n][0].record()
+            locate(n)
+            ev[n][1].record()
+            edge_fn(n)
+            ev[n][2].record()
+        torch.cuda.synchronize()
+        loc = sorted(e[0].elapsed_time(e[1]) for e in ev)
+        edg = sorted(e[1].elapsed_time(e[2]) for e in ev)
+        return sum(loc) / len(loc), sum(edg) / len(edg), edg[len(edg) // 2]
+
+    loc_ms, edge_ms, edge_med = time_phases(lambda n: lk.lutkan_forward_locate(layer, xs[n % nbuf], ws),
+                                            lambda n: lk.lutkan_forward_edges(layer, B, ys[n % nbuf], ws), args.steps)
+    log(f"[bench] locate kernel {loc_ms:.3f} ms, edge kernel {edge_ms:.3f} ms (median {edge_med:.3f})")
+    achieved = FLOP_PER_EDGE * edges / (edge_ms * 1e-3) / 1e12
+    roofline = {"bound": "alu", "kernel": "lutkan_tiled_kernel", "achieved": round(achieved, 3),
+                "peak": round(PEAK_FP32_TFLOPS, 1), "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP32_TFLOPS, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES, "kernel_ms": round(edge_ms, 4),
+                "flop_per_edge_eval": FLOP_PER_EDGE, "peak_packed_fp32": PEAK_FP32_PACKED_TFLOPS,
+                "compulsory_hbm_bytes": int(art.info.table_bytes + 8 * B * d + 4 * B * m),
+                "hbm_time_floor_ms": round((art.info.table_bytes + 8 * B * d + 4 * B * m) / (PEAK_HBM_GBS * 1e9) * 1e3, 4)}
+
+    extra = {"rows_per_s": round(B / (dt / args.steps), 1), "locate_kernel_ms": round(loc_ms, 4),
+             "edge_kernel_edge_evals_per_s": round(edges / (edge_ms * 1e-3), 1)}
+
+    if not args.no_bspline:
+        bl = art.bspline_to_device(dev)
+        wsb = torch.empty(lk.bspline_forward_workspace_bytes(bl, B), dtype=torch.uint8, device=dev)
+        for n in range(max(2, args.warmup // 2)):
+            lk.bspline_kan_forward(bl, xs[n % nbuf], ys[n % nbuf], workspace=wsb)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for n in range(args.steps):
+            lk.bspline_kan_forward(bl, xs[n % nbuf], ys[n % nbuf], workspace=wsb)
+        torch.cuda.synchronize()
+        bs_ms = (time.perf_counter() - t0) / args.steps * 1e3
+        bloc_ms, bedge_ms, _ = time_phases(lambda n: lk.bspline_forward_locate(bl, xs[n % nbuf], wsb),
+                                           lambda n: lk.bspline_forward_edges(bl, B, ys[n % nbuf], wsb), args.steps)
+        extra.update({"bspline_ms_per_step": round(bs_ms, 4), "lut_vs_bspline_speedup": round(bs_ms / ms_per_step, 4),
+                      "bspline_locate_kernel_ms": round(bloc_ms, 4), "bspline_edge_kernel_ms": round(bedge_ms, 4),
+                      "paper_cpu_speedup_context": "LUT vs B-spline on a Ryzen 7 7840HS, 1 thread: ~12x NumPy, ~10x Numba (Tables 2-3)"})
+        log(f"[bench] bspline_kan_forward: {bs_ms:.3f} ms/step -> LUT is {bs_ms / ms_per_step:.2f}x the B-spline layer")
+        del wsb
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        t0 = time.time()
+        ora = oracle.compile_layer(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme)
+        log(f"[bench] oracle compile (not timed into the baseline): {time.time() - t0:.1f}s")
+        threads = oracle.default_threads()
+        probe = 64
+        t0 = time.perf_counter()
+        oracle.lut_forward(ora, s.boundary, s.oob, w.x[:probe], nthreads=threads)
+        rate = probe / (time.perf_counter() - t0)
+        rows = int(min(B, max(probe, rate * 12.0)))      # about 12 s of CPU work
+        t0 = time.perf_counter()
+        ref = oracle.lut_forward(ora, s.boundary, s.oob, w.x[:rows], nthreads=threads)
+        cdt = time.perf_counter() - t0
+        # the same rows on the GPU, as a last parity check of the timed configuration
+        yg = ys[0]
+        lk.lutkan_forward(layer, xs[0], yg, workspace=ws)
+        torch.cuda.synchronize()
+        err = np.abs(yg[:rows].cpu().numpy().astype(np.float64) - ref.y)
+        ok = bool(np.all(err <= 1e-5 * ref.A + 1e-6))
+        cpu = {"value": round(rows * d * m / cdt, 1), "unit": "edge-evals/s", "cores": threads, "kind": "oracle",
+               "sample": f"first {rows} of {B} rows of the same workload, {cdt:.1f}s", "gpu_matches_oracle_on_sample": ok}
+        log(f"[bench] oracle: {rows} rows in {cdt:.1f}s on {threads} threads; GPU within tolerance on them: {ok}")
+
+    out = {"metric": "lutkan_layer_edge_evals_per_s", "value": round(value, 1), "unit": "edge-evals/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": f"cfg4: dense KAN layer {d}->{m}, G={s.G}, k=3, L={s.L} symmetric int8, batch {B}, "
+                                  f"x~N(0,0.5) clipped to [-1.2,1.2], closed+clip_x, seed 0",
+                      "d": d, "m": m, "K": s.G, "L": s.L, "batch": B, "scheme": "sym_int8"},
+           "roofline": roofline, "cpu_baseline": cpu, "extra": extra}
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
