@@ -97,10 +97,12 @@ const float *lutkan_artifact_ext_knots(const lutkan_artifact *a); /* [G+2p+1] */
 
 /* Device tables (host copies to upload verbatim).  Columns are cut into n_tiles tiles of jt outputs; the
  * last tile is zero padded.  LUT table: for tile t and input i one contiguous slice of blob_bytes bytes
- *     float   alpha [K][jt]
- *     float   y_min [K][jt]                    (asymmetric scheme only; elided when y_min == 0, Sec. 7.5)
- *     code    q     [K][L][jt]                 (int8 / uint8, i.e. the [i][segment][sample][j] order per tile)
+ *     param   p     [K+1][jt]                  (symmetric: fp32 alpha; asymmetric: the fp32 pair {alpha, y_min} --
+ *                                               y_min is elided when it is identically 0, Sec. 7.5; row K is all zero)
+ *     code    q     [K*L+2][jt]                (int8 / uint8, row k*L+l, i.e. the [i][segment][sample][j] order
+ *                                               per tile; the two trailing rows are all zero)
  *     zero padding up to a multiple of 16 bytes
+ * The zero rows are where the kernels redirect inputs whose contribution is exactly 0 (oob_policy zero_spline).
  * slices ordered [t][i].  B-spline table: slices of float c[R = G+p][jt], ordered [t][i]. */
 const void *lutkan_artifact_table(const lutkan_artifact *a);
 const void *lutkan_artifact_coef_table(const lutkan_artifact *a);

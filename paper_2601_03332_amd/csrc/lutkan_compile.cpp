@@ -182,8 +182,7 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
         const float *c = desc->coef + e * R;
         const int t = j / jt, jj = j % jt;
         uint8_t *slice = a->table.data() + ((size_t)t * d + i) * lay.bytes;
-        float *slice_alpha = reinterpret_cast<float *>(slice + lay.alpha_off);
-        float *slice_ymin = reinterpret_cast<float *>(slice + lay.ymin_off);
+        float *slice_params = reinterpret_cast<float *>(slice);
         uint8_t *slice_codes = slice + lay.codes_off;
         float *cslice = a->coef_table.data() + ((size_t)t * d + i) * R * jt;
         for (int r = 0; r < R; ++r) cslice[(size_t)r * jt + jj] = c[r];
@@ -204,8 +203,12 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
                                       : quantise_asymmetric(v.data(), L, qc);
           a->scale[e * K + k] = sc.alpha;
           a->ymin[e * K + k] = sc.ymin;
-          slice_alpha[(size_t)k * jt + jj] = sc.alpha;
-          if (scheme == LUTKAN_ASYM_UINT8) slice_ymin[(size_t)k * jt + jj] = sc.ymin;
+          if (scheme == LUTKAN_ASYM_UINT8) {
+            slice_params[((size_t)k * jt + jj) * 2] = sc.alpha;
+            slice_params[((size_t)k * jt + jj) * 2 + 1] = sc.ymin;
+          } else {
+            slice_params[(size_t)k * jt + jj] = sc.alpha;
+          }
           for (int l = 0; l < L; ++l) slice_codes[((size_t)k * L + l) * jt + jj] = qc[l];
         }
       }

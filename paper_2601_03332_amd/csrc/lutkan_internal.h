@@ -15,17 +15,18 @@ namespace lutkan {
 int fail(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
 
 // Byte offsets inside one (tile, input) slice of the LUT device table:
-//   [alpha K*jt f32][y_min K*jt f32 (asymmetric only)][codes K*L*jt bytes][zero pad to 16 B]
+//   [params (K+1) rows of jt entries][codes (K*L+2) rows of jt bytes][zero pad to 16 B]
+// A parameter entry is the fp32 alpha (symmetric) or the fp32 pair {alpha, y_min} (asymmetric).
+// Parameter row K and code rows K*L, K*L+1 are all zero: the kernels send masked inputs there.
 struct BlobLayout {
-  int32_t alpha_off, ymin_off, codes_off, bytes;
+  int32_t param_row_bytes, codes_off, bytes;
 };
 
 inline BlobLayout blob_layout(int K, int L, int jt, int scheme) {
   BlobLayout b;
-  b.alpha_off = 0;
-  b.ymin_off = K * jt * 4;
-  b.codes_off = (scheme == LUTKAN_ASYM_UINT8) ? 2 * K * jt * 4 : K * jt * 4;
-  int raw = b.codes_off + K * L * jt;
+  b.param_row_bytes = jt * ((scheme == LUTKAN_ASYM_UINT8) ? 8 : 4);
+  b.codes_off = (K + 1) * b.param_row_bytes;
+  int raw = b.codes_off + (K * L + 2) * jt;
   b.bytes = (raw + 15) & ~15;
   return b;
 }

@@ -3,7 +3,7 @@
 // Work split (Sec. 4.5, Sec. 5):
 //   1. locate kernel   per (row, input): domain test on the raw x (Sec. 5.2), safe clip (Eq. 13), segment
 //                      (Eq. 14), local coordinate (Eq. 15), (l0, w) (Eq. 16), all in IEEE fp32 with one
-//                      rounding per operation, written as a 8-byte "record" [input][row] so that it is
+//                      rounding per operation, written as a 16-byte "record" [input][row] so that it is
 //                      computed once and reused by all m outputs.
 //   2. edge kernel     per (row, output): for every input gather the two adjacent codes, dequantise (Eq. 10),
 //                      interpolate (Eq. 17), apply the oob_policy (Sec. 5.4) and accumulate (Eq. 1).
@@ -13,6 +13,7 @@
 // The file is compiled with -ffp-contract=off; every fused multiply-add below is written out as fmaf().
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdint>
 
@@ -24,20 +25,29 @@ namespace {
 
 constexpr int kWave = 64;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte load/store
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
-constexpr int kMaskedBit = (int)0x80000000u;   // record: contribution is exactly zero (zero_spline, or padding row)
-constexpr int kRowBits = 20;                   // record: bits 0..19 = k*L + l0, bits 20..26 = k
+
+constexpr int kMaskedBit = (int)0x80000000u;   // index word: contribution is exactly zero (zero_spline, padding row)
+constexpr int kRowBits = 20;                   // index word: bits 0..19 = k*L + l0, bits 20..26 = k
+
+// A LUT lookup record, one per (input, row), stored [input][row]:
+//   x = byte offset of code row k*L+l0 inside the input's table slice   (the all-zero row K*L when masked)
+//   y = byte offset of parameter row k inside the slice                 (the all-zero row K when masked)
+//   z = interpolation weight w as fp32 bits                             (0 when masked, NaN for a NaN input)
+//   w = index word: k*L+l0, k and the masked flag, for the gather kernel and the trace
+// The two offsets are what the tiled kernel adds to a lane's column offset; nothing else is computed per row.
 
 // ------------------------------------------------------------------------------------------------
 // Locate kernel (steps 1-4 of Sec. 4.5 + Sec. 5.2).
 // ------------------------------------------------------------------------------------------------
 struct LocateArgs {
   const float *x;        // [B][d]
-  int32_t *rec_pk;       // [d][Bp]
-  float *rec_w;          // [d][Bp]
+  u32x4 *rec;            // [d][Bp]
   int64_t B, Bp;
   int32_t d, K, L;
   int32_t closed, zero_spline;
+  int32_t jt, codes_off, param_row_bytes;
   float tKs;             // safe upper clip value
   float knots[LUTKAN_MAX_K + 1];
   unsigned long long *stats;   // nullable: {oob_count, oob_any_rows}
@@ -87,14 +97,15 @@ constexpr int kLocRows = 32;    // rows per block
 constexpr int kLocCols = 64;    // inputs per pass
 
 __global__ __launch_bounds__(256) void lutkan_locate_kernel(const LocateArgs a) {
-  __shared__ int32_t s_pk[kLocCols][kLocRows + 1];
-  __shared__ float s_w[kLocCols][kLocRows + 1];
+  __shared__ u32x4 s_rec[kLocCols][kLocRows + 1];
   __shared__ int s_row_oob[kLocRows];
   const int tid = threadIdx.x;
   const int64_t b0 = (int64_t)blockIdx.x * kLocRows;
   if (tid < kLocRows) s_row_oob[tid] = 0;
   __syncthreads();
   unsigned my_oob = 0;
+  const unsigned zero_code_off = (unsigned)(a.codes_off + a.K * a.L * a.jt);
+  const unsigned zero_param_off = (unsigned)(a.K * a.param_row_bytes);
   for (int i0 = 0; i0 < a.d; i0 += kLocCols) {
     // phase 1: read x along inputs (coalesced), locate, park the record in LDS
     const int il = tid & (kLocCols - 1);
@@ -103,14 +114,18 @@ __global__ __launch_bounds__(256) void lutkan_locate_kernel(const LocateArgs a) 
     for (int p = 0; p < kLocRows / 4; ++p) {
       const int bl = p * 4 + (tid >> 6);
       const int64_t b = b0 + bl;
-      int pk = kMaskedBit;
-      float w = 0.0f;
+      u32x4 rec = {zero_code_off, zero_param_off, 0u, (unsigned)kMaskedBit};
       if (b < a.B && i < a.d) {
         const float x = a.x[b * a.d + i];
         const Located o = locate_one(a, x);
         const bool masked = a.zero_spline && !o.inside && !o.is_nan;
-        w = o.is_nan ? __builtin_nanf("") : o.w;
-        pk = (o.k * a.L + o.l0) | (o.k << kRowBits) | (masked ? kMaskedBit : 0);
+        const int row = o.k * a.L + o.l0;
+        rec.w = (unsigned)(row | (o.k << kRowBits) | (masked ? kMaskedBit : 0));
+        if (!masked) {
+          rec.x = (unsigned)(a.codes_off + row * a.jt);
+          rec.y = (unsigned)(o.k * a.param_row_bytes);
+          rec.z = __float_as_uint(o.is_nan ? __builtin_nanf("") : o.w);
+        }
         if (!o.inside) { ++my_oob; s_row_oob[bl] = 1; }
         if (a.k_out) {
           a.k_out[b * a.d + i] = o.k;
@@ -119,20 +134,16 @@ __global__ __launch_bounds__(256) void lutkan_locate_kernel(const LocateArgs a) 
           a.w_out[b * a.d + i] = o.w;
         }
       }
-      s_pk[il][bl] = pk;
-      s_w[il][bl] = w;
+      s_rec[il][bl] = rec;
     }
     __syncthreads();
-    // phase 2: write records along rows (coalesced)
+    // phase 2: write records along rows (coalesced 16-byte stores)
     const int bl2 = tid & (kLocRows - 1);
 #pragma unroll
     for (int p = 0; p < kLocCols / 8; ++p) {
       const int il2 = p * 8 + (tid >> 5);
       const int i2 = i0 + il2;
-      if (i2 < a.d && b0 + bl2 < a.Bp) {
-        a.rec_pk[(int64_t)i2 * a.Bp + b0 + bl2] = s_pk[il2][bl2];
-        a.rec_w[(int64_t)i2 * a.Bp + b0 + bl2] = s_w[il2][bl2];
-      }
+      if (i2 < a.d && b0 + bl2 < a.Bp) a.rec[(int64_t)i2 * a.Bp + b0 + bl2] = s_rec[il2][bl2];
     }
     __syncthreads();
   }
@@ -154,14 +165,13 @@ __global__ __launch_bounds__(256) void lutkan_locate_kernel(const LocateArgs a) 
 // ------------------------------------------------------------------------------------------------
 struct EdgeArgs {
   const unsigned char *table;
-  const int32_t *rec_pk;
-  const float *rec_w;
+  const u32x4 *rec;      // lookup records written by the locate kernel, [d][Bp]
   float *y;
   int16_t *q01_out;      // nullable, [B][d][m][2]
   int64_t B, Bp;
   int32_t d, m, K, L;
   int32_t jt, n_tiles, blob_bytes;
-  int32_t alpha_off, ymin_off, codes_off;
+  int32_t codes_off, param_row_bytes;
 };
 
 template <int SCHEME>
@@ -184,8 +194,8 @@ __global__ __launch_bounds__(256) void lutkan_gather_kernel(const EdgeArgs a, co
   const unsigned char *slice = a.table + (size_t)t * a.d * a.blob_bytes;
   float acc = 0.0f;
   for (int i = 0; i < a.d; ++i, slice += a.blob_bytes) {
-    const int pk = a.rec_pk[(int64_t)i * a.Bp + b];
-    const float w = a.rec_w[(int64_t)i * a.Bp + b];
+    const u32x4 rec = a.rec[(int64_t)i * a.Bp + b];
+    const int pk = (int)rec.w;
     const int row = pk & ((1 << kRowBits) - 1);
     const int k = (pk >> kRowBits) & 0x7f;
     const int l0 = row - k * a.L;
@@ -199,43 +209,56 @@ __global__ __launch_bounds__(256) void lutkan_gather_kernel(const EdgeArgs a, co
       o[1] = (int16_t)code_to_float<SCHEME>(c1);
     }
     if (pk < 0) continue;                                                  // oob_policy zero_spline: exactly 0
-    const float alpha = reinterpret_cast<const float *>(slice + a.alpha_off)[k * a.jt + jj];
+    const float w = __uint_as_float(rec.z);
+    const float *prm = reinterpret_cast<const float *>(slice + (size_t)k * a.param_row_bytes);
     const float f0 = code_to_float<SCHEME>(c0), f1 = code_to_float<SCHEME>(c1);
     const float tq = fmaf(w, f1 - f0, f0);                                 // interpolate the codes ...
-    acc = fmaf(alpha, tq, acc);                                            // ... then one scale per edge
-    if (SCHEME == LUTKAN_ASYM_UINT8) acc += reinterpret_cast<const float *>(slice + a.ymin_off)[k * a.jt + jj];
+    if (SCHEME == LUTKAN_ASYM_UINT8) {
+      acc = fmaf(prm[2 * jj], tq, acc);                                    // ... then one scale per edge
+      acc += prm[2 * jj + 1];
+    } else {
+      acc = fmaf(prm[jj], tq, acc);
+    }
   }
   a.y[b * a.m + j] = acc;
 }
 
-// Tiled variant.  A work-group of NW waves owns NW*RW rows and one column tile of JT = 64*CPL outputs; each
-// wave owns RW rows, each lane CPL adjacent columns, so a lane keeps RW*CPL running sums in registers for the
-// whole walk over the d inputs.  Per input the (tile, input) table slice is copied global -> registers while
-// the previous input is being processed, then registers -> LDS between two barriers.  A wave handles one row
-// at a time: the row's record is wave-uniform (broadcast from the lane that loaded it), the 64 lanes read
-// one contiguous run of codes for l0, one for l0+1 and one run of scales, without bank conflicts.
-// l0+1 is read even when l0 = L-1: then w = 0 exactly, the neighbour is the next segment's first row (or the
-// zeroed padding row after the last segment) and does not change the result.
-template <int SCHEME, int CPL, int RW, int NW, int PF>
+// Tiled variant.  A work-group of NW waves owns NW*RW rows and one column tile of JT = 4*LPR outputs.
+// A wave works on RPS = 64/LPR rows at a time: LPR lanes share a row and each lane owns 4 adjacent columns,
+// so one dword holds a lane's four codes of a table row and one 16-byte read its four scales.  Each wave owns
+// RW = RPS*NP rows and keeps 4*NP running sums per lane in registers for the whole walk over the d inputs.
+//
+// Per input the (tile, input) table slice is copied global -> registers while the previous input is being
+// processed, then registers -> LDS between two barriers; the wave's RW records for the next input travel the
+// same way into a private double-buffered LDS area.  Per row a lane reads its row's record (an LDS broadcast),
+// adds its column offset to the two byte offsets in it, and reads code row l0, code row l0+1 and the scales.
+// There is no branch per row: a masked record (oob_policy zero_spline, or a padding row) points to the
+// all-zero code row K*L and the all-zero parameter row K that every slice carries, which makes its
+// contribution exactly zero.  l0+1 is read even when l0 = L-1: then w = 0 exactly and the neighbour (the
+// next segment's first row, or a zero row) does not change the result.
+template <int SCHEME, int LPR, int NP, int NW, int PF>
 __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a) {
   extern __shared__ __align__(16) unsigned char lds[];
-  constexpr int JT = 64 * CPL;
+  constexpr int JT = 4 * LPR;
+  constexpr int RPS = 64 / LPR;
+  constexpr int RW = RPS * NP;
   constexpr int NT = NW * 64;
+  constexpr int PSZ = (SCHEME == LUTKAN_ASYM_UINT8) ? 32 : 16;   // parameter bytes per lane (4 columns)
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int sub = lane & (LPR - 1);        // which 4-column group of the tile
+  const int hrow = lane / LPR;             // which of the RPS rows of a step
   const int t = blockIdx.x % a.n_tiles;
   const int64_t rt = blockIdx.x / a.n_tiles;
   const int64_t b0 = rt * (NW * RW) + (int64_t)wave * RW;
   const int nvec = a.blob_bytes >> 4;
 
-  for (int o = a.blob_bytes + tid * 4; o < a.blob_bytes + JT + 16; o += NT * 4) *reinterpret_cast<uint32_t *>(lds + o) = 0u;
-
-  float acc[RW][CPL];
+  float acc[NP][4];
 #pragma unroll
-  for (int r = 0; r < RW; ++r)
+  for (int p = 0; p < NP; ++p)
 #pragma unroll
-    for (int c = 0; c < CPL; ++c) acc[r][c] = 0.0f;
+    for (int c = 0; c < 4; ++c) acc[p][c] = 0.0f;
 
   const u32x4 *src = reinterpret_cast<const u32x4 *>(a.table + (size_t)t * a.d * a.blob_bytes);
   u32x4 pf[PF];
@@ -244,15 +267,18 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
     const int v = p * NT + tid;
     if (v < nvec) pf[p] = src[v];
   }
-  const int rl = (lane < RW) ? lane : 0;
-  int cur_pk = a.rec_pk[b0 + rl];
-  float cur_w = a.rec_w[b0 + rl];
+  // records: lane r < RW carries row b0+r of the input that is staged next
+  const bool rec_lane = lane < RW;
+  const u32x4 *rec_src = a.rec + b0 + (rec_lane ? lane : 0);
+  u32x4 rec_pf = *rec_src;
+  unsigned char *rec_area = lds + a.blob_bytes + wave * (2 * RW * 16);
 
-  const unsigned char *codes_lds = lds + a.codes_off + lane * CPL;
-  const unsigned char *alpha_lds = lds + a.alpha_off + lane * CPL * 4;
-  const unsigned char *ymin_lds = lds + a.ymin_off + lane * CPL * 4;
+  const unsigned char *col_codes = lds + sub * 4;
+  const unsigned char *col_params = lds + sub * PSZ;
 
   for (int i = 0; i < a.d; ++i) {
+    unsigned char *rec_buf = rec_area + (i & 1) * (RW * 16);
+    if (rec_lane) *reinterpret_cast<u32x4 *>(rec_buf + lane * 16) = rec_pf;
     __syncthreads();                                   // everyone is done with the previous slice
 #pragma unroll
     for (int p = 0; p < PF; ++p) {
@@ -260,8 +286,6 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
       if (v < nvec) reinterpret_cast<u32x4 *>(lds)[v] = pf[p];
     }
     __syncthreads();
-    int nxt_pk = 0;
-    float nxt_w = 0.0f;
     if (i + 1 < a.d) {
       const u32x4 *nsrc = src + (size_t)(i + 1) * nvec;
 #pragma unroll
@@ -269,56 +293,50 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
         const int v = p * NT + tid;
         if (v < nvec) pf[p] = nsrc[v];
       }
-      nxt_pk = a.rec_pk[(int64_t)(i + 1) * a.Bp + b0 + rl];
-      nxt_w = a.rec_w[(int64_t)(i + 1) * a.Bp + b0 + rl];
+      rec_pf = rec_src[(int64_t)(i + 1) * a.Bp];
     }
 #pragma unroll
-    for (int r = 0; r < RW; ++r) {
-      const int pk = __builtin_amdgcn_readlane(cur_pk, r);
-      const float w = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(cur_w), r));
-      if (pk >= 0) {
-        const int row = pk & ((1 << kRowBits) - 1);
-        const int k = (pk >> kRowBits) & 0x7f;
-        const unsigned char *cp = codes_lds + row * JT;
-        const unsigned char *ap = alpha_lds + k * (JT * 4);
-        if (CPL == 2) {
-          const unsigned c0 = *reinterpret_cast<const uint16_t *>(cp);
-          const unsigned c1 = *reinterpret_cast<const uint16_t *>(cp + JT);
-          const f32x2 al = *reinterpret_cast<const f32x2 *>(ap);
-          const float f00 = code_to_float<SCHEME>(c0), f01 = code_to_float<SCHEME>(c0 >> 8);
-          const float f10 = code_to_float<SCHEME>(c1), f11 = code_to_float<SCHEME>(c1 >> 8);
-          const float t0 = fmaf(w, f10 - f00, f00);
-          const float t1 = fmaf(w, f11 - f01, f01);
-          acc[r][0] = fmaf(al.x, t0, acc[r][0]);
-          acc[r][CPL - 1] = fmaf(al.y, t1, acc[r][CPL - 1]);
-          if (SCHEME == LUTKAN_ASYM_UINT8) {
-            const f32x2 ym = *reinterpret_cast<const f32x2 *>(ymin_lds + k * (JT * 4));
-            acc[r][0] += ym.x;
-            acc[r][CPL - 1] += ym.y;
-          }
-        } else {
-          const unsigned c0 = *cp;
-          const unsigned c1 = *(cp + JT);
-          const float al = *reinterpret_cast<const float *>(ap);
-          const float f0 = code_to_float<SCHEME>(c0), f1 = code_to_float<SCHEME>(c1);
-          const float t0 = fmaf(w, f1 - f0, f0);
-          acc[r][0] = fmaf(al, t0, acc[r][0]);
-          if (SCHEME == LUTKAN_ASYM_UINT8) acc[r][0] += *reinterpret_cast<const float *>(ymin_lds + k * (JT * 4));
-        }
+    for (int p = 0; p < NP; ++p) {
+      const u32x4 rc = *reinterpret_cast<const u32x4 *>(rec_buf + (p * RPS + hrow) * 16);
+      const float w = __uint_as_float(rc.z);
+      const unsigned char *cp = col_codes + rc.x;
+      const unsigned char *pp = col_params + rc.y;
+      const unsigned c0 = *reinterpret_cast<const unsigned *>(cp);
+      const unsigned c1 = *reinterpret_cast<const unsigned *>(cp + JT);
+      float al[4], ym[4];
+      if (SCHEME == LUTKAN_ASYM_UINT8) {
+        const f32x4 p0 = *reinterpret_cast<const f32x4 *>(pp);
+        const f32x4 p1 = *reinterpret_cast<const f32x4 *>(pp + 16);
+        al[0] = p0.x; ym[0] = p0.y; al[1] = p0.z; ym[1] = p0.w;
+        al[2] = p1.x; ym[2] = p1.y; al[3] = p1.z; ym[3] = p1.w;
+      } else {
+        const f32x4 p0 = *reinterpret_cast<const f32x4 *>(pp);
+        al[0] = p0.x; al[1] = p0.y; al[2] = p0.z; al[3] = p0.w;
+        ym[0] = ym[1] = ym[2] = ym[3] = 0.0f;
+      }
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const float f0 = code_to_float<SCHEME>(c0 >> (8 * c));
+        const float f1 = code_to_float<SCHEME>(c1 >> (8 * c));
+        const float tq = fmaf(w, f1 - f0, f0);
+        acc[p][c] = fmaf(al[c], tq, acc[p][c]);
+        if (SCHEME == LUTKAN_ASYM_UINT8) acc[p][c] += ym[c];
       }
     }
-    cur_pk = nxt_pk;
-    cur_w = nxt_w;
   }
 
-  const int j = t * JT + lane * CPL;
+  const int j = t * JT + sub * 4;
 #pragma unroll
-  for (int r = 0; r < RW; ++r) {
-    const int64_t b = b0 + r;
+  for (int p = 0; p < NP; ++p) {
+    const int64_t b = b0 + p * RPS + hrow;
     if (b < a.B) {
+      if (j + 3 < a.m && (a.m & 3) == 0) {
+        *reinterpret_cast<f32x4 *>(a.y + b * a.m + j) = f32x4{acc[p][0], acc[p][1], acc[p][2], acc[p][3]};
+      } else {
 #pragma unroll
-      for (int c = 0; c < CPL; ++c)
-        if (j + c < a.m) a.y[b * a.m + j + c] = acc[r][c];
+        for (int c = 0; c < 4; ++c)
+          if (j + c < a.m) a.y[b * a.m + j + c] = acc[p][c];
+      }
     }
   }
 }
@@ -326,34 +344,37 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
 // ------------------------------------------------------------------------------------------------
 // B-spline baseline (Sec. 3.2-3.3).
 // ------------------------------------------------------------------------------------------------
+// A B-spline record is 32 bytes per (input, row), stored [input][row] as two 16-byte halves:
+//   {byte offset of coefficient row k inside the input's coefficient slice, N0, N1, N2}, {N3, 0, 0, 0}
+// where N0..N3 are the four non-zero cubic basis values (all 0 when masked, NaN for a NaN input).
 struct SplineLocateArgs {
   const float *x;
-  int32_t *rec_pk;       // [d][Bp]: first coefficient row r0 = k, or masked
-  float *rec_n;          // [4][d][Bp]: the four non-zero cubic basis values
+  u32x4 *rec;            // [d][Bp][2]
   int64_t B, Bp;
-  int32_t d, G;
+  int32_t d, G, jt;
   int32_t closed, zero_spline;
   float tKs;
   float ext_knots[LUTKAN_MAX_K + 7];
 };
 
+constexpr int kSplCols = 32;   // inputs per pass of the B-spline locate kernel (32-byte records)
+
 __global__ __launch_bounds__(256) void bspline_locate_kernel(const SplineLocateArgs a) {
-  __shared__ int32_t s_pk[kLocCols][kLocRows + 1];
-  __shared__ float s_n[4][kLocCols][kLocRows + 1];
+  __shared__ u32x4 s_rec[2][kSplCols][kLocRows + 1];
   __shared__ float s_tau[LUTKAN_MAX_K + 7];
   const int tid = threadIdx.x;
   const int64_t b0 = (int64_t)blockIdx.x * kLocRows;
   for (int r = tid; r < a.G + 7; r += 256) s_tau[r] = a.ext_knots[r];
   __syncthreads();
   const float t0 = s_tau[3], tK = s_tau[3 + a.G];
-  for (int i0 = 0; i0 < a.d; i0 += kLocCols) {
-    const int il = tid & (kLocCols - 1);
+  for (int i0 = 0; i0 < a.d; i0 += kSplCols) {
+    const int il = tid & (kSplCols - 1);
     const int i = i0 + il;
 #pragma unroll 1
-    for (int p = 0; p < kLocRows / 4; ++p) {
-      const int bl = p * 4 + (tid >> 6);
+    for (int p = 0; p < kLocRows / 8; ++p) {
+      const int bl = p * 8 + (tid >> 5);
       const int64_t b = b0 + bl;
-      int pk = kMaskedBit;
+      int k = 0;
       float n0 = 0.f, n1 = 0.f, n2 = 0.f, n3 = 0.f;
       if (b < a.B && i < a.d) {
         const float x = a.x[b * a.d + i];
@@ -362,7 +383,6 @@ __global__ __launch_bounds__(256) void bspline_locate_kernel(const SplineLocateA
         float xc = is_nan ? t0 : x;
         xc = (xc < t0) ? t0 : xc;
         xc = (xc > a.tKs) ? a.tKs : xc;
-        int k = 0;
         for (int kappa = 1; kappa < a.G; ++kappa) k += (s_tau[3 + kappa] <= xc) ? 1 : 0;
         // Cox-de Boor on the span mu = k+3, non-zero entries only (Eq. 4-5); knots are distinct.
         const float *tau = s_tau + k;               // tau[0..7] = ext_knots[mu-3 .. mu+4]
@@ -379,26 +399,24 @@ __global__ __launch_bounds__(256) void bspline_locate_kernel(const SplineLocateA
 #pragma unroll
           for (int s = 0; s < 5; ++s) lower[s] = next[s];
         }
+        // oob_policy zero_spline: all four weights 0 (the contribution is then exactly zero); NaN poisons them
         const bool masked = a.zero_spline && !inside && !is_nan;
-        const float poison = is_nan ? __builtin_nanf("") : 1.0f;
-        n0 = lower[0] * poison; n1 = lower[1] * poison; n2 = lower[2] * poison; n3 = lower[3] * poison;
-        pk = k | (masked ? kMaskedBit : 0);
+        const float gate = is_nan ? __builtin_nanf("") : (masked ? 0.0f : 1.0f);
+        n0 = lower[0] * gate; n1 = lower[1] * gate; n2 = lower[2] * gate; n3 = lower[3] * gate;
       }
-      s_pk[il][bl] = pk;
-      s_n[0][il][bl] = n0; s_n[1][il][bl] = n1; s_n[2][il][bl] = n2; s_n[3][il][bl] = n3;
+      s_rec[0][il][bl] = u32x4{(unsigned)(k * a.jt * 4), __float_as_uint(n0), __float_as_uint(n1), __float_as_uint(n2)};
+      s_rec[1][il][bl] = u32x4{__float_as_uint(n3), 0u, 0u, 0u};
     }
     __syncthreads();
     const int bl2 = tid & (kLocRows - 1);
-    const int64_t plane = (int64_t)a.d * a.Bp;
 #pragma unroll 1
-    for (int p = 0; p < kLocCols / 8; ++p) {
+    for (int p = 0; p < kSplCols / 8; ++p) {
       const int il2 = p * 8 + (tid >> 5);
       const int i2 = i0 + il2;
       if (i2 < a.d && b0 + bl2 < a.Bp) {
-        const int64_t o = (int64_t)i2 * a.Bp + b0 + bl2;
-        a.rec_pk[o] = s_pk[il2][bl2];
-#pragma unroll
-        for (int c = 0; c < 4; ++c) a.rec_n[c * plane + o] = s_n[c][il2][bl2];
+        const int64_t o = ((int64_t)i2 * a.Bp + b0 + bl2) * 2;
+        a.rec[o] = s_rec[0][il2][bl2];
+        a.rec[o + 1] = s_rec[1][il2][bl2];
       }
     }
     __syncthreads();
@@ -407,8 +425,7 @@ __global__ __launch_bounds__(256) void bspline_locate_kernel(const SplineLocateA
 
 struct SplineEdgeArgs {
   const float *coef_table;   // [t][i][R][jt]
-  const int32_t *rec_pk;
-  const float *rec_n;
+  const u32x4 *rec;          // [d][Bp][2]
   float *y;
   int64_t B, Bp;
   int32_t d, m, R;
@@ -423,44 +440,47 @@ __global__ __launch_bounds__(256) void bspline_gather_kernel(const SplineEdgeArg
   const int64_t b = (int64_t)blockIdx.x * (256 >> jx_log2) + ty;
   if (j >= a.m || b >= a.B) return;
   const int t = j / a.jt, jj = j - t * a.jt;
-  const int64_t plane = (int64_t)a.d * a.Bp;
   const float *slice = a.coef_table + (size_t)t * a.d * a.R * a.jt;
   float acc = 0.0f;
   for (int i = 0; i < a.d; ++i, slice += (size_t)a.R * a.jt) {
-    const int64_t o = (int64_t)i * a.Bp + b;
-    const int pk = a.rec_pk[o];
-    if (pk < 0) continue;
-    const float *c = slice + (size_t)pk * a.jt + jj;
-    acc = fmaf(a.rec_n[o], c[0], acc);
-    acc = fmaf(a.rec_n[plane + o], c[a.jt], acc);
-    acc = fmaf(a.rec_n[2 * plane + o], c[2 * a.jt], acc);
-    acc = fmaf(a.rec_n[3 * plane + o], c[3 * a.jt], acc);
+    const int64_t o = ((int64_t)i * a.Bp + b) * 2;
+    const u32x4 r0 = a.rec[o];
+    const float n3 = __uint_as_float(a.rec[o + 1].x);
+    const float *c = slice + (r0.x >> 2) + jj;
+    acc = fmaf(__uint_as_float(r0.y), c[0], acc);
+    acc = fmaf(__uint_as_float(r0.z), c[a.jt], acc);
+    acc = fmaf(__uint_as_float(r0.w), c[2 * a.jt], acc);
+    acc = fmaf(n3, c[3 * a.jt], acc);
   }
   a.y[b * a.m + j] = acc;
 }
 
-// Tiled B-spline kernel: same ownership as the LUT tiled kernel; the staged slice is the input's coefficient
-// matrix c[R][JT]; per row four contiguous coefficient runs (r0..r0+3) are read and weighted by the row's
-// four basis values.
-template <int CPL, int RW, int NW, int PF>
+// Tiled B-spline kernel: same ownership and staging as the LUT tiled kernel; the staged slice is the input's
+// coefficient matrix c[R][JT]; per row four contiguous coefficient runs (rows k..k+3) are read and weighted by
+// the row's four basis values.
+template <int LPR, int NP, int NW, int PF>
 __global__ __launch_bounds__(NW * 64) void bspline_tiled_kernel(const SplineEdgeArgs a) {
   extern __shared__ __align__(16) unsigned char lds[];
-  constexpr int JT = 64 * CPL;
+  constexpr int JT = 4 * LPR;
+  constexpr int RPS = 64 / LPR;
+  constexpr int RW = RPS * NP;
   constexpr int NT = NW * 64;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int sub = lane & (LPR - 1);
+  const int hrow = lane / LPR;
   const int t = blockIdx.x % a.n_tiles;
   const int64_t rt = blockIdx.x / a.n_tiles;
   const int64_t b0 = rt * (NW * RW) + (int64_t)wave * RW;
-  const int nvec = (a.R * JT * 4) >> 4;
-  const int64_t plane = (int64_t)a.d * a.Bp;
+  const int blob_bytes = a.R * JT * 4;
+  const int nvec = blob_bytes >> 4;
 
-  float acc[RW][CPL];
+  float acc[NP][4];
 #pragma unroll
-  for (int r = 0; r < RW; ++r)
+  for (int p = 0; p < NP; ++p)
 #pragma unroll
-    for (int c = 0; c < CPL; ++c) acc[r][c] = 0.0f;
+    for (int c = 0; c < 4; ++c) acc[p][c] = 0.0f;
 
   const u32x4 *src = reinterpret_cast<const u32x4 *>(a.coef_table + (size_t)t * a.d * a.R * JT);
   u32x4 pf[PF];
@@ -469,14 +489,18 @@ __global__ __launch_bounds__(NW * 64) void bspline_tiled_kernel(const SplineEdge
     const int v = p * NT + tid;
     if (v < nvec) pf[p] = src[v];
   }
-  const int rl = (lane < RW) ? lane : 0;
-  int cur_pk = a.rec_pk[b0 + rl];
-  float cur_n[4];
-#pragma unroll
-  for (int c = 0; c < 4; ++c) cur_n[c] = a.rec_n[c * plane + b0 + rl];
-  const unsigned char *coef_lds = lds + lane * CPL * 4;
+  const bool rec_lane = lane < RW;
+  const u32x4 *rec_src = a.rec + (b0 + (rec_lane ? lane : 0)) * 2;
+  u32x4 rec_pf0 = rec_src[0], rec_pf1 = rec_src[1];
+  unsigned char *rec_area = lds + blob_bytes + wave * (2 * RW * 32);
+  const unsigned char *col_coef = lds + sub * 16;
 
   for (int i = 0; i < a.d; ++i) {
+    unsigned char *rec_buf = rec_area + (i & 1) * (RW * 32);
+    if (rec_lane) {
+      *reinterpret_cast<u32x4 *>(rec_buf + lane * 32) = rec_pf0;
+      *reinterpret_cast<u32x4 *>(rec_buf + lane * 32 + 16) = rec_pf1;
+    }
     __syncthreads();
 #pragma unroll
     for (int p = 0; p < PF; ++p) {
@@ -484,8 +508,6 @@ __global__ __launch_bounds__(NW * 64) void bspline_tiled_kernel(const SplineEdge
       if (v < nvec) reinterpret_cast<u32x4 *>(lds)[v] = pf[p];
     }
     __syncthreads();
-    int nxt_pk = 0;
-    float nxt_n[4] = {0.f, 0.f, 0.f, 0.f};
     if (i + 1 < a.d) {
       const u32x4 *nsrc = src + (size_t)(i + 1) * nvec;
 #pragma unroll
@@ -493,42 +515,39 @@ __global__ __launch_bounds__(NW * 64) void bspline_tiled_kernel(const SplineEdge
         const int v = p * NT + tid;
         if (v < nvec) pf[p] = nsrc[v];
       }
-      const int64_t o = (int64_t)(i + 1) * a.Bp + b0 + rl;
-      nxt_pk = a.rec_pk[o];
-#pragma unroll
-      for (int c = 0; c < 4; ++c) nxt_n[c] = a.rec_n[c * plane + o];
+      rec_pf0 = rec_src[(int64_t)(i + 1) * a.Bp * 2];
+      rec_pf1 = rec_src[(int64_t)(i + 1) * a.Bp * 2 + 1];
     }
 #pragma unroll
-    for (int r = 0; r < RW; ++r) {
-      const int pk = __builtin_amdgcn_readlane(cur_pk, r);
-      if (pk >= 0) {
-        const unsigned char *cp = coef_lds + pk * (JT * 4);
+    for (int p = 0; p < NP; ++p) {
+      const unsigned char *rp = rec_buf + (p * RPS + hrow) * 32;
+      const u32x4 rc = *reinterpret_cast<const u32x4 *>(rp);
+      const float n3 = *reinterpret_cast<const float *>(rp + 16);
+      const float n[4] = {__uint_as_float(rc.y), __uint_as_float(rc.z), __uint_as_float(rc.w), n3};
+      const unsigned char *cp = col_coef + rc.x;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          const float n = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(cur_n[c]), r));
-          if (CPL == 2) {
-            const f32x2 cf = *reinterpret_cast<const f32x2 *>(cp + c * (JT * 4));
-            acc[r][0] = fmaf(n, cf.x, acc[r][0]);
-            acc[r][CPL - 1] = fmaf(n, cf.y, acc[r][CPL - 1]);
-          } else {
-            acc[r][0] = fmaf(n, *reinterpret_cast<const float *>(cp + c * (JT * 4)), acc[r][0]);
-          }
-        }
+      for (int q = 0; q < 4; ++q) {
+        const f32x4 cf = *reinterpret_cast<const f32x4 *>(cp + q * (JT * 4));
+        acc[p][0] = fmaf(n[q], cf.x, acc[p][0]);
+        acc[p][1] = fmaf(n[q], cf.y, acc[p][1]);
+        acc[p][2] = fmaf(n[q], cf.z, acc[p][2]);
+        acc[p][3] = fmaf(n[q], cf.w, acc[p][3]);
       }
     }
-    cur_pk = nxt_pk;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) cur_n[c] = nxt_n[c];
   }
 
-  const int j = t * JT + lane * CPL;
+  const int j = t * JT + sub * 4;
 #pragma unroll
-  for (int r = 0; r < RW; ++r) {
-    const int64_t b = b0 + r;
+  for (int p = 0; p < NP; ++p) {
+    const int64_t b = b0 + p * RPS + hrow;
     if (b < a.B) {
+      if (j + 3 < a.m && (a.m & 3) == 0) {
+        *reinterpret_cast<f32x4 *>(a.y + b * a.m + j) = f32x4{acc[p][0], acc[p][1], acc[p][2], acc[p][3]};
+      } else {
 #pragma unroll
-      for (int c = 0; c < CPL; ++c)
-        if (j + c < a.m) a.y[b * a.m + j + c] = acc[r][c];
+        for (int c = 0; c < 4; ++c)
+          if (j + c < a.m) a.y[b * a.m + j + c] = acc[p][c];
+      }
     }
   }
 }
@@ -537,10 +556,11 @@ __global__ __launch_bounds__(NW * 64) void bspline_tiled_kernel(const SplineEdge
 // Host launchers.
 // ------------------------------------------------------------------------------------------------
 constexpr int kTileWaves = 16;          // waves per tiled work-group (1024 threads, one work-group per CU)
-constexpr int kMaxRowTile = kTileWaves * 32;
+constexpr int kMaxTileRows = kTileWaves * 64;   // largest row tile of any tiled variant; Bp is a multiple of it
+constexpr int kMaxTiledLds = 144 * 1024;
 
 inline int64_t round_up(int64_t v, int64_t q) { return (v + q - 1) / q * q; }
-inline int64_t padded_rows(int64_t B) { return round_up(B, kMaxRowTile); }
+inline int64_t padded_rows(int64_t B) { return round_up(B, kMaxTileRows); }
 
 int check_launch(const char *what) {
   hipError_t e = hipGetLastError();
@@ -572,61 +592,54 @@ int gather_jx_log2(int m) {
   return lg;
 }
 
-template <int SCHEME, int CPL, int RW>
-int launch_tiled_pf(const EdgeArgs &ea, hipStream_t s) {
+// Row steps per wave: the largest of 16/8/4/2 that still gives every CU a work-group.
+int choose_np(int64_t B, int n_tiles, int rps) {
+  for (int np = 16; np > 2; np >>= 1) {
+    const int64_t groups = (B + kTileWaves * rps * np - 1) / (kTileWaves * rps * np) * n_tiles;
+    if (groups >= 256) return np;
+  }
+  return 2;
+}
+
+template <typename Kern, typename Args>
+int launch_with_lds(Kern kern, bool *raised, const dim3 &grid, size_t lds, hipStream_t s, const Args &args, const char *what) {
+  if (lds > (size_t)kMaxTiledLds) return fail(LUTKAN_EUNSUPPORTED, "%s: needs %zu bytes of LDS", what, lds);
+  if (!*raised) {   // the default cap on dynamic LDS is below the 160 KiB a gfx950 CU has
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kMaxTiledLds);
+    if (e != hipSuccess) return fail(LUTKAN_EHIP, "hipFuncSetAttribute(LDS): %s", hipGetErrorString(e));
+    *raised = true;
+  }
+  hipLaunchKernelGGL(kern, grid, dim3(kTileWaves * 64), lds, s, args);
+  return check_launch(what);
+}
+
+template <int SCHEME, int LPR, int NP>
+int launch_tiled_np(const EdgeArgs &ea, hipStream_t s) {
   constexpr int NW = kTileWaves;
+  constexpr int RW = (64 / LPR) * NP;
   const int nvec = ea.blob_bytes >> 4;
   const int pf = (nvec + NW * 64 - 1) / (NW * 64);
   const int64_t row_tiles = (ea.B + NW * RW - 1) / (NW * RW);
   const dim3 grid((unsigned)(row_tiles * ea.n_tiles));
-  const size_t lds = (size_t)ea.blob_bytes + 64 * CPL + 16;
-#define LUTKAN_TILED_CASE(N)                                                                                          \
-  case N: {                                                                                                           \
-    auto kern = lutkan_tiled_kernel<SCHEME, CPL, RW, NW, N>;                                                          \
-    static bool lds_raised = false; /* the default cap on dynamic LDS is below the 160 KiB a gfx950 CU has */         \
-    if (!lds_raised) {                                                                                                \
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 120 * 1024); \
-      if (e != hipSuccess) return fail(LUTKAN_EHIP, "hipFuncSetAttribute(LDS): %s", hipGetErrorString(e));            \
-      lds_raised = true;                                                                                              \
-    }                                                                                                                 \
-    hipLaunchKernelGGL(kern, grid, dim3(NW * 64), lds, s, ea);                                                        \
-    break;                                                                                                            \
-  }
-  switch (pf) {
-    LUTKAN_TILED_CASE(1)
-    LUTKAN_TILED_CASE(2)
-    LUTKAN_TILED_CASE(3)
-    LUTKAN_TILED_CASE(4)
-    LUTKAN_TILED_CASE(5)
-    LUTKAN_TILED_CASE(6)
-    default:
-      return fail(LUTKAN_EUNSUPPORTED, "tiled kernel: table slice of %d bytes is too large to stage", ea.blob_bytes);
-  }
-#undef LUTKAN_TILED_CASE
-  return check_launch("lutkan_tiled_kernel");
+  const size_t lds = (size_t)ea.blob_bytes + (size_t)NW * 2 * RW * 16;
+  static bool raised2 = false, raised6 = false;
+  if (pf <= 2) return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, 2>, &raised2, grid, lds, s, ea, "lutkan_tiled_kernel");
+  if (pf <= 6) return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, 6>, &raised6, grid, lds, s, ea, "lutkan_tiled_kernel");
+  return fail(LUTKAN_EUNSUPPORTED, "tiled kernel: table slice of %d bytes is too large to stage", ea.blob_bytes);
 }
 
-template <int SCHEME, int CPL>
-int launch_tiled(const EdgeArgs &ea, int rw, hipStream_t s) {
-  switch (rw) {
-    case 32: return launch_tiled_pf<SCHEME, CPL, 32>(ea, s);
-    case 16: return launch_tiled_pf<SCHEME, CPL, 16>(ea, s);
-    case 8: return launch_tiled_pf<SCHEME, CPL, 8>(ea, s);
-    default: return launch_tiled_pf<SCHEME, CPL, 4>(ea, s);
+template <int SCHEME, int LPR>
+int launch_tiled(const EdgeArgs &ea, int np, hipStream_t s) {
+  switch (np) {
+    case 16: return launch_tiled_np<SCHEME, LPR, 16>(ea, s);
+    case 8: return launch_tiled_np<SCHEME, LPR, 8>(ea, s);
+    case 4: return launch_tiled_np<SCHEME, LPR, 4>(ea, s);
+    default: return launch_tiled_np<SCHEME, LPR, 2>(ea, s);
   }
-}
-
-// Rows per wave: the largest of 32/16/8/4 that still gives every CU a work-group.
-int choose_rw(int64_t B, int n_tiles) {
-  for (int rw = 32; rw > 4; rw >>= 1) {
-    const int64_t groups = (B + kTileWaves * rw - 1) / (kTileWaves * rw) * n_tiles;
-    if (groups >= 256) return rw;
-  }
-  return 4;
 }
 
 bool tiled_supported(int jt, int blob_bytes) {
-  return (jt == 64 || jt == 128) && blob_bytes <= 6 * kTileWaves * 64 * 16;
+  return (jt == 64 || jt == 128) && blob_bytes <= lutkan::kLdsSliceBudget;
 }
 
 enum { kLocate = 1, kEdges = 2 };
@@ -645,14 +658,15 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   if ((reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return fail(LUTKAN_EINVAL, "%s: workspace must be 256-byte aligned", who);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const int64_t Bp = padded_rows(B);
+  const lutkan::BlobLayout lay = lutkan::blob_layout(l->K, l->L, l->jt, l->scheme);
 
   LocateArgs la;
   la.x = x;
-  la.rec_pk = static_cast<int32_t *>(workspace);
-  la.rec_w = reinterpret_cast<float *>(static_cast<char *>(workspace) + (size_t)l->d * Bp * 4);
+  la.rec = static_cast<u32x4 *>(workspace);
   la.B = B; la.Bp = Bp; la.d = l->d; la.K = l->K; la.L = l->L;
   la.closed = (l->boundary == LUTKAN_CLOSED);
   la.zero_spline = (l->oob == LUTKAN_ZERO_SPLINE);
+  la.jt = l->jt; la.codes_off = lay.codes_off; la.param_row_bytes = lay.param_row_bytes;
   la.tKs = la.closed ? l->knots[l->K] : std::nextafterf(l->knots[l->K], -INFINITY);
   for (int k = 0; k <= l->K; ++k) la.knots[k] = l->knots[k];
   la.stats = reinterpret_cast<unsigned long long *>(stats);
@@ -663,22 +677,21 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   }
   if (!(phases & kEdges)) return LUTKAN_OK;
 
-  const lutkan::BlobLayout lay = lutkan::blob_layout(l->K, l->L, l->jt, l->scheme);
   EdgeArgs ea;
   ea.table = static_cast<const unsigned char *>(l->table);
-  ea.rec_pk = la.rec_pk; ea.rec_w = la.rec_w; ea.y = y; ea.q01_out = q01_out;
+  ea.rec = la.rec; ea.y = y; ea.q01_out = q01_out;
   ea.B = B; ea.Bp = Bp; ea.d = l->d; ea.m = l->m; ea.K = l->K; ea.L = l->L;
   ea.jt = l->jt; ea.n_tiles = l->n_tiles; ea.blob_bytes = l->blob_bytes;
-  ea.alpha_off = lay.alpha_off; ea.ymin_off = lay.ymin_off; ea.codes_off = lay.codes_off;
+  ea.codes_off = lay.codes_off; ea.param_row_bytes = lay.param_row_bytes;
 
   bool tiled = tiled_supported(l->jt, l->blob_bytes) && !q01_out;
   if (l->algo == LUTKAN_ALGO_GATHER) tiled = false;
   if (l->algo == LUTKAN_ALGO_TILED && !tiled) return fail(LUTKAN_EUNSUPPORTED, "%s: tiled kernel needs jt in {64,128} and a slice <= 96 KiB", who);
   if (tiled) {
-    const int rw = choose_rw(B, l->n_tiles);
+    const int np = choose_np(B, l->n_tiles, 64 / (l->jt / 4));
     if (l->scheme == LUTKAN_SYM_INT8)
-      return (l->jt == 128) ? launch_tiled<LUTKAN_SYM_INT8, 2>(ea, rw, s) : launch_tiled<LUTKAN_SYM_INT8, 1>(ea, rw, s);
-    return (l->jt == 128) ? launch_tiled<LUTKAN_ASYM_UINT8, 2>(ea, rw, s) : launch_tiled<LUTKAN_ASYM_UINT8, 1>(ea, rw, s);
+      return (l->jt == 128) ? launch_tiled<LUTKAN_SYM_INT8, 32>(ea, np, s) : launch_tiled<LUTKAN_SYM_INT8, 16>(ea, np, s);
+    return (l->jt == 128) ? launch_tiled<LUTKAN_ASYM_UINT8, 32>(ea, np, s) : launch_tiled<LUTKAN_ASYM_UINT8, 16>(ea, np, s);
   }
   const int lg = gather_jx_log2(l->m);
   const dim3 grid((unsigned)((B + (256 >> lg) - 1) / (256 >> lg)), (unsigned)((l->m + (1 << lg) - 1) >> lg));
@@ -693,68 +706,30 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   return check_launch("lutkan_gather_kernel");
 }
 
-template <int CPL, int RW>
-int launch_spline_tiled_rw(const SplineEdgeArgs &ea, hipStream_t s) {
+template <int LPR, int NP>
+int launch_spline_tiled_np(const SplineEdgeArgs &ea, hipStream_t s) {
   constexpr int NW = kTileWaves;
-  const int bytes = ea.R * 64 * CPL * 4;
+  constexpr int RW = (64 / LPR) * NP;
+  const int bytes = ea.R * 4 * LPR * 4;
   const int pf = ((bytes >> 4) + NW * 64 - 1) / (NW * 64);
   const int64_t row_tiles = (ea.B + NW * RW - 1) / (NW * RW);
   const dim3 grid((unsigned)(row_tiles * ea.n_tiles));
-  if (pf == 1) hipLaunchKernelGGL((bspline_tiled_kernel<CPL, RW, NW, 1>), grid, dim3(NW * 64), (size_t)bytes, s, ea);
-  else if (pf == 2) hipLaunchKernelGGL((bspline_tiled_kernel<CPL, RW, NW, 2>), grid, dim3(NW * 64), (size_t)bytes, s, ea);
-  else if (pf == 3) hipLaunchKernelGGL((bspline_tiled_kernel<CPL, RW, NW, 3>), grid, dim3(NW * 64), (size_t)bytes, s, ea);
-  else return fail(LUTKAN_EUNSUPPORTED, "bspline tiled kernel: coefficient slice of %d bytes too large", bytes);
-  return check_launch("bspline_tiled_kernel");
+  const size_t lds = (size_t)bytes + (size_t)NW * 2 * RW * 32;
+  static bool raised = false;
+  if (pf > 3) return fail(LUTKAN_EUNSUPPORTED, "bspline tiled kernel: coefficient slice of %d bytes too large", bytes);
+  return launch_with_lds(bspline_tiled_kernel<LPR, NP, NW, 3>, &raised, grid, lds, s, ea, "bspline_tiled_kernel");
 }
 
-template <int CPL>
-int launch_spline_tiled(const SplineEdgeArgs &ea, int rw, hipStream_t s) {
-  switch (rw) {
-    case 32: return launch_spline_tiled_rw<CPL, 32>(ea, s);
-    case 16: return launch_spline_tiled_rw<CPL, 16>(ea, s);
-    case 8: return launch_spline_tiled_rw<CPL, 8>(ea, s);
-    default: return launch_spline_tiled_rw<CPL, 4>(ea, s);
+template <int LPR>
+int launch_spline_tiled(const SplineEdgeArgs &ea, int np, hipStream_t s) {
+  switch (np) {
+    case 16: return launch_spline_tiled_np<LPR, 16>(ea, s);
+    case 8: return launch_spline_tiled_np<LPR, 8>(ea, s);
+    case 4: return launch_spline_tiled_np<LPR, 4>(ea, s);
+    default: return launch_spline_tiled_np<LPR, 2>(ea, s);
   }
 }
 
-}  // namespace
-
-extern "C" size_t lutkan_forward_workspace_bytes(const lutkan_dev_layer *layer, int64_t B) {
-  if (!layer || B <= 0) return 0;
-  return (size_t)layer->d * (size_t)padded_rows(B) * 8;
-}
-
-extern "C" size_t bspline_forward_workspace_bytes(const bspline_dev_layer *layer, int64_t B) {
-  if (!layer || B <= 0) return 0;
-  return (size_t)layer->d * (size_t)padded_rows(B) * 20;
-}
-
-extern "C" int lutkan_forward(const lutkan_dev_layer *layer, const float *x, int64_t B, float *y,
-                              lutkan_oob_stats *stats, void *workspace, size_t workspace_bytes, void *hip_stream) {
-  return forward_impl(layer, x, B, y, stats, nullptr, nullptr, nullptr, nullptr, nullptr, false, workspace,
-                      workspace_bytes, hip_stream, "lutkan_forward");
-}
-
-extern "C" int lutkan_forward_locate(const lutkan_dev_layer *layer, const float *x, int64_t B, lutkan_oob_stats *stats,
-                                     void *workspace, size_t workspace_bytes, void *hip_stream) {
-  return forward_impl(layer, x, B, nullptr, stats, nullptr, nullptr, nullptr, nullptr, nullptr, false, workspace,
-                      workspace_bytes, hip_stream, "lutkan_forward_locate", kLocate);
-}
-
-extern "C" int lutkan_forward_edges(const lutkan_dev_layer *layer, int64_t B, float *y, void *workspace,
-                                    size_t workspace_bytes, void *hip_stream) {
-  return forward_impl(layer, nullptr, B, y, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, false, workspace,
-                      workspace_bytes, hip_stream, "lutkan_forward_edges", kEdges);
-}
-
-extern "C" int lutkan_forward_trace(const lutkan_dev_layer *layer, const float *x, int64_t B, float *y,
-                                    int32_t *k_out, int32_t *l0_out, uint8_t *in_out, float *w_out, int16_t *q01_out,
-                                    void *workspace, size_t workspace_bytes, void *hip_stream) {
-  return forward_impl(layer, x, B, y, nullptr, k_out, l0_out, in_out, w_out, q01_out, true, workspace,
-                      workspace_bytes, hip_stream, "lutkan_forward_trace");
-}
-
-namespace {
 int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y, void *workspace,
                  size_t workspace_bytes, void *hip_stream, const char *who, int phases) {
   if (!l) return fail(LUTKAN_EINVAL, "%s: null layer", who);
@@ -781,9 +756,8 @@ int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y
 
   SplineLocateArgs la;
   la.x = x;
-  la.rec_pk = static_cast<int32_t *>(workspace);
-  la.rec_n = reinterpret_cast<float *>(static_cast<char *>(workspace) + (size_t)l->d * Bp * 4);
-  la.B = B; la.Bp = Bp; la.d = l->d; la.G = G;
+  la.rec = static_cast<u32x4 *>(workspace);
+  la.B = B; la.Bp = Bp; la.d = l->d; la.G = G; la.jt = l->jt;
   la.closed = (l->boundary == LUTKAN_CLOSED);
   la.zero_spline = (l->oob == LUTKAN_ZERO_SPLINE);
   la.tKs = la.closed ? l->ext_knots[3 + G] : std::nextafterf(l->ext_knots[3 + G], -INFINITY);
@@ -795,21 +769,57 @@ int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y
   if (!(phases & kEdges)) return LUTKAN_OK;
 
   SplineEdgeArgs ea;
-  ea.coef_table = l->coef_table; ea.rec_pk = la.rec_pk; ea.rec_n = la.rec_n; ea.y = y;
+  ea.coef_table = l->coef_table; ea.rec = la.rec; ea.y = y;
   ea.B = B; ea.Bp = Bp; ea.d = l->d; ea.m = l->m; ea.R = G + 3; ea.jt = l->jt; ea.n_tiles = l->n_tiles;
   bool tiled = (l->jt == 64 || l->jt == 128) && (ea.R * l->jt * 4) <= 3 * kTileWaves * 64 * 16;
   if (l->algo == LUTKAN_ALGO_GATHER) tiled = false;
   if (l->algo == LUTKAN_ALGO_TILED && !tiled) return fail(LUTKAN_EUNSUPPORTED, "%s: tiled kernel needs jt in {64,128}", who);
   if (tiled) {
-    const int rw = choose_rw(B, l->n_tiles);
-    return (l->jt == 128) ? launch_spline_tiled<2>(ea, rw, s) : launch_spline_tiled<1>(ea, rw, s);
+    const int np = choose_np(B, l->n_tiles, 64 / (l->jt / 4));
+    return (l->jt == 128) ? launch_spline_tiled<32>(ea, np, s) : launch_spline_tiled<16>(ea, np, s);
   }
   const int lg = gather_jx_log2(l->m);
   const dim3 grid((unsigned)((B + (256 >> lg) - 1) / (256 >> lg)), (unsigned)((l->m + (1 << lg) - 1) >> lg));
   hipLaunchKernelGGL(bspline_gather_kernel, grid, dim3(256), 0, s, ea, lg);
   return check_launch("bspline_gather_kernel");
 }
+
 }  // namespace
+
+extern "C" size_t lutkan_forward_workspace_bytes(const lutkan_dev_layer *layer, int64_t B) {
+  if (!layer || B <= 0) return 0;
+  return (size_t)layer->d * (size_t)padded_rows(B) * 16;
+}
+
+extern "C" size_t bspline_forward_workspace_bytes(const bspline_dev_layer *layer, int64_t B) {
+  if (!layer || B <= 0) return 0;
+  return (size_t)layer->d * (size_t)padded_rows(B) * 32;
+}
+
+extern "C" int lutkan_forward(const lutkan_dev_layer *layer, const float *x, int64_t B, float *y,
+                              lutkan_oob_stats *stats, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  return forward_impl(layer, x, B, y, stats, nullptr, nullptr, nullptr, nullptr, nullptr, false, workspace,
+                      workspace_bytes, hip_stream, "lutkan_forward");
+}
+
+extern "C" int lutkan_forward_locate(const lutkan_dev_layer *layer, const float *x, int64_t B, lutkan_oob_stats *stats,
+                                     void *workspace, size_t workspace_bytes, void *hip_stream) {
+  return forward_impl(layer, x, B, nullptr, stats, nullptr, nullptr, nullptr, nullptr, nullptr, false, workspace,
+                      workspace_bytes, hip_stream, "lutkan_forward_locate", kLocate);
+}
+
+extern "C" int lutkan_forward_edges(const lutkan_dev_layer *layer, int64_t B, float *y, void *workspace,
+                                    size_t workspace_bytes, void *hip_stream) {
+  return forward_impl(layer, nullptr, B, y, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, false, workspace,
+                      workspace_bytes, hip_stream, "lutkan_forward_edges", kEdges);
+}
+
+extern "C" int lutkan_forward_trace(const lutkan_dev_layer *layer, const float *x, int64_t B, float *y,
+                                    int32_t *k_out, int32_t *l0_out, uint8_t *in_out, float *w_out, int16_t *q01_out,
+                                    void *workspace, size_t workspace_bytes, void *hip_stream) {
+  return forward_impl(layer, x, B, y, nullptr, k_out, l0_out, in_out, w_out, q01_out, true, workspace,
+                      workspace_bytes, hip_stream, "lutkan_forward_trace");
+}
 
 extern "C" int bspline_kan_forward(const bspline_dev_layer *l, const float *x, int64_t B, float *y,
                                    void *workspace, size_t workspace_bytes, void *hip_stream) {

@@ -57,8 +57,8 @@ def test_host_compile_is_bit_identical_to_the_oracle_and_tables_follow_the_docum
     K, L, jt, nt = I.K, I.L, I.jt, I.n_tiles
     assert nt == -(-s.m // jt) and (jt & (jt - 1)) == 0 and 4 <= jt <= 128
     asym = s.scheme == ASYM_UINT8
-    codes_off = K * jt * 4 * (2 if asym else 1)
-    assert I.blob_bytes == (codes_off + K * L * jt + 15) // 16 * 16
+    codes_off = (K + 1) * jt * 4 * (2 if asym else 1)
+    assert I.blob_bytes == (codes_off + (K * L + 2) * jt + 15) // 16 * 16
     assert I.table_bytes == nt * s.d * I.blob_bytes and I.coef_table_bytes == nt * s.d * (s.G + 3) * jt * 4
     assert I.artifact_bytes == oracle.artifact_bytes(s.d * s.m, K, L, 8)
     tab = art.table.reshape(nt, s.d, I.blob_bytes)
@@ -70,12 +70,14 @@ def test_host_compile_is_bit_identical_to_the_oracle_and_tables_follow_the_docum
         for i in range(s.d):
             e = i * s.m + cols
             blob = tab[t, i]
-            alpha = blob[:K * jt * 4].view(np.float32).reshape(K, jt)
-            np.testing.assert_array_equal(alpha[:, :n], art.scale[e].T)
-            assert np.all(alpha[:, n:] == 0)
             if asym:
-                ymin = blob[K * jt * 4:2 * K * jt * 4].view(np.float32).reshape(K, jt)
-                np.testing.assert_array_equal(ymin[:, :n], art.y_min[e].T)
+                prm = blob[:codes_off].view(np.float32).reshape(K + 1, jt, 2)
+                np.testing.assert_array_equal(prm[:K, :n, 0], art.scale[e].T)
+                np.testing.assert_array_equal(prm[:K, :n, 1], art.y_min[e].T)
+            else:
+                prm = blob[:codes_off].view(np.float32).reshape(K + 1, jt, 1)
+                np.testing.assert_array_equal(prm[:K, :n, 0], art.scale[e].T)
+            assert np.all(prm[:, n:] == 0) and np.all(prm[K] == 0)
             codes = blob[codes_off:codes_off + K * L * jt].view(qdt).reshape(K, L, jt)
             np.testing.assert_array_equal(codes[:, :, :n], np.transpose(art.q[e], (1, 2, 0)))
             assert np.all(codes[:, :, n:] == 0) and np.all(blob[codes_off + K * L * jt:] == 0)
@@ -93,7 +95,7 @@ def test_device_struct_initialisers():
     bl = binding._SplineDevLayer()
     assert lib.bspline_dev_layer_init(art._h, C.byref(bl)) == 0
     assert (bl.d, bl.m, bl.G, bl.degree) == (78, 16, 5, 3) and list(bl.ext_knots)[:12] == list(art.ext_knots)
-    assert lib.lutkan_forward_workspace_bytes(C.byref(dl), 1000) == 78 * 1024 * 8
+    assert lib.lutkan_forward_workspace_bytes(C.byref(dl), 1000) == 78 * 1024 * 16
     assert lib.lutkan_forward_workspace_bytes(C.byref(dl), 0) == 0
     assert I_tK_star(art, CLOSED) == art.knots[-1]
 
