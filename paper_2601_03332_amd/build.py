@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
-LIB = os.path.join(HERE, "liblutkan.so")
+LIB = os.environ.get("LUTKAN_LIBRARY", os.path.join(HERE, "liblutkan.so"))
 SOURCES = [os.path.join(CSRC, "lutkan_compile.cpp"), os.path.join(CSRC, "lutkan_kernels.hip")]
 HEADERS = [os.path.join(CSRC, "lutkan_internal.h"), os.path.join(ROOT, "include", "lutkan.h")]
 

@@ -30,12 +30,9 @@ int fail(int code, const char *fmt, ...) {
 }
 
 int choose_jt(int m, int K, int L, int scheme) {
-  if (m > 64) {
-    if (blob_layout(K, L, 128, scheme).bytes <= kLdsSliceBudget) return 128;
-    return 64;
-  }
   int jt = 4;
-  while (jt < m) jt *= 2;
+  while (jt < m && jt < 128) jt *= 2;
+  while (jt > 32 && blob_layout(K, L, jt, scheme).bytes > kLdsSliceBudget) jt /= 2;
   return jt;
 }
 

@@ -31,12 +31,12 @@ inline BlobLayout blob_layout(int K, int L, int jt, int scheme) {
   return b;
 }
 
-// Largest table slice the tiled kernels stage in LDS: 96 KiB, i.e. six 16-byte vectors per thread of a
-// 1024-thread work-group while the slice is in flight between global memory and LDS.
-constexpr int kLdsSliceBudget = 96 * 1024;
+// Largest table slice of the tiled kernels: two slice buffers plus the per-wave record buffers must fit the
+// 160 KiB of LDS of a gfx950 CU.
+constexpr int kLdsSliceBudget = 56 * 1024;
 
-// Column-tile width for a layer: 128 columns (two per lane of a wave) when the slice fits the LDS
-// budget, 64 when only that fits, and for narrow layers the next power of two >= m (at least 4).
+// Column-tile width for a layer: the widest of 128 / 64 / 32 columns whose slice fits the LDS budget (32 if
+// none does; such layers run on the gather kernel), and for narrow layers the next power of two >= m (>= 4).
 int choose_jt(int m, int K, int L, int scheme);
 
 }  // namespace lutkan

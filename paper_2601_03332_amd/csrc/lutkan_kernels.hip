@@ -223,26 +223,46 @@ __global__ __launch_bounds__(256) void lutkan_gather_kernel(const EdgeArgs a, co
   a.y[b * a.m + j] = acc;
 }
 
+// Asynchronous global -> LDS copy of 16 bytes per lane (gfx950 LDS-DMA form of the global load): the wave's
+// active lanes each fetch 16 bytes from their own global address and the data lands at lds_dst + 16*lane.
+// lds_dst must be wave-uniform.  Completion is tracked by vmcnt like any other vector memory load.
+__device__ __forceinline__ void copy16_global_to_lds(const void *gsrc, void *lds_dst) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gsrc,
+                                   (__attribute__((address_space(3))) void *)lds_dst, 16, 0, 0);
+}
+
+__device__ __forceinline__ void wait_all_vector_loads() { __builtin_amdgcn_s_waitcnt(0x0f70); }   // vmcnt(0)
+
+// Copies n16 16-byte vectors from gsrc to lds_dst with all NW waves of the work-group, 1 KiB per wave step.
+template <int NW>
+__device__ __forceinline__ void stage_slice(const u32x4 *gsrc, unsigned char *lds_dst, int n16, int wave, int lane) {
+  for (int c = wave; c * 64 < n16; c += NW) {
+    const int v = c * 64 + lane;
+    if (v < n16) copy16_global_to_lds(gsrc + v, lds_dst + c * 1024);
+  }
+}
+
 // Tiled variant.  A work-group of NW waves owns NW*RW rows and one column tile of JT = 4*LPR outputs.
 // A wave works on RPS = 64/LPR rows at a time: LPR lanes share a row and each lane owns 4 adjacent columns,
 // so one dword holds a lane's four codes of a table row and one 16-byte read its four scales.  Each wave owns
 // RW = RPS*NP rows and keeps 4*NP running sums per lane in registers for the whole walk over the d inputs.
 //
-// Per input the (tile, input) table slice is copied global -> registers while the previous input is being
-// processed, then registers -> LDS between two barriers; the wave's RW records for the next input travel the
-// same way into a private double-buffered LDS area.  Per row a lane reads its row's record (an LDS broadcast),
-// adds its column offset to the two byte offsets in it, and reads code row l0, code row l0+1 and the scales.
+// LDS holds two slice buffers and, per wave, two record buffers.  While input i is processed out of one
+// buffer, the (tile, i+1) table slice and the wave's RW records for input i+1 stream from global memory
+// straight into the other one (no registers, no LDS store instructions); one barrier per input separates
+// the two roles.  Per row a lane reads its row's record (an LDS broadcast), adds its column offset to the two
+// byte offsets in it, and reads code row l0, code row l0+1 and the scales.
 // There is no branch per row: a masked record (oob_policy zero_spline, or a padding row) points to the
 // all-zero code row K*L and the all-zero parameter row K that every slice carries, which makes its
 // contribution exactly zero.  l0+1 is read even when l0 = L-1: then w = 0 exactly and the neighbour (the
 // next segment's first row, or a zero row) does not change the result.
-template <int SCHEME, int LPR, int NP, int NW, int PF>
+template <int SCHEME, int LPR, int NP, int NW>
 __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a) {
   extern __shared__ __align__(16) unsigned char lds[];
   constexpr int JT = 4 * LPR;
   constexpr int RPS = 64 / LPR;
   constexpr int RW = RPS * NP;
-  constexpr int NT = NW * 64;
+  static_assert(RW <= 64, "a wave's records for one input must fit one 1 KiB copy step");
   constexpr int PSZ = (SCHEME == LUTKAN_ASYM_UINT8) ? 32 : 16;   // parameter bytes per lane (4 columns)
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -261,43 +281,27 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
     for (int c = 0; c < 4; ++c) acc[p][c] = 0.0f;
 
   const u32x4 *src = reinterpret_cast<const u32x4 *>(a.table + (size_t)t * a.d * a.blob_bytes);
-  u32x4 pf[PF];
-#pragma unroll
-  for (int p = 0; p < PF; ++p) {
-    const int v = p * NT + tid;
-    if (v < nvec) pf[p] = src[v];
-  }
-  // records: lane r < RW carries row b0+r of the input that is staged next
-  const bool rec_lane = lane < RW;
-  const u32x4 *rec_src = a.rec + b0 + (rec_lane ? lane : 0);
-  u32x4 rec_pf = *rec_src;
-  unsigned char *rec_area = lds + a.blob_bytes + wave * (2 * RW * 16);
+  const u32x4 *rec_src = a.rec + b0 + (lane < RW ? lane : 0);
+  unsigned char *rec_area = lds + 2 * a.blob_bytes + wave * (2 * RW * 16);
 
-  const unsigned char *col_codes = lds + sub * 4;
-  const unsigned char *col_params = lds + sub * PSZ;
+  stage_slice<NW>(src, lds, nvec, wave, lane);
+  if (lane < RW) copy16_global_to_lds(rec_src, rec_area);
+  wait_all_vector_loads();
+  __syncthreads();
 
   for (int i = 0; i < a.d; ++i) {
-    unsigned char *rec_buf = rec_area + (i & 1) * (RW * 16);
-    if (rec_lane) *reinterpret_cast<u32x4 *>(rec_buf + lane * 16) = rec_pf;
-    __syncthreads();                                   // everyone is done with the previous slice
-#pragma unroll
-    for (int p = 0; p < PF; ++p) {
-      const int v = p * NT + tid;
-      if (v < nvec) reinterpret_cast<u32x4 *>(lds)[v] = pf[p];
+    const int cur = i & 1;
+    if (i + 1 < a.d) {                                 // stream the next input's slice and records
+      stage_slice<NW>(src + (size_t)(i + 1) * nvec, lds + (cur ^ 1) * a.blob_bytes, nvec, wave, lane);
+      if (lane < RW) copy16_global_to_lds(rec_src + (int64_t)(i + 1) * a.Bp, rec_area + (cur ^ 1) * (RW * 16));
     }
-    __syncthreads();
-    if (i + 1 < a.d) {
-      const u32x4 *nsrc = src + (size_t)(i + 1) * nvec;
-#pragma unroll
-      for (int p = 0; p < PF; ++p) {
-        const int v = p * NT + tid;
-        if (v < nvec) pf[p] = nsrc[v];
-      }
-      rec_pf = rec_src[(int64_t)(i + 1) * a.Bp];
-    }
+    const unsigned char *slice = lds + cur * a.blob_bytes;
+    const unsigned char *rec_buf = rec_area + cur * (RW * 16) + hrow * 16;
+    const unsigned char *col_codes = slice + sub * 4;
+    const unsigned char *col_params = slice + sub * PSZ;
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
-      const u32x4 rc = *reinterpret_cast<const u32x4 *>(rec_buf + (p * RPS + hrow) * 16);
+      const u32x4 rc = *reinterpret_cast<const u32x4 *>(rec_buf + p * (RPS * 16));
       const float w = __uint_as_float(rc.z);
       const unsigned char *cp = col_codes + rc.x;
       const unsigned char *pp = col_params + rc.y;
@@ -323,6 +327,8 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
         if (SCHEME == LUTKAN_ASYM_UINT8) acc[p][c] += ym[c];
       }
     }
+    wait_all_vector_loads();                           // my share of the next slice has landed ...
+    __syncthreads();                                   // ... everyone's has, and everyone is done with this one
   }
 
   const int j = t * JT + sub * 4;
@@ -455,16 +461,16 @@ __global__ __launch_bounds__(256) void bspline_gather_kernel(const SplineEdgeArg
   a.y[b * a.m + j] = acc;
 }
 
-// Tiled B-spline kernel: same ownership and staging as the LUT tiled kernel; the staged slice is the input's
+// Tiled B-spline kernel: same ownership and streaming as the LUT tiled kernel; the staged slice is the input's
 // coefficient matrix c[R][JT]; per row four contiguous coefficient runs (rows k..k+3) are read and weighted by
 // the row's four basis values.
-template <int LPR, int NP, int NW, int PF>
+template <int LPR, int NP, int NW>
 __global__ __launch_bounds__(NW * 64) void bspline_tiled_kernel(const SplineEdgeArgs a) {
   extern __shared__ __align__(16) unsigned char lds[];
   constexpr int JT = 4 * LPR;
   constexpr int RPS = 64 / LPR;
   constexpr int RW = RPS * NP;
-  constexpr int NT = NW * 64;
+  static_assert(RW <= 64, "a wave's records for one input must fit two 1 KiB copy steps");
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -483,44 +489,31 @@ __global__ __launch_bounds__(NW * 64) void bspline_tiled_kernel(const SplineEdge
     for (int c = 0; c < 4; ++c) acc[p][c] = 0.0f;
 
   const u32x4 *src = reinterpret_cast<const u32x4 *>(a.coef_table + (size_t)t * a.d * a.R * JT);
-  u32x4 pf[PF];
-#pragma unroll
-  for (int p = 0; p < PF; ++p) {
-    const int v = p * NT + tid;
-    if (v < nvec) pf[p] = src[v];
-  }
-  const bool rec_lane = lane < RW;
-  const u32x4 *rec_src = a.rec + (b0 + (rec_lane ? lane : 0)) * 2;
-  u32x4 rec_pf0 = rec_src[0], rec_pf1 = rec_src[1];
-  unsigned char *rec_area = lds + blob_bytes + wave * (2 * RW * 32);
-  const unsigned char *col_coef = lds + sub * 16;
+  // a wave's RW 32-byte records are 2*RW consecutive 16-byte vectors: lanes 0..63 take the first 64, then the rest
+  const u32x4 *rec_src = a.rec + b0 * 2;
+  unsigned char *rec_area = lds + 2 * blob_bytes + wave * (2 * RW * 32);
+  auto stage_records = [&](int i, unsigned char *dst) {
+    const u32x4 *g = rec_src + (int64_t)i * a.Bp * 2;
+    if (lane < 2 * RW) copy16_global_to_lds(g + lane, dst);
+    if (2 * RW > 64 && lane + 64 < 2 * RW) copy16_global_to_lds(g + 64 + lane, dst + 1024);
+  };
+
+  stage_slice<NW>(src, lds, nvec, wave, lane);
+  stage_records(0, rec_area);
+  wait_all_vector_loads();
+  __syncthreads();
 
   for (int i = 0; i < a.d; ++i) {
-    unsigned char *rec_buf = rec_area + (i & 1) * (RW * 32);
-    if (rec_lane) {
-      *reinterpret_cast<u32x4 *>(rec_buf + lane * 32) = rec_pf0;
-      *reinterpret_cast<u32x4 *>(rec_buf + lane * 32 + 16) = rec_pf1;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int p = 0; p < PF; ++p) {
-      const int v = p * NT + tid;
-      if (v < nvec) reinterpret_cast<u32x4 *>(lds)[v] = pf[p];
-    }
-    __syncthreads();
+    const int cur = i & 1;
     if (i + 1 < a.d) {
-      const u32x4 *nsrc = src + (size_t)(i + 1) * nvec;
-#pragma unroll
-      for (int p = 0; p < PF; ++p) {
-        const int v = p * NT + tid;
-        if (v < nvec) pf[p] = nsrc[v];
-      }
-      rec_pf0 = rec_src[(int64_t)(i + 1) * a.Bp * 2];
-      rec_pf1 = rec_src[(int64_t)(i + 1) * a.Bp * 2 + 1];
+      stage_slice<NW>(src + (size_t)(i + 1) * nvec, lds + (cur ^ 1) * blob_bytes, nvec, wave, lane);
+      stage_records(i + 1, rec_area + (cur ^ 1) * (RW * 32));
     }
+    const unsigned char *rec_buf = rec_area + cur * (RW * 32) + hrow * 32;
+    const unsigned char *col_coef = lds + cur * blob_bytes + sub * 16;
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
-      const unsigned char *rp = rec_buf + (p * RPS + hrow) * 32;
+      const unsigned char *rp = rec_buf + p * (RPS * 32);
       const u32x4 rc = *reinterpret_cast<const u32x4 *>(rp);
       const float n3 = *reinterpret_cast<const float *>(rp + 16);
       const float n[4] = {__uint_as_float(rc.y), __uint_as_float(rc.z), __uint_as_float(rc.w), n3};
@@ -534,6 +527,8 @@ __global__ __launch_bounds__(NW * 64) void bspline_tiled_kernel(const SplineEdge
         acc[p][3] = fmaf(n[q], cf.w, acc[p][3]);
       }
     }
+    wait_all_vector_loads();
+    __syncthreads();
   }
 
   const int j = t * JT + sub * 4;
@@ -592,9 +587,10 @@ int gather_jx_log2(int m) {
   return lg;
 }
 
-// Row steps per wave: the largest of 16/8/4/2 that still gives every CU a work-group.
+// Row steps per wave: the largest of 16/8/4/2 (at most 64 rows per wave) that still gives every CU a work-group.
 int choose_np(int64_t B, int n_tiles, int rps) {
-  for (int np = 16; np > 2; np >>= 1) {
+  int np = std::min(16, 64 / rps);
+  for (; np > 2; np >>= 1) {
     const int64_t groups = (B + kTileWaves * rps * np - 1) / (kTileWaves * rps * np) * n_tiles;
     if (groups >= 256) return np;
   }
@@ -617,29 +613,34 @@ template <int SCHEME, int LPR, int NP>
 int launch_tiled_np(const EdgeArgs &ea, hipStream_t s) {
   constexpr int NW = kTileWaves;
   constexpr int RW = (64 / LPR) * NP;
-  const int nvec = ea.blob_bytes >> 4;
-  const int pf = (nvec + NW * 64 - 1) / (NW * 64);
   const int64_t row_tiles = (ea.B + NW * RW - 1) / (NW * RW);
   const dim3 grid((unsigned)(row_tiles * ea.n_tiles));
-  const size_t lds = (size_t)ea.blob_bytes + (size_t)NW * 2 * RW * 16;
-  static bool raised2 = false, raised6 = false;
-  if (pf <= 2) return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, 2>, &raised2, grid, lds, s, ea, "lutkan_tiled_kernel");
-  if (pf <= 6) return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, 6>, &raised6, grid, lds, s, ea, "lutkan_tiled_kernel");
-  return fail(LUTKAN_EUNSUPPORTED, "tiled kernel: table slice of %d bytes is too large to stage", ea.blob_bytes);
+  const size_t lds = 2 * (size_t)ea.blob_bytes + (size_t)NW * 2 * RW * 16;
+  static bool raised = false;
+  return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW>, &raised, grid, lds, s, ea, "lutkan_tiled_kernel");
 }
 
 template <int SCHEME, int LPR>
 int launch_tiled(const EdgeArgs &ea, int np, hipStream_t s) {
   switch (np) {
-    case 16: return launch_tiled_np<SCHEME, LPR, 16>(ea, s);
+    case 16: if constexpr (LPR >= 16) return launch_tiled_np<SCHEME, LPR, 16>(ea, s);
     case 8: return launch_tiled_np<SCHEME, LPR, 8>(ea, s);
     case 4: return launch_tiled_np<SCHEME, LPR, 4>(ea, s);
     default: return launch_tiled_np<SCHEME, LPR, 2>(ea, s);
   }
 }
 
+template <int SCHEME>
+int launch_tiled_jt(const EdgeArgs &ea, int np, hipStream_t s) {
+  switch (ea.jt) {
+    case 128: return launch_tiled<SCHEME, 32>(ea, np, s);
+    case 64: return launch_tiled<SCHEME, 16>(ea, np, s);
+    default: return launch_tiled<SCHEME, 8>(ea, np, s);
+  }
+}
+
 bool tiled_supported(int jt, int blob_bytes) {
-  return (jt == 64 || jt == 128) && blob_bytes <= lutkan::kLdsSliceBudget;
+  return (jt == 32 || jt == 64 || jt == 128) && blob_bytes <= lutkan::kLdsSliceBudget;
 }
 
 enum { kLocate = 1, kEdges = 2 };
@@ -686,12 +687,10 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
 
   bool tiled = tiled_supported(l->jt, l->blob_bytes) && !q01_out;
   if (l->algo == LUTKAN_ALGO_GATHER) tiled = false;
-  if (l->algo == LUTKAN_ALGO_TILED && !tiled) return fail(LUTKAN_EUNSUPPORTED, "%s: tiled kernel needs jt in {64,128} and a slice <= 96 KiB", who);
+  if (l->algo == LUTKAN_ALGO_TILED && !tiled) return fail(LUTKAN_EUNSUPPORTED, "%s: tiled kernel needs jt in {32,64,128} and a slice <= 56 KiB", who);
   if (tiled) {
     const int np = choose_np(B, l->n_tiles, 64 / (l->jt / 4));
-    if (l->scheme == LUTKAN_SYM_INT8)
-      return (l->jt == 128) ? launch_tiled<LUTKAN_SYM_INT8, 32>(ea, np, s) : launch_tiled<LUTKAN_SYM_INT8, 16>(ea, np, s);
-    return (l->jt == 128) ? launch_tiled<LUTKAN_ASYM_UINT8, 32>(ea, np, s) : launch_tiled<LUTKAN_ASYM_UINT8, 16>(ea, np, s);
+    return (l->scheme == LUTKAN_SYM_INT8) ? launch_tiled_jt<LUTKAN_SYM_INT8>(ea, np, s) : launch_tiled_jt<LUTKAN_ASYM_UINT8>(ea, np, s);
   }
   const int lg = gather_jx_log2(l->m);
   const dim3 grid((unsigned)((B + (256 >> lg) - 1) / (256 >> lg)), (unsigned)((l->m + (1 << lg) - 1) >> lg));
@@ -711,19 +710,17 @@ int launch_spline_tiled_np(const SplineEdgeArgs &ea, hipStream_t s) {
   constexpr int NW = kTileWaves;
   constexpr int RW = (64 / LPR) * NP;
   const int bytes = ea.R * 4 * LPR * 4;
-  const int pf = ((bytes >> 4) + NW * 64 - 1) / (NW * 64);
   const int64_t row_tiles = (ea.B + NW * RW - 1) / (NW * RW);
   const dim3 grid((unsigned)(row_tiles * ea.n_tiles));
-  const size_t lds = (size_t)bytes + (size_t)NW * 2 * RW * 32;
+  const size_t lds = 2 * (size_t)bytes + (size_t)NW * 2 * RW * 32;
   static bool raised = false;
-  if (pf > 3) return fail(LUTKAN_EUNSUPPORTED, "bspline tiled kernel: coefficient slice of %d bytes too large", bytes);
-  return launch_with_lds(bspline_tiled_kernel<LPR, NP, NW, 3>, &raised, grid, lds, s, ea, "bspline_tiled_kernel");
+  return launch_with_lds(bspline_tiled_kernel<LPR, NP, NW>, &raised, grid, lds, s, ea, "bspline_tiled_kernel");
 }
 
 template <int LPR>
 int launch_spline_tiled(const SplineEdgeArgs &ea, int np, hipStream_t s) {
   switch (np) {
-    case 16: return launch_spline_tiled_np<LPR, 16>(ea, s);
+    case 16: if constexpr (LPR >= 16) return launch_spline_tiled_np<LPR, 16>(ea, s);
     case 8: return launch_spline_tiled_np<LPR, 8>(ea, s);
     case 4: return launch_spline_tiled_np<LPR, 4>(ea, s);
     default: return launch_spline_tiled_np<LPR, 2>(ea, s);
@@ -771,12 +768,13 @@ int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y
   SplineEdgeArgs ea;
   ea.coef_table = l->coef_table; ea.rec = la.rec; ea.y = y;
   ea.B = B; ea.Bp = Bp; ea.d = l->d; ea.m = l->m; ea.R = G + 3; ea.jt = l->jt; ea.n_tiles = l->n_tiles;
-  bool tiled = (l->jt == 64 || l->jt == 128) && (ea.R * l->jt * 4) <= 3 * kTileWaves * 64 * 16;
+  bool tiled = (l->jt == 32 || l->jt == 64 || l->jt == 128);
   if (l->algo == LUTKAN_ALGO_GATHER) tiled = false;
-  if (l->algo == LUTKAN_ALGO_TILED && !tiled) return fail(LUTKAN_EUNSUPPORTED, "%s: tiled kernel needs jt in {64,128}", who);
+  if (l->algo == LUTKAN_ALGO_TILED && !tiled) return fail(LUTKAN_EUNSUPPORTED, "%s: tiled kernel needs jt in {32,64,128}", who);
   if (tiled) {
     const int np = choose_np(B, l->n_tiles, 64 / (l->jt / 4));
-    return (l->jt == 128) ? launch_spline_tiled<32>(ea, np, s) : launch_spline_tiled<16>(ea, np, s);
+    return (l->jt == 128) ? launch_spline_tiled<32>(ea, np, s)
+                          : (l->jt == 64) ? launch_spline_tiled<16>(ea, np, s) : launch_spline_tiled<8>(ea, np, s);
   }
   const int lg = gather_jx_log2(l->m);
   const dim3 grid((unsigned)((B + (256 >> lg) - 1) / (256 >> lg)), (unsigned)((l->m + (1 << lg) - 1) >> lg));
