@@ -25,6 +25,7 @@ namespace {
 
 constexpr int kWave = 64;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte load/store
+typedef unsigned int u32x3 __attribute__((ext_vector_type(3)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
@@ -299,33 +300,55 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
     const unsigned char *rec_buf = rec_area + cur * (RW * 16) + hrow * 16;
     const unsigned char *col_codes = slice + sub * 4;
     const unsigned char *col_params = slice + sub * PSZ;
-#pragma unroll
-    for (int p = 0; p < NP; ++p) {
-      const u32x4 rc = *reinterpret_cast<const u32x4 *>(rec_buf + p * (RPS * 16));
-      const float w = __uint_as_float(rc.z);
+    // Software pipeline over the NP row steps.  The reads of step p+1 (codes, parameters) and the record of
+    // step p+2 are issued before the arithmetic of step p, and they are issued right AFTER the one point per
+    // step where the wave waits for its outstanding LDS reads (the first touch of step p's data): what the
+    // wave waits for was issued a whole step earlier, what it issues now has a whole step to arrive.
+    struct Fetched { unsigned c0, c1; f32x4 pa, pb; };
+    auto fetch = [&](const u32x3 &rc) {
+      Fetched f;
       const unsigned char *cp = col_codes + rc.x;
       const unsigned char *pp = col_params + rc.y;
-      const unsigned c0 = *reinterpret_cast<const unsigned *>(cp);
-      const unsigned c1 = *reinterpret_cast<const unsigned *>(cp + JT);
+      f.c0 = *reinterpret_cast<const unsigned *>(cp);
+      f.c1 = *reinterpret_cast<const unsigned *>(cp + JT);
+      f.pa = *reinterpret_cast<const f32x4 *>(pp);
+      f.pb = (SCHEME == LUTKAN_ASYM_UINT8) ? *reinterpret_cast<const f32x4 *>(pp + 16) : f32x4{0.f, 0.f, 0.f, 0.f};
+      return f;
+    };
+    u32x3 rc_cur = *reinterpret_cast<const u32x3 *>(rec_buf);
+    u32x3 rc_nxt = *reinterpret_cast<const u32x3 *>(rec_buf + (NP > 1 ? RPS * 16 : 0));
+    Fetched f_cur = fetch(rc_cur);
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+      Fetched f_nxt = f_cur;
+      u32x3 rc_nn = rc_nxt;
+      if (SCHEME == LUTKAN_ASYM_UINT8) asm volatile("" ::"v"(f_cur.pb));
+      asm volatile("" ::"v"(f_cur.pa), "v"(f_cur.c1), "v"(rc_nxt.y));          // first touch of step p's data
+      __builtin_amdgcn_sched_barrier(0);
+      if (p + 2 < NP) rc_nn = *reinterpret_cast<const u32x3 *>(rec_buf + (p + 2) * (RPS * 16));
+      if (p + 1 < NP) f_nxt = fetch(rc_nxt);
+      __builtin_amdgcn_sched_barrier(0);
+      const float w = __uint_as_float(rc_cur.z);
       float al[4], ym[4];
       if (SCHEME == LUTKAN_ASYM_UINT8) {
-        const f32x4 p0 = *reinterpret_cast<const f32x4 *>(pp);
-        const f32x4 p1 = *reinterpret_cast<const f32x4 *>(pp + 16);
-        al[0] = p0.x; ym[0] = p0.y; al[1] = p0.z; ym[1] = p0.w;
-        al[2] = p1.x; ym[2] = p1.y; al[3] = p1.z; ym[3] = p1.w;
+        al[0] = f_cur.pa.x; ym[0] = f_cur.pa.y; al[1] = f_cur.pa.z; ym[1] = f_cur.pa.w;
+        al[2] = f_cur.pb.x; ym[2] = f_cur.pb.y; al[3] = f_cur.pb.z; ym[3] = f_cur.pb.w;
       } else {
-        const f32x4 p0 = *reinterpret_cast<const f32x4 *>(pp);
-        al[0] = p0.x; al[1] = p0.y; al[2] = p0.z; al[3] = p0.w;
+        al[0] = f_cur.pa.x; al[1] = f_cur.pa.y; al[2] = f_cur.pa.z; al[3] = f_cur.pa.w;
         ym[0] = ym[1] = ym[2] = ym[3] = 0.0f;
       }
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        const float f0 = code_to_float<SCHEME>(c0 >> (8 * c));
-        const float f1 = code_to_float<SCHEME>(c1 >> (8 * c));
+        const float f0 = code_to_float<SCHEME>(f_cur.c0 >> (8 * c));
+        const float f1 = code_to_float<SCHEME>(f_cur.c1 >> (8 * c));
         const float tq = fmaf(w, f1 - f0, f0);
         acc[p][c] = fmaf(al[c], tq, acc[p][c]);
         if (SCHEME == LUTKAN_ASYM_UINT8) acc[p][c] += ym[c];
       }
+      __builtin_amdgcn_sched_barrier(0);
+      rc_cur = rc_nxt;
+      rc_nxt = rc_nn;
+      f_cur = f_nxt;
     }
     wait_all_vector_loads();                           // my share of the next slice has landed ...
     __syncthreads();                                   // ... everyone's has, and everyone is done with this one
