@@ -534,21 +534,47 @@ __global__ __launch_bounds__(NW * 64) void bspline_tiled_kernel(const SplineEdge
     }
     const unsigned char *rec_buf = rec_area + cur * (RW * 32) + hrow * 32;
     const unsigned char *col_coef = lds + cur * blob_bytes + sub * 16;
+    // Same software pipeline as the LUT kernel: wait once per step, then issue the coefficient reads of step
+    // p+1 and the record of step p+2, then do the arithmetic of step p.
+    struct Rec { u32x4 a; float n3; };
+    struct Coefs { f32x4 c[4]; };
+    auto read_rec = [&](int p) {
+      Rec r;
+      r.a = *reinterpret_cast<const u32x4 *>(rec_buf + p * (RPS * 32));
+      r.n3 = *reinterpret_cast<const float *>(rec_buf + p * (RPS * 32) + 16);
+      return r;
+    };
+    auto fetch = [&](const Rec &r) {
+      Coefs f;
+      const unsigned char *cp = col_coef + r.a.x;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) f.c[q] = *reinterpret_cast<const f32x4 *>(cp + q * (JT * 4));
+      return f;
+    };
+    Rec rc_cur = read_rec(0);
+    Rec rc_nxt = read_rec(NP > 1 ? 1 : 0);
+    Coefs f_cur = fetch(rc_cur);
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
-      const unsigned char *rp = rec_buf + p * (RPS * 32);
-      const u32x4 rc = *reinterpret_cast<const u32x4 *>(rp);
-      const float n3 = *reinterpret_cast<const float *>(rp + 16);
-      const float n[4] = {__uint_as_float(rc.y), __uint_as_float(rc.z), __uint_as_float(rc.w), n3};
-      const unsigned char *cp = col_coef + rc.x;
+      Coefs f_nxt = f_cur;
+      Rec rc_nn = rc_nxt;
+      asm volatile("" ::"v"(f_cur.c[3]), "v"(rc_nxt.n3));                       // first touch of step p's data
+      __builtin_amdgcn_sched_barrier(0);
+      if (p + 2 < NP) rc_nn = read_rec(p + 2);
+      if (p + 1 < NP) f_nxt = fetch(rc_nxt);
+      __builtin_amdgcn_sched_barrier(0);
+      const float n[4] = {__uint_as_float(rc_cur.a.y), __uint_as_float(rc_cur.a.z), __uint_as_float(rc_cur.a.w), rc_cur.n3};
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const f32x4 cf = *reinterpret_cast<const f32x4 *>(cp + q * (JT * 4));
-        acc[p][0] = fmaf(n[q], cf.x, acc[p][0]);
-        acc[p][1] = fmaf(n[q], cf.y, acc[p][1]);
-        acc[p][2] = fmaf(n[q], cf.z, acc[p][2]);
-        acc[p][3] = fmaf(n[q], cf.w, acc[p][3]);
+        acc[p][0] = fmaf(n[q], f_cur.c[q].x, acc[p][0]);
+        acc[p][1] = fmaf(n[q], f_cur.c[q].y, acc[p][1]);
+        acc[p][2] = fmaf(n[q], f_cur.c[q].z, acc[p][2]);
+        acc[p][3] = fmaf(n[q], f_cur.c[q].w, acc[p][3]);
       }
+      __builtin_amdgcn_sched_barrier(0);
+      rc_cur = rc_nxt;
+      rc_nxt = rc_nn;
+      f_cur = f_nxt;
     }
     wait_all_vector_loads();
     __syncthreads();
