@@ -46,6 +46,8 @@ def main():
     ap.add_argument("--batch", type=int, default=32768)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bspline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy, as a known-size reference for HBM counters")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU by design (rows are independent: more GPUs would each run the "
@@ -78,6 +80,14 @@ def main():
 
     def step(n):
         lk.lutkan_forward(layer, xs[n % nbuf], ys[n % nbuf], workspace=ws)
+
+    if args.copy_calibration:                           # 2^28 floats read + 2^28 floats written = 1 GiB each way
+        ca = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        cb = torch.empty_like(ca)
+        for _ in range(3):
+            cb.copy_(ca)
+        torch.cuda.synchronize()
+        del ca, cb
 
     for n in range(args.warmup):
         step(n)

@@ -99,8 +99,9 @@ const float *lutkan_artifact_ext_knots(const lutkan_artifact *a); /* [G+2p+1] */
  * last tile is zero padded.  LUT table: for tile t and input i one contiguous slice of blob_bytes bytes
  *     param   p     [K+1][jt]                  (symmetric: fp32 alpha; asymmetric: the fp32 pair {alpha, y_min} --
  *                                               y_min is elided when it is identically 0, Sec. 7.5; row K is all zero)
- *     code    q     [K*L+2][jt]                (int8 / uint8, row k*L+l, i.e. the [i][segment][sample][j] order
- *                                               per tile; the two trailing rows are all zero)
+ *     code    q     [K*L+2][jt]                (one byte per code, row k*L+l, i.e. the [i][segment][sample][j]
+ *                                               order per tile: uint8 codes as they are, int8 codes excess-128,
+ *                                               byte = q + 128; the two trailing rows are all-zero bytes)
  *     zero padding up to a multiple of 16 bytes
  * The zero rows are where the kernels redirect inputs whose contribution is exactly 0 (oob_policy zero_spline).
  * slices ordered [t][i].  B-spline table: slices of float c[R = G+p][jt], ordered [t][i]. */

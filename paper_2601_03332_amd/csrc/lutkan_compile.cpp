@@ -206,7 +206,9 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
           } else {
             slice_params[(size_t)k * jt + jj] = sc.alpha;
           }
-          for (int l = 0; l < L; ++l) slice_codes[((size_t)k * L + l) * jt + jj] = qc[l];
+          // device codes: uint8 as is; int8 stored excess-128 (q + 128), which the kernels undo exactly
+          const uint8_t flip = (scheme == LUTKAN_SYM_INT8) ? 0x80 : 0x00;
+          for (int l = 0; l < L; ++l) slice_codes[((size_t)k * L + l) * jt + jj] = qc[l] ^ flip;
         }
       }
     }

@@ -28,7 +28,10 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte
 typedef unsigned int u32x3 __attribute__((ext_vector_type(3)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
+constexpr float kTwoTo24 = 16777216.0f;
+constexpr float kTwoToMinus24 = 1.0f / 16777216.0f;
 constexpr int kMaskedBit = (int)0x80000000u;   // index word: contribution is exactly zero (zero_spline, padding row)
 constexpr int kRowBits = 20;                   // index word: bits 0..19 = k*L + l0, bits 20..26 = k
 
@@ -175,10 +178,17 @@ struct EdgeArgs {
   int32_t codes_off, param_row_bytes;
 };
 
+// Device-table byte -> code value.  Symmetric int8 codes are stored excess-128 (byte = q + 128).
 template <int SCHEME>
 __device__ __forceinline__ float code_to_float(unsigned byte) {
-  if (SCHEME == LUTKAN_SYM_INT8) return (float)(int)(int8_t)byte;
+  if (SCHEME == LUTKAN_SYM_INT8) return (float)((int)(byte & 0xffu) - 128);
   return (float)(byte & 0xffu);
+}
+
+__device__ __forceinline__ f16x2 bits_to_f16x2(unsigned v) {
+  union { unsigned u; f16x2 h; } c;
+  c.u = v;
+  return c.h;
 }
 
 // Gather variant: one thread per (row, output column); consecutive threads take consecutive columns so the
@@ -253,6 +263,11 @@ __device__ __forceinline__ void stage_slice(const u32x4 *gsrc, unsigned char *ld
 // straight into the other one (no registers, no LDS store instructions); one barrier per input separates
 // the two roles.  Per row a lane reads its row's record (an LDS broadcast), adds its column offset to the two
 // byte offsets in it, and reads code row l0, code row l0+1 and the scales.
+// Arithmetic per edge (Eq. 10 + Eq. 17 folded): acc += alpha * (q0 + w * (q1 - q0)) [+ y_min].  A byte code c,
+// zero-extended to 16 bits, IS the fp16 denormal c * 2^-24, so the four codes of a dword become two packed-fp16
+// registers with two byte permutes; the difference q1 - q0 (and the removal of the excess-128 bias of symmetric
+// codes) is then exact packed-fp16 arithmetic on denormals, and q0 + w*(q1-q0) one mixed-precision FMA with a
+// single fp32 rounding.  The running sums therefore carry a factor 2^-24, removed exactly at the end.
 // There is no branch per row: a masked record (oob_policy zero_spline, or a padding row) points to the
 // all-zero code row K*L and the all-zero parameter row K that every slice carries, which makes its
 // contribution exactly zero.  l0+1 is read even when l0 = L-1: then w = 0 exactly and the neighbour (the
@@ -337,13 +352,28 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
         al[0] = f_cur.pa.x; al[1] = f_cur.pa.y; al[2] = f_cur.pa.z; al[3] = f_cur.pa.w;
         ym[0] = ym[1] = ym[2] = ym[3] = 0.0f;
       }
+      // bytes {b3,b2,b1,b0} -> packed fp16 denormals {b1,b0} and {b3,b2}, each worth byte * 2^-24
+      f16x2 q0lo = bits_to_f16x2(__builtin_amdgcn_perm(f_cur.c0, f_cur.c0, 0x0c010c00u));
+      f16x2 q0hi = bits_to_f16x2(__builtin_amdgcn_perm(f_cur.c0, f_cur.c0, 0x0c030c02u));
+      const f16x2 q1lo = bits_to_f16x2(__builtin_amdgcn_perm(f_cur.c1, f_cur.c1, 0x0c010c00u));
+      const f16x2 q1hi = bits_to_f16x2(__builtin_amdgcn_perm(f_cur.c1, f_cur.c1, 0x0c030c02u));
+      const f16x2 dlo = q1lo - q0lo, dhi = q1hi - q0hi;                        // (q1 - q0) * 2^-24, exact
+      if (SCHEME == LUTKAN_SYM_INT8) {                                         // remove the excess-128 bias, exact
+        const f16x2 bias = bits_to_f16x2(0x00800080u);
+        q0lo = q0lo - bias;
+        q0hi = q0hi - bias;
+      }
+      const float t0 = fmaf(w, (float)dlo.x, (float)q0lo.x);                   // one rounding each
+      const float t1 = fmaf(w, (float)dlo.y, (float)q0lo.y);
+      const float t2 = fmaf(w, (float)dhi.x, (float)q0hi.x);
+      const float t3 = fmaf(w, (float)dhi.y, (float)q0hi.y);
+      acc[p][0] = fmaf(al[0], t0, acc[p][0]);
+      acc[p][1] = fmaf(al[1], t1, acc[p][1]);
+      acc[p][2] = fmaf(al[2], t2, acc[p][2]);
+      acc[p][3] = fmaf(al[3], t3, acc[p][3]);
+      if (SCHEME == LUTKAN_ASYM_UINT8) {
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const float f0 = code_to_float<SCHEME>(f_cur.c0 >> (8 * c));
-        const float f1 = code_to_float<SCHEME>(f_cur.c1 >> (8 * c));
-        const float tq = fmaf(w, f1 - f0, f0);
-        acc[p][c] = fmaf(al[c], tq, acc[p][c]);
-        if (SCHEME == LUTKAN_ASYM_UINT8) acc[p][c] += ym[c];
+        for (int c = 0; c < 4; ++c) acc[p][c] = fmaf(ym[c], kTwoToMinus24, acc[p][c]);
       }
       __builtin_amdgcn_sched_barrier(0);
       rc_cur = rc_nxt;
@@ -357,6 +387,8 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
   const int j = t * JT + sub * 4;
 #pragma unroll
   for (int p = 0; p < NP; ++p) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) acc[p][c] *= kTwoTo24;                         // exact: undo the 2^-24 of the codes
     const int64_t b = b0 + p * RPS + hrow;
     if (b < a.B) {
       if (j + 3 < a.m && (a.m & 3) == 0) {

@@ -78,8 +78,10 @@ def test_host_compile_is_bit_identical_to_the_oracle_and_tables_follow_the_docum
                 prm = blob[:codes_off].view(np.float32).reshape(K + 1, jt, 1)
                 np.testing.assert_array_equal(prm[:K, :n, 0], art.scale[e].T)
             assert np.all(prm[:, n:] == 0) and np.all(prm[K] == 0)
-            codes = blob[codes_off:codes_off + K * L * jt].view(qdt).reshape(K, L, jt)
-            np.testing.assert_array_equal(codes[:, :, :n], np.transpose(art.q[e], (1, 2, 0)))
+            codes = blob[codes_off:codes_off + K * L * jt].reshape(K, L, jt)
+            want = np.transpose(art.q[e], (1, 2, 0))
+            want = want.view(np.uint8) if asym else (want.astype(np.int16) + 128).astype(np.uint8)   # int8: excess-128
+            np.testing.assert_array_equal(codes[:, :, :n], want)
             assert np.all(codes[:, :, n:] == 0) and np.all(blob[codes_off + K * L * jt:] == 0)
             np.testing.assert_array_equal(ctab[t, i, :, :n], s.coef[i, cols].T)
 
