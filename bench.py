@@ -30,8 +30,9 @@ PEAK_HBM_GBS = 8000.0
 # Algorithmic fp32 operations per edge evaluation (Eq. 10 twice: 2 mul + 2 add; Eq. 17: 2 mul + 1 add;
 # Eq. 1: 1 add).  Integer->float conversions, address arithmetic and the 1-w subtraction are not counted.
 FLOP_PER_EDGE = 8
-# HBM traffic of one edge-kernel launch measured with rocprofv3 --pmc (see profiles/); None until measured.
-MEASURED_TRAFFIC_BYTES = None
+# HBM traffic of one edge-kernel launch on the default workload, from rocprofv3 --pmc FETCH_SIZE (x2.0, the factor a
+# plain 1 GiB copy gives) + WRITE_SIZE (x1.0); see profiles/lutkan_tiled_kernel_cfg4_B32768.md.
+MEASURED_TRAFFIC_BYTES = {32768: 5.868e9}
 
 
 def log(msg):
@@ -121,7 +122,7 @@ def main():
     achieved = FLOP_PER_EDGE * edges / (edge_ms * 1e-3) / 1e12
     roofline = {"bound": "alu", "kernel": "lutkan_tiled_kernel", "achieved": round(achieved, 3),
                 "peak": round(PEAK_FP32_TFLOPS, 1), "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP32_TFLOPS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES, "kernel_ms": round(edge_ms, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get(B), "kernel_ms": round(edge_ms, 4),
                 "flop_per_edge_eval": FLOP_PER_EDGE, "peak_packed_fp32": PEAK_FP32_PACKED_TFLOPS,
                 "compulsory_hbm_bytes": int(art.info.table_bytes + 8 * B * d + 4 * B * m),
                 "hbm_time_floor_ms": round((art.info.table_bytes + 8 * B * d + 4 * B * m) / (PEAK_HBM_GBS * 1e9) * 1e3, 4)}
