@@ -176,6 +176,8 @@ struct EdgeArgs {
   int32_t d, m, K, L;
   int32_t jt, n_tiles, blob_bytes;
   int32_t codes_off, param_row_bytes;
+  int32_t chunk;           // tiled kernels: inputs per work-group (blockIdx.y selects the chunk of inputs)
+  int64_t split_stride;    // tiled kernels: floats between the partial outputs of consecutive chunks (0 if one chunk)
 };
 
 // Device-table byte -> code value.  Symmetric int8 codes are stored excess-128 (byte = q + 128).
@@ -300,14 +302,19 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
   const u32x4 *rec_src = a.rec + b0 + (lane < RW ? lane : 0);
   unsigned char *rec_area = lds + 2 * a.blob_bytes + wave * (2 * RW * 16);
 
-  stage_slice<NW>(src, lds, nvec, wave, lane);
-  if (lane < RW) copy16_global_to_lds(rec_src, rec_area);
+  // this work-group walks the inputs [i_begin, i_end) and writes one set of (partial) sums
+  const int i_begin = blockIdx.y * a.chunk;
+  const int i_end = min(a.d, i_begin + a.chunk);
+  float *yout = a.y + (int64_t)blockIdx.y * a.split_stride;
+
+  stage_slice<NW>(src + (size_t)i_begin * nvec, lds, nvec, wave, lane);
+  if (lane < RW) copy16_global_to_lds(rec_src + (int64_t)i_begin * a.Bp, rec_area);
   wait_all_vector_loads();
   __syncthreads();
 
-  for (int i = 0; i < a.d; ++i) {
-    const int cur = i & 1;
-    if (i + 1 < a.d) {                                 // stream the next input's slice and records
+  for (int i = i_begin; i < i_end; ++i) {
+    const int cur = (i - i_begin) & 1;
+    if (i + 1 < i_end) {                               // stream the next input's slice and records
       stage_slice<NW>(src + (size_t)(i + 1) * nvec, lds + (cur ^ 1) * a.blob_bytes, nvec, wave, lane);
       if (lane < RW) copy16_global_to_lds(rec_src + (int64_t)(i + 1) * a.Bp, rec_area + (cur ^ 1) * (RW * 16));
     }
@@ -392,11 +399,11 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
     const int64_t b = b0 + p * RPS + hrow;
     if (b < a.B) {
       if (j + 3 < a.m && (a.m & 3) == 0) {
-        *reinterpret_cast<f32x4 *>(a.y + b * a.m + j) = f32x4{acc[p][0], acc[p][1], acc[p][2], acc[p][3]};
+        *reinterpret_cast<f32x4 *>(yout + b * a.m + j) = f32x4{acc[p][0], acc[p][1], acc[p][2], acc[p][3]};
       } else {
 #pragma unroll
         for (int c = 0; c < 4; ++c)
-          if (j + c < a.m) a.y[b * a.m + j + c] = acc[p][c];
+          if (j + c < a.m) yout[b * a.m + j + c] = acc[p][c];
       }
     }
   }
@@ -491,6 +498,8 @@ struct SplineEdgeArgs {
   int64_t B, Bp;
   int32_t d, m, R;
   int32_t jt, n_tiles;
+  int32_t chunk;
+  int64_t split_stride;
 };
 
 __global__ __launch_bounds__(256) void bspline_gather_kernel(const SplineEdgeArgs a, const int jx_log2) {
@@ -553,14 +562,18 @@ __global__ __launch_bounds__(NW * 64) void bspline_tiled_kernel(const SplineEdge
     if (2 * RW > 64 && lane + 64 < 2 * RW) copy16_global_to_lds(g + 64 + lane, dst + 1024);
   };
 
-  stage_slice<NW>(src, lds, nvec, wave, lane);
-  stage_records(0, rec_area);
+  const int i_begin = blockIdx.y * a.chunk;
+  const int i_end = min(a.d, i_begin + a.chunk);
+  float *yout = a.y + (int64_t)blockIdx.y * a.split_stride;
+
+  stage_slice<NW>(src + (size_t)i_begin * nvec, lds, nvec, wave, lane);
+  stage_records(i_begin, rec_area);
   wait_all_vector_loads();
   __syncthreads();
 
-  for (int i = 0; i < a.d; ++i) {
-    const int cur = i & 1;
-    if (i + 1 < a.d) {
+  for (int i = i_begin; i < i_end; ++i) {
+    const int cur = (i - i_begin) & 1;
+    if (i + 1 < i_end) {
       stage_slice<NW>(src + (size_t)(i + 1) * nvec, lds + (cur ^ 1) * blob_bytes, nvec, wave, lane);
       stage_records(i + 1, rec_area + (cur ^ 1) * (RW * 32));
     }
@@ -618,12 +631,28 @@ __global__ __launch_bounds__(NW * 64) void bspline_tiled_kernel(const SplineEdge
     const int64_t b = b0 + p * RPS + hrow;
     if (b < a.B) {
       if (j + 3 < a.m && (a.m & 3) == 0) {
-        *reinterpret_cast<f32x4 *>(a.y + b * a.m + j) = f32x4{acc[p][0], acc[p][1], acc[p][2], acc[p][3]};
+        *reinterpret_cast<f32x4 *>(yout + b * a.m + j) = f32x4{acc[p][0], acc[p][1], acc[p][2], acc[p][3]};
       } else {
 #pragma unroll
         for (int c = 0; c < 4; ++c)
-          if (j + c < a.m) a.y[b * a.m + j + c] = acc[p][c];
+          if (j + c < a.m) yout[b * a.m + j + c] = acc[p][c];
       }
+    }
+  }
+}
+
+// Sums the n_split partial outputs of the tiled kernels in ascending chunk order (deterministic): y = sum_s part[s].
+__global__ __launch_bounds__(256) void sum_partials_kernel(const float *part, float *y, int64_t n, int n_split) {
+  const int64_t e = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (e + 3 < n && (n & 3) == 0) {                   // 16-byte path needs every chunk's base aligned
+    f32x4 acc = *reinterpret_cast<const f32x4 *>(part + e);
+    for (int s = 1; s < n_split; ++s) acc += *reinterpret_cast<const f32x4 *>(part + (int64_t)s * n + e);
+    *reinterpret_cast<f32x4 *>(y + e) = acc;
+  } else {
+    for (int64_t q = e; q < n && q < e + 4; ++q) {
+      float acc = part[q];
+      for (int s = 1; s < n_split; ++s) acc += part[(int64_t)s * n + q];
+      y[q] = acc;
     }
   }
 }
@@ -637,6 +666,7 @@ constexpr int kMaxTiledLds = 144 * 1024;
 
 inline int64_t round_up(int64_t v, int64_t q) { return (v + q - 1) / q * q; }
 inline int64_t padded_rows(int64_t B) { return round_up(B, kMaxTileRows); }
+inline size_t record_bytes(int d, int64_t Bp, int bytes_per_record) { return (size_t)round_up((int64_t)d * Bp * bytes_per_record, 256); }
 
 int check_launch(const char *what) {
   hipError_t e = hipGetLastError();
@@ -668,14 +698,28 @@ int gather_jx_log2(int m) {
   return lg;
 }
 
-// Row steps per wave: the largest of 16/8/4/2 (at most 64 rows per wave) that still gives every CU a work-group.
-int choose_np(int64_t B, int n_tiles, int rps) {
-  int np = std::min(16, 64 / rps);
-  for (; np > 2; np >>= 1) {
+// Launch shape of the tiled kernels for B rows: NP row steps per wave (16/8/4/2, at most 64 rows per wave) and
+// the number of chunks the d inputs are split into.  Large row tiles re-read the table least, so NP starts at the
+// smallest value whose row tile covers B and shrinks only while the grid would still leave compute units idle
+// even with the inputs split (each chunk keeps at least 16 inputs).
+struct TilePlan {
+  int np, n_split, chunk;
+};
+
+TilePlan plan_tiles(int64_t B, int d, int n_tiles, int rps) {
+  const int np_max = std::min(16, 64 / rps);
+  int np_cap = 2;
+  while (np_cap < np_max && (int64_t)kTileWaves * rps * np_cap < B) np_cap <<= 1;
+  const int max_split = std::max(1, std::min(32, d / 16));
+  TilePlan best{np_cap, 1, d};
+  for (int np = np_cap; np >= 2; np >>= 1) {
     const int64_t groups = (B + kTileWaves * rps * np - 1) / (kTileWaves * rps * np) * n_tiles;
-    if (groups >= 256) return np;
+    const int split = (int)std::min<int64_t>(max_split, std::max<int64_t>(1, (256 + groups - 1) / groups));
+    best = TilePlan{np, split, (d + split - 1) / split};
+    if (groups * split >= 256) break;
   }
-  return 2;
+  best.n_split = (d + best.chunk - 1) / best.chunk;      // drop empty trailing chunks
+  return best;
 }
 
 template <typename Kern, typename Args>
@@ -695,7 +739,7 @@ int launch_tiled_np(const EdgeArgs &ea, hipStream_t s) {
   constexpr int NW = kTileWaves;
   constexpr int RW = (64 / LPR) * NP;
   const int64_t row_tiles = (ea.B + NW * RW - 1) / (NW * RW);
-  const dim3 grid((unsigned)(row_tiles * ea.n_tiles));
+  const dim3 grid((unsigned)(row_tiles * ea.n_tiles), (unsigned)((ea.d + ea.chunk - 1) / ea.chunk));
   const size_t lds = 2 * (size_t)ea.blob_bytes + (size_t)NW * 2 * RW * 16;
   static bool raised = false;
   return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW>, &raised, grid, lds, s, ea, "lutkan_tiled_kernel");
@@ -769,9 +813,18 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   bool tiled = tiled_supported(l->jt, l->blob_bytes) && !q01_out;
   if (l->algo == LUTKAN_ALGO_GATHER) tiled = false;
   if (l->algo == LUTKAN_ALGO_TILED && !tiled) return fail(LUTKAN_EUNSUPPORTED, "%s: tiled kernel needs jt in {32,64,128} and a slice <= 56 KiB", who);
+  ea.chunk = l->d;
+  ea.split_stride = 0;
   if (tiled) {
-    const int np = choose_np(B, l->n_tiles, 64 / (l->jt / 4));
-    return (l->scheme == LUTKAN_SYM_INT8) ? launch_tiled_jt<LUTKAN_SYM_INT8>(ea, np, s) : launch_tiled_jt<LUTKAN_ASYM_UINT8>(ea, np, s);
+    const TilePlan tp = plan_tiles(B, l->d, l->n_tiles, 64 / (l->jt / 4));
+    float *partials = reinterpret_cast<float *>(static_cast<char *>(workspace) + record_bytes(l->d, Bp, 16));
+    ea.chunk = tp.chunk;
+    if (tp.n_split > 1) { ea.y = partials; ea.split_stride = B * l->m; }
+    const int rc = (l->scheme == LUTKAN_SYM_INT8) ? launch_tiled_jt<LUTKAN_SYM_INT8>(ea, tp.np, s) : launch_tiled_jt<LUTKAN_ASYM_UINT8>(ea, tp.np, s);
+    if (rc || tp.n_split == 1) return rc;
+    const int64_t n = B * l->m;
+    hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, s, partials, y, n, tp.n_split);
+    return check_launch("sum_partials_kernel");
   }
   const int lg = gather_jx_log2(l->m);
   const dim3 grid((unsigned)((B + (256 >> lg) - 1) / (256 >> lg)), (unsigned)((l->m + (1 << lg) - 1) >> lg));
@@ -792,7 +845,7 @@ int launch_spline_tiled_np(const SplineEdgeArgs &ea, hipStream_t s) {
   constexpr int RW = (64 / LPR) * NP;
   const int bytes = ea.R * 4 * LPR * 4;
   const int64_t row_tiles = (ea.B + NW * RW - 1) / (NW * RW);
-  const dim3 grid((unsigned)(row_tiles * ea.n_tiles));
+  const dim3 grid((unsigned)(row_tiles * ea.n_tiles), (unsigned)((ea.d + ea.chunk - 1) / ea.chunk));
   const size_t lds = 2 * (size_t)bytes + (size_t)NW * 2 * RW * 32;
   static bool raised = false;
   return launch_with_lds(bspline_tiled_kernel<LPR, NP, NW>, &raised, grid, lds, s, ea, "bspline_tiled_kernel");
@@ -852,10 +905,19 @@ int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y
   bool tiled = (l->jt == 32 || l->jt == 64 || l->jt == 128);
   if (l->algo == LUTKAN_ALGO_GATHER) tiled = false;
   if (l->algo == LUTKAN_ALGO_TILED && !tiled) return fail(LUTKAN_EUNSUPPORTED, "%s: tiled kernel needs jt in {32,64,128}", who);
+  ea.chunk = l->d;
+  ea.split_stride = 0;
   if (tiled) {
-    const int np = choose_np(B, l->n_tiles, 64 / (l->jt / 4));
-    return (l->jt == 128) ? launch_spline_tiled<32>(ea, np, s)
-                          : (l->jt == 64) ? launch_spline_tiled<16>(ea, np, s) : launch_spline_tiled<8>(ea, np, s);
+    const TilePlan tp = plan_tiles(B, l->d, l->n_tiles, 64 / (l->jt / 4));
+    float *partials = reinterpret_cast<float *>(static_cast<char *>(workspace) + record_bytes(l->d, Bp, 32));
+    ea.chunk = tp.chunk;
+    if (tp.n_split > 1) { ea.y = partials; ea.split_stride = B * l->m; }
+    const int rc = (l->jt == 128) ? launch_spline_tiled<32>(ea, tp.np, s)
+                                  : (l->jt == 64) ? launch_spline_tiled<16>(ea, tp.np, s) : launch_spline_tiled<8>(ea, tp.np, s);
+    if (rc || tp.n_split == 1) return rc;
+    const int64_t n = B * l->m;
+    hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, s, partials, y, n, tp.n_split);
+    return check_launch("sum_partials_kernel");
   }
   const int lg = gather_jx_log2(l->m);
   const dim3 grid((unsigned)((B + (256 >> lg) - 1) / (256 >> lg)), (unsigned)((l->m + (1 << lg) - 1) >> lg));
@@ -865,14 +927,24 @@ int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y
 
 }  // namespace
 
+// Records for every (input, padded row), then room for the partial sums when the inputs are split into chunks.
+static size_t tiled_workspace_bytes(int d, int m, int jt, int n_tiles, int64_t B, int bytes_per_record) {
+  size_t bytes = record_bytes(d, padded_rows(B), bytes_per_record);
+  if (jt >= 32) {
+    const TilePlan tp = plan_tiles(B, d, n_tiles, 64 / (jt / 4));
+    if (tp.n_split > 1) bytes += (size_t)tp.n_split * (size_t)B * (size_t)m * 4;
+  }
+  return bytes;
+}
+
 extern "C" size_t lutkan_forward_workspace_bytes(const lutkan_dev_layer *layer, int64_t B) {
-  if (!layer || B <= 0) return 0;
-  return (size_t)layer->d * (size_t)padded_rows(B) * 16;
+  if (!layer || B <= 0 || layer->d < 1 || layer->m < 1 || layer->jt < 4 || layer->n_tiles < 1) return 0;
+  return tiled_workspace_bytes(layer->d, layer->m, layer->jt, layer->n_tiles, B, 16);
 }
 
 extern "C" size_t bspline_forward_workspace_bytes(const bspline_dev_layer *layer, int64_t B) {
-  if (!layer || B <= 0) return 0;
-  return (size_t)layer->d * (size_t)padded_rows(B) * 32;
+  if (!layer || B <= 0 || layer->d < 1 || layer->m < 1 || layer->jt < 4 || layer->n_tiles < 1) return 0;
+  return tiled_workspace_bytes(layer->d, layer->m, layer->jt, layer->n_tiles, B, 32);
 }
 
 extern "C" int lutkan_forward(const lutkan_dev_layer *layer, const float *x, int64_t B, float *y,
