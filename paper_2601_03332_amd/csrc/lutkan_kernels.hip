@@ -194,9 +194,14 @@ __device__ __forceinline__ f16x2 bits_to_f16x2(unsigned v) {
 }
 
 // Gather variant: one thread per (row, output column); consecutive threads take consecutive columns so the
-// two code rows and the parameter row are read as contiguous runs.
+// two code rows and the parameter row are read as contiguous runs.  Inputs are taken four at a time: the four
+// records are independent loads, then the eight codes and four parameters, so the dependent-load latency is
+// paid once per four inputs.  Masked records point at the slice's zero rows (no branch).  With TRACE the two
+// gathered codes of every edge are also written out, taken from the index word so that masked edges report
+// the codes they would have used.
 template <int SCHEME, bool TRACE>
 __global__ __launch_bounds__(256) void lutkan_gather_kernel(const EdgeArgs a, const int jx_log2) {
+  constexpr int U = 4;
   const int jx = 1 << jx_log2;
   const int tx = threadIdx.x & (jx - 1);
   const int ty = threadIdx.x >> jx_log2;
@@ -204,33 +209,46 @@ __global__ __launch_bounds__(256) void lutkan_gather_kernel(const EdgeArgs a, co
   const int64_t b = (int64_t)blockIdx.x * (256 >> jx_log2) + ty;
   if (j >= a.m || b >= a.B) return;
   const int t = j / a.jt, jj = j - t * a.jt;
-  const unsigned char *slice = a.table + (size_t)t * a.d * a.blob_bytes;
+  const unsigned char *tile = a.table + (size_t)t * a.d * a.blob_bytes;
+  const int poff = (SCHEME == LUTKAN_ASYM_UINT8) ? 8 * jj : 4 * jj;
   float acc = 0.0f;
-  for (int i = 0; i < a.d; ++i, slice += a.blob_bytes) {
-    const u32x4 rec = a.rec[(int64_t)i * a.Bp + b];
-    const int pk = (int)rec.w;
-    const int row = pk & ((1 << kRowBits) - 1);
-    const int k = (pk >> kRowBits) & 0x7f;
-    const int l0 = row - k * a.L;
-    const int row1 = (l0 + 1 < a.L) ? row + 1 : row;                       // l1 = min(l0+1, L-1)
-    const unsigned char *codes = slice + a.codes_off;
-    const unsigned c0 = codes[(size_t)row * a.jt + jj];
-    const unsigned c1 = codes[(size_t)row1 * a.jt + jj];
-    if (TRACE && a.q01_out) {
-      int16_t *o = a.q01_out + ((b * a.d + i) * a.m + j) * 2;
-      o[0] = (int16_t)code_to_float<SCHEME>(c0);
-      o[1] = (int16_t)code_to_float<SCHEME>(c1);
+  for (int i0 = 0; i0 < a.d; i0 += U) {
+    u32x4 rec[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int i = min(i0 + u, a.d - 1);
+      rec[u] = a.rec[(int64_t)i * a.Bp + b];
     }
-    if (pk < 0) continue;                                                  // oob_policy zero_spline: exactly 0
-    const float w = __uint_as_float(rec.z);
-    const float *prm = reinterpret_cast<const float *>(slice + (size_t)k * a.param_row_bytes);
-    const float f0 = code_to_float<SCHEME>(c0), f1 = code_to_float<SCHEME>(c1);
-    const float tq = fmaf(w, f1 - f0, f0);                                 // interpolate the codes ...
-    if (SCHEME == LUTKAN_ASYM_UINT8) {
-      acc = fmaf(prm[2 * jj], tq, acc);                                    // ... then one scale per edge
-      acc += prm[2 * jj + 1];
-    } else {
-      acc = fmaf(prm[jj], tq, acc);
+    unsigned c0[U], c1[U];
+    float al[U], ym[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const unsigned char *slice = tile + (size_t)min(i0 + u, a.d - 1) * a.blob_bytes;
+      c0[u] = slice[rec[u].x + jj];
+      c1[u] = slice[rec[u].x + a.jt + jj];
+      const float *prm = reinterpret_cast<const float *>(slice + rec[u].y + poff);
+      al[u] = prm[0];
+      ym[u] = (SCHEME == LUTKAN_ASYM_UINT8) ? prm[1] : 0.0f;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (i0 + u < a.d) {
+        const float w = __uint_as_float(rec[u].z);
+        const float f0 = code_to_float<SCHEME>(c0[u]), f1 = code_to_float<SCHEME>(c1[u]);
+        const float tq = fmaf(w, f1 - f0, f0);                             // interpolate the codes ...
+        acc = fmaf(al[u], tq, acc);                                        // ... then one scale per edge
+        if (SCHEME == LUTKAN_ASYM_UINT8) acc += ym[u];
+        if (TRACE && a.q01_out) {
+          const int pk = (int)rec[u].w;
+          const int row = pk & ((1 << kRowBits) - 1);
+          const int k = (pk >> kRowBits) & 0x7f;
+          const int row1 = (row - k * a.L + 1 < a.L) ? row + 1 : row;      // l1 = min(l0+1, L-1)
+          const unsigned char *codes = tile + (size_t)(i0 + u) * a.blob_bytes + a.codes_off;
+          int16_t *o = a.q01_out + ((b * a.d + i0 + u) * a.m + j) * 2;
+          o[0] = (int16_t)code_to_float<SCHEME>(codes[(size_t)row * a.jt + jj]);
+          o[1] = (int16_t)code_to_float<SCHEME>(codes[(size_t)row1 * a.jt + jj]);
+        }
+      }
     }
   }
   a.y[b * a.m + j] = acc;
@@ -503,6 +521,7 @@ struct SplineEdgeArgs {
 };
 
 __global__ __launch_bounds__(256) void bspline_gather_kernel(const SplineEdgeArgs a, const int jx_log2) {
+  constexpr int U = 4;                      // inputs per batch of independent loads, as in the LUT gather kernel
   const int jx = 1 << jx_log2;
   const int tx = threadIdx.x & (jx - 1);
   const int ty = threadIdx.x >> jx_log2;
@@ -510,17 +529,33 @@ __global__ __launch_bounds__(256) void bspline_gather_kernel(const SplineEdgeArg
   const int64_t b = (int64_t)blockIdx.x * (256 >> jx_log2) + ty;
   if (j >= a.m || b >= a.B) return;
   const int t = j / a.jt, jj = j - t * a.jt;
-  const float *slice = a.coef_table + (size_t)t * a.d * a.R * a.jt;
+  const float *tile = a.coef_table + (size_t)t * a.d * a.R * a.jt;
   float acc = 0.0f;
-  for (int i = 0; i < a.d; ++i, slice += (size_t)a.R * a.jt) {
-    const int64_t o = ((int64_t)i * a.Bp + b) * 2;
-    const u32x4 r0 = a.rec[o];
-    const float n3 = __uint_as_float(a.rec[o + 1].x);
-    const float *c = slice + (r0.x >> 2) + jj;
-    acc = fmaf(__uint_as_float(r0.y), c[0], acc);
-    acc = fmaf(__uint_as_float(r0.z), c[a.jt], acc);
-    acc = fmaf(__uint_as_float(r0.w), c[2 * a.jt], acc);
-    acc = fmaf(n3, c[3 * a.jt], acc);
+  for (int i0 = 0; i0 < a.d; i0 += U) {
+    u32x4 r0[U];
+    float n3[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t o = ((int64_t)min(i0 + u, a.d - 1) * a.Bp + b) * 2;
+      r0[u] = a.rec[o];
+      n3[u] = __uint_as_float(a.rec[o + 1].x);
+    }
+    float cf[U][4];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const float *c = tile + (size_t)min(i0 + u, a.d - 1) * a.R * a.jt + (r0[u].x >> 2) + jj;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) cf[u][q] = c[q * a.jt];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (i0 + u < a.d) {
+        acc = fmaf(__uint_as_float(r0[u].y), cf[u][0], acc);
+        acc = fmaf(__uint_as_float(r0[u].z), cf[u][1], acc);
+        acc = fmaf(__uint_as_float(r0[u].w), cf[u][2], acc);
+        acc = fmaf(n3[u], cf[u][3], acc);
+      }
+    }
   }
   a.y[b * a.m + j] = acc;
 }
@@ -698,7 +733,7 @@ int gather_jx_log2(int m) {
   return lg;
 }
 
-// Launch shape of the tiled kernels for B rows: NP row steps per wave (16/8/4/2, at most 64 rows per wave) and
+// Launch shape of the tiled kernels for B rows: NP row steps per wave (16/8/4/2/1, at most 64 rows per wave) and
 // the number of chunks the d inputs are split into.  Large row tiles re-read the table least, so NP starts at the
 // smallest value whose row tile covers B and shrinks only while the grid would still leave compute units idle
 // even with the inputs split (each chunk keeps at least 16 inputs).
@@ -708,11 +743,12 @@ struct TilePlan {
 
 TilePlan plan_tiles(int64_t B, int d, int n_tiles, int rps) {
   const int np_max = std::min(16, 64 / rps);
-  int np_cap = 2;
+  const int np_min = std::min(2, np_max);
+  int np_cap = np_min;
   while (np_cap < np_max && (int64_t)kTileWaves * rps * np_cap < B) np_cap <<= 1;
   const int max_split = std::max(1, std::min(32, d / 16));
   TilePlan best{np_cap, 1, d};
-  for (int np = np_cap; np >= 2; np >>= 1) {
+  for (int np = np_cap; np >= np_min; np >>= 1) {
     const int64_t groups = (B + kTileWaves * rps * np - 1) / (kTileWaves * rps * np) * n_tiles;
     const int split = (int)std::min<int64_t>(max_split, std::max<int64_t>(1, (256 + groups - 1) / groups));
     best = TilePlan{np, split, (d + split - 1) / split};
@@ -747,12 +783,12 @@ int launch_tiled_np(const EdgeArgs &ea, hipStream_t s) {
 
 template <int SCHEME, int LPR>
 int launch_tiled(const EdgeArgs &ea, int np, hipStream_t s) {
-  switch (np) {
-    case 16: if constexpr (LPR >= 16) return launch_tiled_np<SCHEME, LPR, 16>(ea, s);
-    case 8: return launch_tiled_np<SCHEME, LPR, 8>(ea, s);
-    case 4: return launch_tiled_np<SCHEME, LPR, 4>(ea, s);
-    default: return launch_tiled_np<SCHEME, LPR, 2>(ea, s);
-  }
+  constexpr int kMaxNp = (64 / (64 / LPR) < 16) ? 64 / (64 / LPR) : 16;      // at most 64 rows per wave
+  if constexpr (kMaxNp >= 16) { if (np >= 16) return launch_tiled_np<SCHEME, LPR, 16>(ea, s); }
+  if constexpr (kMaxNp >= 8) { if (np >= 8) return launch_tiled_np<SCHEME, LPR, 8>(ea, s); }
+  if constexpr (kMaxNp >= 4) { if (np >= 4) return launch_tiled_np<SCHEME, LPR, 4>(ea, s); }
+  if constexpr (kMaxNp >= 2) { if (np >= 2) return launch_tiled_np<SCHEME, LPR, 2>(ea, s); }
+  return launch_tiled_np<SCHEME, LPR, 1>(ea, s);
 }
 
 template <int SCHEME>
@@ -760,12 +796,15 @@ int launch_tiled_jt(const EdgeArgs &ea, int np, hipStream_t s) {
   switch (ea.jt) {
     case 128: return launch_tiled<SCHEME, 32>(ea, np, s);
     case 64: return launch_tiled<SCHEME, 16>(ea, np, s);
-    default: return launch_tiled<SCHEME, 8>(ea, np, s);
+    case 32: return launch_tiled<SCHEME, 8>(ea, np, s);
+    case 16: return launch_tiled<SCHEME, 4>(ea, np, s);
+    case 8: return launch_tiled<SCHEME, 2>(ea, np, s);
+    default: return launch_tiled<SCHEME, 1>(ea, np, s);
   }
 }
 
 bool tiled_supported(int jt, int blob_bytes) {
-  return (jt == 32 || jt == 64 || jt == 128) && blob_bytes <= lutkan::kLdsSliceBudget;
+  return jt >= 4 && blob_bytes <= lutkan::kLdsSliceBudget;
 }
 
 enum { kLocate = 1, kEdges = 2 };
@@ -812,7 +851,7 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
 
   bool tiled = tiled_supported(l->jt, l->blob_bytes) && !q01_out;
   if (l->algo == LUTKAN_ALGO_GATHER) tiled = false;
-  if (l->algo == LUTKAN_ALGO_TILED && !tiled) return fail(LUTKAN_EUNSUPPORTED, "%s: tiled kernel needs jt in {32,64,128} and a slice <= 56 KiB", who);
+  if (l->algo == LUTKAN_ALGO_TILED && !tiled) return fail(LUTKAN_EUNSUPPORTED, "%s: tiled kernel needs a table slice <= 56 KiB", who);
   ea.chunk = l->d;
   ea.split_stride = 0;
   if (tiled) {
@@ -853,11 +892,22 @@ int launch_spline_tiled_np(const SplineEdgeArgs &ea, hipStream_t s) {
 
 template <int LPR>
 int launch_spline_tiled(const SplineEdgeArgs &ea, int np, hipStream_t s) {
-  switch (np) {
-    case 16: if constexpr (LPR >= 16) return launch_spline_tiled_np<LPR, 16>(ea, s);
-    case 8: return launch_spline_tiled_np<LPR, 8>(ea, s);
-    case 4: return launch_spline_tiled_np<LPR, 4>(ea, s);
-    default: return launch_spline_tiled_np<LPR, 2>(ea, s);
+  constexpr int kMaxNp = (64 / (64 / LPR) < 16) ? 64 / (64 / LPR) : 16;
+  if constexpr (kMaxNp >= 16) { if (np >= 16) return launch_spline_tiled_np<LPR, 16>(ea, s); }
+  if constexpr (kMaxNp >= 8) { if (np >= 8) return launch_spline_tiled_np<LPR, 8>(ea, s); }
+  if constexpr (kMaxNp >= 4) { if (np >= 4) return launch_spline_tiled_np<LPR, 4>(ea, s); }
+  if constexpr (kMaxNp >= 2) { if (np >= 2) return launch_spline_tiled_np<LPR, 2>(ea, s); }
+  return launch_spline_tiled_np<LPR, 1>(ea, s);
+}
+
+int launch_spline_tiled_jt(const SplineEdgeArgs &ea, int np, hipStream_t s) {
+  switch (ea.jt) {
+    case 128: return launch_spline_tiled<32>(ea, np, s);
+    case 64: return launch_spline_tiled<16>(ea, np, s);
+    case 32: return launch_spline_tiled<8>(ea, np, s);
+    case 16: return launch_spline_tiled<4>(ea, np, s);
+    case 8: return launch_spline_tiled<2>(ea, np, s);
+    default: return launch_spline_tiled<1>(ea, np, s);
   }
 }
 
@@ -902,9 +952,9 @@ int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y
   SplineEdgeArgs ea;
   ea.coef_table = l->coef_table; ea.rec = la.rec; ea.y = y;
   ea.B = B; ea.Bp = Bp; ea.d = l->d; ea.m = l->m; ea.R = G + 3; ea.jt = l->jt; ea.n_tiles = l->n_tiles;
-  bool tiled = (l->jt == 32 || l->jt == 64 || l->jt == 128);
+  bool tiled = true;                                   // a coefficient slice always fits LDS (R <= 67)
   if (l->algo == LUTKAN_ALGO_GATHER) tiled = false;
-  if (l->algo == LUTKAN_ALGO_TILED && !tiled) return fail(LUTKAN_EUNSUPPORTED, "%s: tiled kernel needs jt in {32,64,128}", who);
+  if (l->algo == LUTKAN_ALGO_TILED && !tiled) return fail(LUTKAN_EUNSUPPORTED, "%s: tiled kernel unavailable", who);
   ea.chunk = l->d;
   ea.split_stride = 0;
   if (tiled) {
@@ -912,8 +962,7 @@ int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y
     float *partials = reinterpret_cast<float *>(static_cast<char *>(workspace) + record_bytes(l->d, Bp, 32));
     ea.chunk = tp.chunk;
     if (tp.n_split > 1) { ea.y = partials; ea.split_stride = B * l->m; }
-    const int rc = (l->jt == 128) ? launch_spline_tiled<32>(ea, tp.np, s)
-                                  : (l->jt == 64) ? launch_spline_tiled<16>(ea, tp.np, s) : launch_spline_tiled<8>(ea, tp.np, s);
+    const int rc = launch_spline_tiled_jt(ea, tp.np, s);
     if (rc || tp.n_split == 1) return rc;
     const int64_t n = B * l->m;
     hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, s, partials, y, n, tp.n_split);
@@ -930,7 +979,7 @@ int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y
 // Records for every (input, padded row), then room for the partial sums when the inputs are split into chunks.
 static size_t tiled_workspace_bytes(int d, int m, int jt, int n_tiles, int64_t B, int bytes_per_record) {
   size_t bytes = record_bytes(d, padded_rows(B), bytes_per_record);
-  if (jt >= 32) {
+  {
     const TilePlan tp = plan_tiles(B, d, n_tiles, 64 / (jt / 4));
     if (tp.n_split > 1) bytes += (size_t)tp.n_split * (size_t)B * (size_t)m * 4;
   }

@@ -98,6 +98,9 @@ PROPERTY_CASES = [
     (107, 3, 130, 8, 16, SYM_INT8, HALF_OPEN, CLIP_X, 31, False),
     (108, 20, 64, 5, 64, ASYM_UINT8, CLOSED, CLIP_X, 300, True),
     (109, 6, 200, 64, 8, SYM_INT8, CLOSED, ZERO_SPLINE, 129, False),
+    (110, 70, 2, 5, 64, ASYM_UINT8, HALF_OPEN, ZERO_SPLINE, 5000, True),     # inputs split into chunks, 4-column tile
+    (111, 130, 9, 7, 32, SYM_INT8, CLOSED, CLIP_X, 3001, False),            # 16-column tile, 8 chunks
+    (112, 33, 30, 9, 16, SYM_INT8, HALF_OPEN, CLIP_X, 40000, True),         # 32-column tile, many row tiles
 ]
 
 
@@ -106,6 +109,7 @@ def test_property_layers_gather_with_codes(case):
     seed, d, m, G, L, scheme, boundary, oob, B, uniform = case
     w = random_layer(seed, d, m, G, L, scheme, boundary, oob, B, uniform=uniform)
     _check_layer(w.layers[0], w.x, lk.ALGO_GATHER, codes=(B * d * m <= 2_000_000), what=w.name)
+    _check_layer(w.layers[0], w.x, lk.ALGO_TILED, what=w.name)          # narrow column tiles: 4..128 columns
 
 
 TILED_CASES = [
@@ -268,8 +272,7 @@ def test_bspline_layers(case):
     seed, d, m, G, L, scheme, boundary, oob, B, uniform = case
     w = random_layer(seed, d, m, G, L, scheme, boundary, oob, B, uniform=uniform)
     _check_bspline(w.layers[0], w.x, lk.ALGO_GATHER, w.name)
-    if m > 64:
-        _check_bspline(w.layers[0], w.x, lk.ALGO_TILED, w.name)
+    _check_bspline(w.layers[0], w.x, lk.ALGO_TILED, w.name)
 
 
 def test_bspline_special_inputs():
