@@ -52,10 +52,12 @@ def lib():
         L.lko_quantize_segment.restype = None
         L.lko_compile.argtypes = [C.c_int] * 4 + [C.c_void_p, C.c_void_p, C.c_int, C.c_int] + [C.c_void_p] * 5 + [C.c_int]
         L.lko_compile.restype = C.c_int
-        L.lko_lut_forward.argtypes = ([C.c_int] * 7 + [C.c_void_p] * 5 + [C.c_long] + [C.c_void_p] * 8 + [C.c_int])
+        L.lko_lut_forward.argtypes = ([C.c_int] * 7 + [C.c_void_p] * 8 + [C.c_long] + [C.c_void_p] * 8 + [C.c_int])
         L.lko_lut_forward.restype = C.c_int
-        L.lko_bspline_forward.argtypes = [C.c_int] * 4 + [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p,
-                                                          C.c_long, C.c_void_p, C.c_void_p, C.c_int]
+        L.lko_bspline_forward.argtypes = [C.c_int] * 4 + [C.c_void_p] * 5 + [C.c_int, C.c_int, C.c_void_p,
+                                                                           C.c_long, C.c_void_p, C.c_void_p, C.c_int]
+        L.lko_silu.argtypes = [C.c_float]
+        L.lko_silu.restype = C.c_float
         L.lko_bspline_forward.restype = C.c_int
         L.lko_artifact_bytes.argtypes = [C.c_long, C.c_int, C.c_int, C.c_int]
         L.lko_artifact_bytes.restype = C.c_long
@@ -126,8 +128,22 @@ def compile_layer(d, m, G, p, ext_knots, coef, L, scheme, want_v=False, nthreads
     return SimpleNamespace(d=d, m=m, K=K, L=L, scheme=scheme, knots=knots, q=q, scale=scale, y_min=y_min, v=v)
 
 
-def lut_forward(art, boundary, oob, x, trace=False, codes=False, nthreads=None):
-    """Layer forward on the artifact.  Returns y fp32 [B,m], A fp64 [B,m], and optionally the trace."""
+def _edge_scalars(edge_scalars, E):
+    """None (value_repr = phi) or the three per-edge fp32 arrays (s_base, s_spline, s_out) of Eq. 2, each [E]."""
+    if edge_scalars is None:
+        return None, None, None
+    sb, ss, so = (_f32(a).reshape(-1) for a in edge_scalars)
+    assert sb.size == E and ss.size == E and so.size == E
+    return sb, ss, so
+
+
+def silu(x: float) -> float:
+    return float(lib().lko_silu(float(np.float32(x))))
+
+
+def lut_forward(art, boundary, oob, x, trace=False, codes=False, nthreads=None, edge_scalars=None):
+    """Layer forward on the artifact.  Returns y fp32 [B,m], A fp64 [B,m], and optionally the trace.
+    edge_scalars = (s_base, s_spline, s_out) switches to value_repr = spline_component."""
     x = _f32(x)
     B = x.shape[0]
     d, m = art.d, art.m
@@ -143,8 +159,9 @@ def lut_forward(art, boundary, oob, x, trace=False, codes=False, nthreads=None):
     if codes:
         q01 = np.zeros((B, d, m, 2), dtype=np.int16)
     stats = np.zeros(2, dtype=np.uint64)
+    sb, ss, so = _edge_scalars(edge_scalars, d * m)
     rc = lib().lko_lut_forward(d, m, art.K, art.L, art.scheme, boundary, oob,
-                               _p(art.knots), _p(art.q), _p(art.scale), _p(art.y_min), _p(x), B,
+                               _p(art.knots), _p(art.q), _p(art.scale), _p(art.y_min), _p(sb), _p(ss), _p(so), _p(x), B,
                                _p(y), _p(A), _p(k), _p(l0), _p(inn), _p(w), _p(q01), _p(stats),
                                nthreads or default_threads())
     if rc != 0:
@@ -153,14 +170,15 @@ def lut_forward(art, boundary, oob, x, trace=False, codes=False, nthreads=None):
                            oob_count=int(stats[0]), oob_any_rows=int(stats[1]))
 
 
-def bspline_forward(d, m, G, p, ext_knots, coef, boundary, oob, x, nthreads=None):
+def bspline_forward(d, m, G, p, ext_knots, coef, boundary, oob, x, nthreads=None, edge_scalars=None):
     tau = _f32(ext_knots)
     coef = _f32(coef)
     x = _f32(x)
     B = x.shape[0]
     y = np.zeros((B, m), dtype=np.float32)
     A = np.zeros((B, m), dtype=np.float64)
-    rc = lib().lko_bspline_forward(d, m, G, p, _p(tau), _p(coef), boundary, oob, _p(x), B, _p(y), _p(A),
+    sb, ss, so = _edge_scalars(edge_scalars, d * m)
+    rc = lib().lko_bspline_forward(d, m, G, p, _p(tau), _p(coef), _p(sb), _p(ss), _p(so), boundary, oob, _p(x), B, _p(y), _p(A),
                                    nthreads or default_threads())
     if rc != 0:
         raise ValueError(f"lko_bspline_forward failed: {rc}")

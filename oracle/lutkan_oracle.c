@@ -17,7 +17,11 @@
  *   - the dense layer sum y_j = sum_i phi_ij(x_i)         (Sec. 3.1, Eq. 1), accumulated in fp64
  *
  * Readings taken where the paper is silent (each one is also a unit test):
- *   - the edge function is the pure spline branch, phi_ij == s_ij (value_repr = phi, no base branch);
+ *   - value_repr = phi: the edge function is the pure spline branch, phi_ij == s_ij (no base branch);
+ *     value_repr = spline_component (Sec. 4.3 B): the table still holds s_ij and the edge output is
+ *     s_out * (s_base * b(x) + s_spline * m(x) * s^(x')) with b = SiLU evaluated at the RAW input x in fp64 and
+ *     rounded once to fp32, the three per-edge scalars in fp32, one rounding per operation, and the mask m(x)
+ *     applied to the spline branch only (Sec. 5.4, last equation); under clip_x the mask is 1;
  *   - the LUT knots are the G+1 domain breakpoints tau[p..p+G] of the extended knot vector, K = G;
  *   - the spline is sampled in fp64 and rounded once to fp32; quantisation runs in fp32 with one
  *     rounding per operation and round-half-to-even for the code;
@@ -228,8 +232,28 @@ float lko_edge_value(const void *q, int scheme, size_t seg_base, int l0, int l1,
  *   k_out/l0_out/in_out/w_out [B][d], q01_out[B][d][m][2] (the two gathered codes per edge),
  *   stats[2] = { number of (row,input) pairs out of domain, number of rows with any such input }.
  * ---------------------------------------------------------------------------------------- */
+/* b(x) = SiLU(x) = x / (1 + exp(-x)) (Sec. 3.1, the fixed base nonlinearity), fp64, rounded once to fp32. */
+float lko_silu(float x)
+{
+    double xd = (double)x;
+    return (float)(xd / (1.0 + exp(-xd)));
+}
+
+/* Eq. 2 / Sec. 5.4: phi = s_out * (s_base * b + s_spline * spline_term), fp32, one rounding per operation.
+   abs_out (nullable) receives |s_out*s_base*b| + |s_out*s_spline*spline_term|, the tolerance denominator. */
+float lko_edge_compose(float s_base, float s_spline, float s_out, float b, float spline_term, double *abs_out)
+{
+    float tb = s_base * b;
+    float ts = s_spline * spline_term;
+    float sum = tb + ts;
+    float phi = s_out * sum;
+    if (abs_out) *abs_out = fabs((double)s_out * (double)tb) + fabs((double)s_out * (double)ts);
+    return phi;
+}
+
 int lko_lut_forward(int d, int m, int K, int L, int scheme, int boundary, int oob,
                     const float *knots, const void *q, const float *scale, const float *y_min,
+                    const float *edge_base, const float *edge_spline, const float *edge_out, /* [E] or all NULL */
                     const float *x, long B, float *y, double *A,
                     int32_t *k_out, int32_t *l0_out, uint8_t *in_out, float *w_out, int16_t *q01_out,
                     uint64_t *stats, int nthreads)
@@ -245,6 +269,7 @@ int lko_lut_forward(int d, int m, int K, int L, int scheme, int boundary, int oo
         for (int i = 0; i < d; ++i) {
             lko_index ix;
             lko_locate(knots, K, L, boundary, x[(size_t)b * d + i], &ix);
+            const float silu_x = edge_out ? lko_silu(x[(size_t)b * d + i]) : 0.0f;   /* base branch at the raw x */
             if (!ix.in) { ++oob_count; any = 1; }
             if (k_out) k_out[(size_t)b * d + i] = ix.k;
             if (l0_out) l0_out[(size_t)b * d + i] = ix.l0;
@@ -260,9 +285,12 @@ int lko_lut_forward(int d, int m, int K, int L, int scheme, int boundary, int oo
                     q01_out[o + 1] = (int16_t)lko_code(q, scheme, seg + ix.l1);
                 }
                 float phi = (oob == LKO_ZERO_SPLINE && !ix.in) ? 0.0f : v;   /* Sec. 5.4 */
-                if (ix.is_nan) phi = NAN;
+                double aphi = fabs((double)phi);
+                if (edge_out)                                                /* value_repr = spline_component */
+                    phi = lko_edge_compose(edge_base[e], edge_spline[e], edge_out[e], silu_x, phi, &aphi);
+                if (ix.is_nan) { phi = NAN; aphi = NAN; }
                 acc[j] += (double)phi;
-                absacc[j] += fabs((double)phi);
+                absacc[j] += aphi;
             }
         }
         oob_rows += (uint64_t)any;
@@ -281,6 +309,7 @@ int lko_lut_forward(int d, int m, int K, int L, int scheme, int boundary, int oo
  * A[B][m] (nullable) = sum_i sum_r |c_r| B_{r,p}(x'_i) over unmasked inputs.
  * ---------------------------------------------------------------------------------------- */
 int lko_bspline_forward(int d, int m, int G, int p, const float *tau_f, const float *coef,
+                        const float *edge_base, const float *edge_spline, const float *edge_out, /* [E] or all NULL */
                         int boundary, int oob, const float *x, long B, float *y, double *A, int nthreads)
 {
     if (d < 1 || m < 1 || G < 1 || p < 0 || B < 0) return -1;
@@ -299,11 +328,20 @@ int lko_bspline_forward(int d, int m, int G, int p, const float *tau_f, const fl
             lko_locate(T, K, 2, boundary, x[(size_t)b * d + i], &ix);
             lko_bspline_basis(tau, n, p, (double)ix.xc, N);
             int masked = (oob == LKO_ZERO_SPLINE && !ix.in);
+            double bx = 0.0;
+            if (edge_out) { double xd = (double)x[(size_t)b * d + i]; bx = xd / (1.0 + exp(-xd)); }
             for (int j = 0; j < m; ++j) {
                 const float *c = coef + ((size_t)i * m + j) * R;
                 double s = 0.0, sa = 0.0;
                 for (int r = 0; r < R; ++r) { s += (double)c[r] * N[r]; sa += fabs((double)c[r]) * N[r]; }
                 if (masked) { s = 0.0; sa = 0.0; }
+                if (edge_out) {                     /* Eq. 2 in fp64: s_out * (s_base * b(x) + s_spline * s(x')) */
+                    size_t e = (size_t)i * m + j;
+                    double tb = (double)edge_out[e] * (double)edge_base[e] * bx;
+                    double so = (double)edge_out[e] * (double)edge_spline[e];
+                    s = tb + so * s;
+                    sa = fabs(tb) + fabs(so) * sa;
+                }
                 if (ix.is_nan) { s = NAN; sa = NAN; }
                 acc[j] += s;
                 absacc[j] += sa;

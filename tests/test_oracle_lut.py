@@ -382,3 +382,102 @@ def test_lut_tracks_the_exact_spline_layer():
     assert np.abs(z_lut.y - z_ref.y).max() < 6 * 0.02
     far = np.full((2, s.d), 9.0, dtype=np.float32)
     assert np.all(oracle.bspline_forward(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, CLOSED, ZERO_SPLINE, far).y == 0)
+
+
+# ---------------------------------------------------------------- value_repr = spline_component (Eq. 2, Sec. 4.3 B, Sec. 5.4)
+from scipy.special import expit  # noqa: E402
+
+
+def _scalars(rng, E):
+    return (rng.normal(0.0, 1.0, E).astype(np.float32), rng.normal(1.0, 0.3, E).astype(np.float32),
+            rng.normal(1.0, 0.2, E).astype(np.float32))
+
+
+def test_silu_values_and_identities():
+    assert oracle.silu(0.0) == 0.0
+    for x in (0.25, 1.0, 3.5, 17.0):
+        assert abs((oracle.silu(x) - oracle.silu(-x)) - x) <= 2e-7 * max(1.0, x)          # x*s(x) - (-x)*s(-x) = x
+    assert abs(oracle.silu(30.0) - 30.0) < 1e-5 and abs(oracle.silu(-30.0)) < 1e-11
+    xs = np.linspace(-6, 6, 2401)
+    v = np.array([oracle.silu(x) for x in xs])
+    np.testing.assert_allclose(v, xs * expit(xs), rtol=2e-7, atol=1e-9)                     # library routine
+    imin = int(np.argmin(v))
+    assert abs(xs[imin] + 1.2785) < 0.006 and abs(v[imin] + 0.27846) < 1e-5                 # the SiLU minimum
+
+
+def test_spline_component_reduces_to_phi_when_base_is_off():
+    w = random_layer(31, 5, 4, 6, 32, ASYM_UINT8, HALF_OPEN, ZERO_SPLINE, B=500, oob_frac=0.3)
+    art = _compile_spec(w.layers[0])
+    E = 20
+    ones, zeros = np.ones(E, np.float32), np.zeros(E, np.float32)
+    for b in (HALF_OPEN, CLOSED):
+        for o in (CLIP_X, ZERO_SPLINE):
+            phi = oracle.lut_forward(art, b, o, w.x)
+            sc = oracle.lut_forward(art, b, o, w.x, edge_scalars=(zeros, ones, ones))
+            np.testing.assert_array_equal(phi.y, sc.y)
+            np.testing.assert_allclose(phi.A, sc.A, rtol=1e-12)
+
+
+def test_spline_component_base_branch_only_matches_closed_form_at_raw_x():
+    rng = np.random.Generator(np.random.PCG64(32))
+    w = random_layer(32, 6, 3, 5, 16, SYM_INT8, CLOSED, CLIP_X, B=300, oob_frac=1.5)    # many inputs far outside [-1,1]
+    art = _compile_spec(w.layers[0])
+    sb, ss, so = _scalars(rng, 18)
+    r = oracle.lut_forward(art, CLOSED, CLIP_X, w.x, edge_scalars=(sb, np.zeros(18, np.float32), so))
+    x64 = w.x.astype(np.float64)
+    want = (x64 * expit(x64)) @ (so.astype(np.float64) * sb.astype(np.float64)).reshape(6, 3)   # base at RAW x
+    np.testing.assert_allclose(r.y, want, rtol=3e-6, atol=3e-6)
+    clipped = np.clip(x64, -1, 1)
+    wrong = (clipped * expit(clipped)) @ (so.astype(np.float64) * sb.astype(np.float64)).reshape(6, 3)
+    assert np.abs(r.y - wrong).max() > 0.1
+
+
+def test_spline_component_zero_spline_masks_the_spline_branch_only():
+    rng = np.random.Generator(np.random.PCG64(33))
+    w = random_layer(33, 4, 2, 5, 16, ASYM_UINT8, HALF_OPEN, ZERO_SPLINE, B=64)
+    art = _compile_spec(w.layers[0])
+    sb, ss, so = _scalars(rng, 8)
+    x = np.full((3, 4), 2.5, dtype=np.float32)
+    x[1] = -4.0
+    x[2, :2] = 0.3                                                     # a row with two inputs inside, two outside
+    full = oracle.lut_forward(art, HALF_OPEN, ZERO_SPLINE, x, edge_scalars=(sb, ss, so))
+    base = oracle.lut_forward(art, HALF_OPEN, ZERO_SPLINE, x, edge_scalars=(sb, np.zeros(8, np.float32), so))
+    np.testing.assert_array_equal(full.y[:2], base.y[:2])              # all inputs OOB: only the base branch is left
+    assert np.abs(full.y[2] - base.y[2]).max() > 1e-3                  # in-range inputs keep their spline branch
+    clip = oracle.lut_forward(art, HALF_OPEN, CLIP_X, x, edge_scalars=(sb, ss, so))
+    assert np.abs(clip.y[:2] - base.y[:2]).max() > 1e-3                # clip_x keeps the saturated spline value
+
+
+def test_spline_component_single_edge_composition_and_output_scale():
+    rng = np.random.Generator(np.random.PCG64(34))
+    tau = uniform_ext_knots(-1.0, 1.0, 5)
+    art = _one_edge_art(tau, 32, SYM_INT8)
+    x = rng.uniform(-1.5, 1.5, 400).astype(np.float32).reshape(-1, 1)
+    v = oracle.lut_forward(art, CLOSED, ZERO_SPLINE, x).y[:, 0]        # m(x) * s^(x')
+    sb, ss, so = np.float32(0.7), np.float32(-1.3), np.float32(0.9)
+    r = oracle.lut_forward(art, CLOSED, ZERO_SPLINE, x, edge_scalars=([sb], [ss], [so]))
+    b = np.array([oracle.silu(t) for t in x[:, 0]], dtype=np.float32)
+    want = (so * ((sb * b).astype(np.float32) + (ss * v).astype(np.float32)).astype(np.float32)).astype(np.float32)
+    np.testing.assert_array_equal(r.y[:, 0], want)
+    r2 = oracle.lut_forward(art, CLOSED, ZERO_SPLINE, x, edge_scalars=([sb], [ss], [np.float32(2) * so]))
+    np.testing.assert_array_equal(r2.y, np.float32(2) * r.y)           # s_out scales the whole edge (Eq. 2)
+
+
+def test_bspline_layer_spline_component_matches_fp64_closed_form():
+    from scipy.interpolate import BSpline
+    rng = np.random.Generator(np.random.PCG64(35))
+    w = random_layer(35, 3, 2, 6, 16, SYM_INT8, CLOSED, ZERO_SPLINE, B=200, uniform=False, oob_frac=0.4)
+    s = w.layers[0]
+    sb, ss, so = _scalars(rng, 6)
+    r = oracle.bspline_forward(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, CLOSED, ZERO_SPLINE, w.x, edge_scalars=(sb, ss, so))
+    x64 = w.x.astype(np.float64)
+    t64 = s.ext_knots.astype(np.float64)
+    lo, hi = t64[3], t64[3 + s.G]
+    inside = (x64 >= lo) & (x64 <= hi)
+    want = np.zeros((200, s.m))
+    for i in range(s.d):
+        for j in range(s.m):
+            e = i * s.m + j
+            sp = BSpline(t64, s.coef[i, j].astype(np.float64), 3, extrapolate=False)(np.clip(x64[:, i], lo, np.nextafter(hi, -np.inf)))
+            want[:, j] += float(so[e]) * (float(sb[e]) * x64[:, i] * expit(x64[:, i]) + float(ss[e]) * np.where(inside[:, i], sp, 0.0))
+    np.testing.assert_allclose(r.y, want, rtol=2e-6, atol=2e-6)

@@ -27,6 +27,11 @@ MUTATIONS = {
     "l1_not_clamped_to_l0_plus_1": ("o->l1 = (l0 + 1 < L - 1) ? l0 + 1 : L - 1;", "o->l1 = l0;"),
     "asym_min_is_zero": ("*y_min = lo;", "*y_min = 0.0f;"),
     "degree0_closed_indicator": ("(tau[r] <= x && x < tau[r + 1])", "(tau[r] <= x && x <= tau[r + 1])"),
+    "base_branch_at_clipped_x": ("const float silu_x = edge_out ? lko_silu(x[(size_t)b * d + i]) : 0.0f;", "const float silu_x = edge_out ? lko_silu(ix.xc) : 0.0f;"),
+    "silu_wrong_sign": ("return (float)(xd / (1.0 + exp(-xd)));", "return (float)(xd / (1.0 + exp(xd)));"),
+    "edge_output_scale_dropped": ("float phi = s_out * sum;", "float phi = sum;"),
+    "spline_scale_on_base": ("float tb = s_base * b;\n    float ts = s_spline * spline_term;", "float tb = s_spline * b;\n    float ts = s_base * spline_term;"),
+    "bspline_layer_masks_base_too": ("                if (masked) { s = 0.0; sa = 0.0; }\n                if (edge_out) {", "                if (edge_out) {"),
     "layer_sum_skips_first_input": ("for (int i = 0; i < d; ++i) {\n            lko_index ix;\n            lko_locate(knots", "for (int i = (d > 1); i < d; ++i) {\n            lko_index ix;\n            lko_locate(knots"),
 }
 
