@@ -40,6 +40,7 @@ typedef enum { LUTKAN_SYM_INT8 = 0, LUTKAN_ASYM_UINT8 = 1 } lutkan_scheme;      
 typedef enum { LUTKAN_HALF_OPEN = 0, LUTKAN_CLOSED = 1 } lutkan_boundary;          /* Sec. 5.2 */
 typedef enum { LUTKAN_CLIP_X = 0, LUTKAN_ZERO_SPLINE = 1 } lutkan_oob;             /* Sec. 5.4 */
 typedef enum { LUTKAN_ALGO_AUTO = 0, LUTKAN_ALGO_GATHER = 1, LUTKAN_ALGO_TILED = 2 } lutkan_algo;
+typedef enum { LUTKAN_REPR_PHI = 0, LUTKAN_REPR_SPLINE_COMPONENT = 1 } lutkan_value_repr;  /* Sec. 4.3 A / B */
 
 #define LUTKAN_MAX_K 64            /* segments per layer (the knot vector travels in the kernel arguments) */
 #define LUTKAN_MAX_ROWS 65536      /* K * L, table rows per input */
@@ -52,7 +53,12 @@ const char *lutkan_version(void);
  * Host side: compile a B-spline KAN layer into a LUT artifact (Sec. 4.2-4.6, Sec. 6.3).
  * ---------------------------------------------------------------------------------------------- */
 
-/* One dense layer with pure-spline edges phi_ij = s_ij (value_repr = phi, Sec. 4.3).  All pointers are host. */
+/* One dense layer.  All pointers are host.
+ * value_repr = LUTKAN_REPR_PHI: pure-spline edges, phi_ij = s_ij (Sec. 4.3 A with no base branch); the three
+ *   edge_* pointers are ignored.
+ * value_repr = LUTKAN_REPR_SPLINE_COMPONENT (Sec. 4.3 B, Eq. 2): the table still holds the spline branch s_ij and
+ *   the edge output is  s_out * (s_base * SiLU(x) + s_spline * m(x) * s^(x'))  with the base branch evaluated at
+ *   the raw input and the oob mask m(x) applied to the spline branch only (Sec. 5.4); the three arrays are [d][m]. */
 typedef struct {
   int32_t d, m;              /* inputs, outputs */
   int32_t G;                 /* grid intervals; the LUT has K = G segments on the domain grid (Sec. 4.2) */
@@ -63,12 +69,16 @@ typedef struct {
   int32_t scheme;            /* lutkan_scheme */
   int32_t boundary;          /* lutkan_boundary */
   int32_t oob;               /* lutkan_oob */
+  int32_t value_repr;        /* lutkan_value_repr */
+  const float *edge_base_scale;    /* s_base   [d][m], spline_component only */
+  const float *edge_spline_scale;  /* s_spline [d][m] */
+  const float *edge_out_scale;     /* s_out    [d][m] */
 } lutkan_layer_desc;
 
 typedef struct lutkan_artifact lutkan_artifact;     /* opaque, host memory */
 
 typedef struct {
-  int32_t d, m, K, L, G, degree, scheme, boundary, oob;
+  int32_t d, m, K, L, G, degree, scheme, boundary, oob, value_repr;
   int32_t jt;                /* column-tile width of the device tables (a power of two <= 128, or 128) */
   int32_t n_tiles;           /* ceil(m / jt) */
   int32_t blob_bytes;        /* bytes of one (tile, input) slice of the LUT device table */
@@ -94,9 +104,13 @@ const float *lutkan_artifact_scale(const lutkan_artifact *a);     /* alpha  [E][
 const float *lutkan_artifact_ymin(const lutkan_artifact *a);      /* y_min  [E][K] (zeros for symmetric) */
 const float *lutkan_artifact_knots(const lutkan_artifact *a);     /* [K+1] */
 const float *lutkan_artifact_ext_knots(const lutkan_artifact *a); /* [G+2p+1] */
+const float *lutkan_artifact_edge_base_scale(const lutkan_artifact *a);   /* [E], NULL for value_repr = phi (Sec. 4.6) */
+const float *lutkan_artifact_edge_spline_scale(const lutkan_artifact *a); /* [E] */
+const float *lutkan_artifact_edge_out_scale(const lutkan_artifact *a);    /* [E] */
 
 /* Device tables (host copies to upload verbatim).  Columns are cut into n_tiles tiles of jt outputs; the
  * last tile is zero padded.  LUT table: for tile t and input i one contiguous slice of blob_bytes bytes
+ *     float   base  [jt]                       (spline_component only: s_out * s_base of the edge (i, column))
  *     param   p     [K+1][jt]                  (symmetric: fp32 alpha; asymmetric: the fp32 pair {alpha, y_min} --
  *                                               y_min is elided when it is identically 0, Sec. 7.5; row K is all zero)
  *     code    q     [K*L+2][jt]                (one byte per code, row k*L+l, i.e. the [i][segment][sample][j]
@@ -104,6 +118,8 @@ const float *lutkan_artifact_ext_knots(const lutkan_artifact *a); /* [G+2p+1] */
  *                                               byte = q + 128; the two trailing rows are all-zero bytes)
  *     zero padding up to a multiple of 16 bytes
  * The zero rows are where the kernels redirect inputs whose contribution is exactly 0 (oob_policy zero_spline).
+ * With spline_component the product s_out * s_spline of the edge is folded into its alpha and y_min (and into
+ * the coefficients of the B-spline table, whose slices then start with the same base[jt] row).
  * slices ordered [t][i].  B-spline table: slices of float c[R = G+p][jt], ordered [t][i]. */
 const void *lutkan_artifact_table(const lutkan_artifact *a);
 const void *lutkan_artifact_coef_table(const lutkan_artifact *a);
@@ -112,7 +128,7 @@ const void *lutkan_artifact_coef_table(const lutkan_artifact *a);
  * Device side.  The structs are plain host structs; the pointers inside are DEVICE pointers.
  * ---------------------------------------------------------------------------------------------- */
 typedef struct {
-  int32_t d, m, K, L, scheme, boundary, oob;
+  int32_t d, m, K, L, scheme, boundary, oob, value_repr;
   int32_t jt, n_tiles, blob_bytes;
   int32_t algo;                       /* lutkan_algo; AUTO picks by shape */
   float knots[LUTKAN_MAX_K + 1];      /* host copy of T, entries 0..K used */
@@ -120,7 +136,7 @@ typedef struct {
 } lutkan_dev_layer;
 
 typedef struct {
-  int32_t d, m, G, degree, boundary, oob;
+  int32_t d, m, G, degree, boundary, oob, value_repr;
   int32_t jt, n_tiles, coef_blob_bytes;
   int32_t algo;
   float ext_knots[LUTKAN_MAX_K + 7];  /* host copy, entries 0..G+6 used */

@@ -58,6 +58,7 @@ class LayerSpec:
     scheme: int
     boundary: int
     oob: int
+    edge_scales: object = None    # None (value_repr = phi) or (s_base, s_spline, s_out), each [d][m] fp32 (Eq. 2)
 
 
 @dataclass
@@ -138,9 +139,27 @@ def cfg5(seed: int = 0, B: int = 131072, boundary: int = CLOSED, oob: int = CLIP
     return Workload(f"cfg5_deep_G5_L32_asym_{bn}_{on}", layers, x)
 
 
+def draw_edge_scales(rng: np.random.Generator, d: int, m: int):
+    """PyKAN-style per-edge scalars of Eq. 2: s_base ~ N(0,1), s_spline ~ N(1,0.1), s_out ~ N(1,0.2)."""
+    return (rng.normal(0.0, 1.0, size=(d, m)).astype(np.float32), rng.normal(1.0, 0.1, size=(d, m)).astype(np.float32),
+            rng.normal(1.0, 0.2, size=(d, m)).astype(np.float32))
+
+
+def case_a(seed: int = 0, L: int = 64, scheme: int = SYM_INT8, boundary: int = CLOSED, oob: int = CLIP_X,
+           B: int = 1024, clip_inputs: bool = True) -> Workload:
+    """The paper's controlled-sweep shape (Sec. 6.2 Case A): one layer 10->8, grid 8, cubic, value_repr =
+    spline_component with SiLU; inputs N(0,1) clipped to the knot domain [-1,1] (so some sit exactly on t_K)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    layer = _layers(rng, [10, 8], 8, -1.0, 1.0, 1.0, L, scheme, boundary, oob)[0]
+    layer.edge_scales = draw_edge_scales(rng, 10, 8)
+    x = rng.normal(0.0, 1.0, size=(B, 10))
+    x = (np.clip(x, -1.0, 1.0) if clip_inputs else x).astype(np.float32)
+    return Workload(f"caseA_10x8_G8_L{L}_s{scheme}_b{boundary}_o{oob}", [layer], x)
+
+
 def random_layer(seed: int, d: int, m: int, G: int, L: int, scheme: int, boundary: int, oob: int,
                  B: int, lo: float = -1.0, hi: float = 1.0, uniform: bool = True,
-                 oob_frac: float = 0.15, p: int = 3) -> Workload:
+                 oob_frac: float = 0.15, p: int = 3, with_base: bool = False) -> Workload:
     """Property-test layer: optional non-uniform knots; x covers the domain, its exact knots and both tails."""
     rng = np.random.Generator(np.random.PCG64(seed))
     tau = uniform_ext_knots(lo, hi, G, p) if uniform else nonuniform_ext_knots(rng, lo, hi, G, p)
@@ -157,4 +176,6 @@ def random_layer(seed: int, d: int, m: int, G: int, L: int, scheme: int, boundar
                     np.where(nudge > 0, np.nextafter(vals, np.float32(np.inf)), vals)).astype(np.float32)
     x.reshape(-1)[idx] = vals
     layer = LayerSpec(d, m, G, p, tau, coef, L, scheme, boundary, oob)
-    return Workload(f"rand_{d}x{m}_G{G}_L{L}_s{scheme}_b{boundary}_o{oob}_seed{seed}", [layer], x)
+    if with_base:
+        layer.edge_scales = draw_edge_scales(rng, d, m)
+    return Workload(f"rand_{d}x{m}_G{G}_L{L}_s{scheme}_b{boundary}_o{oob}_seed{seed}{'_sc' if with_base else ''}", [layer], x)

@@ -13,6 +13,7 @@ SYM_INT8, ASYM_UINT8 = 0, 1
 HALF_OPEN, CLOSED = 0, 1
 CLIP_X, ZERO_SPLINE = 0, 1
 ALGO_AUTO, ALGO_GATHER, ALGO_TILED = 0, 1, 2
+REPR_PHI, REPR_SPLINE_COMPONENT = 0, 1
 MAX_K = 64
 
 
@@ -23,11 +24,13 @@ class LutKanError(RuntimeError):
 class _LayerDesc(C.Structure):
     _fields_ = [("d", C.c_int32), ("m", C.c_int32), ("G", C.c_int32), ("degree", C.c_int32),
                 ("ext_knots", C.c_void_p), ("coef", C.c_void_p),
-                ("L", C.c_int32), ("scheme", C.c_int32), ("boundary", C.c_int32), ("oob", C.c_int32)]
+                ("L", C.c_int32), ("scheme", C.c_int32), ("boundary", C.c_int32), ("oob", C.c_int32),
+                ("value_repr", C.c_int32), ("edge_base_scale", C.c_void_p), ("edge_spline_scale", C.c_void_p),
+                ("edge_out_scale", C.c_void_p)]
 
 
 class _Info(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("d", "m", "K", "L", "G", "degree", "scheme", "boundary", "oob",
+    _fields_ = [(n, C.c_int32) for n in ("d", "m", "K", "L", "G", "degree", "scheme", "boundary", "oob", "value_repr",
                                          "jt", "n_tiles", "blob_bytes", "coef_blob_bytes")] + \
                [("t0", C.c_float), ("tK", C.c_float), ("tK_star", C.c_float)] + \
                [(n, C.c_size_t) for n in ("q_canonical_bytes", "params_canonical_bytes", "table_bytes",
@@ -35,13 +38,13 @@ class _Info(C.Structure):
 
 
 class _DevLayer(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("d", "m", "K", "L", "scheme", "boundary", "oob", "jt", "n_tiles",
+    _fields_ = [(n, C.c_int32) for n in ("d", "m", "K", "L", "scheme", "boundary", "oob", "value_repr", "jt", "n_tiles",
                                          "blob_bytes", "algo")] + \
                [("knots", C.c_float * (MAX_K + 1)), ("table", C.c_void_p)]
 
 
 class _SplineDevLayer(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("d", "m", "G", "degree", "boundary", "oob", "jt", "n_tiles",
+    _fields_ = [(n, C.c_int32) for n in ("d", "m", "G", "degree", "boundary", "oob", "value_repr", "jt", "n_tiles",
                                          "coef_blob_bytes", "algo")] + \
                [("ext_knots", C.c_float * (MAX_K + 7)), ("coef_table", C.c_void_p)]
 
@@ -50,6 +53,7 @@ EXPORTS = [
     "lutkan_last_error", "lutkan_version", "lutkan_compile", "lutkan_artifact_free", "lutkan_artifact_info",
     "lutkan_artifact_q", "lutkan_artifact_scale", "lutkan_artifact_ymin", "lutkan_artifact_knots",
     "lutkan_artifact_ext_knots", "lutkan_artifact_table", "lutkan_artifact_coef_table",
+    "lutkan_artifact_edge_base_scale", "lutkan_artifact_edge_spline_scale", "lutkan_artifact_edge_out_scale",
     "lutkan_dev_layer_init", "bspline_dev_layer_init", "lutkan_forward_workspace_bytes",
     "bspline_forward_workspace_bytes", "lutkan_forward", "lutkan_forward_trace", "bspline_kan_forward",
     "lutkan_model_workspace_bytes", "lutkan_model_forward", "lutkan_forward_locate", "lutkan_forward_edges",
@@ -78,7 +82,8 @@ def load_library():
     lib.lutkan_artifact_free.argtypes = [vp]
     lib.lutkan_artifact_free.restype = None
     lib.lutkan_artifact_info.argtypes = [vp, C.POINTER(_Info)]
-    for n in ("q", "scale", "ymin", "knots", "ext_knots", "table", "coef_table"):
+    for n in ("q", "scale", "ymin", "knots", "ext_knots", "table", "coef_table", "edge_base_scale", "edge_spline_scale",
+              "edge_out_scale"):
         f = getattr(lib, "lutkan_artifact_" + n)
         f.argtypes = [vp]
         f.restype = vp
@@ -139,11 +144,16 @@ class Artifact:
         self.table = _view(lib.lutkan_artifact_table(handle), info.table_bytes, np.uint8, (info.table_bytes,))
         self.coef_table = _view(lib.lutkan_artifact_coef_table(handle), info.coef_table_bytes, np.float32,
                                 (info.coef_table_bytes // 4,))
+        self.edge_scales = None
+        if info.value_repr == REPR_SPLINE_COMPONENT:
+            self.edge_scales = tuple(_view(getattr(lib, "lutkan_artifact_edge_" + n)(handle), E * 4, np.float32, (E,))
+                                     for n in ("base_scale", "spline_scale", "out_scale"))
 
     def __del__(self):
         h, self._h = getattr(self, "_h", None), None
         if h and _lib is not None:
             self.q = self.scale = self.y_min = self.knots = self.ext_knots = self.table = self.coef_table = None
+            self.edge_scales = None
             _lib.lutkan_artifact_free(h)
 
     def to_device(self, device="cuda:0", algo: int = ALGO_AUTO) -> "LutLayer":
@@ -154,14 +164,19 @@ class Artifact:
 
 
 def lutkan_compile(d: int, m: int, G: int, degree: int, ext_knots, coef, L: int, scheme: int, boundary: int,
-                   oob: int, n_threads: int = 0) -> Artifact:
-    """Host-only LUT compilation of one dense B-spline KAN layer (Sec. 4.2-4.6)."""
+                   oob: int, n_threads: int = 0, edge_scales=None) -> Artifact:
+    """Host-only LUT compilation of one dense B-spline KAN layer (Sec. 4.2-4.6).
+    edge_scales = (s_base, s_spline, s_out), each [d, m], selects value_repr = spline_component (Eq. 2)."""
     lib = load_library()
     tau = np.ascontiguousarray(ext_knots, dtype=np.float32)
     cf = np.ascontiguousarray(coef, dtype=np.float32)
     if tau.size != G + 2 * degree + 1 or cf.size != d * m * (G + degree):
         raise LutKanError("lutkan_compile: ext_knots / coef have the wrong number of elements")
-    desc = _LayerDesc(d, m, G, degree, tau.ctypes.data, cf.ctypes.data, L, scheme, boundary, oob)
+    keep = [np.ascontiguousarray(a, dtype=np.float32).reshape(-1) for a in edge_scales] if edge_scales is not None else []
+    if keep and any(a.size != d * m for a in keep):
+        raise LutKanError("lutkan_compile: every edge scale array needs d*m elements")
+    desc = _LayerDesc(d, m, G, degree, tau.ctypes.data, cf.ctypes.data, L, scheme, boundary, oob,
+                      REPR_SPLINE_COMPONENT if keep else REPR_PHI, *[a.ctypes.data for a in keep])
     out = C.c_void_p()
     _check(lib.lutkan_compile(C.byref(desc), n_threads, C.byref(out)))
     return Artifact(out.value)

@@ -29,10 +29,10 @@ int fail(int code, const char *fmt, ...) {
   return code;
 }
 
-int choose_jt(int m, int K, int L, int scheme) {
+int choose_jt(int m, int K, int L, int scheme, int value_repr) {
   int jt = 4;
   while (jt < m && jt < 128) jt *= 2;
-  while (jt > 32 && blob_layout(K, L, jt, scheme).bytes > kLdsSliceBudget) jt /= 2;
+  while (jt > 32 && blob_layout(K, L, jt, scheme, value_repr).bytes > kLdsSliceBudget) jt /= 2;
   return jt;
 }
 
@@ -126,6 +126,10 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
   if (desc->scheme != LUTKAN_SYM_INT8 && desc->scheme != LUTKAN_ASYM_UINT8) return fail(LUTKAN_EINVAL, "lutkan_compile: bad scheme %d", desc->scheme);
   if (desc->boundary != LUTKAN_HALF_OPEN && desc->boundary != LUTKAN_CLOSED) return fail(LUTKAN_EINVAL, "lutkan_compile: bad boundary_mode %d", desc->boundary);
   if (desc->oob != LUTKAN_CLIP_X && desc->oob != LUTKAN_ZERO_SPLINE) return fail(LUTKAN_EINVAL, "lutkan_compile: bad oob_policy %d", desc->oob);
+  if (desc->value_repr != LUTKAN_REPR_PHI && desc->value_repr != LUTKAN_REPR_SPLINE_COMPONENT) return fail(LUTKAN_EINVAL, "lutkan_compile: bad value_repr %d", desc->value_repr);
+  const bool with_base = (desc->value_repr == LUTKAN_REPR_SPLINE_COMPONENT);
+  if (with_base && (!desc->edge_base_scale || !desc->edge_spline_scale || !desc->edge_out_scale))
+    return fail(LUTKAN_EINVAL, "lutkan_compile: spline_component needs edge_base_scale, edge_spline_scale and edge_out_scale");
   const int K = G, R = G + P, n_knots = G + 2 * P + 1;
   if (K > LUTKAN_MAX_K) return fail(LUTKAN_EUNSUPPORTED, "lutkan_compile: K=%d exceeds LUTKAN_MAX_K=%d", K, LUTKAN_MAX_K);
   if ((int64_t)K * L > LUTKAN_MAX_ROWS) return fail(LUTKAN_EUNSUPPORTED, "lutkan_compile: K*L=%lld exceeds %d", (long long)K * L, LUTKAN_MAX_ROWS);
@@ -136,14 +140,20 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
   const size_t E = (size_t)d * m;
   for (size_t n = 0; n < E * R; ++n)
     if (!std::isfinite(desc->coef[n])) return fail(LUTKAN_EINVAL, "lutkan_compile: coefficient %zu is not finite", n);
+  if (with_base)
+    for (size_t e = 0; e < E; ++e)
+      if (!std::isfinite(desc->edge_base_scale[e]) || !std::isfinite(desc->edge_spline_scale[e]) || !std::isfinite(desc->edge_out_scale[e]))
+        return fail(LUTKAN_EINVAL, "lutkan_compile: edge scale %zu is not finite", e);
 
   lutkan_artifact *a = new (std::nothrow) lutkan_artifact();
   if (!a) return fail(LUTKAN_ENOMEM, "lutkan_compile: out of host memory");
   const int scheme = desc->scheme;
-  const int jt = choose_jt(m, K, L, scheme);
+  const int repr = desc->value_repr;
+  const int jt = choose_jt(m, K, L, scheme, repr);
   const int n_tiles = (m + jt - 1) / jt;
-  const BlobLayout lay = blob_layout(K, L, jt, scheme);
-  const int coef_blob = R * jt * 4;
+  const BlobLayout lay = blob_layout(K, L, jt, scheme, repr);
+  const int coef_rows = coef_slice_rows(R, repr);
+  const int coef_blob = coef_rows * jt * 4;
   try {
     a->ext_knots.assign(desc->ext_knots, desc->ext_knots + n_knots);
     a->knots.assign(desc->ext_knots + P, desc->ext_knots + P + K + 1);
@@ -151,7 +161,12 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
     a->scale.resize(E * K);
     a->ymin.resize(E * K);
     a->table.assign((size_t)n_tiles * d * lay.bytes, 0);
-    a->coef_table.assign((size_t)n_tiles * d * R * jt, 0.0f);
+    a->coef_table.assign((size_t)n_tiles * d * coef_rows * jt, 0.0f);
+    if (with_base) {
+      a->edge_base.assign(desc->edge_base_scale, desc->edge_base_scale + E);
+      a->edge_spline.assign(desc->edge_spline_scale, desc->edge_spline_scale + E);
+      a->edge_out.assign(desc->edge_out_scale, desc->edge_out_scale + E);
+    }
   } catch (const std::bad_alloc &) {
     delete a;
     return fail(LUTKAN_ENOMEM, "lutkan_compile: out of host memory for %zu edges", E);
@@ -179,10 +194,20 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
         const float *c = desc->coef + e * R;
         const int t = j / jt, jj = j % jt;
         uint8_t *slice = a->table.data() + ((size_t)t * d + i) * lay.bytes;
-        float *slice_params = reinterpret_cast<float *>(slice);
+        float *slice_params = reinterpret_cast<float *>(slice + lay.params_off);
         uint8_t *slice_codes = slice + lay.codes_off;
-        float *cslice = a->coef_table.data() + ((size_t)t * d + i) * R * jt;
-        for (int r = 0; r < R; ++r) cslice[(size_t)r * jt + jj] = c[r];
+        float *cslice = a->coef_table.data() + ((size_t)t * d + i) * coef_rows * jt;
+        // spline_component (Eq. 2): the device tables carry s_out*s_base per edge as an extra row and fold
+        // s_out*s_spline into the edge's dequantisation parameters / B-spline coefficients.
+        float spline_gain = 1.0f;
+        if (with_base) {
+          const float base_gain = desc->edge_out_scale[e] * desc->edge_base_scale[e];
+          spline_gain = desc->edge_out_scale[e] * desc->edge_spline_scale[e];
+          reinterpret_cast<float *>(slice)[jj] = base_gain;
+          cslice[jj] = base_gain;
+          cslice += jt;
+        }
+        for (int r = 0; r < R; ++r) cslice[(size_t)r * jt + jj] = with_base ? spline_gain * c[r] : c[r];
         for (int k = 0; k < K; ++k) {
           const double c0 = c[k], c1 = c[k + 1], c2 = c[k + 2], c3 = c[k + 3];
           for (int l = 0; l < L; ++l) {
@@ -201,10 +226,10 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
           a->scale[e * K + k] = sc.alpha;
           a->ymin[e * K + k] = sc.ymin;
           if (scheme == LUTKAN_ASYM_UINT8) {
-            slice_params[((size_t)k * jt + jj) * 2] = sc.alpha;
-            slice_params[((size_t)k * jt + jj) * 2 + 1] = sc.ymin;
+            slice_params[((size_t)k * jt + jj) * 2] = with_base ? spline_gain * sc.alpha : sc.alpha;
+            slice_params[((size_t)k * jt + jj) * 2 + 1] = with_base ? spline_gain * sc.ymin : sc.ymin;
           } else {
-            slice_params[(size_t)k * jt + jj] = sc.alpha;
+            slice_params[(size_t)k * jt + jj] = with_base ? spline_gain * sc.alpha : sc.alpha;
           }
           // device codes: uint8 as is; int8 stored excess-128 (q + 128), which the kernels undo exactly
           const uint8_t flip = (scheme == LUTKAN_SYM_INT8) ? 0x80 : 0x00;
@@ -224,7 +249,7 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
   lutkan_info &I = a->info;
   std::memset(&I, 0, sizeof(I));
   I.d = d; I.m = m; I.K = K; I.L = L; I.G = G; I.degree = P;
-  I.scheme = scheme; I.boundary = desc->boundary; I.oob = desc->oob;
+  I.scheme = scheme; I.boundary = desc->boundary; I.oob = desc->oob; I.value_repr = repr;
   I.jt = jt; I.n_tiles = n_tiles; I.blob_bytes = lay.bytes; I.coef_blob_bytes = coef_blob;
   I.t0 = a->knots[0]; I.tK = a->knots[K];
   I.tK_star = (desc->boundary == LUTKAN_CLOSED) ? I.tK : std::nextafterf(I.tK, -INFINITY);  // Eq. 13
@@ -232,7 +257,7 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
   I.params_canonical_bytes = E * K * 4;
   I.table_bytes = a->table.size();
   I.coef_table_bytes = a->coef_table.size() * 4;
-  I.artifact_bytes = I.q_canonical_bytes + 2 * I.params_canonical_bytes + 4 * (size_t)(K + 1);
+  I.artifact_bytes = I.q_canonical_bytes + 2 * I.params_canonical_bytes + 4 * (size_t)(K + 1) + (with_base ? 12 * E : 0);
   *out = a;
   return LUTKAN_OK;
 }
@@ -250,6 +275,9 @@ extern "C" const float *lutkan_artifact_scale(const lutkan_artifact *a) { return
 extern "C" const float *lutkan_artifact_ymin(const lutkan_artifact *a) { return a ? a->ymin.data() : nullptr; }
 extern "C" const float *lutkan_artifact_knots(const lutkan_artifact *a) { return a ? a->knots.data() : nullptr; }
 extern "C" const float *lutkan_artifact_ext_knots(const lutkan_artifact *a) { return a ? a->ext_knots.data() : nullptr; }
+extern "C" const float *lutkan_artifact_edge_base_scale(const lutkan_artifact *a) { return (a && !a->edge_base.empty()) ? a->edge_base.data() : nullptr; }
+extern "C" const float *lutkan_artifact_edge_spline_scale(const lutkan_artifact *a) { return (a && !a->edge_spline.empty()) ? a->edge_spline.data() : nullptr; }
+extern "C" const float *lutkan_artifact_edge_out_scale(const lutkan_artifact *a) { return (a && !a->edge_out.empty()) ? a->edge_out.data() : nullptr; }
 extern "C" const void *lutkan_artifact_table(const lutkan_artifact *a) { return a ? a->table.data() : nullptr; }
 extern "C" const void *lutkan_artifact_coef_table(const lutkan_artifact *a) { return a ? a->coef_table.data() : nullptr; }
 
@@ -258,7 +286,7 @@ extern "C" int lutkan_dev_layer_init(const lutkan_artifact *a, lutkan_dev_layer 
   std::memset(out, 0, sizeof(*out));
   const lutkan_info &I = a->info;
   out->d = I.d; out->m = I.m; out->K = I.K; out->L = I.L;
-  out->scheme = I.scheme; out->boundary = I.boundary; out->oob = I.oob;
+  out->scheme = I.scheme; out->boundary = I.boundary; out->oob = I.oob; out->value_repr = I.value_repr;
   out->jt = I.jt; out->n_tiles = I.n_tiles; out->blob_bytes = I.blob_bytes;
   out->algo = LUTKAN_ALGO_AUTO;
   for (int k = 0; k <= I.K; ++k) out->knots[k] = a->knots[k];
@@ -271,7 +299,7 @@ extern "C" int bspline_dev_layer_init(const lutkan_artifact *a, bspline_dev_laye
   std::memset(out, 0, sizeof(*out));
   const lutkan_info &I = a->info;
   out->d = I.d; out->m = I.m; out->G = I.G; out->degree = I.degree;
-  out->boundary = I.boundary; out->oob = I.oob;
+  out->boundary = I.boundary; out->oob = I.oob; out->value_repr = I.value_repr;
   out->jt = I.jt; out->n_tiles = I.n_tiles; out->coef_blob_bytes = I.coef_blob_bytes;
   out->algo = LUTKAN_ALGO_AUTO;
   for (int r = 0; r < I.G + 2 * P + 1; ++r) out->ext_knots[r] = a->ext_knots[r];

@@ -15,21 +15,25 @@ namespace lutkan {
 int fail(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
 
 // Byte offsets inside one (tile, input) slice of the LUT device table:
-//   [params (K+1) rows of jt entries][codes (K*L+2) rows of jt bytes][zero pad to 16 B]
+//   [base jt f32 (spline_component only)][params (K+1) rows of jt entries][codes (K*L+2) rows of jt bytes][pad to 16 B]
 // A parameter entry is the fp32 alpha (symmetric) or the fp32 pair {alpha, y_min} (asymmetric).
 // Parameter row K and code rows K*L, K*L+1 are all zero: the kernels send masked inputs there.
 struct BlobLayout {
-  int32_t param_row_bytes, codes_off, bytes;
+  int32_t params_off, param_row_bytes, codes_off, bytes;
 };
 
-inline BlobLayout blob_layout(int K, int L, int jt, int scheme) {
+inline BlobLayout blob_layout(int K, int L, int jt, int scheme, int value_repr) {
   BlobLayout b;
+  b.params_off = (value_repr == LUTKAN_REPR_SPLINE_COMPONENT) ? jt * 4 : 0;
   b.param_row_bytes = jt * ((scheme == LUTKAN_ASYM_UINT8) ? 8 : 4);
-  b.codes_off = (K + 1) * b.param_row_bytes;
+  b.codes_off = b.params_off + (K + 1) * b.param_row_bytes;
   int raw = b.codes_off + (K * L + 2) * jt;
   b.bytes = (raw + 15) & ~15;
   return b;
 }
+
+// Rows of one (tile, input) slice of the B-spline device table: [base row (spline_component only)][R coefficient rows].
+inline int coef_slice_rows(int R, int value_repr) { return R + (value_repr == LUTKAN_REPR_SPLINE_COMPONENT ? 1 : 0); }
 
 // Largest table slice of the tiled kernels: two slice buffers plus the per-wave record buffers must fit the
 // 160 KiB of LDS of a gfx950 CU.
@@ -37,7 +41,7 @@ constexpr int kLdsSliceBudget = 56 * 1024;
 
 // Column-tile width for a layer: the widest of 128 / 64 / 32 columns whose slice fits the LDS budget (32 if
 // none does; such layers run on the gather kernel), and for narrow layers the next power of two >= m (>= 4).
-int choose_jt(int m, int K, int L, int scheme);
+int choose_jt(int m, int K, int L, int scheme, int value_repr);
 
 }  // namespace lutkan
 
@@ -48,6 +52,7 @@ struct lutkan_artifact {
   std::vector<uint8_t> q;         // canonical [E][K][L]
   std::vector<float> scale;       // [E][K]
   std::vector<float> ymin;        // [E][K]
+  std::vector<float> edge_base, edge_spline, edge_out;   // [E] each, empty for value_repr = phi
   std::vector<uint8_t> table;     // device LUT table, [t][i] slices
   std::vector<float> coef_table;  // device B-spline table, [t][i][R][jt]
 };

@@ -16,6 +16,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
+#include <type_traits>
 
 #include "lutkan_internal.h"
 
@@ -32,14 +33,12 @@ typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
 constexpr float kTwoTo24 = 16777216.0f;
 constexpr float kTwoToMinus24 = 1.0f / 16777216.0f;
-constexpr int kMaskedBit = (int)0x80000000u;   // index word: contribution is exactly zero (zero_spline, padding row)
-constexpr int kRowBits = 20;                   // index word: bits 0..19 = k*L + l0, bits 20..26 = k
 
 // A LUT lookup record, one per (input, row), stored [input][row]:
 //   x = byte offset of code row k*L+l0 inside the input's table slice   (the all-zero row K*L when masked)
 //   y = byte offset of parameter row k inside the slice                 (the all-zero row K when masked)
 //   z = interpolation weight w as fp32 bits                             (0 when masked, NaN for a NaN input)
-//   w = index word: k*L+l0, k and the masked flag, for the gather kernel and the trace
+//   w = SiLU(x) of the raw input as fp32 bits (value_repr = spline_component), else 0
 // The two offsets are what the tiled kernel adds to a lane's column offset; nothing else is computed per row.
 
 // ------------------------------------------------------------------------------------------------
@@ -51,7 +50,8 @@ struct LocateArgs {
   int64_t B, Bp;
   int32_t d, K, L;
   int32_t closed, zero_spline;
-  int32_t jt, codes_off, param_row_bytes;
+  int32_t jt, codes_off, params_off, param_row_bytes;
+  int32_t with_base;     // value_repr = spline_component: the record also carries SiLU(x)
   float tKs;             // safe upper clip value
   float knots[LUTKAN_MAX_K + 1];
   unsigned long long *stats;   // nullable: {oob_count, oob_any_rows}
@@ -109,7 +109,7 @@ __global__ __launch_bounds__(256) void lutkan_locate_kernel(const LocateArgs a) 
   __syncthreads();
   unsigned my_oob = 0;
   const unsigned zero_code_off = (unsigned)(a.codes_off + a.K * a.L * a.jt);
-  const unsigned zero_param_off = (unsigned)(a.K * a.param_row_bytes);
+  const unsigned zero_param_off = (unsigned)(a.params_off + a.K * a.param_row_bytes);
   for (int i0 = 0; i0 < a.d; i0 += kLocCols) {
     // phase 1: read x along inputs (coalesced), locate, park the record in LDS
     const int il = tid & (kLocCols - 1);
@@ -118,18 +118,18 @@ __global__ __launch_bounds__(256) void lutkan_locate_kernel(const LocateArgs a) 
     for (int p = 0; p < kLocRows / 4; ++p) {
       const int bl = p * 4 + (tid >> 6);
       const int64_t b = b0 + bl;
-      u32x4 rec = {zero_code_off, zero_param_off, 0u, (unsigned)kMaskedBit};
+      u32x4 rec = {zero_code_off, zero_param_off, 0u, 0u};
       if (b < a.B && i < a.d) {
         const float x = a.x[b * a.d + i];
         const Located o = locate_one(a, x);
         const bool masked = a.zero_spline && !o.inside && !o.is_nan;
-        const int row = o.k * a.L + o.l0;
-        rec.w = (unsigned)(row | (o.k << kRowBits) | (masked ? kMaskedBit : 0));
         if (!masked) {
-          rec.x = (unsigned)(a.codes_off + row * a.jt);
-          rec.y = (unsigned)(o.k * a.param_row_bytes);
+          rec.x = (unsigned)(a.codes_off + (o.k * a.L + o.l0) * a.jt);
+          rec.y = (unsigned)(a.params_off + o.k * a.param_row_bytes);
           rec.z = __float_as_uint(o.is_nan ? __builtin_nanf("") : o.w);
         }
+        // base branch b(x) = SiLU(x) = x / (1 + exp(-x)) at the RAW input (Eq. 2); it is never masked (Sec. 5.4)
+        if (a.with_base) rec.w = __float_as_uint(__fdiv_rn(x, 1.0f + expf(-x)));
         if (!o.inside) { ++my_oob; s_row_oob[bl] = 1; }
         if (a.k_out) {
           a.k_out[b * a.d + i] = o.k;
@@ -175,7 +175,9 @@ struct EdgeArgs {
   int64_t B, Bp;
   int32_t d, m, K, L;
   int32_t jt, n_tiles, blob_bytes;
-  int32_t codes_off, param_row_bytes;
+  int32_t codes_off, params_off, param_row_bytes;
+  int32_t with_base;       // value_repr = spline_component: slices start with a row of s_out*s_base, records carry SiLU(x)
+  const int32_t *k_out, *l0_out;   // code trace only: the located (k, l0) of every (row, input), [B][d]
   int32_t chunk;           // tiled kernels: inputs per work-group (blockIdx.y selects the chunk of inputs)
   int64_t split_stride;    // tiled kernels: floats between the partial outputs of consecutive chunks (0 if one chunk)
 };
@@ -197,8 +199,8 @@ __device__ __forceinline__ f16x2 bits_to_f16x2(unsigned v) {
 // two code rows and the parameter row are read as contiguous runs.  Inputs are taken four at a time: the four
 // records are independent loads, then the eight codes and four parameters, so the dependent-load latency is
 // paid once per four inputs.  Masked records point at the slice's zero rows (no branch).  With TRACE the two
-// gathered codes of every edge are also written out, taken from the index word so that masked edges report
-// the codes they would have used.
+// gathered codes of every edge are also written out, addressed by the traced (k, l0) so that masked edges
+// report the codes they would have used.
 template <int SCHEME, bool TRACE>
 __global__ __launch_bounds__(256) void lutkan_gather_kernel(const EdgeArgs a, const int jx_log2) {
   constexpr int U = 4;
@@ -220,7 +222,7 @@ __global__ __launch_bounds__(256) void lutkan_gather_kernel(const EdgeArgs a, co
       rec[u] = a.rec[(int64_t)i * a.Bp + b];
     }
     unsigned c0[U], c1[U];
-    float al[U], ym[U];
+    float al[U], ym[U], bg[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const unsigned char *slice = tile + (size_t)min(i0 + u, a.d - 1) * a.blob_bytes;
@@ -229,6 +231,7 @@ __global__ __launch_bounds__(256) void lutkan_gather_kernel(const EdgeArgs a, co
       const float *prm = reinterpret_cast<const float *>(slice + rec[u].y + poff);
       al[u] = prm[0];
       ym[u] = (SCHEME == LUTKAN_ASYM_UINT8) ? prm[1] : 0.0f;
+      bg[u] = a.with_base ? reinterpret_cast<const float *>(slice)[jj] : 0.0f;
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -238,11 +241,11 @@ __global__ __launch_bounds__(256) void lutkan_gather_kernel(const EdgeArgs a, co
         const float tq = fmaf(w, f1 - f0, f0);                             // interpolate the codes ...
         acc = fmaf(al[u], tq, acc);                                        // ... then one scale per edge
         if (SCHEME == LUTKAN_ASYM_UINT8) acc += ym[u];
+        if (a.with_base) acc = fmaf(bg[u], __uint_as_float(rec[u].w), acc);  // + s_out*s_base * SiLU(x)
         if (TRACE && a.q01_out) {
-          const int pk = (int)rec[u].w;
-          const int row = pk & ((1 << kRowBits) - 1);
-          const int k = (pk >> kRowBits) & 0x7f;
-          const int row1 = (row - k * a.L + 1 < a.L) ? row + 1 : row;      // l1 = min(l0+1, L-1)
+          const int l0 = a.l0_out[b * a.d + i0 + u];
+          const int row = a.k_out[b * a.d + i0 + u] * a.L + l0;
+          const int row1 = (l0 + 1 < a.L) ? row + 1 : row;                 // l1 = min(l0+1, L-1)
           const unsigned char *codes = tile + (size_t)(i0 + u) * a.blob_bytes + a.codes_off;
           int16_t *o = a.q01_out + ((b * a.d + i0 + u) * a.m + j) * 2;
           o[0] = (int16_t)code_to_float<SCHEME>(codes[(size_t)row * a.jt + jj]);
@@ -292,7 +295,9 @@ __device__ __forceinline__ void stage_slice(const u32x4 *gsrc, unsigned char *ld
 // all-zero code row K*L and the all-zero parameter row K that every slice carries, which makes its
 // contribution exactly zero.  l0+1 is read even when l0 = L-1: then w = 0 exactly and the neighbour (the
 // next segment's first row, or a zero row) does not change the result.
-template <int SCHEME, int LPR, int NP, int NW>
+// With BASE (value_repr = spline_component) every slice starts with a row of s_out*s_base; a lane loads its four
+// values once per input and adds base * SiLU(x) per row, SiLU(x) being the fourth word of the row's record.
+template <int SCHEME, int LPR, int NP, int NW, bool BASE>
 __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a) {
   extern __shared__ __align__(16) unsigned char lds[];
   constexpr int JT = 4 * LPR;
@@ -344,8 +349,11 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
     // step p+2 are issued before the arithmetic of step p, and they are issued right AFTER the one point per
     // step where the wave waits for its outstanding LDS reads (the first touch of step p's data): what the
     // wave waits for was issued a whole step earlier, what it issues now has a whole step to arrive.
+    typedef typename std::conditional<BASE, u32x4, u32x3>::type rec_t;        // 16-byte or 12-byte LDS read
+    f32x4 base_gain = {0.f, 0.f, 0.f, 0.f};
+    if (BASE) base_gain = *reinterpret_cast<const f32x4 *>(slice + sub * 16) * kTwoToMinus24;
     struct Fetched { unsigned c0, c1; f32x4 pa, pb; };
-    auto fetch = [&](const u32x3 &rc) {
+    auto fetch = [&](const rec_t &rc) {
       Fetched f;
       const unsigned char *cp = col_codes + rc.x;
       const unsigned char *pp = col_params + rc.y;
@@ -355,17 +363,17 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
       f.pb = (SCHEME == LUTKAN_ASYM_UINT8) ? *reinterpret_cast<const f32x4 *>(pp + 16) : f32x4{0.f, 0.f, 0.f, 0.f};
       return f;
     };
-    u32x3 rc_cur = *reinterpret_cast<const u32x3 *>(rec_buf);
-    u32x3 rc_nxt = *reinterpret_cast<const u32x3 *>(rec_buf + (NP > 1 ? RPS * 16 : 0));
+    rec_t rc_cur = *reinterpret_cast<const rec_t *>(rec_buf);
+    rec_t rc_nxt = *reinterpret_cast<const rec_t *>(rec_buf + (NP > 1 ? RPS * 16 : 0));
     Fetched f_cur = fetch(rc_cur);
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
       Fetched f_nxt = f_cur;
-      u32x3 rc_nn = rc_nxt;
+      rec_t rc_nn = rc_nxt;
       if (SCHEME == LUTKAN_ASYM_UINT8) asm volatile("" ::"v"(f_cur.pb));
       asm volatile("" ::"v"(f_cur.pa), "v"(f_cur.c1), "v"(rc_nxt.y));          // first touch of step p's data
       __builtin_amdgcn_sched_barrier(0);
-      if (p + 2 < NP) rc_nn = *reinterpret_cast<const u32x3 *>(rec_buf + (p + 2) * (RPS * 16));
+      if (p + 2 < NP) rc_nn = *reinterpret_cast<const rec_t *>(rec_buf + (p + 2) * (RPS * 16));
       if (p + 1 < NP) f_nxt = fetch(rc_nxt);
       __builtin_amdgcn_sched_barrier(0);
       const float w = __uint_as_float(rc_cur.z);
@@ -400,6 +408,13 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
 #pragma unroll
         for (int c = 0; c < 4; ++c) acc[p][c] = fmaf(ym[c], kTwoToMinus24, acc[p][c]);
       }
+      if constexpr (BASE) {
+        const float silu_x = __uint_as_float(rc_cur.w);
+        acc[p][0] = fmaf(base_gain.x, silu_x, acc[p][0]);
+        acc[p][1] = fmaf(base_gain.y, silu_x, acc[p][1]);
+        acc[p][2] = fmaf(base_gain.z, silu_x, acc[p][2]);
+        acc[p][3] = fmaf(base_gain.w, silu_x, acc[p][3]);
+      }
       __builtin_amdgcn_sched_barrier(0);
       rc_cur = rc_nxt;
       rc_nxt = rc_nn;
@@ -431,14 +446,15 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
 // B-spline baseline (Sec. 3.2-3.3).
 // ------------------------------------------------------------------------------------------------
 // A B-spline record is 32 bytes per (input, row), stored [input][row] as two 16-byte halves:
-//   {byte offset of coefficient row k inside the input's coefficient slice, N0, N1, N2}, {N3, 0, 0, 0}
-// where N0..N3 are the four non-zero cubic basis values (all 0 when masked, NaN for a NaN input).
+//   {byte offset of coefficient row k inside the input's coefficient slice, N0, N1, N2}, {N3, SiLU(x), 0, 0}
+// where N0..N3 are the four non-zero cubic basis values (all 0 when masked, NaN for a NaN input) and SiLU(x) of
+// the raw input is present for value_repr = spline_component (else 0).
 struct SplineLocateArgs {
   const float *x;
   u32x4 *rec;            // [d][Bp][2]
   int64_t B, Bp;
   int32_t d, G, jt;
-  int32_t closed, zero_spline;
+  int32_t closed, zero_spline, with_base;
   float tKs;
   float ext_knots[LUTKAN_MAX_K + 7];
 };
@@ -461,9 +477,10 @@ __global__ __launch_bounds__(256) void bspline_locate_kernel(const SplineLocateA
       const int bl = p * 8 + (tid >> 5);
       const int64_t b = b0 + bl;
       int k = 0;
-      float n0 = 0.f, n1 = 0.f, n2 = 0.f, n3 = 0.f;
+      float n0 = 0.f, n1 = 0.f, n2 = 0.f, n3 = 0.f, base = 0.f;
       if (b < a.B && i < a.d) {
         const float x = a.x[b * a.d + i];
+        if (a.with_base) base = __fdiv_rn(x, 1.0f + expf(-x));             // SiLU at the raw input, never masked
         const bool is_nan = (x != x);
         const bool inside = a.closed ? (x >= t0 && x <= tK) : (x >= t0 && x < tK);
         float xc = is_nan ? t0 : x;
@@ -490,8 +507,8 @@ __global__ __launch_bounds__(256) void bspline_locate_kernel(const SplineLocateA
         const float gate = is_nan ? __builtin_nanf("") : (masked ? 0.0f : 1.0f);
         n0 = lower[0] * gate; n1 = lower[1] * gate; n2 = lower[2] * gate; n3 = lower[3] * gate;
       }
-      s_rec[0][il][bl] = u32x4{(unsigned)(k * a.jt * 4), __float_as_uint(n0), __float_as_uint(n1), __float_as_uint(n2)};
-      s_rec[1][il][bl] = u32x4{__float_as_uint(n3), 0u, 0u, 0u};
+      s_rec[0][il][bl] = u32x4{(unsigned)((k + a.with_base) * a.jt * 4), __float_as_uint(n0), __float_as_uint(n1), __float_as_uint(n2)};
+      s_rec[1][il][bl] = u32x4{__float_as_uint(n3), __float_as_uint(base), 0u, 0u};
     }
     __syncthreads();
     const int bl2 = tid & (kLocRows - 1);
@@ -510,11 +527,12 @@ __global__ __launch_bounds__(256) void bspline_locate_kernel(const SplineLocateA
 }
 
 struct SplineEdgeArgs {
-  const float *coef_table;   // [t][i][R][jt]
+  const float *coef_table;   // [t][i][rows][jt]
   const u32x4 *rec;          // [d][Bp][2]
   float *y;
   int64_t B, Bp;
-  int32_t d, m, R;
+  int32_t d, m, rows;        // rows of a coefficient slice: R, plus the leading s_out*s_base row with spline_component
+  int32_t with_base;
   int32_t jt, n_tiles;
   int32_t chunk;
   int64_t split_stride;
@@ -529,23 +547,24 @@ __global__ __launch_bounds__(256) void bspline_gather_kernel(const SplineEdgeArg
   const int64_t b = (int64_t)blockIdx.x * (256 >> jx_log2) + ty;
   if (j >= a.m || b >= a.B) return;
   const int t = j / a.jt, jj = j - t * a.jt;
-  const float *tile = a.coef_table + (size_t)t * a.d * a.R * a.jt;
+  const float *tile = a.coef_table + (size_t)t * a.d * a.rows * a.jt;
   float acc = 0.0f;
   for (int i0 = 0; i0 < a.d; i0 += U) {
-    u32x4 r0[U];
-    float n3[U];
+    u32x4 r0[U], r1[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int64_t o = ((int64_t)min(i0 + u, a.d - 1) * a.Bp + b) * 2;
       r0[u] = a.rec[o];
-      n3[u] = __uint_as_float(a.rec[o + 1].x);
+      r1[u] = a.rec[o + 1];
     }
-    float cf[U][4];
+    float cf[U][4], bg[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const float *c = tile + (size_t)min(i0 + u, a.d - 1) * a.R * a.jt + (r0[u].x >> 2) + jj;
+      const float *sl = tile + (size_t)min(i0 + u, a.d - 1) * a.rows * a.jt;
+      const float *c = sl + (r0[u].x >> 2) + jj;
 #pragma unroll
       for (int q = 0; q < 4; ++q) cf[u][q] = c[q * a.jt];
+      bg[u] = a.with_base ? sl[jj] : 0.0f;
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -553,7 +572,8 @@ __global__ __launch_bounds__(256) void bspline_gather_kernel(const SplineEdgeArg
         acc = fmaf(__uint_as_float(r0[u].y), cf[u][0], acc);
         acc = fmaf(__uint_as_float(r0[u].z), cf[u][1], acc);
         acc = fmaf(__uint_as_float(r0[u].w), cf[u][2], acc);
-        acc = fmaf(n3[u], cf[u][3], acc);
+        acc = fmaf(__uint_as_float(r1[u].x), cf[u][3], acc);
+        if (a.with_base) acc = fmaf(bg[u], __uint_as_float(r1[u].y), acc);
       }
     }
   }
@@ -563,7 +583,7 @@ __global__ __launch_bounds__(256) void bspline_gather_kernel(const SplineEdgeArg
 // Tiled B-spline kernel: same ownership and streaming as the LUT tiled kernel; the staged slice is the input's
 // coefficient matrix c[R][JT]; per row four contiguous coefficient runs (rows k..k+3) are read and weighted by
 // the row's four basis values.
-template <int LPR, int NP, int NW>
+template <int LPR, int NP, int NW, bool BASE>
 __global__ __launch_bounds__(NW * 64) void bspline_tiled_kernel(const SplineEdgeArgs a) {
   extern __shared__ __align__(16) unsigned char lds[];
   constexpr int JT = 4 * LPR;
@@ -578,7 +598,7 @@ __global__ __launch_bounds__(NW * 64) void bspline_tiled_kernel(const SplineEdge
   const int t = blockIdx.x % a.n_tiles;
   const int64_t rt = blockIdx.x / a.n_tiles;
   const int64_t b0 = rt * (NW * RW) + (int64_t)wave * RW;
-  const int blob_bytes = a.R * JT * 4;
+  const int blob_bytes = a.rows * JT * 4;
   const int nvec = blob_bytes >> 4;
 
   float acc[NP][4];
@@ -587,7 +607,7 @@ __global__ __launch_bounds__(NW * 64) void bspline_tiled_kernel(const SplineEdge
 #pragma unroll
     for (int c = 0; c < 4; ++c) acc[p][c] = 0.0f;
 
-  const u32x4 *src = reinterpret_cast<const u32x4 *>(a.coef_table + (size_t)t * a.d * a.R * JT);
+  const u32x4 *src = reinterpret_cast<const u32x4 *>(a.coef_table + (size_t)t * a.d * a.rows * JT);
   // a wave's RW 32-byte records are 2*RW consecutive 16-byte vectors: lanes 0..63 take the first 64, then the rest
   const u32x4 *rec_src = a.rec + b0 * 2;
   unsigned char *rec_area = lds + 2 * blob_bytes + wave * (2 * RW * 32);
@@ -616,12 +636,21 @@ __global__ __launch_bounds__(NW * 64) void bspline_tiled_kernel(const SplineEdge
     const unsigned char *col_coef = lds + cur * blob_bytes + sub * 16;
     // Same software pipeline as the LUT kernel: wait once per step, then issue the coefficient reads of step
     // p+1 and the record of step p+2, then do the arithmetic of step p.
-    struct Rec { u32x4 a; float n3; };
+    struct Rec { u32x4 a; float n3, base; };
     struct Coefs { f32x4 c[4]; };
+    f32x4 base_gain = {0.f, 0.f, 0.f, 0.f};
+    if (BASE) base_gain = *reinterpret_cast<const f32x4 *>(col_coef);        // row 0 of the slice: s_out*s_base
     auto read_rec = [&](int p) {
       Rec r;
       r.a = *reinterpret_cast<const u32x4 *>(rec_buf + p * (RPS * 32));
-      r.n3 = *reinterpret_cast<const float *>(rec_buf + p * (RPS * 32) + 16);
+      if (BASE) {
+        const f32x2 t2 = *reinterpret_cast<const f32x2 *>(rec_buf + p * (RPS * 32) + 16);
+        r.n3 = t2.x;
+        r.base = t2.y;
+      } else {
+        r.n3 = *reinterpret_cast<const float *>(rec_buf + p * (RPS * 32) + 16);
+        r.base = 0.0f;
+      }
       return r;
     };
     auto fetch = [&](const Rec &r) {
@@ -650,6 +679,12 @@ __global__ __launch_bounds__(NW * 64) void bspline_tiled_kernel(const SplineEdge
         acc[p][1] = fmaf(n[q], f_cur.c[q].y, acc[p][1]);
         acc[p][2] = fmaf(n[q], f_cur.c[q].z, acc[p][2]);
         acc[p][3] = fmaf(n[q], f_cur.c[q].w, acc[p][3]);
+      }
+      if constexpr (BASE) {
+        acc[p][0] = fmaf(base_gain.x, rc_cur.base, acc[p][0]);
+        acc[p][1] = fmaf(base_gain.y, rc_cur.base, acc[p][1]);
+        acc[p][2] = fmaf(base_gain.z, rc_cur.base, acc[p][2]);
+        acc[p][3] = fmaf(base_gain.w, rc_cur.base, acc[p][3]);
       }
       __builtin_amdgcn_sched_barrier(0);
       rc_cur = rc_nxt;
@@ -718,11 +753,12 @@ int validate_layer(const lutkan_dev_layer *l, const char *who) {
   if (l->boundary != LUTKAN_HALF_OPEN && l->boundary != LUTKAN_CLOSED) return fail(LUTKAN_EINVAL, "%s: bad boundary_mode %d", who, l->boundary);
   if (l->oob != LUTKAN_CLIP_X && l->oob != LUTKAN_ZERO_SPLINE) return fail(LUTKAN_EINVAL, "%s: bad oob_policy %d", who, l->oob);
   if (l->algo < LUTKAN_ALGO_AUTO || l->algo > LUTKAN_ALGO_TILED) return fail(LUTKAN_EINVAL, "%s: bad algo %d", who, l->algo);
+  if (l->value_repr != LUTKAN_REPR_PHI && l->value_repr != LUTKAN_REPR_SPLINE_COMPONENT) return fail(LUTKAN_EINVAL, "%s: bad value_repr %d", who, l->value_repr);
   for (int k = 0; k < l->K; ++k)
     if (!(l->knots[k] < l->knots[k + 1])) return fail(LUTKAN_EINVAL, "%s: knots not strictly increasing at %d", who, k);
   if (l->jt < 4 || l->jt > 128 || (l->jt & (l->jt - 1))) return fail(LUTKAN_EINVAL, "%s: jt=%d is not a power of two in [4,128]", who, l->jt);
   if (l->n_tiles != (l->m + l->jt - 1) / l->jt) return fail(LUTKAN_ESHAPE, "%s: n_tiles does not match m and jt", who);
-  if (l->blob_bytes != lutkan::blob_layout(l->K, l->L, l->jt, l->scheme).bytes) return fail(LUTKAN_ESHAPE, "%s: blob_bytes does not match K, L, jt, scheme", who);
+  if (l->blob_bytes != lutkan::blob_layout(l->K, l->L, l->jt, l->scheme, l->value_repr).bytes) return fail(LUTKAN_ESHAPE, "%s: blob_bytes does not match K, L, jt, scheme", who);
   if ((reinterpret_cast<uintptr_t>(l->table) & 15) != 0) return fail(LUTKAN_EINVAL, "%s: table must be 16-byte aligned", who);
   return LUTKAN_OK;
 }
@@ -777,8 +813,9 @@ int launch_tiled_np(const EdgeArgs &ea, hipStream_t s) {
   const int64_t row_tiles = (ea.B + NW * RW - 1) / (NW * RW);
   const dim3 grid((unsigned)(row_tiles * ea.n_tiles), (unsigned)((ea.d + ea.chunk - 1) / ea.chunk));
   const size_t lds = 2 * (size_t)ea.blob_bytes + (size_t)NW * 2 * RW * 16;
-  static bool raised = false;
-  return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW>, &raised, grid, lds, s, ea, "lutkan_tiled_kernel");
+  static bool raised = false, raised_base = false;
+  if (ea.with_base) return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, true>, &raised_base, grid, lds, s, ea, "lutkan_tiled_kernel");
+  return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, false>, &raised, grid, lds, s, ea, "lutkan_tiled_kernel");
 }
 
 template <int SCHEME, int LPR>
@@ -823,7 +860,7 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   if ((reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return fail(LUTKAN_EINVAL, "%s: workspace must be 256-byte aligned", who);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const int64_t Bp = padded_rows(B);
-  const lutkan::BlobLayout lay = lutkan::blob_layout(l->K, l->L, l->jt, l->scheme);
+  const lutkan::BlobLayout lay = lutkan::blob_layout(l->K, l->L, l->jt, l->scheme, l->value_repr);
 
   LocateArgs la;
   la.x = x;
@@ -831,7 +868,8 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   la.B = B; la.Bp = Bp; la.d = l->d; la.K = l->K; la.L = l->L;
   la.closed = (l->boundary == LUTKAN_CLOSED);
   la.zero_spline = (l->oob == LUTKAN_ZERO_SPLINE);
-  la.jt = l->jt; la.codes_off = lay.codes_off; la.param_row_bytes = lay.param_row_bytes;
+  la.jt = l->jt; la.codes_off = lay.codes_off; la.params_off = lay.params_off; la.param_row_bytes = lay.param_row_bytes;
+  la.with_base = (l->value_repr == LUTKAN_REPR_SPLINE_COMPONENT);
   la.tKs = la.closed ? l->knots[l->K] : std::nextafterf(l->knots[l->K], -INFINITY);
   for (int k = 0; k <= l->K; ++k) la.knots[k] = l->knots[k];
   la.stats = reinterpret_cast<unsigned long long *>(stats);
@@ -847,7 +885,8 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   ea.rec = la.rec; ea.y = y; ea.q01_out = q01_out;
   ea.B = B; ea.Bp = Bp; ea.d = l->d; ea.m = l->m; ea.K = l->K; ea.L = l->L;
   ea.jt = l->jt; ea.n_tiles = l->n_tiles; ea.blob_bytes = l->blob_bytes;
-  ea.codes_off = lay.codes_off; ea.param_row_bytes = lay.param_row_bytes;
+  ea.codes_off = lay.codes_off; ea.params_off = lay.params_off; ea.param_row_bytes = lay.param_row_bytes;
+  ea.with_base = la.with_base; ea.k_out = k_out; ea.l0_out = l0_out;
 
   bool tiled = tiled_supported(l->jt, l->blob_bytes) && !q01_out;
   if (l->algo == LUTKAN_ALGO_GATHER) tiled = false;
@@ -882,12 +921,13 @@ template <int LPR, int NP>
 int launch_spline_tiled_np(const SplineEdgeArgs &ea, hipStream_t s) {
   constexpr int NW = kTileWaves;
   constexpr int RW = (64 / LPR) * NP;
-  const int bytes = ea.R * 4 * LPR * 4;
+  const int bytes = ea.rows * 4 * LPR * 4;
   const int64_t row_tiles = (ea.B + NW * RW - 1) / (NW * RW);
   const dim3 grid((unsigned)(row_tiles * ea.n_tiles), (unsigned)((ea.d + ea.chunk - 1) / ea.chunk));
   const size_t lds = 2 * (size_t)bytes + (size_t)NW * 2 * RW * 32;
-  static bool raised = false;
-  return launch_with_lds(bspline_tiled_kernel<LPR, NP, NW>, &raised, grid, lds, s, ea, "bspline_tiled_kernel");
+  static bool raised = false, raised_base = false;
+  if (ea.with_base) return launch_with_lds(bspline_tiled_kernel<LPR, NP, NW, true>, &raised_base, grid, lds, s, ea, "bspline_tiled_kernel");
+  return launch_with_lds(bspline_tiled_kernel<LPR, NP, NW, false>, &raised, grid, lds, s, ea, "bspline_tiled_kernel");
 }
 
 template <int LPR>
@@ -920,6 +960,7 @@ int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y
   if (l->boundary != LUTKAN_HALF_OPEN && l->boundary != LUTKAN_CLOSED) return fail(LUTKAN_EINVAL, "%s: bad boundary_mode", who);
   if (l->oob != LUTKAN_CLIP_X && l->oob != LUTKAN_ZERO_SPLINE) return fail(LUTKAN_EINVAL, "%s: bad oob_policy", who);
   if (l->algo < LUTKAN_ALGO_AUTO || l->algo > LUTKAN_ALGO_TILED) return fail(LUTKAN_EINVAL, "%s: bad algo", who);
+  if (l->value_repr != LUTKAN_REPR_PHI && l->value_repr != LUTKAN_REPR_SPLINE_COMPONENT) return fail(LUTKAN_EINVAL, "%s: bad value_repr", who);
   for (int r = 0; r < l->G + 6; ++r)
     if (!(l->ext_knots[r] < l->ext_knots[r + 1])) return fail(LUTKAN_EINVAL, "%s: knots not strictly increasing at %d", who, r);
   if (l->jt < 4 || l->jt > 128 || (l->jt & (l->jt - 1))) return fail(LUTKAN_EINVAL, "%s: bad jt", who);
@@ -939,6 +980,7 @@ int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y
   la.x = x;
   la.rec = static_cast<u32x4 *>(workspace);
   la.B = B; la.Bp = Bp; la.d = l->d; la.G = G; la.jt = l->jt;
+  la.with_base = (l->value_repr == LUTKAN_REPR_SPLINE_COMPONENT);
   la.closed = (l->boundary == LUTKAN_CLOSED);
   la.zero_spline = (l->oob == LUTKAN_ZERO_SPLINE);
   la.tKs = la.closed ? l->ext_knots[3 + G] : std::nextafterf(l->ext_knots[3 + G], -INFINITY);
@@ -951,7 +993,8 @@ int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y
 
   SplineEdgeArgs ea;
   ea.coef_table = l->coef_table; ea.rec = la.rec; ea.y = y;
-  ea.B = B; ea.Bp = Bp; ea.d = l->d; ea.m = l->m; ea.R = G + 3; ea.jt = l->jt; ea.n_tiles = l->n_tiles;
+  ea.B = B; ea.Bp = Bp; ea.d = l->d; ea.m = l->m; ea.rows = lutkan::coef_slice_rows(G + 3, l->value_repr);
+  ea.with_base = la.with_base; ea.jt = l->jt; ea.n_tiles = l->n_tiles;
   bool tiled = true;                                   // a coefficient slice always fits LDS (R <= 67)
   if (l->algo == LUTKAN_ALGO_GATHER) tiled = false;
   if (l->algo == LUTKAN_ALGO_TILED && !tiled) return fail(LUTKAN_EUNSUPPORTED, "%s: tiled kernel unavailable", who);

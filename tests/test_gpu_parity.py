@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 
 import oracle
-from lutkan_inputs import (ASYM_UINT8, CLIP_X, CLOSED, HALF_OPEN, SYM_INT8, ZERO_SPLINE, cfg1, cfg2, cfg3, cfg4,
+from lutkan_inputs import (ASYM_UINT8, CLIP_X, CLOSED, HALF_OPEN, SYM_INT8, ZERO_SPLINE, case_a, cfg1, cfg2, cfg3, cfg4,
                            cfg5, random_layer)
 
 pytestmark = pytest.mark.gpu
@@ -30,11 +30,13 @@ _COMPILED = {}
 def _compile_both(s):
     """Library artifact + oracle artifact for a layer spec; the codes must already agree bit for bit.
     Cached per table content (the contract fields do not change the tables)."""
-    key = (s.d, s.m, s.G, s.L, s.scheme, hash(s.coef.tobytes()), hash(s.ext_knots.tobytes()))
+    key = (s.d, s.m, s.G, s.L, s.scheme, hash(s.coef.tobytes()), hash(s.ext_knots.tobytes()),
+           None if s.edge_scales is None else hash(b"".join(a.tobytes() for a in s.edge_scales)))
     if key not in _COMPILED:
         if len(_COMPILED) > 4:
             _COMPILED.clear()
-        art = lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, s.boundary, s.oob)
+        art = lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, s.boundary, s.oob,
+                                edge_scales=s.edge_scales)
         ora = oracle.compile_layer(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme)
         assert np.array_equal(art.q, ora.q) and np.array_equal(art.scale, ora.scale) and np.array_equal(art.y_min, ora.y_min)
         _COMPILED[key] = (art, ora)
@@ -65,7 +67,7 @@ def _check_layer(s, x, algo, codes=False, what=""):
     stats = torch.zeros(2, dtype=torch.int64, device=DEV)
     y2 = lk.lutkan_forward(layer, xg, stats=stats)
     torch.cuda.synchronize()
-    ref = oracle.lut_forward(ora, s.boundary, s.oob, x, trace=True, codes=codes)
+    ref = oracle.lut_forward(ora, s.boundary, s.oob, x, trace=True, codes=codes, edge_scalars=s.edge_scales)
     np.testing.assert_array_equal(k.cpu().numpy(), ref.k)
     np.testing.assert_array_equal(l0.cpu().numpy(), ref.l0)
     np.testing.assert_array_equal(inside.cpu().numpy(), ref.inside)
@@ -257,12 +259,13 @@ def test_cfg4_wide_layer_full_size_sampled_rows(B):
 
 # ---------------------------------------------------------------- B-spline baseline
 def _check_bspline(s, x, algo, what):
-    art = lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, s.boundary, s.oob)
+    art = lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, s.boundary, s.oob,
+                            edge_scales=s.edge_scales)
     layer = art.bspline_to_device(DEV, algo)
     _say(f"case bspline {what} d={s.d} m={s.m} G={s.G} boundary={s.boundary} oob={s.oob} B={x.shape[0]} algo={algo}")
     y = lk.bspline_kan_forward(layer, torch.from_numpy(x).to(DEV))
     torch.cuda.synchronize()
-    ref = oracle.bspline_forward(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.boundary, s.oob, x)
+    ref = oracle.bspline_forward(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.boundary, s.oob, x, edge_scalars=s.edge_scales)
     _assert_close(y.cpu().numpy(), ref, "bspline " + what)
 
 
@@ -298,3 +301,46 @@ def test_bspline_cfg4_sampled_rows():
     rows = np.arange(0, 4096, 64)
     ref = oracle.bspline_forward(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.boundary, s.oob, w.x[rows])
     _assert_close(y[torch.from_numpy(rows).to(DEV)].cpu().numpy(), ref, "bspline cfg4")
+
+
+# ---------------------------------------------------------------- value_repr = spline_component (Eq. 2, Sec. 4.3 B)
+SC_CASES = [
+    # seed, d, m, G, L, scheme, boundary, oob, B
+    (501, 1, 1, 4, 16, SYM_INT8, CLOSED, CLIP_X, 50),
+    (502, 10, 8, 8, 64, SYM_INT8, HALF_OPEN, ZERO_SPLINE, 1024),
+    (503, 7, 3, 5, 32, ASYM_UINT8, CLOSED, ZERO_SPLINE, 333),
+    (504, 40, 70, 6, 16, ASYM_UINT8, HALF_OPEN, CLIP_X, 2100),
+    (505, 64, 256, 8, 64, SYM_INT8, CLOSED, ZERO_SPLINE, 5000),
+    (506, 33, 130, 10, 64, ASYM_UINT8, HALF_OPEN, ZERO_SPLINE, 1025),
+]
+
+
+@pytest.mark.parametrize("case", SC_CASES, ids=lambda c: f"seed{c[0]}")
+def test_spline_component_layers(case):
+    seed, d, m, G, L, scheme, boundary, oob, B = case
+    w = random_layer(seed, d, m, G, L, scheme, boundary, oob, B, uniform=(seed % 2 == 0), oob_frac=0.5, with_base=True)
+    s = w.layers[0]
+    _check_layer(s, w.x, lk.ALGO_GATHER, codes=(B * d * m <= 2_000_000), what=w.name)
+    _check_layer(s, w.x, lk.ALGO_TILED, what=w.name)
+    _check_bspline(s, w.x, lk.ALGO_GATHER, w.name)
+    _check_bspline(s, w.x, lk.ALGO_TILED, w.name)
+
+
+@pytest.mark.parametrize("boundary,oob", [(HALF_OPEN, CLIP_X), (HALF_OPEN, ZERO_SPLINE), (CLOSED, CLIP_X), (CLOSED, ZERO_SPLINE)])
+def test_case_a_sweep_shape_spline_component(boundary, oob):
+    """The paper's controlled-sweep layer (10->8, grid 8, spline_component) with inputs clipped onto the domain."""
+    for L, scheme in ((16, ASYM_UINT8), (64, SYM_INT8), (128, ASYM_UINT8)):
+        w = case_a(seed=1, L=L, scheme=scheme, boundary=boundary, oob=oob)
+        _check_layer(w.layers[0], w.x, lk.ALGO_AUTO, codes=True, what=w.name)
+
+
+def test_spline_component_special_inputs():
+    w = random_layer(507, 6, 140, 5, 32, SYM_INT8, HALF_OPEN, ZERO_SPLINE, 40, with_base=True)
+    x = w.x.copy()
+    x[3, 2] = np.nan
+    x[5, :] = 80.0          # SiLU(x) ~ x, exp(-x) underflows
+    x[6, :] = -120.0        # exp(-x) overflows to inf: SiLU -> -0
+    x[7, :] = np.inf
+    s = w.layers[0]
+    for algo in (lk.ALGO_GATHER, lk.ALGO_TILED):
+        _check_layer(s, x[:7], algo, what="sc special")

@@ -124,7 +124,7 @@ def test_compile_rejects_bad_arguments_with_error_codes():
         tau = np.ascontiguousarray(a["ext_knots"], dtype=np.float32)
         cf = np.ascontiguousarray(a["coef"], dtype=np.float32)
         desc = binding._LayerDesc(a["d"], a["m"], a["G"], a["degree"], tau.ctypes.data, cf.ctypes.data, a["L"],
-                                  a["scheme"], a["boundary"], a["oob"])
+                                  a["scheme"], a["boundary"], a["oob"], a.get("value_repr", 0), None, None, None)
         out = C.c_void_p()
         code = lib.lutkan_compile(C.byref(desc), 1, C.byref(out))
         if code == 0:
@@ -135,6 +135,9 @@ def test_compile_rejects_bad_arguments_with_error_codes():
     assert rc(L=1) == (-1, "lutkan_compile: L must be >= 2 (got 1)")
     assert rc(degree=2)[0] == -5
     assert rc(scheme=2)[0] == -1 and rc(boundary=-1)[0] == -1 and rc(oob=9)[0] == -1
+    assert rc(value_repr=2)[0] == -1
+    code, msg = rc(value_repr=1)                       # spline_component without its three per-edge arrays
+    assert code == -1 and "edge_base_scale" in msg
     bad = s.ext_knots.copy()
     bad[4] = bad[3]
     code, msg = rc(ext_knots=bad)
@@ -170,3 +173,37 @@ def test_forward_argument_validation_happens_before_any_launch():
     assert lib.lutkan_forward(C.byref(dl), 16, 4, 32, None, 256, 1 << 20, None) == -1
     two = (binding._DevLayer * 2)(dl, dl)
     assert lib.lutkan_model_forward(two, 2, 16, 4, 32, None, 256, 1 << 20, None) == -2     # m of layer 0 != d of layer 1
+
+
+def test_spline_component_tables_carry_the_base_row_and_folded_gains():
+    w = random_layer(77, 3, 70, 5, 16, ASYM_UINT8, CLOSED, ZERO_SPLINE, 4, with_base=True)
+    s = w.layers[0]
+    art = lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, s.boundary, s.oob, edge_scales=s.edge_scales)
+    ora = oracle.compile_layer(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme)
+    np.testing.assert_array_equal(art.q, ora.q)                        # the table still stores the spline branch
+    np.testing.assert_array_equal(art.scale, ora.scale)
+    sb, ss, so = (a.reshape(-1) for a in s.edge_scales)
+    for got, want in zip(art.edge_scales, (sb, ss, so)):
+        np.testing.assert_array_equal(got, want)
+    I = art.info
+    assert I.value_repr == lk.REPR_SPLINE_COMPONENT
+    K, L, jt, nt = I.K, I.L, I.jt, I.n_tiles
+    params_off = jt * 4
+    codes_off = params_off + (K + 1) * jt * 8
+    assert I.blob_bytes == (codes_off + (K * L + 2) * jt + 15) // 16 * 16
+    assert I.artifact_bytes == oracle.artifact_bytes(s.d * s.m, K, L, 8) + 12 * s.d * s.m
+    tab = art.table.reshape(nt, s.d, I.blob_bytes)
+    ctab = art.coef_table.reshape(nt, s.d, s.G + 4, jt)
+    for t in range(nt):
+        cols = np.arange(t * jt, min(s.m, (t + 1) * jt))
+        n = cols.size
+        for i in range(s.d):
+            e = i * s.m + cols
+            base = tab[t, i, :params_off].view(np.float32)
+            np.testing.assert_array_equal(base[:n], so[e] * sb[e])
+            np.testing.assert_array_equal(ctab[t, i, 0, :n], so[e] * sb[e])
+            prm = tab[t, i, params_off:codes_off].view(np.float32).reshape(K + 1, jt, 2)
+            gain = (so[e] * ss[e]).astype(np.float32)
+            np.testing.assert_array_equal(prm[:K, :n, 0], (gain[None, :] * art.scale[e].T).astype(np.float32))
+            np.testing.assert_array_equal(prm[:K, :n, 1], (gain[None, :] * art.y_min[e].T).astype(np.float32))
+            np.testing.assert_array_equal(ctab[t, i, 1:, :n], (gain[None, :] * s.coef[i, cols].T).astype(np.float32))
