@@ -248,6 +248,30 @@ def _sampled_rows_check(w, n_rows, what, seed=0):
     assert int(st[0]) == int((~inside).sum()) and int(st[1]) == int((~inside).any(axis=1).sum())
 
 
+def test_cfg5_full_batch_chain_sampled_rows():
+    """cfg5 at its full batch (131072 rows, the launch shapes a user gets): every layer against the oracle on a
+    sample of rows, fed with the GPU's own activations of the previous layer."""
+    w = cfg5(boundary=HALF_OPEN, oob=ZERO_SPLINE)
+    B = w.x.shape[0]
+    rows = np.unique(np.random.Generator(np.random.PCG64(9)).integers(0, B, size=3000))
+    rows_t = torch.from_numpy(rows).to(DEV)
+    layers, oras = [], []
+    for s in w.layers:
+        art, ora = _compile_both(s)
+        layers.append(_device_layer(art, s))
+        oras.append(ora)
+    cur = torch.from_numpy(w.x).to(DEV)
+    stats = torch.zeros((len(layers), 2), dtype=torch.int64, device=DEV)
+    y_model = lk.lutkan_model_forward(layers, cur, stats=stats)
+    for li, (s, layer, ora) in enumerate(zip(w.layers, layers, oras)):
+        _say(f"case cfg5 full batch layer {li}: {s.d}->{s.m} B={B}")
+        nxt = lk.lutkan_forward(layer, cur)
+        ref = oracle.lut_forward(ora, s.boundary, s.oob, cur[rows_t].cpu().numpy())
+        _assert_close(nxt[rows_t].cpu().numpy(), ref, f"cfg5 full layer {li}")
+        cur = nxt
+    assert torch.equal(cur, y_model)
+
+
 def test_cfg3_full_batch_sampled_rows():
     _sampled_rows_check(cfg3(L=64, scheme=SYM_INT8), 512, "cfg3 L64 sym")
 
