@@ -43,7 +43,7 @@ typedef enum { LUTKAN_ALGO_AUTO = 0, LUTKAN_ALGO_GATHER = 1, LUTKAN_ALGO_TILED =
 typedef enum { LUTKAN_REPR_PHI = 0, LUTKAN_REPR_SPLINE_COMPONENT = 1 } lutkan_value_repr;  /* Sec. 4.3 A / B */
 
 #define LUTKAN_MAX_K 64            /* segments per layer (the knot vector travels in the kernel arguments) */
-#define LUTKAN_MAX_ROWS 65536      /* K * L, table rows per input */
+#define LUTKAN_MAX_ROWS 65535      /* K * L, table rows per input (a row index travels in 16 bits) */
 #define LUTKAN_MAX_LAYERS 16
 
 const char *lutkan_last_error(void);

@@ -3,7 +3,7 @@
 // Work split (Sec. 4.5, Sec. 5):
 //   1. locate kernel   per (row, input): domain test on the raw x (Sec. 5.2), safe clip (Eq. 13), segment
 //                      (Eq. 14), local coordinate (Eq. 15), (l0, w) (Eq. 16), all in IEEE fp32 with one
-//                      rounding per operation, written as a 16-byte "record" [input][row] so that it is
+//                      rounding per operation, written as an 8-byte "record" [input][row] so that it is
 //                      computed once and reused by all m outputs.
 //   2. edge kernel     per (row, output): for every input gather the two adjacent codes, dequantise (Eq. 10),
 //                      interpolate (Eq. 17), apply the oob_policy (Sec. 5.4) and accumulate (Eq. 1).
@@ -27,6 +27,7 @@ namespace {
 constexpr int kWave = 64;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte load/store
 typedef unsigned int u32x3 __attribute__((ext_vector_type(3)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
@@ -34,24 +35,23 @@ typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 constexpr float kTwoTo24 = 16777216.0f;
 constexpr float kTwoToMinus24 = 1.0f / 16777216.0f;
 
-// A LUT lookup record, one per (input, row), stored [input][row]:
-//   x = byte offset of code row k*L+l0 inside the input's table slice   (the all-zero row K*L when masked)
-//   y = byte offset of parameter row k inside the slice                 (the all-zero row K when masked)
-//   z = interpolation weight w as fp32 bits                             (0 when masked, NaN for a NaN input)
-//   w = SiLU(x) of the raw input as fp32 bits (value_repr = spline_component), else 0
-// The two offsets are what the tiled kernel adds to a lane's column offset; nothing else is computed per row.
+// A LUT lookup record, one per (input, row), stored [input][row].  value_repr = phi: 8 bytes
+//   x = table row k*L+l0 in bits 0..15, segment k in bits 16..31   (the all-zero rows K*L and K when masked)
+//   y = interpolation weight w as fp32 bits                        (0 when masked, NaN for a NaN input)
+// value_repr = spline_component: 16 bytes, the same two words, then
+//   z = SiLU(x) of the raw input as fp32 bits, w = 0.
+// The two 16-bit halves of x are what the tiled kernel scales (by the bytes of a code row resp. a parameter row)
+// and adds to a lane's column address, one multiply-add each; nothing else is computed per row.
 
 // ------------------------------------------------------------------------------------------------
 // Locate kernel (steps 1-4 of Sec. 4.5 + Sec. 5.2).
 // ------------------------------------------------------------------------------------------------
 struct LocateArgs {
   const float *x;        // [B][d]
-  u32x4 *rec;            // [d][Bp]
+  void *rec;             // [d][Bp] records of 8 bytes, or 16 with the base branch
   int64_t B, Bp;
   int32_t d, K, L;
   int32_t closed, zero_spline;
-  int32_t jt, codes_off, params_off, param_row_bytes;
-  int32_t with_base;     // value_repr = spline_component: the record also carries SiLU(x)
   float tKs;             // safe upper clip value
   float knots[LUTKAN_MAX_K + 1];
   unsigned long long *stats;   // nullable: {oob_count, oob_any_rows}
@@ -100,16 +100,19 @@ __device__ __forceinline__ Located locate_one(const LocateArgs &a, float x) {
 constexpr int kLocRows = 32;    // rows per block
 constexpr int kLocCols = 64;    // inputs per pass
 
+// BASE: value_repr = spline_component, the record also carries SiLU(x).
+template <bool BASE>
 __global__ __launch_bounds__(256) void lutkan_locate_kernel(const LocateArgs a) {
-  __shared__ u32x4 s_rec[kLocCols][kLocRows + 1];
+  typedef typename std::conditional<BASE, u32x4, u32x2>::type rec_t;
+  __shared__ rec_t s_rec[kLocCols][kLocRows + 1];
+  rec_t *const rec_out = static_cast<rec_t *>(a.rec);
   __shared__ int s_row_oob[kLocRows];
   const int tid = threadIdx.x;
   const int64_t b0 = (int64_t)blockIdx.x * kLocRows;
   if (tid < kLocRows) s_row_oob[tid] = 0;
   __syncthreads();
   unsigned my_oob = 0;
-  const unsigned zero_code_off = (unsigned)(a.codes_off + a.K * a.L * a.jt);
-  const unsigned zero_param_off = (unsigned)(a.params_off + a.K * a.param_row_bytes);
+  const unsigned masked_index = (unsigned)(a.K * a.L) | ((unsigned)a.K << 16);
   for (int i0 = 0; i0 < a.d; i0 += kLocCols) {
     // phase 1: read x along inputs (coalesced), locate, park the record in LDS
     const int il = tid & (kLocCols - 1);
@@ -118,18 +121,18 @@ __global__ __launch_bounds__(256) void lutkan_locate_kernel(const LocateArgs a) 
     for (int p = 0; p < kLocRows / 4; ++p) {
       const int bl = p * 4 + (tid >> 6);
       const int64_t b = b0 + bl;
-      u32x4 rec = {zero_code_off, zero_param_off, 0u, 0u};
+      rec_t rec = {};
+      rec.x = masked_index;
       if (b < a.B && i < a.d) {
         const float x = a.x[b * a.d + i];
         const Located o = locate_one(a, x);
         const bool masked = a.zero_spline && !o.inside && !o.is_nan;
         if (!masked) {
-          rec.x = (unsigned)(a.codes_off + (o.k * a.L + o.l0) * a.jt);
-          rec.y = (unsigned)(a.params_off + o.k * a.param_row_bytes);
-          rec.z = __float_as_uint(o.is_nan ? __builtin_nanf("") : o.w);
+          rec.x = (unsigned)(o.k * a.L + o.l0) | ((unsigned)o.k << 16);
+          rec.y = __float_as_uint(o.is_nan ? __builtin_nanf("") : o.w);
         }
         // base branch b(x) = SiLU(x) = x / (1 + exp(-x)) at the RAW input (Eq. 2); it is never masked (Sec. 5.4)
-        if (a.with_base) rec.w = __float_as_uint(__fdiv_rn(x, 1.0f + expf(-x)));
+        if constexpr (BASE) rec.z = __float_as_uint(__fdiv_rn(x, 1.0f + expf(-x)));
         if (!o.inside) { ++my_oob; s_row_oob[bl] = 1; }
         if (a.k_out) {
           a.k_out[b * a.d + i] = o.k;
@@ -141,13 +144,13 @@ __global__ __launch_bounds__(256) void lutkan_locate_kernel(const LocateArgs a) 
       s_rec[il][bl] = rec;
     }
     __syncthreads();
-    // phase 2: write records along rows (coalesced 16-byte stores)
+    // phase 2: write records along rows (coalesced stores)
     const int bl2 = tid & (kLocRows - 1);
 #pragma unroll
     for (int p = 0; p < kLocCols / 8; ++p) {
       const int il2 = p * 8 + (tid >> 5);
       const int i2 = i0 + il2;
-      if (i2 < a.d && b0 + bl2 < a.Bp) a.rec[(int64_t)i2 * a.Bp + b0 + bl2] = s_rec[il2][bl2];
+      if (i2 < a.d && b0 + bl2 < a.Bp) rec_out[(int64_t)i2 * a.Bp + b0 + bl2] = s_rec[il2][bl2];
     }
     __syncthreads();
   }
@@ -169,7 +172,7 @@ __global__ __launch_bounds__(256) void lutkan_locate_kernel(const LocateArgs a) 
 // ------------------------------------------------------------------------------------------------
 struct EdgeArgs {
   const unsigned char *table;
-  const u32x4 *rec;      // lookup records written by the locate kernel, [d][Bp]
+  const void *rec;       // lookup records written by the locate kernel, [d][Bp], 8 bytes each (16 with_base)
   float *y;
   int16_t *q01_out;      // nullable, [B][d][m][2]
   int64_t B, Bp;
@@ -213,22 +216,28 @@ __global__ __launch_bounds__(256) void lutkan_gather_kernel(const EdgeArgs a, co
   const int t = j / a.jt, jj = j - t * a.jt;
   const unsigned char *tile = a.table + (size_t)t * a.d * a.blob_bytes;
   const int poff = (SCHEME == LUTKAN_ASYM_UINT8) ? 8 * jj : 4 * jj;
+  const int rec_words = a.with_base ? 4 : 2;
+  const unsigned *recs = static_cast<const unsigned *>(a.rec);
   float acc = 0.0f;
   for (int i0 = 0; i0 < a.d; i0 += U) {
-    u32x4 rec[U];
+    u32x2 rec[U];
+    float silu_x[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int i = min(i0 + u, a.d - 1);
-      rec[u] = a.rec[(int64_t)i * a.Bp + b];
+      const unsigned *r = recs + ((int64_t)min(i0 + u, a.d - 1) * a.Bp + b) * rec_words;
+      rec[u] = *reinterpret_cast<const u32x2 *>(r);
+      silu_x[u] = a.with_base ? __uint_as_float(r[2]) : 0.0f;
     }
     unsigned c0[U], c1[U];
     float al[U], ym[U], bg[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const unsigned char *slice = tile + (size_t)min(i0 + u, a.d - 1) * a.blob_bytes;
-      c0[u] = slice[rec[u].x + jj];
-      c1[u] = slice[rec[u].x + a.jt + jj];
-      const float *prm = reinterpret_cast<const float *>(slice + rec[u].y + poff);
+      const unsigned code_off = (unsigned)a.codes_off + (rec[u].x & 0xffffu) * (unsigned)a.jt;
+      const unsigned param_off = (unsigned)a.params_off + (rec[u].x >> 16) * (unsigned)a.param_row_bytes;
+      c0[u] = slice[code_off + jj];
+      c1[u] = slice[code_off + a.jt + jj];
+      const float *prm = reinterpret_cast<const float *>(slice + param_off + poff);
       al[u] = prm[0];
       ym[u] = (SCHEME == LUTKAN_ASYM_UINT8) ? prm[1] : 0.0f;
       bg[u] = a.with_base ? reinterpret_cast<const float *>(slice)[jj] : 0.0f;
@@ -236,12 +245,12 @@ __global__ __launch_bounds__(256) void lutkan_gather_kernel(const EdgeArgs a, co
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       if (i0 + u < a.d) {
-        const float w = __uint_as_float(rec[u].z);
+        const float w = __uint_as_float(rec[u].y);
         const float f0 = code_to_float<SCHEME>(c0[u]), f1 = code_to_float<SCHEME>(c1[u]);
         const float tq = fmaf(w, f1 - f0, f0);                             // interpolate the codes ...
         acc = fmaf(al[u], tq, acc);                                        // ... then one scale per edge
         if (SCHEME == LUTKAN_ASYM_UINT8) acc += ym[u];
-        if (a.with_base) acc = fmaf(bg[u], __uint_as_float(rec[u].w), acc);  // + s_out*s_base * SiLU(x)
+        if (a.with_base) acc = fmaf(bg[u], silu_x[u], acc);                  // + s_out*s_base * SiLU(x)
         if (TRACE && a.q01_out) {
           const int l0 = a.l0_out[b * a.d + i0 + u];
           const int row = a.k_out[b * a.d + i0 + u] * a.L + l0;
@@ -284,8 +293,8 @@ __device__ __forceinline__ void stage_slice(const u32x4 *gsrc, unsigned char *ld
 // LDS holds two slice buffers and, per wave, two record buffers.  While input i is processed out of one
 // buffer, the (tile, i+1) table slice and the wave's RW records for input i+1 stream from global memory
 // straight into the other one (no registers, no LDS store instructions); one barrier per input separates
-// the two roles.  Per row a lane reads its row's record (an LDS broadcast), adds its column offset to the two
-// byte offsets in it, and reads code row l0, code row l0+1 and the scales.
+// the two roles.  Per row a lane reads its row's record (an LDS broadcast), turns the table row and the segment
+// in it into two LDS addresses (one 16-bit multiply-add each), and reads code row l0, code row l0+1 and the scales.
 // Arithmetic per edge (Eq. 10 + Eq. 17 folded): acc += alpha * (q0 + w * (q1 - q0)) [+ y_min].  A byte code c,
 // zero-extended to 16 bits, IS the fp16 denormal c * 2^-24, so the four codes of a dword become two packed-fp16
 // registers with two byte permutes; the difference q1 - q0 (and the removal of the excess-128 bias of symmetric
@@ -296,7 +305,7 @@ __device__ __forceinline__ void stage_slice(const u32x4 *gsrc, unsigned char *ld
 // contribution exactly zero.  l0+1 is read even when l0 = L-1: then w = 0 exactly and the neighbour (the
 // next segment's first row, or a zero row) does not change the result.
 // With BASE (value_repr = spline_component) every slice starts with a row of s_out*s_base; a lane loads its four
-// values once per input and adds base * SiLU(x) per row, SiLU(x) being the fourth word of the row's record.
+// values once per input and adds base * SiLU(x) per row, SiLU(x) being the third word of the row's record.
 template <int SCHEME, int LPR, int NP, int NW, bool BASE>
 __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a) {
   extern __shared__ __align__(16) unsigned char lds[];
@@ -305,6 +314,10 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
   constexpr int RW = RPS * NP;
   static_assert(RW <= 64, "a wave's records for one input must fit one 1 KiB copy step");
   constexpr int PSZ = (SCHEME == LUTKAN_ASYM_UINT8) ? 32 : 16;   // parameter bytes per lane (4 columns)
+  constexpr int RB = BASE ? 16 : 8;                              // bytes per record
+  constexpr int REC_LANES = RW * RB / 16;                        // lanes that copy 16 bytes of the wave's records
+  static_assert((RW * RB) % 16 == 0, "a wave's records are whole 16-byte vectors");
+  typedef const __attribute__((address_space(3))) unsigned char *lds_bytes;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -322,8 +335,8 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
     for (int c = 0; c < 4; ++c) acc[p][c] = 0.0f;
 
   const u32x4 *src = reinterpret_cast<const u32x4 *>(a.table + (size_t)t * a.d * a.blob_bytes);
-  const u32x4 *rec_src = a.rec + b0 + (lane < RW ? lane : 0);
-  unsigned char *rec_area = lds + 2 * a.blob_bytes + wave * (2 * RW * 16);
+  const unsigned char *rec_src = static_cast<const unsigned char *>(a.rec) + b0 * RB + (lane < REC_LANES ? lane : 0) * 16;
+  unsigned char *rec_area = lds + 2 * a.blob_bytes + wave * (2 * RW * RB);
 
   // this work-group walks the inputs [i_begin, i_end) and writes one set of (partial) sums
   const int i_begin = blockIdx.y * a.chunk;
@@ -331,7 +344,7 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
   float *yout = a.y + (int64_t)blockIdx.y * a.split_stride;
 
   stage_slice<NW>(src + (size_t)i_begin * nvec, lds, nvec, wave, lane);
-  if (lane < RW) copy16_global_to_lds(rec_src + (int64_t)i_begin * a.Bp, rec_area);
+  if (lane < REC_LANES) copy16_global_to_lds(rec_src + (int64_t)i_begin * a.Bp * RB, rec_area);
   wait_all_vector_loads();
   __syncthreads();
 
@@ -339,32 +352,40 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
     const int cur = (i - i_begin) & 1;
     if (i + 1 < i_end) {                               // stream the next input's slice and records
       stage_slice<NW>(src + (size_t)(i + 1) * nvec, lds + (cur ^ 1) * a.blob_bytes, nvec, wave, lane);
-      if (lane < RW) copy16_global_to_lds(rec_src + (int64_t)(i + 1) * a.Bp, rec_area + (cur ^ 1) * (RW * 16));
+      if (lane < REC_LANES) copy16_global_to_lds(rec_src + (int64_t)(i + 1) * a.Bp * RB, rec_area + (cur ^ 1) * (RW * RB));
     }
     const unsigned char *slice = lds + cur * a.blob_bytes;
-    const unsigned char *rec_buf = rec_area + cur * (RW * 16) + hrow * 16;
-    const unsigned char *col_codes = slice + sub * 4;
-    const unsigned char *col_params = slice + sub * PSZ;
+    const unsigned char *rec_buf = rec_area + cur * (RW * RB) + hrow * RB;
+    // LDS byte addresses of this lane's columns in code row 0 and parameter row 0 of the slice
+    const unsigned slice_addr = (unsigned)(uintptr_t)(lds_bytes)slice;
+    const unsigned col_codes = slice_addr + (unsigned)a.codes_off + sub * 4;
+    const unsigned col_params = slice_addr + (unsigned)a.params_off + sub * PSZ;
     // Software pipeline over the NP row steps.  The reads of step p+1 (codes, parameters) and the record of
     // step p+2 are issued before the arithmetic of step p, and they are issued right AFTER the one point per
     // step where the wave waits for its outstanding LDS reads (the first touch of step p's data): what the
     // wave waits for was issued a whole step earlier, what it issues now has a whole step to arrive.
-    typedef typename std::conditional<BASE, u32x4, u32x3>::type rec_t;        // 16-byte or 12-byte LDS read
+    typedef typename std::conditional<BASE, u32x3, u32x2>::type rec_t;        // 12-byte or 8-byte LDS read
     f32x4 base_gain = {0.f, 0.f, 0.f, 0.f};
     if (BASE) base_gain = *reinterpret_cast<const f32x4 *>(slice + sub * 16) * kTwoToMinus24;
     struct Fetched { unsigned c0, c1; f32x4 pa, pb; };
     auto fetch = [&](const rec_t &rc) {
       Fetched f;
-      const unsigned char *cp = col_codes + rc.x;
-      const unsigned char *pp = col_params + rc.y;
-      f.c0 = *reinterpret_cast<const unsigned *>(cp);
-      f.c1 = *reinterpret_cast<const unsigned *>(cp + JT);
-      f.pa = *reinterpret_cast<const f32x4 *>(pp);
-      f.pb = (SCHEME == LUTKAN_ASYM_UINT8) ? *reinterpret_cast<const f32x4 *>(pp + 16) : f32x4{0.f, 0.f, 0.f, 0.f};
+      // address = column address + (16-bit half of the record word) * (bytes per row): D = S0.u16 * S1.u16 + S2
+      unsigned code_addr, param_addr;
+      asm("v_mad_u32_u16 %0, %1, %2, %3 op_sel:[0,0,0,0]" : "=v"(code_addr) : "v"(rc.x), "s"(JT), "v"(col_codes));
+      asm("v_mad_u32_u16 %0, %1, %2, %3 op_sel:[1,0,0,0]" : "=v"(param_addr) : "v"(rc.x), "s"(a.param_row_bytes), "v"(col_params));
+      lds_bytes cp = (lds_bytes)(uintptr_t)code_addr;
+      lds_bytes pp = (lds_bytes)(uintptr_t)param_addr;
+      typedef const __attribute__((address_space(3))) unsigned *lds_u32;
+      typedef const __attribute__((address_space(3))) f32x4 *lds_f32x4;
+      f.c0 = *(lds_u32)cp;
+      f.c1 = *(lds_u32)(cp + JT);
+      f.pa = *(lds_f32x4)pp;
+      f.pb = (SCHEME == LUTKAN_ASYM_UINT8) ? *(lds_f32x4)(pp + 16) : f32x4{0.f, 0.f, 0.f, 0.f};
       return f;
     };
     rec_t rc_cur = *reinterpret_cast<const rec_t *>(rec_buf);
-    rec_t rc_nxt = *reinterpret_cast<const rec_t *>(rec_buf + (NP > 1 ? RPS * 16 : 0));
+    rec_t rc_nxt = *reinterpret_cast<const rec_t *>(rec_buf + (NP > 1 ? RPS * RB : 0));
     Fetched f_cur = fetch(rc_cur);
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
@@ -373,10 +394,10 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
       if (SCHEME == LUTKAN_ASYM_UINT8) asm volatile("" ::"v"(f_cur.pb));
       asm volatile("" ::"v"(f_cur.pa), "v"(f_cur.c1), "v"(rc_nxt.y));          // first touch of step p's data
       __builtin_amdgcn_sched_barrier(0);
-      if (p + 2 < NP) rc_nn = *reinterpret_cast<const rec_t *>(rec_buf + (p + 2) * (RPS * 16));
+      if (p + 2 < NP) rc_nn = *reinterpret_cast<const rec_t *>(rec_buf + (p + 2) * (RPS * RB));
       if (p + 1 < NP) f_nxt = fetch(rc_nxt);
       __builtin_amdgcn_sched_barrier(0);
-      const float w = __uint_as_float(rc_cur.z);
+      const float w = __uint_as_float(rc_cur.y);
       float al[4], ym[4];
       if (SCHEME == LUTKAN_ASYM_UINT8) {
         al[0] = f_cur.pa.x; ym[0] = f_cur.pa.y; al[1] = f_cur.pa.z; ym[1] = f_cur.pa.w;
@@ -409,7 +430,7 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
         for (int c = 0; c < 4; ++c) acc[p][c] = fmaf(ym[c], kTwoToMinus24, acc[p][c]);
       }
       if constexpr (BASE) {
-        const float silu_x = __uint_as_float(rc_cur.w);
+        const float silu_x = __uint_as_float(rc_cur.z);
         acc[p][0] = fmaf(base_gain.x, silu_x, acc[p][0]);
         acc[p][1] = fmaf(base_gain.y, silu_x, acc[p][1]);
         acc[p][2] = fmaf(base_gain.z, silu_x, acc[p][2]);
@@ -736,6 +757,7 @@ constexpr int kMaxTiledLds = 144 * 1024;
 
 inline int64_t round_up(int64_t v, int64_t q) { return (v + q - 1) / q * q; }
 inline int64_t padded_rows(int64_t B) { return round_up(B, kMaxTileRows); }
+inline int lut_record_bytes(int value_repr) { return value_repr == LUTKAN_REPR_SPLINE_COMPONENT ? 16 : 8; }
 inline size_t record_bytes(int d, int64_t Bp, int bytes_per_record) { return (size_t)round_up((int64_t)d * Bp * bytes_per_record, 256); }
 
 int check_launch(const char *what) {
@@ -812,7 +834,7 @@ int launch_tiled_np(const EdgeArgs &ea, hipStream_t s) {
   constexpr int RW = (64 / LPR) * NP;
   const int64_t row_tiles = (ea.B + NW * RW - 1) / (NW * RW);
   const dim3 grid((unsigned)(row_tiles * ea.n_tiles), (unsigned)((ea.d + ea.chunk - 1) / ea.chunk));
-  const size_t lds = 2 * (size_t)ea.blob_bytes + (size_t)NW * 2 * RW * 16;
+  const size_t lds = 2 * (size_t)ea.blob_bytes + (size_t)NW * 2 * RW * (ea.with_base ? 16 : 8);
   static bool raised = false, raised_base = false;
   if (ea.with_base) return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, true>, &raised_base, grid, lds, s, ea, "lutkan_tiled_kernel");
   return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, false>, &raised, grid, lds, s, ea, "lutkan_tiled_kernel");
@@ -864,18 +886,18 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
 
   LocateArgs la;
   la.x = x;
-  la.rec = static_cast<u32x4 *>(workspace);
+  la.rec = workspace;
   la.B = B; la.Bp = Bp; la.d = l->d; la.K = l->K; la.L = l->L;
   la.closed = (l->boundary == LUTKAN_CLOSED);
   la.zero_spline = (l->oob == LUTKAN_ZERO_SPLINE);
-  la.jt = l->jt; la.codes_off = lay.codes_off; la.params_off = lay.params_off; la.param_row_bytes = lay.param_row_bytes;
-  la.with_base = (l->value_repr == LUTKAN_REPR_SPLINE_COMPONENT);
+  const bool with_base = (l->value_repr == LUTKAN_REPR_SPLINE_COMPONENT);
   la.tKs = la.closed ? l->knots[l->K] : std::nextafterf(l->knots[l->K], -INFINITY);
   for (int k = 0; k <= l->K; ++k) la.knots[k] = l->knots[k];
   la.stats = reinterpret_cast<unsigned long long *>(stats);
   la.k_out = trace ? k_out : nullptr; la.l0_out = l0_out; la.in_out = in_out; la.w_out = w_out;
   if (phases & kLocate) {
-    hipLaunchKernelGGL(lutkan_locate_kernel, dim3((unsigned)(Bp / kLocRows)), dim3(256), 0, s, la);
+    if (with_base) hipLaunchKernelGGL(lutkan_locate_kernel<true>, dim3((unsigned)(Bp / kLocRows)), dim3(256), 0, s, la);
+    else hipLaunchKernelGGL(lutkan_locate_kernel<false>, dim3((unsigned)(Bp / kLocRows)), dim3(256), 0, s, la);
     if (int rc = check_launch("lutkan_locate_kernel")) return rc;
   }
   if (!(phases & kEdges)) return LUTKAN_OK;
@@ -886,7 +908,7 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   ea.B = B; ea.Bp = Bp; ea.d = l->d; ea.m = l->m; ea.K = l->K; ea.L = l->L;
   ea.jt = l->jt; ea.n_tiles = l->n_tiles; ea.blob_bytes = l->blob_bytes;
   ea.codes_off = lay.codes_off; ea.params_off = lay.params_off; ea.param_row_bytes = lay.param_row_bytes;
-  ea.with_base = la.with_base; ea.k_out = k_out; ea.l0_out = l0_out;
+  ea.with_base = with_base; ea.k_out = k_out; ea.l0_out = l0_out;
 
   bool tiled = tiled_supported(l->jt, l->blob_bytes) && !q01_out;
   if (l->algo == LUTKAN_ALGO_GATHER) tiled = false;
@@ -895,7 +917,7 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   ea.split_stride = 0;
   if (tiled) {
     const TilePlan tp = plan_tiles(B, l->d, l->n_tiles, 64 / (l->jt / 4));
-    float *partials = reinterpret_cast<float *>(static_cast<char *>(workspace) + record_bytes(l->d, Bp, 16));
+    float *partials = reinterpret_cast<float *>(static_cast<char *>(workspace) + record_bytes(l->d, Bp, lut_record_bytes(l->value_repr)));
     ea.chunk = tp.chunk;
     if (tp.n_split > 1) { ea.y = partials; ea.split_stride = B * l->m; }
     const int rc = (l->scheme == LUTKAN_SYM_INT8) ? launch_tiled_jt<LUTKAN_SYM_INT8>(ea, tp.np, s) : launch_tiled_jt<LUTKAN_ASYM_UINT8>(ea, tp.np, s);
@@ -1031,7 +1053,7 @@ static size_t tiled_workspace_bytes(int d, int m, int jt, int n_tiles, int64_t B
 
 extern "C" size_t lutkan_forward_workspace_bytes(const lutkan_dev_layer *layer, int64_t B) {
   if (!layer || B <= 0 || layer->d < 1 || layer->m < 1 || layer->jt < 4 || layer->n_tiles < 1) return 0;
-  return tiled_workspace_bytes(layer->d, layer->m, layer->jt, layer->n_tiles, B, 16);
+  return tiled_workspace_bytes(layer->d, layer->m, layer->jt, layer->n_tiles, B, lut_record_bytes(layer->value_repr));
 }
 
 extern "C" size_t bspline_forward_workspace_bytes(const bspline_dev_layer *layer, int64_t B) {

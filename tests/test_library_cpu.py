@@ -97,8 +97,11 @@ def test_device_struct_initialisers():
     bl = binding._SplineDevLayer()
     assert lib.bspline_dev_layer_init(art._h, C.byref(bl)) == 0
     assert (bl.d, bl.m, bl.G, bl.degree) == (78, 16, 5, 3) and list(bl.ext_knots)[:12] == list(art.ext_knots)
-    need = lib.lutkan_forward_workspace_bytes(C.byref(dl), 1000)      # records (16 B per input and padded row) + partial sums
-    assert 78 * 1024 * 16 <= need <= 78 * 1024 * 16 + 32 * 1000 * 16 * 4
+    need = lib.lutkan_forward_workspace_bytes(C.byref(dl), 1000)      # records (8 B per input and padded row) + partial sums
+    assert 78 * 1024 * 8 <= need <= 78 * 1024 * 8 + 32 * 1000 * 16 * 4
+    dl.value_repr = 1                                                 # spline_component: 16-byte records (with SiLU(x))
+    assert lib.lutkan_forward_workspace_bytes(C.byref(dl), 1000) == need + 78 * 1024 * 8
+    dl.value_repr = 0
     assert lib.lutkan_forward_workspace_bytes(C.byref(dl), 0) == 0
     assert I_tK_star(art, CLOSED) == art.knots[-1]
 
