@@ -32,7 +32,7 @@ PEAK_HBM_GBS = 8000.0
 FLOP_PER_EDGE = 8
 # HBM traffic of one edge-kernel launch on the default workload, from rocprofv3 --pmc FETCH_SIZE (x2.0, the factor a
 # plain 1 GiB copy gives) + WRITE_SIZE (x1.0); see profiles/lutkan_tiled_kernel_cfg4_B32768.md.
-MEASURED_TRAFFIC_BYTES = {32768: 5.868e9}
+MEASURED_TRAFFIC_BYTES = {32768: 3.72e9}
 
 
 def log(msg):

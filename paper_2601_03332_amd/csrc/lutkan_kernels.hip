@@ -113,9 +113,19 @@ __global__ __launch_bounds__(256) void lutkan_locate_kernel(const LocateArgs a) 
   __syncthreads();
   unsigned my_oob = 0;
   const unsigned masked_index = (unsigned)(a.K * a.L) | ((unsigned)a.K << 16);
+  const int il = tid & (kLocCols - 1);
+  // x of one pass: 8 rows x 1 input per thread, loaded one pass ahead so that the loads overlap the record stores
+  float xv[kLocRows / 4];
+  auto load_x = [&](int i0) {
+#pragma unroll
+    for (int p = 0; p < kLocRows / 4; ++p) {
+      const int64_t b = b0 + p * 4 + (tid >> 6);
+      xv[p] = (b < a.B && i0 + il < a.d) ? a.x[b * a.d + i0 + il] : 0.0f;
+    }
+  };
+  load_x(0);
   for (int i0 = 0; i0 < a.d; i0 += kLocCols) {
-    // phase 1: read x along inputs (coalesced), locate, park the record in LDS
-    const int il = tid & (kLocCols - 1);
+    // phase 1: x was read along inputs (coalesced); locate, park the record in LDS
     const int i = i0 + il;
 #pragma unroll
     for (int p = 0; p < kLocRows / 4; ++p) {
@@ -124,7 +134,7 @@ __global__ __launch_bounds__(256) void lutkan_locate_kernel(const LocateArgs a) 
       rec_t rec = {};
       rec.x = masked_index;
       if (b < a.B && i < a.d) {
-        const float x = a.x[b * a.d + i];
+        const float x = xv[p];
         const Located o = locate_one(a, x);
         const bool masked = a.zero_spline && !o.inside && !o.is_nan;
         if (!masked) {
@@ -144,6 +154,7 @@ __global__ __launch_bounds__(256) void lutkan_locate_kernel(const LocateArgs a) 
       s_rec[il][bl] = rec;
     }
     __syncthreads();
+    if (i0 + kLocCols < a.d) load_x(i0 + kLocCols);
     // phase 2: write records along rows (coalesced stores)
     const int bl2 = tid & (kLocRows - 1);
 #pragma unroll
