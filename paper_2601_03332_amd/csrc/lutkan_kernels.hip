@@ -279,13 +279,24 @@ __global__ __launch_bounds__(256) void lutkan_gather_kernel(const EdgeArgs a, co
 
 // Asynchronous global -> LDS copy of 16 bytes per lane (gfx950 LDS-DMA form of the global load): the wave's
 // active lanes each fetch 16 bytes from their own global address and the data lands at lds_dst + 16*lane.
-// lds_dst must be wave-uniform.  Completion is tracked by vmcnt like any other vector memory load.
+// lds_dst must be wave-uniform (it travels in M0; one wait state separates the M0 write from the load).
+// Completion is tracked by vmcnt like any other vector memory load.  The copy is written out as instructions
+// rather than through the compiler's builtin: for the builtin the compiler makes the wave wait for all its
+// outstanding copies before any later LDS read and before every barrier, because it cannot tell the stage
+// buffers apart; here the kernel waits itself (wait_all_vector_loads) before it reads what a copy wrote.
 __device__ __forceinline__ void copy16_global_to_lds(const void *gsrc, void *lds_dst) {
-  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gsrc,
-                                   (__attribute__((address_space(3))) void *)lds_dst, 16, 0, 0);
+  const unsigned dst = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(__attribute__((address_space(3))) void *)lds_dst);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(gsrc) : "m0", "memory");
 }
 
 __device__ __forceinline__ void wait_all_vector_loads() { __builtin_amdgcn_s_waitcnt(0x0f70); }   // vmcnt(0)
+
+// Work-group barrier that orders LDS traffic only (__syncthreads() also drains the wave's global-memory traffic).
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
 
 // Copies n16 16-byte vectors from gsrc to lds_dst with all NW waves of the work-group, 1 KiB per wave step.
 template <int NW>
@@ -453,7 +464,7 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
       f_cur = f_nxt;
     }
     wait_all_vector_loads();                           // my share of the next slice has landed ...
-    __syncthreads();                                   // ... everyone's has, and everyone is done with this one
+    lds_barrier();                                     // ... everyone's has, and everyone is done with this one
   }
 
   const int j = t * JT + sub * 4;
@@ -724,7 +735,7 @@ __global__ __launch_bounds__(NW * 64) void bspline_tiled_kernel(const SplineEdge
       f_cur = f_nxt;
     }
     wait_all_vector_loads();
-    __syncthreads();
+    lds_barrier();
   }
 
   const int j = t * JT + sub * 4;
