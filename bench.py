@@ -47,6 +47,7 @@ def main():
     ap.add_argument("--batch", type=int, default=32768)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bspline", action="store_true")
+    ap.add_argument("--no-probes", action="store_true", help="skip the four peak-rate probes (FMA, LDS, L2, HBM)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy, as a known-size reference for HBM counters")
     args = ap.parse_args()
@@ -129,6 +130,46 @@ def main():
 
     extra = {"rows_per_s": round(B / (dt / args.steps), 1), "locate_kernel_ms": round(loc_ms, 4),
              "edge_kernel_edge_evals_per_s": round(edges / (edge_ms * 1e-3), 1)}
+
+    if not args.no_probes:
+        # Rates this GPU sustains on one resource at a time (kernels of known work, timed with events), and what
+        # the edge kernel asks of each resource per launch: the largest term is the bound, the others show the slack.
+        probe_buf = torch.zeros((1 << 30) // 4 + 4, dtype=torch.float32, device=dev)      # 1 GiB + 16 B, finite floats
+
+        def probe(kind, iters):
+            best, work = None, 0.0
+            for _ in range(3):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                work = lk.lutkan_probe_launch(kind, probe_buf, iters)
+                e1.record()
+                torch.cuda.synchronize()
+                t = e0.elapsed_time(e1) * 1e-3
+                best = t if best is None else min(best, t)
+            return work / best
+
+        fma_flops = probe(lk.PROBE_VALU_FMA, 2048)
+        lds_bps = probe(lk.PROBE_LDS_READ, 512)
+        l2_bps = probe(lk.PROBE_L2_READ, 4)
+        hbm_bps = probe(lk.PROBE_HBM_READ, 2)
+        del probe_buf
+        rec_bytes = 8 * (-(-B // 1024) * 1024) * d
+        valu_ops = 4.5 * edges                                   # 18 vector instructions per 4 edges (lane-operations)
+        lds_bytes = 8.0 * edges                                  # 32 B per lane and row step: record 8, codes 8, scales 16
+        l2_bytes = -(-B // 1024) * art.info.table_bytes + art.info.n_tiles * rec_bytes   # slices and records staged into LDS
+        hbm_bytes = MEASURED_TRAFFIC_BYTES.get(B) or (art.info.table_bytes + rec_bytes + 4 * B * m)
+        terms = {"valu": valu_ops / (fma_flops / 2.0), "lds": (lds_bytes + l2_bytes) / lds_bps,
+                 "l2": l2_bytes / l2_bps, "hbm": hbm_bytes / hbm_bps}
+        binding = max(terms, key=terms.get)
+        roofline.update({
+            "measured_peaks": {"fp32_fma_TFLOPs": round(fma_flops / 1e12, 2), "lds_read_TBs": round(lds_bps / 1e12, 2),
+                               "l2_read_TBs": round(l2_bps / 1e12, 2), "hbm_read_TBs": round(hbm_bps / 1e12, 2)},
+            "terms_ms": {k: round(v * 1e3, 4) for k, v in terms.items()},
+            "binding_term": binding,
+            "frac_of_measured_bound": round(terms[binding] / (edge_ms * 1e-3), 4)})
+        log(f"[bench] measured peaks: FMA {fma_flops / 1e12:.1f} TFLOP/s, LDS {lds_bps / 1e12:.1f} TB/s, "
+            f"L2 {l2_bps / 1e12:.1f} TB/s, HBM {hbm_bps / 1e12:.2f} TB/s; edge-kernel terms (ms): "
+            + ", ".join(f"{k} {v * 1e3:.2f}" for k, v in terms.items()) + f" -> bound by {binding}")
 
     if not args.no_bspline:
         bl = art.bspline_to_device(dev)

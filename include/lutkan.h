@@ -203,6 +203,21 @@ size_t lutkan_model_workspace_bytes(const lutkan_dev_layer *layers, int32_t n_la
 int lutkan_model_forward(const lutkan_dev_layer *layers, int32_t n_layers, const float *x, int64_t B, float *y,
                          lutkan_oob_stats *stats, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Measurement aid, not part of the method: launches one kernel of known work that exercises a single resource, so
+ * that a caller who times it (events on hip_stream) learns the rate this machine sustains and can put the layer
+ * kernels' roofline terms beside measured peaks as well as published ones.
+ *   kind          LUTKAN_PROBE_VALU_FMA  non-packed fp32 FMAs, 16 independent chains per lane   work = flop
+ *                 LUTKAN_PROBE_LDS_READ  conflict-free 16-byte LDS reads                        work = bytes
+ *                 LUTKAN_PROBE_L2_READ   every work-group re-reads the same 2 MiB               work = bytes
+ *                 LUTKAN_PROBE_HBM_READ  the whole buffer once per pass (buffer >= 1 GiB)       work = bytes
+ *   buffer        device, 16-byte aligned; the first 16 bytes are a sink, the rest is read (contents irrelevant, but
+ *                 finite floats for the LDS probe); needs 16 B / 16 KiB+16 / 2 MiB+16 / >= 1 GiB by kind
+ *   iters         repetitions inside the kernel, 1 .. 2^20
+ *   work_out      host: the flop or bytes one launch performs
+ * Errors: EINVAL (null, misaligned, unknown kind, iters), ESHAPE (buffer too small), EHIP. */
+typedef enum { LUTKAN_PROBE_VALU_FMA = 0, LUTKAN_PROBE_LDS_READ = 1, LUTKAN_PROBE_L2_READ = 2, LUTKAN_PROBE_HBM_READ = 3 } lutkan_probe_kind;
+int lutkan_probe_launch(int32_t kind, void *buffer, size_t buffer_bytes, int32_t iters, double *work_out, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -13,6 +13,7 @@ SYM_INT8, ASYM_UINT8 = 0, 1
 HALF_OPEN, CLOSED = 0, 1
 CLIP_X, ZERO_SPLINE = 0, 1
 ALGO_AUTO, ALGO_GATHER, ALGO_TILED = 0, 1, 2
+PROBE_VALU_FMA, PROBE_LDS_READ, PROBE_L2_READ, PROBE_HBM_READ = 0, 1, 2, 3
 REPR_PHI, REPR_SPLINE_COMPONENT = 0, 1
 MAX_K = 64
 
@@ -57,7 +58,7 @@ EXPORTS = [
     "lutkan_dev_layer_init", "bspline_dev_layer_init", "lutkan_forward_workspace_bytes",
     "bspline_forward_workspace_bytes", "lutkan_forward", "lutkan_forward_trace", "bspline_kan_forward",
     "lutkan_model_workspace_bytes", "lutkan_model_forward", "lutkan_forward_locate", "lutkan_forward_edges",
-    "bspline_forward_locate", "bspline_forward_edges",
+    "bspline_forward_locate", "bspline_forward_edges", "lutkan_probe_launch",
 ]
 
 _lib = None
@@ -103,6 +104,7 @@ def load_library():
     lib.lutkan_model_workspace_bytes.argtypes = [C.POINTER(_DevLayer), i32, i64]
     lib.lutkan_model_workspace_bytes.restype = sz
     lib.lutkan_model_forward.argtypes = [C.POINTER(_DevLayer), i32, vp, i64, vp, vp, vp, sz, vp]
+    lib.lutkan_probe_launch.argtypes = [i32, vp, sz, i32, C.POINTER(C.c_double), vp]
     _lib = lib
     return lib
 
@@ -374,3 +376,14 @@ def lutkan_model_forward(layers: List[LutLayer], x, y=None, stats=None, workspac
                                                stats.data_ptr() if stats is not None else None,
                                                ws.data_ptr(), ws.numel(), _stream(x.device)))
     return y
+
+
+def lutkan_probe_launch(kind: int, buffer, iters: int) -> float:
+    """Launches one measurement kernel (see lutkan.h) on the current stream; returns the flop or bytes it performs."""
+    torch = _torch()
+    if not buffer.is_cuda or not buffer.is_contiguous():
+        raise LutKanError("lutkan_probe_launch: buffer must be a contiguous device tensor")
+    work = C.c_double(0.0)
+    _check(load_library().lutkan_probe_launch(kind, buffer.data_ptr(), buffer.numel() * buffer.element_size(), iters,
+                                              C.byref(work), _stream(buffer.device)))
+    return work.value

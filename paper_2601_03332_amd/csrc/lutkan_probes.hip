@@ -1,0 +1,130 @@
+// Measurement aids of liblutkan: four kernels of known work, one per resource the LUT layer forward can be bound
+// by (vector-ALU FMA issue, LDS read bandwidth, L2 read bandwidth, HBM read bandwidth).  A caller times a launch
+// and divides the reported work by the duration to get the rate this machine actually sustains, which is what
+// the roofline terms of the layer kernels are compared with.  They are not part of the method.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "lutkan_internal.h"
+
+using lutkan::fail;
+
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kProbeThreads = 1024;     // 16 waves, like the tiled layer kernels
+constexpr int kFmaChains = 16;          // independent FMA chains per thread (hides the FMA latency at 4 waves / SIMD)
+constexpr int kLdsProbeBytes = 64 * 1024;
+constexpr int kL2ProbeBytes = 2 * 1024 * 1024;   // per pass; fits every XCD's L2, exceeds every CU's L1
+
+// fp32 FMA issue rate: every lane runs kFmaChains dependent chains of `iters` FMAs (non-packed form).
+__global__ __launch_bounds__(kProbeThreads) void probe_valu_fma_kernel(float *sink, int iters, float a, float b) {
+  float x[kFmaChains];
+#pragma unroll
+  for (int c = 0; c < kFmaChains; ++c) x[c] = (float)(threadIdx.x + c);
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int c = 0; c < kFmaChains; ++c) x[c] = fmaf(x[c], a, b);
+  }
+  float s = 0.0f;
+#pragma unroll
+  for (int c = 0; c < kFmaChains; ++c) s += x[c];
+  if (s == 123456.789f) sink[0] = s;     // keeps the chains alive; practically never taken
+}
+
+// LDS read bandwidth: a work-group fills 64 KiB of LDS once, then every lane reads 16 bytes per step, lanes on
+// consecutive addresses (conflict-free), walking the four 16 KiB quarters of the buffer.
+__global__ __launch_bounds__(kProbeThreads) void probe_lds_read_kernel(const float *src, float *sink, int iters) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  f32x4 *cells = reinterpret_cast<f32x4 *>(lds);
+  for (int v = threadIdx.x; v < kLdsProbeBytes / 16; v += kProbeThreads)
+    cells[v] = *reinterpret_cast<const f32x4 *>(src + 4 * (v & 1023));
+  __syncthreads();
+  typedef const __attribute__((address_space(3))) f32x4 *lds_vec;
+  unsigned addr = (unsigned)(uintptr_t)(lds_vec)(cells + threadIdx.x);
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int it = 0; it < iters; ++it) {
+    asm volatile("" : "+v"(addr));          // opaque to the optimiser: the four reads are issued again every pass
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc += *(lds_vec)(uintptr_t)(addr + q * (kProbeThreads * 16));
+  }
+  if (acc.x + acc.y + acc.z + acc.w == 123456.789f) sink[0] = acc.x;
+}
+
+// L2 read bandwidth: every work-group streams the same 2 MiB (coalesced 16-byte loads) `iters` times; after the
+// first pass the data sits in every XCD's L2 and is too large for a CU's L1.
+// HBM read bandwidth: the same kernel over a buffer far larger than the caches, each 16-byte vector read once per pass.
+__global__ __launch_bounds__(kProbeThreads) void probe_global_read_kernel(const f32x4 *src, float *sink, int64_t n16_per_group,
+                                                                           int64_t group_stride16, int iters) {
+  const f32x4 *base = src + (int64_t)blockIdx.x * group_stride16;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int it = 0; it < iters; ++it) {
+    for (int64_t v = threadIdx.x; v < n16_per_group; v += 4 * kProbeThreads) {
+      // four independent loads per step keep enough requests in flight
+      f32x4 r[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int64_t e = v + (int64_t)q * kProbeThreads;
+        r[q] = (e < n16_per_group) ? base[e] : f32x4{0.f, 0.f, 0.f, 0.f};
+      }
+      acc += (r[0] + r[1]) + (r[2] + r[3]);
+    }
+  }
+  if (acc.x + acc.y + acc.z + acc.w == 123456.789f) sink[0] = acc.x;
+}
+
+}  // namespace
+
+extern "C" int lutkan_probe_launch(int32_t kind, void *buffer, size_t buffer_bytes, int32_t iters, double *work_out,
+                                   void *hip_stream) {
+  const char *who = "lutkan_probe_launch";
+  if (!buffer || !work_out) return fail(LUTKAN_EINVAL, "%s: null buffer or work_out", who);
+  if ((reinterpret_cast<uintptr_t>(buffer) & 15) != 0) return fail(LUTKAN_EINVAL, "%s: buffer must be 16-byte aligned", who);
+  if (iters < 1 || iters > (1 << 20)) return fail(LUTKAN_EINVAL, "%s: iters=%d outside [1, 2^20]", who, iters);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  float *fbuf = static_cast<float *>(buffer);
+  const int groups = 256 * 8;                 // eight work-groups per compute unit's worth of work
+  switch (kind) {
+    case LUTKAN_PROBE_VALU_FMA: {
+      if (buffer_bytes < 16) return fail(LUTKAN_ESHAPE, "%s: buffer too small", who);
+      hipLaunchKernelGGL(probe_valu_fma_kernel, dim3(groups), dim3(kProbeThreads), 0, s, fbuf, iters, 0.999f, 0.001f);
+      *work_out = 2.0 * kFmaChains * (double)iters * kProbeThreads * groups;            // flop
+      break;
+    }
+    case LUTKAN_PROBE_LDS_READ: {
+      if (buffer_bytes < 16 * 1024 + 16) return fail(LUTKAN_ESHAPE, "%s: buffer needs 16 KiB + 16 B", who);
+      static bool raised = false;
+      if (!raised) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(probe_lds_read_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsProbeBytes);
+        if (e != hipSuccess) return fail(LUTKAN_EHIP, "hipFuncSetAttribute(LDS): %s", hipGetErrorString(e));
+        raised = true;
+      }
+      hipLaunchKernelGGL(probe_lds_read_kernel, dim3(groups), dim3(kProbeThreads), kLdsProbeBytes, s, fbuf + 4, fbuf, iters);
+      *work_out = 4.0 * 16.0 * (double)iters * kProbeThreads * groups;                  // bytes read from LDS
+      break;
+    }
+    case LUTKAN_PROBE_L2_READ: {
+      if (buffer_bytes < (size_t)kL2ProbeBytes + 16) return fail(LUTKAN_ESHAPE, "%s: buffer needs 2 MiB + 16 B", who);
+      hipLaunchKernelGGL(probe_global_read_kernel, dim3(groups), dim3(kProbeThreads), 0, s,
+                         reinterpret_cast<const f32x4 *>(fbuf + 4), fbuf, (int64_t)(kL2ProbeBytes / 16), (int64_t)0, iters);
+      *work_out = (double)kL2ProbeBytes * iters * groups;                               // bytes read through L2
+      break;
+    }
+    case LUTKAN_PROBE_HBM_READ: {
+      if (buffer_bytes < ((size_t)1 << 30)) return fail(LUTKAN_ESHAPE, "%s: buffer must be at least 1 GiB to defeat the caches", who);
+      const int64_t per_group16 = (int64_t)((buffer_bytes - 16) / 16 / groups);
+      hipLaunchKernelGGL(probe_global_read_kernel, dim3(groups), dim3(kProbeThreads), 0, s,
+                         reinterpret_cast<const f32x4 *>(fbuf + 4), fbuf, per_group16, per_group16, iters);
+      *work_out = 16.0 * (double)per_group16 * groups * iters;                          // bytes read from HBM
+      break;
+    }
+    default:
+      return fail(LUTKAN_EINVAL, "%s: unknown kind %d", who, kind);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(LUTKAN_EHIP, "%s: %s", who, hipGetErrorString(e));
+  return LUTKAN_OK;
+}
