@@ -62,6 +62,10 @@ def lib():
         L.lko_artifact_bytes.argtypes = [C.c_long, C.c_int, C.c_int, C.c_int]
         L.lko_artifact_bytes.restype = C.c_long
         L.lko_max_threads.restype = C.c_int
+        L.lko_round_to_fp16.argtypes = [C.c_float]
+        L.lko_round_to_fp16.restype = C.c_float
+        L.lko_round_params_fp16.argtypes = [C.c_void_p, C.c_long]
+        L.lko_round_params_fp16.restype = C.c_long
         _lib = L
     return _lib
 
@@ -110,8 +114,13 @@ def quantize_segment(v, scheme: int):
     return q, np.float32(a[0]), np.float32(y0[0])
 
 
-def compile_layer(d, m, G, p, ext_knots, coef, L, scheme, want_v=False, nthreads=None):
-    """Artifact arrays of Sec. 4.6: knots [K+1], q [E,K,L] (e=i*m+j), scale [E,K], y_min [E,K]."""
+def round_to_fp16(x: float) -> float:
+    return float(lib().lko_round_to_fp16(float(np.float32(x))))
+
+
+def compile_layer(d, m, G, p, ext_knots, coef, L, scheme, want_v=False, nthreads=None, param_fp16=False):
+    """Artifact arrays of Sec. 4.6: knots [K+1], q [E,K,L] (e=i*m+j), scale [E,K], y_min [E,K].
+    param_fp16: scale and y_min are stored rounded to binary16 (held here as fp32 arrays of those values)."""
     tau = _f32(ext_knots)
     coef = _f32(coef)
     assert tau.size == G + 2 * p + 1 and coef.size == d * m * (G + p)
@@ -125,7 +134,12 @@ def compile_layer(d, m, G, p, ext_knots, coef, L, scheme, want_v=False, nthreads
                            nthreads or default_threads())
     if rc != 0:
         raise ValueError(f"lko_compile failed: {rc}")
-    return SimpleNamespace(d=d, m=m, K=K, L=L, scheme=scheme, knots=knots, q=q, scale=scale, y_min=y_min, v=v)
+    if param_fp16:
+        lost = lib().lko_round_params_fp16(_p(scale), scale.size) + lib().lko_round_params_fp16(_p(y_min), y_min.size)
+        if lost:
+            raise ValueError(f"{lost} dequantisation parameters do not fit binary16")
+    return SimpleNamespace(d=d, m=m, K=K, L=L, scheme=scheme, knots=knots, q=q, scale=scale, y_min=y_min, v=v,
+                           param_fp16=bool(param_fp16))
 
 
 def _edge_scalars(edge_scalars, E):

@@ -28,7 +28,8 @@
  *   - a segment with zero range stores alpha = 1 and all codes 0;
  *   - a NaN input is out of domain, is indexed like t_0, and makes every output of its row NaN
  *     under either oob_policy;
- *   - the B-spline layer applies the same boundary_mode / oob_policy to x before evaluating.
+ *   - the B-spline layer applies the same boundary_mode / oob_policy to x before evaluating;
+ *   - float16 parameters (Sec. 4.6): codes from the fp32 parameters, parameters then rounded to binary16.
  *
  * Parity pins: all functions here are pinned by closed forms, invariants, a library routine
  * (scipy.interpolate.BSpline, numpy.searchsorted) and brute force in tests/test_oracle_*.py.
@@ -353,6 +354,41 @@ int lko_bspline_forward(int d, int m, int G, int p, const float *tau_f, const fl
         }
     }
     return 0;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Half-precision dequantisation parameters (Sec. 4.6 allows scale and y_min to be stored as float16).
+ * Reading: the codes are computed from the fp32 parameters of Eq. 11-12; the parameters are then stored rounded
+ * to the nearest binary16 value (ties to even) and inference dequantises with the stored values (Eq. 10).
+ *
+ * lko_round_to_fp16: the binary16 value nearest to x, returned as a float.  binary16 has 10 fraction bits, normal
+ * exponents -14..15 and subnormals that are multiples of 2^-24; its largest finite value is 65504, and everything
+ * from the midpoint 65520 upwards rounds to infinity.
+ * ---------------------------------------------------------------------------------------- */
+float lko_round_to_fp16(float x)
+{
+    if (x != x || x == 0.0f) return x;
+    double a = fabs((double)x);
+    if (a >= 65520.0) return copysignf(INFINITY, x);
+    int e;
+    (void)frexp(a, &e);                 /* a = f * 2^e with f in [0.5, 1): the leading bit has weight 2^(e-1) */
+    int lead = e - 1;
+    if (lead < -14) lead = -14;         /* subnormal range: fixed spacing 2^-24 */
+    double ulp = ldexp(1.0, lead - 10);
+    double r = nearbyint(a / ulp) * ulp;   /* a / ulp is exact; nearbyint rounds ties to even */
+    return copysignf((float)r, x);
+}
+
+/* Rounds n parameters in place; returns how many became infinite (values that do not fit binary16). */
+long lko_round_params_fp16(float *p, long n)
+{
+    long overflow = 0;
+    for (long t = 0; t < n; ++t) {
+        float r = lko_round_to_fp16(p[t]);
+        if (isinf(r) && !isinf(p[t])) ++overflow;
+        p[t] = r;
+    }
+    return overflow;
 }
 
 /* Bytes of the artifact arrays of Sec. 4.6 for E edges: codes + dequantisation parameters + knots. */

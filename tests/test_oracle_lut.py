@@ -481,3 +481,54 @@ def test_bspline_layer_spline_component_matches_fp64_closed_form():
             sp = BSpline(t64, s.coef[i, j].astype(np.float64), 3, extrapolate=False)(np.clip(x64[:, i], lo, np.nextafter(hi, -np.inf)))
             want[:, j] += float(so[e]) * (float(sb[e]) * x64[:, i] * expit(x64[:, i]) + float(ss[e]) * np.where(inside[:, i], sp, 0.0))
     np.testing.assert_allclose(r.y, want, rtol=2e-6, atol=2e-6)
+
+
+# ---------------------------------------------------------------------------------------------------
+# float16 dequantisation parameters (Sec. 4.6: scale and y_min "float16 or float32")
+# ---------------------------------------------------------------------------------------------------
+def test_round_to_fp16_is_the_library_cast():
+    """Pin: numpy's float32 -> float16 cast (IEEE round-to-nearest-even) on random values, exact ties, the
+    subnormal range and both sides of the overflow threshold."""
+    rng = np.random.default_rng(11)
+    ties = [1 + 2.0 ** -11, 1 + 3 * 2.0 ** -11, 2048 + 1, 2048 + 3, 2.0 ** -14 * (1 + 2.0 ** -11), 2.0 ** -25, 3 * 2.0 ** -25,
+            5 * 2.0 ** -25, 2.0 ** -24, 2.0 ** -26, 65504.0, 65519.996, 65520.0, 65535.0, 1e30, 0.0]
+    x = np.concatenate([rng.normal(0, 1, 20000), rng.normal(0, 1e-6, 10000), rng.uniform(-70000, 70000, 10000),
+                        ties, [-t for t in ties]]).astype(np.float32)
+    with np.errstate(over="ignore"):
+        want = x.astype(np.float16).astype(np.float32)
+    got = np.array([oracle.round_to_fp16(v) for v in x], dtype=np.float32)
+    assert np.array_equal(want, got)
+    assert np.array_equal(np.signbit(want), np.signbit(got))
+
+
+@pytest.mark.parametrize("scheme", [SYM_INT8, ASYM_UINT8])
+def test_fp16_params_keep_the_codes_and_round_the_parameters(scheme):
+    w = random_layer(61, 5, 6, 7, 16, scheme, CLOSED, CLIP_X, 8)
+    s = w.layers[0]
+    a32 = oracle.compile_layer(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, scheme)
+    a16 = oracle.compile_layer(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, scheme, param_fp16=True)
+    assert np.array_equal(a32.q, a16.q)
+    assert np.array_equal(a16.scale, a32.scale.astype(np.float16).astype(np.float32))
+    assert np.array_equal(a16.y_min, a32.y_min.astype(np.float16).astype(np.float32))
+    assert not np.array_equal(a16.scale, a32.scale)
+
+
+def test_fp16_params_forward_dequantises_with_the_stored_values():
+    """d = m = 1, x on a knot: w = 0 and the output is fl(y_min16 + fl(alpha16 * q)) of that segment's first code."""
+    w = random_layer(62, 1, 1, 6, 8, ASYM_UINT8, CLOSED, CLIP_X, 4)
+    s = w.layers[0]
+    art = oracle.compile_layer(1, 1, s.G, s.p, s.ext_knots, s.coef, s.L, ASYM_UINT8, param_fp16=True)
+    x = art.knots[:-1].reshape(-1, 1).copy()
+    out = oracle.lut_forward(art, CLOSED, CLIP_X, x)
+    for k in range(s.G):
+        a16, y16 = np.float32(np.float16(art.scale[0, k])), np.float32(np.float16(art.y_min[0, k]))
+        assert a16 == art.scale[0, k] and y16 == art.y_min[0, k]
+        want = np.float32(y16 + np.float32(a16 * np.float32(art.q[0, k, 0])))
+        assert out.y[k, 0] == want
+
+
+def test_fp16_params_that_do_not_fit_are_refused():
+    w = random_layer(63, 2, 2, 5, 8, SYM_INT8, CLOSED, CLIP_X, 4)
+    s = w.layers[0]
+    with pytest.raises(ValueError):
+        oracle.compile_layer(s.d, s.m, s.G, s.p, s.ext_knots, s.coef * np.float32(1e8), s.L, SYM_INT8, param_fp16=True)

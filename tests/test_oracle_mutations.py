@@ -32,6 +32,9 @@ MUTATIONS = {
     "edge_output_scale_dropped": ("float phi = s_out * sum;", "float phi = sum;"),
     "spline_scale_on_base": ("float tb = s_base * b;\n    float ts = s_spline * spline_term;", "float tb = s_spline * b;\n    float ts = s_base * spline_term;"),
     "bspline_layer_masks_base_too": ("                if (masked) { s = 0.0; sa = 0.0; }\n                if (edge_out) {", "                if (edge_out) {"),
+    "fp16_params_truncated": ("double r = nearbyint(a / ulp) * ulp;", "double r = floor(a / ulp) * ulp;"),
+    "fp16_params_no_subnormals": ("if (lead < -14) lead = -14;", "if (lead < -24) lead = -24;"),
+    "fp16_params_overflow_late": ("if (a >= 65520.0) return", "if (a > 65535.0) return"),
     "layer_sum_skips_first_input": ("for (int i = 0; i < d; ++i) {\n            lko_index ix;\n            lko_locate(knots", "for (int i = (d > 1); i < d; ++i) {\n            lko_index ix;\n            lko_locate(knots"),
 }
 
