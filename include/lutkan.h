@@ -33,7 +33,8 @@ typedef enum {
   LUTKAN_ESHAPE = -2,        /* sizes that do not fit together (workspace too small, d/m mismatch in a chain) */
   LUTKAN_ENOMEM = -3,        /* host allocation failed */
   LUTKAN_EHIP = -4,          /* a HIP runtime call failed */
-  LUTKAN_EUNSUPPORTED = -5   /* degree != 3, K > LUTKAN_MAX_K, K*L > LUTKAN_MAX_ROWS */
+  LUTKAN_EUNSUPPORTED = -5   /* degree != 3, K > LUTKAN_MAX_K, K*L > LUTKAN_MAX_ROWS, fp16 parameters out of range or
+                                combined with spline_component */
 } lutkan_status;
 
 typedef enum { LUTKAN_SYM_INT8 = 0, LUTKAN_ASYM_UINT8 = 1 } lutkan_scheme;        /* Sec. 4.4, Eq. 11-12 */
@@ -41,6 +42,7 @@ typedef enum { LUTKAN_HALF_OPEN = 0, LUTKAN_CLOSED = 1 } lutkan_boundary;       
 typedef enum { LUTKAN_CLIP_X = 0, LUTKAN_ZERO_SPLINE = 1 } lutkan_oob;             /* Sec. 5.4 */
 typedef enum { LUTKAN_ALGO_AUTO = 0, LUTKAN_ALGO_GATHER = 1, LUTKAN_ALGO_TILED = 2 } lutkan_algo;
 typedef enum { LUTKAN_REPR_PHI = 0, LUTKAN_REPR_SPLINE_COMPONENT = 1 } lutkan_value_repr;  /* Sec. 4.3 A / B */
+typedef enum { LUTKAN_PARAM_FP32 = 0, LUTKAN_PARAM_FP16 = 1 } lutkan_param_dtype;   /* Sec. 4.6: dtype of scale, y_min */
 
 #define LUTKAN_MAX_K 64            /* segments per layer (the knot vector travels in the kernel arguments) */
 #define LUTKAN_MAX_ROWS 65535      /* K * L, table rows per input (a row index travels in 16 bits) */
@@ -73,19 +75,23 @@ typedef struct {
   const float *edge_base_scale;    /* s_base   [d][m], spline_component only */
   const float *edge_spline_scale;  /* s_spline [d][m] */
   const float *edge_out_scale;     /* s_out    [d][m] */
+  int32_t param_dtype;       /* lutkan_param_dtype.  FP16: the codes are computed from the fp32 alpha and y_min of
+                                Eq. 11-12, then both are stored rounded to the nearest binary16 value and inference
+                                dequantises with the stored values (Eq. 10).  Not available with spline_component;
+                                EUNSUPPORTED if a parameter is too large for binary16. */
 } lutkan_layer_desc;
 
 typedef struct lutkan_artifact lutkan_artifact;     /* opaque, host memory */
 
 typedef struct {
-  int32_t d, m, K, L, G, degree, scheme, boundary, oob, value_repr;
+  int32_t d, m, K, L, G, degree, scheme, boundary, oob, value_repr, param_dtype;
   int32_t jt;                /* column-tile width of the device tables (a power of two <= 128, or 128) */
   int32_t n_tiles;           /* ceil(m / jt) */
   int32_t blob_bytes;        /* bytes of one (tile, input) slice of the LUT device table */
   int32_t coef_blob_bytes;   /* bytes of one (tile, input) slice of the B-spline device table */
   float t0, tK, tK_star;     /* domain ends and the safe upper clip value of Eq. 13 */
   size_t q_canonical_bytes;  /* d*m*K*L */
-  size_t params_canonical_bytes; /* d*m*K*4, for scale and for y_min each */
+  size_t params_canonical_bytes; /* d*m*K*4 (d*m*K*2 with fp16 parameters), for scale and for y_min each */
   size_t table_bytes;        /* whole LUT device table = n_tiles*d*blob_bytes */
   size_t coef_table_bytes;   /* whole B-spline device table = n_tiles*d*coef_blob_bytes */
   size_t artifact_bytes;     /* Sec. 4.6 arrays: q + scale + y_min + knots (what Sec. 6.6 "LUT artifact bytes" counts) */
@@ -100,7 +106,7 @@ int lutkan_artifact_info(const lutkan_artifact *a, lutkan_info *out);
 
 /* Read-only host views, valid until lutkan_artifact_free.  Canonical arrays (Sec. 4.6), edge e = i*m + j: */
 const void *lutkan_artifact_q(const lutkan_artifact *a);          /* int8 or uint8 [E][K][L] */
-const float *lutkan_artifact_scale(const lutkan_artifact *a);     /* alpha  [E][K] */
+const float *lutkan_artifact_scale(const lutkan_artifact *a);     /* alpha  [E][K] (fp16 parameters: the rounded values, as floats) */
 const float *lutkan_artifact_ymin(const lutkan_artifact *a);      /* y_min  [E][K] (zeros for symmetric) */
 const float *lutkan_artifact_knots(const lutkan_artifact *a);     /* [K+1] */
 const float *lutkan_artifact_ext_knots(const lutkan_artifact *a); /* [G+2p+1] */
@@ -112,7 +118,8 @@ const float *lutkan_artifact_edge_out_scale(const lutkan_artifact *a);    /* [E]
  * last tile is zero padded.  LUT table: for tile t and input i one contiguous slice of blob_bytes bytes
  *     float   base  [jt]                       (spline_component only: s_out * s_base of the edge (i, column))
  *     param   p     [K+1][jt]                  (symmetric: fp32 alpha; asymmetric: the fp32 pair {alpha, y_min} --
- *                                               y_min is elided when it is identically 0, Sec. 7.5; row K is all zero)
+ *                                               y_min is elided when it is identically 0, Sec. 7.5; row K is all zero;
+ *                                               with fp16 parameters each value is a binary16)
  *     code    q     [K*L+2][jt]                (one byte per code, row k*L+l, i.e. the [i][segment][sample][j]
  *                                               order per tile: uint8 codes as they are, int8 codes excess-128,
  *                                               byte = q + 128; the two trailing rows are all-zero bytes)
@@ -128,7 +135,7 @@ const void *lutkan_artifact_coef_table(const lutkan_artifact *a);
  * Device side.  The structs are plain host structs; the pointers inside are DEVICE pointers.
  * ---------------------------------------------------------------------------------------------- */
 typedef struct {
-  int32_t d, m, K, L, scheme, boundary, oob, value_repr;
+  int32_t d, m, K, L, scheme, boundary, oob, value_repr, param_dtype;
   int32_t jt, n_tiles, blob_bytes;
   int32_t algo;                       /* lutkan_algo; AUTO picks by shape */
   float knots[LUTKAN_MAX_K + 1];      /* host copy of T, entries 0..K used */

@@ -13,6 +13,7 @@ SYM_INT8, ASYM_UINT8 = 0, 1
 HALF_OPEN, CLOSED = 0, 1
 CLIP_X, ZERO_SPLINE = 0, 1
 ALGO_AUTO, ALGO_GATHER, ALGO_TILED = 0, 1, 2
+PARAM_FP32, PARAM_FP16 = 0, 1
 PROBE_VALU_FMA, PROBE_LDS_READ, PROBE_L2_READ, PROBE_HBM_READ = 0, 1, 2, 3
 REPR_PHI, REPR_SPLINE_COMPONENT = 0, 1
 MAX_K = 64
@@ -27,20 +28,20 @@ class _LayerDesc(C.Structure):
                 ("ext_knots", C.c_void_p), ("coef", C.c_void_p),
                 ("L", C.c_int32), ("scheme", C.c_int32), ("boundary", C.c_int32), ("oob", C.c_int32),
                 ("value_repr", C.c_int32), ("edge_base_scale", C.c_void_p), ("edge_spline_scale", C.c_void_p),
-                ("edge_out_scale", C.c_void_p)]
+                ("edge_out_scale", C.c_void_p), ("param_dtype", C.c_int32)]
 
 
 class _Info(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("d", "m", "K", "L", "G", "degree", "scheme", "boundary", "oob", "value_repr",
-                                         "jt", "n_tiles", "blob_bytes", "coef_blob_bytes")] + \
+                                         "param_dtype", "jt", "n_tiles", "blob_bytes", "coef_blob_bytes")] + \
                [("t0", C.c_float), ("tK", C.c_float), ("tK_star", C.c_float)] + \
                [(n, C.c_size_t) for n in ("q_canonical_bytes", "params_canonical_bytes", "table_bytes",
                                           "coef_table_bytes", "artifact_bytes")]
 
 
 class _DevLayer(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("d", "m", "K", "L", "scheme", "boundary", "oob", "value_repr", "jt", "n_tiles",
-                                         "blob_bytes", "algo")] + \
+    _fields_ = [(n, C.c_int32) for n in ("d", "m", "K", "L", "scheme", "boundary", "oob", "value_repr", "param_dtype",
+                                         "jt", "n_tiles", "blob_bytes", "algo")] + \
                [("knots", C.c_float * (MAX_K + 1)), ("table", C.c_void_p)]
 
 
@@ -166,9 +167,10 @@ class Artifact:
 
 
 def lutkan_compile(d: int, m: int, G: int, degree: int, ext_knots, coef, L: int, scheme: int, boundary: int,
-                   oob: int, n_threads: int = 0, edge_scales=None) -> Artifact:
+                   oob: int, n_threads: int = 0, edge_scales=None, param_dtype: int = PARAM_FP32) -> Artifact:
     """Host-only LUT compilation of one dense B-spline KAN layer (Sec. 4.2-4.6).
-    edge_scales = (s_base, s_spline, s_out), each [d, m], selects value_repr = spline_component (Eq. 2)."""
+    edge_scales = (s_base, s_spline, s_out), each [d, m], selects value_repr = spline_component (Eq. 2).
+    param_dtype = PARAM_FP16 stores scale and y_min as binary16 values (Sec. 4.6)."""
     lib = load_library()
     tau = np.ascontiguousarray(ext_knots, dtype=np.float32)
     cf = np.ascontiguousarray(coef, dtype=np.float32)
@@ -179,6 +181,7 @@ def lutkan_compile(d: int, m: int, G: int, degree: int, ext_knots, coef, L: int,
         raise LutKanError("lutkan_compile: every edge scale array needs d*m elements")
     desc = _LayerDesc(d, m, G, degree, tau.ctypes.data, cf.ctypes.data, L, scheme, boundary, oob,
                       REPR_SPLINE_COMPONENT if keep else REPR_PHI, *[a.ctypes.data for a in keep])
+    desc.param_dtype = param_dtype
     out = C.c_void_p()
     _check(lib.lutkan_compile(C.byref(desc), n_threads, C.byref(out)))
     return Artifact(out.value)

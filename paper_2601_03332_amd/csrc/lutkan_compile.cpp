@@ -10,6 +10,7 @@
 // fp32; quantisation is fp32 with one rounding per operation and round-half-to-even.  This file must be
 // compiled without FMA contraction.
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -29,10 +30,10 @@ int fail(int code, const char *fmt, ...) {
   return code;
 }
 
-int choose_jt(int m, int K, int L, int scheme, int value_repr) {
+int choose_jt(int m, int K, int L, int scheme, int value_repr, int param_dtype) {
   int jt = 4;
   while (jt < m && jt < 128) jt *= 2;
-  while (jt > 32 && blob_layout(K, L, jt, scheme, value_repr).bytes > kLdsSliceBudget) jt /= 2;
+  while (jt > 32 && blob_layout(K, L, jt, scheme, value_repr, param_dtype).bytes > kLdsSliceBudget) jt /= 2;
   return jt;
 }
 
@@ -108,6 +109,21 @@ SegmentCodes quantise_asymmetric(const float *v, int L, uint8_t *q) {
   return {alpha, lo};
 }
 
+// Sec. 4.6 lets scale and y_min be stored as float16: the nearest binary16 value (the conversion rounds to nearest,
+// ties to even) and its bit pattern for the device table.
+struct HalfValue {
+  float value;
+  uint16_t bits;
+};
+
+HalfValue to_binary16(float x) {
+  const _Float16 h = (_Float16)x;
+  HalfValue out;
+  out.value = (float)h;
+  std::memcpy(&out.bits, &h, sizeof(out.bits));
+  return out;
+}
+
 }  // namespace
 }  // namespace lutkan
 
@@ -127,7 +143,11 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
   if (desc->boundary != LUTKAN_HALF_OPEN && desc->boundary != LUTKAN_CLOSED) return fail(LUTKAN_EINVAL, "lutkan_compile: bad boundary_mode %d", desc->boundary);
   if (desc->oob != LUTKAN_CLIP_X && desc->oob != LUTKAN_ZERO_SPLINE) return fail(LUTKAN_EINVAL, "lutkan_compile: bad oob_policy %d", desc->oob);
   if (desc->value_repr != LUTKAN_REPR_PHI && desc->value_repr != LUTKAN_REPR_SPLINE_COMPONENT) return fail(LUTKAN_EINVAL, "lutkan_compile: bad value_repr %d", desc->value_repr);
+  if (desc->param_dtype != LUTKAN_PARAM_FP32 && desc->param_dtype != LUTKAN_PARAM_FP16) return fail(LUTKAN_EINVAL, "lutkan_compile: bad param_dtype %d", desc->param_dtype);
+  const bool half_params = (desc->param_dtype == LUTKAN_PARAM_FP16);
   const bool with_base = (desc->value_repr == LUTKAN_REPR_SPLINE_COMPONENT);
+  if (half_params && with_base)
+    return fail(LUTKAN_EUNSUPPORTED, "lutkan_compile: float16 parameters are not available with value_repr = spline_component");
   if (with_base && (!desc->edge_base_scale || !desc->edge_spline_scale || !desc->edge_out_scale))
     return fail(LUTKAN_EINVAL, "lutkan_compile: spline_component needs edge_base_scale, edge_spline_scale and edge_out_scale");
   const int K = G, R = G + P, n_knots = G + 2 * P + 1;
@@ -149,9 +169,9 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
   if (!a) return fail(LUTKAN_ENOMEM, "lutkan_compile: out of host memory");
   const int scheme = desc->scheme;
   const int repr = desc->value_repr;
-  const int jt = choose_jt(m, K, L, scheme, repr);
+  const int jt = choose_jt(m, K, L, scheme, repr, desc->param_dtype);
   const int n_tiles = (m + jt - 1) / jt;
-  const BlobLayout lay = blob_layout(K, L, jt, scheme, repr);
+  const BlobLayout lay = blob_layout(K, L, jt, scheme, repr, desc->param_dtype);
   const int coef_rows = coef_slice_rows(R, repr);
   const int coef_blob = coef_rows * jt * 4;
   try {
@@ -186,6 +206,7 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
   int nt = n_threads > 0 ? n_threads : (int)std::thread::hardware_concurrency();
   nt = std::max(1, std::min(nt, 64));
   nt = (int)std::min<size_t>((size_t)nt, (size_t)d);
+  std::atomic<long> unrepresentable{0};       // float16 parameters that overflowed
   auto work = [&](int tid) {
     std::vector<float> v((size_t)L);
     for (int i = tid; i < d; i += nt) {
@@ -195,6 +216,7 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
         const int t = j / jt, jj = j % jt;
         uint8_t *slice = a->table.data() + ((size_t)t * d + i) * lay.bytes;
         float *slice_params = reinterpret_cast<float *>(slice + lay.params_off);
+        uint16_t *slice_params16 = reinterpret_cast<uint16_t *>(slice + lay.params_off);
         uint8_t *slice_codes = slice + lay.codes_off;
         float *cslice = a->coef_table.data() + ((size_t)t * d + i) * coef_rows * jt;
         // spline_component (Eq. 2): the device tables carry s_out*s_base per edge as an extra row and fold
@@ -223,13 +245,26 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
           const SegmentCodes sc = (scheme == LUTKAN_SYM_INT8)
                                       ? quantise_symmetric(v.data(), L, reinterpret_cast<int8_t *>(qc))
                                       : quantise_asymmetric(v.data(), L, qc);
-          a->scale[e * K + k] = sc.alpha;
-          a->ymin[e * K + k] = sc.ymin;
-          if (scheme == LUTKAN_ASYM_UINT8) {
-            slice_params[((size_t)k * jt + jj) * 2] = with_base ? spline_gain * sc.alpha : sc.alpha;
-            slice_params[((size_t)k * jt + jj) * 2 + 1] = with_base ? spline_gain * sc.ymin : sc.ymin;
+          if (half_params) {
+            const HalfValue ha = to_binary16(sc.alpha), hy = to_binary16(sc.ymin);
+            if (std::isinf(ha.value) || std::isinf(hy.value)) unrepresentable.fetch_add(1);
+            a->scale[e * K + k] = ha.value;
+            a->ymin[e * K + k] = hy.value;
+            if (scheme == LUTKAN_ASYM_UINT8) {
+              slice_params16[((size_t)k * jt + jj) * 2] = ha.bits;
+              slice_params16[((size_t)k * jt + jj) * 2 + 1] = hy.bits;
+            } else {
+              slice_params16[(size_t)k * jt + jj] = ha.bits;
+            }
           } else {
-            slice_params[(size_t)k * jt + jj] = with_base ? spline_gain * sc.alpha : sc.alpha;
+            a->scale[e * K + k] = sc.alpha;
+            a->ymin[e * K + k] = sc.ymin;
+            if (scheme == LUTKAN_ASYM_UINT8) {
+              slice_params[((size_t)k * jt + jj) * 2] = with_base ? spline_gain * sc.alpha : sc.alpha;
+              slice_params[((size_t)k * jt + jj) * 2 + 1] = with_base ? spline_gain * sc.ymin : sc.ymin;
+            } else {
+              slice_params[(size_t)k * jt + jj] = with_base ? spline_gain * sc.alpha : sc.alpha;
+            }
           }
           // device codes: uint8 as is; int8 stored excess-128 (q + 128), which the kernels undo exactly
           const uint8_t flip = (scheme == LUTKAN_SYM_INT8) ? 0x80 : 0x00;
@@ -246,15 +281,21 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
     for (auto &th : pool) th.join();
   }
 
+  if (unrepresentable.load() != 0) {
+    const long n = unrepresentable.load();
+    delete a;
+    return fail(LUTKAN_EUNSUPPORTED, "lutkan_compile: %ld segments have an alpha or y_min too large for float16", n);
+  }
+
   lutkan_info &I = a->info;
   std::memset(&I, 0, sizeof(I));
   I.d = d; I.m = m; I.K = K; I.L = L; I.G = G; I.degree = P;
-  I.scheme = scheme; I.boundary = desc->boundary; I.oob = desc->oob; I.value_repr = repr;
+  I.scheme = scheme; I.boundary = desc->boundary; I.oob = desc->oob; I.value_repr = repr; I.param_dtype = desc->param_dtype;
   I.jt = jt; I.n_tiles = n_tiles; I.blob_bytes = lay.bytes; I.coef_blob_bytes = coef_blob;
   I.t0 = a->knots[0]; I.tK = a->knots[K];
   I.tK_star = (desc->boundary == LUTKAN_CLOSED) ? I.tK : std::nextafterf(I.tK, -INFINITY);  // Eq. 13
   I.q_canonical_bytes = E * K * L;
-  I.params_canonical_bytes = E * K * 4;
+  I.params_canonical_bytes = E * K * (half_params ? 2 : 4);
   I.table_bytes = a->table.size();
   I.coef_table_bytes = a->coef_table.size() * 4;
   I.artifact_bytes = I.q_canonical_bytes + 2 * I.params_canonical_bytes + 4 * (size_t)(K + 1) + (with_base ? 12 * E : 0);
@@ -287,6 +328,7 @@ extern "C" int lutkan_dev_layer_init(const lutkan_artifact *a, lutkan_dev_layer 
   const lutkan_info &I = a->info;
   out->d = I.d; out->m = I.m; out->K = I.K; out->L = I.L;
   out->scheme = I.scheme; out->boundary = I.boundary; out->oob = I.oob; out->value_repr = I.value_repr;
+  out->param_dtype = I.param_dtype;
   out->jt = I.jt; out->n_tiles = I.n_tiles; out->blob_bytes = I.blob_bytes;
   out->algo = LUTKAN_ALGO_AUTO;
   for (int k = 0; k <= I.K; ++k) out->knots[k] = a->knots[k];

@@ -16,16 +16,16 @@ int fail(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
 
 // Byte offsets inside one (tile, input) slice of the LUT device table:
 //   [base jt f32 (spline_component only)][params (K+1) rows of jt entries][codes (K*L+2) rows of jt bytes][pad to 16 B]
-// A parameter entry is the fp32 alpha (symmetric) or the fp32 pair {alpha, y_min} (asymmetric).
+// A parameter entry is alpha (symmetric) or the pair {alpha, y_min} (asymmetric), fp32 or binary16 values.
 // Parameter row K and code rows K*L, K*L+1 are all zero: the kernels send masked inputs there.
 struct BlobLayout {
   int32_t params_off, param_row_bytes, codes_off, bytes;
 };
 
-inline BlobLayout blob_layout(int K, int L, int jt, int scheme, int value_repr) {
+inline BlobLayout blob_layout(int K, int L, int jt, int scheme, int value_repr, int param_dtype) {
   BlobLayout b;
   b.params_off = (value_repr == LUTKAN_REPR_SPLINE_COMPONENT) ? jt * 4 : 0;
-  b.param_row_bytes = jt * ((scheme == LUTKAN_ASYM_UINT8) ? 8 : 4);
+  b.param_row_bytes = jt * ((scheme == LUTKAN_ASYM_UINT8) ? 2 : 1) * ((param_dtype == LUTKAN_PARAM_FP16) ? 2 : 4);
   b.codes_off = b.params_off + (K + 1) * b.param_row_bytes;
   int raw = b.codes_off + (K * L + 2) * jt;
   b.bytes = (raw + 15) & ~15;
@@ -41,7 +41,7 @@ constexpr int kLdsSliceBudget = 56 * 1024;
 
 // Column-tile width for a layer: the widest of 128 / 64 / 32 columns whose slice fits the LDS budget (32 if
 // none does; such layers run on the gather kernel), and for narrow layers the next power of two >= m (>= 4).
-int choose_jt(int m, int K, int L, int scheme, int value_repr);
+int choose_jt(int m, int K, int L, int scheme, int value_repr, int param_dtype);
 
 }  // namespace lutkan
 

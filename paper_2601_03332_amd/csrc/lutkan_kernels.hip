@@ -191,6 +191,7 @@ struct EdgeArgs {
   int32_t jt, n_tiles, blob_bytes;
   int32_t codes_off, params_off, param_row_bytes;
   int32_t with_base;       // value_repr = spline_component: slices start with a row of s_out*s_base, records carry SiLU(x)
+  int32_t param_fp16;      // dequantisation parameters are binary16 values (Sec. 4.6), else fp32
   const int32_t *k_out, *l0_out;   // code trace only: the located (k, l0) of every (row, input), [B][d]
   int32_t chunk;           // tiled kernels: inputs per work-group (blockIdx.y selects the chunk of inputs)
   int64_t split_stride;    // tiled kernels: floats between the partial outputs of consecutive chunks (0 if one chunk)
@@ -226,7 +227,7 @@ __global__ __launch_bounds__(256) void lutkan_gather_kernel(const EdgeArgs a, co
   if (j >= a.m || b >= a.B) return;
   const int t = j / a.jt, jj = j - t * a.jt;
   const unsigned char *tile = a.table + (size_t)t * a.d * a.blob_bytes;
-  const int poff = (SCHEME == LUTKAN_ASYM_UINT8) ? 8 * jj : 4 * jj;
+  const int poff = ((SCHEME == LUTKAN_ASYM_UINT8) ? 8 * jj : 4 * jj) >> (a.param_fp16 ? 1 : 0);
   const int rec_words = a.with_base ? 4 : 2;
   const unsigned *recs = static_cast<const unsigned *>(a.rec);
   float acc = 0.0f;
@@ -248,9 +249,15 @@ __global__ __launch_bounds__(256) void lutkan_gather_kernel(const EdgeArgs a, co
       const unsigned param_off = (unsigned)a.params_off + (rec[u].x >> 16) * (unsigned)a.param_row_bytes;
       c0[u] = slice[code_off + jj];
       c1[u] = slice[code_off + a.jt + jj];
-      const float *prm = reinterpret_cast<const float *>(slice + param_off + poff);
-      al[u] = prm[0];
-      ym[u] = (SCHEME == LUTKAN_ASYM_UINT8) ? prm[1] : 0.0f;
+      if (a.param_fp16) {
+        const _Float16 *prm = reinterpret_cast<const _Float16 *>(slice + param_off + poff);
+        al[u] = (float)prm[0];
+        ym[u] = (SCHEME == LUTKAN_ASYM_UINT8) ? (float)prm[1] : 0.0f;
+      } else {
+        const float *prm = reinterpret_cast<const float *>(slice + param_off + poff);
+        al[u] = prm[0];
+        ym[u] = (SCHEME == LUTKAN_ASYM_UINT8) ? prm[1] : 0.0f;
+      }
       bg[u] = a.with_base ? reinterpret_cast<const float *>(slice)[jj] : 0.0f;
     }
 #pragma unroll
@@ -328,14 +335,18 @@ __device__ __forceinline__ void stage_slice(const u32x4 *gsrc, unsigned char *ld
 // next segment's first row, or a zero row) does not change the result.
 // With BASE (value_repr = spline_component) every slice starts with a row of s_out*s_base; a lane loads its four
 // values once per input and adds base * SiLU(x) per row, SiLU(x) being the third word of the row's record.
-template <int SCHEME, int LPR, int NP, int NW, bool BASE>
+// With PH the dequantisation parameters are binary16 values: half the LDS bytes per edge; they enter the same FMAs
+// through the mixed-precision form (fp16 factor, fp32 product and sum), so the arithmetic is that of the fp32 path
+// on the stored values.
+template <int SCHEME, int LPR, int NP, int NW, bool BASE, bool PH>
 __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a) {
   extern __shared__ __align__(16) unsigned char lds[];
   constexpr int JT = 4 * LPR;
   constexpr int RPS = 64 / LPR;
   constexpr int RW = RPS * NP;
   static_assert(RW <= 64, "a wave's records for one input must fit one 1 KiB copy step");
-  constexpr int PSZ = (SCHEME == LUTKAN_ASYM_UINT8) ? 32 : 16;   // parameter bytes per lane (4 columns)
+  constexpr int PSZ = ((SCHEME == LUTKAN_ASYM_UINT8) ? 32 : 16) / (PH ? 2 : 1);   // parameter bytes per lane (4 columns)
+  static_assert(!(BASE && PH), "float16 parameters are not combined with the base branch");
   constexpr int RB = BASE ? 16 : 8;                              // bytes per record
   constexpr int REC_LANES = RW * RB / 16;                        // lanes that copy 16 bytes of the wave's records
   static_assert((RW * RB) % 16 == 0, "a wave's records are whole 16-byte vectors");
@@ -389,6 +400,8 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
     typedef typename std::conditional<BASE, u32x3, u32x2>::type rec_t;        // 12-byte or 8-byte LDS read
     f32x4 base_gain = {0.f, 0.f, 0.f, 0.f};
     if (BASE) base_gain = *reinterpret_cast<const f32x4 *>(slice + sub * 16) * kTwoToMinus24;
+    // parameters of the lane's 4 columns as loaded: fp32 {a0,a1,a2,a3} or {a0,y0,a1,y1},{a2,y2,a3,y3};
+    // binary16: the same values packed two per word, in pa.x, pa.y (symmetric) or pa.x .. pa.w (asymmetric)
     struct Fetched { unsigned c0, c1; f32x4 pa, pb; };
     auto fetch = [&](const rec_t &rc) {
       Fetched f;
@@ -402,8 +415,15 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
       typedef const __attribute__((address_space(3))) f32x4 *lds_f32x4;
       f.c0 = *(lds_u32)cp;
       f.c1 = *(lds_u32)(cp + JT);
-      f.pa = *(lds_f32x4)pp;
-      f.pb = (SCHEME == LUTKAN_ASYM_UINT8) ? *(lds_f32x4)(pp + 16) : f32x4{0.f, 0.f, 0.f, 0.f};
+      if constexpr (PH && SCHEME == LUTKAN_SYM_INT8) {
+        typedef const __attribute__((address_space(3))) f32x2 *lds_f32x2;
+        const f32x2 h = *(lds_f32x2)pp;
+        f.pa = f32x4{h.x, h.y, 0.f, 0.f};
+        f.pb = f32x4{0.f, 0.f, 0.f, 0.f};
+      } else {
+        f.pa = *(lds_f32x4)pp;
+        f.pb = (SCHEME == LUTKAN_ASYM_UINT8 && !PH) ? *(lds_f32x4)(pp + 16) : f32x4{0.f, 0.f, 0.f, 0.f};
+      }
       return f;
     };
     rec_t rc_cur = *reinterpret_cast<const rec_t *>(rec_buf);
@@ -413,15 +433,25 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
     for (int p = 0; p < NP; ++p) {
       Fetched f_nxt = f_cur;
       rec_t rc_nn = rc_nxt;
-      if (SCHEME == LUTKAN_ASYM_UINT8) asm volatile("" ::"v"(f_cur.pb));
-      asm volatile("" ::"v"(f_cur.pa), "v"(f_cur.c1), "v"(rc_nxt.y));          // first touch of step p's data
+      if (SCHEME == LUTKAN_ASYM_UINT8 && !PH) asm volatile("" ::"v"(f_cur.pb));
+      asm volatile("" ::"v"(f_cur.pa.x), "v"(f_cur.c1), "v"(rc_nxt.y));        // first touch of step p's data
       __builtin_amdgcn_sched_barrier(0);
       if (p + 2 < NP) rc_nn = *reinterpret_cast<const rec_t *>(rec_buf + (p + 2) * (RPS * RB));
       if (p + 1 < NP) f_nxt = fetch(rc_nxt);
       __builtin_amdgcn_sched_barrier(0);
       const float w = __uint_as_float(rc_cur.y);
       float al[4], ym[4];
-      if (SCHEME == LUTKAN_ASYM_UINT8) {
+      if constexpr (PH) {
+        const f16x2 h0 = bits_to_f16x2(__float_as_uint(f_cur.pa.x)), h1 = bits_to_f16x2(__float_as_uint(f_cur.pa.y));
+        if (SCHEME == LUTKAN_ASYM_UINT8) {
+          const f16x2 h2 = bits_to_f16x2(__float_as_uint(f_cur.pa.z)), h3 = bits_to_f16x2(__float_as_uint(f_cur.pa.w));
+          al[0] = (float)h0.x; ym[0] = (float)h0.y; al[1] = (float)h1.x; ym[1] = (float)h1.y;
+          al[2] = (float)h2.x; ym[2] = (float)h2.y; al[3] = (float)h3.x; ym[3] = (float)h3.y;
+        } else {
+          al[0] = (float)h0.x; al[1] = (float)h0.y; al[2] = (float)h1.x; al[3] = (float)h1.y;
+          ym[0] = ym[1] = ym[2] = ym[3] = 0.0f;
+        }
+      } else if (SCHEME == LUTKAN_ASYM_UINT8) {
         al[0] = f_cur.pa.x; ym[0] = f_cur.pa.y; al[1] = f_cur.pa.z; ym[1] = f_cur.pa.w;
         al[2] = f_cur.pb.x; ym[2] = f_cur.pb.y; al[3] = f_cur.pb.z; ym[3] = f_cur.pb.w;
       } else {
@@ -798,11 +828,13 @@ int validate_layer(const lutkan_dev_layer *l, const char *who) {
   if (l->oob != LUTKAN_CLIP_X && l->oob != LUTKAN_ZERO_SPLINE) return fail(LUTKAN_EINVAL, "%s: bad oob_policy %d", who, l->oob);
   if (l->algo < LUTKAN_ALGO_AUTO || l->algo > LUTKAN_ALGO_TILED) return fail(LUTKAN_EINVAL, "%s: bad algo %d", who, l->algo);
   if (l->value_repr != LUTKAN_REPR_PHI && l->value_repr != LUTKAN_REPR_SPLINE_COMPONENT) return fail(LUTKAN_EINVAL, "%s: bad value_repr %d", who, l->value_repr);
+  if (l->param_dtype != LUTKAN_PARAM_FP32 && l->param_dtype != LUTKAN_PARAM_FP16) return fail(LUTKAN_EINVAL, "%s: bad param_dtype %d", who, l->param_dtype);
+  if (l->param_dtype == LUTKAN_PARAM_FP16 && l->value_repr == LUTKAN_REPR_SPLINE_COMPONENT) return fail(LUTKAN_EUNSUPPORTED, "%s: float16 parameters are not available with spline_component", who);
   for (int k = 0; k < l->K; ++k)
     if (!(l->knots[k] < l->knots[k + 1])) return fail(LUTKAN_EINVAL, "%s: knots not strictly increasing at %d", who, k);
   if (l->jt < 4 || l->jt > 128 || (l->jt & (l->jt - 1))) return fail(LUTKAN_EINVAL, "%s: jt=%d is not a power of two in [4,128]", who, l->jt);
   if (l->n_tiles != (l->m + l->jt - 1) / l->jt) return fail(LUTKAN_ESHAPE, "%s: n_tiles does not match m and jt", who);
-  if (l->blob_bytes != lutkan::blob_layout(l->K, l->L, l->jt, l->scheme, l->value_repr).bytes) return fail(LUTKAN_ESHAPE, "%s: blob_bytes does not match K, L, jt, scheme", who);
+  if (l->blob_bytes != lutkan::blob_layout(l->K, l->L, l->jt, l->scheme, l->value_repr, l->param_dtype).bytes) return fail(LUTKAN_ESHAPE, "%s: blob_bytes does not match K, L, jt, scheme, param_dtype", who);
   if ((reinterpret_cast<uintptr_t>(l->table) & 15) != 0) return fail(LUTKAN_EINVAL, "%s: table must be 16-byte aligned", who);
   return LUTKAN_OK;
 }
@@ -858,8 +890,10 @@ int launch_tiled_np(const EdgeArgs &ea, hipStream_t s) {
   const dim3 grid((unsigned)(row_tiles * ea.n_tiles), (unsigned)((ea.d + ea.chunk - 1) / ea.chunk));
   const size_t lds = 2 * (size_t)ea.blob_bytes + (size_t)NW * 2 * RW * (ea.with_base ? 16 : 8);
   static bool raised = false, raised_base = false;
-  if (ea.with_base) return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, true>, &raised_base, grid, lds, s, ea, "lutkan_tiled_kernel");
-  return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, false>, &raised, grid, lds, s, ea, "lutkan_tiled_kernel");
+  static bool raised_half = false;
+  if (ea.with_base) return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, true, false>, &raised_base, grid, lds, s, ea, "lutkan_tiled_kernel");
+  if (ea.param_fp16) return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, false, true>, &raised_half, grid, lds, s, ea, "lutkan_tiled_kernel");
+  return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, false, false>, &raised, grid, lds, s, ea, "lutkan_tiled_kernel");
 }
 
 template <int SCHEME, int LPR>
@@ -904,7 +938,7 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   if ((reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return fail(LUTKAN_EINVAL, "%s: workspace must be 256-byte aligned", who);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const int64_t Bp = padded_rows(B);
-  const lutkan::BlobLayout lay = lutkan::blob_layout(l->K, l->L, l->jt, l->scheme, l->value_repr);
+  const lutkan::BlobLayout lay = lutkan::blob_layout(l->K, l->L, l->jt, l->scheme, l->value_repr, l->param_dtype);
 
   LocateArgs la;
   la.x = x;
@@ -931,6 +965,7 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   ea.jt = l->jt; ea.n_tiles = l->n_tiles; ea.blob_bytes = l->blob_bytes;
   ea.codes_off = lay.codes_off; ea.params_off = lay.params_off; ea.param_row_bytes = lay.param_row_bytes;
   ea.with_base = with_base; ea.k_out = k_out; ea.l0_out = l0_out;
+  ea.param_fp16 = (l->param_dtype == LUTKAN_PARAM_FP16);
 
   bool tiled = tiled_supported(l->jt, l->blob_bytes) && !q01_out;
   if (l->algo == LUTKAN_ALGO_GATHER) tiled = false;

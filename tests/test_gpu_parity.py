@@ -27,17 +27,17 @@ def _say(msg):
 _COMPILED = {}
 
 
-def _compile_both(s):
+def _compile_both(s, param_fp16=False):
     """Library artifact + oracle artifact for a layer spec; the codes must already agree bit for bit.
     Cached per table content (the contract fields do not change the tables)."""
-    key = (s.d, s.m, s.G, s.L, s.scheme, hash(s.coef.tobytes()), hash(s.ext_knots.tobytes()),
+    key = (s.d, s.m, s.G, s.L, s.scheme, hash(s.coef.tobytes()), hash(s.ext_knots.tobytes()), param_fp16,
            None if s.edge_scales is None else hash(b"".join(a.tobytes() for a in s.edge_scales)))
     if key not in _COMPILED:
         if len(_COMPILED) > 4:
             _COMPILED.clear()
         art = lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, s.boundary, s.oob,
-                                edge_scales=s.edge_scales)
-        ora = oracle.compile_layer(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme)
+                                edge_scales=s.edge_scales, param_dtype=lk.PARAM_FP16 if param_fp16 else lk.PARAM_FP32)
+        ora = oracle.compile_layer(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, param_fp16=param_fp16)
         assert np.array_equal(art.q, ora.q) and np.array_equal(art.scale, ora.scale) and np.array_equal(art.y_min, ora.y_min)
         _COMPILED[key] = (art, ora)
     return _COMPILED[key]
@@ -57,12 +57,12 @@ def _assert_close(y_gpu, ref, what):
     return float(np.nanmax(err / tol))
 
 
-def _check_layer(s, x, algo, codes=False, what=""):
-    art, ora = _compile_both(s)
+def _check_layer(s, x, algo, codes=False, what="", param_fp16=False):
+    art, ora = _compile_both(s, param_fp16)
     layer = _device_layer(art, s, algo)
     xg = torch.from_numpy(x).to(DEV)
     _say(f"case {what} d={s.d} m={s.m} K={s.G} L={s.L} scheme={s.scheme} boundary={s.boundary} oob={s.oob} "
-         f"B={x.shape[0]} algo={algo} jt={art.info.jt}")
+         f"B={x.shape[0]} algo={algo} jt={art.info.jt} param_fp16={param_fp16}")
     y, k, l0, inside, w, q01 = lk.lutkan_forward_trace(layer, xg, codes=codes)
     stats = torch.zeros(2, dtype=torch.int64, device=DEV)
     y2 = lk.lutkan_forward(layer, xg, stats=stats)
@@ -133,6 +133,25 @@ def test_property_layers_tiled(case):
     w = random_layer(seed, d, m, G, L, scheme, boundary, oob, B, uniform=(seed % 2 == 0))
     _check_layer(w.layers[0], w.x, lk.ALGO_TILED, what=w.name)
     _check_layer(w.layers[0], w.x, lk.ALGO_GATHER, what=w.name)
+
+
+FP16_PARAM_CASES = [
+    # seed, d, m, G, L, scheme, boundary, oob, B          float16 scale / y_min (Sec. 4.6)
+    (601, 4, 3, 5, 16, SYM_INT8, CLOSED, CLIP_X, 200),                # 4-column tile
+    (602, 78, 16, 5, 64, ASYM_UINT8, CLOSED, CLIP_X, 3000),           # 16-column tile, inputs split
+    (603, 33, 130, 8, 64, ASYM_UINT8, HALF_OPEN, ZERO_SPLINE, 1025),  # 128-column tiles, ragged last tile
+    (604, 64, 256, 8, 128, SYM_INT8, CLOSED, ZERO_SPLINE, 2500),      # 64-column tiles
+    (605, 40, 300, 6, 16, SYM_INT8, HALF_OPEN, CLIP_X, 4099),
+    (606, 20, 64, 10, 64, ASYM_UINT8, CLOSED, CLIP_X, 17000),         # 16 row steps per wave
+]
+
+
+@pytest.mark.parametrize("case", FP16_PARAM_CASES, ids=lambda c: f"seed{c[0]}")
+def test_fp16_parameters(case):
+    seed, d, m, G, L, scheme, boundary, oob, B = case
+    w = random_layer(seed, d, m, G, L, scheme, boundary, oob, B, uniform=(seed % 2 == 0))
+    _check_layer(w.layers[0], w.x, lk.ALGO_TILED, what=w.name, param_fp16=True)
+    _check_layer(w.layers[0], w.x, lk.ALGO_GATHER, codes=(B * d * m <= 2_000_000), what=w.name, param_fp16=True)
 
 
 def test_special_inputs_nan_inf_all_oob():

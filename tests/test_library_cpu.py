@@ -210,3 +210,57 @@ def test_spline_component_tables_carry_the_base_row_and_folded_gains():
             np.testing.assert_array_equal(prm[:K, :n, 0], (gain[None, :] * art.scale[e].T).astype(np.float32))
             np.testing.assert_array_equal(prm[:K, :n, 1], (gain[None, :] * art.y_min[e].T).astype(np.float32))
             np.testing.assert_array_equal(ctab[t, i, 1:, :n], (gain[None, :] * s.coef[i, cols].T).astype(np.float32))
+
+
+@pytest.mark.parametrize("scheme", [SYM_INT8, ASYM_UINT8])
+def test_fp16_parameter_tables(scheme):
+    """Sec. 4.6 float16 scale / y_min: codes as with fp32 parameters, parameters bit-identical to the oracle's
+    rounding, device rows hold the binary16 bit patterns, the byte accounting halves the parameter bytes."""
+    w = random_layer(91, 3, 70, 6, 16, scheme, CLOSED, CLIP_X, 4)
+    s = w.layers[0]
+    art = lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, scheme, s.boundary, s.oob, param_dtype=lk.PARAM_FP16)
+    a32 = lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, scheme, s.boundary, s.oob)
+    ora = oracle.compile_layer(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, scheme, param_fp16=True)
+    np.testing.assert_array_equal(art.q, a32.q)
+    np.testing.assert_array_equal(art.q, ora.q)
+    np.testing.assert_array_equal(art.scale.view(np.uint32), ora.scale.view(np.uint32))
+    np.testing.assert_array_equal(art.y_min.view(np.uint32), ora.y_min.view(np.uint32))
+    I = art.info
+    assert I.param_dtype == lk.PARAM_FP16 and a32.info.param_dtype == lk.PARAM_FP32
+    K, L, jt, nt = I.K, I.L, I.jt, I.n_tiles
+    per = 2 if scheme == ASYM_UINT8 else 1
+    codes_off = (K + 1) * jt * 2 * per
+    assert I.blob_bytes == (codes_off + (K * L + 2) * jt + 15) // 16 * 16
+    assert I.params_canonical_bytes == s.d * s.m * K * 2
+    assert I.artifact_bytes == oracle.artifact_bytes(s.d * s.m, K, L, 4)
+    tab = art.table.reshape(nt, s.d, I.blob_bytes)
+    for t in range(nt):
+        cols = np.arange(t * jt, min(s.m, (t + 1) * jt))
+        n = cols.size
+        for i in range(s.d):
+            e = i * s.m + cols
+            prm = tab[t, i, :codes_off].view(np.float16).reshape(K + 1, jt, per)
+            np.testing.assert_array_equal(prm[:K, :n, 0].astype(np.float32), art.scale[e].T)
+            if scheme == ASYM_UINT8:
+                np.testing.assert_array_equal(prm[:K, :n, 1].astype(np.float32), art.y_min[e].T)
+            assert np.all(prm[:, n:] == 0) and np.all(prm[K] == 0)
+            codes = tab[t, i, codes_off:codes_off + K * L * jt].reshape(K, L, jt)
+            want = np.transpose(art.q[e], (1, 2, 0))
+            want = want.view(np.uint8) if scheme == ASYM_UINT8 else (want.astype(np.int16) + 128).astype(np.uint8)
+            np.testing.assert_array_equal(codes[:, :, :n], want)
+
+
+def test_fp16_parameters_are_refused_where_they_cannot_hold():
+    w = random_layer(92, 2, 3, 5, 8, SYM_INT8, CLOSED, CLIP_X, 4, with_base=True)
+    s = w.layers[0]
+    with pytest.raises(lk.LutKanError) as e:                      # not combined with the base branch
+        lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, s.boundary, s.oob,
+                          edge_scales=s.edge_scales, param_dtype=lk.PARAM_FP16)
+    assert str(e.value).startswith("[-5]")
+    with pytest.raises(lk.LutKanError) as e:                      # alpha beyond the largest binary16
+        lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef * np.float32(1e8), s.L, s.scheme, s.boundary, s.oob,
+                          param_dtype=lk.PARAM_FP16)
+    assert str(e.value).startswith("[-5]")
+    with pytest.raises(lk.LutKanError) as e:
+        lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, s.boundary, s.oob, param_dtype=7)
+    assert str(e.value).startswith("[-1]")
