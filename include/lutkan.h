@@ -104,6 +104,26 @@ int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, lutkan_arti
 void lutkan_artifact_free(lutkan_artifact *a);
 int lutkan_artifact_info(const lutkan_artifact *a, lutkan_info *out);
 
+/* The stored arrays of one layer artifact (Sec. 4.6 "Stored Arrays and Shapes" and the manifest fields of its
+ * "Serialization Format"), all host pointers, edge e = i*m + j:
+ *   knots fp32 [K+1] strictly increasing; q_table int8 / uint8 [E][K][L]; scale, y_min fp32 [E][K] (with
+ *   param_dtype = FP16 every value must already be a binary16 value); the three edge_* arrays fp32 [E] with
+ *   value_repr = spline_component, else ignored. */
+typedef struct {
+  int32_t d, m, K, L;
+  int32_t scheme, boundary, oob, value_repr, param_dtype;
+  const float *knots;
+  const void *q_table;
+  const float *scale, *y_min;
+  const float *edge_base_scale, *edge_spline_scale, *edge_out_scale;
+} lutkan_artifact_arrays;
+
+/* Rebuilds an artifact (canonical arrays + LUT device table) from stored arrays, e.g. after reading them back from
+ * disk: the inverse of the lutkan_artifact_* accessors.  The arrays are copied.  Such an artifact carries no spline
+ * coefficients: info.G = 0, the ext_knots / coef_table accessors return NULL and bspline_dev_layer_init refuses it.
+ * Errors as lutkan_compile; EINVAL also for non-finite parameters or fp16 parameters that are not binary16 values. */
+int lutkan_artifact_from_arrays(const lutkan_artifact_arrays *arrays, lutkan_artifact **out);
+
 /* Read-only host views, valid until lutkan_artifact_free.  Canonical arrays (Sec. 4.6), edge e = i*m + j: */
 const void *lutkan_artifact_q(const lutkan_artifact *a);          /* int8 or uint8 [E][K][L] */
 const float *lutkan_artifact_scale(const lutkan_artifact *a);     /* alpha  [E][K] (fp16 parameters: the rounded values, as floats) */

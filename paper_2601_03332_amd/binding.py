@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import ctypes as C
+import json
 import os
 from typing import List, Optional, Sequence
 
@@ -29,6 +30,12 @@ class _LayerDesc(C.Structure):
                 ("L", C.c_int32), ("scheme", C.c_int32), ("boundary", C.c_int32), ("oob", C.c_int32),
                 ("value_repr", C.c_int32), ("edge_base_scale", C.c_void_p), ("edge_spline_scale", C.c_void_p),
                 ("edge_out_scale", C.c_void_p), ("param_dtype", C.c_int32)]
+
+
+class _ArtifactArrays(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("d", "m", "K", "L", "scheme", "boundary", "oob", "value_repr", "param_dtype")] + \
+               [(n, C.c_void_p) for n in ("knots", "q_table", "scale", "y_min", "edge_base_scale", "edge_spline_scale",
+                                          "edge_out_scale")]
 
 
 class _Info(C.Structure):
@@ -59,7 +66,7 @@ EXPORTS = [
     "lutkan_dev_layer_init", "bspline_dev_layer_init", "lutkan_forward_workspace_bytes",
     "bspline_forward_workspace_bytes", "lutkan_forward", "lutkan_forward_trace", "bspline_kan_forward",
     "lutkan_model_workspace_bytes", "lutkan_model_forward", "lutkan_forward_locate", "lutkan_forward_edges",
-    "bspline_forward_locate", "bspline_forward_edges", "lutkan_probe_launch",
+    "bspline_forward_locate", "bspline_forward_edges", "lutkan_probe_launch", "lutkan_artifact_from_arrays",
 ]
 
 _lib = None
@@ -81,6 +88,7 @@ def load_library():
     lib.lutkan_last_error.restype = C.c_char_p
     lib.lutkan_version.restype = C.c_char_p
     lib.lutkan_compile.argtypes = [C.POINTER(_LayerDesc), i32, C.POINTER(vp)]
+    lib.lutkan_artifact_from_arrays.argtypes = [C.POINTER(_ArtifactArrays), C.POINTER(vp)]
     lib.lutkan_artifact_free.argtypes = [vp]
     lib.lutkan_artifact_free.restype = None
     lib.lutkan_artifact_info.argtypes = [vp, C.POINTER(_Info)]
@@ -123,41 +131,93 @@ def _check(rc: int):
         raise LutKanError(f"[{rc}] {lutkan_last_error()}")
 
 
-def _view(ptr, nbytes, dtype, shape):
+def _view(ptr, nbytes, dtype, shape, owner):
+    """numpy view of library-owned host memory; the view keeps `owner` (the Artifact) alive."""
     buf = (C.c_char * nbytes).from_address(ptr)
+    buf._owner = owner
     return np.frombuffer(buf, dtype=dtype).reshape(shape)
 
 
 class Artifact:
-    """Host LUT artifact (Sec. 4.6) owned by the library; numpy views stay valid while this object lives."""
+    """Host LUT artifact (Sec. 4.6) owned by the library.  The array attributes are numpy views of the library's
+    memory, made on access; each view keeps the artifact alive, and the artifact is freed with its last reference."""
 
     def __init__(self, handle):
         self._h = handle
-        lib = load_library()
         info = _Info()
-        _check(lib.lutkan_artifact_info(handle, C.byref(info)))
+        _check(load_library().lutkan_artifact_info(handle, C.byref(info)))
         self.info = info
-        E, K, L = info.d * info.m, info.K, info.L
-        qdt = np.int8 if info.scheme == SYM_INT8 else np.uint8
-        self.q = _view(lib.lutkan_artifact_q(handle), E * K * L, qdt, (E, K, L))
-        self.scale = _view(lib.lutkan_artifact_scale(handle), E * K * 4, np.float32, (E, K))
-        self.y_min = _view(lib.lutkan_artifact_ymin(handle), E * K * 4, np.float32, (E, K))
-        self.knots = _view(lib.lutkan_artifact_knots(handle), (K + 1) * 4, np.float32, (K + 1,))
-        self.ext_knots = _view(lib.lutkan_artifact_ext_knots(handle), (info.G + 7) * 4, np.float32, (info.G + 7,))
-        self.table = _view(lib.lutkan_artifact_table(handle), info.table_bytes, np.uint8, (info.table_bytes,))
-        self.coef_table = _view(lib.lutkan_artifact_coef_table(handle), info.coef_table_bytes, np.float32,
-                                (info.coef_table_bytes // 4,))
-        self.edge_scales = None
-        if info.value_repr == REPR_SPLINE_COMPONENT:
-            self.edge_scales = tuple(_view(getattr(lib, "lutkan_artifact_edge_" + n)(handle), E * 4, np.float32, (E,))
-                                     for n in ("base_scale", "spline_scale", "out_scale"))
+
+    def _array(self, getter, count, dtype, shape):
+        return _view(getattr(load_library(), getter)(self._h), count * np.dtype(dtype).itemsize, dtype, shape, self)
+
+    @property
+    def q(self):
+        E, K, L = self.info.d * self.info.m, self.info.K, self.info.L
+        return self._array("lutkan_artifact_q", E * K * L, np.int8 if self.info.scheme == SYM_INT8 else np.uint8, (E, K, L))
+
+    @property
+    def scale(self):
+        E, K = self.info.d * self.info.m, self.info.K
+        return self._array("lutkan_artifact_scale", E * K, np.float32, (E, K))
+
+    @property
+    def y_min(self):
+        E, K = self.info.d * self.info.m, self.info.K
+        return self._array("lutkan_artifact_ymin", E * K, np.float32, (E, K))
+
+    @property
+    def knots(self):
+        return self._array("lutkan_artifact_knots", self.info.K + 1, np.float32, (self.info.K + 1,))
+
+    @property
+    def ext_knots(self):
+        """None for an artifact rebuilt from stored arrays (it has no spline side)."""
+        return self._array("lutkan_artifact_ext_knots", self.info.G + 7, np.float32, (self.info.G + 7,)) if self.info.G > 0 else None
+
+    @property
+    def table(self):
+        return self._array("lutkan_artifact_table", self.info.table_bytes, np.uint8, (self.info.table_bytes,))
+
+    @property
+    def coef_table(self):
+        n = self.info.coef_table_bytes // 4
+        return self._array("lutkan_artifact_coef_table", n, np.float32, (n,)) if self.info.G > 0 else None
+
+    @property
+    def edge_scales(self):
+        """(s_base, s_spline, s_out), each [E], with value_repr = spline_component; else None."""
+        if self.info.value_repr != REPR_SPLINE_COMPONENT:
+            return None
+        E = self.info.d * self.info.m
+        return tuple(self._array("lutkan_artifact_edge_" + n, E, np.float32, (E,)) for n in ("base_scale", "spline_scale", "out_scale"))
 
     def __del__(self):
         h, self._h = getattr(self, "_h", None), None
         if h and _lib is not None:
-            self.q = self.scale = self.y_min = self.knots = self.ext_knots = self.table = self.coef_table = None
-            self.edge_scales = None
             _lib.lutkan_artifact_free(h)
+
+    def save(self, path: str) -> None:
+        """Writes the artifact as a compressed NPZ whose `manifest` entry is the JSON manifest (Sec. 4.6): metadata
+        format_version, value_repr, interp, boundary_mode, oob_policy, scheme; grid knots, L; tables q_table, scale,
+        y_min (float16 arrays with float16 parameters); the reconstruction scalars and base_kind with
+        spline_component."""
+        I = self.info
+        pdt = np.float16 if I.param_dtype == PARAM_FP16 else np.float32
+        manifest = {"format_version": 1, "value_repr": "spline_component" if I.value_repr == REPR_SPLINE_COMPONENT else "phi",
+                    "interp": "linear", "boundary_mode": "closed" if I.boundary == CLOSED else "half_open",
+                    "oob_policy": "zero_spline" if I.oob == ZERO_SPLINE else "clip_x",
+                    "scheme": "symmetric_int8" if I.scheme == SYM_INT8 else "asymmetric_uint8",
+                    "L": int(I.L), "K": int(I.K), "in_features": int(I.d), "out_features": int(I.m),
+                    "param_dtype": "float16" if I.param_dtype == PARAM_FP16 else "float32"}
+        arrays = {"knots": self.knots, "q_table": self.q, "scale": self.scale.astype(pdt), "y_min": self.y_min.astype(pdt)}
+        if self.edge_scales is not None:
+            manifest["base_kind"] = "silu"
+            arrays.update(edge_base_scale=self.edge_scales[0], edge_spline_scale=self.edge_scales[1],
+                          edge_out_scale=self.edge_scales[2])
+        with open(path, "wb") as f:
+            np.savez_compressed(f, manifest=np.frombuffer(json.dumps(manifest, sort_keys=True).encode(), dtype=np.uint8),
+                                **arrays)
 
     def to_device(self, device="cuda:0", algo: int = ALGO_AUTO) -> "LutLayer":
         return LutLayer(self, device, algo)
@@ -185,6 +245,54 @@ def lutkan_compile(d: int, m: int, G: int, degree: int, ext_knots, coef, L: int,
     out = C.c_void_p()
     _check(lib.lutkan_compile(C.byref(desc), n_threads, C.byref(out)))
     return Artifact(out.value)
+
+
+def lutkan_artifact_from_arrays(d: int, m: int, knots, q_table, scale, y_min, boundary: int, oob: int,
+                                edge_scales=None, param_dtype: int = PARAM_FP32) -> Artifact:
+    """Artifact (with its device table) from stored arrays: q_table int8 (symmetric) or uint8 (asymmetric) [d*m, K, L]."""
+    q = np.ascontiguousarray(q_table)
+    if q.dtype not in (np.int8, np.uint8) or q.ndim != 3 or q.shape[0] != d * m:
+        raise LutKanError("lutkan_artifact_from_arrays: q_table must be int8 or uint8 with shape [d*m, K, L]")
+    K, L = int(q.shape[1]), int(q.shape[2])
+    kn = np.ascontiguousarray(knots, dtype=np.float32).reshape(-1)
+    sc = np.ascontiguousarray(scale, dtype=np.float32).reshape(-1)
+    ym = np.ascontiguousarray(y_min, dtype=np.float32).reshape(-1)
+    if kn.size != K + 1 or sc.size != d * m * K or ym.size != d * m * K:
+        raise LutKanError("lutkan_artifact_from_arrays: knots / scale / y_min do not match q_table's shape")
+    keep = [np.ascontiguousarray(a, dtype=np.float32).reshape(-1) for a in edge_scales] if edge_scales is not None else []
+    if keep and any(a.size != d * m for a in keep):
+        raise LutKanError("lutkan_artifact_from_arrays: every edge scale array needs d*m elements")
+    arr = _ArtifactArrays(d, m, K, L, SYM_INT8 if q.dtype == np.int8 else ASYM_UINT8, boundary, oob,
+                          REPR_SPLINE_COMPONENT if keep else REPR_PHI, param_dtype, kn.ctypes.data, q.ctypes.data,
+                          sc.ctypes.data, ym.ctypes.data, *[a.ctypes.data for a in keep])
+    out = C.c_void_p()
+    _check(load_library().lutkan_artifact_from_arrays(C.byref(arr), C.byref(out)))
+    return Artifact(out.value)
+
+
+def lutkan_artifact_load(path: str) -> Artifact:
+    """Reads an artifact written by Artifact.save (NPZ + JSON manifest, Sec. 4.6).  Nothing in the file is executed."""
+    with np.load(path, allow_pickle=False) as z:
+        man = json.loads(bytes(z["manifest"]).decode())
+        if man.get("format_version") != 1 or man.get("interp") != "linear":
+            raise LutKanError(f"lutkan_artifact_load: unsupported manifest {man}")
+        names = {"boundary_mode": {"half_open": HALF_OPEN, "closed": CLOSED}, "oob_policy": {"clip_x": CLIP_X, "zero_spline": ZERO_SPLINE},
+                 "scheme": {"symmetric_int8": SYM_INT8, "asymmetric_uint8": ASYM_UINT8}, "param_dtype": {"float32": PARAM_FP32, "float16": PARAM_FP16},
+                 "value_repr": {"phi": REPR_PHI, "spline_component": REPR_SPLINE_COMPONENT}}
+        try:
+            f = {k: v[man[k]] for k, v in names.items()}
+        except KeyError as e:
+            raise LutKanError(f"lutkan_artifact_load: bad manifest field {e}") from None
+        q = z["q_table"]
+        if (q.dtype == np.int8) != (f["scheme"] == SYM_INT8):
+            raise LutKanError("lutkan_artifact_load: q_table dtype does not match the manifest's scheme")
+        scales = None
+        if f["value_repr"] == REPR_SPLINE_COMPONENT:
+            if man.get("base_kind") != "silu":
+                raise LutKanError("lutkan_artifact_load: only base_kind = silu is supported")
+            scales = (z["edge_base_scale"], z["edge_spline_scale"], z["edge_out_scale"])
+        return lutkan_artifact_from_arrays(int(man["in_features"]), int(man["out_features"]), z["knots"], q, z["scale"],
+                                           z["y_min"], f["boundary_mode"], f["oob_policy"], scales, f["param_dtype"])
 
 
 def _torch():

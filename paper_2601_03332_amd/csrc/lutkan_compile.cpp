@@ -124,6 +124,62 @@ HalfValue to_binary16(float x) {
   return out;
 }
 
+// Writes one edge's share of a (tile, input) slice of the LUT device table (layout in lutkan.h).
+struct SlicePacker {
+  BlobLayout lay;
+  int jt, L, scheme;
+  bool half_params;
+
+  // s_out * s_base of the edge in column jj (spline_component only)
+  void put_base(uint8_t *slice, int jj, float base_gain) const { reinterpret_cast<float *>(slice)[jj] = base_gain; }
+
+  // Segment k of the edge in column jj: its dequantisation parameters (times gain = s_out * s_spline with
+  // spline_component, else exactly as given; binary16 parameters arrive already rounded) and its L codes.
+  void put_segment(uint8_t *slice, int jj, int k, float alpha, float ymin, bool with_gain, float gain, const uint8_t *codes) const {
+    uint8_t *params = slice + lay.params_off;
+    if (half_params) {
+      uint16_t *p16 = reinterpret_cast<uint16_t *>(params);
+      if (scheme == LUTKAN_ASYM_UINT8) {
+        p16[((size_t)k * jt + jj) * 2] = to_binary16(alpha).bits;
+        p16[((size_t)k * jt + jj) * 2 + 1] = to_binary16(ymin).bits;
+      } else {
+        p16[(size_t)k * jt + jj] = to_binary16(alpha).bits;
+      }
+    } else {
+      float *p32 = reinterpret_cast<float *>(params);
+      if (scheme == LUTKAN_ASYM_UINT8) {
+        p32[((size_t)k * jt + jj) * 2] = with_gain ? gain * alpha : alpha;
+        p32[((size_t)k * jt + jj) * 2 + 1] = with_gain ? gain * ymin : ymin;
+      } else {
+        p32[(size_t)k * jt + jj] = with_gain ? gain * alpha : alpha;
+      }
+    }
+    // device codes: uint8 as is; int8 stored excess-128 (q + 128), which the kernels undo exactly
+    const uint8_t flip = (scheme == LUTKAN_SYM_INT8) ? 0x80 : 0x00;
+    uint8_t *dst = slice + lay.codes_off;
+    for (int l = 0; l < L; ++l) dst[((size_t)k * L + l) * jt + jj] = codes[l] ^ flip;
+  }
+};
+
+// Fills the size and contract fields of an artifact's info once its arrays and tables are in place.
+void fill_info(lutkan_artifact *a, int d, int m, int K, int L, int G, int scheme, int boundary, int oob, int repr,
+               int param_dtype, int jt, int n_tiles, const BlobLayout &lay, int coef_blob) {
+  const size_t E = (size_t)d * m;
+  lutkan_info &I = a->info;
+  std::memset(&I, 0, sizeof(I));
+  I.d = d; I.m = m; I.K = K; I.L = L; I.G = G; I.degree = P;
+  I.scheme = scheme; I.boundary = boundary; I.oob = oob; I.value_repr = repr; I.param_dtype = param_dtype;
+  I.jt = jt; I.n_tiles = n_tiles; I.blob_bytes = lay.bytes; I.coef_blob_bytes = coef_blob;
+  I.t0 = a->knots[0]; I.tK = a->knots[K];
+  I.tK_star = (boundary == LUTKAN_CLOSED) ? I.tK : std::nextafterf(I.tK, -INFINITY);  // Eq. 13
+  I.q_canonical_bytes = E * K * L;
+  I.params_canonical_bytes = E * K * (param_dtype == LUTKAN_PARAM_FP16 ? 2 : 4);
+  I.table_bytes = a->table.size();
+  I.coef_table_bytes = a->coef_table.size() * 4;
+  I.artifact_bytes = I.q_canonical_bytes + 2 * I.params_canonical_bytes + 4 * (size_t)(K + 1) +
+                     (repr == LUTKAN_REPR_SPLINE_COMPONENT ? 12 * E : 0);
+}
+
 }  // namespace
 }  // namespace lutkan
 
@@ -207,6 +263,7 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
   nt = std::max(1, std::min(nt, 64));
   nt = (int)std::min<size_t>((size_t)nt, (size_t)d);
   std::atomic<long> unrepresentable{0};       // float16 parameters that overflowed
+  const SlicePacker packer{lay, jt, L, scheme, half_params};
   auto work = [&](int tid) {
     std::vector<float> v((size_t)L);
     for (int i = tid; i < d; i += nt) {
@@ -215,9 +272,6 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
         const float *c = desc->coef + e * R;
         const int t = j / jt, jj = j % jt;
         uint8_t *slice = a->table.data() + ((size_t)t * d + i) * lay.bytes;
-        float *slice_params = reinterpret_cast<float *>(slice + lay.params_off);
-        uint16_t *slice_params16 = reinterpret_cast<uint16_t *>(slice + lay.params_off);
-        uint8_t *slice_codes = slice + lay.codes_off;
         float *cslice = a->coef_table.data() + ((size_t)t * d + i) * coef_rows * jt;
         // spline_component (Eq. 2): the device tables carry s_out*s_base per edge as an extra row and fold
         // s_out*s_spline into the edge's dequantisation parameters / B-spline coefficients.
@@ -225,7 +279,7 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
         if (with_base) {
           const float base_gain = desc->edge_out_scale[e] * desc->edge_base_scale[e];
           spline_gain = desc->edge_out_scale[e] * desc->edge_spline_scale[e];
-          reinterpret_cast<float *>(slice)[jj] = base_gain;
+          packer.put_base(slice, jj, base_gain);
           cslice[jj] = base_gain;
           cslice += jt;
         }
@@ -245,30 +299,15 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
           const SegmentCodes sc = (scheme == LUTKAN_SYM_INT8)
                                       ? quantise_symmetric(v.data(), L, reinterpret_cast<int8_t *>(qc))
                                       : quantise_asymmetric(v.data(), L, qc);
+          float alpha = sc.alpha, ymin = sc.ymin;
           if (half_params) {
-            const HalfValue ha = to_binary16(sc.alpha), hy = to_binary16(sc.ymin);
-            if (std::isinf(ha.value) || std::isinf(hy.value)) unrepresentable.fetch_add(1);
-            a->scale[e * K + k] = ha.value;
-            a->ymin[e * K + k] = hy.value;
-            if (scheme == LUTKAN_ASYM_UINT8) {
-              slice_params16[((size_t)k * jt + jj) * 2] = ha.bits;
-              slice_params16[((size_t)k * jt + jj) * 2 + 1] = hy.bits;
-            } else {
-              slice_params16[(size_t)k * jt + jj] = ha.bits;
-            }
-          } else {
-            a->scale[e * K + k] = sc.alpha;
-            a->ymin[e * K + k] = sc.ymin;
-            if (scheme == LUTKAN_ASYM_UINT8) {
-              slice_params[((size_t)k * jt + jj) * 2] = with_base ? spline_gain * sc.alpha : sc.alpha;
-              slice_params[((size_t)k * jt + jj) * 2 + 1] = with_base ? spline_gain * sc.ymin : sc.ymin;
-            } else {
-              slice_params[(size_t)k * jt + jj] = with_base ? spline_gain * sc.alpha : sc.alpha;
-            }
+            alpha = to_binary16(sc.alpha).value;
+            ymin = to_binary16(sc.ymin).value;
+            if (std::isinf(alpha) || std::isinf(ymin)) unrepresentable.fetch_add(1);
           }
-          // device codes: uint8 as is; int8 stored excess-128 (q + 128), which the kernels undo exactly
-          const uint8_t flip = (scheme == LUTKAN_SYM_INT8) ? 0x80 : 0x00;
-          for (int l = 0; l < L; ++l) slice_codes[((size_t)k * L + l) * jt + jj] = qc[l] ^ flip;
+          a->scale[e * K + k] = alpha;
+          a->ymin[e * K + k] = ymin;
+          packer.put_segment(slice, jj, k, alpha, ymin, with_base, spline_gain, qc);
         }
       }
     }
@@ -287,18 +326,80 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
     return fail(LUTKAN_EUNSUPPORTED, "lutkan_compile: %ld segments have an alpha or y_min too large for float16", n);
   }
 
-  lutkan_info &I = a->info;
-  std::memset(&I, 0, sizeof(I));
-  I.d = d; I.m = m; I.K = K; I.L = L; I.G = G; I.degree = P;
-  I.scheme = scheme; I.boundary = desc->boundary; I.oob = desc->oob; I.value_repr = repr; I.param_dtype = desc->param_dtype;
-  I.jt = jt; I.n_tiles = n_tiles; I.blob_bytes = lay.bytes; I.coef_blob_bytes = coef_blob;
-  I.t0 = a->knots[0]; I.tK = a->knots[K];
-  I.tK_star = (desc->boundary == LUTKAN_CLOSED) ? I.tK : std::nextafterf(I.tK, -INFINITY);  // Eq. 13
-  I.q_canonical_bytes = E * K * L;
-  I.params_canonical_bytes = E * K * (half_params ? 2 : 4);
-  I.table_bytes = a->table.size();
-  I.coef_table_bytes = a->coef_table.size() * 4;
-  I.artifact_bytes = I.q_canonical_bytes + 2 * I.params_canonical_bytes + 4 * (size_t)(K + 1) + (with_base ? 12 * E : 0);
+  fill_info(a, d, m, K, L, G, scheme, desc->boundary, desc->oob, repr, desc->param_dtype, jt, n_tiles, lay, coef_blob);
+  *out = a;
+  return LUTKAN_OK;
+}
+
+extern "C" int lutkan_artifact_from_arrays(const lutkan_artifact_arrays *in, lutkan_artifact **out) {
+  const char *who = "lutkan_artifact_from_arrays";
+  if (!in || !out) return fail(LUTKAN_EINVAL, "%s: null argument", who);
+  if (!in->knots || !in->q_table || !in->scale || !in->y_min) return fail(LUTKAN_EINVAL, "%s: null knots / q_table / scale / y_min", who);
+  const int d = in->d, m = in->m, K = in->K, L = in->L, scheme = in->scheme, repr = in->value_repr;
+  if (d < 1 || m < 1 || K < 1) return fail(LUTKAN_EINVAL, "%s: d, m, K must be >= 1", who);
+  if (L < 2) return fail(LUTKAN_EINVAL, "%s: L must be >= 2 (got %d)", who, L);
+  if (scheme != LUTKAN_SYM_INT8 && scheme != LUTKAN_ASYM_UINT8) return fail(LUTKAN_EINVAL, "%s: bad scheme %d", who, scheme);
+  if (in->boundary != LUTKAN_HALF_OPEN && in->boundary != LUTKAN_CLOSED) return fail(LUTKAN_EINVAL, "%s: bad boundary_mode %d", who, in->boundary);
+  if (in->oob != LUTKAN_CLIP_X && in->oob != LUTKAN_ZERO_SPLINE) return fail(LUTKAN_EINVAL, "%s: bad oob_policy %d", who, in->oob);
+  if (repr != LUTKAN_REPR_PHI && repr != LUTKAN_REPR_SPLINE_COMPONENT) return fail(LUTKAN_EINVAL, "%s: bad value_repr %d", who, repr);
+  if (in->param_dtype != LUTKAN_PARAM_FP32 && in->param_dtype != LUTKAN_PARAM_FP16) return fail(LUTKAN_EINVAL, "%s: bad param_dtype %d", who, in->param_dtype);
+  const bool with_base = (repr == LUTKAN_REPR_SPLINE_COMPONENT);
+  const bool half_params = (in->param_dtype == LUTKAN_PARAM_FP16);
+  if (half_params && with_base) return fail(LUTKAN_EUNSUPPORTED, "%s: float16 parameters are not available with value_repr = spline_component", who);
+  if (with_base && (!in->edge_base_scale || !in->edge_spline_scale || !in->edge_out_scale))
+    return fail(LUTKAN_EINVAL, "%s: spline_component needs edge_base_scale, edge_spline_scale and edge_out_scale", who);
+  if (K > LUTKAN_MAX_K) return fail(LUTKAN_EUNSUPPORTED, "%s: K=%d exceeds LUTKAN_MAX_K=%d", who, K, LUTKAN_MAX_K);
+  if ((int64_t)K * L > LUTKAN_MAX_ROWS) return fail(LUTKAN_EUNSUPPORTED, "%s: K*L=%lld exceeds %d", who, (long long)K * L, LUTKAN_MAX_ROWS);
+  for (int k = 0; k <= K; ++k)
+    if (!std::isfinite(in->knots[k])) return fail(LUTKAN_EINVAL, "%s: knot %d is not finite", who, k);
+  for (int k = 0; k < K; ++k)
+    if (!(in->knots[k] < in->knots[k + 1])) return fail(LUTKAN_EINVAL, "%s: knots not strictly increasing at %d", who, k);
+  const size_t E = (size_t)d * m;
+  for (size_t n = 0; n < E * K; ++n) {
+    if (!std::isfinite(in->scale[n]) || !std::isfinite(in->y_min[n])) return fail(LUTKAN_EINVAL, "%s: scale / y_min entry %zu is not finite", who, n);
+    if (half_params && (to_binary16(in->scale[n]).value != in->scale[n] || to_binary16(in->y_min[n]).value != in->y_min[n]))
+      return fail(LUTKAN_EINVAL, "%s: scale / y_min entry %zu is not a float16 value", who, n);
+  }
+  if (with_base)
+    for (size_t e = 0; e < E; ++e)
+      if (!std::isfinite(in->edge_base_scale[e]) || !std::isfinite(in->edge_spline_scale[e]) || !std::isfinite(in->edge_out_scale[e]))
+        return fail(LUTKAN_EINVAL, "%s: edge scale %zu is not finite", who, e);
+
+  lutkan_artifact *a = new (std::nothrow) lutkan_artifact();
+  if (!a) return fail(LUTKAN_ENOMEM, "%s: out of host memory", who);
+  const int jt = choose_jt(m, K, L, scheme, repr, in->param_dtype);
+  const int n_tiles = (m + jt - 1) / jt;
+  const BlobLayout lay = blob_layout(K, L, jt, scheme, repr, in->param_dtype);
+  try {
+    a->knots.assign(in->knots, in->knots + K + 1);
+    a->q.assign(static_cast<const uint8_t *>(in->q_table), static_cast<const uint8_t *>(in->q_table) + E * K * L);
+    a->scale.assign(in->scale, in->scale + E * K);
+    a->ymin.assign(in->y_min, in->y_min + E * K);
+    a->table.assign((size_t)n_tiles * d * lay.bytes, 0);
+    if (with_base) {
+      a->edge_base.assign(in->edge_base_scale, in->edge_base_scale + E);
+      a->edge_spline.assign(in->edge_spline_scale, in->edge_spline_scale + E);
+      a->edge_out.assign(in->edge_out_scale, in->edge_out_scale + E);
+    }
+  } catch (const std::bad_alloc &) {
+    delete a;
+    return fail(LUTKAN_ENOMEM, "%s: out of host memory for %zu edges", who, E);
+  }
+  const SlicePacker packer{lay, jt, L, scheme, half_params};
+  for (int i = 0; i < d; ++i)
+    for (int j = 0; j < m; ++j) {
+      const size_t e = (size_t)i * m + j;
+      uint8_t *slice = a->table.data() + ((size_t)(j / jt) * d + i) * lay.bytes;
+      float spline_gain = 1.0f;
+      if (with_base) {
+        packer.put_base(slice, j % jt, a->edge_out[e] * a->edge_base[e]);
+        spline_gain = a->edge_out[e] * a->edge_spline[e];
+      }
+      for (int k = 0; k < K; ++k)
+        packer.put_segment(slice, j % jt, k, a->scale[e * K + k], a->ymin[e * K + k], with_base, spline_gain, a->q.data() + (e * K + k) * L);
+    }
+  // a LUT artifact holds no spline coefficients: G = 0 and an empty B-spline table say so
+  fill_info(a, d, m, K, L, 0, scheme, in->boundary, in->oob, repr, in->param_dtype, jt, n_tiles, lay, 0);
   *out = a;
   return LUTKAN_OK;
 }
@@ -315,12 +416,12 @@ extern "C" const void *lutkan_artifact_q(const lutkan_artifact *a) { return a ? 
 extern "C" const float *lutkan_artifact_scale(const lutkan_artifact *a) { return a ? a->scale.data() : nullptr; }
 extern "C" const float *lutkan_artifact_ymin(const lutkan_artifact *a) { return a ? a->ymin.data() : nullptr; }
 extern "C" const float *lutkan_artifact_knots(const lutkan_artifact *a) { return a ? a->knots.data() : nullptr; }
-extern "C" const float *lutkan_artifact_ext_knots(const lutkan_artifact *a) { return a ? a->ext_knots.data() : nullptr; }
+extern "C" const float *lutkan_artifact_ext_knots(const lutkan_artifact *a) { return (a && !a->ext_knots.empty()) ? a->ext_knots.data() : nullptr; }
 extern "C" const float *lutkan_artifact_edge_base_scale(const lutkan_artifact *a) { return (a && !a->edge_base.empty()) ? a->edge_base.data() : nullptr; }
 extern "C" const float *lutkan_artifact_edge_spline_scale(const lutkan_artifact *a) { return (a && !a->edge_spline.empty()) ? a->edge_spline.data() : nullptr; }
 extern "C" const float *lutkan_artifact_edge_out_scale(const lutkan_artifact *a) { return (a && !a->edge_out.empty()) ? a->edge_out.data() : nullptr; }
 extern "C" const void *lutkan_artifact_table(const lutkan_artifact *a) { return a ? a->table.data() : nullptr; }
-extern "C" const void *lutkan_artifact_coef_table(const lutkan_artifact *a) { return a ? a->coef_table.data() : nullptr; }
+extern "C" const void *lutkan_artifact_coef_table(const lutkan_artifact *a) { return (a && !a->coef_table.empty()) ? a->coef_table.data() : nullptr; }
 
 extern "C" int lutkan_dev_layer_init(const lutkan_artifact *a, lutkan_dev_layer *out) {
   if (!a || !out) return fail(LUTKAN_EINVAL, "lutkan_dev_layer_init: null argument");
@@ -338,6 +439,7 @@ extern "C" int lutkan_dev_layer_init(const lutkan_artifact *a, lutkan_dev_layer 
 
 extern "C" int bspline_dev_layer_init(const lutkan_artifact *a, bspline_dev_layer *out) {
   if (!a || !out) return fail(LUTKAN_EINVAL, "bspline_dev_layer_init: null argument");
+  if (a->coef_table.empty()) return fail(LUTKAN_EUNSUPPORTED, "bspline_dev_layer_init: the artifact was built from LUT arrays and holds no spline coefficients");
   std::memset(out, 0, sizeof(*out));
   const lutkan_info &I = a->info;
   out->d = I.d; out->m = I.m; out->G = I.G; out->degree = I.degree;

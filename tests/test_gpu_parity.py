@@ -154,6 +154,25 @@ def test_fp16_parameters(case):
     _check_layer(w.layers[0], w.x, lk.ALGO_GATHER, codes=(B * d * m <= 2_000_000), what=w.name, param_fp16=True)
 
 
+def test_loaded_artifact_runs_like_the_compiled_one(tmp_path):
+    """An artifact written to NPZ + manifest and read back (Sec. 4.6) gives bit-identical outputs and counters."""
+    w = random_layer(611, 20, 150, 6, 32, ASYM_UINT8, HALF_OPEN, ZERO_SPLINE, 3000)
+    s = w.layers[0]
+    art = lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, s.boundary, s.oob)
+    path = str(tmp_path / "layer.npz")
+    art.save(path)
+    back = lk.lutkan_artifact_load(path)
+    xg = torch.from_numpy(w.x).to(DEV)
+    _say(f"case {w.name} loaded artifact jt={back.info.jt}")
+    st1, st2 = torch.zeros(2, dtype=torch.int64, device=DEV), torch.zeros(2, dtype=torch.int64, device=DEV)
+    y1 = lk.lutkan_forward(art.to_device(DEV), xg, stats=st1)
+    y2 = lk.lutkan_forward(back.to_device(DEV), xg, stats=st2)
+    torch.cuda.synchronize()
+    assert torch.equal(y1, y2) and torch.equal(st1, st2)
+    ora = oracle.compile_layer(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme)
+    _assert_close(y2.cpu().numpy(), oracle.lut_forward(ora, s.boundary, s.oob, w.x), w.name)
+
+
 def test_special_inputs_nan_inf_all_oob():
     w = random_layer(301, 6, 140, 5, 32, ASYM_UINT8, CLOSED, ZERO_SPLINE, 40)
     x = w.x.copy()

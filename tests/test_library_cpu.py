@@ -264,3 +264,58 @@ def test_fp16_parameters_are_refused_where_they_cannot_hold():
     with pytest.raises(lk.LutKanError) as e:
         lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, s.boundary, s.oob, param_dtype=7)
     assert str(e.value).startswith("[-1]")
+
+
+@pytest.mark.parametrize("with_base,param_dtype,scheme", [(False, 0, SYM_INT8), (False, 1, ASYM_UINT8), (True, 0, ASYM_UINT8)])
+def test_artifact_round_trip_through_npz_and_manifest(tmp_path, with_base, param_dtype, scheme):
+    """Sec. 4.6 serialisation: the NPZ holds the paper's keys, the manifest its metadata fields, and loading it gives
+    back the same canonical arrays and a byte-identical device table."""
+    import json
+    w = random_layer(93, 3, 70, 6, 16, scheme, HALF_OPEN, ZERO_SPLINE, 4, with_base=with_base)
+    s = w.layers[0]
+    art = lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, scheme, s.boundary, s.oob,
+                            edge_scales=s.edge_scales, param_dtype=param_dtype)
+    path = str(tmp_path / "layer0.npz")
+    art.save(path)
+    with np.load(path, allow_pickle=False) as z:
+        keys = set(z.files)
+        man = json.loads(bytes(z["manifest"]).decode())
+        assert z["q_table"].shape == (s.d * s.m, s.G, s.L) and z["knots"].shape == (s.G + 1,)
+        assert z["scale"].dtype == (np.float16 if param_dtype else np.float32) and z["scale"].shape == (s.d * s.m, s.G)
+        payload = sum(z[k].nbytes for k in keys - {"manifest"})
+    want_keys = {"manifest", "knots", "q_table", "scale", "y_min"}
+    if with_base:
+        want_keys |= {"edge_base_scale", "edge_spline_scale", "edge_out_scale"}
+        assert man["base_kind"] == "silu"
+    assert keys == want_keys
+    assert payload == art.info.artifact_bytes                       # "LUT artifact bytes = sum of NPZ payload fields" (Sec. 6.6)
+    assert (man["format_version"], man["interp"], man["boundary_mode"], man["oob_policy"], man["L"]) == (1, "linear", "half_open", "zero_spline", s.L)
+    assert man["value_repr"] == ("spline_component" if with_base else "phi")
+    back = lk.lutkan_artifact_load(path)
+    for name in ("q", "scale", "y_min", "knots", "table"):
+        np.testing.assert_array_equal(getattr(back, name), getattr(art, name), err_msg=name)
+    if with_base:
+        for a, b in zip(back.edge_scales, art.edge_scales):
+            np.testing.assert_array_equal(a, b)
+    for f in ("d", "m", "K", "L", "scheme", "boundary", "oob", "value_repr", "param_dtype", "jt", "n_tiles", "blob_bytes",
+              "table_bytes", "artifact_bytes", "tK_star"):
+        assert getattr(back.info, f) == getattr(art.info, f), f
+    assert back.info.G == 0 and back.coef_table is None and back.ext_knots is None
+    bl = binding._SplineDevLayer()
+    assert lk.load_library().bspline_dev_layer_init(back._h, C.byref(bl)) == -5     # no spline coefficients in a LUT artifact
+
+
+def test_artifact_from_arrays_validates_its_input():
+    s = random_layer(94, 2, 3, 5, 8, ASYM_UINT8, CLOSED, CLIP_X, 4).layers[0]
+    art = lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, s.boundary, s.oob)
+    ok = lambda **kw: lk.lutkan_artifact_from_arrays(**{**dict(d=s.d, m=s.m, knots=art.knots, q_table=art.q, scale=art.scale,
+                                                                  y_min=art.y_min, boundary=CLOSED, oob=CLIP_X), **kw})
+    np.testing.assert_array_equal(ok().table, art.table)
+    bad_knots = art.knots.copy(); bad_knots[2] = bad_knots[1]
+    nan_scale = art.scale.copy(); nan_scale[0, 0] = np.nan
+    for kw, code in ((dict(knots=bad_knots), "[-1]"), (dict(scale=nan_scale), "[-1]"), (dict(boundary=5), "[-1]"),
+                     (dict(param_dtype=lk.PARAM_FP16), "[-1]"),            # fp32 values that are not binary16 values
+                     (dict(q_table=art.q.astype(np.int16)), "q_table must be"), (dict(knots=art.knots[:-1]), "do not match")):
+        with pytest.raises(lk.LutKanError) as e:
+            ok(**kw)
+        assert code in str(e.value), (kw.keys(), str(e.value))
