@@ -230,6 +230,26 @@ size_t lutkan_model_workspace_bytes(const lutkan_dev_layer *layers, int32_t n_la
 int lutkan_model_forward(const lutkan_dev_layer *layers, int32_t n_layers, const float *x, int64_t B, float *y,
                          lutkan_oob_stats *stats, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Error statistics of the OOB evaluation protocol (Sec. 5.6 and the accuracy metrics of Sec. 6.5), in one pass on the
+ * device: |y - y_ref| over the outputs of the in-range samples (rows whose d inputs all satisfy the domain predicate
+ * In(x) of Sec. 5.2 under `boundary` on [t0, tK]) and of the OOB-only samples (rows with at least one input outside;
+ * NaN counts as outside).  MAE of a subset = sum_abs / (rows * m - its NaN outputs); OOB_any_frac = rows_oob / B.
+ *   y, y_ref   device [B][m] fp32 (e.g. the LUT layer and the B-spline layer on the same x)
+ *   x          device [B][d] fp32, the layer input that decides the subset of each row
+ *   out        device, 8-byte aligned, overwritten
+ *   workspace  device, >= lutkan_error_stats_workspace_bytes(B), 16-byte aligned
+ * Differences are taken and summed in fp64; partial sums are combined in a fixed order (the result is reproducible).
+ * Outputs whose difference is NaN are counted in nan_outputs and left out of the sums and maxima. */
+typedef struct {
+  unsigned long long rows_in, rows_oob, nan_outputs;
+  double sum_abs_in, sum_abs_oob;
+  double max_abs_in, max_abs_oob;
+} lutkan_error_summary;
+size_t lutkan_error_stats_workspace_bytes(int64_t B);
+int lutkan_error_stats(const float *y, const float *y_ref, int64_t B, int32_t m, const float *x, int32_t d,
+                       float t0, float tK, int32_t boundary, lutkan_error_summary *out, void *workspace,
+                       size_t workspace_bytes, void *hip_stream);
+
 /* Measurement aid, not part of the method: launches one kernel of known work that exercises a single resource, so
  * that a caller who times it (events on hip_stream) learns the rate this machine sustains and can put the layer
  * kernels' roofline terms beside measured peaks as well as published ones.

@@ -201,3 +201,26 @@ def bspline_forward(d, m, G, p, ext_knots, coef, boundary, oob, x, nthreads=None
 
 def artifact_bytes(E: int, K: int, L: int, param_bytes_per_segment: int) -> int:
     return int(lib().lko_artifact_bytes(E, K, L, param_bytes_per_segment))
+
+
+def error_stats(y, y_ref, x, t0, tK, boundary):
+    """OOB evaluation protocol of Sec. 5.6 written out: a sample (row) is in-range when every input satisfies the
+    domain predicate In(x) of Sec. 5.2 (half_open: t0 <= x < tK, closed: t0 <= x <= tK; NaN is outside), else it is
+    in the OOB-only subset.  Per subset: number of rows, sum and maximum of |y - y_ref| over the rows' outputs in
+    fp64, MAE = sum / (number of non-NaN differences); differences that are NaN are counted and left out."""
+    x = _f32(x)
+    y = np.asarray(y, dtype=np.float32).astype(np.float64)
+    y_ref = np.asarray(y_ref, dtype=np.float32).astype(np.float64)
+    t0, tK = np.float32(t0), np.float32(tK)
+    inside = (x >= t0) & ((x <= tK) if boundary == CLOSED else (x < tK))
+    row_in = inside.all(axis=1)
+    err = np.abs(y - y_ref)
+    nan = np.isnan(err)
+    out = {"rows_in": int(row_in.sum()), "rows_oob": int((~row_in).sum()), "nan_outputs": int(nan.sum()),
+           "oob_any_frac": float((~row_in).mean())}
+    for name, rows in (("in", row_in), ("oob", ~row_in)):
+        e = err[rows][~nan[rows]]
+        out["sum_abs_" + name] = float(e.sum()) if e.size else 0.0
+        out["max_abs_" + name] = float(e.max()) if e.size else 0.0
+        out["mae_" + name] = float(e.sum() / (int(rows.sum()) * y.shape[1])) if rows.any() else float("nan")
+    return out

@@ -67,6 +67,7 @@ EXPORTS = [
     "bspline_forward_workspace_bytes", "lutkan_forward", "lutkan_forward_trace", "bspline_kan_forward",
     "lutkan_model_workspace_bytes", "lutkan_model_forward", "lutkan_forward_locate", "lutkan_forward_edges",
     "bspline_forward_locate", "bspline_forward_edges", "lutkan_probe_launch", "lutkan_artifact_from_arrays",
+    "lutkan_error_stats_workspace_bytes", "lutkan_error_stats",
 ]
 
 _lib = None
@@ -114,6 +115,9 @@ def load_library():
     lib.lutkan_model_workspace_bytes.restype = sz
     lib.lutkan_model_forward.argtypes = [C.POINTER(_DevLayer), i32, vp, i64, vp, vp, vp, sz, vp]
     lib.lutkan_probe_launch.argtypes = [i32, vp, sz, i32, C.POINTER(C.c_double), vp]
+    lib.lutkan_error_stats_workspace_bytes.argtypes = [i64]
+    lib.lutkan_error_stats_workspace_bytes.restype = sz
+    lib.lutkan_error_stats.argtypes = [vp, vp, i64, i32, vp, i32, C.c_float, C.c_float, i32, vp, vp, sz, vp]
     _lib = lib
     return lib
 
@@ -498,3 +502,27 @@ def lutkan_probe_launch(kind: int, buffer, iters: int) -> float:
     _check(load_library().lutkan_probe_launch(kind, buffer.data_ptr(), buffer.numel() * buffer.element_size(), iters,
                                               C.byref(work), _stream(buffer.device)))
     return work.value
+
+
+def lutkan_error_stats(y, y_ref, x, t0: float, tK: float, boundary: int) -> dict:
+    """|y - y_ref| statistics on the in-range and the OOB-only samples (Sec. 5.6), reduced on the device.
+    Returns rows_in, rows_oob, nan_outputs, sum / max / mae per subset and oob_any_frac."""
+    torch = _torch()
+    for t, what in ((y, "y"), (y_ref, "y_ref"), (x, "x")):
+        _require(t, torch.float32, what)
+    B, m, d = y.shape[0], y.shape[1], x.shape[1]
+    if y_ref.shape != y.shape or x.shape[0] != B:
+        raise LutKanError("lutkan_error_stats: y, y_ref must be [B,m] and x [B,d]")
+    lib = load_library()
+    out = torch.zeros(7, dtype=torch.float64, device=y.device)            # 3 x uint64 + 4 x double = 56 bytes
+    ws = torch.empty(max(16, lib.lutkan_error_stats_workspace_bytes(B)), dtype=torch.uint8, device=y.device)
+    _check(lib.lutkan_error_stats(y.data_ptr(), y_ref.data_ptr(), B, m, x.data_ptr(), d, float(t0), float(tK), boundary,
+                                  out.data_ptr(), ws.data_ptr(), ws.numel(), _stream(y.device)))
+    raw = out.cpu().numpy()
+    rows_in, rows_oob, nans = (int(v) for v in raw[:3].view(np.uint64))
+    s_in, s_oob, mx_in, mx_oob = (float(v) for v in raw[3:])
+    res = dict(rows_in=rows_in, rows_oob=rows_oob, nan_outputs=nans, sum_abs_in=s_in, sum_abs_oob=s_oob,
+               max_abs_in=mx_in, max_abs_oob=mx_oob, oob_any_frac=rows_oob / B)
+    res["mae_in"] = s_in / (rows_in * m) if rows_in else float("nan")
+    res["mae_oob"] = s_oob / (rows_oob * m) if rows_oob else float("nan")
+    return res

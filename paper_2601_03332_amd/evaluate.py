@@ -8,8 +8,10 @@ spline_component, inputs N(0,1) clipped to the knot domain) it prints
     quantisation schemes (Sec. 7.1, Table 1's protocol: closed + clip_x), and
   * the 2x2 boundary_mode x oob_policy matrix at L = 64 symmetric int8 (Sec. 7.4, Table 5's protocol): fraction
     of rows with any out-of-domain input, error on those rows, error on the in-range rows.
-Both layers run as the library's HIP kernels; only the error statistics are taken with torch.  The layers are
-randomly initialised here, so the absolute numbers are not the paper's; the trends are (error halves per
+With --sweep it also prints, for the 256 -> 256 layer of the L x scheme sweep (G = 8, batch 16384), the error of
+the LUT layer against the B-spline layer and the time of both per point: the latency is flat in L (Sec. 7.2).
+Both layers and the error statistics (lutkan_error_stats, Sec. 5.6) run as the library's HIP kernels.  The layers
+are randomly initialised here, so the absolute numbers are not the paper's; the trends are (error halves per
 doubling of L; in-range error independent of the contract; half_open counts inputs clipped onto t_K as OOB).
 """
 from __future__ import annotations
@@ -23,11 +25,12 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--seeds", type=int, default=5)
     ap.add_argument("--batch", type=int, default=4096)
+    ap.add_argument("--sweep", action="store_true", help="also run the 256->256 L x scheme sweep with timings")
     args = ap.parse_args()
     import torch
 
     import paper_2601_03332_amd as lk
-    from lutkan_inputs import ASYM_UINT8, CLIP_X, CLOSED, HALF_OPEN, SYM_INT8, ZERO_SPLINE, case_a
+    from lutkan_inputs import ASYM_UINT8, CLIP_X, CLOSED, HALF_OPEN, SYM_INT8, ZERO_SPLINE, case_a, cfg3
 
     dev = "cuda:0"
 
@@ -37,21 +40,13 @@ def main():
         art = lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, s.boundary, s.oob,
                                 edge_scales=s.edge_scales)
         x = torch.from_numpy(w.x).to(dev)
-        stats = torch.zeros(2, dtype=torch.int64, device=dev)
-        y_lut = lk.lutkan_forward(art.to_device(dev), x, stats=stats)
+        y_lut = lk.lutkan_forward(art.to_device(dev), x)
         # reference: the un-quantised spline layer under closed + clip_x (every clipped input is in its domain)
         y_ref = lk.bspline_kan_forward(art.bspline_to_device(dev).with_contract(CLOSED, CLIP_X), x)
-        lo, hi = float(art.knots[0]), float(art.knots[-1])
-        inside = (x >= lo) & ((x <= hi) if boundary == CLOSED else (x < hi))
-        row_in = inside.all(dim=1)
-        err = (y_lut - y_ref).abs()
-        e_in = err[row_in]
-        e_out = err[~row_in]
-        return dict(mae_in=float(e_in.mean()) if e_in.numel() else float("nan"),
-                    max_in=float(e_in.max()) if e_in.numel() else float("nan"),
-                    mae_oob=float(e_out.mean()) if e_out.numel() else float("nan"),
-                    max_oob=float(e_out.max()) if e_out.numel() else float("nan"),
-                    oob_any_frac=float(stats[1].item()) / x.shape[0])
+        st = lk.lutkan_error_stats(y_lut, y_ref, x, float(art.knots[0]), float(art.knots[-1]), boundary)
+        return dict(mae_in=st["mae_in"], max_in=st["max_abs_in"] if st["rows_in"] else float("nan"),
+                    mae_oob=st["mae_oob"], max_oob=st["max_abs_oob"] if st["rows_oob"] else float("nan"),
+                    oob_any_frac=st["oob_any_frac"])
 
     def agg(rows, key):
         v = np.array([r[key] for r in rows], dtype=np.float64)
@@ -70,6 +65,39 @@ def main():
         for oob, on in ((CLIP_X, "clip_x"), (ZERO_SPLINE, "zero_spline")):
             rows = [run(seed, 64, SYM_INT8, boundary, oob) for seed in range(args.seeds)]
             print(f"{bn:>10} {on:>12} {agg(rows, 'oob_any_frac'):>20} {agg(rows, 'mae_oob'):>24} {agg(rows, 'max_oob'):>24} {agg(rows, 'mae_in'):>24}")
+
+    if args.sweep:
+        def timed(fn, n=30, warm=5):
+            for _ in range(warm):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(n):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / n
+
+        print()
+        print("256 -> 256, G = 8, batch 16384, x ~ U(-1,1), closed + clip_x: error vs the B-spline layer and time per forward")
+        print(f"{'L':>4} {'scheme':>10} {'MAE':>12} {'MaxAbs':>12} {'LUT ms':>9} {'B-spline ms':>12} {'G edge-evals/s':>15} {'table MiB':>10}")
+        for scheme, name in ((SYM_INT8, "symmetric"), (ASYM_UINT8, "asymmetric")):
+            for L in (16, 32, 64, 128):
+                w = cfg3(L=L, scheme=scheme)
+                s = w.layers[0]
+                art = lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, s.boundary, s.oob)
+                x = torch.from_numpy(w.x).to(dev)
+                lut, spl = art.to_device(dev), art.bspline_to_device(dev)
+                B = x.shape[0]
+                y_lut = torch.empty((B, s.m), dtype=torch.float32, device=dev)
+                y_ref = torch.empty_like(y_lut)
+                ws = torch.empty(lk.lutkan_forward_workspace_bytes(lut, B), dtype=torch.uint8, device=dev)
+                wsb = torch.empty(lk.bspline_forward_workspace_bytes(spl, B), dtype=torch.uint8, device=dev)
+                t_lut = timed(lambda: lk.lutkan_forward(lut, x, y_lut, workspace=ws))
+                t_spl = timed(lambda: lk.bspline_kan_forward(spl, x, y_ref, workspace=wsb))
+                st = lk.lutkan_error_stats(y_lut, y_ref, x, float(art.knots[0]), float(art.knots[-1]), s.boundary)
+                print(f"{L:>4} {name:>10} {st['mae_in']:>12.6f} {st['max_abs_in']:>12.6f} {t_lut:>9.3f} {t_spl:>12.3f} "
+                      f"{B * s.d * s.m / t_lut / 1e6:>15.1f} {art.info.table_bytes / 2**20:>10.1f}")
 
 
 if __name__ == "__main__":

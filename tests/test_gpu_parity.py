@@ -406,3 +406,57 @@ def test_spline_component_special_inputs():
     s = w.layers[0]
     for algo in (lk.ALGO_GATHER, lk.ALGO_TILED):
         _check_layer(s, x[:7], algo, what="sc special")
+
+
+STATS_CASES = [
+    # seed, B, d, m, boundary, spread of x around the domain [-1, 1]
+    (701, 1, 1, 1, CLOSED, 1.5),
+    (702, 63, 7, 5, HALF_OPEN, 1.2),
+    (703, 1000, 70, 130, CLOSED, 1.05),
+    (704, 4099, 64, 8, HALF_OPEN, 1.0),          # U(-1, 1): every row in-range
+    (705, 300, 300, 3, CLOSED, 3.0),             # every row has an input outside
+    (706, 20000, 16, 64, HALF_OPEN, 1.01),
+]
+
+
+@pytest.mark.parametrize("case", STATS_CASES, ids=lambda c: f"seed{c[0]}")
+def test_error_stats_kernel(case):
+    """Sec. 5.6 statistics reduced on the device against their plain definition: counts and maxima exact, fp64 sums
+    up to the order of summation."""
+    seed, B, d, m, boundary, spread = case
+    rng = np.random.Generator(np.random.PCG64(seed))
+    x = rng.uniform(-spread, spread, size=(B, d)).astype(np.float32)
+    x.reshape(-1)[rng.integers(0, B * d, size=max(1, B * d // 50))] = np.float32(1.0)      # inputs exactly on t_K
+    y = rng.normal(size=(B, m)).astype(np.float32)
+    r = (y + rng.normal(scale=1e-3, size=(B, m))).astype(np.float32)
+    if B > 10:
+        x[B // 2, 0] = np.nan
+        y[B // 3, m // 2] = np.nan
+    _say(f"case stats seed={seed} B={B} d={d} m={m} boundary={boundary}")
+    got = lk.lutkan_error_stats(torch.from_numpy(y).to(DEV), torch.from_numpy(r).to(DEV), torch.from_numpy(x).to(DEV),
+                                -1.0, 1.0, boundary)
+    want = oracle.error_stats(y, r, x, -1.0, 1.0, boundary)
+    for key in ("rows_in", "rows_oob", "nan_outputs", "max_abs_in", "max_abs_oob", "oob_any_frac"):
+        assert got[key] == want[key], key
+    for key in ("sum_abs_in", "sum_abs_oob", "mae_in", "mae_oob"):
+        if np.isnan(want[key]):
+            assert np.isnan(got[key]), key
+        else:
+            assert abs(got[key] - want[key]) <= 1e-12 * abs(want[key]) + 1e-300, key
+
+
+def test_error_stats_of_a_lut_layer_against_its_spline_layer():
+    """The protocol end to end on one layer: LUT output vs B-spline output, subsets by In(x)."""
+    w = random_layer(711, 8, 128, 5, 32, ASYM_UINT8, HALF_OPEN, ZERO_SPLINE, 8192)
+    s = w.layers[0]
+    art, _ = _compile_both(s)
+    xg = torch.from_numpy(w.x).to(DEV)
+    y_lut = lk.lutkan_forward(_device_layer(art, s), xg)
+    y_ref = lk.bspline_kan_forward(art.bspline_to_device(DEV).with_contract(CLOSED, CLIP_X), xg)
+    got = lk.lutkan_error_stats(y_lut, y_ref, xg, float(art.knots[0]), float(art.knots[-1]), s.boundary)
+    torch.cuda.synchronize()
+    want = oracle.error_stats(y_lut.cpu().numpy(), y_ref.cpu().numpy(), w.x, art.knots[0], art.knots[-1], s.boundary)
+    assert (got["rows_in"], got["rows_oob"]) == (want["rows_in"], want["rows_oob"]) and min(got["rows_in"], got["rows_oob"]) > 100
+    assert got["max_abs_in"] == want["max_abs_in"] and got["max_abs_oob"] == want["max_abs_oob"]
+    assert abs(got["mae_in"] - want["mae_in"]) <= 1e-12 * want["mae_in"]
+    assert got["mae_oob"] > 2 * got["mae_in"]                     # zero_spline drops the OOB inputs' contributions

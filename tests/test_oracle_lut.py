@@ -532,3 +532,56 @@ def test_fp16_params_that_do_not_fit_are_refused():
     s = w.layers[0]
     with pytest.raises(ValueError):
         oracle.compile_layer(s.d, s.m, s.G, s.p, s.ext_knots, s.coef * np.float32(1e8), s.L, SYM_INT8, param_fp16=True)
+
+
+# ---------------------------------------------------------------------------------------------------
+# OOB evaluation protocol (Sec. 5.6): in-range / OOB-only error statistics
+# ---------------------------------------------------------------------------------------------------
+def test_error_stats_on_a_hand_made_example():
+    """Three rows on the domain [-1, 1]: all inside; one input at t_K; one input beyond.  Values by hand."""
+    x = np.array([[0.0, 0.5], [1.0, -1.0], [0.2, 1.5]], dtype=np.float32)
+    y = np.array([[1.0, 2.0], [3.0, 5.0], [0.0, 0.0]], dtype=np.float32)
+    r = np.array([[1.5, 2.0], [2.0, 5.5], [4.0, -1.0]], dtype=np.float32)
+    c = oracle.error_stats(y, r, x, -1.0, 1.0, CLOSED)            # t_K belongs to the domain: rows 0, 1 in-range
+    assert (c["rows_in"], c["rows_oob"], c["nan_outputs"]) == (2, 1, 0)
+    assert c["sum_abs_in"] == 0.5 + 0.0 + 1.0 + 0.5 and c["max_abs_in"] == 1.0 and c["mae_in"] == 2.0 / 4
+    assert c["sum_abs_oob"] == 5.0 and c["max_abs_oob"] == 4.0 and c["mae_oob"] == 2.5 and c["oob_any_frac"] == 1 / 3
+    h = oracle.error_stats(y, r, x, -1.0, 1.0, HALF_OPEN)         # x = t_K is outside (Sec. 5.5): row 1 moves over
+    assert (h["rows_in"], h["rows_oob"]) == (1, 2)
+    assert h["sum_abs_in"] == 0.5 and h["sum_abs_oob"] == 6.5 and h["max_abs_oob"] == 4.0 and h["mae_oob"] == 6.5 / 4
+
+
+def test_error_stats_against_plain_loops_and_nan_rules():
+    rng = np.random.default_rng(5)
+    B, d, m = 37, 5, 3
+    x = rng.uniform(-1.4, 1.4, size=(B, d)).astype(np.float32)
+    x[3, 2] = np.nan                                              # NaN input: the row is OOB
+    y = rng.normal(size=(B, m)).astype(np.float32)
+    r = rng.normal(size=(B, m)).astype(np.float32)
+    y[7, 1] = np.nan                                              # NaN difference: counted, left out
+    for boundary in (HALF_OPEN, CLOSED):
+        got = oracle.error_stats(y, r, x, -1.0, 1.0, boundary)
+        rows = {"in": 0, "oob": 0}
+        sums = {"in": 0.0, "oob": 0.0}
+        maxs = {"in": 0.0, "oob": 0.0}
+        nans = 0
+        for b in range(B):
+            inside = True
+            for i in range(d):
+                v = float(x[b, i])
+                ok = (v >= -1.0) and ((v <= 1.0) if boundary == CLOSED else (v < 1.0))
+                inside = inside and ok
+            key = "in" if inside else "oob"
+            rows[key] += 1
+            for j in range(m):
+                e = abs(float(y[b, j]) - float(r[b, j]))
+                if e != e:
+                    nans += 1
+                    continue
+                sums[key] += e
+                maxs[key] = max(maxs[key], e)
+        assert (got["rows_in"], got["rows_oob"], got["nan_outputs"]) == (rows["in"], rows["oob"], nans) and nans == 1
+        for key in ("in", "oob"):
+            assert abs(got["sum_abs_" + key] - sums[key]) <= 1e-12 * sums[key]
+            assert got["max_abs_" + key] == maxs[key]
+            assert abs(got["mae_" + key] - sums[key] / (rows[key] * m)) <= 1e-15
