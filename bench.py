@@ -39,6 +39,80 @@ def log(msg):
     print(msg, file=sys.stderr, flush=True)
 
 
+def time_all_configs(lk, torch, dev, with_oracle):
+    """Every workload of the scope table: one lutkan_model_forward and the chained B-spline layers (events, mean of 20
+    after 3 warm-up runs), and the oracle chain on a bounded sample of rows with all host threads."""
+    import numpy as np
+    from lutkan_inputs import ASYM_UINT8, HALF_OPEN, SYM_INT8, ZERO_SPLINE, cfg1, cfg2, cfg3, cfg4, cfg5
+
+    def timed(fn, n=20, warm=3):
+        for _ in range(warm):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    def oracle_rate(wl, budget_s=4.0):
+        import oracle
+        arts = [oracle.compile_layer(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme) for s in wl.layers]
+        per_row = sum(s.d * s.m for s in wl.layers)
+        threads = oracle.default_threads()
+
+        def chain(x):
+            for a, s in zip(arts, wl.layers):
+                x = oracle.lut_forward(a, s.boundary, s.oob, x, nthreads=threads).y
+            return x
+
+        rows = min(wl.x.shape[0], 64)
+        t0 = time.perf_counter()
+        chain(wl.x[:rows])
+        rate = rows / (time.perf_counter() - t0)
+        rows = int(min(wl.x.shape[0], max(rows, rate * budget_s)))
+        t0 = time.perf_counter()
+        chain(wl.x[:rows])
+        return rows * per_row / (time.perf_counter() - t0), rows
+
+    workloads = [("cfg1", cfg1()), ("cfg2", cfg2())]
+    workloads += [(f"cfg3 L={L} {'sym' if sc == SYM_INT8 else 'asym'}", cfg3(L=L, scheme=sc)) for sc in (SYM_INT8, ASYM_UINT8)
+                  for L in (16, 32, 64, 128)]
+    workloads += [(f"cfg4 B={B}", cfg4(B=B)) for B in (256, 4096, 32768)]
+    workloads += [("cfg5 closed+clip_x", cfg5()), ("cfg5 half_open+zero_spline", cfg5(boundary=HALF_OPEN, oob=ZERO_SPLINE))]
+    rows_out = []
+    log(f"[bench] {'workload':28s} {'B':>7s} {'LUT ms':>9s} {'G edge-evals/s':>15s} {'B-spline ms':>12s} {'ratio':>6s} {'oracle G/s':>11s}")
+    for name, wl in workloads:
+        arts = [lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, s.boundary, s.oob) for s in wl.layers]
+        layers = [a.to_device(dev) for a in arts]
+        splines = [a.bspline_to_device(dev) for a in arts]
+        x = torch.from_numpy(wl.x).to(dev)
+        B = x.shape[0]
+        ws = torch.empty(lk.lutkan_model_workspace_bytes(layers, B), dtype=torch.uint8, device=dev)
+        y = torch.empty((B, layers[-1].m), dtype=torch.float32, device=dev)
+        ms = timed(lambda: lk.lutkan_model_forward(layers, x, y, workspace=ws))
+        acts = [x] + [torch.empty((B, s.m), dtype=torch.float32, device=dev) for s in wl.layers]
+        wsb = torch.empty(max(lk.bspline_forward_workspace_bytes(b, B) for b in splines), dtype=torch.uint8, device=dev)
+
+        def spline_chain():
+            for li, b in enumerate(splines):
+                lk.bspline_kan_forward(b, acts[li], acts[li + 1], workspace=wsb)
+
+        msb = timed(spline_chain)
+        edges = sum(B * s.d * s.m for s in wl.layers)
+        rec = {"workload": name, "batch": B, "lut_ms": round(ms, 4), "edge_evals_per_s": round(edges / ms * 1e3, 1),
+               "bspline_ms": round(msb, 4), "lut_vs_bspline_speedup": round(msb / ms, 3)}
+        if with_oracle:
+            rate, rows = oracle_rate(wl)
+            rec.update(oracle_edge_evals_per_s=round(rate, 1), oracle_rows=rows)
+        rows_out.append(rec)
+        log(f"[bench] {name:28s} {B:7d} {ms:9.3f} {edges / ms / 1e6:15.1f} {msb:12.3f} {msb / ms:6.2f} "
+            f"{rec.get('oracle_edge_evals_per_s', float('nan')) / 1e9:11.3f}")
+        del arts, layers, splines, x, ws, y, acts, wsb
+    return rows_out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -48,6 +122,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bspline", action="store_true")
     ap.add_argument("--no-probes", action="store_true", help="skip the four peak-rate probes (FMA, LDS, L2, HBM)")
+    ap.add_argument("--all-configs", action="store_true",
+                    help="also time every workload of the scope table (LUT chain, B-spline chain, bounded oracle sample); "
+                         "the results go to extra.configs and, as a table, to stderr")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy, as a known-size reference for HBM counters")
     args = ap.parse_args()
@@ -211,9 +288,19 @@ def main():
         torch.cuda.synchronize()
         err = np.abs(yg[:rows].cpu().numpy().astype(np.float64) - ref.y)
         ok = bool(np.all(err <= 1e-5 * ref.A + 1e-6))
+        t0 = time.perf_counter()                              # the paper's protocol is single-threaded (Sec. 6.1)
+        oracle.lut_forward(ora, s.boundary, s.oob, w.x[:probe // 2], nthreads=1)
+        single = (probe // 2) * d * m / (time.perf_counter() - t0)
         cpu = {"value": round(rows * d * m / cdt, 1), "unit": "edge-evals/s", "cores": threads, "kind": "oracle",
-               "sample": f"first {rows} of {B} rows of the same workload, {cdt:.1f}s", "gpu_matches_oracle_on_sample": ok}
-        log(f"[bench] oracle: {rows} rows in {cdt:.1f}s on {threads} threads; GPU within tolerance on them: {ok}")
+               "sample": f"first {rows} of {B} rows of the same workload, {cdt:.1f}s", "gpu_matches_oracle_on_sample": ok,
+               "single_thread_value": round(single, 1)}
+        log(f"[bench] oracle: {rows} rows in {cdt:.1f}s on {threads} threads; GPU within tolerance on them: {ok}; "
+            f"one thread: {single:.3g} edge-evals/s")
+        del ora, ref
+
+    if args.all_configs:
+        del xs, ys, ws, layer, art
+        extra["configs"] = time_all_configs(lk, torch, dev, with_oracle=not args.no_cpu_baseline)
 
     out = {"metric": "lutkan_layer_edge_evals_per_s", "value": round(value, 1), "unit": "edge-evals/s", "n_gpus": 1,
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
