@@ -54,7 +54,6 @@ struct LocateArgs {
   int32_t closed, zero_spline;
   float tKs;             // safe upper clip value
   float knots[LUTKAN_MAX_K + 1];
-  unsigned long long *stats;   // nullable: {oob_count, oob_any_rows}
   int32_t *k_out, *l0_out;     // nullable trace outputs, [B][d]
   uint8_t *in_out;
   float *w_out;
@@ -98,83 +97,94 @@ __device__ __forceinline__ Located locate_one(const LocateArgs &a, float x) {
 }
 
 constexpr int kLocRows = 32;    // rows per block
-constexpr int kLocCols = 64;    // inputs per pass
+constexpr int kLocCols = 64;    // inputs per block
 
+// One block locates a tile of 32 rows x 64 inputs: x is read along inputs (coalesced), every thread locates eight
+// elements, the records are transposed through LDS and written along rows (coalesced): records are stored
+// [input][row].  blockIdx.x = row tile, blockIdx.y = input tile, so small batches still fill the GPU.
 // BASE: value_repr = spline_component, the record also carries SiLU(x).
 template <bool BASE>
 __global__ __launch_bounds__(256) void lutkan_locate_kernel(const LocateArgs a) {
   typedef typename std::conditional<BASE, u32x4, u32x2>::type rec_t;
   __shared__ rec_t s_rec[kLocCols][kLocRows + 1];
   rec_t *const rec_out = static_cast<rec_t *>(a.rec);
-  __shared__ int s_row_oob[kLocRows];
   const int tid = threadIdx.x;
   const int64_t b0 = (int64_t)blockIdx.x * kLocRows;
-  if (tid < kLocRows) s_row_oob[tid] = 0;
-  __syncthreads();
-  unsigned my_oob = 0;
+  const int i0 = blockIdx.y * kLocCols;
   const unsigned masked_index = (unsigned)(a.K * a.L) | ((unsigned)a.K << 16);
   const int il = tid & (kLocCols - 1);
-  // x of one pass: 8 rows x 1 input per thread, loaded one pass ahead so that the loads overlap the record stores
+  const int i = i0 + il;
   float xv[kLocRows / 4];
-  auto load_x = [&](int i0) {
 #pragma unroll
-    for (int p = 0; p < kLocRows / 4; ++p) {
-      const int64_t b = b0 + p * 4 + (tid >> 6);
-      xv[p] = (b < a.B && i0 + il < a.d) ? a.x[b * a.d + i0 + il] : 0.0f;
-    }
-  };
-  load_x(0);
-  for (int i0 = 0; i0 < a.d; i0 += kLocCols) {
-    // phase 1: x was read along inputs (coalesced); locate, park the record in LDS
-    const int i = i0 + il;
-#pragma unroll
-    for (int p = 0; p < kLocRows / 4; ++p) {
-      const int bl = p * 4 + (tid >> 6);
-      const int64_t b = b0 + bl;
-      rec_t rec = {};
-      rec.x = masked_index;
-      if (b < a.B && i < a.d) {
-        const float x = xv[p];
-        const Located o = locate_one(a, x);
-        const bool masked = a.zero_spline && !o.inside && !o.is_nan;
-        if (!masked) {
-          rec.x = (unsigned)(o.k * a.L + o.l0) | ((unsigned)o.k << 16);
-          rec.y = __float_as_uint(o.is_nan ? __builtin_nanf("") : o.w);
-        }
-        // base branch b(x) = SiLU(x) = x / (1 + exp(-x)) at the RAW input (Eq. 2); it is never masked (Sec. 5.4)
-        if constexpr (BASE) rec.z = __float_as_uint(__fdiv_rn(x, 1.0f + expf(-x)));
-        if (!o.inside) { ++my_oob; s_row_oob[bl] = 1; }
-        if (a.k_out) {
-          a.k_out[b * a.d + i] = o.k;
-          a.l0_out[b * a.d + i] = o.l0;
-          a.in_out[b * a.d + i] = o.inside ? 1 : 0;
-          a.w_out[b * a.d + i] = o.w;
-        }
-      }
-      s_rec[il][bl] = rec;
-    }
-    __syncthreads();
-    if (i0 + kLocCols < a.d) load_x(i0 + kLocCols);
-    // phase 2: write records along rows (coalesced stores)
-    const int bl2 = tid & (kLocRows - 1);
-#pragma unroll
-    for (int p = 0; p < kLocCols / 8; ++p) {
-      const int il2 = p * 8 + (tid >> 5);
-      const int i2 = i0 + il2;
-      if (i2 < a.d && b0 + bl2 < a.Bp) rec_out[(int64_t)i2 * a.Bp + b0 + bl2] = s_rec[il2][bl2];
-    }
-    __syncthreads();
+  for (int p = 0; p < kLocRows / 4; ++p) {               // all eight loads in flight before the first is used
+    const int64_t b = b0 + p * 4 + (tid >> 6);
+    xv[p] = (b < a.B && i < a.d) ? a.x[b * a.d + i] : 0.0f;
   }
-  if (a.stats) {
-    // one atomic per wave for the input counter, one per block for the row counter
-    unsigned v = my_oob;
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, kWave);
-    if ((tid & 63) == 0 && v) atomicAdd(&a.stats[0], (unsigned long long)v);
-    if (tid < kLocRows) {
-      unsigned r = (unsigned)s_row_oob[tid];
-      for (int off = 16; off > 0; off >>= 1) r += __shfl_down(r, off, kWave);
-      if (tid == 0 && r) atomicAdd(&a.stats[1], (unsigned long long)r);
+#pragma unroll
+  for (int p = 0; p < kLocRows / 4; ++p) {
+    const int bl = p * 4 + (tid >> 6);
+    const int64_t b = b0 + bl;
+    rec_t rec = {};
+    rec.x = masked_index;
+    if (b < a.B && i < a.d) {
+      const float x = xv[p];
+      const Located o = locate_one(a, x);
+      const bool masked = a.zero_spline && !o.inside && !o.is_nan;
+      if (!masked) {
+        rec.x = (unsigned)(o.k * a.L + o.l0) | ((unsigned)o.k << 16);
+        rec.y = __float_as_uint(o.is_nan ? __builtin_nanf("") : o.w);
+      }
+      // base branch b(x) = SiLU(x) = x / (1 + exp(-x)) at the RAW input (Eq. 2); it is never masked (Sec. 5.4)
+      if constexpr (BASE) rec.z = __float_as_uint(__fdiv_rn(x, 1.0f + expf(-x)));
+      if (a.k_out) {
+        a.k_out[b * a.d + i] = o.k;
+        a.l0_out[b * a.d + i] = o.l0;
+        a.in_out[b * a.d + i] = o.inside ? 1 : 0;
+        a.w_out[b * a.d + i] = o.w;
+      }
     }
+    s_rec[il][bl] = rec;
+  }
+  __syncthreads();
+  const int bl2 = tid & (kLocRows - 1);
+#pragma unroll
+  for (int p = 0; p < kLocCols / 8; ++p) {
+    const int il2 = p * 8 + (tid >> 5);
+    const int i2 = i0 + il2;
+    if (i2 < a.d && b0 + bl2 < a.Bp) rec_out[(int64_t)i2 * a.Bp + b0 + bl2] = s_rec[il2][bl2];
+  }
+}
+
+// OOB counters of Sec. 5.5-5.6 (optional): inputs (b,i) with In(x) = 0 and rows with at least one such input.
+// One wave per row at a time; one atomic per work-group and counter.
+constexpr int kOobRowsPerWave = 8;
+
+__global__ __launch_bounds__(256) void oob_count_kernel(const float *x, int64_t B, int d, float t0, float tK, int closed,
+                                                        unsigned long long *stats) {
+  __shared__ unsigned s_inputs[4], s_rows[4];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  unsigned inputs = 0, rows = 0;
+  for (int r = 0; r < kOobRowsPerWave; ++r) {
+    const int64_t b = ((int64_t)blockIdx.x * kOobRowsPerWave + r) * 4 + wave;
+    if (b >= B) break;                                   // wave-uniform
+    unsigned outside = 0;
+    for (int i = lane; i < d; i += 64) {
+      const float v = x[b * d + i];
+      const bool in = closed ? (v >= t0 && v <= tK) : (v >= t0 && v < tK);
+      outside += in ? 0u : 1u;
+    }
+    for (int off = 32; off > 0; off >>= 1) outside += __shfl_down(outside, off, kWave);
+    outside = __shfl(outside, 0, kWave);
+    inputs += outside;
+    rows += outside ? 1u : 0u;
+  }
+  if (lane == 0) { s_inputs[wave] = inputs; s_rows[wave] = rows; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const unsigned ti = s_inputs[0] + s_inputs[1] + s_inputs[2] + s_inputs[3];
+    const unsigned tr = s_rows[0] + s_rows[1] + s_rows[2] + s_rows[3];
+    if (ti) atomicAdd(&stats[0], (unsigned long long)ti);
+    if (tr) atomicAdd(&stats[1], (unsigned long long)tr);
   }
 }
 
@@ -532,8 +542,9 @@ struct SplineLocateArgs {
   float ext_knots[LUTKAN_MAX_K + 7];
 };
 
-constexpr int kSplCols = 32;   // inputs per pass of the B-spline locate kernel (32-byte records)
+constexpr int kSplCols = 32;   // inputs per block of the B-spline locate kernel (32-byte records)
 
+// Same tiling as the LUT locate kernel: blockIdx.x = tile of 32 rows, blockIdx.y = tile of 32 inputs.
 __global__ __launch_bounds__(256) void bspline_locate_kernel(const SplineLocateArgs a) {
   __shared__ u32x4 s_rec[2][kSplCols][kLocRows + 1];
   __shared__ float s_tau[LUTKAN_MAX_K + 7];
@@ -542,7 +553,8 @@ __global__ __launch_bounds__(256) void bspline_locate_kernel(const SplineLocateA
   for (int r = tid; r < a.G + 7; r += 256) s_tau[r] = a.ext_knots[r];
   __syncthreads();
   const float t0 = s_tau[3], tK = s_tau[3 + a.G];
-  for (int i0 = 0; i0 < a.d; i0 += kSplCols) {
+  {
+    const int i0 = blockIdx.y * kSplCols;
     const int il = tid & (kSplCols - 1);
     const int i = i0 + il;
 #pragma unroll 1
@@ -595,7 +607,6 @@ __global__ __launch_bounds__(256) void bspline_locate_kernel(const SplineLocateA
         a.rec[o + 1] = s_rec[1][il2][bl2];
       }
     }
-    __syncthreads();
   }
 }
 
@@ -949,12 +960,19 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   const bool with_base = (l->value_repr == LUTKAN_REPR_SPLINE_COMPONENT);
   la.tKs = la.closed ? l->knots[l->K] : std::nextafterf(l->knots[l->K], -INFINITY);
   for (int k = 0; k <= l->K; ++k) la.knots[k] = l->knots[k];
-  la.stats = reinterpret_cast<unsigned long long *>(stats);
   la.k_out = trace ? k_out : nullptr; la.l0_out = l0_out; la.in_out = in_out; la.w_out = w_out;
   if (phases & kLocate) {
-    if (with_base) hipLaunchKernelGGL(lutkan_locate_kernel<true>, dim3((unsigned)(Bp / kLocRows)), dim3(256), 0, s, la);
-    else hipLaunchKernelGGL(lutkan_locate_kernel<false>, dim3((unsigned)(Bp / kLocRows)), dim3(256), 0, s, la);
+    const dim3 lgrid((unsigned)(Bp / kLocRows), (unsigned)((l->d + kLocCols - 1) / kLocCols));
+    if (lgrid.y > 65535u) return fail(LUTKAN_EUNSUPPORTED, "%s: d too large", who);
+    if (with_base) hipLaunchKernelGGL(lutkan_locate_kernel<true>, lgrid, dim3(256), 0, s, la);
+    else hipLaunchKernelGGL(lutkan_locate_kernel<false>, lgrid, dim3(256), 0, s, la);
     if (int rc = check_launch("lutkan_locate_kernel")) return rc;
+    if (stats) {
+      const int64_t rows_per_group = 4 * kOobRowsPerWave;
+      hipLaunchKernelGGL(oob_count_kernel, dim3((unsigned)((B + rows_per_group - 1) / rows_per_group)), dim3(256), 0, s, x, B, l->d,
+                         l->knots[0], l->knots[l->K], la.closed, reinterpret_cast<unsigned long long *>(stats));
+      if (int rc = check_launch("oob_count_kernel")) return rc;
+    }
   }
   if (!(phases & kEdges)) return LUTKAN_OK;
 
@@ -1065,7 +1083,9 @@ int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y
   la.tKs = la.closed ? l->ext_knots[3 + G] : std::nextafterf(l->ext_knots[3 + G], -INFINITY);
   for (int r = 0; r < G + 7; ++r) la.ext_knots[r] = l->ext_knots[r];
   if (phases & kLocate) {
-    hipLaunchKernelGGL(bspline_locate_kernel, dim3((unsigned)(Bp / kLocRows)), dim3(256), 0, s, la);
+    const dim3 lgrid((unsigned)(Bp / kLocRows), (unsigned)((l->d + kSplCols - 1) / kSplCols));
+    if (lgrid.y > 65535u) return fail(LUTKAN_EUNSUPPORTED, "%s: d too large", who);
+    hipLaunchKernelGGL(bspline_locate_kernel, lgrid, dim3(256), 0, s, la);
     if (int rc = check_launch("bspline_locate_kernel")) return rc;
   }
   if (!(phases & kEdges)) return LUTKAN_OK;

@@ -460,3 +460,36 @@ def test_error_stats_of_a_lut_layer_against_its_spline_layer():
     assert got["max_abs_in"] == want["max_abs_in"] and got["max_abs_oob"] == want["max_abs_oob"]
     assert abs(got["mae_in"] - want["mae_in"]) <= 1e-12 * want["mae_in"]
     assert got["mae_oob"] > 2 * got["mae_in"]                     # zero_spline drops the OOB inputs' contributions
+
+
+def test_model_forward_replays_correctly_from_a_hip_graph():
+    """The chain launches only kernels (no allocation, no memset, no synchronisation), so it can be captured;
+    every replay, with eager work in between, reproduces the eager result bit for bit."""
+    w = cfg2(B=5000)
+    arts = [lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, s.boundary, s.oob) for s in w.layers]
+    layers = [a.to_device(DEV) for a in arts]
+    x = torch.from_numpy(w.x).to(DEV)
+    B = x.shape[0]
+    ws = torch.empty(lk.lutkan_model_workspace_bytes(layers, B), dtype=torch.uint8, device=DEV)
+    y = torch.empty((B, layers[-1].m), dtype=torch.float32, device=DEV)
+    stats = torch.zeros((len(layers), 2), dtype=torch.int64, device=DEV)
+    _say(f"case graph capture {w.name} B={B}")
+    lk.lutkan_model_forward(layers, x, y, stats=stats, workspace=ws)           # warm-up: one-time kernel attributes
+    torch.cuda.synchronize()
+    y_eager, stats_eager = y.clone(), stats.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        lk.lutkan_model_forward(layers, x, y, stats=stats, workspace=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        lk.lutkan_model_forward(layers, x, y, stats=stats, workspace=ws)
+    for _ in range(3):
+        y.fill_(7.0)
+        stats.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, y_eager) and torch.equal(stats, stats_eager)
+        lk.lutkan_model_forward(layers, x, y, workspace=ws)                    # eager work between replays
+        torch.cuda.synchronize()
