@@ -137,9 +137,9 @@ const float *lutkan_artifact_edge_out_scale(const lutkan_artifact *a);    /* [E]
 /* Device tables (host copies to upload verbatim).  Columns are cut into n_tiles tiles of jt outputs; the
  * last tile is zero padded.  LUT table: for tile t and input i one contiguous slice of blob_bytes bytes
  *     float   base  [jt]                       (spline_component only: s_out * s_base of the edge (i, column))
- *     param   p     [K+1][jt]                  (symmetric: fp32 alpha; asymmetric: the fp32 pair {alpha, y_min} --
+ *     param   p     [K+1] rows                 (a row is alpha[jt], followed for the asymmetric scheme by y_min[jt] --
  *                                               y_min is elided when it is identically 0, Sec. 7.5; row K is all zero;
- *                                               with fp16 parameters each value is a binary16)
+ *                                               values are fp32, or binary16 with fp16 parameters)
  *     code    q     [K*L+2][jt]                (one byte per code, row k*L+l, i.e. the [i][segment][sample][j]
  *                                               order per tile: uint8 codes as they are, int8 codes excess-128,
  *                                               byte = q + 128; the two trailing rows are all-zero bytes)

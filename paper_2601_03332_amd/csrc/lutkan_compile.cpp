@@ -136,23 +136,16 @@ struct SlicePacker {
   // Segment k of the edge in column jj: its dequantisation parameters (times gain = s_out * s_spline with
   // spline_component, else exactly as given; binary16 parameters arrive already rounded) and its L codes.
   void put_segment(uint8_t *slice, int jj, int k, float alpha, float ymin, bool with_gain, float gain, const uint8_t *codes) const {
-    uint8_t *params = slice + lay.params_off;
+    // parameter row k: the alpha of every column, then (asymmetric only) the y_min of every column
+    uint8_t *row = slice + lay.params_off + (size_t)k * lay.param_row_bytes;
     if (half_params) {
-      uint16_t *p16 = reinterpret_cast<uint16_t *>(params);
-      if (scheme == LUTKAN_ASYM_UINT8) {
-        p16[((size_t)k * jt + jj) * 2] = to_binary16(alpha).bits;
-        p16[((size_t)k * jt + jj) * 2 + 1] = to_binary16(ymin).bits;
-      } else {
-        p16[(size_t)k * jt + jj] = to_binary16(alpha).bits;
-      }
+      uint16_t *p16 = reinterpret_cast<uint16_t *>(row);
+      p16[jj] = to_binary16(alpha).bits;
+      if (scheme == LUTKAN_ASYM_UINT8) p16[jt + jj] = to_binary16(ymin).bits;
     } else {
-      float *p32 = reinterpret_cast<float *>(params);
-      if (scheme == LUTKAN_ASYM_UINT8) {
-        p32[((size_t)k * jt + jj) * 2] = with_gain ? gain * alpha : alpha;
-        p32[((size_t)k * jt + jj) * 2 + 1] = with_gain ? gain * ymin : ymin;
-      } else {
-        p32[(size_t)k * jt + jj] = with_gain ? gain * alpha : alpha;
-      }
+      float *p32 = reinterpret_cast<float *>(row);
+      p32[jj] = with_gain ? gain * alpha : alpha;
+      if (scheme == LUTKAN_ASYM_UINT8) p32[jt + jj] = with_gain ? gain * ymin : ymin;
     }
     // device codes: uint8 as is; int8 stored excess-128 (q + 128), which the kernels undo exactly
     const uint8_t flip = (scheme == LUTKAN_SYM_INT8) ? 0x80 : 0x00;

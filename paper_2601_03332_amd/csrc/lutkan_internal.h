@@ -16,7 +16,7 @@ int fail(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
 
 // Byte offsets inside one (tile, input) slice of the LUT device table:
 //   [base jt f32 (spline_component only)][params (K+1) rows of jt entries][codes (K*L+2) rows of jt bytes][pad to 16 B]
-// A parameter entry is alpha (symmetric) or the pair {alpha, y_min} (asymmetric), fp32 or binary16 values.
+// A parameter row is alpha[jt], then for the asymmetric scheme y_min[jt]; fp32 or binary16 values.
 // Parameter row K and code rows K*L, K*L+1 are all zero: the kernels send masked inputs there.
 struct BlobLayout {
   int32_t params_off, param_row_bytes, codes_off, bytes;

@@ -237,7 +237,6 @@ __global__ __launch_bounds__(256) void lutkan_gather_kernel(const EdgeArgs a, co
   if (j >= a.m || b >= a.B) return;
   const int t = j / a.jt, jj = j - t * a.jt;
   const unsigned char *tile = a.table + (size_t)t * a.d * a.blob_bytes;
-  const int poff = ((SCHEME == LUTKAN_ASYM_UINT8) ? 8 * jj : 4 * jj) >> (a.param_fp16 ? 1 : 0);
   const int rec_words = a.with_base ? 4 : 2;
   const unsigned *recs = static_cast<const unsigned *>(a.rec);
   float acc = 0.0f;
@@ -259,14 +258,15 @@ __global__ __launch_bounds__(256) void lutkan_gather_kernel(const EdgeArgs a, co
       const unsigned param_off = (unsigned)a.params_off + (rec[u].x >> 16) * (unsigned)a.param_row_bytes;
       c0[u] = slice[code_off + jj];
       c1[u] = slice[code_off + a.jt + jj];
+      // a parameter row is the alpha of every column, then (asymmetric) the y_min of every column
       if (a.param_fp16) {
-        const _Float16 *prm = reinterpret_cast<const _Float16 *>(slice + param_off + poff);
-        al[u] = (float)prm[0];
-        ym[u] = (SCHEME == LUTKAN_ASYM_UINT8) ? (float)prm[1] : 0.0f;
+        const _Float16 *prm = reinterpret_cast<const _Float16 *>(slice + param_off);
+        al[u] = (float)prm[jj];
+        ym[u] = (SCHEME == LUTKAN_ASYM_UINT8) ? (float)prm[a.jt + jj] : 0.0f;
       } else {
-        const float *prm = reinterpret_cast<const float *>(slice + param_off + poff);
-        al[u] = prm[0];
-        ym[u] = (SCHEME == LUTKAN_ASYM_UINT8) ? prm[1] : 0.0f;
+        const float *prm = reinterpret_cast<const float *>(slice + param_off);
+        al[u] = prm[jj];
+        ym[u] = (SCHEME == LUTKAN_ASYM_UINT8) ? prm[a.jt + jj] : 0.0f;
       }
       bg[u] = a.with_base ? reinterpret_cast<const float *>(slice)[jj] : 0.0f;
     }
@@ -355,7 +355,8 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
   constexpr int RPS = 64 / LPR;
   constexpr int RW = RPS * NP;
   static_assert(RW <= 64, "a wave's records for one input must fit one 1 KiB copy step");
-  constexpr int PSZ = ((SCHEME == LUTKAN_ASYM_UINT8) ? 32 : 16) / (PH ? 2 : 1);   // parameter bytes per lane (4 columns)
+  constexpr int PSZ = PH ? 8 : 16;         // bytes of a lane's four alphas (and of its four y_min, one plane further)
+  constexpr int PLANE = JT * (PH ? 2 : 4); // a parameter row is the alpha plane, then (asymmetric) the y_min plane
   static_assert(!(BASE && PH), "float16 parameters are not combined with the base branch");
   constexpr int RB = BASE ? 16 : 8;                              // bytes per record
   constexpr int REC_LANES = RW * RB / 16;                        // lanes that copy 16 bytes of the wave's records
@@ -410,8 +411,8 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
     typedef typename std::conditional<BASE, u32x3, u32x2>::type rec_t;        // 12-byte or 8-byte LDS read
     f32x4 base_gain = {0.f, 0.f, 0.f, 0.f};
     if (BASE) base_gain = *reinterpret_cast<const f32x4 *>(slice + sub * 16) * kTwoToMinus24;
-    // parameters of the lane's 4 columns as loaded: fp32 {a0,a1,a2,a3} or {a0,y0,a1,y1},{a2,y2,a3,y3};
-    // binary16: the same values packed two per word, in pa.x, pa.y (symmetric) or pa.x .. pa.w (asymmetric)
+    // parameters of the lane's 4 columns as loaded: pa = the four alphas, pb = the four y_min (asymmetric);
+    // binary16 parameters are packed two per word in .x and .y
     struct Fetched { unsigned c0, c1; f32x4 pa, pb; };
     auto fetch = [&](const rec_t &rc) {
       Fetched f;
@@ -425,14 +426,18 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
       typedef const __attribute__((address_space(3))) f32x4 *lds_f32x4;
       f.c0 = *(lds_u32)cp;
       f.c1 = *(lds_u32)(cp + JT);
-      if constexpr (PH && SCHEME == LUTKAN_SYM_INT8) {
+      f.pb = f32x4{0.f, 0.f, 0.f, 0.f};
+      if constexpr (PH) {
         typedef const __attribute__((address_space(3))) f32x2 *lds_f32x2;
-        const f32x2 h = *(lds_f32x2)pp;
-        f.pa = f32x4{h.x, h.y, 0.f, 0.f};
-        f.pb = f32x4{0.f, 0.f, 0.f, 0.f};
+        const f32x2 ha = *(lds_f32x2)pp;
+        f.pa = f32x4{ha.x, ha.y, 0.f, 0.f};
+        if (SCHEME == LUTKAN_ASYM_UINT8) {
+          const f32x2 hy = *(lds_f32x2)(pp + PLANE);
+          f.pb = f32x4{hy.x, hy.y, 0.f, 0.f};
+        }
       } else {
         f.pa = *(lds_f32x4)pp;
-        f.pb = (SCHEME == LUTKAN_ASYM_UINT8 && !PH) ? *(lds_f32x4)(pp + 16) : f32x4{0.f, 0.f, 0.f, 0.f};
+        if (SCHEME == LUTKAN_ASYM_UINT8) f.pb = *(lds_f32x4)(pp + PLANE);
       }
       return f;
     };
@@ -443,7 +448,7 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
     for (int p = 0; p < NP; ++p) {
       Fetched f_nxt = f_cur;
       rec_t rc_nn = rc_nxt;
-      if (SCHEME == LUTKAN_ASYM_UINT8 && !PH) asm volatile("" ::"v"(f_cur.pb));
+      if (SCHEME == LUTKAN_ASYM_UINT8) asm volatile("" ::"v"(f_cur.pb.x));
       asm volatile("" ::"v"(f_cur.pa.x), "v"(f_cur.c1), "v"(rc_nxt.y));        // first touch of step p's data
       __builtin_amdgcn_sched_barrier(0);
       if (p + 2 < NP) rc_nn = *reinterpret_cast<const rec_t *>(rec_buf + (p + 2) * (RPS * RB));
@@ -452,21 +457,13 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
       const float w = __uint_as_float(rc_cur.y);
       float al[4], ym[4];
       if constexpr (PH) {
-        const f16x2 h0 = bits_to_f16x2(__float_as_uint(f_cur.pa.x)), h1 = bits_to_f16x2(__float_as_uint(f_cur.pa.y));
-        if (SCHEME == LUTKAN_ASYM_UINT8) {
-          const f16x2 h2 = bits_to_f16x2(__float_as_uint(f_cur.pa.z)), h3 = bits_to_f16x2(__float_as_uint(f_cur.pa.w));
-          al[0] = (float)h0.x; ym[0] = (float)h0.y; al[1] = (float)h1.x; ym[1] = (float)h1.y;
-          al[2] = (float)h2.x; ym[2] = (float)h2.y; al[3] = (float)h3.x; ym[3] = (float)h3.y;
-        } else {
-          al[0] = (float)h0.x; al[1] = (float)h0.y; al[2] = (float)h1.x; al[3] = (float)h1.y;
-          ym[0] = ym[1] = ym[2] = ym[3] = 0.0f;
-        }
-      } else if (SCHEME == LUTKAN_ASYM_UINT8) {
-        al[0] = f_cur.pa.x; ym[0] = f_cur.pa.y; al[1] = f_cur.pa.z; ym[1] = f_cur.pa.w;
-        al[2] = f_cur.pb.x; ym[2] = f_cur.pb.y; al[3] = f_cur.pb.z; ym[3] = f_cur.pb.w;
+        const f16x2 a01 = bits_to_f16x2(__float_as_uint(f_cur.pa.x)), a23 = bits_to_f16x2(__float_as_uint(f_cur.pa.y));
+        const f16x2 y01 = bits_to_f16x2(__float_as_uint(f_cur.pb.x)), y23 = bits_to_f16x2(__float_as_uint(f_cur.pb.y));
+        al[0] = (float)a01.x; al[1] = (float)a01.y; al[2] = (float)a23.x; al[3] = (float)a23.y;
+        ym[0] = (float)y01.x; ym[1] = (float)y01.y; ym[2] = (float)y23.x; ym[3] = (float)y23.y;
       } else {
         al[0] = f_cur.pa.x; al[1] = f_cur.pa.y; al[2] = f_cur.pa.z; al[3] = f_cur.pa.w;
-        ym[0] = ym[1] = ym[2] = ym[3] = 0.0f;
+        ym[0] = f_cur.pb.x; ym[1] = f_cur.pb.y; ym[2] = f_cur.pb.z; ym[3] = f_cur.pb.w;
       }
       // bytes {b3,b2,b1,b0} -> packed fp16 denormals {b1,b0} and {b3,b2}, each worth byte * 2^-24
       f16x2 q0lo = bits_to_f16x2(__builtin_amdgcn_perm(f_cur.c0, f_cur.c0, 0x0c010c00u));

@@ -70,14 +70,11 @@ def test_host_compile_is_bit_identical_to_the_oracle_and_tables_follow_the_docum
         for i in range(s.d):
             e = i * s.m + cols
             blob = tab[t, i]
+            prm = blob[:codes_off].view(np.float32).reshape(K + 1, 2 if asym else 1, jt)   # row = alpha plane, y_min plane
+            np.testing.assert_array_equal(prm[:K, 0, :n], art.scale[e].T)
             if asym:
-                prm = blob[:codes_off].view(np.float32).reshape(K + 1, jt, 2)
-                np.testing.assert_array_equal(prm[:K, :n, 0], art.scale[e].T)
-                np.testing.assert_array_equal(prm[:K, :n, 1], art.y_min[e].T)
-            else:
-                prm = blob[:codes_off].view(np.float32).reshape(K + 1, jt, 1)
-                np.testing.assert_array_equal(prm[:K, :n, 0], art.scale[e].T)
-            assert np.all(prm[:, n:] == 0) and np.all(prm[K] == 0)
+                np.testing.assert_array_equal(prm[:K, 1, :n], art.y_min[e].T)
+            assert np.all(prm[:, :, n:] == 0) and np.all(prm[K] == 0)
             codes = blob[codes_off:codes_off + K * L * jt].reshape(K, L, jt)
             want = np.transpose(art.q[e], (1, 2, 0))
             want = want.view(np.uint8) if asym else (want.astype(np.int16) + 128).astype(np.uint8)   # int8: excess-128
@@ -205,10 +202,10 @@ def test_spline_component_tables_carry_the_base_row_and_folded_gains():
             base = tab[t, i, :params_off].view(np.float32)
             np.testing.assert_array_equal(base[:n], so[e] * sb[e])
             np.testing.assert_array_equal(ctab[t, i, 0, :n], so[e] * sb[e])
-            prm = tab[t, i, params_off:codes_off].view(np.float32).reshape(K + 1, jt, 2)
+            prm = tab[t, i, params_off:codes_off].view(np.float32).reshape(K + 1, 2, jt)
             gain = (so[e] * ss[e]).astype(np.float32)
-            np.testing.assert_array_equal(prm[:K, :n, 0], (gain[None, :] * art.scale[e].T).astype(np.float32))
-            np.testing.assert_array_equal(prm[:K, :n, 1], (gain[None, :] * art.y_min[e].T).astype(np.float32))
+            np.testing.assert_array_equal(prm[:K, 0, :n], (gain[None, :] * art.scale[e].T).astype(np.float32))
+            np.testing.assert_array_equal(prm[:K, 1, :n], (gain[None, :] * art.y_min[e].T).astype(np.float32))
             np.testing.assert_array_equal(ctab[t, i, 1:, :n], (gain[None, :] * s.coef[i, cols].T).astype(np.float32))
 
 
@@ -239,11 +236,11 @@ def test_fp16_parameter_tables(scheme):
         n = cols.size
         for i in range(s.d):
             e = i * s.m + cols
-            prm = tab[t, i, :codes_off].view(np.float16).reshape(K + 1, jt, per)
-            np.testing.assert_array_equal(prm[:K, :n, 0].astype(np.float32), art.scale[e].T)
+            prm = tab[t, i, :codes_off].view(np.float16).reshape(K + 1, per, jt)
+            np.testing.assert_array_equal(prm[:K, 0, :n].astype(np.float32), art.scale[e].T)
             if scheme == ASYM_UINT8:
-                np.testing.assert_array_equal(prm[:K, :n, 1].astype(np.float32), art.y_min[e].T)
-            assert np.all(prm[:, n:] == 0) and np.all(prm[K] == 0)
+                np.testing.assert_array_equal(prm[:K, 1, :n].astype(np.float32), art.y_min[e].T)
+            assert np.all(prm[:, :, n:] == 0) and np.all(prm[K] == 0)
             codes = tab[t, i, codes_off:codes_off + K * L * jt].reshape(K, L, jt)
             want = np.transpose(art.q[e], (1, 2, 0))
             want = want.view(np.uint8) if scheme == ASYM_UINT8 else (want.astype(np.int16) + 128).astype(np.uint8)
