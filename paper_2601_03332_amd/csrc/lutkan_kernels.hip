@@ -7,9 +7,9 @@
 //                      computed once and reused by all m outputs.
 //   2. edge kernel     per (row, output): for every input gather the two adjacent codes, dequantise (Eq. 10),
 //                      interpolate (Eq. 17), apply the oob_policy (Sec. 5.4) and accumulate (Eq. 1).
-//                      "gather" variant: codes straight from global memory (any shape, used for narrow layers
-//                      and for the trace);  "tiled" variant: a work-group owns (row tile) x (column tile),
-//                      walks the inputs, and stages each input's table slice in LDS.
+//                      "tiled" variant: a work-group owns (row tile) x (column tile), walks the inputs, and
+//                      stages each input's table slice in LDS;  "gather" variant: codes straight from global
+//                      memory (used for table slices too large for LDS and for the code trace).
 // The file is compiled with -ffp-contract=off; every fused multiply-add below is written out as fmaf().
 #include <hip/hip_runtime.h>
 
