@@ -856,7 +856,8 @@ int gather_jx_log2(int m) {
 // Launch shape of the tiled kernels for B rows: NP row steps per wave (16/8/4/2/1, at most 64 rows per wave) and
 // the number of chunks the d inputs are split into.  Large row tiles re-read the table least, so NP starts at the
 // smallest value whose row tile covers B and shrinks only while the grid would still leave compute units idle
-// even with the inputs split (each chunk keeps at least 16 inputs).
+// even with the inputs split (each chunk keeps at least 16 inputs).  (Preferring small row tiles to splitting was
+// measured and lost: with few row steps per input the per-input barrier dominates.)
 struct TilePlan {
   int np, n_split, chunk;
 };
@@ -1060,6 +1061,7 @@ int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y
   if (l->jt < 4 || l->jt > 128 || (l->jt & (l->jt - 1))) return fail(LUTKAN_EINVAL, "%s: bad jt", who);
   if (l->n_tiles != (l->m + l->jt - 1) / l->jt) return fail(LUTKAN_ESHAPE, "%s: n_tiles does not match m and jt", who);
   if ((reinterpret_cast<uintptr_t>(l->coef_table) & 15) != 0) return fail(LUTKAN_EINVAL, "%s: coef_table must be 16-byte aligned", who);
+  if (l->coef_blob_bytes != lutkan::coef_slice_rows(l->G + 3, l->value_repr) * l->jt * 4) return fail(LUTKAN_ESHAPE, "%s: coef_blob_bytes does not match G, jt, value_repr", who);
   if (B < 0) return fail(LUTKAN_EINVAL, "%s: B < 0", who);
   if (B == 0) return LUTKAN_OK;
   if (((phases & kLocate) && !x) || ((phases & kEdges) && !y) || x == y) return fail(LUTKAN_EINVAL, "%s: null or aliased x / y", who);
@@ -1118,10 +1120,8 @@ int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y
 // Records for every (input, padded row), then room for the partial sums when the inputs are split into chunks.
 static size_t tiled_workspace_bytes(int d, int m, int jt, int n_tiles, int64_t B, int bytes_per_record) {
   size_t bytes = record_bytes(d, padded_rows(B), bytes_per_record);
-  {
-    const TilePlan tp = plan_tiles(B, d, n_tiles, 64 / (jt / 4));
-    if (tp.n_split > 1) bytes += (size_t)tp.n_split * (size_t)B * (size_t)m * 4;
-  }
+  const TilePlan tp = plan_tiles(B, d, n_tiles, 64 / (jt / 4));
+  if (tp.n_split > 1) bytes += (size_t)tp.n_split * (size_t)B * (size_t)m * 4;
   return bytes;
 }
 
