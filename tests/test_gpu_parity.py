@@ -493,3 +493,32 @@ def test_model_forward_replays_correctly_from_a_hip_graph():
         assert torch.equal(y, y_eager) and torch.equal(stats, stats_eager)
         lk.lutkan_model_forward(layers, x, y, workspace=ws)                    # eager work between replays
         torch.cuda.synchronize()
+
+
+def test_random_shapes_and_contracts():
+    """Sixty layers with shapes, grids, table sizes and contracts drawn at random (seeded), covering every tile width,
+    ragged tiles and batches, both value representations, both parameter dtypes and both kernel families; the LUT
+    layer (trace and plain launch, counters) and the B-spline layer against the oracle."""
+    rng = np.random.Generator(np.random.PCG64(2024))
+    worst = 0.0
+    for it in range(60):
+        G = int(rng.choice([1, 2, 3, 5, 8, 10, 17, 33, 64]))
+        L = int(rng.choice([2, 3, 5, 16, 31, 64, 128, 512]))
+        L = min(L, 65535 // G)
+        d = int(rng.integers(1, 41))
+        m = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 9, 16, 17, 31, 32, 33, 64, 65, 100, 128, 129, 200, 300]))
+        B = int(rng.choice([1, 2, 15, 16, 17, 63, 64, 65, 255, 256, 257, 1000, 1024, 1025, 2500]))
+        scheme, boundary, oob = (int(rng.integers(0, 2)) for _ in range(3))
+        base = bool(rng.integers(0, 2))
+        half = bool(rng.integers(0, 2)) and not base
+        algo = int(rng.choice([lk.ALGO_AUTO, lk.ALGO_GATHER]))
+        w = random_layer(2000 + it, d, m, G, L, scheme, boundary, oob, B, uniform=bool(rng.integers(0, 2)), with_base=base)
+        s = w.layers[0]
+        _say(f"case random {it}: d={d} m={m} G={G} L={L} B={B} scheme={scheme} boundary={boundary} oob={oob} base={base} "
+             f"fp16={half} algo={algo}")
+        worst = max(worst, _check_layer(s, w.x, algo, what=w.name, param_fp16=half))
+        yb = lk.bspline_kan_forward(_compile_both(s, half)[0].bspline_to_device(DEV), torch.from_numpy(w.x).to(DEV))
+        torch.cuda.synchronize()
+        refb = oracle.bspline_forward(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.boundary, s.oob, w.x, edge_scalars=s.edge_scales)
+        worst = max(worst, _assert_close(yb.cpu().numpy(), refb, w.name + " bspline"))
+    _say(f"random layers: worst error / tolerance = {worst:.3f}")
