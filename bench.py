@@ -192,9 +192,13 @@ def main():
         torch.cuda.synchronize()
         loc = sorted(e[0].elapsed_time(e[1]) for e in ev)
         edg = sorted(e[1].elapsed_time(e[2]) for e in ev)
-        return sum(loc) / len(loc), sum(edg) / len(edg), edg[len(edg) // 2]
+        tot = sorted(e[0].elapsed_time(e[2]) for e in ev)
+        mean = sum(tot) / len(tot)
+        spread = {"median": tot[len(tot) // 2], "mean": mean, "std": (sum((t - mean) ** 2 for t in tot) / len(tot)) ** 0.5,
+                  "min": tot[0], "max": tot[-1]}
+        return sum(loc) / len(loc), sum(edg) / len(edg), edg[len(edg) // 2], spread
 
-    loc_ms, edge_ms, edge_med = time_phases(lambda n: lk.lutkan_forward_locate(layer, xs[n % nbuf], ws),
+    loc_ms, edge_ms, edge_med, step_spread = time_phases(lambda n: lk.lutkan_forward_locate(layer, xs[n % nbuf], ws),
                                             lambda n: lk.lutkan_forward_edges(layer, B, ys[n % nbuf], ws), args.steps)
     log(f"[bench] locate kernel {loc_ms:.3f} ms, edge kernel {edge_ms:.3f} ms (median {edge_med:.3f})")
     achieved = FLOP_PER_EDGE * edges / (edge_ms * 1e-3) / 1e12
@@ -206,7 +210,8 @@ def main():
                 "hbm_time_floor_ms": round((art.info.table_bytes + 8 * B * d + 4 * B * m) / (PEAK_HBM_GBS * 1e9) * 1e3, 4)}
 
     extra = {"rows_per_s": round(B / (dt / args.steps), 1), "locate_kernel_ms": round(loc_ms, 4),
-             "edge_kernel_edge_evals_per_s": round(edges / (edge_ms * 1e-3), 1)}
+             "edge_kernel_edge_evals_per_s": round(edges / (edge_ms * 1e-3), 1),
+             "step_ms_by_events": {k: round(v, 4) for k, v in step_spread.items()}}
 
     if not args.no_probes:
         # Rates this GPU sustains on one resource at a time (kernels of known work, timed with events), and what
@@ -259,7 +264,7 @@ def main():
             lk.bspline_kan_forward(bl, xs[n % nbuf], ys[n % nbuf], workspace=wsb)
         torch.cuda.synchronize()
         bs_ms = (time.perf_counter() - t0) / args.steps * 1e3
-        bloc_ms, bedge_ms, _ = time_phases(lambda n: lk.bspline_forward_locate(bl, xs[n % nbuf], wsb),
+        bloc_ms, bedge_ms, _, _ = time_phases(lambda n: lk.bspline_forward_locate(bl, xs[n % nbuf], wsb),
                                            lambda n: lk.bspline_forward_edges(bl, B, ys[n % nbuf], wsb), args.steps)
         extra.update({"bspline_ms_per_step": round(bs_ms, 4), "lut_vs_bspline_speedup": round(bs_ms / ms_per_step, 4),
                       "bspline_locate_kernel_ms": round(bloc_ms, 4), "bspline_edge_kernel_ms": round(bedge_ms, 4),
