@@ -96,33 +96,35 @@ __device__ __forceinline__ Located locate_one(const LocateArgs &a, float x) {
   return o;
 }
 
-constexpr int kLocRows = 32;    // rows per block
-constexpr int kLocCols = 64;    // inputs per block
+constexpr int kLocTile = 2048;  // (row, input) pairs per block of the LUT locate kernel: 256 threads x 8
 
-// One block locates a tile of 32 rows x 64 inputs: x is read along inputs (coalesced), every thread locates eight
-// elements, the records are transposed through LDS and written along rows (coalesced): records are stored
-// [input][row].  blockIdx.x = row tile, blockIdx.y = input tile, so small batches still fill the GPU.
+// One block locates a tile of ROWS rows x COLS inputs (ROWS * COLS = 2048; COLS = 64, 32 or 16 so that narrow layers
+// do not idle most lanes): x is read along inputs (coalesced), every thread locates eight elements, the records are
+// transposed through LDS and written along rows (coalesced): records are stored [input][row].
+// blockIdx.x = row tile, blockIdx.y = input tile, so small batches still fill the GPU.
 // BASE: value_repr = spline_component, the record also carries SiLU(x).
-template <bool BASE>
+template <bool BASE, int COLS>
 __global__ __launch_bounds__(256) void lutkan_locate_kernel(const LocateArgs a) {
   typedef typename std::conditional<BASE, u32x4, u32x2>::type rec_t;
-  __shared__ rec_t s_rec[kLocCols][kLocRows + 1];
+  constexpr int ROWS = kLocTile / COLS;
+  constexpr int ROW_GROUPS = 256 / COLS;                 // rows handled side by side in phase 1
+  __shared__ rec_t s_rec[COLS][ROWS + 1];
   rec_t *const rec_out = static_cast<rec_t *>(a.rec);
   const int tid = threadIdx.x;
-  const int64_t b0 = (int64_t)blockIdx.x * kLocRows;
-  const int i0 = blockIdx.y * kLocCols;
+  const int64_t b0 = (int64_t)blockIdx.x * ROWS;
+  const int i0 = blockIdx.y * COLS;
   const unsigned masked_index = (unsigned)(a.K * a.L) | ((unsigned)a.K << 16);
-  const int il = tid & (kLocCols - 1);
+  const int il = tid % COLS;
   const int i = i0 + il;
-  float xv[kLocRows / 4];
+  float xv[8];
 #pragma unroll
-  for (int p = 0; p < kLocRows / 4; ++p) {               // all eight loads in flight before the first is used
-    const int64_t b = b0 + p * 4 + (tid >> 6);
+  for (int p = 0; p < 8; ++p) {                          // all eight loads in flight before the first is used
+    const int64_t b = b0 + p * ROW_GROUPS + tid / COLS;
     xv[p] = (b < a.B && i < a.d) ? a.x[b * a.d + i] : 0.0f;
   }
 #pragma unroll
-  for (int p = 0; p < kLocRows / 4; ++p) {
-    const int bl = p * 4 + (tid >> 6);
+  for (int p = 0; p < 8; ++p) {
+    const int bl = p * ROW_GROUPS + tid / COLS;
     const int64_t b = b0 + bl;
     rec_t rec = {};
     rec.x = masked_index;
@@ -146,10 +148,10 @@ __global__ __launch_bounds__(256) void lutkan_locate_kernel(const LocateArgs a) 
     s_rec[il][bl] = rec;
   }
   __syncthreads();
-  const int bl2 = tid & (kLocRows - 1);
+  const int bl2 = tid % ROWS;
 #pragma unroll
-  for (int p = 0; p < kLocCols / 8; ++p) {
-    const int il2 = p * 8 + (tid >> 5);
+  for (int p = 0; p < 8; ++p) {
+    const int il2 = p * (256 / ROWS) + tid / ROWS;
     const int i2 = i0 + il2;
     if (i2 < a.d && b0 + bl2 < a.Bp) rec_out[(int64_t)i2 * a.Bp + b0 + bl2] = s_rec[il2][bl2];
   }
@@ -539,24 +541,27 @@ struct SplineLocateArgs {
   float ext_knots[LUTKAN_MAX_K + 7];
 };
 
-constexpr int kSplCols = 32;   // inputs per block of the B-spline locate kernel (32-byte records)
+constexpr int kSplTile = 1024;  // (row, input) pairs per block of the B-spline locate kernel (32-byte records)
 
-// Same tiling as the LUT locate kernel: blockIdx.x = tile of 32 rows, blockIdx.y = tile of 32 inputs.
+// Same tiling as the LUT locate kernel: blockIdx.x = tile of ROWS rows, blockIdx.y = tile of COLS inputs
+// (COLS = 32 or 16, ROWS * COLS = 1024).
+template <int COLS>
 __global__ __launch_bounds__(256) void bspline_locate_kernel(const SplineLocateArgs a) {
-  __shared__ u32x4 s_rec[2][kSplCols][kLocRows + 1];
+  constexpr int ROWS = kSplTile / COLS;
+  __shared__ u32x4 s_rec[2][COLS][ROWS + 1];
   __shared__ float s_tau[LUTKAN_MAX_K + 7];
   const int tid = threadIdx.x;
-  const int64_t b0 = (int64_t)blockIdx.x * kLocRows;
+  const int64_t b0 = (int64_t)blockIdx.x * ROWS;
   for (int r = tid; r < a.G + 7; r += 256) s_tau[r] = a.ext_knots[r];
   __syncthreads();
   const float t0 = s_tau[3], tK = s_tau[3 + a.G];
   {
-    const int i0 = blockIdx.y * kSplCols;
-    const int il = tid & (kSplCols - 1);
+    const int i0 = blockIdx.y * COLS;
+    const int il = tid % COLS;
     const int i = i0 + il;
 #pragma unroll 1
-    for (int p = 0; p < kLocRows / 8; ++p) {
-      const int bl = p * 8 + (tid >> 5);
+    for (int p = 0; p < kSplTile / 256; ++p) {
+      const int bl = p * (256 / COLS) + tid / COLS;
       const int64_t b = b0 + bl;
       int k = 0;
       float n0 = 0.f, n1 = 0.f, n2 = 0.f, n3 = 0.f, base = 0.f;
@@ -593,10 +598,10 @@ __global__ __launch_bounds__(256) void bspline_locate_kernel(const SplineLocateA
       s_rec[1][il][bl] = u32x4{__float_as_uint(n3), __float_as_uint(base), 0u, 0u};
     }
     __syncthreads();
-    const int bl2 = tid & (kLocRows - 1);
+    const int bl2 = tid % ROWS;
 #pragma unroll 1
-    for (int p = 0; p < kSplCols / 8; ++p) {
-      const int il2 = p * 8 + (tid >> 5);
+    for (int p = 0; p < kSplTile / 256; ++p) {
+      const int il2 = p * (256 / ROWS) + tid / ROWS;
       const int i2 = i0 + il2;
       if (i2 < a.d && b0 + bl2 < a.Bp) {
         const int64_t o = ((int64_t)i2 * a.Bp + b0 + bl2) * 2;
@@ -960,10 +965,21 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   for (int k = 0; k <= l->K; ++k) la.knots[k] = l->knots[k];
   la.k_out = trace ? k_out : nullptr; la.l0_out = l0_out; la.in_out = in_out; la.w_out = w_out;
   if (phases & kLocate) {
-    const dim3 lgrid((unsigned)(Bp / kLocRows), (unsigned)((l->d + kLocCols - 1) / kLocCols));
+    // inputs per block: the width in {64, 32, 16} that pads d least (the widest on ties: longer runs of x)
+    int cols = 64;
+    for (int c = 32; c >= 16; c >>= 1)
+      if ((l->d + c - 1) / c * c < (l->d + cols - 1) / cols * cols) cols = c;
+    const dim3 lgrid((unsigned)(Bp / (kLocTile / cols)), (unsigned)((l->d + cols - 1) / cols));
     if (lgrid.y > 65535u) return fail(LUTKAN_EUNSUPPORTED, "%s: d too large", who);
-    if (with_base) hipLaunchKernelGGL(lutkan_locate_kernel<true>, lgrid, dim3(256), 0, s, la);
-    else hipLaunchKernelGGL(lutkan_locate_kernel<false>, lgrid, dim3(256), 0, s, la);
+    if (with_base) {
+      if (cols == 64) hipLaunchKernelGGL((lutkan_locate_kernel<true, 64>), lgrid, dim3(256), 0, s, la);
+      else if (cols == 32) hipLaunchKernelGGL((lutkan_locate_kernel<true, 32>), lgrid, dim3(256), 0, s, la);
+      else hipLaunchKernelGGL((lutkan_locate_kernel<true, 16>), lgrid, dim3(256), 0, s, la);
+    } else {
+      if (cols == 64) hipLaunchKernelGGL((lutkan_locate_kernel<false, 64>), lgrid, dim3(256), 0, s, la);
+      else if (cols == 32) hipLaunchKernelGGL((lutkan_locate_kernel<false, 32>), lgrid, dim3(256), 0, s, la);
+      else hipLaunchKernelGGL((lutkan_locate_kernel<false, 16>), lgrid, dim3(256), 0, s, la);
+    }
     if (int rc = check_launch("lutkan_locate_kernel")) return rc;
     if (stats) {
       const int64_t rows_per_group = 4 * kOobRowsPerWave;
@@ -1082,9 +1098,11 @@ int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y
   la.tKs = la.closed ? l->ext_knots[3 + G] : std::nextafterf(l->ext_knots[3 + G], -INFINITY);
   for (int r = 0; r < G + 7; ++r) la.ext_knots[r] = l->ext_knots[r];
   if (phases & kLocate) {
-    const dim3 lgrid((unsigned)(Bp / kLocRows), (unsigned)((l->d + kSplCols - 1) / kSplCols));
+    const int cols = ((l->d + 15) / 16 * 16 < (l->d + 31) / 32 * 32) ? 16 : 32;      // the width that pads d least
+    const dim3 lgrid((unsigned)(Bp / (kSplTile / cols)), (unsigned)((l->d + cols - 1) / cols));
     if (lgrid.y > 65535u) return fail(LUTKAN_EUNSUPPORTED, "%s: d too large", who);
-    hipLaunchKernelGGL(bspline_locate_kernel, lgrid, dim3(256), 0, s, la);
+    if (cols == 32) hipLaunchKernelGGL(bspline_locate_kernel<32>, lgrid, dim3(256), 0, s, la);
+    else hipLaunchKernelGGL(bspline_locate_kernel<16>, lgrid, dim3(256), 0, s, la);
     if (int rc = check_launch("bspline_locate_kernel")) return rc;
   }
   if (!(phases & kEdges)) return LUTKAN_OK;
