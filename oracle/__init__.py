@@ -50,11 +50,11 @@ def lib():
         L.lko_sample_x.restype = C.c_double
         L.lko_quantize_segment.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
         L.lko_quantize_segment.restype = None
-        L.lko_compile.argtypes = [C.c_int] * 4 + [C.c_void_p, C.c_void_p, C.c_int, C.c_int] + [C.c_void_p] * 5 + [C.c_int]
+        L.lko_compile.argtypes = [C.c_int] * 4 + [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int] + [C.c_void_p] * 5 + [C.c_int]
         L.lko_compile.restype = C.c_int
         L.lko_lut_forward.argtypes = ([C.c_int] * 7 + [C.c_void_p] * 8 + [C.c_long] + [C.c_void_p] * 8 + [C.c_int])
         L.lko_lut_forward.restype = C.c_int
-        L.lko_bspline_forward.argtypes = [C.c_int] * 4 + [C.c_void_p] * 5 + [C.c_int, C.c_int, C.c_void_p,
+        L.lko_bspline_forward.argtypes = [C.c_int] * 4 + [C.c_void_p] * 5 + [C.c_int, C.c_int, C.c_int, C.c_void_p,
                                                                            C.c_long, C.c_void_p, C.c_void_p, C.c_int]
         L.lko_silu.argtypes = [C.c_float]
         L.lko_silu.restype = C.c_float
@@ -118,19 +118,20 @@ def round_to_fp16(x: float) -> float:
     return float(lib().lko_round_to_fp16(float(np.float32(x))))
 
 
-def compile_layer(d, m, G, p, ext_knots, coef, L, scheme, want_v=False, nthreads=None, param_fp16=False):
+def compile_layer(d, m, G, p, ext_knots, coef, L, scheme, want_v=False, nthreads=None, param_fp16=False, extended=False):
     """Artifact arrays of Sec. 4.6: knots [K+1], q [E,K,L] (e=i*m+j), scale [E,K], y_min [E,K].
-    param_fp16: scale and y_min are stored rounded to binary16 (held here as fp32 arrays of those values)."""
+    param_fp16: scale and y_min are stored rounded to binary16 (held here as fp32 arrays of those values).
+    extended: the LUT covers every interval of the extended knot vector, K = G + 2p (else the domain grid, K = G)."""
     tau = _f32(ext_knots)
     coef = _f32(coef)
     assert tau.size == G + 2 * p + 1 and coef.size == d * m * (G + p)
-    E, K = d * m, G
+    E, K = d * m, (G + 2 * p if extended else G)
     q = np.zeros((E, K, L), dtype=np.int8 if scheme == SYM_INT8 else np.uint8)
     scale = np.zeros((E, K), dtype=np.float32)
     y_min = np.zeros((E, K), dtype=np.float32)
     knots = np.zeros(K + 1, dtype=np.float32)
     v = np.zeros((E, K, L), dtype=np.float32) if want_v else None
-    rc = lib().lko_compile(d, m, G, p, _p(tau), _p(coef), L, scheme, _p(q), _p(scale), _p(y_min), _p(knots), _p(v),
+    rc = lib().lko_compile(d, m, G, p, _p(tau), _p(coef), L, scheme, int(bool(extended)), _p(q), _p(scale), _p(y_min), _p(knots), _p(v),
                            nthreads or default_threads())
     if rc != 0:
         raise ValueError(f"lko_compile failed: {rc}")
@@ -184,7 +185,7 @@ def lut_forward(art, boundary, oob, x, trace=False, codes=False, nthreads=None, 
                            oob_count=int(stats[0]), oob_any_rows=int(stats[1]))
 
 
-def bspline_forward(d, m, G, p, ext_knots, coef, boundary, oob, x, nthreads=None, edge_scalars=None):
+def bspline_forward(d, m, G, p, ext_knots, coef, boundary, oob, x, nthreads=None, edge_scalars=None, extended=False):
     tau = _f32(ext_knots)
     coef = _f32(coef)
     x = _f32(x)
@@ -192,7 +193,7 @@ def bspline_forward(d, m, G, p, ext_knots, coef, boundary, oob, x, nthreads=None
     y = np.zeros((B, m), dtype=np.float32)
     A = np.zeros((B, m), dtype=np.float64)
     sb, ss, so = _edge_scalars(edge_scalars, d * m)
-    rc = lib().lko_bspline_forward(d, m, G, p, _p(tau), _p(coef), _p(sb), _p(ss), _p(so), boundary, oob, _p(x), B, _p(y), _p(A),
+    rc = lib().lko_bspline_forward(d, m, G, p, _p(tau), _p(coef), _p(sb), _p(ss), _p(so), boundary, oob, int(bool(extended)), _p(x), B, _p(y), _p(A),
                                    nthreads or default_threads())
     if rc != 0:
         raise ValueError(f"lko_bspline_forward failed: {rc}")

@@ -29,7 +29,11 @@
  *   - a NaN input is out of domain, is indexed like t_0, and makes every output of its row NaN
  *     under either oob_policy;
  *   - the B-spline layer applies the same boundary_mode / oob_policy to x before evaluating;
- *   - float16 parameters (Sec. 4.6): codes from the fp32 parameters, parameters then rounded to binary16.
+ *   - float16 parameters (Sec. 4.6): codes from the fp32 parameters, parameters then rounded to binary16;
+ *   - `extended` (the other reading of "knot grid", the one the byte counts of Table 9 imply): the LUT knots are
+ *     all G+2p+1 knots of the extended vector, K = G+2p, and the domain is [tau_0, tau_{G+2p}].  The spline there is
+ *     still the sum of Eq. 3 over the G+p coefficients; on the outer p intervals of each side fewer than p+1 basis
+ *     functions exist, and at the last knot itself every basis function is 0 (half-open degree-0 indicator, Eq. 4).
  *
  * Parity pins: all functions here are pinned by closed forms, invariants, a library routine
  * (scipy.interpolate.BSpline, numpy.searchsorted) and brute force in tests/test_oracle_*.py.
@@ -130,13 +134,14 @@ void lko_quantize_segment(const float *v, int L, int scheme, void *q, float *alp
  * The basis values at the K*L sampling positions depend only on the shared knot vector, so they
  * are evaluated once and reused by every edge; each edge value is still the sum of Eq. 3.
  * ---------------------------------------------------------------------------------------- */
-int lko_compile(int d, int m, int G, int p, const float *tau_f, const float *coef, int L, int scheme,
+int lko_compile(int d, int m, int G, int p, const float *tau_f, const float *coef, int L, int scheme, int extended,
                 void *q, float *scale, float *y_min, float *knots, float *v_out, int nthreads)
 {
     if (d < 1 || m < 1 || G < 1 || p < 0 || L < 2) return -1;
-    int n = G + 2 * p + 1, R = G + p, K = G;
+    int n = G + 2 * p + 1, R = G + p;
+    int K = extended ? n - 1 : G;                        /* LUT segments: every extended interval, or the domain grid */
     for (int r = 0; r + 1 < n; ++r) if (!(tau_f[r] < tau_f[r + 1])) return -2;
-    for (int k = 0; k <= K; ++k) knots[k] = tau_f[p + k];
+    for (int k = 0; k <= K; ++k) knots[k] = extended ? tau_f[k] : tau_f[p + k];
     double *tau = (double *)malloc(sizeof(double) * n);
     double *Bs = (double *)malloc(sizeof(double) * (size_t)K * L * n);
     if (!tau || !Bs) { free(tau); free(Bs); return -3; }
@@ -311,14 +316,15 @@ int lko_lut_forward(int d, int m, int K, int L, int scheme, int boundary, int oo
  * ---------------------------------------------------------------------------------------- */
 int lko_bspline_forward(int d, int m, int G, int p, const float *tau_f, const float *coef,
                         const float *edge_base, const float *edge_spline, const float *edge_out, /* [E] or all NULL */
-                        int boundary, int oob, const float *x, long B, float *y, double *A, int nthreads)
+                        int boundary, int oob, int extended, const float *x, long B, float *y, double *A, int nthreads)
 {
     if (d < 1 || m < 1 || G < 1 || p < 0 || B < 0) return -1;
-    int n = G + 2 * p + 1, R = G + p, K = G;
+    int n = G + 2 * p + 1, R = G + p;
+    int K = extended ? n - 1 : G;                        /* the domain is the LUT's: all extended knots, or the grid */
     double tau[n];
     float T[K + 1];
     for (int r = 0; r < n; ++r) tau[r] = (double)tau_f[r];
-    for (int k = 0; k <= K; ++k) T[k] = tau_f[p + k];
+    for (int k = 0; k <= K; ++k) T[k] = extended ? tau_f[k] : tau_f[p + k];
     (void)nthreads;
 #pragma omp parallel for num_threads(nthreads > 0 ? nthreads : 1) schedule(static)
     for (long b = 0; b < B; ++b) {

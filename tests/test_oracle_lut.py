@@ -585,3 +585,86 @@ def test_error_stats_against_plain_loops_and_nan_rules():
             assert abs(got["sum_abs_" + key] - sums[key]) <= 1e-12 * sums[key]
             assert got["max_abs_" + key] == maxs[key]
             assert abs(got["mae_" + key] - sums[key] / (rows[key] * m)) <= 1e-15
+
+
+# ---------------------------------------------------------------------------------------------------
+# LUT over the whole extended knot vector (the reading that the byte counts of Table 9 imply)
+# ---------------------------------------------------------------------------------------------------
+def _basis_sum(tau, coef, x):
+    """sum_r c_r B_{r,3}(x) with SciPy's basis elements (each is zero outside its own support)."""
+    from scipy.interpolate import BSpline
+    total = np.zeros_like(x, dtype=np.float64)
+    for r in range(coef.size):
+        b = BSpline.basis_element(tau[r:r + 5].astype(np.float64), extrapolate=False)(x)
+        total += float(coef[r]) * np.nan_to_num(b, nan=0.0)
+    return total
+
+
+@pytest.mark.parametrize("uniform", [True, False])
+def test_extended_lut_covers_every_extended_interval(uniform):
+    G, L = 5, 16
+    w = random_layer(71, 2, 3, G, L, ASYM_UINT8, CLOSED, CLIP_X, 4, uniform=uniform)
+    s = w.layers[0]
+    dom = oracle.compile_layer(s.d, s.m, G, P, s.ext_knots, s.coef, L, ASYM_UINT8, want_v=True)
+    ext = oracle.compile_layer(s.d, s.m, G, P, s.ext_knots, s.coef, L, ASYM_UINT8, want_v=True, extended=True)
+    assert ext.K == G + 2 * P == 11 and np.array_equal(ext.knots, s.ext_knots)
+    # the G inner segments are the domain artifact, bit for bit
+    assert np.array_equal(ext.q[:, P:P + G], dom.q) and np.array_equal(ext.scale[:, P:P + G], dom.scale)
+    assert np.array_equal(ext.y_min[:, P:P + G], dom.y_min) and np.array_equal(ext.v[:, P:P + G], dom.v)
+    # on the outer intervals fewer than p+1 basis functions exist; the samples are still the sum of Eq. 3
+    tau = s.ext_knots
+    for k in list(range(P)) + list(range(P + G, G + 2 * P)):
+        xs = np.array([oracle.sample_x(tau, L, k, l) for l in range(L)])
+        for e in range(s.d * s.m):
+            want = _basis_sum(tau, s.coef.reshape(-1, G + P)[e], xs)
+            np.testing.assert_allclose(ext.v[e, k], want, rtol=0, atol=2e-6)
+    assert np.abs(ext.v[:, 0, 0]).max() == 0.0                      # at tau_0 itself nothing is non-zero yet
+
+
+def test_extended_bspline_layer_and_the_last_knot():
+    G = 4
+    w = random_layer(72, 3, 2, G, 8, SYM_INT8, CLOSED, CLIP_X, 4, uniform=False)
+    s = w.layers[0]
+    tau = s.ext_knots
+    x = np.random.Generator(np.random.PCG64(3)).uniform(tau[0], tau[-1], size=(40, 3)).astype(np.float32)
+    x[0, :] = tau[-1]                                               # closed mode: in the domain, but every basis function is 0 there
+    x[1, :] = np.float32(tau[-1] + 1.0)                             # clipped onto the last knot
+    x[2, :] = tau[0]
+    out = oracle.bspline_forward(s.d, s.m, G, P, tau, s.coef, CLOSED, CLIP_X, x, extended=True)
+    assert np.all(out.y[0] == 0.0) and np.all(out.y[1] == 0.0) and np.all(out.y[2] == 0.0)
+    want = np.zeros((40, 2))
+    for i in range(3):
+        for j in range(2):
+            want[:, j] += _basis_sum(tau, s.coef[i, j], x[:, i].astype(np.float64))
+    np.testing.assert_allclose(out.y[3:], want[3:], rtol=0, atol=5e-6)
+    # the same inputs in domain mode are clipped to the inner grid instead
+    inner = oracle.bspline_forward(s.d, s.m, G, P, tau, s.coef, CLOSED, CLIP_X, x)
+    far = np.any((x < tau[P]) | (x > tau[P + G]), axis=1)
+    assert far.any() and not np.allclose(inner.y[far], out.y[far])
+    # zero_spline in half_open mode: the last knot is out of the domain
+    z = oracle.bspline_forward(s.d, s.m, G, P, tau, s.coef, HALF_OPEN, ZERO_SPLINE, x[:3], extended=True)
+    assert np.all(z.y[:2] == 0.0)
+
+
+def test_extended_lut_forward_tracks_the_extended_spline():
+    G, L = 6, 64
+    w = random_layer(73, 4, 3, G, L, SYM_INT8, HALF_OPEN, CLIP_X, 4)
+    s = w.layers[0]
+    tau = s.ext_knots
+    art = oracle.compile_layer(s.d, s.m, G, P, tau, s.coef, L, SYM_INT8, extended=True)
+    x = np.random.Generator(np.random.PCG64(9)).uniform(tau[0], tau[-2], size=(300, 4)).astype(np.float32)
+    lut = oracle.lut_forward(art, HALF_OPEN, CLIP_X, x, trace=True)
+    ref = oracle.bspline_forward(s.d, s.m, G, P, tau, s.coef, HALF_OPEN, CLIP_X, x, extended=True)
+    assert lut.inside.all() and lut.k.max() == G + 2 * P - 2 and lut.k.min() == 0
+    assert np.abs(lut.y - ref.y).max() < 0.5 and np.abs(lut.y - ref.y).mean() < 0.08     # O(1/L) table error, d = 4 edges per output
+
+
+def test_table9_segment_count_is_the_extended_reading():
+    """Table 9's byte counts fit K = 11 = G + 2p for the case study's grid 5, cubic: the extended artifact's K."""
+    s = random_layer(74, 1, 1, 5, 64, ASYM_UINT8, CLOSED, CLIP_X, 4).layers[0]
+    art = oracle.compile_layer(1, 1, 5, P, s.ext_knots, s.coef, 64, ASYM_UINT8, param_fp16=True, extended=True)
+    rows = [l.split() for l in open(os.path.join(GOLD, "table9_artifact_bytes.txt")) if l[0] != "#"]
+    for E, K, L, nbytes in rows:
+        assert int(K) == art.K and int(L) == art.L
+        per_edge = art.q[0].nbytes + art.scale[0].size * 2 + art.y_min[0].size * 2      # float16 scale and y_min
+        assert int(E) * per_edge + art.knots.nbytes == int(nbytes)

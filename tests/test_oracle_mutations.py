@@ -35,6 +35,8 @@ MUTATIONS = {
     "fp16_params_truncated": ("double r = nearbyint(a / ulp) * ulp;", "double r = floor(a / ulp) * ulp;"),
     "fp16_params_no_subnormals": ("if (lead < -14) lead = -14;", "if (lead < -24) lead = -24;"),
     "fp16_params_overflow_late": ("if (a >= 65520.0) return", "if (a > 65535.0) return"),
+    "extended_lut_drops_last_interval": ("int K = extended ? n - 1 : G;                        /* LUT segments", "int K = extended ? n - 2 : G;                        /* LUT segments"),
+    "extended_layer_keeps_inner_domain": ("for (int k = 0; k <= K; ++k) T[k] = extended ? tau_f[k] : tau_f[p + k];", "for (int k = 0; k <= K; ++k) T[k] = extended ? tau_f[k < p ? p : (k > p + G ? p + G : k)] : tau_f[p + k];"),
     "layer_sum_skips_first_input": ("for (int i = 0; i < d; ++i) {\n            lko_index ix;\n            lko_locate(knots", "for (int i = (d > 1); i < d; ++i) {\n            lko_index ix;\n            lko_locate(knots"),
 }
 
