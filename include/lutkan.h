@@ -43,6 +43,10 @@ typedef enum { LUTKAN_CLIP_X = 0, LUTKAN_ZERO_SPLINE = 1 } lutkan_oob;          
 typedef enum { LUTKAN_ALGO_AUTO = 0, LUTKAN_ALGO_GATHER = 1, LUTKAN_ALGO_TILED = 2 } lutkan_algo;
 typedef enum { LUTKAN_REPR_PHI = 0, LUTKAN_REPR_SPLINE_COMPONENT = 1 } lutkan_value_repr;  /* Sec. 4.3 A / B */
 typedef enum { LUTKAN_PARAM_FP32 = 0, LUTKAN_PARAM_FP16 = 1 } lutkan_param_dtype;   /* Sec. 4.6: dtype of scale, y_min */
+/* Which knots are the LUT's "knot grid" (Sec. 4.2): the G+1 breakpoints of the domain [ext_knots[p], ext_knots[p+G]]
+ * (K = G), or every knot of the extended vector (K = G + 2p, domain [ext_knots[0], ext_knots[G+2p]]) -- the reading
+ * under which the per-layer byte counts of Table 9 come out exactly. */
+typedef enum { LUTKAN_SPAN_DOMAIN = 0, LUTKAN_SPAN_EXTENDED = 1 } lutkan_knot_span;
 
 #define LUTKAN_MAX_K 64            /* segments per layer (the knot vector travels in the kernel arguments) */
 #define LUTKAN_MAX_ROWS 65535      /* K * L, table rows per input (a row index travels in 16 bits) */
@@ -79,12 +83,16 @@ typedef struct {
                                 Eq. 11-12, then both are stored rounded to the nearest binary16 value and inference
                                 dequantises with the stored values (Eq. 10).  Not available with spline_component;
                                 EUNSUPPORTED if a parameter is too large for binary16. */
+  int32_t knot_span;         /* lutkan_knot_span.  EXTENDED: the spline is still the sum of Eq. 3 over the G+p
+                                coefficients; on the outer p intervals of each side fewer than p+1 basis functions
+                                exist, and at the last knot itself all of them are 0 (half-open indicator of Eq. 4).
+                                The B-spline layer of the artifact uses the same domain.  Needs G + 2p <= LUTKAN_MAX_K. */
 } lutkan_layer_desc;
 
 typedef struct lutkan_artifact lutkan_artifact;     /* opaque, host memory */
 
 typedef struct {
-  int32_t d, m, K, L, G, degree, scheme, boundary, oob, value_repr, param_dtype;
+  int32_t d, m, K, L, G, degree, scheme, boundary, oob, value_repr, param_dtype, knot_span;
   int32_t jt;                /* column-tile width of the device tables (a power of two <= 128, or 128) */
   int32_t n_tiles;           /* ceil(m / jt) */
   int32_t blob_bytes;        /* bytes of one (tile, input) slice of the LUT device table */
@@ -163,7 +171,7 @@ typedef struct {
 } lutkan_dev_layer;
 
 typedef struct {
-  int32_t d, m, G, degree, boundary, oob, value_repr;
+  int32_t d, m, G, degree, boundary, oob, value_repr, knot_span;
   int32_t jt, n_tiles, coef_blob_bytes;
   int32_t algo;
   float ext_knots[LUTKAN_MAX_K + 7];  /* host copy, entries 0..G+6 used */

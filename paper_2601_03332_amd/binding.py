@@ -15,6 +15,7 @@ HALF_OPEN, CLOSED = 0, 1
 CLIP_X, ZERO_SPLINE = 0, 1
 ALGO_AUTO, ALGO_GATHER, ALGO_TILED = 0, 1, 2
 PARAM_FP32, PARAM_FP16 = 0, 1
+SPAN_DOMAIN, SPAN_EXTENDED = 0, 1
 PROBE_VALU_FMA, PROBE_LDS_READ, PROBE_L2_READ, PROBE_HBM_READ = 0, 1, 2, 3
 REPR_PHI, REPR_SPLINE_COMPONENT = 0, 1
 MAX_K = 64
@@ -29,7 +30,7 @@ class _LayerDesc(C.Structure):
                 ("ext_knots", C.c_void_p), ("coef", C.c_void_p),
                 ("L", C.c_int32), ("scheme", C.c_int32), ("boundary", C.c_int32), ("oob", C.c_int32),
                 ("value_repr", C.c_int32), ("edge_base_scale", C.c_void_p), ("edge_spline_scale", C.c_void_p),
-                ("edge_out_scale", C.c_void_p), ("param_dtype", C.c_int32)]
+                ("edge_out_scale", C.c_void_p), ("param_dtype", C.c_int32), ("knot_span", C.c_int32)]
 
 
 class _ArtifactArrays(C.Structure):
@@ -40,7 +41,7 @@ class _ArtifactArrays(C.Structure):
 
 class _Info(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("d", "m", "K", "L", "G", "degree", "scheme", "boundary", "oob", "value_repr",
-                                         "param_dtype", "jt", "n_tiles", "blob_bytes", "coef_blob_bytes")] + \
+                                         "param_dtype", "knot_span", "jt", "n_tiles", "blob_bytes", "coef_blob_bytes")] + \
                [("t0", C.c_float), ("tK", C.c_float), ("tK_star", C.c_float)] + \
                [(n, C.c_size_t) for n in ("q_canonical_bytes", "params_canonical_bytes", "table_bytes",
                                           "coef_table_bytes", "artifact_bytes")]
@@ -53,8 +54,8 @@ class _DevLayer(C.Structure):
 
 
 class _SplineDevLayer(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("d", "m", "G", "degree", "boundary", "oob", "value_repr", "jt", "n_tiles",
-                                         "coef_blob_bytes", "algo")] + \
+    _fields_ = [(n, C.c_int32) for n in ("d", "m", "G", "degree", "boundary", "oob", "value_repr", "knot_span", "jt",
+                                         "n_tiles", "coef_blob_bytes", "algo")] + \
                [("ext_knots", C.c_float * (MAX_K + 7)), ("coef_table", C.c_void_p)]
 
 
@@ -231,10 +232,12 @@ class Artifact:
 
 
 def lutkan_compile(d: int, m: int, G: int, degree: int, ext_knots, coef, L: int, scheme: int, boundary: int,
-                   oob: int, n_threads: int = 0, edge_scales=None, param_dtype: int = PARAM_FP32) -> Artifact:
+                   oob: int, n_threads: int = 0, edge_scales=None, param_dtype: int = PARAM_FP32,
+                   knot_span: int = SPAN_DOMAIN) -> Artifact:
     """Host-only LUT compilation of one dense B-spline KAN layer (Sec. 4.2-4.6).
     edge_scales = (s_base, s_spline, s_out), each [d, m], selects value_repr = spline_component (Eq. 2).
-    param_dtype = PARAM_FP16 stores scale and y_min as binary16 values (Sec. 4.6)."""
+    param_dtype = PARAM_FP16 stores scale and y_min as binary16 values (Sec. 4.6).
+    knot_span = SPAN_EXTENDED makes every interval of the extended knot vector a LUT segment (K = G + 2*degree)."""
     lib = load_library()
     tau = np.ascontiguousarray(ext_knots, dtype=np.float32)
     cf = np.ascontiguousarray(coef, dtype=np.float32)
@@ -246,6 +249,7 @@ def lutkan_compile(d: int, m: int, G: int, degree: int, ext_knots, coef, L: int,
     desc = _LayerDesc(d, m, G, degree, tau.ctypes.data, cf.ctypes.data, L, scheme, boundary, oob,
                       REPR_SPLINE_COMPONENT if keep else REPR_PHI, *[a.ctypes.data for a in keep])
     desc.param_dtype = param_dtype
+    desc.knot_span = knot_span
     out = C.c_void_p()
     _check(lib.lutkan_compile(C.byref(desc), n_threads, C.byref(out)))
     return Artifact(out.value)

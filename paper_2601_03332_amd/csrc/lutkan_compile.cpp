@@ -71,6 +71,22 @@ void nonzero_cubic_basis(const double *tau, int mu, double x, double out[4]) {
   for (int a = 0; a < 4; ++a) out[a] = lower[a];
 }
 
+// The same four values for a span anywhere in the extended knot vector (mu = 0 .. n-2): out[a] = B_{mu-3+a, 3}(x)
+// where that function exists (0 <= mu-3+a < R), else 0.  The recursion is run on a copy of the knots padded by three
+// made-up knots per side; an existing function only ever touches real knots, and the others are dropped.
+void cubic_basis_on_any_span(const std::vector<double> &tau, int R, int mu, double x, double out[4]) {
+  const int n = (int)tau.size();
+  std::vector<double> padded((size_t)n + 6);
+  for (int r = 0; r < n; ++r) padded[(size_t)r + 3] = tau[r];
+  for (int t = 1; t <= 3; ++t) {
+    padded[(size_t)3 - t] = tau[0] - t * (tau[1] - tau[0]);
+    padded[(size_t)n + 2 + t] = tau[n - 1] + t * (tau[n - 1] - tau[n - 2]);
+  }
+  nonzero_cubic_basis(padded.data(), mu + 3, x, out);
+  for (int a = 0; a < 4; ++a)
+    if (mu - 3 + a < 0 || mu - 3 + a >= R) out[a] = 0.0;
+}
+
 struct SegmentCodes {
   float alpha, ymin;
 };
@@ -193,13 +209,17 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
   if (desc->oob != LUTKAN_CLIP_X && desc->oob != LUTKAN_ZERO_SPLINE) return fail(LUTKAN_EINVAL, "lutkan_compile: bad oob_policy %d", desc->oob);
   if (desc->value_repr != LUTKAN_REPR_PHI && desc->value_repr != LUTKAN_REPR_SPLINE_COMPONENT) return fail(LUTKAN_EINVAL, "lutkan_compile: bad value_repr %d", desc->value_repr);
   if (desc->param_dtype != LUTKAN_PARAM_FP32 && desc->param_dtype != LUTKAN_PARAM_FP16) return fail(LUTKAN_EINVAL, "lutkan_compile: bad param_dtype %d", desc->param_dtype);
+  if (desc->knot_span != LUTKAN_SPAN_DOMAIN && desc->knot_span != LUTKAN_SPAN_EXTENDED) return fail(LUTKAN_EINVAL, "lutkan_compile: bad knot_span %d", desc->knot_span);
+  const bool extended = (desc->knot_span == LUTKAN_SPAN_EXTENDED);
   const bool half_params = (desc->param_dtype == LUTKAN_PARAM_FP16);
   const bool with_base = (desc->value_repr == LUTKAN_REPR_SPLINE_COMPONENT);
   if (half_params && with_base)
     return fail(LUTKAN_EUNSUPPORTED, "lutkan_compile: float16 parameters are not available with value_repr = spline_component");
   if (with_base && (!desc->edge_base_scale || !desc->edge_spline_scale || !desc->edge_out_scale))
     return fail(LUTKAN_EINVAL, "lutkan_compile: spline_component needs edge_base_scale, edge_spline_scale and edge_out_scale");
-  const int K = G, R = G + P, n_knots = G + 2 * P + 1;
+  const int R = G + P, n_knots = G + 2 * P + 1;
+  const int first_knot = extended ? 0 : P;             // LUT knot k is extended knot first_knot + k
+  const int K = extended ? G + 2 * P : G;
   if (K > LUTKAN_MAX_K) return fail(LUTKAN_EUNSUPPORTED, "lutkan_compile: K=%d exceeds LUTKAN_MAX_K=%d", K, LUTKAN_MAX_K);
   if ((int64_t)K * L > LUTKAN_MAX_ROWS) return fail(LUTKAN_EUNSUPPORTED, "lutkan_compile: K*L=%lld exceeds %d", (long long)K * L, LUTKAN_MAX_ROWS);
   for (int r = 0; r < n_knots; ++r)
@@ -225,7 +245,7 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
   const int coef_blob = coef_rows * jt * 4;
   try {
     a->ext_knots.assign(desc->ext_knots, desc->ext_knots + n_knots);
-    a->knots.assign(desc->ext_knots + P, desc->ext_knots + P + K + 1);
+    a->knots.assign(desc->ext_knots + first_knot, desc->ext_knots + first_knot + K + 1);
     a->q.resize(E * K * L);
     a->scale.resize(E * K);
     a->ymin.resize(E * K);
@@ -243,13 +263,18 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
 
   // Basis values at the K*L sampling positions x_{k,l} = t_k + l*(t_{k+1}-t_k)/L (Eq. 7).  The knot vector is
   // shared by all edges of the layer, so this small table is built once: basis[(k*L+l)*4 + a] multiplies
-  // coefficient c_{k+a} (span mu = k+3, first non-zero function r = mu-3 = k).
+  // coefficient c_{mu-3+a} of span mu = first_knot + k (on the domain grid mu-3 = k; outside it some of the four
+  // functions do not exist and their entry is 0).
   std::vector<double> tau(a->ext_knots.begin(), a->ext_knots.end());
   std::vector<double> basis((size_t)K * L * 4);
   for (int k = 0; k < K; ++k) {
     const double left = (double)a->knots[k];
     const double step = ((double)a->knots[k + 1] - left) / (double)L;
-    for (int l = 0; l < L; ++l) nonzero_cubic_basis(tau.data(), k + P, left + (double)l * step, &basis[((size_t)k * L + l) * 4]);
+    for (int l = 0; l < L; ++l) {
+      double *out = &basis[((size_t)k * L + l) * 4];
+      if (extended) cubic_basis_on_any_span(tau, R, first_knot + k, left + (double)l * step, out);
+      else nonzero_cubic_basis(tau.data(), k + P, left + (double)l * step, out);
+    }
   }
 
   int nt = n_threads > 0 ? n_threads : (int)std::thread::hardware_concurrency();
@@ -278,7 +303,9 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
         }
         for (int r = 0; r < R; ++r) cslice[(size_t)r * jt + jj] = with_base ? spline_gain * c[r] : c[r];
         for (int k = 0; k < K; ++k) {
-          const double c0 = c[k], c1 = c[k + 1], c2 = c[k + 2], c3 = c[k + 3];
+          const int r0 = first_knot + k - P;               // coefficient of the span's first basis function
+          auto coefficient = [&](int r) { return (r >= 0 && r < R) ? (double)c[r] : 0.0; };
+          const double c0 = coefficient(r0), c1 = coefficient(r0 + 1), c2 = coefficient(r0 + 2), c3 = coefficient(r0 + 3);
           for (int l = 0; l < L; ++l) {
             const double *N = &basis[((size_t)k * L + l) * 4];
             double s = 0.0;
@@ -320,6 +347,7 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
   }
 
   fill_info(a, d, m, K, L, G, scheme, desc->boundary, desc->oob, repr, desc->param_dtype, jt, n_tiles, lay, coef_blob);
+  a->info.knot_span = desc->knot_span;
   *out = a;
   return LUTKAN_OK;
 }
@@ -436,7 +464,7 @@ extern "C" int bspline_dev_layer_init(const lutkan_artifact *a, bspline_dev_laye
   std::memset(out, 0, sizeof(*out));
   const lutkan_info &I = a->info;
   out->d = I.d; out->m = I.m; out->G = I.G; out->degree = I.degree;
-  out->boundary = I.boundary; out->oob = I.oob; out->value_repr = I.value_repr;
+  out->boundary = I.boundary; out->oob = I.oob; out->value_repr = I.value_repr; out->knot_span = I.knot_span;
   out->jt = I.jt; out->n_tiles = I.n_tiles; out->coef_blob_bytes = I.coef_blob_bytes;
   out->algo = LUTKAN_ALGO_AUTO;
   for (int r = 0; r < I.G + 2 * P + 1; ++r) out->ext_knots[r] = a->ext_knots[r];

@@ -537,6 +537,7 @@ struct SplineLocateArgs {
   int64_t B, Bp;
   int32_t d, G, jt;
   int32_t closed, zero_spline, with_base;
+  int32_t extended;      // the domain is the whole extended knot vector (else its inner G intervals)
   float tKs;
   float ext_knots[LUTKAN_MAX_K + 7];
 };
@@ -549,12 +550,25 @@ template <int COLS>
 __global__ __launch_bounds__(256) void bspline_locate_kernel(const SplineLocateArgs a) {
   constexpr int ROWS = kSplTile / COLS;
   __shared__ u32x4 s_rec[2][COLS][ROWS + 1];
-  __shared__ float s_tau[LUTKAN_MAX_K + 7];
+  // the extended knots with three made-up knots on either side: s_pad[3 + r] = ext_knots[r].  A basis function that
+  // exists (index 0 .. G+2) only ever touches real knots; the padding keeps the recursion of the others in bounds.
+  __shared__ float s_pad[LUTKAN_MAX_K + 13];
   const int tid = threadIdx.x;
   const int64_t b0 = (int64_t)blockIdx.x * ROWS;
-  for (int r = tid; r < a.G + 7; r += 256) s_tau[r] = a.ext_knots[r];
+  const int n = a.G + 7;
+  for (int r = tid; r < n + 6; r += 256) {
+    float v;
+    if (r < 3) v = a.ext_knots[0] - (float)(3 - r) * (a.ext_knots[1] - a.ext_knots[0]);
+    else if (r >= n + 3) v = a.ext_knots[n - 1] + (float)(r - n - 2) * (a.ext_knots[n - 1] - a.ext_knots[n - 2]);
+    else v = a.ext_knots[r - 3];
+    s_pad[r] = v;
+  }
   __syncthreads();
-  const float t0 = s_tau[3], tK = s_tau[3 + a.G];
+  const float *s_tau = s_pad + 3;
+  const int first_knot = a.extended ? 0 : 3;           // domain knot kappa is extended knot first_knot + kappa
+  const int segments = a.extended ? a.G + 6 : a.G;
+  const int R = a.G + 3;
+  const float t0 = s_tau[first_knot], tK = s_tau[first_knot + segments];
   {
     const int i0 = blockIdx.y * COLS;
     const int il = tid % COLS;
@@ -573,9 +587,10 @@ __global__ __launch_bounds__(256) void bspline_locate_kernel(const SplineLocateA
         float xc = is_nan ? t0 : x;
         xc = (xc < t0) ? t0 : xc;
         xc = (xc > a.tKs) ? a.tKs : xc;
-        for (int kappa = 1; kappa < a.G; ++kappa) k += (s_tau[3 + kappa] <= xc) ? 1 : 0;
-        // Cox-de Boor on the span mu = k+3, non-zero entries only (Eq. 4-5); knots are distinct.
-        const float *tau = s_tau + k;               // tau[0..7] = ext_knots[mu-3 .. mu+4]
+        for (int kappa = 1; kappa < segments; ++kappa) k += (s_tau[first_knot + kappa] <= xc) ? 1 : 0;
+        // Cox-de Boor on the span mu = first_knot + k, non-zero entries only (Eq. 4-5); knots are distinct.
+        const int mu = first_knot + k;
+        const float *tau = s_tau + (mu - 3);        // tau[0..7] = ext_knots[mu-3 .. mu+4] (padding beyond the ends)
         float lower[5] = {0.f, 0.f, 0.f, 1.f, 0.f};
 #pragma unroll
         for (int q = 1; q <= 3; ++q) {
@@ -591,8 +606,24 @@ __global__ __launch_bounds__(256) void bspline_locate_kernel(const SplineLocateA
         }
         // oob_policy zero_spline: all four weights 0 (the contribution is then exactly zero); NaN poisons them
         const bool masked = a.zero_spline && !inside && !is_nan;
-        const float gate = is_nan ? __builtin_nanf("") : (masked ? 0.0f : 1.0f);
-        n0 = lower[0] * gate; n1 = lower[1] * gate; n2 = lower[2] * gate; n3 = lower[3] * gate;
+        float gate = is_nan ? __builtin_nanf("") : (masked ? 0.0f : 1.0f);
+        // at the last extended knot itself every basis function is 0 (half-open degree-0 indicator, Eq. 4)
+        if (a.extended && xc == tK && !is_nan) gate = 0.0f;
+        // lower[e] belongs to function mu-3+e.  The four coefficient rows read are first .. first+3 with first
+        // clamped into [0, R-4]; a slot whose function does not exist (outer spans of the extended range) gets 0.
+        const int first = min(max(mu - 3, 0), R - 4);
+        const int shift = first - (mu - 3);          // -3 .. 3, 0 on the inner grid
+        float slot[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int from = e + shift;
+          float v = 0.0f;
+#pragma unroll
+          for (int f = 0; f < 4; ++f) v = (from == f) ? lower[f] : v;
+          slot[e] = v * gate;
+        }
+        n0 = slot[0]; n1 = slot[1]; n2 = slot[2]; n3 = slot[3];
+        k = first;
       }
       s_rec[0][il][bl] = u32x4{(unsigned)((k + a.with_base) * a.jt * 4), __float_as_uint(n0), __float_as_uint(n1), __float_as_uint(n2)};
       s_rec[1][il][bl] = u32x4{__float_as_uint(n3), __float_as_uint(base), 0u, 0u};
@@ -1072,6 +1103,7 @@ int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y
   if (l->oob != LUTKAN_CLIP_X && l->oob != LUTKAN_ZERO_SPLINE) return fail(LUTKAN_EINVAL, "%s: bad oob_policy", who);
   if (l->algo < LUTKAN_ALGO_AUTO || l->algo > LUTKAN_ALGO_TILED) return fail(LUTKAN_EINVAL, "%s: bad algo", who);
   if (l->value_repr != LUTKAN_REPR_PHI && l->value_repr != LUTKAN_REPR_SPLINE_COMPONENT) return fail(LUTKAN_EINVAL, "%s: bad value_repr", who);
+  if (l->knot_span != LUTKAN_SPAN_DOMAIN && l->knot_span != LUTKAN_SPAN_EXTENDED) return fail(LUTKAN_EINVAL, "%s: bad knot_span", who);
   for (int r = 0; r < l->G + 6; ++r)
     if (!(l->ext_knots[r] < l->ext_knots[r + 1])) return fail(LUTKAN_EINVAL, "%s: knots not strictly increasing at %d", who, r);
   if (l->jt < 4 || l->jt > 128 || (l->jt & (l->jt - 1))) return fail(LUTKAN_EINVAL, "%s: bad jt", who);
@@ -1095,7 +1127,9 @@ int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y
   la.with_base = (l->value_repr == LUTKAN_REPR_SPLINE_COMPONENT);
   la.closed = (l->boundary == LUTKAN_CLOSED);
   la.zero_spline = (l->oob == LUTKAN_ZERO_SPLINE);
-  la.tKs = la.closed ? l->ext_knots[3 + G] : std::nextafterf(l->ext_knots[3 + G], -INFINITY);
+  la.extended = (l->knot_span == LUTKAN_SPAN_EXTENDED);
+  const float domain_end = la.extended ? l->ext_knots[G + 6] : l->ext_knots[3 + G];
+  la.tKs = la.closed ? domain_end : std::nextafterf(domain_end, -INFINITY);
   for (int r = 0; r < G + 7; ++r) la.ext_knots[r] = l->ext_knots[r];
   if (phases & kLocate) {
     const int cols = ((l->d + 15) / 16 * 16 < (l->d + 31) / 32 * 32) ? 16 : 32;      // the width that pads d least

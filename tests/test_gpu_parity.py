@@ -173,6 +173,50 @@ def test_loaded_artifact_runs_like_the_compiled_one(tmp_path):
     _assert_close(y2.cpu().numpy(), oracle.lut_forward(ora, s.boundary, s.oob, w.x), w.name)
 
 
+EXTENDED_CASES = [
+    # seed, d, m, G, L, scheme, boundary, oob, B, uniform          LUT and B-spline layer over the extended knot vector
+    (801, 3, 5, 5, 16, SYM_INT8, CLOSED, CLIP_X, 300, True),
+    (802, 10, 130, 4, 32, ASYM_UINT8, HALF_OPEN, ZERO_SPLINE, 1500, False),
+    (803, 20, 64, 8, 64, SYM_INT8, CLOSED, ZERO_SPLINE, 2000, False),
+    (804, 7, 9, 1, 8, ASYM_UINT8, HALF_OPEN, CLIP_X, 500, True),       # one grid interval: R = 4 coefficients
+    (805, 5, 40, 58, 4, SYM_INT8, CLOSED, CLIP_X, 700, True),         # K = 64 segments
+]
+
+
+@pytest.mark.parametrize("case", EXTENDED_CASES, ids=lambda c: f"seed{c[0]}")
+def test_extended_knot_span(case):
+    seed, d, m, G, L, scheme, boundary, oob, B, uniform = case
+    w = random_layer(seed, d, m, G, L, scheme, boundary, oob, B, uniform=uniform)
+    s = w.layers[0]
+    tau = s.ext_knots
+    rng = np.random.Generator(np.random.PCG64(seed))
+    span = float(tau[-1] - tau[0])
+    x = rng.uniform(tau[0] - 0.1 * span, tau[-1] + 0.1 * span, size=(B, d)).astype(np.float32)
+    pick = rng.integers(0, B * d, size=B * d // 8)                    # exact extended knots and their neighbours
+    vals = tau[rng.integers(0, tau.size, size=pick.size)]
+    nudge = rng.integers(-1, 2, size=pick.size)
+    x.reshape(-1)[pick] = np.where(nudge < 0, np.nextafter(vals, np.float32(-np.inf)),
+                                   np.where(nudge > 0, np.nextafter(vals, np.float32(np.inf)), vals)).astype(np.float32)
+    art = lk.lutkan_compile(d, m, G, 3, tau, s.coef, L, scheme, boundary, oob, knot_span=lk.SPAN_EXTENDED)
+    ora = oracle.compile_layer(d, m, G, 3, tau, s.coef, L, scheme, extended=True)
+    assert np.array_equal(art.q, ora.q) and np.array_equal(art.scale, ora.scale) and np.array_equal(art.y_min, ora.y_min)
+    xg = torch.from_numpy(x).to(DEV)
+    _say(f"case extended {w.name} K={art.info.K} jt={art.info.jt}")
+    y, k, l0, inside, wgt, _ = lk.lutkan_forward_trace(art.to_device(DEV), xg)
+    yb = lk.bspline_kan_forward(art.bspline_to_device(DEV), xg)
+    yb_g = lk.bspline_kan_forward(art.bspline_to_device(DEV, lk.ALGO_GATHER), xg)
+    torch.cuda.synchronize()
+    ref = oracle.lut_forward(ora, boundary, oob, x, trace=True)
+    np.testing.assert_array_equal(k.cpu().numpy(), ref.k)
+    np.testing.assert_array_equal(l0.cpu().numpy(), ref.l0)
+    np.testing.assert_array_equal(inside.cpu().numpy(), ref.inside)
+    np.testing.assert_array_equal(wgt.cpu().numpy().view(np.uint32), ref.w.view(np.uint32))
+    _assert_close(y.cpu().numpy(), ref, w.name)
+    refb = oracle.bspline_forward(d, m, G, 3, tau, s.coef, boundary, oob, x, extended=True)
+    _assert_close(yb.cpu().numpy(), refb, w.name + " bspline")
+    _assert_close(yb_g.cpu().numpy(), refb, w.name + " bspline gather")
+
+
 def test_special_inputs_nan_inf_all_oob():
     w = random_layer(301, 6, 140, 5, 32, ASYM_UINT8, CLOSED, ZERO_SPLINE, 40)
     x = w.x.copy()

@@ -316,3 +316,38 @@ def test_artifact_from_arrays_validates_its_input():
         with pytest.raises(lk.LutKanError) as e:
             ok(**kw)
         assert code in str(e.value), (kw.keys(), str(e.value))
+
+
+@pytest.mark.parametrize("scheme,uniform", [(SYM_INT8, True), (ASYM_UINT8, False)])
+def test_extended_knot_span_compiles_like_the_oracle(scheme, uniform):
+    s = random_layer(95, 3, 5, 6, 16, scheme, CLOSED, CLIP_X, 4, uniform=uniform).layers[0]
+    art = lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, scheme, s.boundary, s.oob, knot_span=lk.SPAN_EXTENDED)
+    ora = oracle.compile_layer(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, scheme, extended=True)
+    assert (art.info.K, art.info.G, art.info.knot_span) == (s.G + 6, s.G, lk.SPAN_EXTENDED)
+    np.testing.assert_array_equal(art.knots, s.ext_knots)
+    np.testing.assert_array_equal(art.q, ora.q)
+    np.testing.assert_array_equal(art.scale.view(np.uint32), ora.scale.view(np.uint32))
+    np.testing.assert_array_equal(art.y_min.view(np.uint32), ora.y_min.view(np.uint32))
+    assert art.info.t0 == s.ext_knots[0] and art.info.tK == s.ext_knots[-1]
+    with pytest.raises(lk.LutKanError) as e:                      # G + 2p segments must fit the kernels' knot table
+        big = random_layer(96, 1, 1, 60, 2, scheme, CLOSED, CLIP_X, 4).layers[0]
+        lk.lutkan_compile(1, 1, 60, 3, big.ext_knots, big.coef, 2, scheme, CLOSED, CLIP_X, knot_span=lk.SPAN_EXTENDED)
+    assert str(e.value).startswith("[-5]")
+
+
+def test_table9_artifact_bytes_from_the_compiler():
+    """Table 9 (Sec. 8.6): LUT artifact bytes of the case study's layers [78,32,16,1], grid 5, cubic, L = 64.  The
+    compiler reproduces every row with the LUT over the extended knot vector and float16 scale / y_min."""
+    gold = os.path.join(ROOT, "tests", "golden", "table9_artifact_bytes.txt")
+    rows = [[int(v) for v in l.split()] for l in open(gold) if l[0] != "#"]
+    widths = [78, 32, 16, 1]
+    rng = np.random.Generator(np.random.PCG64(9))
+    total = 0
+    for (d, m), (E, K, L, nbytes) in zip(zip(widths[:-1], widths[1:]), rows):
+        assert d * m == E
+        s = random_layer(int(rng.integers(1 << 30)), d, m, 5, L, ASYM_UINT8, CLOSED, CLIP_X, 2).layers[0]
+        art = lk.lutkan_compile(d, m, 5, 3, s.ext_knots, s.coef, L, ASYM_UINT8, CLOSED, CLIP_X,
+                                param_dtype=lk.PARAM_FP16, knot_span=lk.SPAN_EXTENDED)
+        assert art.info.K == K and art.info.artifact_bytes == nbytes
+        total += art.info.artifact_bytes
+    assert total == 2262096                                          # the table's "LUT Total"
