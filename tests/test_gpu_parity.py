@@ -363,6 +363,13 @@ def test_cfg4_wide_layer_full_size_sampled_rows(B):
     _sampled_rows_check(cfg4(B=B), 96, f"cfg4 B={B}")
 
 
+def test_two_million_rows_sampled():
+    """A batch far beyond the workloads (2^21 rows, 2048 row tiles, 1 GiB of lookup records): 64-bit row indexing in
+    every kernel, checked on sampled rows and through the exact OOB counters."""
+    w = random_layer(351, 64, 48, 6, 32, ASYM_UINT8, HALF_OPEN, ZERO_SPLINE, 1 << 21)
+    _sampled_rows_check(w, 400, "2^21 rows, 64 -> 48")
+
+
 # ---------------------------------------------------------------- B-spline baseline
 def _check_bspline(s, x, algo, what):
     art = lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, s.boundary, s.oob,
