@@ -932,6 +932,7 @@ int launch_tiled_np(const EdgeArgs &ea, hipStream_t s) {
   constexpr int NW = kTileWaves;
   constexpr int RW = (64 / LPR) * NP;
   const int64_t row_tiles = (ea.B + NW * RW - 1) / (NW * RW);
+  if (row_tiles * ea.n_tiles > 0x7fffffffLL) return fail(LUTKAN_EUNSUPPORTED, "lutkan_tiled_kernel: B * m too large for one launch");
   const dim3 grid((unsigned)(row_tiles * ea.n_tiles), (unsigned)((ea.d + ea.chunk - 1) / ea.chunk));
   const size_t lds = 2 * (size_t)ea.blob_bytes + (size_t)NW * 2 * RW * (ea.with_base ? 16 : 8);
   static bool raised = false, raised_base = false;
@@ -1065,6 +1066,7 @@ int launch_spline_tiled_np(const SplineEdgeArgs &ea, hipStream_t s) {
   constexpr int RW = (64 / LPR) * NP;
   const int bytes = ea.rows * 4 * LPR * 4;
   const int64_t row_tiles = (ea.B + NW * RW - 1) / (NW * RW);
+  if (row_tiles * ea.n_tiles > 0x7fffffffLL) return fail(LUTKAN_EUNSUPPORTED, "bspline_tiled_kernel: B * m too large for one launch");
   const dim3 grid((unsigned)(row_tiles * ea.n_tiles), (unsigned)((ea.d + ea.chunk - 1) / ea.chunk));
   const size_t lds = 2 * (size_t)bytes + (size_t)NW * 2 * RW * 32;
   static bool raised = false, raised_base = false;
