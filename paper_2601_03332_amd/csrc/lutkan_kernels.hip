@@ -65,7 +65,8 @@ struct Located {
   bool inside, is_nan;
 };
 
-__device__ __forceinline__ Located locate_one(const LocateArgs &a, float x) {
+// s_knots: the K+1 knots in LDS, for the two lookups by the lane's own segment index.
+__device__ __forceinline__ Located locate_one(const LocateArgs &a, const float *s_knots, float x) {
   Located o;
   const float t0 = a.knots[0];
   const float tK = a.knots[a.K];
@@ -76,14 +77,8 @@ __device__ __forceinline__ Located locate_one(const LocateArgs &a, float x) {
   xc = (xc > a.tKs) ? a.tKs : xc;
   // k = #{kappa in 1..K-1 : T[kappa] <= x'}; T[0] <= x' always holds and T[K] is clipped away (Eq. 14).
   int k = 0;
-  float tk = t0, tk1 = a.knots[1];
-  for (int kappa = 1; kappa < a.K; ++kappa) {
-    const float t = a.knots[kappa];
-    const bool ge = (t <= xc);
-    k += ge ? 1 : 0;
-    tk = ge ? t : tk;
-    tk1 = ge ? a.knots[kappa + 1] : tk1;
-  }
+  for (int kappa = 1; kappa < a.K; ++kappa) k += (a.knots[kappa] <= xc) ? 1 : 0;     // knots sit in scalar registers
+  const float tk = s_knots[k], tk1 = s_knots[k + 1];
   const float num = __fsub_rn(xc, tk);
   const float den = __fsub_rn(tk1, tk);
   const float u = __fdiv_rn(num, den);                       // Eq. 15, correctly rounded
@@ -109,8 +104,10 @@ __global__ __launch_bounds__(256) void lutkan_locate_kernel(const LocateArgs a) 
   constexpr int ROWS = kLocTile / COLS;
   constexpr int ROW_GROUPS = 256 / COLS;                 // rows handled side by side in phase 1
   __shared__ rec_t s_rec[COLS][ROWS + 1];
+  __shared__ float s_knots[LUTKAN_MAX_K + 1];
   rec_t *const rec_out = static_cast<rec_t *>(a.rec);
   const int tid = threadIdx.x;
+  if (tid <= a.K) s_knots[tid] = a.knots[tid];
   const int64_t b0 = (int64_t)blockIdx.x * ROWS;
   const int i0 = blockIdx.y * COLS;
   const unsigned masked_index = (unsigned)(a.K * a.L) | ((unsigned)a.K << 16);
@@ -122,6 +119,7 @@ __global__ __launch_bounds__(256) void lutkan_locate_kernel(const LocateArgs a) 
     const int64_t b = b0 + p * ROW_GROUPS + tid / COLS;
     xv[p] = (b < a.B && i < a.d) ? a.x[b * a.d + i] : 0.0f;
   }
+  __syncthreads();                                       // s_knots is filled
 #pragma unroll
   for (int p = 0; p < 8; ++p) {
     const int bl = p * ROW_GROUPS + tid / COLS;
@@ -130,7 +128,7 @@ __global__ __launch_bounds__(256) void lutkan_locate_kernel(const LocateArgs a) 
     rec.x = masked_index;
     if (b < a.B && i < a.d) {
       const float x = xv[p];
-      const Located o = locate_one(a, x);
+      const Located o = locate_one(a, s_knots, x);
       const bool masked = a.zero_spline && !o.inside && !o.is_nan;
       if (!masked) {
         rec.x = (unsigned)(o.k * a.L + o.l0) | ((unsigned)o.k << 16);
