@@ -351,3 +351,31 @@ def test_table9_artifact_bytes_from_the_compiler():
         assert art.info.K == K and art.info.artifact_bytes == nbytes
         total += art.info.artifact_bytes
     assert total == 2262096                                          # the table's "LUT Total"
+
+
+def test_m0_is_only_touched_by_the_lds_dma_helper(tmp_path):
+    """The LDS-DMA copy helper writes M0 inside an inline-asm block and declares it clobbered.  That is only sound
+    while the compiler itself keeps nothing in M0 in the kernels that use the helper: check the generated gfx950
+    assembly (every mention of m0 in a tiled kernel lies inside an inline-asm block)."""
+    import subprocess
+    from paper_2601_03332_amd import build as lib_build
+    out = tmp_path / "kernels.s"
+    src = os.path.join(ROOT, "paper_2601_03332_amd", "csrc", "lutkan_kernels.hip")
+    cmd = [os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")] + lib_build.HIPCC_FLAGS + \
+          ["-I", os.path.join(ROOT, "include"), "-I", os.path.join(ROOT, "paper_2601_03332_amd", "csrc"),
+           "-x", "hip", "--cuda-device-only", "-S", src, "-o", str(out)]
+    subprocess.run(cmd, check=True, capture_output=True)
+    kernels, inside_asm, current = 0, False, None
+    for line in open(out):
+        text = line.strip()
+        if re.match(r"_Z\S*tiled_kernel\S*:", text):
+            current, kernels = text.split(":")[0], kernels + 1
+        elif text.startswith(".Lfunc_end"):
+            current = None
+        elif text.startswith(";;#ASMSTART"):
+            inside_asm = True
+        elif text.startswith(";;#ASMEND"):
+            inside_asm = False
+        elif current and not text.startswith(";") and re.search(r"\bm0\b", text.split(";")[0]):
+            assert inside_asm, f"compiler-generated use of m0 in {current}: {text}"
+    assert kernels > 50                                              # every LUT and B-spline tiled variant was seen
