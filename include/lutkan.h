@@ -33,8 +33,7 @@ typedef enum {
   LUTKAN_ESHAPE = -2,        /* sizes that do not fit together (workspace too small, d/m mismatch in a chain) */
   LUTKAN_ENOMEM = -3,        /* host allocation failed */
   LUTKAN_EHIP = -4,          /* a HIP runtime call failed */
-  LUTKAN_EUNSUPPORTED = -5   /* degree != 3, K > LUTKAN_MAX_K, K*L > LUTKAN_MAX_ROWS, fp16 parameters out of range or
-                                combined with spline_component */
+  LUTKAN_EUNSUPPORTED = -5   /* degree != 3, K > LUTKAN_MAX_K, K*L > LUTKAN_MAX_ROWS, fp16 parameters out of range */
 } lutkan_status;
 
 typedef enum { LUTKAN_SYM_INT8 = 0, LUTKAN_ASYM_UINT8 = 1 } lutkan_scheme;        /* Sec. 4.4, Eq. 11-12 */
@@ -81,8 +80,8 @@ typedef struct {
   const float *edge_out_scale;     /* s_out    [d][m] */
   int32_t param_dtype;       /* lutkan_param_dtype.  FP16: the codes are computed from the fp32 alpha and y_min of
                                 Eq. 11-12, then both are stored rounded to the nearest binary16 value and inference
-                                dequantises with the stored values (Eq. 10).  Not available with spline_component;
-                                EUNSUPPORTED if a parameter is too large for binary16. */
+                                dequantises with the stored values (Eq. 10).  EUNSUPPORTED if a parameter is too
+                                large for binary16. */
   int32_t knot_span;         /* lutkan_knot_span.  EXTENDED: the spline is still the sum of Eq. 3 over the G+p
                                 coefficients; on the outer p intervals of each side fewer than p+1 basis functions
                                 exist, and at the last knot itself all of them are 0 (half-open indicator of Eq. 4).
@@ -145,6 +144,7 @@ const float *lutkan_artifact_edge_out_scale(const lutkan_artifact *a);    /* [E]
 /* Device tables (host copies to upload verbatim).  Columns are cut into n_tiles tiles of jt outputs; the
  * last tile is zero padded.  LUT table: for tile t and input i one contiguous slice of blob_bytes bytes
  *     float   base  [jt]                       (spline_component only: s_out * s_base of the edge (i, column))
+ *     float   gain  [jt]                       (spline_component with fp16 parameters only: s_out * s_spline)
  *     param   p     [K+1] rows                 (a row is alpha[jt], followed for the asymmetric scheme by y_min[jt] --
  *                                               y_min is elided when it is identically 0, Sec. 7.5; row K is all zero;
  *                                               values are fp32, or binary16 with fp16 parameters)
@@ -153,8 +153,9 @@ const float *lutkan_artifact_edge_out_scale(const lutkan_artifact *a);    /* [E]
  *                                               byte = q + 128; the two trailing rows are all-zero bytes)
  *     zero padding up to a multiple of 16 bytes
  * The zero rows are where the kernels redirect inputs whose contribution is exactly 0 (oob_policy zero_spline).
- * With spline_component the product s_out * s_spline of the edge is folded into its alpha and y_min (and into
- * the coefficients of the B-spline table, whose slices then start with the same base[jt] row).
+ * With spline_component the product s_out * s_spline of the edge is folded into its fp32 alpha and y_min (fp16
+ * parameters are stored as they are, rounded, and the product sits in the gain row), and into the coefficients of
+ * the B-spline table, whose slices then start with the same base[jt] row.
  * slices ordered [t][i].  B-spline table: slices of float c[R = G+p][jt], ordered [t][i]. */
 const void *lutkan_artifact_table(const lutkan_artifact *a);
 const void *lutkan_artifact_coef_table(const lutkan_artifact *a);

@@ -146,8 +146,12 @@ struct SlicePacker {
   int jt, L, scheme;
   bool half_params;
 
-  // s_out * s_base of the edge in column jj (spline_component only)
-  void put_base(uint8_t *slice, int jj, float base_gain) const { reinterpret_cast<float *>(slice)[jj] = base_gain; }
+  // s_out * s_base of the edge in column jj (spline_component only); with float16 parameters also s_out * s_spline,
+  // which cannot be folded into parameters that are stored rounded
+  void put_base(uint8_t *slice, int jj, float base_gain, float spline_gain) const {
+    reinterpret_cast<float *>(slice)[jj] = base_gain;
+    if (half_params) reinterpret_cast<float *>(slice)[jt + jj] = spline_gain;
+  }
 
   // Segment k of the edge in column jj: its dequantisation parameters (times gain = s_out * s_spline with
   // spline_component, else exactly as given; binary16 parameters arrive already rounded) and its L codes.
@@ -213,8 +217,6 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
   const bool extended = (desc->knot_span == LUTKAN_SPAN_EXTENDED);
   const bool half_params = (desc->param_dtype == LUTKAN_PARAM_FP16);
   const bool with_base = (desc->value_repr == LUTKAN_REPR_SPLINE_COMPONENT);
-  if (half_params && with_base)
-    return fail(LUTKAN_EUNSUPPORTED, "lutkan_compile: float16 parameters are not available with value_repr = spline_component");
   if (with_base && (!desc->edge_base_scale || !desc->edge_spline_scale || !desc->edge_out_scale))
     return fail(LUTKAN_EINVAL, "lutkan_compile: spline_component needs edge_base_scale, edge_spline_scale and edge_out_scale");
   const int R = G + P, n_knots = G + 2 * P + 1;
@@ -297,7 +299,7 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
         if (with_base) {
           const float base_gain = desc->edge_out_scale[e] * desc->edge_base_scale[e];
           spline_gain = desc->edge_out_scale[e] * desc->edge_spline_scale[e];
-          packer.put_base(slice, jj, base_gain);
+          packer.put_base(slice, jj, base_gain, spline_gain);
           cslice[jj] = base_gain;
           cslice += jt;
         }
@@ -366,7 +368,6 @@ extern "C" int lutkan_artifact_from_arrays(const lutkan_artifact_arrays *in, lut
   if (in->param_dtype != LUTKAN_PARAM_FP32 && in->param_dtype != LUTKAN_PARAM_FP16) return fail(LUTKAN_EINVAL, "%s: bad param_dtype %d", who, in->param_dtype);
   const bool with_base = (repr == LUTKAN_REPR_SPLINE_COMPONENT);
   const bool half_params = (in->param_dtype == LUTKAN_PARAM_FP16);
-  if (half_params && with_base) return fail(LUTKAN_EUNSUPPORTED, "%s: float16 parameters are not available with value_repr = spline_component", who);
   if (with_base && (!in->edge_base_scale || !in->edge_spline_scale || !in->edge_out_scale))
     return fail(LUTKAN_EINVAL, "%s: spline_component needs edge_base_scale, edge_spline_scale and edge_out_scale", who);
   if (K > LUTKAN_MAX_K) return fail(LUTKAN_EUNSUPPORTED, "%s: K=%d exceeds LUTKAN_MAX_K=%d", who, K, LUTKAN_MAX_K);
@@ -413,8 +414,8 @@ extern "C" int lutkan_artifact_from_arrays(const lutkan_artifact_arrays *in, lut
       uint8_t *slice = a->table.data() + ((size_t)(j / jt) * d + i) * lay.bytes;
       float spline_gain = 1.0f;
       if (with_base) {
-        packer.put_base(slice, j % jt, a->edge_out[e] * a->edge_base[e]);
         spline_gain = a->edge_out[e] * a->edge_spline[e];
+        packer.put_base(slice, j % jt, a->edge_out[e] * a->edge_base[e], spline_gain);
       }
       for (int k = 0; k < K; ++k)
         packer.put_segment(slice, j % jt, k, a->scale[e * K + k], a->ymin[e * K + k], with_base, spline_gain, a->q.data() + (e * K + k) * L);

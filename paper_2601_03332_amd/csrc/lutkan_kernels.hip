@@ -250,7 +250,7 @@ __global__ __launch_bounds__(256) void lutkan_gather_kernel(const EdgeArgs a, co
       silu_x[u] = a.with_base ? __uint_as_float(r[2]) : 0.0f;
     }
     unsigned c0[U], c1[U];
-    float al[U], ym[U], bg[U];
+    float al[U], ym[U], bg[U], sg[U];      // alpha, y_min, s_out*s_base, s_out*s_spline (1 where it is folded in)
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const unsigned char *slice = tile + (size_t)min(i0 + u, a.d - 1) * a.blob_bytes;
@@ -269,6 +269,7 @@ __global__ __launch_bounds__(256) void lutkan_gather_kernel(const EdgeArgs a, co
         ym[u] = (SCHEME == LUTKAN_ASYM_UINT8) ? prm[a.jt + jj] : 0.0f;
       }
       bg[u] = a.with_base ? reinterpret_cast<const float *>(slice)[jj] : 0.0f;
+      sg[u] = (a.with_base && a.param_fp16) ? reinterpret_cast<const float *>(slice)[a.jt + jj] : 1.0f;
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -276,8 +277,12 @@ __global__ __launch_bounds__(256) void lutkan_gather_kernel(const EdgeArgs a, co
         const float w = __uint_as_float(rec[u].y);
         const float f0 = code_to_float<SCHEME>(c0[u]), f1 = code_to_float<SCHEME>(c1[u]);
         const float tq = fmaf(w, f1 - f0, f0);                             // interpolate the codes ...
-        acc = fmaf(al[u], tq, acc);                                        // ... then one scale per edge
-        if (SCHEME == LUTKAN_ASYM_UINT8) acc += ym[u];
+        if (a.with_base && a.param_fp16) {                                 // unfolded: s_out*s_spline * (y_min + alpha * t)
+          acc = fmaf(sg[u], fmaf(al[u], tq, ym[u]), acc);
+        } else {
+          acc = fmaf(al[u], tq, acc);                                      // ... then one scale per edge
+          if (SCHEME == LUTKAN_ASYM_UINT8) acc += ym[u];
+        }
         if (a.with_base) acc = fmaf(bg[u], silu_x[u], acc);                  // + s_out*s_base * SiLU(x)
         if (TRACE && a.q01_out) {
           const int l0 = a.l0_out[b * a.d + i0 + u];
@@ -359,7 +364,6 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
   static_assert(RW <= 64, "a wave's records for one input must fit one 1 KiB copy step");
   constexpr int PSZ = PH ? 8 : 16;         // bytes of a lane's four alphas (and of its four y_min, one plane further)
   constexpr int PLANE = JT * (PH ? 2 : 4); // a parameter row is the alpha plane, then (asymmetric) the y_min plane
-  static_assert(!(BASE && PH), "float16 parameters are not combined with the base branch");
   constexpr int RB = BASE ? 16 : 8;                              // bytes per record
   constexpr int REC_LANES = RW * RB / 16;                        // lanes that copy 16 bytes of the wave's records
   static_assert((RW * RB) % 16 == 0, "a wave's records are whole 16-byte vectors");
@@ -411,8 +415,10 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
     // step where the wave waits for its outstanding LDS reads (the first touch of step p's data): what the
     // wave waits for was issued a whole step earlier, what it issues now has a whole step to arrive.
     typedef typename std::conditional<BASE, u32x3, u32x2>::type rec_t;        // 12-byte or 8-byte LDS read
-    f32x4 base_gain = {0.f, 0.f, 0.f, 0.f};
+    f32x4 base_gain = {0.f, 0.f, 0.f, 0.f}, spline_gain = {1.f, 1.f, 1.f, 1.f};
     if (BASE) base_gain = *reinterpret_cast<const f32x4 *>(slice + sub * 16) * kTwoToMinus24;
+    // float16 parameters are stored rounded, so s_out*s_spline cannot be folded into them: it has a row of its own
+    if (BASE && PH) spline_gain = *reinterpret_cast<const f32x4 *>(slice + JT * 4 + sub * 16);
     // parameters of the lane's 4 columns as loaded: pa = the four alphas, pb = the four y_min (asymmetric);
     // binary16 parameters are packed two per word in .x and .y
     struct Fetched { unsigned c0, c1; f32x4 pa, pb; };
@@ -482,13 +488,24 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
       const float t1 = fmaf(w, (float)dlo.y, (float)q0lo.y);
       const float t2 = fmaf(w, (float)dhi.x, (float)q0hi.x);
       const float t3 = fmaf(w, (float)dhi.y, (float)q0hi.y);
-      acc[p][0] = fmaf(al[0], t0, acc[p][0]);
-      acc[p][1] = fmaf(al[1], t1, acc[p][1]);
-      acc[p][2] = fmaf(al[2], t2, acc[p][2]);
-      acc[p][3] = fmaf(al[3], t3, acc[p][3]);
-      if (SCHEME == LUTKAN_ASYM_UINT8) {
+      if constexpr (BASE && PH) {                                              // gain * (alpha * t + y_min * 2^-24)
+        const float u0 = fmaf(al[0], t0, (SCHEME == LUTKAN_ASYM_UINT8) ? ym[0] * kTwoToMinus24 : 0.0f);
+        const float u1 = fmaf(al[1], t1, (SCHEME == LUTKAN_ASYM_UINT8) ? ym[1] * kTwoToMinus24 : 0.0f);
+        const float u2 = fmaf(al[2], t2, (SCHEME == LUTKAN_ASYM_UINT8) ? ym[2] * kTwoToMinus24 : 0.0f);
+        const float u3 = fmaf(al[3], t3, (SCHEME == LUTKAN_ASYM_UINT8) ? ym[3] * kTwoToMinus24 : 0.0f);
+        acc[p][0] = fmaf(spline_gain.x, u0, acc[p][0]);
+        acc[p][1] = fmaf(spline_gain.y, u1, acc[p][1]);
+        acc[p][2] = fmaf(spline_gain.z, u2, acc[p][2]);
+        acc[p][3] = fmaf(spline_gain.w, u3, acc[p][3]);
+      } else {
+        acc[p][0] = fmaf(al[0], t0, acc[p][0]);
+        acc[p][1] = fmaf(al[1], t1, acc[p][1]);
+        acc[p][2] = fmaf(al[2], t2, acc[p][2]);
+        acc[p][3] = fmaf(al[3], t3, acc[p][3]);
+        if (SCHEME == LUTKAN_ASYM_UINT8) {
 #pragma unroll
-        for (int c = 0; c < 4; ++c) acc[p][c] = fmaf(ym[c], kTwoToMinus24, acc[p][c]);
+          for (int c = 0; c < 4; ++c) acc[p][c] = fmaf(ym[c], kTwoToMinus24, acc[p][c]);
+        }
       }
       if constexpr (BASE) {
         const float silu_x = __uint_as_float(rc_cur.z);
@@ -873,7 +890,6 @@ int validate_layer(const lutkan_dev_layer *l, const char *who) {
   if (l->algo < LUTKAN_ALGO_AUTO || l->algo > LUTKAN_ALGO_TILED) return fail(LUTKAN_EINVAL, "%s: bad algo %d", who, l->algo);
   if (l->value_repr != LUTKAN_REPR_PHI && l->value_repr != LUTKAN_REPR_SPLINE_COMPONENT) return fail(LUTKAN_EINVAL, "%s: bad value_repr %d", who, l->value_repr);
   if (l->param_dtype != LUTKAN_PARAM_FP32 && l->param_dtype != LUTKAN_PARAM_FP16) return fail(LUTKAN_EINVAL, "%s: bad param_dtype %d", who, l->param_dtype);
-  if (l->param_dtype == LUTKAN_PARAM_FP16 && l->value_repr == LUTKAN_REPR_SPLINE_COMPONENT) return fail(LUTKAN_EUNSUPPORTED, "%s: float16 parameters are not available with spline_component", who);
   for (int k = 0; k < l->K; ++k)
     if (!(l->knots[k] < l->knots[k + 1])) return fail(LUTKAN_EINVAL, "%s: knots not strictly increasing at %d", who, k);
   if (l->jt < 4 || l->jt > 128 || (l->jt & (l->jt - 1))) return fail(LUTKAN_EINVAL, "%s: jt=%d is not a power of two in [4,128]", who, l->jt);
@@ -936,7 +952,8 @@ int launch_tiled_np(const EdgeArgs &ea, hipStream_t s) {
   const dim3 grid((unsigned)(row_tiles * ea.n_tiles), (unsigned)((ea.d + ea.chunk - 1) / ea.chunk));
   const size_t lds = 2 * (size_t)ea.blob_bytes + (size_t)NW * 2 * RW * (ea.with_base ? 16 : 8);
   static bool raised = false, raised_base = false;
-  static bool raised_half = false;
+  static bool raised_half = false, raised_base_half = false;
+  if (ea.with_base && ea.param_fp16) return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, true, true>, &raised_base_half, grid, lds, s, ea, "lutkan_tiled_kernel");
   if (ea.with_base) return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, true, false>, &raised_base, grid, lds, s, ea, "lutkan_tiled_kernel");
   if (ea.param_fp16) return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, false, true>, &raised_half, grid, lds, s, ea, "lutkan_tiled_kernel");
   return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, false, false>, &raised, grid, lds, s, ea, "lutkan_tiled_kernel");

@@ -154,6 +154,16 @@ def test_fp16_parameters(case):
     _check_layer(w.layers[0], w.x, lk.ALGO_GATHER, codes=(B * d * m <= 2_000_000), what=w.name, param_fp16=True)
 
 
+@pytest.mark.parametrize("case", FP16_PARAM_CASES, ids=lambda c: f"seed{c[0]}")
+def test_fp16_parameters_with_spline_component(case):
+    """The deployment combination of Sec. 8: asymmetric or symmetric codes, float16 scale / y_min, Eq. 2's base branch
+    and per-edge scalars; the scalars multiply the dequantised value, the parameters stay the rounded ones."""
+    seed, d, m, G, L, scheme, boundary, oob, B = case
+    w = random_layer(seed + 50, d, m, G, L, scheme, boundary, oob, B, uniform=(seed % 2 == 1), with_base=True)
+    _check_layer(w.layers[0], w.x, lk.ALGO_TILED, what=w.name, param_fp16=True)
+    _check_layer(w.layers[0], w.x, lk.ALGO_GATHER, codes=(B * d * m <= 2_000_000), what=w.name, param_fp16=True)
+
+
 def test_loaded_artifact_runs_like_the_compiled_one(tmp_path):
     """An artifact written to NPZ + manifest and read back (Sec. 4.6) gives bit-identical outputs and counters."""
     w = random_layer(611, 20, 150, 6, 32, ASYM_UINT8, HALF_OPEN, ZERO_SPLINE, 3000)
@@ -561,7 +571,7 @@ def test_random_shapes_and_contracts():
         B = int(rng.choice([1, 2, 15, 16, 17, 63, 64, 65, 255, 256, 257, 1000, 1024, 1025, 2500]))
         scheme, boundary, oob = (int(rng.integers(0, 2)) for _ in range(3))
         base = bool(rng.integers(0, 2))
-        half = bool(rng.integers(0, 2)) and not base
+        half = bool(rng.integers(0, 2))
         algo = int(rng.choice([lk.ALGO_AUTO, lk.ALGO_GATHER]))
         w = random_layer(2000 + it, d, m, G, L, scheme, boundary, oob, B, uniform=bool(rng.integers(0, 2)), with_base=base)
         s = w.layers[0]

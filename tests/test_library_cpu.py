@@ -247,13 +247,45 @@ def test_fp16_parameter_tables(scheme):
             np.testing.assert_array_equal(codes[:, :, :n], want)
 
 
-def test_fp16_parameters_are_refused_where_they_cannot_hold():
-    w = random_layer(92, 2, 3, 5, 8, SYM_INT8, CLOSED, CLIP_X, 4, with_base=True)
+@pytest.mark.parametrize("scheme", [SYM_INT8, ASYM_UINT8])
+def test_fp16_parameters_with_spline_component(scheme):
+    """Sec. 4.6 float16 parameters together with Eq. 2's per-edge scalars: the parameters stay the rounded values
+    themselves (what Eq. 10 dequantises with), and s_out*s_spline has a float32 row of its own after the base row."""
+    w = random_layer(97, 3, 70, 6, 16, scheme, CLOSED, CLIP_X, 4, with_base=True)
     s = w.layers[0]
-    with pytest.raises(lk.LutKanError) as e:                      # not combined with the base branch
-        lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, s.boundary, s.oob,
-                          edge_scales=s.edge_scales, param_dtype=lk.PARAM_FP16)
-    assert str(e.value).startswith("[-5]")
+    art = lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, scheme, s.boundary, s.oob,
+                            edge_scales=s.edge_scales, param_dtype=lk.PARAM_FP16)
+    ora = oracle.compile_layer(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, scheme, param_fp16=True)
+    np.testing.assert_array_equal(art.q, ora.q)
+    np.testing.assert_array_equal(art.scale.view(np.uint32), ora.scale.view(np.uint32))
+    np.testing.assert_array_equal(art.y_min.view(np.uint32), ora.y_min.view(np.uint32))
+    I = art.info
+    K, L, jt, nt = I.K, I.L, I.jt, I.n_tiles
+    per = 2 if scheme == ASYM_UINT8 else 1
+    params_off = 2 * jt * 4
+    codes_off = params_off + (K + 1) * jt * 2 * per
+    assert I.blob_bytes == (codes_off + (K * L + 2) * jt + 15) // 16 * 16
+    sb, ss, so = (np.asarray(v, np.float32).reshape(-1) for v in s.edge_scales)
+    tab = art.table.reshape(nt, s.d, I.blob_bytes)
+    for t in range(nt):
+        cols = np.arange(t * jt, min(s.m, (t + 1) * jt))
+        n = cols.size
+        for i in range(s.d):
+            e = i * s.m + cols
+            head = tab[t, i, :params_off].view(np.float32).reshape(2, jt)
+            np.testing.assert_array_equal(head[0, :n], so[e] * sb[e])
+            np.testing.assert_array_equal(head[1, :n], so[e] * ss[e])
+            assert np.all(head[:, n:] == 0)
+            prm = tab[t, i, params_off:codes_off].view(np.float16).reshape(K + 1, per, jt)
+            np.testing.assert_array_equal(prm[:K, 0, :n].astype(np.float32), art.scale[e].T)
+            if scheme == ASYM_UINT8:
+                np.testing.assert_array_equal(prm[:K, 1, :n].astype(np.float32), art.y_min[e].T)
+            assert np.all(prm[K] == 0)
+
+
+def test_fp16_parameters_are_refused_where_they_cannot_hold():
+    w = random_layer(92, 2, 3, 5, 8, SYM_INT8, CLOSED, CLIP_X, 4)
+    s = w.layers[0]
     with pytest.raises(lk.LutKanError) as e:                      # alpha beyond the largest binary16
         lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef * np.float32(1e8), s.L, s.scheme, s.boundary, s.oob,
                           param_dtype=lk.PARAM_FP16)
@@ -263,7 +295,7 @@ def test_fp16_parameters_are_refused_where_they_cannot_hold():
     assert str(e.value).startswith("[-1]")
 
 
-@pytest.mark.parametrize("with_base,param_dtype,scheme", [(False, 0, SYM_INT8), (False, 1, ASYM_UINT8), (True, 0, ASYM_UINT8)])
+@pytest.mark.parametrize("with_base,param_dtype,scheme", [(False, 0, SYM_INT8), (False, 1, ASYM_UINT8), (True, 0, ASYM_UINT8), (True, 1, ASYM_UINT8)])
 def test_artifact_round_trip_through_npz_and_manifest(tmp_path, with_base, param_dtype, scheme):
     """Sec. 4.6 serialisation: the NPZ holds the paper's keys, the manifest its metadata fields, and loading it gives
     back the same canonical arrays and a byte-identical device table."""
@@ -391,8 +423,6 @@ def test_host_compile_matches_the_oracle_on_random_shapes():
         d, m = int(rng.integers(1, 9)), int(rng.choice([1, 2, 3, 5, 8, 15, 16, 17, 40, 70, 130]))
         scheme = int(rng.integers(0, 2))
         half, extended, base = bool(rng.integers(0, 2)), bool(rng.integers(0, 2)), bool(rng.integers(0, 2))
-        if half:
-            base = False
         s = random_layer(3000 + it, d, m, G, L, scheme, CLOSED, CLIP_X, 2, uniform=bool(rng.integers(0, 2)), with_base=base).layers[0]
         art = lk.lutkan_compile(d, m, G, 3, s.ext_knots, s.coef, L, scheme, CLOSED, CLIP_X, edge_scales=s.edge_scales,
                                 param_dtype=int(half), knot_span=int(extended), n_threads=int(rng.integers(1, 5)))
