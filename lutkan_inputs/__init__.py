@@ -52,13 +52,14 @@ class LayerSpec:
     m: int
     G: int
     p: int
-    ext_knots: np.ndarray      # [G+2p+1] fp32
+    ext_knots: np.ndarray      # [G+2p+1] fp32, or [d][G+2p+1] with per_input
     coef: np.ndarray           # [d][m][G+p] fp32
     L: int
     scheme: int
     boundary: int
     oob: int
     edge_scales: object = None    # None (value_repr = phi) or (s_base, s_spline, s_out), each [d][m] fp32 (Eq. 2)
+    per_input: bool = False       # one knot vector per input dimension (Sec. 6.2 "shared per input dimension")
 
 
 @dataclass
@@ -179,3 +180,33 @@ def random_layer(seed: int, d: int, m: int, G: int, L: int, scheme: int, boundar
     if with_base:
         layer.edge_scales = draw_edge_scales(rng, d, m)
     return Workload(f"rand_{d}x{m}_G{G}_L{L}_s{scheme}_b{boundary}_o{oob}_seed{seed}{'_sc' if with_base else ''}", [layer], x)
+
+
+def per_input_layer(seed: int, d: int, m: int, G: int, L: int, scheme: int, boundary: int, oob: int, B: int,
+                    oob_frac: float = 0.15, p: int = 3, with_base: bool = False) -> Workload:
+    """Layer whose inputs each have their own knot vector, as after a per-feature grid update: input i has the domain
+    [lo_i, hi_i] with lo_i ~ U(-3,-0.5) and width ~ U(0.5,4), uniform or (every other input) non-uniform knots; x_i
+    covers that domain and both tails, with exact knot values and their fp32 neighbours sprinkled in."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    n = G + 2 * p + 1
+    tau = np.zeros((d, n), dtype=np.float32)
+    x = np.zeros((B, d), dtype=np.float32)
+    for i in range(d):
+        lo = float(rng.uniform(-3.0, -0.5))
+        hi = lo + float(rng.uniform(0.5, 4.0))
+        tau[i] = uniform_ext_knots(lo, hi, G, p) if i % 2 == 0 else nonuniform_ext_knots(rng, lo, hi, G, p)
+        assert np.all(np.diff(tau[i]) > 0)
+        span = hi - lo
+        col = rng.uniform(lo - oob_frac * span, hi + oob_frac * span, size=B).astype(np.float32)
+        n_special = max(1, B // 16)
+        idx = rng.integers(0, B, size=n_special)
+        vals = tau[i, p:p + G + 1][rng.integers(0, G + 1, size=n_special)]
+        nudge = rng.integers(-1, 2, size=n_special)
+        col[idx] = np.where(nudge < 0, np.nextafter(vals, np.float32(-np.inf)),
+                            np.where(nudge > 0, np.nextafter(vals, np.float32(np.inf)), vals)).astype(np.float32)
+        x[:, i] = col
+    coef = rng.normal(0.0, 1.0, size=(d, m, G + p)).astype(np.float32)
+    layer = LayerSpec(d, m, G, p, tau, coef, L, scheme, boundary, oob, per_input=True)
+    if with_base:
+        layer.edge_scales = draw_edge_scales(rng, d, m)
+    return Workload(f"perinput_{d}x{m}_G{G}_L{L}_s{scheme}_b{boundary}_o{oob}_seed{seed}{'_sc' if with_base else ''}", [layer], x)

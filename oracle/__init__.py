@@ -50,11 +50,11 @@ def lib():
         L.lko_sample_x.restype = C.c_double
         L.lko_quantize_segment.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
         L.lko_quantize_segment.restype = None
-        L.lko_compile.argtypes = [C.c_int] * 4 + [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int] + [C.c_void_p] * 5 + [C.c_int]
+        L.lko_compile.argtypes = [C.c_int] * 4 + [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int] + [C.c_void_p] * 5 + [C.c_int]
         L.lko_compile.restype = C.c_int
-        L.lko_lut_forward.argtypes = ([C.c_int] * 7 + [C.c_void_p] * 8 + [C.c_long] + [C.c_void_p] * 8 + [C.c_int])
+        L.lko_lut_forward.argtypes = ([C.c_int] * 7 + [C.c_void_p, C.c_int] + [C.c_void_p] * 7 + [C.c_long] + [C.c_void_p] * 8 + [C.c_int])
         L.lko_lut_forward.restype = C.c_int
-        L.lko_bspline_forward.argtypes = [C.c_int] * 4 + [C.c_void_p] * 5 + [C.c_int, C.c_int, C.c_int, C.c_void_p,
+        L.lko_bspline_forward.argtypes = [C.c_int] * 4 + [C.c_void_p, C.c_int] + [C.c_void_p] * 4 + [C.c_int, C.c_int, C.c_int, C.c_void_p,
                                                                            C.c_long, C.c_void_p, C.c_void_p, C.c_int]
         L.lko_silu.argtypes = [C.c_float]
         L.lko_silu.restype = C.c_float
@@ -118,20 +118,22 @@ def round_to_fp16(x: float) -> float:
     return float(lib().lko_round_to_fp16(float(np.float32(x))))
 
 
-def compile_layer(d, m, G, p, ext_knots, coef, L, scheme, want_v=False, nthreads=None, param_fp16=False, extended=False):
+def compile_layer(d, m, G, p, ext_knots, coef, L, scheme, want_v=False, nthreads=None, param_fp16=False, extended=False,
+                  per_input=False):
     """Artifact arrays of Sec. 4.6: knots [K+1], q [E,K,L] (e=i*m+j), scale [E,K], y_min [E,K].
     param_fp16: scale and y_min are stored rounded to binary16 (held here as fp32 arrays of those values).
-    extended: the LUT covers every interval of the extended knot vector, K = G + 2p (else the domain grid, K = G)."""
+    extended: the LUT covers every interval of the extended knot vector, K = G + 2p (else the domain grid, K = G).
+    per_input: ext_knots is [d, G+2p+1], one knot vector per input dimension, and knots comes back as [d, K+1]."""
     tau = _f32(ext_knots)
     coef = _f32(coef)
-    assert tau.size == G + 2 * p + 1 and coef.size == d * m * (G + p)
+    assert tau.size == (d if per_input else 1) * (G + 2 * p + 1) and coef.size == d * m * (G + p)
     E, K = d * m, (G + 2 * p if extended else G)
     q = np.zeros((E, K, L), dtype=np.int8 if scheme == SYM_INT8 else np.uint8)
     scale = np.zeros((E, K), dtype=np.float32)
     y_min = np.zeros((E, K), dtype=np.float32)
-    knots = np.zeros(K + 1, dtype=np.float32)
+    knots = np.zeros((d, K + 1) if per_input else K + 1, dtype=np.float32)
     v = np.zeros((E, K, L), dtype=np.float32) if want_v else None
-    rc = lib().lko_compile(d, m, G, p, _p(tau), _p(coef), L, scheme, int(bool(extended)), _p(q), _p(scale), _p(y_min), _p(knots), _p(v),
+    rc = lib().lko_compile(d, m, G, p, _p(tau), _p(coef), L, scheme, int(bool(extended)), int(bool(per_input)), _p(q), _p(scale), _p(y_min), _p(knots), _p(v),
                            nthreads or default_threads())
     if rc != 0:
         raise ValueError(f"lko_compile failed: {rc}")
@@ -140,7 +142,7 @@ def compile_layer(d, m, G, p, ext_knots, coef, L, scheme, want_v=False, nthreads
         if lost:
             raise ValueError(f"{lost} dequantisation parameters do not fit binary16")
     return SimpleNamespace(d=d, m=m, K=K, L=L, scheme=scheme, knots=knots, q=q, scale=scale, y_min=y_min, v=v,
-                           param_fp16=bool(param_fp16))
+                           param_fp16=bool(param_fp16), per_input=bool(per_input))
 
 
 def _edge_scalars(edge_scalars, E):
@@ -176,7 +178,7 @@ def lut_forward(art, boundary, oob, x, trace=False, codes=False, nthreads=None, 
     stats = np.zeros(2, dtype=np.uint64)
     sb, ss, so = _edge_scalars(edge_scalars, d * m)
     rc = lib().lko_lut_forward(d, m, art.K, art.L, art.scheme, boundary, oob,
-                               _p(art.knots), _p(art.q), _p(art.scale), _p(art.y_min), _p(sb), _p(ss), _p(so), _p(x), B,
+                               _p(art.knots), int(getattr(art, "per_input", False)), _p(art.q), _p(art.scale), _p(art.y_min), _p(sb), _p(ss), _p(so), _p(x), B,
                                _p(y), _p(A), _p(k), _p(l0), _p(inn), _p(w), _p(q01), _p(stats),
                                nthreads or default_threads())
     if rc != 0:
@@ -185,15 +187,17 @@ def lut_forward(art, boundary, oob, x, trace=False, codes=False, nthreads=None, 
                            oob_count=int(stats[0]), oob_any_rows=int(stats[1]))
 
 
-def bspline_forward(d, m, G, p, ext_knots, coef, boundary, oob, x, nthreads=None, edge_scalars=None, extended=False):
+def bspline_forward(d, m, G, p, ext_knots, coef, boundary, oob, x, nthreads=None, edge_scalars=None, extended=False,
+                    per_input=False):
     tau = _f32(ext_knots)
+    assert tau.size == (d if per_input else 1) * (G + 2 * p + 1)
     coef = _f32(coef)
     x = _f32(x)
     B = x.shape[0]
     y = np.zeros((B, m), dtype=np.float32)
     A = np.zeros((B, m), dtype=np.float64)
     sb, ss, so = _edge_scalars(edge_scalars, d * m)
-    rc = lib().lko_bspline_forward(d, m, G, p, _p(tau), _p(coef), _p(sb), _p(ss), _p(so), boundary, oob, int(bool(extended)), _p(x), B, _p(y), _p(A),
+    rc = lib().lko_bspline_forward(d, m, G, p, _p(tau), int(bool(per_input)), _p(coef), _p(sb), _p(ss), _p(so), boundary, oob, int(bool(extended)), _p(x), B, _p(y), _p(A),
                                    nthreads or default_threads())
     if rc != 0:
         raise ValueError(f"lko_bspline_forward failed: {rc}")
@@ -207,12 +211,12 @@ def artifact_bytes(E: int, K: int, L: int, param_bytes_per_segment: int) -> int:
 def error_stats(y, y_ref, x, t0, tK, boundary):
     """OOB evaluation protocol of Sec. 5.6 written out: a sample (row) is in-range when every input satisfies the
     domain predicate In(x) of Sec. 5.2 (half_open: t0 <= x < tK, closed: t0 <= x <= tK; NaN is outside), else it is
-    in the OOB-only subset.  Per subset: number of rows, sum and maximum of |y - y_ref| over the rows' outputs in
+    in the OOB-only subset.  t0 and tK are scalars, or [d] arrays when every input has its own domain.  Per subset: number of rows, sum and maximum of |y - y_ref| over the rows' outputs in
     fp64, MAE = sum / (number of non-NaN differences); differences that are NaN are counted and left out."""
     x = _f32(x)
     y = np.asarray(y, dtype=np.float32).astype(np.float64)
     y_ref = np.asarray(y_ref, dtype=np.float32).astype(np.float64)
-    t0, tK = np.float32(t0), np.float32(tK)
+    t0, tK = np.asarray(t0, dtype=np.float32), np.asarray(tK, dtype=np.float32)
     inside = (x >= t0) & ((x <= tK) if boundary == CLOSED else (x < tK))
     row_in = inside.all(axis=1)
     err = np.abs(y - y_ref)

@@ -131,33 +131,43 @@ void lko_quantize_segment(const float *v, int L, int scheme, void *q, float *alp
  * Compile one dense layer into the artifact arrays of Sec. 4.6:
  *   knots[K+1], q[E][K][L] (e = i*m + j), scale[E][K], y_min[E][K];  v_out (nullable) gets the
  *   unquantised fp32 samples v_{e,k,l}.
- * The basis values at the K*L sampling positions depend only on the shared knot vector, so they
- * are evaluated once and reused by every edge; each edge value is still the sum of Eq. 3.
+ * The basis values at the K*L sampling positions depend only on the knot vector, so they are
+ * evaluated once per knot vector and reused by every edge on it; each edge value is still the sum of Eq. 3.
+ * per_input = 0: one knot vector for the layer (Sec. 4.6), tau_f[n], knots[K+1].
+ * per_input = 1: one knot vector per input dimension (the "knot grid shared per input dimension" of Sec. 6.2; all
+ *   edges leaving input i share it), tau_f[d][n], knots[d][K+1]; everything else is unchanged.
  * ---------------------------------------------------------------------------------------- */
 int lko_compile(int d, int m, int G, int p, const float *tau_f, const float *coef, int L, int scheme, int extended,
-                void *q, float *scale, float *y_min, float *knots, float *v_out, int nthreads)
+                int per_input, void *q, float *scale, float *y_min, float *knots, float *v_out, int nthreads)
 {
     if (d < 1 || m < 1 || G < 1 || p < 0 || L < 2) return -1;
     int n = G + 2 * p + 1, R = G + p;
     int K = extended ? n - 1 : G;                        /* LUT segments: every extended interval, or the domain grid */
-    for (int r = 0; r + 1 < n; ++r) if (!(tau_f[r] < tau_f[r + 1])) return -2;
-    for (int k = 0; k <= K; ++k) knots[k] = extended ? tau_f[k] : tau_f[p + k];
+    int vectors = per_input ? d : 1;                     /* number of distinct knot vectors */
+    for (int h = 0; h < vectors; ++h)
+        for (int r = 0; r + 1 < n; ++r) if (!(tau_f[(size_t)h * n + r] < tau_f[(size_t)h * n + r + 1])) return -2;
     double *tau = (double *)malloc(sizeof(double) * n);
-    double *Bs = (double *)malloc(sizeof(double) * (size_t)K * L * n);
+    double *Bs = (double *)malloc(sizeof(double) * (size_t)vectors * K * L * n);
     if (!tau || !Bs) { free(tau); free(Bs); return -3; }
-    for (int r = 0; r < n; ++r) tau[r] = (double)tau_f[r];
-    for (int k = 0; k < K; ++k)
-        for (int l = 0; l < L; ++l)
-            lko_bspline_basis(tau, n, p, lko_sample_x(knots, L, k, l), Bs + ((size_t)k * L + l) * n);
+    for (int h = 0; h < vectors; ++h) {
+        const float *th = tau_f + (size_t)h * n;
+        float *Th = knots + (size_t)h * (K + 1);
+        for (int k = 0; k <= K; ++k) Th[k] = extended ? th[k] : th[p + k];
+        for (int r = 0; r < n; ++r) tau[r] = (double)th[r];
+        for (int k = 0; k < K; ++k)
+            for (int l = 0; l < L; ++l)
+                lko_bspline_basis(tau, n, p, lko_sample_x(Th, L, k, l), Bs + (((size_t)h * K + k) * L + l) * n);
+    }
     long E = (long)d * m;
     (void)nthreads;
 #pragma omp parallel for num_threads(nthreads > 0 ? nthreads : 1) schedule(static)
     for (long e = 0; e < E; ++e) {
         float v[L];
         const float *c = coef + (size_t)e * R;
+        const double *Bh = Bs + (per_input ? (size_t)(e / m) : 0) * K * L * n;   /* edge e leaves input i = e / m */
         for (int k = 0; k < K; ++k) {
             for (int l = 0; l < L; ++l) {
-                const double *N = Bs + ((size_t)k * L + l) * n;
+                const double *N = Bh + ((size_t)k * L + l) * n;
                 double s = 0.0;
                 for (int r = 0; r < R; ++r) s += (double)c[r] * N[r];
                 v[l] = (float)s;
@@ -237,6 +247,7 @@ float lko_edge_value(const void *q, int scheme, size_t seg_base, int l0, int l1,
  * Optional outputs (nullable): A[B][m] = sum_i |phi_ij| (fp64, the tolerance denominator),
  *   k_out/l0_out/in_out/w_out [B][d], q01_out[B][d][m][2] (the two gathered codes per edge),
  *   stats[2] = { number of (row,input) pairs out of domain, number of rows with any such input }.
+ * per_input: knots is [d][K+1], input i is located on (and its domain is that of) row i; else knots is [K+1].
  * ---------------------------------------------------------------------------------------- */
 /* b(x) = SiLU(x) = x / (1 + exp(-x)) (Sec. 3.1, the fixed base nonlinearity), fp64, rounded once to fp32. */
 float lko_silu(float x)
@@ -258,7 +269,7 @@ float lko_edge_compose(float s_base, float s_spline, float s_out, float b, float
 }
 
 int lko_lut_forward(int d, int m, int K, int L, int scheme, int boundary, int oob,
-                    const float *knots, const void *q, const float *scale, const float *y_min,
+                    const float *knots, int per_input, const void *q, const float *scale, const float *y_min,
                     const float *edge_base, const float *edge_spline, const float *edge_out, /* [E] or all NULL */
                     const float *x, long B, float *y, double *A,
                     int32_t *k_out, int32_t *l0_out, uint8_t *in_out, float *w_out, int16_t *q01_out,
@@ -274,7 +285,7 @@ int lko_lut_forward(int d, int m, int K, int L, int scheme, int boundary, int oo
         int any = 0;
         for (int i = 0; i < d; ++i) {
             lko_index ix;
-            lko_locate(knots, K, L, boundary, x[(size_t)b * d + i], &ix);
+            lko_locate(knots + (per_input ? (size_t)i * (K + 1) : 0), K, L, boundary, x[(size_t)b * d + i], &ix);
             const float silu_x = edge_out ? lko_silu(x[(size_t)b * d + i]) : 0.0f;   /* base branch at the raw x */
             if (!ix.in) { ++oob_count; any = 1; }
             if (k_out) k_out[(size_t)b * d + i] = ix.k;
@@ -313,18 +324,22 @@ int lko_lut_forward(int d, int m, int K, int L, int scheme, int boundary, int oo
  * B-spline layer forward (the same-backend baseline of Sec. 3.3 / 6.4): the exact spline of
  * Eq. 3 in fp64 at the safely clipped input x', masked by the same oob_policy, summed over i.
  * A[B][m] (nullable) = sum_i sum_r |c_r| B_{r,p}(x'_i) over unmasked inputs.
+ * per_input: tau_f is [d][n], the splines leaving input i live on row i; else tau_f is [n].
  * ---------------------------------------------------------------------------------------- */
-int lko_bspline_forward(int d, int m, int G, int p, const float *tau_f, const float *coef,
+int lko_bspline_forward(int d, int m, int G, int p, const float *tau_f, int per_input, const float *coef,
                         const float *edge_base, const float *edge_spline, const float *edge_out, /* [E] or all NULL */
                         int boundary, int oob, int extended, const float *x, long B, float *y, double *A, int nthreads)
 {
     if (d < 1 || m < 1 || G < 1 || p < 0 || B < 0) return -1;
     int n = G + 2 * p + 1, R = G + p;
     int K = extended ? n - 1 : G;                        /* the domain is the LUT's: all extended knots, or the grid */
-    double tau[n];
-    float T[K + 1];
-    for (int r = 0; r < n; ++r) tau[r] = (double)tau_f[r];
-    for (int k = 0; k <= K; ++k) T[k] = extended ? tau_f[k] : tau_f[p + k];
+    int vectors = per_input ? d : 1;
+    double tau_all[vectors][n];
+    float T_all[vectors][K + 1];
+    for (int h = 0; h < vectors; ++h) {
+        for (int r = 0; r < n; ++r) tau_all[h][r] = (double)tau_f[(size_t)h * n + r];
+        for (int k = 0; k <= K; ++k) T_all[h][k] = extended ? tau_f[(size_t)h * n + k] : tau_f[(size_t)h * n + p + k];
+    }
     (void)nthreads;
 #pragma omp parallel for num_threads(nthreads > 0 ? nthreads : 1) schedule(static)
     for (long b = 0; b < B; ++b) {
@@ -332,7 +347,8 @@ int lko_bspline_forward(int d, int m, int G, int p, const float *tau_f, const fl
         for (int j = 0; j < m; ++j) { acc[j] = 0.0; absacc[j] = 0.0; }
         for (int i = 0; i < d; ++i) {
             lko_index ix;
-            lko_locate(T, K, 2, boundary, x[(size_t)b * d + i], &ix);
+            const double *tau = tau_all[per_input ? i : 0];
+            lko_locate(T_all[per_input ? i : 0], K, 2, boundary, x[(size_t)b * d + i], &ix);
             lko_bspline_basis(tau, n, p, (double)ix.xc, N);
             int masked = (oob == LKO_ZERO_SPLINE && !ix.in);
             double bx = 0.0;

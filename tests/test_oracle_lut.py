@@ -668,3 +668,106 @@ def test_table9_segment_count_is_the_extended_reading():
         assert int(K) == art.K and int(L) == art.L
         per_edge = art.q[0].nbytes + art.scale[0].size * 2 + art.y_min[0].size * 2      # float16 scale and y_min
         assert int(E) * per_edge + art.knots.nbytes == int(nbytes)
+
+
+# ---- one knot vector per input dimension (Sec. 6.2 "knot grid shared per input dimension") ----
+
+from lutkan_inputs import per_input_layer  # noqa: E402
+
+
+def test_per_input_knots_equal_rows_are_the_shared_layer():
+    """d copies of one knot vector must give the shared-vector layer bit for bit (artifact, outputs, trace)."""
+    w = random_layer(81, 4, 3, 6, 16, ASYM_UINT8, HALF_OPEN, ZERO_SPLINE, 200, uniform=False, with_base=True)
+    s = w.layers[0]
+    tiled = np.tile(s.ext_knots, (s.d, 1))
+    one = oracle.compile_layer(s.d, s.m, s.G, P, s.ext_knots, s.coef, s.L, s.scheme)
+    per = oracle.compile_layer(s.d, s.m, s.G, P, tiled, s.coef, s.L, s.scheme, per_input=True)
+    assert per.knots.shape == (s.d, s.G + 1) and all(np.array_equal(per.knots[i], one.knots) for i in range(s.d))
+    assert np.array_equal(per.q, one.q) and np.array_equal(per.scale, one.scale) and np.array_equal(per.y_min, one.y_min)
+    a = oracle.lut_forward(one, s.boundary, s.oob, w.x, trace=True, edge_scalars=s.edge_scales)
+    b = oracle.lut_forward(per, s.boundary, s.oob, w.x, trace=True, edge_scalars=s.edge_scales)
+    for f in ("y", "A", "k", "l0", "inside", "w"):
+        np.testing.assert_array_equal(getattr(a, f), getattr(b, f), err_msg=f)
+    assert (a.oob_count, a.oob_any_rows) == (b.oob_count, b.oob_any_rows)
+    ya = oracle.bspline_forward(s.d, s.m, s.G, P, s.ext_knots, s.coef, s.boundary, s.oob, w.x, edge_scalars=s.edge_scales)
+    yb = oracle.bspline_forward(s.d, s.m, s.G, P, tiled, s.coef, s.boundary, s.oob, w.x, edge_scalars=s.edge_scales, per_input=True)
+    np.testing.assert_array_equal(ya.y, yb.y)
+
+
+@pytest.mark.parametrize("scheme,boundary,oob", [(SYM_INT8, CLOSED, CLIP_X), (ASYM_UINT8, HALF_OPEN, ZERO_SPLINE)])
+def test_per_input_knots_layer_is_the_sum_of_its_single_input_layers(scheme, boundary, oob):
+    """Each input's edges form a shared-vector layer of their own (d = 1) on that input's knots: artifact rows, trace
+    columns and counters must be theirs, and the outputs the fp64 sum of theirs."""
+    w = per_input_layer(82, 5, 3, 6, 16, scheme, boundary, oob, 300)
+    s = w.layers[0]
+    per = oracle.compile_layer(s.d, s.m, s.G, P, s.ext_knots, s.coef, s.L, scheme, per_input=True)
+    full = oracle.lut_forward(per, boundary, oob, w.x, trace=True)
+    spl = oracle.bspline_forward(s.d, s.m, s.G, P, s.ext_knots, s.coef, boundary, oob, w.x, per_input=True)
+    want, want_spl, oob_count = np.zeros((300, s.m)), np.zeros((300, s.m)), 0
+    any_oob = np.zeros(300, dtype=bool)
+    for i in range(s.d):
+        one = oracle.compile_layer(1, s.m, s.G, P, s.ext_knots[i], s.coef[i], s.L, scheme)
+        rows = slice(i * s.m, (i + 1) * s.m)
+        assert np.array_equal(per.knots[i], one.knots) and np.array_equal(per.q[rows], one.q)
+        assert np.array_equal(per.scale[rows], one.scale) and np.array_equal(per.y_min[rows], one.y_min)
+        r = oracle.lut_forward(one, boundary, oob, w.x[:, i:i + 1], trace=True)
+        for f in ("k", "l0", "inside", "w"):
+            np.testing.assert_array_equal(getattr(full, f)[:, i], getattr(r, f)[:, 0], err_msg=f"{f} of input {i}")
+        # numpy's searchsorted on this input's own knots (Eq. 14) and its own domain (Sec. 5.2)
+        T = per.knots[i]
+        xc = np.clip(w.x[:, i], T[0], T[-1] if boundary == CLOSED else np.nextafter(T[-1], np.float32(-np.inf)))
+        np.testing.assert_array_equal(full.k[:, i], np.clip(np.searchsorted(T, xc, side="right") - 1, 0, s.G - 1))
+        inside = (w.x[:, i] >= T[0]) & ((w.x[:, i] <= T[-1]) if boundary == CLOSED else (w.x[:, i] < T[-1]))
+        np.testing.assert_array_equal(full.inside[:, i], inside.astype(np.uint8))
+        oob_count += int((~inside).sum())
+        any_oob |= ~inside
+        want += r.y.astype(np.float64)     # a single-input layer's fp32 output is its one edge value exactly
+        want_spl += oracle.bspline_forward(1, s.m, s.G, P, s.ext_knots[i], s.coef[i], boundary, oob, w.x[:, i:i + 1]).y
+    assert (full.oob_count, full.oob_any_rows) == (oob_count, int(any_oob.sum()))
+    np.testing.assert_array_equal(full.y, want.astype(np.float32))
+    np.testing.assert_allclose(spl.y, want_spl, rtol=0, atol=1e-5)
+
+
+def test_per_input_knots_domains_decide_the_mask_closed_form():
+    """All coefficients 1: every spline is 1 on its domain (partition of unity), so with zero_spline the output
+    counts the inputs that lie in THEIR OWN domain; mixing up the vectors changes the count."""
+    G, L, d, m = 4, 8, 3, 2
+    tau = np.stack([uniform_ext_knots(-1, 1, G), uniform_ext_knots(2, 3, G), uniform_ext_knots(-5, -4, G)])
+    coef = np.ones((d, m, G + P), dtype=np.float32)
+    x = np.array([[0.0, 2.5, -4.5],      # all three inside their own domain
+                  [0.0, 0.0, 0.0],       # only input 0
+                  [2.5, 2.5, 2.5],       # only input 1
+                  [-4.5, -4.5, 2.5],     # none
+                  [1.0, 3.0, -4.0]],     # the right ends: inside when closed, outside when half-open
+                 dtype=np.float32)
+    per = oracle.compile_layer(d, m, G, P, tau, coef, L, ASYM_UINT8, per_input=True)
+    assert np.all(per.q == 0) and np.all(per.y_min == 1.0)           # a constant segment: alpha = 0, y_min = the value
+    yc = oracle.lut_forward(per, CLOSED, ZERO_SPLINE, x).y
+    yh = oracle.lut_forward(per, HALF_OPEN, ZERO_SPLINE, x).y
+    np.testing.assert_array_equal(yc[:, 0], [3, 1, 1, 0, 3])
+    np.testing.assert_array_equal(yh[:, 0], [3, 1, 1, 0, 0])
+    np.testing.assert_array_equal(yc[:, 1], yc[:, 0])
+    bs = oracle.bspline_forward(d, m, G, P, tau, coef, HALF_OPEN, ZERO_SPLINE, x, per_input=True).y
+    np.testing.assert_allclose(bs[:, 0], [3, 1, 1, 0, 0], atol=1e-6)
+    # clip_x: every input saturates at its own domain end, where its spline is still 1
+    np.testing.assert_allclose(oracle.bspline_forward(d, m, G, P, tau, coef, CLOSED, CLIP_X, x, per_input=True).y, 3.0, atol=1e-6)
+
+
+def test_per_input_knots_linear_functions_closed_form():
+    """Greville coefficients c_r = mean of the r-th knot triple reproduce f(x) = x on every knot vector; on per-input
+    knots the exact layer output is sum_i clip(x_i) and the LUT tracks it to O(range/L) + quantisation."""
+    G, L, d = 6, 128, 4
+    w = per_input_layer(83, d, 1, G, L, ASYM_UINT8, CLOSED, CLIP_X, 400)
+    s = w.layers[0]
+    coef = np.zeros((d, 1, G + P), dtype=np.float32)
+    for i in range(d):
+        t = s.ext_knots[i].astype(np.float64)
+        coef[i, 0] = [(t[r + 1] + t[r + 2] + t[r + 3]) / 3.0 for r in range(G + P)]
+    lo, hi = s.ext_knots[:, P], s.ext_knots[:, P + G]
+    want = np.clip(w.x, lo, hi).astype(np.float64).sum(axis=1)
+    bs = oracle.bspline_forward(d, 1, G, P, s.ext_knots, coef, CLOSED, CLIP_X, w.x, per_input=True).y[:, 0]
+    np.testing.assert_allclose(bs, want, rtol=0, atol=5e-6)
+    per = oracle.compile_layer(d, 1, G, P, s.ext_knots, coef, L, ASYM_UINT8, per_input=True)
+    lut = oracle.lut_forward(per, CLOSED, CLIP_X, w.x).y[:, 0]
+    widths = (hi - lo).astype(np.float64) / G
+    assert np.abs(lut - want).max() <= float((widths / L + widths / 255.0).sum()) * 1.01

@@ -36,15 +36,20 @@ MUTATIONS = {
     "fp16_params_no_subnormals": ("if (lead < -14) lead = -14;", "if (lead < -24) lead = -24;"),
     "fp16_params_overflow_late": ("if (a >= 65520.0) return", "if (a > 65535.0) return"),
     "extended_lut_drops_last_interval": ("int K = extended ? n - 1 : G;                        /* LUT segments", "int K = extended ? n - 2 : G;                        /* LUT segments"),
-    "extended_layer_keeps_inner_domain": ("for (int k = 0; k <= K; ++k) T[k] = extended ? tau_f[k] : tau_f[p + k];", "for (int k = 0; k <= K; ++k) T[k] = extended ? tau_f[k < p ? p : (k > p + G ? p + G : k)] : tau_f[p + k];"),
+    "extended_layer_keeps_inner_domain": ("T_all[h][k] = extended ? tau_f[(size_t)h * n + k] :", "T_all[h][k] = extended ? tau_f[(size_t)h * n + (k < p ? p : (k > p + G ? p + G : k))] :"),
     "layer_sum_skips_first_input": ("for (int i = 0; i < d; ++i) {\n            lko_index ix;\n            lko_locate(knots", "for (int i = (d > 1); i < d; ++i) {\n            lko_index ix;\n            lko_locate(knots"),
+    "per_input_forward_uses_first_vector": ("lko_locate(knots + (per_input ? (size_t)i * (K + 1) : 0),", "lko_locate(knots + (per_input ? (size_t)0 * (K + 1) : 0),"),
+    "per_input_compile_uses_first_vector": ("const double *Bh = Bs + (per_input ? (size_t)(e / m) : 0) * K * L * n;", "const double *Bh = Bs;"),
+    "per_input_compile_indexes_by_output": ("const double *Bh = Bs + (per_input ? (size_t)(e / m) : 0) * K * L * n;", "const double *Bh = Bs + (per_input ? (size_t)((e % m) % d) : 0) * K * L * n;"),
+    "per_input_bspline_uses_first_vector": ("const double *tau = tau_all[per_input ? i : 0];", "const double *tau = tau_all[0];"),
+    "per_input_bspline_domain_of_first_vector": ("lko_locate(T_all[per_input ? i : 0], K, 2,", "lko_locate(T_all[0], K, 2,"),
 }
 
 
 def test_every_mutation_text_is_present_once():
     src = open(SRC).read()
     for name, (old, _) in MUTATIONS.items():
-        assert src.count(old) == 1, name
+        assert src.count(old) == 1, name        # (two mutations may share one site)
 
 
 @pytest.mark.parametrize("name", sorted(MUTATIONS))
