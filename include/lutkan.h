@@ -68,7 +68,8 @@ typedef struct {
   int32_t d, m;              /* inputs, outputs */
   int32_t G;                 /* grid intervals; the LUT has K = G segments on the domain grid (Sec. 4.2) */
   int32_t degree;            /* spline degree p; must be 3 */
-  const float *ext_knots;    /* [G + 2*degree + 1] strictly increasing; domain = [ext_knots[p], ext_knots[p+G]] */
+  const float *ext_knots;    /* [G + 2*degree + 1] strictly increasing; domain = [ext_knots[p], ext_knots[p+G]];
+                                [d][G + 2*degree + 1] with knots_per_input */
   const float *coef;         /* [d][m][G + degree] B-spline coefficients c_r of Eq. 3 */
   int32_t L;                 /* samples per segment, >= 2 (Eq. 7) */
   int32_t scheme;            /* lutkan_scheme */
@@ -86,22 +87,26 @@ typedef struct {
                                 coefficients; on the outer p intervals of each side fewer than p+1 basis functions
                                 exist, and at the last knot itself all of them are 0 (half-open indicator of Eq. 4).
                                 The B-spline layer of the artifact uses the same domain.  Needs G + 2p <= LUTKAN_MAX_K. */
+  int32_t knots_per_input;   /* 0: one knot vector for the layer (Sec. 4.6).  1: one per input dimension (the grid
+                                "shared per input dimension" of Sec. 6.2, e.g. after a per-feature grid update): all
+                                edges leaving input i are sampled, located and masked on row i of ext_knots. */
 } lutkan_layer_desc;
 
 typedef struct lutkan_artifact lutkan_artifact;     /* opaque, host memory */
 
 typedef struct {
-  int32_t d, m, K, L, G, degree, scheme, boundary, oob, value_repr, param_dtype, knot_span;
+  int32_t d, m, K, L, G, degree, scheme, boundary, oob, value_repr, param_dtype, knot_span, knots_per_input;
   int32_t jt;                /* column-tile width of the device tables (a power of two <= 128, or 128) */
   int32_t n_tiles;           /* ceil(m / jt) */
   int32_t blob_bytes;        /* bytes of one (tile, input) slice of the LUT device table */
   int32_t coef_blob_bytes;   /* bytes of one (tile, input) slice of the B-spline device table */
-  float t0, tK, tK_star;     /* domain ends and the safe upper clip value of Eq. 13 */
+  float t0, tK, tK_star;     /* domain ends and the safe upper clip value of Eq. 13 (of input 0 with knots_per_input) */
   size_t q_canonical_bytes;  /* d*m*K*L */
   size_t params_canonical_bytes; /* d*m*K*4 (d*m*K*2 with fp16 parameters), for scale and for y_min each */
   size_t table_bytes;        /* whole LUT device table = n_tiles*d*blob_bytes */
   size_t coef_table_bytes;   /* whole B-spline device table = n_tiles*d*coef_blob_bytes */
-  size_t artifact_bytes;     /* Sec. 4.6 arrays: q + scale + y_min + knots (what Sec. 6.6 "LUT artifact bytes" counts) */
+  size_t artifact_bytes;     /* Sec. 4.6 arrays: q + scale + y_min + knots (what Sec. 6.6 "LUT artifact bytes" counts;
+                                knots are 4*(K+1) bytes, times d with knots_per_input) */
 } lutkan_info;
 
 /* Samples every edge on every segment in fp64 (Eq. 3-5, Eq. 7), quantises in fp32 (Eq. 11-12) and lays the
@@ -113,12 +118,13 @@ int lutkan_artifact_info(const lutkan_artifact *a, lutkan_info *out);
 
 /* The stored arrays of one layer artifact (Sec. 4.6 "Stored Arrays and Shapes" and the manifest fields of its
  * "Serialization Format"), all host pointers, edge e = i*m + j:
- *   knots fp32 [K+1] strictly increasing; q_table int8 / uint8 [E][K][L]; scale, y_min fp32 [E][K] (with
+ *   knots fp32 [K+1] strictly increasing ([d][K+1], every row increasing, with knots_per_input); q_table int8 /
+ *   uint8 [E][K][L]; scale, y_min fp32 [E][K] (with
  *   param_dtype = FP16 every value must already be a binary16 value); the three edge_* arrays fp32 [E] with
  *   value_repr = spline_component, else ignored. */
 typedef struct {
   int32_t d, m, K, L;
-  int32_t scheme, boundary, oob, value_repr, param_dtype;
+  int32_t scheme, boundary, oob, value_repr, param_dtype, knots_per_input;
   const float *knots;
   const void *q_table;
   const float *scale, *y_min;
@@ -135,8 +141,8 @@ int lutkan_artifact_from_arrays(const lutkan_artifact_arrays *arrays, lutkan_art
 const void *lutkan_artifact_q(const lutkan_artifact *a);          /* int8 or uint8 [E][K][L] */
 const float *lutkan_artifact_scale(const lutkan_artifact *a);     /* alpha  [E][K] (fp16 parameters: the rounded values, as floats) */
 const float *lutkan_artifact_ymin(const lutkan_artifact *a);      /* y_min  [E][K] (zeros for symmetric) */
-const float *lutkan_artifact_knots(const lutkan_artifact *a);     /* [K+1] */
-const float *lutkan_artifact_ext_knots(const lutkan_artifact *a); /* [G+2p+1] */
+const float *lutkan_artifact_knots(const lutkan_artifact *a);     /* [K+1], or [d][K+1] with knots_per_input */
+const float *lutkan_artifact_ext_knots(const lutkan_artifact *a); /* [G+2p+1], or [d][G+2p+1] */
 const float *lutkan_artifact_edge_base_scale(const lutkan_artifact *a);   /* [E], NULL for value_repr = phi (Sec. 4.6) */
 const float *lutkan_artifact_edge_spline_scale(const lutkan_artifact *a); /* [E] */
 const float *lutkan_artifact_edge_out_scale(const lutkan_artifact *a);    /* [E] */
@@ -167,8 +173,10 @@ typedef struct {
   int32_t d, m, K, L, scheme, boundary, oob, value_repr, param_dtype;
   int32_t jt, n_tiles, blob_bytes;
   int32_t algo;                       /* lutkan_algo; AUTO picks by shape */
-  float knots[LUTKAN_MAX_K + 1];      /* host copy of T, entries 0..K used */
+  float knots[LUTKAN_MAX_K + 1];      /* host copy of T, entries 0..K used (not used with knots_per_input) */
   const void *table;                  /* device, lutkan_info.table_bytes bytes, 16-byte aligned */
+  int32_t knots_per_input;            /* 1: every input is located on its own row of input_knots */
+  const float *input_knots;           /* device fp32 [d][K+1], a verbatim copy of lutkan_artifact_knots; NULL if shared */
 } lutkan_dev_layer;
 
 typedef struct {
@@ -177,9 +185,11 @@ typedef struct {
   int32_t algo;
   float ext_knots[LUTKAN_MAX_K + 7];  /* host copy, entries 0..G+6 used */
   const float *coef_table;            /* device, lutkan_info.coef_table_bytes bytes, 16-byte aligned */
+  int32_t knots_per_input;
+  const float *input_ext_knots;       /* device fp32 [d][G+2p+1], a copy of lutkan_artifact_ext_knots; NULL if shared */
 } bspline_dev_layer;
 
-/* Fills every field of the device structs from an artifact except the device pointer (set to NULL). */
+/* Fills every field of the device structs from an artifact except the device pointers (set to NULL). */
 int lutkan_dev_layer_init(const lutkan_artifact *a, lutkan_dev_layer *out);
 int bspline_dev_layer_init(const lutkan_artifact *a, bspline_dev_layer *out);
 
@@ -242,7 +252,8 @@ int lutkan_model_forward(const lutkan_dev_layer *layers, int32_t n_layers, const
 /* Error statistics of the OOB evaluation protocol (Sec. 5.6 and the accuracy metrics of Sec. 6.5), in one pass on the
  * device: |y - y_ref| over the outputs of the in-range samples (rows whose d inputs all satisfy the domain predicate
  * In(x) of Sec. 5.2 under `boundary` on [t0, tK]) and of the OOB-only samples (rows with at least one input outside;
- * NaN counts as outside).  MAE of a subset = sum_abs / (rows * m - its NaN outputs); OOB_any_frac = rows_oob / B.
+ * NaN counts as outside).  input_domain (device fp32 [d][2], nullable) gives every input its own {t0, tK} instead,
+ * for layers with one knot vector per input.  MAE of a subset = sum_abs / (rows * m - its NaN outputs); OOB_any_frac = rows_oob / B.
  *   y, y_ref   device [B][m] fp32 (e.g. the LUT layer and the B-spline layer on the same x)
  *   x          device [B][d] fp32, the layer input that decides the subset of each row
  *   out        device, 8-byte aligned, overwritten
@@ -256,8 +267,8 @@ typedef struct {
 } lutkan_error_summary;
 size_t lutkan_error_stats_workspace_bytes(int64_t B);
 int lutkan_error_stats(const float *y, const float *y_ref, int64_t B, int32_t m, const float *x, int32_t d,
-                       float t0, float tK, int32_t boundary, lutkan_error_summary *out, void *workspace,
-                       size_t workspace_bytes, void *hip_stream);
+                       float t0, float tK, const float *input_domain, int32_t boundary, lutkan_error_summary *out,
+                       void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Measurement aid, not part of the method: launches one kernel of known work that exercises a single resource, so
  * that a caller who times it (events on hip_stream) learns the rate this machine sustains and can put the layer

@@ -30,18 +30,21 @@ class _LayerDesc(C.Structure):
                 ("ext_knots", C.c_void_p), ("coef", C.c_void_p),
                 ("L", C.c_int32), ("scheme", C.c_int32), ("boundary", C.c_int32), ("oob", C.c_int32),
                 ("value_repr", C.c_int32), ("edge_base_scale", C.c_void_p), ("edge_spline_scale", C.c_void_p),
-                ("edge_out_scale", C.c_void_p), ("param_dtype", C.c_int32), ("knot_span", C.c_int32)]
+                ("edge_out_scale", C.c_void_p), ("param_dtype", C.c_int32), ("knot_span", C.c_int32),
+                ("knots_per_input", C.c_int32)]
 
 
 class _ArtifactArrays(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("d", "m", "K", "L", "scheme", "boundary", "oob", "value_repr", "param_dtype")] + \
+    _fields_ = [(n, C.c_int32) for n in ("d", "m", "K", "L", "scheme", "boundary", "oob", "value_repr", "param_dtype",
+                                         "knots_per_input")] + \
                [(n, C.c_void_p) for n in ("knots", "q_table", "scale", "y_min", "edge_base_scale", "edge_spline_scale",
                                           "edge_out_scale")]
 
 
 class _Info(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("d", "m", "K", "L", "G", "degree", "scheme", "boundary", "oob", "value_repr",
-                                         "param_dtype", "knot_span", "jt", "n_tiles", "blob_bytes", "coef_blob_bytes")] + \
+                                         "param_dtype", "knot_span", "knots_per_input", "jt", "n_tiles", "blob_bytes",
+                                         "coef_blob_bytes")] + \
                [("t0", C.c_float), ("tK", C.c_float), ("tK_star", C.c_float)] + \
                [(n, C.c_size_t) for n in ("q_canonical_bytes", "params_canonical_bytes", "table_bytes",
                                           "coef_table_bytes", "artifact_bytes")]
@@ -50,13 +53,15 @@ class _Info(C.Structure):
 class _DevLayer(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("d", "m", "K", "L", "scheme", "boundary", "oob", "value_repr", "param_dtype",
                                          "jt", "n_tiles", "blob_bytes", "algo")] + \
-               [("knots", C.c_float * (MAX_K + 1)), ("table", C.c_void_p)]
+               [("knots", C.c_float * (MAX_K + 1)), ("table", C.c_void_p), ("knots_per_input", C.c_int32),
+                ("input_knots", C.c_void_p)]
 
 
 class _SplineDevLayer(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("d", "m", "G", "degree", "boundary", "oob", "value_repr", "knot_span", "jt",
                                          "n_tiles", "coef_blob_bytes", "algo")] + \
-               [("ext_knots", C.c_float * (MAX_K + 7)), ("coef_table", C.c_void_p)]
+               [("ext_knots", C.c_float * (MAX_K + 7)), ("coef_table", C.c_void_p), ("knots_per_input", C.c_int32),
+                ("input_ext_knots", C.c_void_p)]
 
 
 EXPORTS = [
@@ -118,7 +123,7 @@ def load_library():
     lib.lutkan_probe_launch.argtypes = [i32, vp, sz, i32, C.POINTER(C.c_double), vp]
     lib.lutkan_error_stats_workspace_bytes.argtypes = [i64]
     lib.lutkan_error_stats_workspace_bytes.restype = sz
-    lib.lutkan_error_stats.argtypes = [vp, vp, i64, i32, vp, i32, C.c_float, C.c_float, i32, vp, vp, sz, vp]
+    lib.lutkan_error_stats.argtypes = [vp, vp, i64, i32, vp, i32, C.c_float, C.c_float, vp, i32, vp, vp, sz, vp]
     _lib = lib
     return lib
 
@@ -173,12 +178,17 @@ class Artifact:
 
     @property
     def knots(self):
-        return self._array("lutkan_artifact_knots", self.info.K + 1, np.float32, (self.info.K + 1,))
+        """[K+1], or [d, K+1] with one knot vector per input."""
+        I = self.info
+        shape = (I.d, I.K + 1) if I.knots_per_input else (I.K + 1,)
+        return self._array("lutkan_artifact_knots", int(np.prod(shape)), np.float32, shape)
 
     @property
     def ext_knots(self):
         """None for an artifact rebuilt from stored arrays (it has no spline side)."""
-        return self._array("lutkan_artifact_ext_knots", self.info.G + 7, np.float32, (self.info.G + 7,)) if self.info.G > 0 else None
+        I = self.info
+        shape = (I.d, I.G + 7) if I.knots_per_input else (I.G + 7,)
+        return self._array("lutkan_artifact_ext_knots", int(np.prod(shape)), np.float32, shape) if I.G > 0 else None
 
     @property
     def table(self):
@@ -214,7 +224,8 @@ class Artifact:
                     "oob_policy": "zero_spline" if I.oob == ZERO_SPLINE else "clip_x",
                     "scheme": "symmetric_int8" if I.scheme == SYM_INT8 else "asymmetric_uint8",
                     "L": int(I.L), "K": int(I.K), "in_features": int(I.d), "out_features": int(I.m),
-                    "param_dtype": "float16" if I.param_dtype == PARAM_FP16 else "float32"}
+                    "param_dtype": "float16" if I.param_dtype == PARAM_FP16 else "float32",
+                    "knots_per_input": bool(I.knots_per_input)}
         arrays = {"knots": self.knots, "q_table": self.q, "scale": self.scale.astype(pdt), "y_min": self.y_min.astype(pdt)}
         if self.edge_scales is not None:
             manifest["base_kind"] = "silu"
@@ -233,15 +244,16 @@ class Artifact:
 
 def lutkan_compile(d: int, m: int, G: int, degree: int, ext_knots, coef, L: int, scheme: int, boundary: int,
                    oob: int, n_threads: int = 0, edge_scales=None, param_dtype: int = PARAM_FP32,
-                   knot_span: int = SPAN_DOMAIN) -> Artifact:
+                   knot_span: int = SPAN_DOMAIN, knots_per_input: bool = False) -> Artifact:
     """Host-only LUT compilation of one dense B-spline KAN layer (Sec. 4.2-4.6).
+    knots_per_input: ext_knots is [d, G + 2*degree + 1], one knot vector per input dimension (Sec. 6.2).
     edge_scales = (s_base, s_spline, s_out), each [d, m], selects value_repr = spline_component (Eq. 2).
     param_dtype = PARAM_FP16 stores scale and y_min as binary16 values (Sec. 4.6).
     knot_span = SPAN_EXTENDED makes every interval of the extended knot vector a LUT segment (K = G + 2*degree)."""
     lib = load_library()
     tau = np.ascontiguousarray(ext_knots, dtype=np.float32)
     cf = np.ascontiguousarray(coef, dtype=np.float32)
-    if tau.size != G + 2 * degree + 1 or cf.size != d * m * (G + degree):
+    if tau.size != (d if knots_per_input else 1) * (G + 2 * degree + 1) or cf.size != d * m * (G + degree):
         raise LutKanError("lutkan_compile: ext_knots / coef have the wrong number of elements")
     keep = [np.ascontiguousarray(a, dtype=np.float32).reshape(-1) for a in edge_scales] if edge_scales is not None else []
     if keep and any(a.size != d * m for a in keep):
@@ -250,14 +262,16 @@ def lutkan_compile(d: int, m: int, G: int, degree: int, ext_knots, coef, L: int,
                       REPR_SPLINE_COMPONENT if keep else REPR_PHI, *[a.ctypes.data for a in keep])
     desc.param_dtype = param_dtype
     desc.knot_span = knot_span
+    desc.knots_per_input = int(bool(knots_per_input))
     out = C.c_void_p()
     _check(lib.lutkan_compile(C.byref(desc), n_threads, C.byref(out)))
     return Artifact(out.value)
 
 
 def lutkan_artifact_from_arrays(d: int, m: int, knots, q_table, scale, y_min, boundary: int, oob: int,
-                                edge_scales=None, param_dtype: int = PARAM_FP32) -> Artifact:
-    """Artifact (with its device table) from stored arrays: q_table int8 (symmetric) or uint8 (asymmetric) [d*m, K, L]."""
+                                edge_scales=None, param_dtype: int = PARAM_FP32, knots_per_input: bool = False) -> Artifact:
+    """Artifact (with its device table) from stored arrays: q_table int8 (symmetric) or uint8 (asymmetric) [d*m, K, L];
+    knots [K+1], or [d, K+1] with knots_per_input."""
     q = np.ascontiguousarray(q_table)
     if q.dtype not in (np.int8, np.uint8) or q.ndim != 3 or q.shape[0] != d * m:
         raise LutKanError("lutkan_artifact_from_arrays: q_table must be int8 or uint8 with shape [d*m, K, L]")
@@ -265,13 +279,14 @@ def lutkan_artifact_from_arrays(d: int, m: int, knots, q_table, scale, y_min, bo
     kn = np.ascontiguousarray(knots, dtype=np.float32).reshape(-1)
     sc = np.ascontiguousarray(scale, dtype=np.float32).reshape(-1)
     ym = np.ascontiguousarray(y_min, dtype=np.float32).reshape(-1)
-    if kn.size != K + 1 or sc.size != d * m * K or ym.size != d * m * K:
+    if kn.size != (d if knots_per_input else 1) * (K + 1) or sc.size != d * m * K or ym.size != d * m * K:
         raise LutKanError("lutkan_artifact_from_arrays: knots / scale / y_min do not match q_table's shape")
     keep = [np.ascontiguousarray(a, dtype=np.float32).reshape(-1) for a in edge_scales] if edge_scales is not None else []
     if keep and any(a.size != d * m for a in keep):
         raise LutKanError("lutkan_artifact_from_arrays: every edge scale array needs d*m elements")
     arr = _ArtifactArrays(d, m, K, L, SYM_INT8 if q.dtype == np.int8 else ASYM_UINT8, boundary, oob,
-                          REPR_SPLINE_COMPONENT if keep else REPR_PHI, param_dtype, kn.ctypes.data, q.ctypes.data,
+                          REPR_SPLINE_COMPONENT if keep else REPR_PHI, param_dtype, int(bool(knots_per_input)),
+                          kn.ctypes.data, q.ctypes.data,
                           sc.ctypes.data, ym.ctypes.data, *[a.ctypes.data for a in keep])
     out = C.c_void_p()
     _check(load_library().lutkan_artifact_from_arrays(C.byref(arr), C.byref(out)))
@@ -300,7 +315,8 @@ def lutkan_artifact_load(path: str) -> Artifact:
                 raise LutKanError("lutkan_artifact_load: only base_kind = silu is supported")
             scales = (z["edge_base_scale"], z["edge_spline_scale"], z["edge_out_scale"])
         return lutkan_artifact_from_arrays(int(man["in_features"]), int(man["out_features"]), z["knots"], q, z["scale"],
-                                           z["y_min"], f["boundary_mode"], f["oob_policy"], scales, f["param_dtype"])
+                                           z["y_min"], f["boundary_mode"], f["oob_policy"], scales, f["param_dtype"],
+                                           bool(man.get("knots_per_input", False)))
 
 
 def _torch():
@@ -322,6 +338,8 @@ class LutLayer:
         self.c.algo = algo
         self.table = _upload(art.table, device)
         self.c.table = self.table.data_ptr()
+        self.input_knots = _upload(art.knots, device) if art.info.knots_per_input else None     # [d, K+1]
+        self.c.input_knots = self.input_knots.data_ptr() if self.input_knots is not None else None
         self.device = self.table.device
         self.d, self.m = self.c.d, self.c.m
 
@@ -333,6 +351,7 @@ class LutLayer:
         if algo is not None:
             other.c.algo = algo
         other.table, other.device, other.d, other.m = self.table, self.device, self.d, self.m
+        other.input_knots = self.input_knots
         return other
 
 
@@ -343,6 +362,8 @@ class BsplineLayer:
         self.c.algo = algo
         self.coef_table = _upload(art.coef_table, device)
         self.c.coef_table = self.coef_table.data_ptr()
+        self.input_ext_knots = _upload(art.ext_knots, device) if art.info.knots_per_input else None   # [d, G+7]
+        self.c.input_ext_knots = self.input_ext_knots.data_ptr() if self.input_ext_knots is not None else None
         self.device = self.coef_table.device
         self.d, self.m = self.c.d, self.c.m
 
@@ -353,6 +374,7 @@ class BsplineLayer:
         if algo is not None:
             other.c.algo = algo
         other.coef_table, other.device, other.d, other.m = self.coef_table, self.device, self.d, self.m
+        other.input_ext_knots = self.input_ext_knots
         return other
 
 
@@ -508,8 +530,9 @@ def lutkan_probe_launch(kind: int, buffer, iters: int) -> float:
     return work.value
 
 
-def lutkan_error_stats(y, y_ref, x, t0: float, tK: float, boundary: int) -> dict:
+def lutkan_error_stats(y, y_ref, x, t0: float, tK: float, boundary: int, input_domain=None) -> dict:
     """|y - y_ref| statistics on the in-range and the OOB-only samples (Sec. 5.6), reduced on the device.
+    input_domain: optional device tensor [d, 2] fp32 of per-input {t0, tK} (layers with one knot vector per input).
     Returns rows_in, rows_oob, nan_outputs, sum / max / mae per subset and oob_any_frac."""
     torch = _torch()
     for t, what in ((y, "y"), (y_ref, "y_ref"), (x, "x")):
@@ -517,10 +540,15 @@ def lutkan_error_stats(y, y_ref, x, t0: float, tK: float, boundary: int) -> dict
     B, m, d = y.shape[0], y.shape[1], x.shape[1]
     if y_ref.shape != y.shape or x.shape[0] != B:
         raise LutKanError("lutkan_error_stats: y, y_ref must be [B,m] and x [B,d]")
+    if input_domain is not None:
+        _require(input_domain, torch.float32, "input_domain")
+        if tuple(input_domain.shape) != (d, 2):
+            raise LutKanError("lutkan_error_stats: input_domain must be [d, 2]")
     lib = load_library()
     out = torch.zeros(7, dtype=torch.float64, device=y.device)            # 3 x uint64 + 4 x double = 56 bytes
     ws = torch.empty(max(16, lib.lutkan_error_stats_workspace_bytes(B)), dtype=torch.uint8, device=y.device)
-    _check(lib.lutkan_error_stats(y.data_ptr(), y_ref.data_ptr(), B, m, x.data_ptr(), d, float(t0), float(tK), boundary,
+    _check(lib.lutkan_error_stats(y.data_ptr(), y_ref.data_ptr(), B, m, x.data_ptr(), d, float(t0), float(tK),
+                                  input_domain.data_ptr() if input_domain is not None else None, boundary,
                                   out.data_ptr(), ws.data_ptr(), ws.numel(), _stream(y.device)))
     raw = out.cpu().numpy()
     rows_in, rows_oob, nans = (int(v) for v in raw[:3].view(np.uint64))

@@ -176,12 +176,13 @@ struct SlicePacker {
 
 // Fills the size and contract fields of an artifact's info once its arrays and tables are in place.
 void fill_info(lutkan_artifact *a, int d, int m, int K, int L, int G, int scheme, int boundary, int oob, int repr,
-               int param_dtype, int jt, int n_tiles, const BlobLayout &lay, int coef_blob) {
+               int param_dtype, int knots_per_input, int jt, int n_tiles, const BlobLayout &lay, int coef_blob) {
   const size_t E = (size_t)d * m;
   lutkan_info &I = a->info;
   std::memset(&I, 0, sizeof(I));
   I.d = d; I.m = m; I.K = K; I.L = L; I.G = G; I.degree = P;
   I.scheme = scheme; I.boundary = boundary; I.oob = oob; I.value_repr = repr; I.param_dtype = param_dtype;
+  I.knots_per_input = knots_per_input;
   I.jt = jt; I.n_tiles = n_tiles; I.blob_bytes = lay.bytes; I.coef_blob_bytes = coef_blob;
   I.t0 = a->knots[0]; I.tK = a->knots[K];
   I.tK_star = (boundary == LUTKAN_CLOSED) ? I.tK : std::nextafterf(I.tK, -INFINITY);  // Eq. 13
@@ -189,7 +190,7 @@ void fill_info(lutkan_artifact *a, int d, int m, int K, int L, int G, int scheme
   I.params_canonical_bytes = E * K * (param_dtype == LUTKAN_PARAM_FP16 ? 2 : 4);
   I.table_bytes = a->table.size();
   I.coef_table_bytes = a->coef_table.size() * 4;
-  I.artifact_bytes = I.q_canonical_bytes + 2 * I.params_canonical_bytes + 4 * (size_t)(K + 1) +
+  I.artifact_bytes = I.q_canonical_bytes + 2 * I.params_canonical_bytes + 4 * (size_t)(K + 1) * (knots_per_input ? d : 1) +
                      (repr == LUTKAN_REPR_SPLINE_COMPONENT ? 12 * E : 0);
 }
 
@@ -214,7 +215,9 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
   if (desc->value_repr != LUTKAN_REPR_PHI && desc->value_repr != LUTKAN_REPR_SPLINE_COMPONENT) return fail(LUTKAN_EINVAL, "lutkan_compile: bad value_repr %d", desc->value_repr);
   if (desc->param_dtype != LUTKAN_PARAM_FP32 && desc->param_dtype != LUTKAN_PARAM_FP16) return fail(LUTKAN_EINVAL, "lutkan_compile: bad param_dtype %d", desc->param_dtype);
   if (desc->knot_span != LUTKAN_SPAN_DOMAIN && desc->knot_span != LUTKAN_SPAN_EXTENDED) return fail(LUTKAN_EINVAL, "lutkan_compile: bad knot_span %d", desc->knot_span);
+  if (desc->knots_per_input != 0 && desc->knots_per_input != 1) return fail(LUTKAN_EINVAL, "lutkan_compile: bad knots_per_input %d", desc->knots_per_input);
   const bool extended = (desc->knot_span == LUTKAN_SPAN_EXTENDED);
+  const bool per_input = (desc->knots_per_input == 1);
   const bool half_params = (desc->param_dtype == LUTKAN_PARAM_FP16);
   const bool with_base = (desc->value_repr == LUTKAN_REPR_SPLINE_COMPONENT);
   if (with_base && (!desc->edge_base_scale || !desc->edge_spline_scale || !desc->edge_out_scale))
@@ -224,10 +227,14 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
   const int K = extended ? G + 2 * P : G;
   if (K > LUTKAN_MAX_K) return fail(LUTKAN_EUNSUPPORTED, "lutkan_compile: K=%d exceeds LUTKAN_MAX_K=%d", K, LUTKAN_MAX_K);
   if ((int64_t)K * L > LUTKAN_MAX_ROWS) return fail(LUTKAN_EUNSUPPORTED, "lutkan_compile: K*L=%lld exceeds %d", (long long)K * L, LUTKAN_MAX_ROWS);
-  for (int r = 0; r < n_knots; ++r)
-    if (!std::isfinite(desc->ext_knots[r])) return fail(LUTKAN_EINVAL, "lutkan_compile: knot %d is not finite", r);
-  for (int r = 0; r + 1 < n_knots; ++r)
-    if (!(desc->ext_knots[r] < desc->ext_knots[r + 1])) return fail(LUTKAN_EINVAL, "lutkan_compile: knots not strictly increasing at %d", r);
+  const int n_vectors = per_input ? d : 1;             // distinct knot vectors
+  for (int h = 0; h < n_vectors; ++h) {
+    const float *tau_h = desc->ext_knots + (size_t)h * n_knots;
+    for (int r = 0; r < n_knots; ++r)
+      if (!std::isfinite(tau_h[r])) return fail(LUTKAN_EINVAL, "lutkan_compile: knot %d of vector %d is not finite", r, h);
+    for (int r = 0; r + 1 < n_knots; ++r)
+      if (!(tau_h[r] < tau_h[r + 1])) return fail(LUTKAN_EINVAL, "lutkan_compile: knots of vector %d not strictly increasing at %d", h, r);
+  }
   const size_t E = (size_t)d * m;
   for (size_t n = 0; n < E * R; ++n)
     if (!std::isfinite(desc->coef[n])) return fail(LUTKAN_EINVAL, "lutkan_compile: coefficient %zu is not finite", n);
@@ -246,8 +253,10 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
   const int coef_rows = coef_slice_rows(R, repr);
   const int coef_blob = coef_rows * jt * 4;
   try {
-    a->ext_knots.assign(desc->ext_knots, desc->ext_knots + n_knots);
-    a->knots.assign(desc->ext_knots + first_knot, desc->ext_knots + first_knot + K + 1);
+    a->ext_knots.assign(desc->ext_knots, desc->ext_knots + (size_t)n_vectors * n_knots);
+    a->knots.resize((size_t)n_vectors * (K + 1));
+    for (int h = 0; h < n_vectors; ++h)
+      for (int k = 0; k <= K; ++k) a->knots[(size_t)h * (K + 1) + k] = desc->ext_knots[(size_t)h * n_knots + first_knot + k];
     a->q.resize(E * K * L);
     a->scale.resize(E * K);
     a->ymin.resize(E * K);
@@ -263,21 +272,26 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
     return fail(LUTKAN_ENOMEM, "lutkan_compile: out of host memory for %zu edges", E);
   }
 
-  // Basis values at the K*L sampling positions x_{k,l} = t_k + l*(t_{k+1}-t_k)/L (Eq. 7).  The knot vector is
-  // shared by all edges of the layer, so this small table is built once: basis[(k*L+l)*4 + a] multiplies
-  // coefficient c_{mu-3+a} of span mu = first_knot + k (on the domain grid mu-3 = k; outside it some of the four
-  // functions do not exist and their entry is 0).
-  std::vector<double> tau(a->ext_knots.begin(), a->ext_knots.end());
-  std::vector<double> basis((size_t)K * L * 4);
-  for (int k = 0; k < K; ++k) {
-    const double left = (double)a->knots[k];
-    const double step = ((double)a->knots[k + 1] - left) / (double)L;
-    for (int l = 0; l < L; ++l) {
-      double *out = &basis[((size_t)k * L + l) * 4];
-      if (extended) cubic_basis_on_any_span(tau, R, first_knot + k, left + (double)l * step, out);
-      else nonzero_cubic_basis(tau.data(), k + P, left + (double)l * step, out);
+  // Basis values at the K*L sampling positions x_{k,l} = t_k + l*(t_{k+1}-t_k)/L (Eq. 7).  A knot vector is
+  // shared by all edges on it (the whole layer, or the edges leaving one input), so this small table is built once
+  // per vector: basis[(k*L+l)*4 + a] multiplies coefficient c_{mu-3+a} of span mu = first_knot + k (on the domain
+  // grid mu-3 = k; outside it some of the four functions do not exist and their entry is 0).
+  auto basis_table = [&](int h, std::vector<double> &basis) {
+    const std::vector<double> tau(a->ext_knots.begin() + (size_t)h * n_knots, a->ext_knots.begin() + (size_t)(h + 1) * n_knots);
+    const float *T = a->knots.data() + (size_t)h * (K + 1);
+    basis.resize((size_t)K * L * 4);
+    for (int k = 0; k < K; ++k) {
+      const double left = (double)T[k];
+      const double step = ((double)T[k + 1] - left) / (double)L;
+      for (int l = 0; l < L; ++l) {
+        double *out = &basis[((size_t)k * L + l) * 4];
+        if (extended) cubic_basis_on_any_span(tau, R, first_knot + k, left + (double)l * step, out);
+        else nonzero_cubic_basis(tau.data(), k + P, left + (double)l * step, out);
+      }
     }
-  }
+  };
+  std::vector<double> shared_basis;
+  if (!per_input) basis_table(0, shared_basis);
 
   int nt = n_threads > 0 ? n_threads : (int)std::thread::hardware_concurrency();
   nt = std::max(1, std::min(nt, 64));
@@ -286,7 +300,10 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
   const SlicePacker packer{lay, jt, L, scheme, half_params};
   auto work = [&](int tid) {
     std::vector<float> v((size_t)L);
+    std::vector<double> own_basis;
     for (int i = tid; i < d; i += nt) {
+      if (per_input) basis_table(i, own_basis);
+      const std::vector<double> &basis = per_input ? own_basis : shared_basis;
       for (int j = 0; j < m; ++j) {
         const size_t e = (size_t)i * m + j;
         const float *c = desc->coef + e * R;
@@ -348,7 +365,7 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
     return fail(LUTKAN_EUNSUPPORTED, "lutkan_compile: %ld segments have an alpha or y_min too large for float16", n);
   }
 
-  fill_info(a, d, m, K, L, G, scheme, desc->boundary, desc->oob, repr, desc->param_dtype, jt, n_tiles, lay, coef_blob);
+  fill_info(a, d, m, K, L, G, scheme, desc->boundary, desc->oob, repr, desc->param_dtype, desc->knots_per_input, jt, n_tiles, lay, coef_blob);
   a->info.knot_span = desc->knot_span;
   *out = a;
   return LUTKAN_OK;
@@ -366,16 +383,21 @@ extern "C" int lutkan_artifact_from_arrays(const lutkan_artifact_arrays *in, lut
   if (in->oob != LUTKAN_CLIP_X && in->oob != LUTKAN_ZERO_SPLINE) return fail(LUTKAN_EINVAL, "%s: bad oob_policy %d", who, in->oob);
   if (repr != LUTKAN_REPR_PHI && repr != LUTKAN_REPR_SPLINE_COMPONENT) return fail(LUTKAN_EINVAL, "%s: bad value_repr %d", who, repr);
   if (in->param_dtype != LUTKAN_PARAM_FP32 && in->param_dtype != LUTKAN_PARAM_FP16) return fail(LUTKAN_EINVAL, "%s: bad param_dtype %d", who, in->param_dtype);
+  if (in->knots_per_input != 0 && in->knots_per_input != 1) return fail(LUTKAN_EINVAL, "%s: bad knots_per_input %d", who, in->knots_per_input);
+  const int n_vectors = in->knots_per_input ? d : 1;
   const bool with_base = (repr == LUTKAN_REPR_SPLINE_COMPONENT);
   const bool half_params = (in->param_dtype == LUTKAN_PARAM_FP16);
   if (with_base && (!in->edge_base_scale || !in->edge_spline_scale || !in->edge_out_scale))
     return fail(LUTKAN_EINVAL, "%s: spline_component needs edge_base_scale, edge_spline_scale and edge_out_scale", who);
   if (K > LUTKAN_MAX_K) return fail(LUTKAN_EUNSUPPORTED, "%s: K=%d exceeds LUTKAN_MAX_K=%d", who, K, LUTKAN_MAX_K);
   if ((int64_t)K * L > LUTKAN_MAX_ROWS) return fail(LUTKAN_EUNSUPPORTED, "%s: K*L=%lld exceeds %d", who, (long long)K * L, LUTKAN_MAX_ROWS);
-  for (int k = 0; k <= K; ++k)
-    if (!std::isfinite(in->knots[k])) return fail(LUTKAN_EINVAL, "%s: knot %d is not finite", who, k);
-  for (int k = 0; k < K; ++k)
-    if (!(in->knots[k] < in->knots[k + 1])) return fail(LUTKAN_EINVAL, "%s: knots not strictly increasing at %d", who, k);
+  for (int h = 0; h < n_vectors; ++h) {
+    const float *T = in->knots + (size_t)h * (K + 1);
+    for (int k = 0; k <= K; ++k)
+      if (!std::isfinite(T[k])) return fail(LUTKAN_EINVAL, "%s: knot %d of vector %d is not finite", who, k, h);
+    for (int k = 0; k < K; ++k)
+      if (!(T[k] < T[k + 1])) return fail(LUTKAN_EINVAL, "%s: knots of vector %d not strictly increasing at %d", who, h, k);
+  }
   const size_t E = (size_t)d * m;
   for (size_t n = 0; n < E * K; ++n) {
     if (!std::isfinite(in->scale[n]) || !std::isfinite(in->y_min[n])) return fail(LUTKAN_EINVAL, "%s: scale / y_min entry %zu is not finite", who, n);
@@ -393,7 +415,7 @@ extern "C" int lutkan_artifact_from_arrays(const lutkan_artifact_arrays *in, lut
   const int n_tiles = (m + jt - 1) / jt;
   const BlobLayout lay = blob_layout(K, L, jt, scheme, repr, in->param_dtype);
   try {
-    a->knots.assign(in->knots, in->knots + K + 1);
+    a->knots.assign(in->knots, in->knots + (size_t)n_vectors * (K + 1));
     a->q.assign(static_cast<const uint8_t *>(in->q_table), static_cast<const uint8_t *>(in->q_table) + E * K * L);
     a->scale.assign(in->scale, in->scale + E * K);
     a->ymin.assign(in->y_min, in->y_min + E * K);
@@ -421,7 +443,7 @@ extern "C" int lutkan_artifact_from_arrays(const lutkan_artifact_arrays *in, lut
         packer.put_segment(slice, j % jt, k, a->scale[e * K + k], a->ymin[e * K + k], with_base, spline_gain, a->q.data() + (e * K + k) * L);
     }
   // a LUT artifact holds no spline coefficients: G = 0 and an empty B-spline table say so
-  fill_info(a, d, m, K, L, 0, scheme, in->boundary, in->oob, repr, in->param_dtype, jt, n_tiles, lay, 0);
+  fill_info(a, d, m, K, L, 0, scheme, in->boundary, in->oob, repr, in->param_dtype, in->knots_per_input, jt, n_tiles, lay, 0);
   *out = a;
   return LUTKAN_OK;
 }
@@ -456,6 +478,8 @@ extern "C" int lutkan_dev_layer_init(const lutkan_artifact *a, lutkan_dev_layer 
   out->algo = LUTKAN_ALGO_AUTO;
   for (int k = 0; k <= I.K; ++k) out->knots[k] = a->knots[k];
   out->table = nullptr;
+  out->knots_per_input = I.knots_per_input;
+  out->input_knots = nullptr;
   return LUTKAN_OK;
 }
 
@@ -470,5 +494,7 @@ extern "C" int bspline_dev_layer_init(const lutkan_artifact *a, bspline_dev_laye
   out->algo = LUTKAN_ALGO_AUTO;
   for (int r = 0; r < I.G + 2 * P + 1; ++r) out->ext_knots[r] = a->ext_knots[r];
   out->coef_table = nullptr;
+  out->knots_per_input = I.knots_per_input;
+  out->input_ext_knots = nullptr;
   return LUTKAN_OK;
 }

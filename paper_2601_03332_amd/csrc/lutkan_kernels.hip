@@ -54,6 +54,7 @@ struct LocateArgs {
   int32_t closed, zero_spline;
   float tKs;             // safe upper clip value
   float knots[LUTKAN_MAX_K + 1];
+  const float *input_knots;    // [d][K+1]: one knot vector per input (then knots and tKs are not used)
   int32_t *k_out, *l0_out;     // nullable trace outputs, [B][d]
   uint8_t *in_out;
   float *w_out;
@@ -65,19 +66,31 @@ struct Located {
   bool inside, is_nan;
 };
 
-// s_knots: the K+1 knots in LDS, for the two lookups by the lane's own segment index.
+// The largest float below a finite t: nextafter(t, -inf), the safe upper clip value of Eq. 13 in half-open mode.
+__device__ __forceinline__ float next_float_below(float t) {
+  const unsigned bits = __float_as_uint(t);
+  if (t > 0.0f) return __uint_as_float(bits - 1u);
+  if (t < 0.0f) return __uint_as_float(bits + 1u);
+  return __uint_as_float(0x80000001u);                 // below +-0: the smallest negative subnormal
+}
+
+// s_knots: the K+1 knots of this element's input in LDS.  With one vector per layer (PERIN false) the comparisons
+// run against the copy in the kernel arguments (scalar registers) and LDS serves the two lookups by the lane's own
+// segment index; with one vector per input every lane reads its own input's row.
+template <bool PERIN>
 __device__ __forceinline__ Located locate_one(const LocateArgs &a, const float *s_knots, float x) {
   Located o;
-  const float t0 = a.knots[0];
-  const float tK = a.knots[a.K];
+  const float t0 = PERIN ? s_knots[0] : a.knots[0];
+  const float tK = PERIN ? s_knots[a.K] : a.knots[a.K];
+  const float tKs = PERIN ? (a.closed ? tK : next_float_below(tK)) : a.tKs;
   o.is_nan = (x != x);
   o.inside = a.closed ? (x >= t0 && x <= tK) : (x >= t0 && x < tK);
   float xc = o.is_nan ? t0 : x;
   xc = (xc < t0) ? t0 : xc;
-  xc = (xc > a.tKs) ? a.tKs : xc;
+  xc = (xc > tKs) ? tKs : xc;
   // k = #{kappa in 1..K-1 : T[kappa] <= x'}; T[0] <= x' always holds and T[K] is clipped away (Eq. 14).
   int k = 0;
-  for (int kappa = 1; kappa < a.K; ++kappa) k += (a.knots[kappa] <= xc) ? 1 : 0;     // knots sit in scalar registers
+  for (int kappa = 1; kappa < a.K; ++kappa) k += ((PERIN ? s_knots[kappa] : a.knots[kappa]) <= xc) ? 1 : 0;
   const float tk = s_knots[k], tk1 = s_knots[k + 1];
   const float num = __fsub_rn(xc, tk);
   const float den = __fsub_rn(tk1, tk);
@@ -98,18 +111,29 @@ constexpr int kLocTile = 2048;  // (row, input) pairs per block of the LUT locat
 // transposed through LDS and written along rows (coalesced): records are stored [input][row].
 // blockIdx.x = row tile, blockIdx.y = input tile, so small batches still fill the GPU.
 // BASE: value_repr = spline_component, the record also carries SiLU(x).
-template <bool BASE, int COLS>
+// PERIN: one knot vector per input; the block keeps the vectors of its COLS inputs in LDS (odd row stride, so lanes
+// that read the same knot index of different inputs hit different banks).
+template <bool BASE, int COLS, bool PERIN>
 __global__ __launch_bounds__(256) void lutkan_locate_kernel(const LocateArgs a) {
   typedef typename std::conditional<BASE, u32x4, u32x2>::type rec_t;
   constexpr int ROWS = kLocTile / COLS;
   constexpr int ROW_GROUPS = 256 / COLS;                 // rows handled side by side in phase 1
+  constexpr int KSTRIDE = LUTKAN_MAX_K + 1;
+  static_assert(KSTRIDE % 2 == 1, "odd stride between the knot rows");
   __shared__ rec_t s_rec[COLS][ROWS + 1];
-  __shared__ float s_knots[LUTKAN_MAX_K + 1];
+  __shared__ float s_knots[(PERIN ? COLS : 1) * KSTRIDE];
   rec_t *const rec_out = static_cast<rec_t *>(a.rec);
   const int tid = threadIdx.x;
-  if (tid <= a.K) s_knots[tid] = a.knots[tid];
   const int64_t b0 = (int64_t)blockIdx.x * ROWS;
   const int i0 = blockIdx.y * COLS;
+  if constexpr (PERIN) {
+    for (int q = tid; q < COLS * (a.K + 1); q += 256) {
+      const int c = q / (a.K + 1), kappa = q - c * (a.K + 1);
+      s_knots[c * KSTRIDE + kappa] = (i0 + c < a.d) ? a.input_knots[(int64_t)(i0 + c) * (a.K + 1) + kappa] : 0.0f;
+    }
+  } else {
+    if (tid <= a.K) s_knots[tid] = a.knots[tid];
+  }
   const unsigned masked_index = (unsigned)(a.K * a.L) | ((unsigned)a.K << 16);
   const int il = tid % COLS;
   const int i = i0 + il;
@@ -128,7 +152,7 @@ __global__ __launch_bounds__(256) void lutkan_locate_kernel(const LocateArgs a) 
     rec.x = masked_index;
     if (b < a.B && i < a.d) {
       const float x = xv[p];
-      const Located o = locate_one(a, s_knots, x);
+      const Located o = locate_one<PERIN>(a, s_knots + (PERIN ? il * KSTRIDE : 0), x);
       const bool masked = a.zero_spline && !o.inside && !o.is_nan;
       if (!masked) {
         rec.x = (unsigned)(o.k * a.L + o.l0) | ((unsigned)o.k << 16);
@@ -159,8 +183,9 @@ __global__ __launch_bounds__(256) void lutkan_locate_kernel(const LocateArgs a) 
 // One wave per row at a time; one atomic per work-group and counter.
 constexpr int kOobRowsPerWave = 8;
 
+// input_knots (nullable): [d][K+1], every input has its own domain [row[0], row[K]] instead of [t0, tK].
 __global__ __launch_bounds__(256) void oob_count_kernel(const float *x, int64_t B, int d, float t0, float tK, int closed,
-                                                        unsigned long long *stats) {
+                                                        const float *input_knots, int K, unsigned long long *stats) {
   __shared__ unsigned s_inputs[4], s_rows[4];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   unsigned inputs = 0, rows = 0;
@@ -170,7 +195,9 @@ __global__ __launch_bounds__(256) void oob_count_kernel(const float *x, int64_t 
     unsigned outside = 0;
     for (int i = lane; i < d; i += 64) {
       const float v = x[b * d + i];
-      const bool in = closed ? (v >= t0 && v <= tK) : (v >= t0 && v < tK);
+      const float lo = input_knots ? input_knots[(int64_t)i * (K + 1)] : t0;
+      const float hi = input_knots ? input_knots[(int64_t)i * (K + 1) + K] : tK;
+      const bool in = closed ? (v >= lo && v <= hi) : (v >= lo && v < hi);
       outside += in ? 0u : 1u;
     }
     for (int off = 32; off > 0; off >>= 1) outside += __shfl_down(outside, off, kWave);
@@ -557,39 +584,47 @@ struct SplineLocateArgs {
   int32_t extended;      // the domain is the whole extended knot vector (else its inner G intervals)
   float tKs;
   float ext_knots[LUTKAN_MAX_K + 7];
+  const float *input_ext_knots;   // [d][G+7]: one knot vector per input (then ext_knots and tKs are not used)
 };
 
 constexpr int kSplTile = 1024;  // (row, input) pairs per block of the B-spline locate kernel (32-byte records)
 
 // Same tiling as the LUT locate kernel: blockIdx.x = tile of ROWS rows, blockIdx.y = tile of COLS inputs
-// (COLS = 32 or 16, ROWS * COLS = 1024).
-template <int COLS>
+// (COLS = 32 or 16, ROWS * COLS = 1024).  PERIN: one knot vector per input, the block keeps those of its COLS inputs.
+template <int COLS, bool PERIN>
 __global__ __launch_bounds__(256) void bspline_locate_kernel(const SplineLocateArgs a) {
   constexpr int ROWS = kSplTile / COLS;
+  constexpr int PSTRIDE = LUTKAN_MAX_K + 13;
+  static_assert(PSTRIDE % 2 == 1, "odd stride between the knot rows");
   __shared__ u32x4 s_rec[2][COLS][ROWS + 1];
   // the extended knots with three made-up knots on either side: s_pad[3 + r] = ext_knots[r].  A basis function that
   // exists (index 0 .. G+2) only ever touches real knots; the padding keeps the recursion of the others in bounds.
-  __shared__ float s_pad[LUTKAN_MAX_K + 13];
+  __shared__ float s_pad[(PERIN ? COLS : 1) * PSTRIDE];
   const int tid = threadIdx.x;
   const int64_t b0 = (int64_t)blockIdx.x * ROWS;
+  const int i0 = blockIdx.y * COLS;
   const int n = a.G + 7;
-  for (int r = tid; r < n + 6; r += 256) {
-    float v;
-    if (r < 3) v = a.ext_knots[0] - (float)(3 - r) * (a.ext_knots[1] - a.ext_knots[0]);
-    else if (r >= n + 3) v = a.ext_knots[n - 1] + (float)(r - n - 2) * (a.ext_knots[n - 1] - a.ext_knots[n - 2]);
-    else v = a.ext_knots[r - 3];
-    s_pad[r] = v;
+  for (int q = tid; q < (PERIN ? COLS : 1) * (n + 6); q += 256) {
+    const int c = q / (n + 6), r = q - c * (n + 6);
+    float v = 0.0f;
+    if (!PERIN || i0 + c < a.d) {
+      const float *src = PERIN ? a.input_ext_knots + (int64_t)(i0 + c) * n : a.ext_knots;
+      if (r < 3) v = src[0] - (float)(3 - r) * (src[1] - src[0]);
+      else if (r >= n + 3) v = src[n - 1] + (float)(r - n - 2) * (src[n - 1] - src[n - 2]);
+      else v = src[r - 3];
+    }
+    s_pad[c * PSTRIDE + r] = v;
   }
   __syncthreads();
-  const float *s_tau = s_pad + 3;
   const int first_knot = a.extended ? 0 : 3;           // domain knot kappa is extended knot first_knot + kappa
   const int segments = a.extended ? a.G + 6 : a.G;
   const int R = a.G + 3;
-  const float t0 = s_tau[first_knot], tK = s_tau[first_knot + segments];
   {
-    const int i0 = blockIdx.y * COLS;
     const int il = tid % COLS;
     const int i = i0 + il;
+    const float *s_tau = s_pad + (PERIN ? il * PSTRIDE : 0) + 3;
+    const float t0 = s_tau[first_knot], tK = s_tau[first_knot + segments];
+    const float tKs = PERIN ? (a.closed ? tK : next_float_below(tK)) : a.tKs;
 #pragma unroll 1
     for (int p = 0; p < kSplTile / 256; ++p) {
       const int bl = p * (256 / COLS) + tid / COLS;
@@ -603,7 +638,7 @@ __global__ __launch_bounds__(256) void bspline_locate_kernel(const SplineLocateA
         const bool inside = a.closed ? (x >= t0 && x <= tK) : (x >= t0 && x < tK);
         float xc = is_nan ? t0 : x;
         xc = (xc < t0) ? t0 : xc;
-        xc = (xc > a.tKs) ? a.tKs : xc;
+        xc = (xc > tKs) ? tKs : xc;
         for (int kappa = 1; kappa < segments; ++kappa) k += (s_tau[first_knot + kappa] <= xc) ? 1 : 0;
         // Cox-de Boor on the span mu = first_knot + k, non-zero entries only (Eq. 4-5); knots are distinct.
         const int mu = first_knot + k;
@@ -896,6 +931,9 @@ int validate_layer(const lutkan_dev_layer *l, const char *who) {
   if (l->n_tiles != (l->m + l->jt - 1) / l->jt) return fail(LUTKAN_ESHAPE, "%s: n_tiles does not match m and jt", who);
   if (l->blob_bytes != lutkan::blob_layout(l->K, l->L, l->jt, l->scheme, l->value_repr, l->param_dtype).bytes) return fail(LUTKAN_ESHAPE, "%s: blob_bytes does not match K, L, jt, scheme, param_dtype", who);
   if ((reinterpret_cast<uintptr_t>(l->table) & 15) != 0) return fail(LUTKAN_EINVAL, "%s: table must be 16-byte aligned", who);
+  if (l->knots_per_input != 0 && l->knots_per_input != 1) return fail(LUTKAN_EINVAL, "%s: bad knots_per_input %d", who, l->knots_per_input);
+  if (l->knots_per_input && (!l->input_knots || (reinterpret_cast<uintptr_t>(l->input_knots) & 3) != 0))
+    return fail(LUTKAN_EINVAL, "%s: knots_per_input needs layer.input_knots (device, 4-byte aligned)", who);
   return LUTKAN_OK;
 }
 
@@ -987,6 +1025,13 @@ bool tiled_supported(int jt, int blob_bytes) {
 
 enum { kLocate = 1, kEdges = 2 };
 
+template <bool BASE, bool PERIN>
+void launch_locate(int cols, dim3 grid, hipStream_t s, const LocateArgs &la) {
+  if (cols == 64) hipLaunchKernelGGL((lutkan_locate_kernel<BASE, 64, PERIN>), grid, dim3(256), 0, s, la);
+  else if (cols == 32) hipLaunchKernelGGL((lutkan_locate_kernel<BASE, 32, PERIN>), grid, dim3(256), 0, s, la);
+  else hipLaunchKernelGGL((lutkan_locate_kernel<BASE, 16, PERIN>), grid, dim3(256), 0, s, la);
+}
+
 int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y, lutkan_oob_stats *stats,
                  int32_t *k_out, int32_t *l0_out, uint8_t *in_out, float *w_out, int16_t *q01_out, bool trace,
                  void *workspace, size_t workspace_bytes, void *hip_stream, const char *who, int phases = kLocate | kEdges) {
@@ -1012,6 +1057,7 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   const bool with_base = (l->value_repr == LUTKAN_REPR_SPLINE_COMPONENT);
   la.tKs = la.closed ? l->knots[l->K] : std::nextafterf(l->knots[l->K], -INFINITY);
   for (int k = 0; k <= l->K; ++k) la.knots[k] = l->knots[k];
+  la.input_knots = l->knots_per_input ? l->input_knots : nullptr;
   la.k_out = trace ? k_out : nullptr; la.l0_out = l0_out; la.in_out = in_out; la.w_out = w_out;
   if (phases & kLocate) {
     // inputs per block: the width in {64, 32, 16} that pads d least (the widest on ties: longer runs of x)
@@ -1020,20 +1066,18 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
       if ((l->d + c - 1) / c * c < (l->d + cols - 1) / cols * cols) cols = c;
     const dim3 lgrid((unsigned)(Bp / (kLocTile / cols)), (unsigned)((l->d + cols - 1) / cols));
     if (lgrid.y > 65535u) return fail(LUTKAN_EUNSUPPORTED, "%s: d too large", who);
-    if (with_base) {
-      if (cols == 64) hipLaunchKernelGGL((lutkan_locate_kernel<true, 64>), lgrid, dim3(256), 0, s, la);
-      else if (cols == 32) hipLaunchKernelGGL((lutkan_locate_kernel<true, 32>), lgrid, dim3(256), 0, s, la);
-      else hipLaunchKernelGGL((lutkan_locate_kernel<true, 16>), lgrid, dim3(256), 0, s, la);
+    if (l->knots_per_input) {
+      if (with_base) launch_locate<true, true>(cols, lgrid, s, la);
+      else launch_locate<false, true>(cols, lgrid, s, la);
     } else {
-      if (cols == 64) hipLaunchKernelGGL((lutkan_locate_kernel<false, 64>), lgrid, dim3(256), 0, s, la);
-      else if (cols == 32) hipLaunchKernelGGL((lutkan_locate_kernel<false, 32>), lgrid, dim3(256), 0, s, la);
-      else hipLaunchKernelGGL((lutkan_locate_kernel<false, 16>), lgrid, dim3(256), 0, s, la);
+      if (with_base) launch_locate<true, false>(cols, lgrid, s, la);
+      else launch_locate<false, false>(cols, lgrid, s, la);
     }
     if (int rc = check_launch("lutkan_locate_kernel")) return rc;
     if (stats) {
       const int64_t rows_per_group = 4 * kOobRowsPerWave;
       hipLaunchKernelGGL(oob_count_kernel, dim3((unsigned)((B + rows_per_group - 1) / rows_per_group)), dim3(256), 0, s, x, B, l->d,
-                         l->knots[0], l->knots[l->K], la.closed, reinterpret_cast<unsigned long long *>(stats));
+                         l->knots[0], l->knots[l->K], la.closed, la.input_knots, l->K, reinterpret_cast<unsigned long long *>(stats));
       if (int rc = check_launch("oob_count_kernel")) return rc;
     }
   }
@@ -1116,6 +1160,9 @@ int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y
                  size_t workspace_bytes, void *hip_stream, const char *who, int phases) {
   if (!l) return fail(LUTKAN_EINVAL, "%s: null layer", who);
   if (!l->coef_table) return fail(LUTKAN_EINVAL, "%s: layer.coef_table is null", who);
+  if (l->knots_per_input != 0 && l->knots_per_input != 1) return fail(LUTKAN_EINVAL, "%s: bad knots_per_input %d", who, l->knots_per_input);
+  if (l->knots_per_input && (!l->input_ext_knots || (reinterpret_cast<uintptr_t>(l->input_ext_knots) & 3) != 0))
+    return fail(LUTKAN_EINVAL, "%s: knots_per_input needs layer.input_ext_knots (device, 4-byte aligned)", who);
   if (l->d < 1 || l->m < 1 || l->G < 1 || l->G > LUTKAN_MAX_K) return fail(LUTKAN_EINVAL, "%s: bad d/m/G", who);
   if (l->degree != 3) return fail(LUTKAN_EUNSUPPORTED, "%s: only cubic splines", who);
   if (l->boundary != LUTKAN_HALF_OPEN && l->boundary != LUTKAN_CLOSED) return fail(LUTKAN_EINVAL, "%s: bad boundary_mode", who);
@@ -1150,12 +1197,18 @@ int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y
   const float domain_end = la.extended ? l->ext_knots[G + 6] : l->ext_knots[3 + G];
   la.tKs = la.closed ? domain_end : std::nextafterf(domain_end, -INFINITY);
   for (int r = 0; r < G + 7; ++r) la.ext_knots[r] = l->ext_knots[r];
+  la.input_ext_knots = l->knots_per_input ? l->input_ext_knots : nullptr;
   if (phases & kLocate) {
     const int cols = ((l->d + 15) / 16 * 16 < (l->d + 31) / 32 * 32) ? 16 : 32;      // the width that pads d least
     const dim3 lgrid((unsigned)(Bp / (kSplTile / cols)), (unsigned)((l->d + cols - 1) / cols));
     if (lgrid.y > 65535u) return fail(LUTKAN_EUNSUPPORTED, "%s: d too large", who);
-    if (cols == 32) hipLaunchKernelGGL(bspline_locate_kernel<32>, lgrid, dim3(256), 0, s, la);
-    else hipLaunchKernelGGL(bspline_locate_kernel<16>, lgrid, dim3(256), 0, s, la);
+    if (l->knots_per_input) {
+      if (cols == 32) hipLaunchKernelGGL((bspline_locate_kernel<32, true>), lgrid, dim3(256), 0, s, la);
+      else hipLaunchKernelGGL((bspline_locate_kernel<16, true>), lgrid, dim3(256), 0, s, la);
+    } else {
+      if (cols == 32) hipLaunchKernelGGL((bspline_locate_kernel<32, false>), lgrid, dim3(256), 0, s, la);
+      else hipLaunchKernelGGL((bspline_locate_kernel<16, false>), lgrid, dim3(256), 0, s, la);
+    }
     if (int rc = check_launch("bspline_locate_kernel")) return rc;
   }
   if (!(phases & kEdges)) return LUTKAN_OK;

@@ -58,7 +58,8 @@ __device__ __forceinline__ Acc shuffle_down(const Acc &a, int off) {
 
 __global__ __launch_bounds__(kStatWaves * 64) void error_stats_partial_kernel(const float *y, const float *y_ref, const float *x,
                                                                               int64_t B, int m, int d, float t0, float tK,
-                                                                              int closed, Partial *partials) {
+                                                                              const float *input_domain, int closed,
+                                                                              Partial *partials) {
   __shared__ Acc s_acc[kStatWaves];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
@@ -70,7 +71,9 @@ __global__ __launch_bounds__(kStatWaves * 64) void error_stats_partial_kernel(co
     int outside = 0;
     for (int i = lane; i < d; i += 64) {
       const float v = x[b * d + i];
-      const bool in = closed ? (v >= t0 && v <= tK) : (v >= t0 && v < tK);
+      const float lo = input_domain ? input_domain[2 * i] : t0;
+      const float hi = input_domain ? input_domain[2 * i + 1] : tK;
+      const bool in = closed ? (v >= lo && v <= hi) : (v >= lo && v < hi);
       outside |= in ? 0 : 1;
     }
     const bool row_in = (__ballot(outside != 0) == 0ull);
@@ -139,12 +142,12 @@ extern "C" size_t lutkan_error_stats_workspace_bytes(int64_t B) {
 }
 
 extern "C" int lutkan_error_stats(const float *y, const float *y_ref, int64_t B, int32_t m, const float *x, int32_t d,
-                                  float t0, float tK, int32_t boundary, lutkan_error_summary *out, void *workspace,
-                                  size_t workspace_bytes, void *hip_stream) {
+                                  float t0, float tK, const float *input_domain, int32_t boundary,
+                                  lutkan_error_summary *out, void *workspace, size_t workspace_bytes, void *hip_stream) {
   const char *who = "lutkan_error_stats";
   if (!y || !y_ref || !x || !out) return fail(LUTKAN_EINVAL, "%s: null y / y_ref / x / out", who);
   if (B < 1 || m < 1 || d < 1) return fail(LUTKAN_EINVAL, "%s: B, m, d must be >= 1", who);
-  if (!(t0 < tK)) return fail(LUTKAN_EINVAL, "%s: need t0 < tK", who);
+  if (!input_domain && !(t0 < tK)) return fail(LUTKAN_EINVAL, "%s: need t0 < tK", who);
   if (boundary != LUTKAN_HALF_OPEN && boundary != LUTKAN_CLOSED) return fail(LUTKAN_EINVAL, "%s: bad boundary_mode %d", who, boundary);
   if ((reinterpret_cast<uintptr_t>(out) & 7) != 0) return fail(LUTKAN_EINVAL, "%s: out must be 8-byte aligned", who);
   const size_t need = lutkan_error_stats_workspace_bytes(B);
@@ -155,7 +158,7 @@ extern "C" int lutkan_error_stats(const float *y, const float *y_ref, int64_t B,
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   Partial *partials = static_cast<Partial *>(workspace);
   hipLaunchKernelGGL(error_stats_partial_kernel, dim3((unsigned)groups), dim3(kStatWaves * 64), 0, s, y, y_ref, x, B, m, d, t0, tK,
-                     boundary == LUTKAN_CLOSED ? 1 : 0, partials);
+                     input_domain, boundary == LUTKAN_CLOSED ? 1 : 0, partials);
   hipLaunchKernelGGL(error_stats_final_kernel, dim3(1), dim3(256), 0, s, partials, groups, out);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(LUTKAN_EHIP, "%s: %s", who, hipGetErrorString(e));

@@ -10,6 +10,7 @@ import pytest
 import oracle
 from lutkan_inputs import (ASYM_UINT8, CLIP_X, CLOSED, HALF_OPEN, SYM_INT8, ZERO_SPLINE, case_a, cfg1, cfg2, cfg3, cfg4,
                            cfg5, random_layer)
+from lutkan_inputs import per_input_layer
 
 pytestmark = pytest.mark.gpu
 
@@ -30,14 +31,16 @@ _COMPILED = {}
 def _compile_both(s, param_fp16=False):
     """Library artifact + oracle artifact for a layer spec; the codes must already agree bit for bit.
     Cached per table content (the contract fields do not change the tables)."""
-    key = (s.d, s.m, s.G, s.L, s.scheme, hash(s.coef.tobytes()), hash(s.ext_knots.tobytes()), param_fp16,
+    key = (s.d, s.m, s.G, s.L, s.scheme, hash(s.coef.tobytes()), hash(s.ext_knots.tobytes()), param_fp16, s.per_input,
            None if s.edge_scales is None else hash(b"".join(a.tobytes() for a in s.edge_scales)))
     if key not in _COMPILED:
         if len(_COMPILED) > 4:
             _COMPILED.clear()
         art = lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, s.boundary, s.oob,
-                                edge_scales=s.edge_scales, param_dtype=lk.PARAM_FP16 if param_fp16 else lk.PARAM_FP32)
-        ora = oracle.compile_layer(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, param_fp16=param_fp16)
+                                edge_scales=s.edge_scales, param_dtype=lk.PARAM_FP16 if param_fp16 else lk.PARAM_FP32,
+                                knots_per_input=s.per_input)
+        ora = oracle.compile_layer(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, param_fp16=param_fp16,
+                                   per_input=s.per_input)
         assert np.array_equal(art.q, ora.q) and np.array_equal(art.scale, ora.scale) and np.array_equal(art.y_min, ora.y_min)
         _COMPILED[key] = (art, ora)
     return _COMPILED[key]
@@ -162,6 +165,58 @@ def test_fp16_parameters_with_spline_component(case):
     w = random_layer(seed + 50, d, m, G, L, scheme, boundary, oob, B, uniform=(seed % 2 == 1), with_base=True)
     _check_layer(w.layers[0], w.x, lk.ALGO_TILED, what=w.name, param_fp16=True)
     _check_layer(w.layers[0], w.x, lk.ALGO_GATHER, codes=(B * d * m <= 2_000_000), what=w.name, param_fp16=True)
+
+
+PER_INPUT_CASES = [
+    # seed, d, m, G, L, scheme, boundary, oob, B, with_base, param_fp16
+    (801, 1, 1, 3, 2, SYM_INT8, CLOSED, CLIP_X, 1, False, False),
+    (802, 3, 5, 5, 16, ASYM_UINT8, HALF_OPEN, ZERO_SPLINE, 300, False, False),      # 16 inputs per locate block
+    (803, 20, 16, 8, 64, SYM_INT8, HALF_OPEN, CLIP_X, 1025, True, False),           # 32 inputs per locate block
+    (804, 70, 130, 10, 32, ASYM_UINT8, CLOSED, ZERO_SPLINE, 2100, False, True),     # two blocks of 64 inputs, ragged
+    (805, 33, 64, 64, 8, SYM_INT8, CLOSED, CLIP_X, 700, True, True),                # the longest knot vectors
+    (806, 129, 40, 6, 128, ASYM_UINT8, HALF_OPEN, ZERO_SPLINE, 4099, True, False),
+]
+
+
+@pytest.mark.parametrize("case", PER_INPUT_CASES, ids=lambda c: f"seed{c[0]}")
+def test_one_knot_vector_per_input(case):
+    """Sec. 6.2's knot grid "shared per input dimension": every input is located, clipped and masked on its own knot
+    vector (different domains, uniform and non-uniform); LUT layer (both kernels, counters) and B-spline layer."""
+    seed, d, m, G, L, scheme, boundary, oob, B, with_base, half = case
+    w = per_input_layer(seed, d, m, G, L, scheme, boundary, oob, B, with_base=with_base)
+    s = w.layers[0]
+    _check_layer(s, w.x, lk.ALGO_AUTO, what=w.name, param_fp16=half)
+    _check_layer(s, w.x, lk.ALGO_GATHER, codes=(B * d * m <= 2_000_000), what=w.name, param_fp16=half)
+    art = _compile_both(s, half)[0]
+    xg = torch.from_numpy(w.x).to(DEV)
+    refb = oracle.bspline_forward(d, m, G, s.p, s.ext_knots, s.coef, boundary, oob, w.x, edge_scalars=s.edge_scales, per_input=True)
+    for algo in (lk.ALGO_AUTO, lk.ALGO_GATHER):
+        yb = lk.bspline_kan_forward(art.bspline_to_device(DEV, algo), xg)
+        torch.cuda.synchronize()
+        _assert_close(yb.cpu().numpy(), refb, f"{w.name} bspline algo={algo}")
+    # the error statistics with every input's own domain
+    y_lut = lk.lutkan_forward(_device_layer(art, s), xg)
+    dom = torch.from_numpy(np.ascontiguousarray(art.knots[:, [0, -1]])).to(DEV)
+    got = lk.lutkan_error_stats(y_lut, yb, xg, 0.0, 0.0, boundary, input_domain=dom)
+    want = oracle.error_stats(y_lut.cpu().numpy(), yb.cpu().numpy(), w.x, art.knots[:, 0], art.knots[:, -1], boundary)
+    for key in ("rows_in", "rows_oob", "nan_outputs", "max_abs_in", "max_abs_oob"):
+        assert got[key] == want[key], key
+    for key in ("sum_abs_in", "sum_abs_oob"):
+        assert abs(got[key] - want[key]) <= 1e-12 * abs(want[key]) + 1e-300, key
+
+
+def test_per_input_layer_without_its_knot_table_is_refused():
+    w = per_input_layer(810, 4, 4, 5, 8, SYM_INT8, CLOSED, CLIP_X, 16)
+    s = w.layers[0]
+    art = _compile_both(s)[0]
+    layer, bl = art.to_device(DEV), art.bspline_to_device(DEV)
+    layer.c.input_knots = None
+    bl.c.input_ext_knots = None
+    xg = torch.from_numpy(w.x).to(DEV)
+    for call in (lambda: lk.lutkan_forward(layer, xg), lambda: lk.bspline_kan_forward(bl, xg)):
+        with pytest.raises(lk.LutKanError) as e:
+            call()
+        assert str(e.value).startswith("[-1]")
 
 
 def test_loaded_artifact_runs_like_the_compiled_one(tmp_path):

@@ -13,6 +13,7 @@ import paper_2601_03332_amd as lk
 from paper_2601_03332_amd import binding
 from lutkan_inputs import (ASYM_UINT8, CLIP_X, CLOSED, HALF_OPEN, SYM_INT8, ZERO_SPLINE, cfg1, cfg2, cfg5,
                            random_layer, uniform_ext_knots)
+from lutkan_inputs import per_input_layer
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -365,6 +366,53 @@ def test_extended_knot_span_compiles_like_the_oracle(scheme, uniform):
         big = random_layer(96, 1, 1, 60, 2, scheme, CLOSED, CLIP_X, 4).layers[0]
         lk.lutkan_compile(1, 1, 60, 3, big.ext_knots, big.coef, 2, scheme, CLOSED, CLIP_X, knot_span=lk.SPAN_EXTENDED)
     assert str(e.value).startswith("[-5]")
+
+
+@pytest.mark.parametrize("scheme,extended,half,base", [(SYM_INT8, False, False, False), (ASYM_UINT8, True, True, True)])
+def test_knots_per_input_compile_like_the_oracle(scheme, extended, half, base, tmp_path):
+    """One knot vector per input dimension (Sec. 6.2): codes, parameters and knot rows bit-identical to the oracle's,
+    the byte accounting counts d knot vectors, and the NPZ round trip keeps the [d, K+1] knots."""
+    s = per_input_layer(98, 5, 70, 6, 16, scheme, HALF_OPEN, ZERO_SPLINE, 4, with_base=base).layers[0]
+    art = lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, scheme, s.boundary, s.oob, edge_scales=s.edge_scales,
+                            param_dtype=int(half), knot_span=int(extended), knots_per_input=True, n_threads=3)
+    ora = oracle.compile_layer(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, scheme, param_fp16=half, extended=extended,
+                               per_input=True)
+    I = art.info
+    K = s.G + 6 if extended else s.G
+    assert (I.knots_per_input, I.K) == (1, K) and art.knots.shape == (s.d, K + 1) and art.ext_knots.shape == (s.d, s.G + 7)
+    np.testing.assert_array_equal(art.knots, ora.knots)
+    np.testing.assert_array_equal(art.ext_knots, s.ext_knots)
+    np.testing.assert_array_equal(art.q, ora.q)
+    np.testing.assert_array_equal(art.scale.view(np.uint32), ora.scale.view(np.uint32))
+    np.testing.assert_array_equal(art.y_min.view(np.uint32), ora.y_min.view(np.uint32))
+    E = s.d * s.m
+    assert I.artifact_bytes == E * K * s.L + 2 * E * K * (2 if half else 4) + 4 * s.d * (K + 1) + (12 * E if base else 0)
+    assert (I.t0, I.tK) == (art.knots[0, 0], art.knots[0, -1])
+    # the tables of input i are those of a single-input layer on knot vector i
+    one = lk.lutkan_compile(1, s.m, s.G, s.p, s.ext_knots[2], s.coef[2], s.L, scheme, s.boundary, s.oob,
+                            edge_scales=None if not base else tuple(a[2] for a in s.edge_scales),
+                            param_dtype=int(half), knot_span=int(extended))
+    np.testing.assert_array_equal(art.table.reshape(I.n_tiles, s.d, I.blob_bytes)[:, 2], one.table.reshape(I.n_tiles, 1, I.blob_bytes)[:, 0])
+    path = str(tmp_path / "per_input.npz")
+    art.save(path)
+    back = lk.lutkan_artifact_load(path)
+    assert back.info.knots_per_input == 1
+    for name in ("q", "scale", "y_min", "knots", "table"):
+        np.testing.assert_array_equal(getattr(back, name), getattr(art, name), err_msg=name)
+    bad = s.ext_knots.copy()
+    bad[3, 4] = bad[3, 3]
+    with pytest.raises(lk.LutKanError) as e:
+        lk.lutkan_compile(s.d, s.m, s.G, s.p, bad, s.coef, s.L, scheme, s.boundary, s.oob, knots_per_input=True)
+    assert str(e.value).startswith("[-1]") and "vector 3" in str(e.value)
+    bad_rows = art.knots.copy()
+    bad_rows[4, 1] = np.nan
+    with pytest.raises(lk.LutKanError) as e:
+        lk.lutkan_artifact_from_arrays(s.d, s.m, bad_rows, art.q, art.scale, art.y_min, s.boundary, s.oob,
+                                       edge_scales=art.edge_scales, param_dtype=int(half), knots_per_input=True)
+    assert str(e.value).startswith("[-1]") and "vector 4" in str(e.value)
+    dl = binding._DevLayer()
+    assert lk.load_library().lutkan_dev_layer_init(art._h, C.byref(dl)) == 0
+    assert dl.knots_per_input == 1 and not dl.input_knots and not dl.table
 
 
 def test_table9_artifact_bytes_from_the_compiler():
