@@ -249,6 +249,19 @@ size_t lutkan_model_workspace_bytes(const lutkan_dev_layer *layers, int32_t n_la
 int lutkan_model_forward(const lutkan_dev_layer *layers, int32_t n_layers, const float *x, int64_t B, float *y,
                          lutkan_oob_stats *stats, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* The same chain as lutkan_model_forward in ONE launch, for narrow networks at small batches (the batch-256 latency
+ * setting of Sec. 8, where the per-layer launches cost more than the arithmetic): one wave carries one row through all
+ * layers, activations stay in LDS, no workspace.  Per (row, input) and per edge the arithmetic is that of
+ * lutkan_forward; only the order of the sum over the inputs differs (interleaved groups of inputs, then a fixed
+ * butterfly), so results agree with lutkan_model_forward to rounding, not bit for bit.
+ *   hidden   device, nullable: receives the activations between the layers, layer after layer, each [B][m_l]
+ *            (sum over l < n_layers-1 of B*m_l floats)
+ *   stats    device, nullable, n_layers entries, ADDED to
+ * EUNSUPPORTED: more than 8 layers, a layer with more than 64 outputs or more than 1024 inputs, or with one knot
+ * vector per input (use lutkan_model_forward).  Other errors as lutkan_model_forward. */
+int lutkan_chain_forward(const lutkan_dev_layer *layers, int32_t n_layers, const float *x, int64_t B, float *y,
+                         float *hidden, lutkan_oob_stats *stats, void *hip_stream);
+
 /* Error statistics of the OOB evaluation protocol (Sec. 5.6 and the accuracy metrics of Sec. 6.5), in one pass on the
  * device: |y - y_ref| over the outputs of the in-range samples (rows whose d inputs all satisfy the domain predicate
  * In(x) of Sec. 5.2 under `boundary` on [t0, tK]) and of the OOB-only samples (rows with at least one input outside;

@@ -71,7 +71,7 @@ EXPORTS = [
     "lutkan_artifact_edge_base_scale", "lutkan_artifact_edge_spline_scale", "lutkan_artifact_edge_out_scale",
     "lutkan_dev_layer_init", "bspline_dev_layer_init", "lutkan_forward_workspace_bytes",
     "bspline_forward_workspace_bytes", "lutkan_forward", "lutkan_forward_trace", "bspline_kan_forward",
-    "lutkan_model_workspace_bytes", "lutkan_model_forward", "lutkan_forward_locate", "lutkan_forward_edges",
+    "lutkan_model_workspace_bytes", "lutkan_model_forward", "lutkan_chain_forward", "lutkan_forward_locate", "lutkan_forward_edges",
     "bspline_forward_locate", "bspline_forward_edges", "lutkan_probe_launch", "lutkan_artifact_from_arrays",
     "lutkan_error_stats_workspace_bytes", "lutkan_error_stats",
 ]
@@ -120,6 +120,7 @@ def load_library():
     lib.lutkan_model_workspace_bytes.argtypes = [C.POINTER(_DevLayer), i32, i64]
     lib.lutkan_model_workspace_bytes.restype = sz
     lib.lutkan_model_forward.argtypes = [C.POINTER(_DevLayer), i32, vp, i64, vp, vp, vp, sz, vp]
+    lib.lutkan_chain_forward.argtypes = [C.POINTER(_DevLayer), i32, vp, i64, vp, vp, vp, vp]
     lib.lutkan_probe_launch.argtypes = [i32, vp, sz, i32, C.POINTER(C.c_double), vp]
     lib.lutkan_error_stats_workspace_bytes.argtypes = [i64]
     lib.lutkan_error_stats_workspace_bytes.restype = sz
@@ -516,6 +517,28 @@ def lutkan_model_forward(layers: List[LutLayer], x, y=None, stats=None, workspac
     _check(load_library().lutkan_model_forward(arr, len(layers), x.data_ptr(), B, y.data_ptr(),
                                                stats.data_ptr() if stats is not None else None,
                                                ws.data_ptr(), ws.numel(), _stream(x.device)))
+    return y
+
+
+def lutkan_chain_forward(layers: List[LutLayer], x, y=None, stats=None, hidden=None):
+    """The chain in one launch (narrow layers, small batches; see lutkan.h).  hidden: optional float32 CUDA tensor of
+    sum_{l < n-1} B*m_l elements that receives the activations between the layers."""
+    torch = _torch()
+    _require(x, torch.float32, "x")
+    B = x.shape[0]
+    arr = (_DevLayer * len(layers))(*[l.c for l in layers])
+    if y is None:
+        y = torch.empty((B, layers[-1].m), dtype=torch.float32, device=x.device)
+    _require(y, torch.float32, "y")
+    if stats is not None:
+        _require(stats, torch.int64, "stats")
+    if hidden is not None:
+        _require(hidden, torch.float32, "hidden")
+        if hidden.numel() < B * sum(l.m for l in layers[:-1]):
+            raise LutKanError("lutkan_chain_forward: hidden is too small")
+    _check(load_library().lutkan_chain_forward(arr, len(layers), x.data_ptr(), B, y.data_ptr(),
+                                               hidden.data_ptr() if hidden is not None else None,
+                                               stats.data_ptr() if stats is not None else None, _stream(x.device)))
     return y
 
 

@@ -77,8 +77,8 @@ __device__ __forceinline__ float next_float_below(float t) {
 // s_knots: the K+1 knots of this element's input in LDS.  With one vector per layer (PERIN false) the comparisons
 // run against the copy in the kernel arguments (scalar registers) and LDS serves the two lookups by the lane's own
 // segment index; with one vector per input every lane reads its own input's row.
-template <bool PERIN>
-__device__ __forceinline__ Located locate_one(const LocateArgs &a, const float *s_knots, float x) {
+template <bool PERIN, typename Args>
+__device__ __forceinline__ Located locate_one(const Args &a, const float *s_knots, float x) {
   Located o;
   const float t0 = PERIN ? s_knots[0] : a.knots[0];
   const float tK = PERIN ? s_knots[a.K] : a.knots[a.K];
@@ -565,6 +565,155 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
           if (j + c < a.m) yout[b * a.m + j + c] = acc[p][c];
       }
     }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Fused chain for narrow networks and small batches (Sec. 5.1 chaining; the batch-256 latency setting of Sec. 8).
+// ------------------------------------------------------------------------------------------------
+// One wave carries one row through every layer; nothing but the input row, the optional hidden activations and
+// the output row touches global memory besides the tables, and the whole network is one launch.  Per layer:
+//   locate   lanes take the layer's inputs 64 at a time (from global memory for the first layer, from the wave's
+//            activation buffer in LDS afterwards), run steps 1-4 of Sec. 4.5 with the same code as the locate
+//            kernel and leave one record per input in the wave's LDS record buffer
+//   edges    the 64 lanes are S = 64/jt groups of jt columns; group s walks the inputs s, s+S, ... (four at a
+//            time, so their table reads are in flight together), a lane accumulates its column over them with
+//            the arithmetic of the gather kernel, and a fixed butterfly over the S groups adds the partial sums
+//   the m sums become the next layer's inputs (LDS), and, if asked for, a row of the hidden-activation trace.
+// A work-group is four waves (four rows) that share the layers' knot vectors in LDS; the barriers between the
+// phases are reached by every wave (all loops over layers are uniform, rows past B are computed on row B-1 and
+// not stored).
+constexpr int kChainWaves = 4;
+constexpr int kChainMaxLayers = 8;
+constexpr int kChainMaxInputs = 1024;     // widest layer input: its records must fit the wave's LDS buffer
+constexpr int kChainMaxColumns = 64;      // widest layer output: one lane per column
+
+struct ChainLayer {
+  const unsigned char *table;
+  int32_t d, m, K, L, jt_log2, blob_bytes;
+  int32_t codes_off, params_off, param_row_bytes;
+  int32_t sym, with_base, param_fp16, closed, zero_spline;
+  float tKs;
+  float knots[LUTKAN_MAX_K + 1];
+};
+
+struct ChainArgs {
+  const float *x;
+  float *y;
+  float *hidden;                   // nullable: the activations between the layers, layer after layer, each [B][m_l]
+  unsigned long long *stats;       // nullable: two counters per layer
+  int64_t B;
+  int32_t n_layers, rec_stride;    // rec_stride: record slots per wave
+  ChainLayer layer[kChainMaxLayers];
+};
+
+__global__ __launch_bounds__(kChainWaves * 64) void lutkan_chain_kernel(const ChainArgs a) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  // LDS: records [waves][rec_stride] of 16 bytes, activations [waves][64] floats, knots [n_layers][MAX_K+1] floats
+  u32x4 *s_rec = reinterpret_cast<u32x4 *>(lds) + (size_t)wave * a.rec_stride;
+  float *s_act = reinterpret_cast<float *>(lds + (size_t)kChainWaves * a.rec_stride * 16) + wave * kChainMaxColumns;
+  float *s_knots = reinterpret_cast<float *>(lds + (size_t)kChainWaves * a.rec_stride * 16) + kChainWaves * kChainMaxColumns;
+  for (int q = threadIdx.x; q < a.n_layers * (LUTKAN_MAX_K + 1); q += kChainWaves * 64) {
+    const int l = q / (LUTKAN_MAX_K + 1), kappa = q - l * (LUTKAN_MAX_K + 1);
+    s_knots[q] = (kappa <= a.layer[l].K) ? a.layer[l].knots[kappa] : 0.0f;
+  }
+  __syncthreads();
+  const int64_t row = (int64_t)blockIdx.x * kChainWaves + wave;
+  const bool live = row < a.B;
+  const int64_t b = live ? row : a.B - 1;
+  int64_t hidden_off = 0;
+
+  for (int l = 0; l < a.n_layers; ++l) {
+    const ChainLayer &Y = a.layer[l];
+    const float *T = s_knots + l * (LUTKAN_MAX_K + 1);
+    // ---- locate: one record per input of this row
+    const unsigned masked_index = (unsigned)(Y.K * Y.L) | ((unsigned)Y.K << 16);
+    unsigned outside = 0;
+    for (int i = lane; i < Y.d; i += 64) {
+      const float x = (l == 0) ? a.x[b * Y.d + i] : s_act[i];
+      const Located o = locate_one<false>(Y, T, x);
+      u32x4 rec = {masked_index, 0u, 0u, 0u};
+      const bool masked = Y.zero_spline && !o.inside && !o.is_nan;
+      if (!masked) {
+        rec.x = (unsigned)(o.k * Y.L + o.l0) | ((unsigned)o.k << 16);
+        rec.y = __float_as_uint(o.is_nan ? __builtin_nanf("") : o.w);
+      }
+      if (Y.with_base) rec.z = __float_as_uint(__fdiv_rn(x, 1.0f + expf(-x)));          // SiLU at the raw input, never masked
+      s_rec[i] = rec;
+      outside += o.inside ? 0u : 1u;
+    }
+    if (a.stats) {                                       // Sec. 5.5 counters of this layer
+      for (int off = 32; off > 0; off >>= 1) outside += __shfl_down(outside, off, kWave);
+      if (lane == 0 && live && outside) {
+        atomicAdd(&a.stats[2 * l], (unsigned long long)outside);
+        atomicAdd(&a.stats[2 * l + 1], 1ull);
+      }
+    }
+    __syncthreads();                                     // records written (and the activations they came from read)
+
+    // ---- edges: lane = (group s, column jj); group s takes the inputs s, s + S, ...
+    const int jt = 1 << Y.jt_log2;
+    const int jj = lane & (jt - 1);
+    const int s = lane >> Y.jt_log2;
+    const int S = 64 >> Y.jt_log2;
+    constexpr int U = 4;                                 // eight at a time was measured no faster
+    float acc = 0.0f;
+    for (int i0 = s; i0 < Y.d; i0 += U * S) {
+      u32x4 rec[U];
+      unsigned c0[U], c1[U];
+      float al[U], ym[U], bg[U], sg[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int i = min(i0 + u * S, Y.d - 1);
+        rec[u] = s_rec[i];
+        const unsigned char *slice = Y.table + (size_t)i * Y.blob_bytes;
+        const unsigned code_off = (unsigned)Y.codes_off + (rec[u].x & 0xffffu) * (unsigned)jt;
+        const unsigned param_off = (unsigned)Y.params_off + (rec[u].x >> 16) * (unsigned)Y.param_row_bytes;
+        c0[u] = slice[code_off + jj];
+        c1[u] = slice[code_off + jt + jj];
+        if (Y.param_fp16) {
+          const _Float16 *prm = reinterpret_cast<const _Float16 *>(slice + param_off);
+          al[u] = (float)prm[jj];
+          ym[u] = Y.sym ? 0.0f : (float)prm[jt + jj];
+        } else {
+          const float *prm = reinterpret_cast<const float *>(slice + param_off);
+          al[u] = prm[jj];
+          ym[u] = Y.sym ? 0.0f : prm[jt + jj];
+        }
+        bg[u] = Y.with_base ? reinterpret_cast<const float *>(slice)[jj] : 0.0f;
+        sg[u] = (Y.with_base && Y.param_fp16) ? reinterpret_cast<const float *>(slice)[jt + jj] : 1.0f;
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (i0 + u * S < Y.d) {
+          const float w = __uint_as_float(rec[u].y);
+          const float bias = Y.sym ? 128.0f : 0.0f;                           // int8 codes are stored excess-128
+          const float f0 = (float)c0[u] - bias, f1 = (float)c1[u] - bias;
+          const float tq = fmaf(w, f1 - f0, f0);                               // Eq. 17 on the codes ...
+          if (Y.with_base && Y.param_fp16) {
+            acc = fmaf(sg[u], fmaf(al[u], tq, ym[u]), acc);
+          } else {
+            acc = fmaf(al[u], tq, acc);                                        // ... Eq. 10 once per edge
+            if (!Y.sym) acc += ym[u];
+          }
+          if (Y.with_base) acc = fmaf(bg[u], __uint_as_float(rec[u].z), acc);  // + s_out*s_base * SiLU(x)
+        }
+      }
+    }
+    for (int off = jt; off < 64; off <<= 1) acc += __shfl_xor(acc, off, kWave);          // fixed order over the groups
+    const bool last = (l + 1 == a.n_layers);
+    if (s == 0 && jj < Y.m) {
+      if (last) {
+        if (live) a.y[b * Y.m + jj] = acc;
+      } else {
+        s_act[jj] = acc;
+        if (a.hidden && live) a.hidden[hidden_off + b * Y.m + jj] = acc;
+      }
+    }
+    hidden_off += a.B * Y.m;
+    __syncthreads();                                     // the next layer's inputs are in place, its records may be overwritten
   }
 }
 
@@ -1307,6 +1456,55 @@ extern "C" size_t lutkan_model_workspace_bytes(const lutkan_dev_layer *layers, i
     scratch = std::max(scratch, lutkan_forward_workspace_bytes(&layers[l], B));
   }
   return 2 * act + scratch;
+}
+
+extern "C" int lutkan_chain_forward(const lutkan_dev_layer *layers, int32_t n_layers, const float *x, int64_t B, float *y,
+                                    float *hidden, lutkan_oob_stats *stats, void *hip_stream) {
+  const char *who = "lutkan_chain_forward";
+  if (!layers || n_layers < 1) return fail(LUTKAN_EINVAL, "%s: need at least one layer", who);
+  if (n_layers > kChainMaxLayers) return fail(LUTKAN_EUNSUPPORTED, "%s: at most %d layers (got %d)", who, kChainMaxLayers, n_layers);
+  ChainArgs ca = {};
+  int widest = 0;
+  for (int l = 0; l < n_layers; ++l) {
+    const lutkan_dev_layer *L = &layers[l];
+    if (int rc = validate_layer(L, who)) return rc;
+    if (l + 1 < n_layers && L->m != layers[l + 1].d) return fail(LUTKAN_ESHAPE, "%s: layer %d has m=%d but layer %d has d=%d", who, l, L->m, l + 1, layers[l + 1].d);
+    if (L->n_tiles != 1 || L->jt > kChainMaxColumns) return fail(LUTKAN_EUNSUPPORTED, "%s: layer %d has %d outputs, the fused chain takes at most %d per layer", who, l, L->m, kChainMaxColumns);
+    if (L->d > kChainMaxInputs) return fail(LUTKAN_EUNSUPPORTED, "%s: layer %d has %d inputs, the fused chain takes at most %d", who, l, L->d, kChainMaxInputs);
+    if (L->knots_per_input) return fail(LUTKAN_EUNSUPPORTED, "%s: layer %d has one knot vector per input; use lutkan_model_forward", who, l);
+    const lutkan::BlobLayout lay = lutkan::blob_layout(L->K, L->L, L->jt, L->scheme, L->value_repr, L->param_dtype);
+    ChainLayer &c = ca.layer[l];
+    c.table = static_cast<const unsigned char *>(L->table);
+    c.d = L->d; c.m = L->m; c.K = L->K; c.L = L->L; c.blob_bytes = L->blob_bytes;
+    c.jt_log2 = 0;
+    while ((1 << c.jt_log2) < L->jt) ++c.jt_log2;
+    c.codes_off = lay.codes_off; c.params_off = lay.params_off; c.param_row_bytes = lay.param_row_bytes;
+    c.sym = (L->scheme == LUTKAN_SYM_INT8);
+    c.with_base = (L->value_repr == LUTKAN_REPR_SPLINE_COMPONENT);
+    c.param_fp16 = (L->param_dtype == LUTKAN_PARAM_FP16);
+    c.closed = (L->boundary == LUTKAN_CLOSED);
+    c.zero_spline = (L->oob == LUTKAN_ZERO_SPLINE);
+    c.tKs = c.closed ? L->knots[L->K] : std::nextafterf(L->knots[L->K], -INFINITY);
+    for (int k = 0; k <= L->K; ++k) c.knots[k] = L->knots[k];
+    widest = std::max(widest, L->d);
+  }
+  if (B < 0) return fail(LUTKAN_EINVAL, "%s: B < 0", who);
+  if (B == 0) return LUTKAN_OK;
+  if (!x || !y || x == y) return fail(LUTKAN_EINVAL, "%s: null or aliased x / y", who);
+  const int64_t groups = (B + kChainWaves - 1) / kChainWaves;
+  if (groups > 0x7fffffff) return fail(LUTKAN_EUNSUPPORTED, "%s: B too large", who);
+  ca.x = x; ca.y = y; ca.hidden = hidden;
+  ca.stats = reinterpret_cast<unsigned long long *>(stats);
+  ca.B = B; ca.n_layers = n_layers; ca.rec_stride = widest;
+  const size_t lds = (size_t)kChainWaves * widest * 16 + (size_t)kChainWaves * kChainMaxColumns * 4 + (size_t)n_layers * (LUTKAN_MAX_K + 1) * 4;
+  static bool raised = false;   // the default cap on dynamic LDS (64 KiB) is below what the widest supported layer needs
+  if (!raised) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(lutkan_chain_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kMaxTiledLds);
+    if (e != hipSuccess) return fail(LUTKAN_EHIP, "%s: hipFuncSetAttribute(LDS): %s", who, hipGetErrorString(e));
+    raised = true;
+  }
+  hipLaunchKernelGGL(lutkan_chain_kernel, dim3((unsigned)groups), dim3(kChainWaves * 64), lds, static_cast<hipStream_t>(hip_stream), ca);
+  return check_launch("lutkan_chain_kernel");
 }
 
 extern "C" int lutkan_model_forward(const lutkan_dev_layer *layers, int32_t n_layers, const float *x, int64_t B, float *y,

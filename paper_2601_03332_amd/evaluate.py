@@ -13,6 +13,7 @@ the LUT layer against the B-spline layer and the time of both per point: the lat
 With --cold-start it times the tabular chain 78 -> 16 -> 2 (L = 64 asymmetric uint8, batch 65536) twice, as the
 latency metrics of Sec. 6.5 distinguish: steady state (tables resident on the GPU) and cold start (every iteration
 reads the NPZ artifacts, rebuilds the device tables and uploads them before the forward).
+With --latency it times narrow chains at batches 1 .. 65536 as per-layer launches and as the fused one-launch chain.
 Both layers and the error statistics (lutkan_error_stats, Sec. 5.6) run as the library's HIP kernels.  The layers
 are randomly initialised here, so the absolute numbers are not the paper's; the trends are (error halves per
 doubling of L; in-range error independent of the contract; half_open counts inputs clipped onto t_K as OOB).
@@ -30,6 +31,7 @@ def main():
     ap.add_argument("--batch", type=int, default=4096)
     ap.add_argument("--sweep", action="store_true", help="also run the 256->256 L x scheme sweep with timings")
     ap.add_argument("--cold-start", action="store_true", help="also time steady-state vs cold-start latency of the 78->16->2 chain")
+    ap.add_argument("--latency", action="store_true", help="also time narrow chains at small batches: per-layer launches vs the fused chain")
     args = ap.parse_args()
     import torch
 
@@ -143,6 +145,53 @@ def main():
         print()
         print(f"78 -> 16 -> 2, L = 64 asymmetric uint8, batch {B}: steady state {t_steady:.3f} ms/iter "
               f"({t_steady / B * 1e6:.3f} ns/sample), cold start {t_cold:.3f} ms/iter (NPZ artifacts: {size} bytes)")
+
+    if args.latency:
+        import time
+
+        from lutkan_inputs import LayerSpec, draw_edge_scales, uniform_ext_knots
+
+        def chain(widths, scheme, with_base, half):
+            rng = np.random.Generator(np.random.PCG64(5))
+            arts = []
+            for d, m in zip(widths[:-1], widths[1:]):
+                coef = rng.normal(0.0, 1.0 / np.sqrt(d), size=(d, m, 8)).astype(np.float32)
+                sc = draw_edge_scales(rng, d, m) if with_base else None
+                arts.append(lk.lutkan_compile(d, m, 5, 3, uniform_ext_knots(-3.0, 3.0, 5, 3), coef, 64, scheme, CLOSED, CLIP_X,
+                                              edge_scales=sc, param_dtype=lk.PARAM_FP16 if half else lk.PARAM_FP32))
+            return [a.to_device(dev) for a in arts]
+
+        def per_call_ms(fn, n):
+            for _ in range(10):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(n):
+                fn()
+                torch.cuda.synchronize()
+            wall = (time.perf_counter() - t0) / n * 1e3
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(n):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return wall, e0.elapsed_time(e1) / n
+
+        print()
+        print("Narrow chains, L = 64, grid 5: ms per forward, synchronised after every call | back to back on the stream")
+        print(f"{'network':>18} {'options':>28} {'batch':>7} {'per-layer launches':>22} {'fused chain':>22}")
+        for widths, scheme, base, half, label in (((78, 16, 2), ASYM_UINT8, False, False, "uint8 phi fp32"),
+                                                  ((78, 32, 16, 1), SYM_INT8, True, False, "int8 spline_component fp32"),
+                                                  ((78, 32, 16, 1), ASYM_UINT8, True, True, "uint8 spline_component fp16")):
+            layers = chain(widths, scheme, base, half)
+            for B in (1, 256, 4096, 65536):
+                x = torch.randn((B, widths[0]), dtype=torch.float32, device=dev)
+                y = torch.empty((B, widths[-1]), dtype=torch.float32, device=dev)
+                ws = torch.empty(lk.lutkan_model_workspace_bytes(layers, B), dtype=torch.uint8, device=dev)
+                a = per_call_ms(lambda: lk.lutkan_model_forward(layers, x, y, workspace=ws), 200)
+                f = per_call_ms(lambda: lk.lutkan_chain_forward(layers, x, y), 200)
+                print(f"{'->'.join(map(str, widths)):>18} {label:>28} {B:>7} {a[0]:>10.4f} | {a[1]:<9.4f} {f[0]:>10.4f} | {f[1]:<9.4f}")
 
 
 if __name__ == "__main__":

@@ -638,3 +638,101 @@ def test_random_shapes_and_contracts():
         refb = oracle.bspline_forward(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.boundary, s.oob, w.x, edge_scalars=s.edge_scales)
         worst = max(worst, _assert_close(yb.cpu().numpy(), refb, w.name + " bspline"))
     _say(f"random layers: worst error / tolerance = {worst:.3f}")
+
+
+# ---- fused chain: the whole narrow network in one launch ----
+
+def _narrow_chain(seed, widths, G, L, scheme, boundary, oob, B, with_base=False, lo=-2.0, hi=2.0):
+    """Layers of a narrow network on [lo, hi] with coefficients ~ N(0, 1/sqrt(d)); x ~ N(0,1) with heavy tails."""
+    from lutkan_inputs import LayerSpec, draw_edge_scales, uniform_ext_knots
+    rng = np.random.Generator(np.random.PCG64(seed))
+    layers = []
+    for d, m in zip(widths[:-1], widths[1:]):
+        coef = rng.normal(0.0, 1.0 / np.sqrt(d), size=(d, m, G + 3)).astype(np.float32)
+        s = LayerSpec(d, m, G, 3, uniform_ext_knots(lo, hi, G, 3), coef, L, scheme, boundary, oob)
+        if with_base:
+            s.edge_scales = draw_edge_scales(rng, d, m)
+        layers.append(s)
+    x = np.where(rng.random((B, widths[0])) < 0.1, rng.standard_t(3.0, size=(B, widths[0])), rng.normal(size=(B, widths[0]))).astype(np.float32)
+    return layers, x
+
+
+def _fused_chain_check(specs, x, what, param_fp16=False):
+    """Every layer of the fused launch against the oracle on the SAME input (the launch's own hidden activation of
+    the previous layer), its counters against the oracle's, and the result against the layer-by-layer chain."""
+    compiled = [_compile_both_uncached(s, param_fp16) for s in specs]
+    layers = [_device_layer(art, s) for s, (art, _) in zip(specs, compiled)]
+    B = x.shape[0]
+    xg = torch.from_numpy(x).to(DEV)
+    hidden = torch.full((B * sum(s.m for s in specs[:-1]) + 1,), float("nan"), dtype=torch.float32, device=DEV)
+    stats = torch.zeros((len(specs), 2), dtype=torch.int64, device=DEV)
+    _say(f"case {what}: fused chain {[s.d for s in specs] + [specs[-1].m]} B={B} fp16={param_fp16}")
+    y = lk.lutkan_chain_forward(layers, xg, stats=stats, hidden=hidden)
+    y_plain = lk.lutkan_chain_forward(layers, xg)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y_plain) or np.array_equal(np.isnan(y.cpu().numpy()), np.isnan(y_plain.cpu().numpy()))
+    h = hidden.cpu().numpy()
+    assert np.isnan(h[-1])                                # nothing written past the trace
+    cur, off, worst = x, 0, 0.0
+    for li, (s, (art, ora)) in enumerate(zip(specs, compiled)):
+        ref = oracle.lut_forward(ora, s.boundary, s.oob, cur, edge_scalars=s.edge_scales)
+        if li + 1 < len(specs):
+            nxt = h[off:off + B * s.m].reshape(B, s.m)
+            off += B * s.m
+        else:
+            nxt = y.cpu().numpy()
+        worst = max(worst, _assert_close(nxt, ref, f"{what} layer {li}"))
+        st = stats[li].cpu().numpy()
+        assert (int(st[0]), int(st[1])) == (ref.oob_count, ref.oob_any_rows), f"{what} layer {li} counters"
+        cur = nxt
+    y_model = lk.lutkan_model_forward(layers, xg).cpu().numpy()
+    scale = np.abs(y_model[np.isfinite(y_model)]).max() if np.isfinite(y_model).any() else 1.0
+    ok = np.isfinite(y_model)
+    assert np.abs(y.cpu().numpy()[ok] - y_model[ok]).max() <= 1e-3 * max(scale, 1.0)
+    return worst
+
+
+def _compile_both_uncached(s, param_fp16):
+    art = lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, s.boundary, s.oob,
+                            edge_scales=s.edge_scales, param_dtype=lk.PARAM_FP16 if param_fp16 else lk.PARAM_FP32)
+    ora = oracle.compile_layer(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, param_fp16=param_fp16)
+    assert np.array_equal(art.q, ora.q) and np.array_equal(art.scale, ora.scale) and np.array_equal(art.y_min, ora.y_min)
+    return art, ora
+
+
+FUSED_CHAIN_CASES = [
+    # seed, widths, G, L, scheme, boundary, oob, B, with_base, param_fp16
+    (901, (78, 16, 2), 5, 64, ASYM_UINT8, CLOSED, CLIP_X, 256, False, False),          # the tabular shape at the latency batch
+    (902, (78, 32, 16, 1), 5, 64, SYM_INT8, CLOSED, CLIP_X, 256, True, False),         # the case study's network (Sec. 8)
+    (903, (78, 32, 16, 1), 5, 64, ASYM_UINT8, HALF_OPEN, ZERO_SPLINE, 1027, True, True),
+    (904, (10, 8), 8, 16, SYM_INT8, HALF_OPEN, ZERO_SPLINE, 1, False, False),           # one layer, one row
+    (905, (5, 64, 3, 64, 4), 3, 8, ASYM_UINT8, CLOSED, ZERO_SPLINE, 3, False, True),    # 64-column layers, one group per wave
+    (906, (1024, 4, 1), 4, 32, SYM_INT8, CLOSED, CLIP_X, 70, False, False),             # the widest input, 16 groups of inputs
+    (907, (3, 5, 7, 9, 11, 13, 15, 17, 2), 6, 16, ASYM_UINT8, HALF_OPEN, CLIP_X, 4099, True, False),   # eight layers
+]
+
+
+@pytest.mark.parametrize("case", FUSED_CHAIN_CASES, ids=lambda c: f"seed{c[0]}")
+def test_fused_chain(case):
+    seed, widths, G, L, scheme, boundary, oob, B, with_base, half = case
+    specs, x = _narrow_chain(seed, widths, G, L, scheme, boundary, oob, B, with_base)
+    if B > 10:
+        x[B // 2, 0] = np.nan                       # poisons its own row only
+        x[B // 3, :] = 50.0                         # every input out of domain
+    _fused_chain_check(specs, x, f"fused seed{seed}", half)
+
+
+def test_fused_chain_refuses_what_it_cannot_hold():
+    specs, x = _narrow_chain(920, (8, 128, 4), 4, 8, SYM_INT8, CLOSED, CLIP_X, 8)
+    layers = [_device_layer(_compile_both_uncached(s, False)[0], s) for s in specs]
+    xg = torch.from_numpy(x).to(DEV)
+    with pytest.raises(lk.LutKanError) as e:        # a 128-column layer
+        lk.lutkan_chain_forward(layers, xg)
+    assert str(e.value).startswith("[-5]")
+    with pytest.raises(lk.LutKanError) as e:        # widths that do not chain
+        lk.lutkan_chain_forward([layers[0], layers[0]], xg)
+    assert str(e.value).startswith("[-2]")
+    w = per_input_layer(921, 4, 4, 5, 8, SYM_INT8, CLOSED, CLIP_X, 16)
+    with pytest.raises(lk.LutKanError) as e:        # one knot vector per input
+        lk.lutkan_chain_forward([_device_layer(_compile_both(w.layers[0])[0], w.layers[0])], torch.from_numpy(w.x).to(DEV))
+    assert str(e.value).startswith("[-5]")

@@ -174,6 +174,24 @@ def test_forward_argument_validation_happens_before_any_launch():
     assert lib.lutkan_forward(C.byref(dl), 16, 4, 32, None, 256, 1 << 20, None) == -1
     two = (binding._DevLayer * 2)(dl, dl)
     assert lib.lutkan_model_forward(two, 2, 16, 4, 32, None, 256, 1 << 20, None) == -2     # m of layer 0 != d of layer 1
+    # the fused chain: same checks, plus the shapes it cannot hold
+    assert lib.lutkan_chain_forward(two, 2, 16, 4, 32, None, None, None) == -1             # the knots are still broken
+    dl.knots[2] = np.float32(0.5 * (dl.knots[1] + dl.knots[3]))
+    two, one = (binding._DevLayer * 2)(dl, dl), (binding._DevLayer * 1)(dl)
+    assert lib.lutkan_chain_forward(two, 2, 16, 4, 32, None, None, None) == -2
+    assert lib.lutkan_chain_forward(one, 1, 16, 0, 32, None, None, None) == 0               # B == 0: no-op
+    assert lib.lutkan_chain_forward(one, 1, None, 4, 32, None, None, None) == -1
+    assert lib.lutkan_chain_forward(one, 1, 16, 4, 16, None, None, None) == -1              # x and y alias
+    assert lib.lutkan_chain_forward(one, 0, 16, 4, 32, None, None, None) == -1
+    nine = (binding._DevLayer * 9)(*([dl] * 9))
+    assert lib.lutkan_chain_forward(nine, 9, 16, 4, 32, None, None, None) == -5             # more than eight layers
+    wide = cfg5().layers[1]                                                                  # 128 -> 128
+    wl = binding._DevLayer()
+    wide_art = _both(wide)[0]                                                               # stays alive across the call
+    lib.lutkan_dev_layer_init(wide_art._h, C.byref(wl))
+    wl.table = 4096
+    assert lib.lutkan_chain_forward((binding._DevLayer * 1)(wl), 1, 16, 4, 32, None, None, None) == -5
+    assert "at most 64" in lk.lutkan_last_error()
 
 
 def test_spline_component_tables_carry_the_base_row_and_folded_gains():
