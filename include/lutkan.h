@@ -96,7 +96,7 @@ typedef struct lutkan_artifact lutkan_artifact;     /* opaque, host memory */
 
 typedef struct {
   int32_t d, m, K, L, G, degree, scheme, boundary, oob, value_repr, param_dtype, knot_span, knots_per_input;
-  int32_t jt;                /* column-tile width of the device tables (a power of two <= 128, or 128) */
+  int32_t jt;                /* column-tile width of the device tables: a power of two in 4 .. 128 */
   int32_t n_tiles;           /* ceil(m / jt) */
   int32_t blob_bytes;        /* bytes of one (tile, input) slice of the LUT device table */
   int32_t coef_blob_bytes;   /* bytes of one (tile, input) slice of the B-spline device table */

@@ -33,8 +33,11 @@ int fail(int code, const char *fmt, ...) {
 int choose_jt(int m, int K, int L, int scheme, int value_repr, int param_dtype) {
   int jt = 4;
   while (jt < m && jt < 128) jt *= 2;
-  while (jt > 32 && blob_layout(K, L, jt, scheme, value_repr, param_dtype).bytes > kLdsSliceBudget) jt /= 2;
-  return jt;
+  int fit = jt;
+  while (fit > 4 && blob_layout(K, L, fit, scheme, value_repr, param_dtype).bytes > kLdsSliceBudget) fit /= 2;
+  if (blob_layout(K, L, fit, scheme, value_repr, param_dtype).bytes <= kLdsSliceBudget) return fit;
+  return jt < 32 ? jt : 32;   // no width fits: the gather kernel, which is fastest on 32-column tiles
+
 }
 
 namespace {

@@ -40,8 +40,9 @@ inline int coef_slice_rows(int R, int value_repr) { return R + (value_repr == LU
 // 160 KiB of LDS of a gfx950 CU.
 constexpr int kLdsSliceBudget = 56 * 1024;
 
-// Column-tile width for a layer: the widest of 128 / 64 / 32 columns whose slice fits the LDS budget (32 if
-// none does; such layers run on the gather kernel), and for narrow layers the next power of two >= m (>= 4).
+// Column-tile width for a layer: the widest power of two in 4 .. 128 (not wider than the next power of two >= m)
+// whose slice fits the LDS budget; a table of 4096 rows still runs on the tiled kernel, 8 columns at a time, twice
+// as fast as on the gather kernel.  If not even 4 columns fit: 32 (or the layer's width), for the gather kernel.
 int choose_jt(int m, int K, int L, int scheme, int value_repr, int param_dtype);
 
 }  // namespace lutkan

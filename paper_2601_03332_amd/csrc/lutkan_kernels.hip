@@ -1469,7 +1469,7 @@ extern "C" int lutkan_chain_forward(const lutkan_dev_layer *layers, int32_t n_la
     const lutkan_dev_layer *L = &layers[l];
     if (int rc = validate_layer(L, who)) return rc;
     if (l + 1 < n_layers && L->m != layers[l + 1].d) return fail(LUTKAN_ESHAPE, "%s: layer %d has m=%d but layer %d has d=%d", who, l, L->m, l + 1, layers[l + 1].d);
-    if (L->n_tiles != 1 || L->jt > kChainMaxColumns) return fail(LUTKAN_EUNSUPPORTED, "%s: layer %d has %d outputs, the fused chain takes at most %d per layer", who, l, L->m, kChainMaxColumns);
+    if (L->n_tiles != 1 || L->jt > kChainMaxColumns) return fail(LUTKAN_EUNSUPPORTED, "%s: layer %d has %d outputs in %d column tiles, the fused chain takes one tile of at most %d columns", who, l, L->m, L->n_tiles, kChainMaxColumns);
     if (L->d > kChainMaxInputs) return fail(LUTKAN_EUNSUPPORTED, "%s: layer %d has %d inputs, the fused chain takes at most %d", who, l, L->d, kChainMaxInputs);
     if (L->knots_per_input) return fail(LUTKAN_EUNSUPPORTED, "%s: layer %d has one knot vector per input; use lutkan_model_forward", who, l);
     const lutkan::BlobLayout lay = lutkan::blob_layout(L->K, L->L, L->jt, L->scheme, L->value_repr, L->param_dtype);

@@ -127,6 +127,9 @@ TILED_CASES = [
     (206, 64, 256, 8, 128, ASYM_UINT8, HALF_OPEN, CLIP_X, 9000),
     (207, 3, 1000, 10, 64, SYM_INT8, CLOSED, CLIP_X, 20000),         # enough rows for the 32-rows-per-wave variant
     (208, 1, 128, 2, 2, ASYM_UINT8, CLOSED, CLIP_X, 1),
+    (209, 7, 70, 16, 128, SYM_INT8, CLOSED, CLIP_X, 1500),           # 2048 table rows: 16-column tiles of a wide layer
+    (210, 5, 50, 32, 128, ASYM_UINT8, HALF_OPEN, ZERO_SPLINE, 2100), # 4096 table rows: 8-column tiles, ragged last tile
+    (211, 3, 21, 64, 200, SYM_INT8, HALF_OPEN, CLIP_X, 300),         # 12800 table rows: 4-column tiles
 ]
 
 
@@ -136,6 +139,19 @@ def test_property_layers_tiled(case):
     w = random_layer(seed, d, m, G, L, scheme, boundary, oob, B, uniform=(seed % 2 == 0))
     _check_layer(w.layers[0], w.x, lk.ALGO_TILED, what=w.name)
     _check_layer(w.layers[0], w.x, lk.ALGO_GATHER, what=w.name)
+
+
+def test_table_too_large_for_any_tile_runs_on_the_gather_kernel():
+    """32768 table rows: not even a 4-column slice fits the LDS budget; AUTO takes the gather kernel on 32-column
+    tiles, and asking for the tiled kernel is an error, not a silent fallback."""
+    w = random_layer(212, 2, 40, 64, 512, ASYM_UINT8, CLOSED, ZERO_SPLINE, 257)
+    s = w.layers[0]
+    _check_layer(s, w.x, lk.ALGO_AUTO, what=w.name)
+    art = _compile_both(s)[0]
+    assert art.info.jt == 32 and art.info.blob_bytes > 56 * 1024
+    with pytest.raises(lk.LutKanError) as e:
+        lk.lutkan_forward(_device_layer(art, s, lk.ALGO_TILED), torch.from_numpy(w.x).to(DEV))
+    assert str(e.value).startswith("[-5]")
 
 
 FP16_PARAM_CASES = [

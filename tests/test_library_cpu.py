@@ -191,7 +191,7 @@ def test_forward_argument_validation_happens_before_any_launch():
     lib.lutkan_dev_layer_init(wide_art._h, C.byref(wl))
     wl.table = 4096
     assert lib.lutkan_chain_forward((binding._DevLayer * 1)(wl), 1, 16, 4, 32, None, None, None) == -5
-    assert "at most 64" in lk.lutkan_last_error()
+    assert "at most 64 columns" in lk.lutkan_last_error()
 
 
 def test_spline_component_tables_carry_the_base_row_and_folded_gains():
@@ -431,6 +431,19 @@ def test_knots_per_input_compile_like_the_oracle(scheme, extended, half, base, t
     dl = binding._DevLayer()
     assert lk.load_library().lutkan_dev_layer_init(art._h, C.byref(dl)) == 0
     assert dl.knots_per_input == 1 and not dl.input_knots and not dl.table
+
+
+def test_tile_width_follows_the_table_size():
+    """The widest power of two in 4..128 whose slice fits 56 KiB of LDS; 32 (gather kernel) if not even 4 columns fit."""
+    rng = np.random.Generator(np.random.PCG64(3))
+    for G, L, m, want in ((8, 64, 300, 64), (8, 128, 300, 32), (16, 128, 300, 16), (32, 128, 300, 8), (64, 200, 300, 4),
+                          (64, 512, 300, 32), (64, 512, 10, 16), (8, 16, 300, 128), (8, 16, 5, 8), (32, 128, 3, 4)):
+        tau = np.linspace(-1.0, 1.0, G + 7).astype(np.float32)
+        art = lk.lutkan_compile(1, m, G, 3, tau, rng.normal(size=(1, m, G + 3)).astype(np.float32), L, SYM_INT8, CLOSED, CLIP_X)
+        I = art.info
+        assert I.jt == want, (G, L, m, I.jt, want)
+        assert I.n_tiles == -(-m // I.jt) and I.table_bytes == I.n_tiles * I.blob_bytes
+        assert (I.blob_bytes <= 56 * 1024) == (not (G == 64 and L == 512))
 
 
 def test_table9_artifact_bytes_from_the_compiler():
