@@ -272,6 +272,43 @@ def main():
         log(f"[bench] bspline_kan_forward: {bs_ms:.3f} ms/step -> LUT is {bs_ms / ms_per_step:.2f}x the B-spline layer")
         del wsb
 
+    if not args.no_bspline:
+        # The tabular chain 78 -> 16 -> 2 (L = 64 asymmetric uint8): throughput at batch 65536 through the per-layer
+        # launches, and latency at batch 256 (the batch of the paper's deployment measurements, Sec. 8) through the
+        # per-layer launches and through the fused one-launch chain.
+        from lutkan_inputs import cfg2
+        w2 = cfg2(seed=0)
+        chain = [lk.lutkan_compile(c.d, c.m, c.G, c.p, c.ext_knots, c.coef, c.L, c.scheme, c.boundary, c.oob).to_device(dev)
+                 for c in w2.layers]
+        x2 = torch.from_numpy(w2.x).to(dev)
+
+        def chain_ms(fn, n=50):
+            for _ in range(5):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(n):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / n
+
+        B2 = x2.shape[0]
+        y2 = torch.empty((B2, 2), dtype=torch.float32, device=dev)
+        ws2 = torch.empty(lk.lutkan_model_workspace_bytes(chain, B2), dtype=torch.uint8, device=dev)
+        full_ms = chain_ms(lambda: lk.lutkan_model_forward(chain, x2, y2, workspace=ws2))
+        xs256, ys256 = x2[:256].contiguous(), y2[:256].contiguous()
+        layers_ms = chain_ms(lambda: lk.lutkan_model_forward(chain, xs256, ys256, workspace=ws2))
+        fused_ms = chain_ms(lambda: lk.lutkan_chain_forward(chain, xs256, ys256))
+        chain_edges = sum(c.d * c.m for c in w2.layers)
+        extra["tabular_chain_78_16_2"] = {"batch_65536_ms": round(full_ms, 4),
+                                          "batch_65536_edge_evals_per_s": round(B2 * chain_edges / (full_ms * 1e-3), 1),
+                                          "batch_256_per_layer_launches_ms": round(layers_ms, 4),
+                                          "batch_256_fused_chain_ms": round(fused_ms, 4)}
+        log(f"[bench] 78->16->2: batch {B2} {full_ms:.3f} ms; batch 256: {layers_ms:.4f} ms per-layer launches, "
+            f"{fused_ms:.4f} ms fused chain")
+        del chain, x2, y2, ws2
+
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
