@@ -250,8 +250,8 @@ int lutkan_model_forward(const lutkan_dev_layer *layers, int32_t n_layers, const
                          lutkan_oob_stats *stats, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* The same chain as lutkan_model_forward in ONE launch, for narrow networks at small batches (the batch-256 latency
- * setting of Sec. 8, where the per-layer launches cost more than the arithmetic): one wave carries one row through all
- * layers, activations stay in LDS, no workspace.  Per (row, input) and per edge the arithmetic is that of
+ * setting of Sec. 8, where the per-layer launches cost more than the arithmetic): a work-group (up to 1024 rows) or a
+ * wave (beyond) carries one row through all layers, activations stay in LDS, no workspace.  Per (row, input) and per edge the arithmetic is that of
  * lutkan_forward; only the order of the sum over the inputs differs (interleaved groups of inputs, then a fixed
  * butterfly), so results agree with lutkan_model_forward to rounding, not bit for bit.
  *   hidden   device, nullable: receives the activations between the layers, layer after layer, each [B][m_l]

@@ -571,21 +571,23 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
 // ------------------------------------------------------------------------------------------------
 // Fused chain for narrow networks and small batches (Sec. 5.1 chaining; the batch-256 latency setting of Sec. 8).
 // ------------------------------------------------------------------------------------------------
-// One wave carries one row through every layer; nothing but the input row, the optional hidden activations and
-// the output row touches global memory besides the tables, and the whole network is one launch.  Per layer:
-//   locate   lanes take the layer's inputs 64 at a time (from global memory for the first layer, from the wave's
+// WPR waves (4 or 1) carry one row through every layer; nothing but the input row, the optional hidden activations
+// and the output row touches global memory besides the tables, and the whole network is one launch.  Per layer:
+//   locate   the row's WPR*64 lanes take the layer's inputs (from global memory for the first layer, from the row's
 //            activation buffer in LDS afterwards), run steps 1-4 of Sec. 4.5 with the same code as the locate
-//            kernel and leave one record per input in the wave's LDS record buffer
-//   edges    the 64 lanes are S = 64/jt groups of jt columns; group s walks the inputs s, s+S, ... (four at a
-//            time, so their table reads are in flight together), a lane accumulates its column over them with
-//            the arithmetic of the gather kernel, and a fixed butterfly over the S groups adds the partial sums
+//            kernel and leave one record per input in the row's LDS record buffer
+//   edges    a wave is S = 64/jt groups of jt columns, the row's waves WPR*S groups; group g walks the inputs g,
+//            g + WPR*S, ... (four at a time, so their table reads are in flight together), a lane accumulates its
+//            column over them with the arithmetic of the gather kernel; a fixed butterfly adds the groups of a wave,
+//            and with WPR = 4 the four waves' sums are added in wave order through LDS
 //   the m sums become the next layer's inputs (LDS), and, if asked for, a row of the hidden-activation trace.
-// A work-group is four waves (four rows) that share the layers' knot vectors in LDS; the barriers between the
-// phases are reached by every wave (all loops over layers are uniform, rows past B are computed on row B-1 and
-// not stored).
-constexpr int kChainWaves = 4;
+// A work-group is four waves: one row (WPR = 4) or four rows (WPR = 1).  Splitting a row's inputs over four waves
+// shortens the chain of dependent table reads per layer, which is what a small batch waits for; one wave per row
+// moves a quarter of the work-groups through the GPU and wins from a few thousand rows on.  Every barrier is reached
+// by every thread: all loops over layers are uniform, rows past B are computed on row B-1 and not stored.
+constexpr int kChainWaves = 4;          // the sum over the waves below is written out for four
 constexpr int kChainMaxLayers = 8;
-constexpr int kChainMaxInputs = 1024;     // widest layer input: its records must fit the wave's LDS buffer
+constexpr int kChainMaxInputs = 1024;     // widest layer input: its records must fit the LDS record buffer
 constexpr int kChainMaxColumns = 64;      // widest layer output: one lane per column
 
 struct ChainLayer {
@@ -603,24 +605,35 @@ struct ChainArgs {
   float *hidden;                   // nullable: the activations between the layers, layer after layer, each [B][m_l]
   unsigned long long *stats;       // nullable: two counters per layer
   int64_t B;
-  int32_t n_layers, rec_stride;    // rec_stride: record slots per wave
+  int32_t n_layers, rec_stride;    // rec_stride: record slots (the widest layer input)
   ChainLayer layer[kChainMaxLayers];
 };
 
+template <int WPR>
 __global__ __launch_bounds__(kChainWaves * 64) void lutkan_chain_kernel(const ChainArgs a) {
+  static_assert(WPR == 1 || WPR == kChainWaves, "a row is carried by one wave or by the whole work-group");
+  constexpr int ROWS = kChainWaves / WPR;                // rows per work-group
   extern __shared__ __align__(16) unsigned char lds[];
-  const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
-  // LDS: records [waves][rec_stride] of 16 bytes, activations [waves][64] floats, knots [n_layers][MAX_K+1] floats
-  u32x4 *s_rec = reinterpret_cast<u32x4 *>(lds) + (size_t)wave * a.rec_stride;
-  float *s_act = reinterpret_cast<float *>(lds + (size_t)kChainWaves * a.rec_stride * 16) + wave * kChainMaxColumns;
-  float *s_knots = reinterpret_cast<float *>(lds + (size_t)kChainWaves * a.rec_stride * 16) + kChainWaves * kChainMaxColumns;
-  for (int q = threadIdx.x; q < a.n_layers * (LUTKAN_MAX_K + 1); q += kChainWaves * 64) {
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int rrow = wave / WPR;                           // which of the work-group's rows
+  const int wr = wave % WPR;                             // which of the row's waves
+  const int rtid = wr * 64 + lane;                       // thread index inside the row's waves
+  // LDS: records [ROWS][rec_stride] of 16 bytes, activations [ROWS][64], per-wave sums [waves][64], outside
+  // counts [waves], knots [n_layers][MAX_K+1]
+  u32x4 *s_rec = reinterpret_cast<u32x4 *>(lds) + (size_t)rrow * a.rec_stride;
+  float *s_act_all = reinterpret_cast<float *>(lds + (size_t)ROWS * a.rec_stride * 16);
+  float *s_act = s_act_all + rrow * kChainMaxColumns;
+  float *s_part = s_act_all + ROWS * kChainMaxColumns;
+  unsigned *s_outside = reinterpret_cast<unsigned *>(s_part + kChainWaves * kChainMaxColumns);
+  float *s_knots = reinterpret_cast<float *>(s_outside + kChainWaves);
+  for (int q = tid; q < a.n_layers * (LUTKAN_MAX_K + 1); q += kChainWaves * 64) {
     const int l = q / (LUTKAN_MAX_K + 1), kappa = q - l * (LUTKAN_MAX_K + 1);
     s_knots[q] = (kappa <= a.layer[l].K) ? a.layer[l].knots[kappa] : 0.0f;
   }
   __syncthreads();
-  const int64_t row = (int64_t)blockIdx.x * kChainWaves + wave;
+  const int64_t row = (int64_t)blockIdx.x * ROWS + rrow;
   const bool live = row < a.B;
   const int64_t b = live ? row : a.B - 1;
   int64_t hidden_off = 0;
@@ -631,7 +644,7 @@ __global__ __launch_bounds__(kChainWaves * 64) void lutkan_chain_kernel(const Ch
     // ---- locate: one record per input of this row
     const unsigned masked_index = (unsigned)(Y.K * Y.L) | ((unsigned)Y.K << 16);
     unsigned outside = 0;
-    for (int i = lane; i < Y.d; i += 64) {
+    for (int i = rtid; i < Y.d; i += WPR * 64) {
       const float x = (l == 0) ? a.x[b * Y.d + i] : s_act[i];
       const Located o = locate_one<false>(Y, T, x);
       u32x4 rec = {masked_index, 0u, 0u, 0u};
@@ -646,27 +659,33 @@ __global__ __launch_bounds__(kChainWaves * 64) void lutkan_chain_kernel(const Ch
     }
     if (a.stats) {                                       // Sec. 5.5 counters of this layer
       for (int off = 32; off > 0; off >>= 1) outside += __shfl_down(outside, off, kWave);
-      if (lane == 0 && live && outside) {
-        atomicAdd(&a.stats[2 * l], (unsigned long long)outside);
+      if (lane == 0) s_outside[wave] = outside;
+    }
+    __syncthreads();                                     // records written (and the activations they came from read)
+    if (a.stats && rtid == 0 && live) {
+      unsigned total = 0;
+      for (int v = 0; v < WPR; ++v) total += s_outside[rrow * WPR + v];
+      if (total) {
+        atomicAdd(&a.stats[2 * l], (unsigned long long)total);
         atomicAdd(&a.stats[2 * l + 1], 1ull);
       }
     }
-    __syncthreads();                                     // records written (and the activations they came from read)
 
-    // ---- edges: lane = (group s, column jj); group s takes the inputs s, s + S, ...
+    // ---- edges: lane = (group s of its wave, column jj); group g = wave * S + s takes the inputs g, g + 4S, ...
     const int jt = 1 << Y.jt_log2;
     const int jj = lane & (jt - 1);
-    const int s = lane >> Y.jt_log2;
     const int S = 64 >> Y.jt_log2;
-    constexpr int U = 4;                                 // eight at a time was measured no faster
+    const int g = wr * S + (lane >> Y.jt_log2);
+    const int stride = WPR * S;
+    constexpr int U = 4;
     float acc = 0.0f;
-    for (int i0 = s; i0 < Y.d; i0 += U * S) {
+    for (int i0 = g; i0 < Y.d; i0 += U * stride) {
       u32x4 rec[U];
       unsigned c0[U], c1[U];
       float al[U], ym[U], bg[U], sg[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        const int i = min(i0 + u * S, Y.d - 1);
+        const int i = min(i0 + u * stride, Y.d - 1);
         rec[u] = s_rec[i];
         const unsigned char *slice = Y.table + (size_t)i * Y.blob_bytes;
         const unsigned code_off = (unsigned)Y.codes_off + (rec[u].x & 0xffffu) * (unsigned)jt;
@@ -687,7 +706,7 @@ __global__ __launch_bounds__(kChainWaves * 64) void lutkan_chain_kernel(const Ch
       }
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        if (i0 + u * S < Y.d) {
+        if (i0 + u * stride < Y.d) {
           const float w = __uint_as_float(rec[u].y);
           const float bias = Y.sym ? 128.0f : 0.0f;                           // int8 codes are stored excess-128
           const float f0 = (float)c0[u] - bias, f1 = (float)c1[u] - bias;
@@ -702,14 +721,19 @@ __global__ __launch_bounds__(kChainWaves * 64) void lutkan_chain_kernel(const Ch
         }
       }
     }
-    for (int off = jt; off < 64; off <<= 1) acc += __shfl_xor(acc, off, kWave);          // fixed order over the groups
+    for (int off = jt; off < 64; off <<= 1) acc += __shfl_xor(acc, off, kWave);          // fixed order over a wave's groups
+    if (lane < jt) s_part[wave * kChainMaxColumns + lane] = acc;
+    __syncthreads();                                     // the waves' sums are in place; everyone is done with the records
     const bool last = (l + 1 == a.n_layers);
-    if (s == 0 && jj < Y.m) {
+    if (rtid < Y.m) {
+      const float *part = s_part + rrow * WPR * kChainMaxColumns + rtid;
+      float total = part[0];
+      for (int v = 1; v < WPR; ++v) total += part[v * kChainMaxColumns];     // wave order
       if (last) {
-        if (live) a.y[b * Y.m + jj] = acc;
+        if (live) a.y[b * Y.m + rtid] = total;
       } else {
-        s_act[jj] = acc;
-        if (a.hidden && live) a.hidden[hidden_off + b * Y.m + jj] = acc;
+        s_act[rtid] = total;
+        if (a.hidden && live) a.hidden[hidden_off + b * Y.m + rtid] = total;
       }
     }
     hidden_off += a.B * Y.m;
@@ -1491,19 +1515,28 @@ extern "C" int lutkan_chain_forward(const lutkan_dev_layer *layers, int32_t n_la
   if (B < 0) return fail(LUTKAN_EINVAL, "%s: B < 0", who);
   if (B == 0) return LUTKAN_OK;
   if (!x || !y || x == y) return fail(LUTKAN_EINVAL, "%s: null or aliased x / y", who);
-  const int64_t groups = (B + kChainWaves - 1) / kChainWaves;
+  // up to 1024 rows a whole work-group carries a row (the shortest path through a layer); beyond, one wave does
+  const int wpr = (B <= 1024) ? kChainWaves : 1;
+  const int rows_per_group = kChainWaves / wpr;
+  const int64_t groups = (B + rows_per_group - 1) / rows_per_group;
   if (groups > 0x7fffffff) return fail(LUTKAN_EUNSUPPORTED, "%s: B too large", who);
   ca.x = x; ca.y = y; ca.hidden = hidden;
   ca.stats = reinterpret_cast<unsigned long long *>(stats);
   ca.B = B; ca.n_layers = n_layers; ca.rec_stride = widest;
-  const size_t lds = (size_t)kChainWaves * widest * 16 + (size_t)kChainWaves * kChainMaxColumns * 4 + (size_t)n_layers * (LUTKAN_MAX_K + 1) * 4;
-  static bool raised = false;   // the default cap on dynamic LDS (64 KiB) is below what the widest supported layer needs
-  if (!raised) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(lutkan_chain_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kMaxTiledLds);
-    if (e != hipSuccess) return fail(LUTKAN_EHIP, "%s: hipFuncSetAttribute(LDS): %s", who, hipGetErrorString(e));
-    raised = true;
+  const size_t lds = (size_t)rows_per_group * widest * 16 + (size_t)(rows_per_group + kChainWaves) * kChainMaxColumns * 4 +
+                     kChainWaves * 4 + (size_t)n_layers * (LUTKAN_MAX_K + 1) * 4;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (wpr == 1) {
+    static bool raised = false;   // the default cap on dynamic LDS (64 KiB) is below what four rows of the widest layer need
+    if (!raised) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(lutkan_chain_kernel<1>), hipFuncAttributeMaxDynamicSharedMemorySize, kMaxTiledLds);
+      if (e != hipSuccess) return fail(LUTKAN_EHIP, "%s: hipFuncSetAttribute(LDS): %s", who, hipGetErrorString(e));
+      raised = true;
+    }
+    hipLaunchKernelGGL(lutkan_chain_kernel<1>, dim3((unsigned)groups), dim3(kChainWaves * 64), lds, s, ca);
+  } else {
+    hipLaunchKernelGGL(lutkan_chain_kernel<kChainWaves>, dim3((unsigned)groups), dim3(kChainWaves * 64), lds, s, ca);
   }
-  hipLaunchKernelGGL(lutkan_chain_kernel, dim3((unsigned)groups), dim3(kChainWaves * 64), lds, static_cast<hipStream_t>(hip_stream), ca);
   return check_launch("lutkan_chain_kernel");
 }
 
