@@ -14,6 +14,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdint>
 #include <type_traits>
@@ -1142,14 +1143,30 @@ TilePlan plan_tiles(int64_t B, int d, int n_tiles, int rps) {
   return best;
 }
 
+// The default cap on a kernel's dynamic LDS (64 KiB) is below the 160 KiB a gfx950 CU has.  Raising it is a
+// per-kernel, per-device setting: one of these per kernel remembers which devices have it (bit = device ordinal).
+struct LdsCap {
+  std::atomic<uint64_t> devices{0};
+};
+
+template <typename Kern>
+int raise_lds_cap(Kern kern, LdsCap *cap, const char *what) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(LUTKAN_EHIP, "%s: hipGetDevice: %s", what, hipGetErrorString(e));
+  if (dev < 0 || dev >= 64) return fail(LUTKAN_EUNSUPPORTED, "%s: device ordinal %d", what, dev);
+  const uint64_t bit = 1ull << dev;
+  if (cap->devices.load(std::memory_order_acquire) & bit) return LUTKAN_OK;
+  e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kMaxTiledLds);
+  if (e != hipSuccess) return fail(LUTKAN_EHIP, "%s: hipFuncSetAttribute(LDS): %s", what, hipGetErrorString(e));
+  cap->devices.fetch_or(bit, std::memory_order_release);
+  return LUTKAN_OK;
+}
+
 template <typename Kern, typename Args>
-int launch_with_lds(Kern kern, bool *raised, const dim3 &grid, size_t lds, hipStream_t s, const Args &args, const char *what) {
+int launch_with_lds(Kern kern, LdsCap *cap, const dim3 &grid, size_t lds, hipStream_t s, const Args &args, const char *what) {
   if (lds > (size_t)kMaxTiledLds) return fail(LUTKAN_EUNSUPPORTED, "%s: needs %zu bytes of LDS", what, lds);
-  if (!*raised) {   // the default cap on dynamic LDS is below the 160 KiB a gfx950 CU has
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kMaxTiledLds);
-    if (e != hipSuccess) return fail(LUTKAN_EHIP, "hipFuncSetAttribute(LDS): %s", hipGetErrorString(e));
-    *raised = true;
-  }
+  if (int rc = raise_lds_cap(kern, cap, what)) return rc;
   hipLaunchKernelGGL(kern, grid, dim3(kTileWaves * 64), lds, s, args);
   return check_launch(what);
 }
@@ -1162,8 +1179,7 @@ int launch_tiled_np(const EdgeArgs &ea, hipStream_t s) {
   if (row_tiles * ea.n_tiles > 0x7fffffffLL) return fail(LUTKAN_EUNSUPPORTED, "lutkan_tiled_kernel: B * m too large for one launch");
   const dim3 grid((unsigned)(row_tiles * ea.n_tiles), (unsigned)((ea.d + ea.chunk - 1) / ea.chunk));
   const size_t lds = 2 * (size_t)ea.blob_bytes + (size_t)NW * 2 * RW * (ea.with_base ? 16 : 8);
-  static bool raised = false, raised_base = false;
-  static bool raised_half = false, raised_base_half = false;
+  static LdsCap raised, raised_base, raised_half, raised_base_half;
   if (ea.with_base && ea.param_fp16) return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, true, true>, &raised_base_half, grid, lds, s, ea, "lutkan_tiled_kernel");
   if (ea.with_base) return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, true, false>, &raised_base, grid, lds, s, ea, "lutkan_tiled_kernel");
   if (ea.param_fp16) return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, false, true>, &raised_half, grid, lds, s, ea, "lutkan_tiled_kernel");
@@ -1303,7 +1319,7 @@ int launch_spline_tiled_np(const SplineEdgeArgs &ea, hipStream_t s) {
   if (row_tiles * ea.n_tiles > 0x7fffffffLL) return fail(LUTKAN_EUNSUPPORTED, "bspline_tiled_kernel: B * m too large for one launch");
   const dim3 grid((unsigned)(row_tiles * ea.n_tiles), (unsigned)((ea.d + ea.chunk - 1) / ea.chunk));
   const size_t lds = 2 * (size_t)bytes + (size_t)NW * 2 * RW * 32;
-  static bool raised = false, raised_base = false;
+  static LdsCap raised, raised_base;
   if (ea.with_base) return launch_with_lds(bspline_tiled_kernel<LPR, NP, NW, true>, &raised_base, grid, lds, s, ea, "bspline_tiled_kernel");
   return launch_with_lds(bspline_tiled_kernel<LPR, NP, NW, false>, &raised, grid, lds, s, ea, "bspline_tiled_kernel");
 }
@@ -1527,12 +1543,8 @@ extern "C" int lutkan_chain_forward(const lutkan_dev_layer *layers, int32_t n_la
                      kChainWaves * 4 + (size_t)n_layers * (LUTKAN_MAX_K + 1) * 4;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   if (wpr == 1) {
-    static bool raised = false;   // the default cap on dynamic LDS (64 KiB) is below what four rows of the widest layer need
-    if (!raised) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(lutkan_chain_kernel<1>), hipFuncAttributeMaxDynamicSharedMemorySize, kMaxTiledLds);
-      if (e != hipSuccess) return fail(LUTKAN_EHIP, "%s: hipFuncSetAttribute(LDS): %s", who, hipGetErrorString(e));
-      raised = true;
-    }
+    static LdsCap raised;         // four rows of the widest layer need more than the default 64 KiB
+    if (int rc = raise_lds_cap(lutkan_chain_kernel<1>, &raised, who)) return rc;
     hipLaunchKernelGGL(lutkan_chain_kernel<1>, dim3((unsigned)groups), dim3(kChainWaves * 64), lds, s, ca);
   } else {
     hipLaunchKernelGGL(lutkan_chain_kernel<kChainWaves>, dim3((unsigned)groups), dim3(kChainWaves * 64), lds, s, ca);

@@ -314,6 +314,35 @@ def test_special_inputs_nan_inf_all_oob():
                 _check_layer(s, x, algo, what="special")
 
 
+def test_domain_ends_at_zero_and_below_and_subnormal_inputs():
+    """The safe upper clip value of Eq. 13 in half-open mode is nextafter(t_K, -inf): below t_K = 0 that is the
+    smallest negative subnormal, below a negative t_K the next float of larger magnitude.  Shared knots (clip value
+    from the host) and one vector per input (clip value computed in the kernel), inputs on and around those values."""
+    from lutkan_inputs import LayerSpec, uniform_ext_knots
+    rng = np.random.Generator(np.random.PCG64(31))
+    G, L, m = 4, 16, 5
+    tiny = np.float32(1e-45)                                            # the smallest positive subnormal
+    ends = [(-2.0, 0.0), (-3.0, -1.0), (0.0, 2.0), (-1.0, 1.0)]
+    specials = []
+    for lo, hi in ends:
+        for v in (lo, hi):
+            v = np.float32(v)
+            specials += [v, np.nextafter(v, np.float32(-np.inf)), np.nextafter(v, np.float32(np.inf))]
+    specials += [np.float32(0.0), np.float32(-0.0), tiny, -tiny, np.float32(1e-39), np.float32(-1e-39)]
+    specials = np.array(specials, dtype=np.float32)
+    for boundary in (HALF_OPEN, CLOSED):
+        for oob in (CLIP_X, ZERO_SPLINE):
+            # one vector per input: the four domains side by side, every special value in every column
+            tau = np.stack([uniform_ext_knots(lo, hi, G, 3) for lo, hi in ends])
+            coef = rng.normal(size=(4, m, G + 3)).astype(np.float32)
+            x = np.tile(specials[:, None], (1, 4))
+            _check_layer(LayerSpec(4, m, G, 3, tau, coef, L, SYM_INT8, boundary, oob, per_input=True), x, lk.ALGO_AUTO,
+                         what=f"zero-ended domains, per input, b{boundary} o{oob}")
+            for row, (lo, hi) in enumerate(ends):                       # the same domains as shared vectors
+                _check_layer(LayerSpec(1, m, G, 3, tau[row], coef[row:row + 1], L, SYM_INT8, boundary, oob), x[:, :1].copy(),
+                             lk.ALGO_AUTO, what=f"domain [{lo},{hi}] shared b{boundary} o{oob}")
+
+
 def test_empty_batch_and_argument_errors():
     w = cfg1(B=8)
     s = w.layers[0]
