@@ -10,6 +10,10 @@
 //                      "tiled" variant: a work-group owns (row tile) x (column tile), walks the inputs, and
 //                      stages each input's table slice in LDS;  "gather" variant: codes straight from global
 //                      memory (used for table slices too large for LDS and for the code trace).
+//   3. chain kernel    both steps for every layer of a narrow network in one launch, activations in LDS (small
+//                      batches, where the launches of 1. and 2. per layer cost more than the arithmetic).
+// The B-spline baseline layer (Sec. 3.2-3.3) has the same split: span + basis values per (row, input), then four
+// coefficient FMAs per edge.
 // The file is compiled with -ffp-contract=off; every fused multiply-add below is written out as fmaf().
 #include <hip/hip_runtime.h>
 
