@@ -656,6 +656,38 @@ def test_model_forward_replays_correctly_from_a_hip_graph():
         torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("B", [256, 5000])
+def test_fused_chain_replays_correctly_from_a_hip_graph(B):
+    """One kernel launch and nothing else: captured after one eager call (which sets the kernel's one-time
+    attribute), every replay with eager work in between reproduces the eager result bit for bit."""
+    w = cfg2(B=B)
+    arts = [lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, s.boundary, s.oob) for s in w.layers]
+    layers = [a.to_device(DEV) for a in arts]
+    x = torch.from_numpy(w.x).to(DEV)
+    y = torch.empty((B, layers[-1].m), dtype=torch.float32, device=DEV)
+    stats = torch.zeros((len(layers), 2), dtype=torch.int64, device=DEV)
+    _say(f"case graph capture of the fused chain {w.name} B={B}")
+    lk.lutkan_chain_forward(layers, x, y, stats=stats)
+    torch.cuda.synchronize()
+    y_eager, stats_eager = y.clone(), stats.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        lk.lutkan_chain_forward(layers, x, y, stats=stats)
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        lk.lutkan_chain_forward(layers, x, y, stats=stats)
+    for _ in range(3):
+        y.fill_(7.0)
+        stats.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, y_eager) and torch.equal(stats, stats_eager)
+        lk.lutkan_chain_forward(layers, x, y)                                  # eager work between replays
+        torch.cuda.synchronize()
+
+
 def test_random_shapes_and_contracts():
     """Sixty layers with shapes, grids, table sizes and contracts drawn at random (seeded), covering every tile width,
     ragged tiles and batches, both value representations, both parameter dtypes and both kernel families; the LUT
