@@ -258,6 +258,9 @@ __device__ __forceinline__ f16x2 bits_to_f16x2(unsigned v) {
 // paid once per four inputs.  Masked records point at the slice's zero rows (no branch).  With TRACE the two
 // gathered codes of every edge are also written out, addressed by the traced (k, l0) so that masked edges
 // report the codes they would have used.
+// blockIdx.z selects a chunk of a.chunk inputs; with more than one chunk the kernel writes partial sums (chunk
+// after chunk, a.split_stride floats apart) that sum_partials_kernel adds in chunk order.  That is how a batch of a
+// few rows still fills the GPU: the walk over the inputs, a chain of dependent reads, is cut into many short ones.
 template <int SCHEME, bool TRACE>
 __global__ __launch_bounds__(256) void lutkan_gather_kernel(const EdgeArgs a, const int jx_log2) {
   constexpr int U = 4;
@@ -271,13 +274,15 @@ __global__ __launch_bounds__(256) void lutkan_gather_kernel(const EdgeArgs a, co
   const unsigned char *tile = a.table + (size_t)t * a.d * a.blob_bytes;
   const int rec_words = a.with_base ? 4 : 2;
   const unsigned *recs = static_cast<const unsigned *>(a.rec);
+  const int i_begin = blockIdx.z * a.chunk;
+  const int i_end = min(a.d, i_begin + a.chunk);
   float acc = 0.0f;
-  for (int i0 = 0; i0 < a.d; i0 += U) {
+  for (int i0 = i_begin; i0 < i_end; i0 += U) {
     u32x2 rec[U];
     float silu_x[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const unsigned *r = recs + ((int64_t)min(i0 + u, a.d - 1) * a.Bp + b) * rec_words;
+      const unsigned *r = recs + ((int64_t)min(i0 + u, i_end - 1) * a.Bp + b) * rec_words;
       rec[u] = *reinterpret_cast<const u32x2 *>(r);
       silu_x[u] = a.with_base ? __uint_as_float(r[2]) : 0.0f;
     }
@@ -285,7 +290,7 @@ __global__ __launch_bounds__(256) void lutkan_gather_kernel(const EdgeArgs a, co
     float al[U], ym[U], bg[U], sg[U];      // alpha, y_min, s_out*s_base, s_out*s_spline (1 where it is folded in)
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const unsigned char *slice = tile + (size_t)min(i0 + u, a.d - 1) * a.blob_bytes;
+      const unsigned char *slice = tile + (size_t)min(i0 + u, i_end - 1) * a.blob_bytes;
       const unsigned code_off = (unsigned)a.codes_off + (rec[u].x & 0xffffu) * (unsigned)a.jt;
       const unsigned param_off = (unsigned)a.params_off + (rec[u].x >> 16) * (unsigned)a.param_row_bytes;
       c0[u] = slice[code_off + jj];
@@ -305,7 +310,7 @@ __global__ __launch_bounds__(256) void lutkan_gather_kernel(const EdgeArgs a, co
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      if (i0 + u < a.d) {
+      if (i0 + u < i_end) {
         const float w = __uint_as_float(rec[u].y);
         const float f0 = code_to_float<SCHEME>(c0[u]), f1 = code_to_float<SCHEME>(c1[u]);
         const float tq = fmaf(w, f1 - f0, f0);                             // interpolate the codes ...
@@ -328,7 +333,7 @@ __global__ __launch_bounds__(256) void lutkan_gather_kernel(const EdgeArgs a, co
       }
     }
   }
-  a.y[b * a.m + j] = acc;
+  a.y[(int64_t)blockIdx.z * a.split_stride + b * a.m + j] = acc;
 }
 
 // Asynchronous global -> LDS copy of 16 bytes per lane (gfx950 LDS-DMA form of the global load): the wave's
@@ -895,19 +900,21 @@ __global__ __launch_bounds__(256) void bspline_gather_kernel(const SplineEdgeArg
   if (j >= a.m || b >= a.B) return;
   const int t = j / a.jt, jj = j - t * a.jt;
   const float *tile = a.coef_table + (size_t)t * a.d * a.rows * a.jt;
+  const int i_begin = blockIdx.z * a.chunk;            // chunks of inputs and partial sums as in the LUT gather kernel
+  const int i_end = min(a.d, i_begin + a.chunk);
   float acc = 0.0f;
-  for (int i0 = 0; i0 < a.d; i0 += U) {
+  for (int i0 = i_begin; i0 < i_end; i0 += U) {
     u32x4 r0[U], r1[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int64_t o = ((int64_t)min(i0 + u, a.d - 1) * a.Bp + b) * 2;
+      const int64_t o = ((int64_t)min(i0 + u, i_end - 1) * a.Bp + b) * 2;
       r0[u] = a.rec[o];
       r1[u] = a.rec[o + 1];
     }
     float cf[U][4], bg[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const float *sl = tile + (size_t)min(i0 + u, a.d - 1) * a.rows * a.jt;
+      const float *sl = tile + (size_t)min(i0 + u, i_end - 1) * a.rows * a.jt;
       const float *c = sl + (r0[u].x >> 2) + jj;
 #pragma unroll
       for (int q = 0; q < 4; ++q) cf[u][q] = c[q * a.jt];
@@ -915,7 +922,7 @@ __global__ __launch_bounds__(256) void bspline_gather_kernel(const SplineEdgeArg
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      if (i0 + u < a.d) {
+      if (i0 + u < i_end) {
         acc = fmaf(__uint_as_float(r0[u].y), cf[u][0], acc);
         acc = fmaf(__uint_as_float(r0[u].z), cf[u][1], acc);
         acc = fmaf(__uint_as_float(r0[u].w), cf[u][2], acc);
@@ -924,7 +931,7 @@ __global__ __launch_bounds__(256) void bspline_gather_kernel(const SplineEdgeArg
       }
     }
   }
-  a.y[b * a.m + j] = acc;
+  a.y[(int64_t)blockIdx.z * a.split_stride + b * a.m + j] = acc;
 }
 
 // Tiled B-spline kernel: same ownership and streaming as the LUT tiled kernel; the staged slice is the input's
@@ -1063,7 +1070,8 @@ __global__ __launch_bounds__(256) void sum_partials_kernel(const float *part, fl
   const int64_t e = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
   if (e + 3 < n && (n & 3) == 0) {                   // 16-byte path needs every chunk's base aligned
     f32x4 acc = *reinterpret_cast<const f32x4 *>(part + e);
-    for (int s = 1; s < n_split; ++s) acc += *reinterpret_cast<const f32x4 *>(part + (int64_t)s * n + e);
+#pragma unroll 8
+    for (int s = 1; s < n_split; ++s) acc += *reinterpret_cast<const f32x4 *>(part + (int64_t)s * n + e);   // loads of 8 chunks in flight
     *reinterpret_cast<f32x4 *>(y + e) = acc;
   } else {
     for (int64_t q = e; q < n && q < e + 4; ++q) {
@@ -1145,6 +1153,31 @@ TilePlan plan_tiles(int64_t B, int d, int n_tiles, int rps) {
   }
   best.n_split = (d + best.chunk - 1) / best.chunk;      // drop empty trailing chunks
   return best;
+}
+
+// Launch shape of the gather kernel: the d inputs are cut into chunks (at least 4 inputs each, at most 64 chunks)
+// until the launch has about a million threads: a thread's walk over its inputs is a chain of dependent reads,
+// four inputs per round trip, so short chunks matter more than full compute units.
+struct GatherPlan {
+  int n_split, chunk;
+};
+
+GatherPlan plan_gather(int64_t B, int d, int m) {
+  const int64_t threads = B * (int64_t)m;
+  int64_t want = (threads >= (1 << 20)) ? 1 : ((1 << 20) + threads - 1) / threads;
+  want = std::min<int64_t>(want, std::min(64, std::max(1, d / 4)));
+  const int chunk = (int)((d + want - 1) / want);
+  return GatherPlan{(d + chunk - 1) / chunk, chunk};
+}
+
+// True when a batch is so small that reading only the table rows it touches (gather kernel, inputs split over the
+// GPU) moves fewer bytes than the whole table, which the tiled kernel streams once whatever the batch.
+bool prefer_gather_for_small_batch(const lutkan_dev_layer *l, int64_t B) {
+  const lutkan::BlobLayout lay = lutkan::blob_layout(l->K, l->L, l->jt, l->scheme, l->value_repr, l->param_dtype);
+  // per (row, input, column tile): two code rows and one parameter row
+  const double touched = (double)B * l->d * l->n_tiles * (2.0 * l->jt + (double)lay.param_row_bytes);
+  const double table = (double)l->n_tiles * l->d * l->blob_bytes;
+  return touched <= table;     // measured crossover: 1024x1024 near 100 rows, 256x256 near 200, both where the two are equal
 }
 
 // The default cap on a kernel's dynamic LDS (64 KiB) is below the 160 KiB a gfx950 CU has.  Raising it is a
@@ -1287,6 +1320,7 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
 
   bool tiled = tiled_supported(l->jt, l->blob_bytes) && !q01_out;
   if (l->algo == LUTKAN_ALGO_GATHER) tiled = false;
+  if (l->algo == LUTKAN_ALGO_AUTO && tiled && prefer_gather_for_small_batch(l, B)) tiled = false;
   if (l->algo == LUTKAN_ALGO_TILED && !tiled) return fail(LUTKAN_EUNSUPPORTED, "%s: tiled kernel needs a table slice <= 56 KiB", who);
   ea.chunk = l->d;
   ea.split_stride = 0;
@@ -1302,7 +1336,11 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
     return check_launch("sum_partials_kernel");
   }
   const int lg = gather_jx_log2(l->m);
-  const dim3 grid((unsigned)((B + (256 >> lg) - 1) / (256 >> lg)), (unsigned)((l->m + (1 << lg) - 1) >> lg));
+  const GatherPlan gp = plan_gather(B, l->d, l->m);
+  float *partials = reinterpret_cast<float *>(static_cast<char *>(workspace) + record_bytes(l->d, Bp, lut_record_bytes(l->value_repr)));
+  ea.chunk = gp.chunk;
+  if (gp.n_split > 1) { ea.y = partials; ea.split_stride = B * l->m; }
+  const dim3 grid((unsigned)((B + (256 >> lg) - 1) / (256 >> lg)), (unsigned)((l->m + (1 << lg) - 1) >> lg), (unsigned)gp.n_split);
   if (grid.y > 65535u) return fail(LUTKAN_EUNSUPPORTED, "%s: m too large for the gather kernel", who);
   if (l->scheme == LUTKAN_SYM_INT8) {
     if (q01_out) hipLaunchKernelGGL((lutkan_gather_kernel<LUTKAN_SYM_INT8, true>), grid, dim3(256), 0, s, ea, lg);
@@ -1311,7 +1349,11 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
     if (q01_out) hipLaunchKernelGGL((lutkan_gather_kernel<LUTKAN_ASYM_UINT8, true>), grid, dim3(256), 0, s, ea, lg);
     else hipLaunchKernelGGL((lutkan_gather_kernel<LUTKAN_ASYM_UINT8, false>), grid, dim3(256), 0, s, ea, lg);
   }
-  return check_launch("lutkan_gather_kernel");
+  if (int rc = check_launch("lutkan_gather_kernel")) return rc;
+  if (gp.n_split == 1) return LUTKAN_OK;
+  const int64_t n = B * l->m;
+  hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, s, partials, y, n, gp.n_split);
+  return check_launch("sum_partials_kernel");
 }
 
 template <int LPR, int NP>
@@ -1412,6 +1454,9 @@ int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y
   ea.with_base = la.with_base; ea.jt = l->jt; ea.n_tiles = l->n_tiles;
   bool tiled = true;                                   // a coefficient slice always fits LDS (R <= 67)
   if (l->algo == LUTKAN_ALGO_GATHER) tiled = false;
+  // up to 16 rows the gather kernel with the inputs split over the GPU is the faster one (measured on 256x256 and
+  // 1024x1024 layers): the tiled kernel's walk over all inputs is then a longer chain than the arithmetic
+  if (l->algo == LUTKAN_ALGO_AUTO && B <= 16) tiled = false;
   if (l->algo == LUTKAN_ALGO_TILED && !tiled) return fail(LUTKAN_EUNSUPPORTED, "%s: tiled kernel unavailable", who);
   ea.chunk = l->d;
   ea.split_stride = 0;
@@ -1427,9 +1472,17 @@ int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y
     return check_launch("sum_partials_kernel");
   }
   const int lg = gather_jx_log2(l->m);
-  const dim3 grid((unsigned)((B + (256 >> lg) - 1) / (256 >> lg)), (unsigned)((l->m + (1 << lg) - 1) >> lg));
+  const GatherPlan gp = plan_gather(B, l->d, l->m);
+  float *partials = reinterpret_cast<float *>(static_cast<char *>(workspace) + record_bytes(l->d, Bp, 32));
+  ea.chunk = gp.chunk;
+  if (gp.n_split > 1) { ea.y = partials; ea.split_stride = B * l->m; }
+  const dim3 grid((unsigned)((B + (256 >> lg) - 1) / (256 >> lg)), (unsigned)((l->m + (1 << lg) - 1) >> lg), (unsigned)gp.n_split);
   hipLaunchKernelGGL(bspline_gather_kernel, grid, dim3(256), 0, s, ea, lg);
-  return check_launch("bspline_gather_kernel");
+  if (int rc = check_launch("bspline_gather_kernel")) return rc;
+  if (gp.n_split == 1) return LUTKAN_OK;
+  const int64_t n = B * l->m;
+  hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, s, partials, y, n, gp.n_split);
+  return check_launch("sum_partials_kernel");
 }
 
 }  // namespace
@@ -1438,7 +1491,9 @@ int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y
 static size_t tiled_workspace_bytes(int d, int m, int jt, int n_tiles, int64_t B, int bytes_per_record) {
   size_t bytes = record_bytes(d, padded_rows(B), bytes_per_record);
   const TilePlan tp = plan_tiles(B, d, n_tiles, 64 / (jt / 4));
-  if (tp.n_split > 1) bytes += (size_t)tp.n_split * (size_t)B * (size_t)m * 4;
+  const GatherPlan gp = plan_gather(B, d, m);           // either kernel may run: room for the larger set of partial sums
+  const int n_split = std::max(tp.n_split, gp.n_split);
+  if (n_split > 1) bytes += (size_t)n_split * (size_t)B * (size_t)m * 4;
   return bytes;
 }
 

@@ -468,9 +468,22 @@ def test_cfg3_full_batch_sampled_rows():
     _sampled_rows_check(cfg3(L=64, scheme=SYM_INT8), 512, "cfg3 L64 sym")
 
 
-@pytest.mark.parametrize("B", [256, 4096, 32768])
+@pytest.mark.parametrize("B", [1, 7, 64, 100, 256, 4096, 32768])
 def test_cfg4_wide_layer_full_size_sampled_rows(B):
+    """The widest workload at its three batches, and at batches of a few rows, where AUTO runs the gather kernel
+    with the inputs split into chunks (partial sums added in chunk order)."""
     _sampled_rows_check(cfg4(B=B), 96, f"cfg4 B={B}")
+
+
+@pytest.mark.parametrize("B", [1, 5, 16, 17])
+def test_bspline_wide_layer_small_batches(B):
+    """The B-spline layer at a few rows: up to 16 rows AUTO takes the gather kernel with the inputs split into chunks."""
+    w = cfg4(B=B)
+    s = w.layers[0]
+    art = lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, s.boundary, s.oob)
+    y = lk.bspline_kan_forward(art.bspline_to_device(DEV), torch.from_numpy(w.x).to(DEV))
+    ref = oracle.bspline_forward(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.boundary, s.oob, w.x)
+    _assert_close(y.cpu().numpy(), ref, f"bspline cfg4 B={B}")
 
 
 def test_two_million_rows_sampled():
