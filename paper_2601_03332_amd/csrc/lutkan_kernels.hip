@@ -1130,28 +1130,46 @@ int gather_jx_log2(int m) {
 }
 
 // Launch shape of the tiled kernels for B rows: NP row steps per wave (16/8/4/2/1, at most 64 rows per wave) and
-// the number of chunks the d inputs are split into.  Large row tiles re-read the table least, so NP starts at the
-// smallest value whose row tile covers B and shrinks only while the grid would still leave compute units idle
-// even with the inputs split (each chunk keeps at least 16 inputs).  (Preferring small row tiles to splitting was
-// measured and lost: with few row steps per input the per-input barrier dominates.)
+// the number of chunks the d inputs are split into (each with its own work-groups and its own set of partial sums).
+// Chosen by a small cost model, in microseconds, over every (NP, chunk count) pair:
+//   one input of one work-group   max(0.55 + 0.11 * NP, slice bytes at 100 GB/s) + 0.1
+//                                 (barrier and address set-up, NP row steps of 256 edges per wave, the slice's
+//                                 global -> LDS copy when that is the longer of the two)
+//   one work-group                3 + its inputs (pipeline fill, accumulator write-back)
+//   the launch                    rounds of 256 work-groups (one per compute unit), one after the other
+//   the partial sums              4 + their bytes at 3 TB/s, when there is more than one chunk
+// The constants come from the widest workload (2.4 us per input at NP = 16), a 64x1024 layer at NP = 4 (1.1 us) and
+// sweeps over batch sizes of 78x16 ... 4096x256 layers; the model replaced a rule (largest row tile first, split the inputs until 256
+// work-groups, at most 32 chunks) that lost up to 40 % on wide-input, narrow-output layers at a few hundred rows.
 struct TilePlan {
   int np, n_split, chunk;
 };
 
-TilePlan plan_tiles(int64_t B, int d, int n_tiles, int rps) {
+TilePlan plan_tiles(int64_t B, int d, int m, int n_tiles, int rps, int slice_bytes) {
   const int np_max = std::min(16, 64 / rps);
-  const int np_min = std::min(2, np_max);
-  int np_cap = np_min;
-  while (np_cap < np_max && (int64_t)kTileWaves * rps * np_cap < B) np_cap <<= 1;
-  const int max_split = std::max(1, std::min(32, d / 16));
-  TilePlan best{np_cap, 1, d};
-  for (int np = np_cap; np >= np_min; np >>= 1) {
-    const int64_t groups = (B + kTileWaves * rps * np - 1) / (kTileWaves * rps * np) * n_tiles;
-    const int split = (int)std::min<int64_t>(max_split, std::max<int64_t>(1, (256 + groups - 1) / groups));
-    best = TilePlan{np, split, (d + split - 1) / split};
-    if (groups * split >= 256) break;
+  const int max_split = std::max(1, std::min(128, d / 8));
+  TilePlan best{np_max, 1, d};
+  double best_cost = 1e300;
+  for (int np = np_max; np >= 1; np >>= 1) {
+    const int64_t rows = (int64_t)kTileWaves * rps * np;
+    const int64_t groups = (B + rows - 1) / rows * n_tiles;
+    const double per_input = std::max(0.55 + 0.11 * np, slice_bytes / 100e3) + 0.1;
+    // candidate chunk counts: 1 .. 8, then the counts that fill whole rounds of 256 work-groups, and the cap
+    int candidates[16];
+    int n_candidates = 0;
+    for (int c = 1; c <= 8; ++c) candidates[n_candidates++] = c;
+    for (int rounds = 1; rounds <= 4; ++rounds) candidates[n_candidates++] = (int)std::min<int64_t>(max_split, (256 * rounds + groups - 1) / groups);
+    candidates[n_candidates++] = max_split;
+    for (int q = 0; q < n_candidates; ++q) {
+      const int want = std::min(candidates[q], max_split);
+      const int chunk = (d + want - 1) / want;
+      const int split = (d + chunk - 1) / chunk;      // no empty trailing chunks
+      const double rounds = (double)((groups * split + 255) / 256);
+      double cost = rounds * (3.0 + chunk * per_input);
+      if (split > 1) cost += 4.0 + (double)split * (double)B * m * 4.0 / 3e6;
+      if (cost < best_cost) { best_cost = cost; best = TilePlan{np, split, chunk}; }
+    }
   }
-  best.n_split = (d + best.chunk - 1) / best.chunk;      // drop empty trailing chunks
   return best;
 }
 
@@ -1325,7 +1343,7 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   ea.chunk = l->d;
   ea.split_stride = 0;
   if (tiled) {
-    const TilePlan tp = plan_tiles(B, l->d, l->n_tiles, 64 / (l->jt / 4));
+    const TilePlan tp = plan_tiles(B, l->d, l->m, l->n_tiles, 64 / (l->jt / 4), l->blob_bytes);
     float *partials = reinterpret_cast<float *>(static_cast<char *>(workspace) + record_bytes(l->d, Bp, lut_record_bytes(l->value_repr)));
     ea.chunk = tp.chunk;
     if (tp.n_split > 1) { ea.y = partials; ea.split_stride = B * l->m; }
@@ -1461,7 +1479,7 @@ int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y
   ea.chunk = l->d;
   ea.split_stride = 0;
   if (tiled) {
-    const TilePlan tp = plan_tiles(B, l->d, l->n_tiles, 64 / (l->jt / 4));
+    const TilePlan tp = plan_tiles(B, l->d, l->m, l->n_tiles, 64 / (l->jt / 4), l->coef_blob_bytes);
     float *partials = reinterpret_cast<float *>(static_cast<char *>(workspace) + record_bytes(l->d, Bp, 32));
     ea.chunk = tp.chunk;
     if (tp.n_split > 1) { ea.y = partials; ea.split_stride = B * l->m; }
@@ -1488,9 +1506,9 @@ int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y
 }  // namespace
 
 // Records for every (input, padded row), then room for the partial sums when the inputs are split into chunks.
-static size_t tiled_workspace_bytes(int d, int m, int jt, int n_tiles, int64_t B, int bytes_per_record) {
+static size_t tiled_workspace_bytes(int d, int m, int jt, int n_tiles, int64_t B, int bytes_per_record, int slice_bytes) {
   size_t bytes = record_bytes(d, padded_rows(B), bytes_per_record);
-  const TilePlan tp = plan_tiles(B, d, n_tiles, 64 / (jt / 4));
+  const TilePlan tp = plan_tiles(B, d, m, n_tiles, 64 / (jt / 4), slice_bytes);
   const GatherPlan gp = plan_gather(B, d, m);           // either kernel may run: room for the larger set of partial sums
   const int n_split = std::max(tp.n_split, gp.n_split);
   if (n_split > 1) bytes += (size_t)n_split * (size_t)B * (size_t)m * 4;
@@ -1499,12 +1517,12 @@ static size_t tiled_workspace_bytes(int d, int m, int jt, int n_tiles, int64_t B
 
 extern "C" size_t lutkan_forward_workspace_bytes(const lutkan_dev_layer *layer, int64_t B) {
   if (!layer || B <= 0 || layer->d < 1 || layer->m < 1 || layer->jt < 4 || layer->n_tiles < 1) return 0;
-  return tiled_workspace_bytes(layer->d, layer->m, layer->jt, layer->n_tiles, B, lut_record_bytes(layer->value_repr));
+  return tiled_workspace_bytes(layer->d, layer->m, layer->jt, layer->n_tiles, B, lut_record_bytes(layer->value_repr), layer->blob_bytes);
 }
 
 extern "C" size_t bspline_forward_workspace_bytes(const bspline_dev_layer *layer, int64_t B) {
   if (!layer || B <= 0 || layer->d < 1 || layer->m < 1 || layer->jt < 4 || layer->n_tiles < 1) return 0;
-  return tiled_workspace_bytes(layer->d, layer->m, layer->jt, layer->n_tiles, B, 32);
+  return tiled_workspace_bytes(layer->d, layer->m, layer->jt, layer->n_tiles, B, 32, layer->coef_blob_bytes);
 }
 
 extern "C" int lutkan_forward(const lutkan_dev_layer *layer, const float *x, int64_t B, float *y,
