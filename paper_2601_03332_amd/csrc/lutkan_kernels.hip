@@ -1276,6 +1276,61 @@ void launch_locate(int cols, dim3 grid, hipStream_t s, const LocateArgs &la) {
   else hipLaunchKernelGGL((lutkan_locate_kernel<BASE, 16, PERIN>), grid, dim3(256), 0, s, la);
 }
 
+// The fused chain: validation, kernel arguments and launch (the body of lutkan_chain_forward; lutkan_forward also
+// comes here with a single small layer).
+int chain_impl(const lutkan_dev_layer *layers, int32_t n_layers, const float *x, int64_t B, float *y,
+               float *hidden, lutkan_oob_stats *stats, void *hip_stream, const char *who) {
+  if (!layers || n_layers < 1) return fail(LUTKAN_EINVAL, "%s: need at least one layer", who);
+  if (n_layers > kChainMaxLayers) return fail(LUTKAN_EUNSUPPORTED, "%s: at most %d layers (got %d)", who, kChainMaxLayers, n_layers);
+  ChainArgs ca = {};
+  int widest = 0;
+  for (int l = 0; l < n_layers; ++l) {
+    const lutkan_dev_layer *L = &layers[l];
+    if (int rc = validate_layer(L, who)) return rc;
+    if (l + 1 < n_layers && L->m != layers[l + 1].d) return fail(LUTKAN_ESHAPE, "%s: layer %d has m=%d but layer %d has d=%d", who, l, L->m, l + 1, layers[l + 1].d);
+    if (L->n_tiles != 1 || L->jt > kChainMaxColumns) return fail(LUTKAN_EUNSUPPORTED, "%s: layer %d has %d outputs in %d column tiles, the fused chain takes one tile of at most %d columns", who, l, L->m, L->n_tiles, kChainMaxColumns);
+    if (L->d > kChainMaxInputs) return fail(LUTKAN_EUNSUPPORTED, "%s: layer %d has %d inputs, the fused chain takes at most %d", who, l, L->d, kChainMaxInputs);
+    if (L->knots_per_input) return fail(LUTKAN_EUNSUPPORTED, "%s: layer %d has one knot vector per input; use lutkan_model_forward", who, l);
+    const lutkan::BlobLayout lay = lutkan::blob_layout(L->K, L->L, L->jt, L->scheme, L->value_repr, L->param_dtype);
+    ChainLayer &c = ca.layer[l];
+    c.table = static_cast<const unsigned char *>(L->table);
+    c.d = L->d; c.m = L->m; c.K = L->K; c.L = L->L; c.blob_bytes = L->blob_bytes;
+    c.jt_log2 = 0;
+    while ((1 << c.jt_log2) < L->jt) ++c.jt_log2;
+    c.codes_off = lay.codes_off; c.params_off = lay.params_off; c.param_row_bytes = lay.param_row_bytes;
+    c.sym = (L->scheme == LUTKAN_SYM_INT8);
+    c.with_base = (L->value_repr == LUTKAN_REPR_SPLINE_COMPONENT);
+    c.param_fp16 = (L->param_dtype == LUTKAN_PARAM_FP16);
+    c.closed = (L->boundary == LUTKAN_CLOSED);
+    c.zero_spline = (L->oob == LUTKAN_ZERO_SPLINE);
+    c.tKs = c.closed ? L->knots[L->K] : std::nextafterf(L->knots[L->K], -INFINITY);
+    for (int k = 0; k <= L->K; ++k) c.knots[k] = L->knots[k];
+    widest = std::max(widest, L->d);
+  }
+  if (B < 0) return fail(LUTKAN_EINVAL, "%s: B < 0", who);
+  if (B == 0) return LUTKAN_OK;
+  if (!x || !y || x == y) return fail(LUTKAN_EINVAL, "%s: null or aliased x / y", who);
+  // up to 1024 rows a whole work-group carries a row (the shortest path through a layer); beyond, one wave does
+  const int wpr = (B <= 1024) ? kChainWaves : 1;
+  const int rows_per_group = kChainWaves / wpr;
+  const int64_t groups = (B + rows_per_group - 1) / rows_per_group;
+  if (groups > 0x7fffffff) return fail(LUTKAN_EUNSUPPORTED, "%s: B too large", who);
+  ca.x = x; ca.y = y; ca.hidden = hidden;
+  ca.stats = reinterpret_cast<unsigned long long *>(stats);
+  ca.B = B; ca.n_layers = n_layers; ca.rec_stride = widest;
+  const size_t lds = (size_t)rows_per_group * widest * 16 + (size_t)(rows_per_group + kChainWaves) * kChainMaxColumns * 4 +
+                     kChainWaves * 4 + (size_t)n_layers * (LUTKAN_MAX_K + 1) * 4;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (wpr == 1) {
+    static LdsCap raised;         // four rows of the widest layer need more than the default 64 KiB
+    if (int rc = raise_lds_cap(lutkan_chain_kernel<1>, &raised, who)) return rc;
+    hipLaunchKernelGGL(lutkan_chain_kernel<1>, dim3((unsigned)groups), dim3(kChainWaves * 64), lds, s, ca);
+  } else {
+    hipLaunchKernelGGL(lutkan_chain_kernel<kChainWaves>, dim3((unsigned)groups), dim3(kChainWaves * 64), lds, s, ca);
+  }
+  return check_launch("lutkan_chain_kernel");
+}
+
 int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y, lutkan_oob_stats *stats,
                  int32_t *k_out, int32_t *l0_out, uint8_t *in_out, float *w_out, int16_t *q01_out, bool trace,
                  void *workspace, size_t workspace_bytes, void *hip_stream, const char *who, int phases = kLocate | kEdges) {
@@ -1288,6 +1343,12 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   const size_t need = lutkan_forward_workspace_bytes(l, B);
   if (!workspace || workspace_bytes < need) return fail(LUTKAN_ESHAPE, "%s: workspace of %zu bytes, need %zu", who, workspace_bytes, need);
   if ((reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return fail(LUTKAN_EINVAL, "%s: workspace must be 256-byte aligned", who);
+  // A small narrow layer at a moderate batch: the one-launch chain kernel with a single layer beats locate + edge
+  // kernel (+ partial sums) by 1.4-2x (78x16, 128x8, 64x32 up to 8192 rows); with more inputs per output column the
+  // per-row walk over the inputs gets too long for it (256x64, 1024x64: slower).
+  if (l->algo == LUTKAN_ALGO_AUTO && phases == (kLocate | kEdges) && !trace && !q01_out && l->n_tiles == 1 &&
+      l->jt <= kChainMaxColumns && !l->knots_per_input && l->d * l->jt <= 4096 && B <= 8192)
+    return chain_impl(l, 1, x, B, y, nullptr, stats, hip_stream, who);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const int64_t Bp = padded_rows(B);
   const lutkan::BlobLayout lay = lutkan::blob_layout(l->K, l->L, l->jt, l->scheme, l->value_repr, l->param_dtype);
@@ -1577,56 +1638,7 @@ extern "C" size_t lutkan_model_workspace_bytes(const lutkan_dev_layer *layers, i
 
 extern "C" int lutkan_chain_forward(const lutkan_dev_layer *layers, int32_t n_layers, const float *x, int64_t B, float *y,
                                     float *hidden, lutkan_oob_stats *stats, void *hip_stream) {
-  const char *who = "lutkan_chain_forward";
-  if (!layers || n_layers < 1) return fail(LUTKAN_EINVAL, "%s: need at least one layer", who);
-  if (n_layers > kChainMaxLayers) return fail(LUTKAN_EUNSUPPORTED, "%s: at most %d layers (got %d)", who, kChainMaxLayers, n_layers);
-  ChainArgs ca = {};
-  int widest = 0;
-  for (int l = 0; l < n_layers; ++l) {
-    const lutkan_dev_layer *L = &layers[l];
-    if (int rc = validate_layer(L, who)) return rc;
-    if (l + 1 < n_layers && L->m != layers[l + 1].d) return fail(LUTKAN_ESHAPE, "%s: layer %d has m=%d but layer %d has d=%d", who, l, L->m, l + 1, layers[l + 1].d);
-    if (L->n_tiles != 1 || L->jt > kChainMaxColumns) return fail(LUTKAN_EUNSUPPORTED, "%s: layer %d has %d outputs in %d column tiles, the fused chain takes one tile of at most %d columns", who, l, L->m, L->n_tiles, kChainMaxColumns);
-    if (L->d > kChainMaxInputs) return fail(LUTKAN_EUNSUPPORTED, "%s: layer %d has %d inputs, the fused chain takes at most %d", who, l, L->d, kChainMaxInputs);
-    if (L->knots_per_input) return fail(LUTKAN_EUNSUPPORTED, "%s: layer %d has one knot vector per input; use lutkan_model_forward", who, l);
-    const lutkan::BlobLayout lay = lutkan::blob_layout(L->K, L->L, L->jt, L->scheme, L->value_repr, L->param_dtype);
-    ChainLayer &c = ca.layer[l];
-    c.table = static_cast<const unsigned char *>(L->table);
-    c.d = L->d; c.m = L->m; c.K = L->K; c.L = L->L; c.blob_bytes = L->blob_bytes;
-    c.jt_log2 = 0;
-    while ((1 << c.jt_log2) < L->jt) ++c.jt_log2;
-    c.codes_off = lay.codes_off; c.params_off = lay.params_off; c.param_row_bytes = lay.param_row_bytes;
-    c.sym = (L->scheme == LUTKAN_SYM_INT8);
-    c.with_base = (L->value_repr == LUTKAN_REPR_SPLINE_COMPONENT);
-    c.param_fp16 = (L->param_dtype == LUTKAN_PARAM_FP16);
-    c.closed = (L->boundary == LUTKAN_CLOSED);
-    c.zero_spline = (L->oob == LUTKAN_ZERO_SPLINE);
-    c.tKs = c.closed ? L->knots[L->K] : std::nextafterf(L->knots[L->K], -INFINITY);
-    for (int k = 0; k <= L->K; ++k) c.knots[k] = L->knots[k];
-    widest = std::max(widest, L->d);
-  }
-  if (B < 0) return fail(LUTKAN_EINVAL, "%s: B < 0", who);
-  if (B == 0) return LUTKAN_OK;
-  if (!x || !y || x == y) return fail(LUTKAN_EINVAL, "%s: null or aliased x / y", who);
-  // up to 1024 rows a whole work-group carries a row (the shortest path through a layer); beyond, one wave does
-  const int wpr = (B <= 1024) ? kChainWaves : 1;
-  const int rows_per_group = kChainWaves / wpr;
-  const int64_t groups = (B + rows_per_group - 1) / rows_per_group;
-  if (groups > 0x7fffffff) return fail(LUTKAN_EUNSUPPORTED, "%s: B too large", who);
-  ca.x = x; ca.y = y; ca.hidden = hidden;
-  ca.stats = reinterpret_cast<unsigned long long *>(stats);
-  ca.B = B; ca.n_layers = n_layers; ca.rec_stride = widest;
-  const size_t lds = (size_t)rows_per_group * widest * 16 + (size_t)(rows_per_group + kChainWaves) * kChainMaxColumns * 4 +
-                     kChainWaves * 4 + (size_t)n_layers * (LUTKAN_MAX_K + 1) * 4;
-  hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  if (wpr == 1) {
-    static LdsCap raised;         // four rows of the widest layer need more than the default 64 KiB
-    if (int rc = raise_lds_cap(lutkan_chain_kernel<1>, &raised, who)) return rc;
-    hipLaunchKernelGGL(lutkan_chain_kernel<1>, dim3((unsigned)groups), dim3(kChainWaves * 64), lds, s, ca);
-  } else {
-    hipLaunchKernelGGL(lutkan_chain_kernel<kChainWaves>, dim3((unsigned)groups), dim3(kChainWaves * 64), lds, s, ca);
-  }
-  return check_launch("lutkan_chain_kernel");
+  return chain_impl(layers, n_layers, x, B, y, hidden, stats, hip_stream, "lutkan_chain_forward");
 }
 
 extern "C" int lutkan_model_forward(const lutkan_dev_layer *layers, int32_t n_layers, const float *x, int64_t B, float *y,

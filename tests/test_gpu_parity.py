@@ -78,10 +78,9 @@ def _check_layer(s, x, algo, codes=False, what="", param_fp16=False):
     if codes:
         np.testing.assert_array_equal(q01.cpu().numpy(), ref.q01)
     worst = _assert_close(y.cpu().numpy(), ref, what)
-    if not codes:
+    worst = max(worst, _assert_close(y2.cpu().numpy(), ref, what + " (plain launch)"))
+    if not codes and algo != lk.ALGO_AUTO:              # a named kernel: trace and plain launch are the same arithmetic
         assert torch.equal(y, y2) or np.array_equal(np.isnan(y.cpu().numpy()), np.isnan(y2.cpu().numpy()))
-    else:
-        _assert_close(y2.cpu().numpy(), ref, what + " (non-trace launch)")
     st = stats.cpu().numpy()
     assert (int(st[0]), int(st[1])) == (ref.oob_count, ref.oob_any_rows)
     return worst
