@@ -41,7 +41,9 @@ typedef enum { LUTKAN_HALF_OPEN = 0, LUTKAN_CLOSED = 1 } lutkan_boundary;       
 typedef enum { LUTKAN_CLIP_X = 0, LUTKAN_ZERO_SPLINE = 1 } lutkan_oob;             /* Sec. 5.4 */
 /* Which edge kernel runs.  TILED stages each (tile, input) table slice in LDS; GATHER reads the touched table rows
  * from global memory and splits the inputs over the GPU.  AUTO: tiled when a slice fits LDS, except for batches of so
- * few rows that they touch less than the whole table (then gather); results agree to rounding, not bit for bit. */
+ * few rows that they touch less than the whole table (then gather), and except for a small narrow layer (one column
+ * tile, d * jt <= 4096) at up to 8192 rows, which lutkan_forward runs as a one-layer launch of the fused chain kernel;
+ * results agree to rounding, not bit for bit. */
 typedef enum { LUTKAN_ALGO_AUTO = 0, LUTKAN_ALGO_GATHER = 1, LUTKAN_ALGO_TILED = 2 } lutkan_algo;
 typedef enum { LUTKAN_REPR_PHI = 0, LUTKAN_REPR_SPLINE_COMPONENT = 1 } lutkan_value_repr;  /* Sec. 4.3 A / B */
 typedef enum { LUTKAN_PARAM_FP32 = 0, LUTKAN_PARAM_FP16 = 1 } lutkan_param_dtype;   /* Sec. 4.6: dtype of scale, y_min */
