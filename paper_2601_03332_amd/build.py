@@ -9,8 +9,10 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.environ.get("LUTKAN_LIBRARY", os.path.join(HERE, "liblutkan.so"))
 SOURCES = [os.path.join(CSRC, "lutkan_compile.cpp"), os.path.join(CSRC, "lutkan_kernels.hip"),
-           os.path.join(CSRC, "lutkan_probes.hip"), os.path.join(CSRC, "lutkan_stats.hip")]
-HEADERS = [os.path.join(CSRC, "lutkan_internal.h"), os.path.join(ROOT, "include", "lutkan.h")]
+           os.path.join(CSRC, "bspline_kernels.hip"), os.path.join(CSRC, "lutkan_probes.hip"),
+           os.path.join(CSRC, "lutkan_stats.hip")]
+HEADERS = [os.path.join(CSRC, "lutkan_internal.h"), os.path.join(CSRC, "lutkan_device.h"),
+           os.path.join(ROOT, "include", "lutkan.h")]
 
 # -ffp-contract=off: the index arithmetic of the locate kernel and the host quantiser must round once per
 #   operation; fused multiply-adds in the edge kernels are written explicitly.
@@ -20,7 +22,7 @@ HIPCC_FLAGS = [
     "-fhip-fp32-correctly-rounded-divide-sqrt",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-command-line-argument",
-    "-Wno-inline-asm",      # the LDS-DMA helper names M0 in its clobber list on purpose (see lutkan_kernels.hip)
+    "-Wno-inline-asm",      # the LDS-DMA helper names M0 in its clobber list on purpose (see lutkan_device.h)
 ]
 
 

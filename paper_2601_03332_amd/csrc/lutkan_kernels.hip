@@ -1,4 +1,5 @@
-// gfx950 kernels and launchers of liblutkan: LUT-KAN layer forward and the B-spline baseline layer.
+// gfx950 kernels and launchers of liblutkan: the LUT-KAN layer forward (the B-spline baseline layer is in
+// bspline_kernels.hip, what the two share in lutkan_device.h).
 //
 // Work split (Sec. 4.5, Sec. 5):
 //   1. locate kernel   per (row, input): domain test on the raw x (Sec. 5.2), safe clip (Eq. 13), segment
@@ -12,41 +13,10 @@
 //                      memory (used for table slices too large for LDS and for the code trace).
 //   3. chain kernel    both steps for every layer of a narrow network in one launch, activations in LDS (small
 //                      batches, where the launches of 1. and 2. per layer cost more than the arithmetic).
-// The B-spline baseline layer (Sec. 3.2-3.3) has the same split: span + basis values per (row, input), then four
-// coefficient FMAs per edge.
 // The file is compiled with -ffp-contract=off; every fused multiply-add below is written out as fmaf().
-#include <hip/hip_runtime.h>
-
-#include <algorithm>
-#include <atomic>
-#include <cmath>
-#include <cstdint>
-#include <type_traits>
-
-#include "lutkan_internal.h"
-
-using lutkan::fail;
+#include "lutkan_device.h"
 
 namespace {
-
-constexpr int kWave = 64;
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte load/store
-typedef unsigned int u32x3 __attribute__((ext_vector_type(3)));
-typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
-
-constexpr float kTwoTo24 = 16777216.0f;
-constexpr float kTwoToMinus24 = 1.0f / 16777216.0f;
-
-// A LUT lookup record, one per (input, row), stored [input][row].  value_repr = phi: 8 bytes
-//   x = table row k*L+l0 in bits 0..15, segment k in bits 16..31   (the all-zero rows K*L and K when masked)
-//   y = interpolation weight w as fp32 bits                        (0 when masked, NaN for a NaN input)
-// value_repr = spline_component: 16 bytes, the same two words, then
-//   z = SiLU(x) of the raw input as fp32 bits, w = 0.
-// The two 16-bit halves of x are what the tiled kernel scales (by the bytes of a code row resp. a parameter row)
-// and adds to a lane's column address, one multiply-add each; nothing else is computed per row.
 
 // ------------------------------------------------------------------------------------------------
 // Locate kernel (steps 1-4 of Sec. 4.5 + Sec. 5.2).
@@ -71,13 +41,6 @@ struct Located {
   bool inside, is_nan;
 };
 
-// The largest float below a finite t: nextafter(t, -inf), the safe upper clip value of Eq. 13 in half-open mode.
-__device__ __forceinline__ float next_float_below(float t) {
-  const unsigned bits = __float_as_uint(t);
-  if (t > 0.0f) return __uint_as_float(bits - 1u);
-  if (t < 0.0f) return __uint_as_float(bits + 1u);
-  return __uint_as_float(0x80000001u);                 // below +-0: the smallest negative subnormal
-}
 
 // s_knots: the K+1 knots of this element's input in LDS.  With one vector per layer (PERIN false) the comparisons
 // run against the copy in the kernel arguments (scalar registers) and LDS serves the two lookups by the lane's own
@@ -336,37 +299,6 @@ __global__ __launch_bounds__(256) void lutkan_gather_kernel(const EdgeArgs a, co
   a.y[(int64_t)blockIdx.z * a.split_stride + b * a.m + j] = acc;
 }
 
-// Asynchronous global -> LDS copy of 16 bytes per lane (gfx950 LDS-DMA form of the global load): the wave's
-// active lanes each fetch 16 bytes from their own global address and the data lands at lds_dst + 16*lane.
-// lds_dst must be wave-uniform (it travels in M0; one wait state separates the M0 write from the load).  M0 is
-// declared clobbered; nothing else in these kernels may keep a value in M0 (a test checks the generated code:
-// saving and restoring M0 around every copy was measured 1.3 % slower on the widest layer).
-// Completion is tracked by vmcnt like any other vector memory load.  The copy is written out as instructions
-// rather than through the compiler's builtin: for the builtin the compiler makes the wave wait for all its
-// outstanding copies before any later LDS read and before every barrier, because it cannot tell the stage
-// buffers apart; here the kernel waits itself (wait_all_vector_loads) before it reads what a copy wrote.
-__device__ __forceinline__ void copy16_global_to_lds(const void *gsrc, void *lds_dst) {
-  const unsigned dst = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(__attribute__((address_space(3))) void *)lds_dst);
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(gsrc) : "m0", "memory");
-}
-
-__device__ __forceinline__ void wait_all_vector_loads() { __builtin_amdgcn_s_waitcnt(0x0f70); }   // vmcnt(0)
-
-// Work-group barrier that orders LDS traffic only (__syncthreads() also drains the wave's global-memory traffic).
-__device__ __forceinline__ void lds_barrier() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-  __builtin_amdgcn_s_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
-
-// Copies n16 16-byte vectors from gsrc to lds_dst with all NW waves of the work-group, 1 KiB per wave step.
-template <int NW>
-__device__ __forceinline__ void stage_slice(const u32x4 *gsrc, unsigned char *lds_dst, int n16, int wave, int lane) {
-  for (int c = wave; c * 64 < n16; c += NW) {
-    const int v = c * 64 + lane;
-    if (v < n16) copy16_global_to_lds(gsrc + v, lds_dst + c * 1024);
-  }
-}
 
 // Tiled variant.  A work-group of NW waves owns NW*RW rows and one column tile of JT = 4*LPR outputs.
 // A wave works on RPS = 64/LPR rows at a time: LPR lanes share a row and each lane owns 4 adjacent columns,
@@ -751,355 +683,6 @@ __global__ __launch_bounds__(kChainWaves * 64) void lutkan_chain_kernel(const Ch
   }
 }
 
-// ------------------------------------------------------------------------------------------------
-// B-spline baseline (Sec. 3.2-3.3).
-// ------------------------------------------------------------------------------------------------
-// A B-spline record is 32 bytes per (input, row), stored [input][row] as two 16-byte halves:
-//   {byte offset of coefficient row k inside the input's coefficient slice, N0, N1, N2}, {N3, SiLU(x), 0, 0}
-// where N0..N3 are the four non-zero cubic basis values (all 0 when masked, NaN for a NaN input) and SiLU(x) of
-// the raw input is present for value_repr = spline_component (else 0).
-struct SplineLocateArgs {
-  const float *x;
-  u32x4 *rec;            // [d][Bp][2]
-  int64_t B, Bp;
-  int32_t d, G, jt;
-  int32_t closed, zero_spline, with_base;
-  int32_t extended;      // the domain is the whole extended knot vector (else its inner G intervals)
-  float tKs;
-  float ext_knots[LUTKAN_MAX_K + 7];
-  const float *input_ext_knots;   // [d][G+7]: one knot vector per input (then ext_knots and tKs are not used)
-};
-
-constexpr int kSplTile = 1024;  // (row, input) pairs per block of the B-spline locate kernel (32-byte records)
-
-// Same tiling as the LUT locate kernel: blockIdx.x = tile of ROWS rows, blockIdx.y = tile of COLS inputs
-// (COLS = 32 or 16, ROWS * COLS = 1024).  PERIN: one knot vector per input, the block keeps those of its COLS inputs.
-template <int COLS, bool PERIN>
-__global__ __launch_bounds__(256) void bspline_locate_kernel(const SplineLocateArgs a) {
-  constexpr int ROWS = kSplTile / COLS;
-  constexpr int PSTRIDE = LUTKAN_MAX_K + 13;
-  static_assert(PSTRIDE % 2 == 1, "odd stride between the knot rows");
-  __shared__ u32x4 s_rec[2][COLS][ROWS + 1];
-  // the extended knots with three made-up knots on either side: s_pad[3 + r] = ext_knots[r].  A basis function that
-  // exists (index 0 .. G+2) only ever touches real knots; the padding keeps the recursion of the others in bounds.
-  __shared__ float s_pad[(PERIN ? COLS : 1) * PSTRIDE];
-  const int tid = threadIdx.x;
-  const int64_t b0 = (int64_t)blockIdx.x * ROWS;
-  const int i0 = blockIdx.y * COLS;
-  const int n = a.G + 7;
-  for (int q = tid; q < (PERIN ? COLS : 1) * (n + 6); q += 256) {
-    const int c = q / (n + 6), r = q - c * (n + 6);
-    float v = 0.0f;
-    if (!PERIN || i0 + c < a.d) {
-      const float *src = PERIN ? a.input_ext_knots + (int64_t)(i0 + c) * n : a.ext_knots;
-      if (r < 3) v = src[0] - (float)(3 - r) * (src[1] - src[0]);
-      else if (r >= n + 3) v = src[n - 1] + (float)(r - n - 2) * (src[n - 1] - src[n - 2]);
-      else v = src[r - 3];
-    }
-    s_pad[c * PSTRIDE + r] = v;
-  }
-  __syncthreads();
-  const int first_knot = a.extended ? 0 : 3;           // domain knot kappa is extended knot first_knot + kappa
-  const int segments = a.extended ? a.G + 6 : a.G;
-  const int R = a.G + 3;
-  {
-    const int il = tid % COLS;
-    const int i = i0 + il;
-    const float *s_tau = s_pad + (PERIN ? il * PSTRIDE : 0) + 3;
-    const float t0 = s_tau[first_knot], tK = s_tau[first_knot + segments];
-    const float tKs = PERIN ? (a.closed ? tK : next_float_below(tK)) : a.tKs;
-#pragma unroll 1
-    for (int p = 0; p < kSplTile / 256; ++p) {
-      const int bl = p * (256 / COLS) + tid / COLS;
-      const int64_t b = b0 + bl;
-      int k = 0;
-      float n0 = 0.f, n1 = 0.f, n2 = 0.f, n3 = 0.f, base = 0.f;
-      if (b < a.B && i < a.d) {
-        const float x = a.x[b * a.d + i];
-        if (a.with_base) base = __fdiv_rn(x, 1.0f + expf(-x));             // SiLU at the raw input, never masked
-        const bool is_nan = (x != x);
-        const bool inside = a.closed ? (x >= t0 && x <= tK) : (x >= t0 && x < tK);
-        float xc = is_nan ? t0 : x;
-        xc = (xc < t0) ? t0 : xc;
-        xc = (xc > tKs) ? tKs : xc;
-        for (int kappa = 1; kappa < segments; ++kappa) k += (s_tau[first_knot + kappa] <= xc) ? 1 : 0;
-        // Cox-de Boor on the span mu = first_knot + k, non-zero entries only (Eq. 4-5); knots are distinct.
-        const int mu = first_knot + k;
-        const float *tau = s_tau + (mu - 3);        // tau[0..7] = ext_knots[mu-3 .. mu+4] (padding beyond the ends)
-        float lower[5] = {0.f, 0.f, 0.f, 1.f, 0.f};
-#pragma unroll
-        for (int q = 1; q <= 3; ++q) {
-          float next[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-          for (int s = 3 - q; s <= 3; ++s) {
-            const float left = (xc - tau[s]) / (tau[s + q] - tau[s]) * lower[s];
-            const float right = (tau[s + q + 1] - xc) / (tau[s + q + 1] - tau[s + 1]) * lower[s + 1];
-            next[s] = left + right;
-          }
-#pragma unroll
-          for (int s = 0; s < 5; ++s) lower[s] = next[s];
-        }
-        // oob_policy zero_spline: all four weights 0 (the contribution is then exactly zero); NaN poisons them
-        const bool masked = a.zero_spline && !inside && !is_nan;
-        float gate = is_nan ? __builtin_nanf("") : (masked ? 0.0f : 1.0f);
-        // at the last extended knot itself every basis function is 0 (half-open degree-0 indicator, Eq. 4)
-        if (a.extended && xc == tK && !is_nan) gate = 0.0f;
-        // lower[e] belongs to function mu-3+e.  The four coefficient rows read are first .. first+3 with first
-        // clamped into [0, R-4]; a slot whose function does not exist (outer spans of the extended range) gets 0.
-        const int first = min(max(mu - 3, 0), R - 4);
-        const int shift = first - (mu - 3);          // -3 .. 3, 0 on the inner grid
-        float slot[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int from = e + shift;
-          float v = 0.0f;
-#pragma unroll
-          for (int f = 0; f < 4; ++f) v = (from == f) ? lower[f] : v;
-          slot[e] = v * gate;
-        }
-        n0 = slot[0]; n1 = slot[1]; n2 = slot[2]; n3 = slot[3];
-        k = first;
-      }
-      s_rec[0][il][bl] = u32x4{(unsigned)((k + a.with_base) * a.jt * 4), __float_as_uint(n0), __float_as_uint(n1), __float_as_uint(n2)};
-      s_rec[1][il][bl] = u32x4{__float_as_uint(n3), __float_as_uint(base), 0u, 0u};
-    }
-    __syncthreads();
-    const int bl2 = tid % ROWS;
-#pragma unroll 1
-    for (int p = 0; p < kSplTile / 256; ++p) {
-      const int il2 = p * (256 / ROWS) + tid / ROWS;
-      const int i2 = i0 + il2;
-      if (i2 < a.d && b0 + bl2 < a.Bp) {
-        const int64_t o = ((int64_t)i2 * a.Bp + b0 + bl2) * 2;
-        a.rec[o] = s_rec[0][il2][bl2];
-        a.rec[o + 1] = s_rec[1][il2][bl2];
-      }
-    }
-  }
-}
-
-struct SplineEdgeArgs {
-  const float *coef_table;   // [t][i][rows][jt]
-  const u32x4 *rec;          // [d][Bp][2]
-  float *y;
-  int64_t B, Bp;
-  int32_t d, m, rows;        // rows of a coefficient slice: R, plus the leading s_out*s_base row with spline_component
-  int32_t with_base;
-  int32_t jt, n_tiles;
-  int32_t chunk;
-  int64_t split_stride;
-};
-
-__global__ __launch_bounds__(256) void bspline_gather_kernel(const SplineEdgeArgs a, const int jx_log2) {
-  constexpr int U = 4;                      // inputs per batch of independent loads, as in the LUT gather kernel
-  const int jx = 1 << jx_log2;
-  const int tx = threadIdx.x & (jx - 1);
-  const int ty = threadIdx.x >> jx_log2;
-  const int j = blockIdx.y * jx + tx;
-  const int64_t b = (int64_t)blockIdx.x * (256 >> jx_log2) + ty;
-  if (j >= a.m || b >= a.B) return;
-  const int t = j / a.jt, jj = j - t * a.jt;
-  const float *tile = a.coef_table + (size_t)t * a.d * a.rows * a.jt;
-  const int i_begin = blockIdx.z * a.chunk;            // chunks of inputs and partial sums as in the LUT gather kernel
-  const int i_end = min(a.d, i_begin + a.chunk);
-  float acc = 0.0f;
-  for (int i0 = i_begin; i0 < i_end; i0 += U) {
-    u32x4 r0[U], r1[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int64_t o = ((int64_t)min(i0 + u, i_end - 1) * a.Bp + b) * 2;
-      r0[u] = a.rec[o];
-      r1[u] = a.rec[o + 1];
-    }
-    float cf[U][4], bg[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const float *sl = tile + (size_t)min(i0 + u, i_end - 1) * a.rows * a.jt;
-      const float *c = sl + (r0[u].x >> 2) + jj;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) cf[u][q] = c[q * a.jt];
-      bg[u] = a.with_base ? sl[jj] : 0.0f;
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      if (i0 + u < i_end) {
-        acc = fmaf(__uint_as_float(r0[u].y), cf[u][0], acc);
-        acc = fmaf(__uint_as_float(r0[u].z), cf[u][1], acc);
-        acc = fmaf(__uint_as_float(r0[u].w), cf[u][2], acc);
-        acc = fmaf(__uint_as_float(r1[u].x), cf[u][3], acc);
-        if (a.with_base) acc = fmaf(bg[u], __uint_as_float(r1[u].y), acc);
-      }
-    }
-  }
-  a.y[(int64_t)blockIdx.z * a.split_stride + b * a.m + j] = acc;
-}
-
-// Tiled B-spline kernel: same ownership and streaming as the LUT tiled kernel; the staged slice is the input's
-// coefficient matrix c[R][JT]; per row four contiguous coefficient runs (rows k..k+3) are read and weighted by
-// the row's four basis values.
-template <int LPR, int NP, int NW, bool BASE>
-__global__ __launch_bounds__(NW * 64) void bspline_tiled_kernel(const SplineEdgeArgs a) {
-  extern __shared__ __align__(16) unsigned char lds[];
-  constexpr int JT = 4 * LPR;
-  constexpr int RPS = 64 / LPR;
-  constexpr int RW = RPS * NP;
-  static_assert(RW <= 64, "a wave's records for one input must fit two 1 KiB copy steps");
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int sub = lane & (LPR - 1);
-  const int hrow = lane / LPR;
-  const int t = blockIdx.x % a.n_tiles;
-  const int64_t rt = blockIdx.x / a.n_tiles;
-  const int64_t b0 = rt * (NW * RW) + (int64_t)wave * RW;
-  const int blob_bytes = a.rows * JT * 4;
-  const int nvec = blob_bytes >> 4;
-
-  float acc[NP][4];
-#pragma unroll
-  for (int p = 0; p < NP; ++p)
-#pragma unroll
-    for (int c = 0; c < 4; ++c) acc[p][c] = 0.0f;
-
-  const u32x4 *src = reinterpret_cast<const u32x4 *>(a.coef_table + (size_t)t * a.d * a.rows * JT);
-  // a wave's RW 32-byte records are 2*RW consecutive 16-byte vectors: lanes 0..63 take the first 64, then the rest
-  const u32x4 *rec_src = a.rec + b0 * 2;
-  unsigned char *rec_area = lds + 2 * blob_bytes + wave * (2 * RW * 32);
-  auto stage_records = [&](int i, unsigned char *dst) {
-    const u32x4 *g = rec_src + (int64_t)i * a.Bp * 2;
-    if (lane < 2 * RW) copy16_global_to_lds(g + lane, dst);
-    if (2 * RW > 64 && lane + 64 < 2 * RW) copy16_global_to_lds(g + 64 + lane, dst + 1024);
-  };
-
-  const int i_begin = blockIdx.y * a.chunk;
-  const int i_end = min(a.d, i_begin + a.chunk);
-  float *yout = a.y + (int64_t)blockIdx.y * a.split_stride;
-
-  stage_slice<NW>(src + (size_t)i_begin * nvec, lds, nvec, wave, lane);
-  stage_records(i_begin, rec_area);
-  wait_all_vector_loads();
-  __syncthreads();
-
-  for (int i = i_begin; i < i_end; ++i) {
-    const int cur = (i - i_begin) & 1;
-    if (i + 1 < i_end) {
-      stage_slice<NW>(src + (size_t)(i + 1) * nvec, lds + (cur ^ 1) * blob_bytes, nvec, wave, lane);
-      stage_records(i + 1, rec_area + (cur ^ 1) * (RW * 32));
-    }
-    const unsigned char *rec_buf = rec_area + cur * (RW * 32) + hrow * 32;
-    const unsigned char *col_coef = lds + cur * blob_bytes + sub * 16;
-    // Same software pipeline as the LUT kernel: wait once per step, then issue the coefficient reads of step
-    // p+1 and the record of step p+2, then do the arithmetic of step p.
-    struct Rec { u32x4 a; float n3, base; };
-    struct Coefs { f32x4 c[4]; };
-    f32x4 base_gain = {0.f, 0.f, 0.f, 0.f};
-    if (BASE) base_gain = *reinterpret_cast<const f32x4 *>(col_coef);        // row 0 of the slice: s_out*s_base
-    auto read_rec = [&](int p) {
-      Rec r;
-      r.a = *reinterpret_cast<const u32x4 *>(rec_buf + p * (RPS * 32));
-      if (BASE) {
-        const f32x2 t2 = *reinterpret_cast<const f32x2 *>(rec_buf + p * (RPS * 32) + 16);
-        r.n3 = t2.x;
-        r.base = t2.y;
-      } else {
-        r.n3 = *reinterpret_cast<const float *>(rec_buf + p * (RPS * 32) + 16);
-        r.base = 0.0f;
-      }
-      return r;
-    };
-    auto fetch = [&](const Rec &r) {
-      Coefs f;
-      const unsigned char *cp = col_coef + r.a.x;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) f.c[q] = *reinterpret_cast<const f32x4 *>(cp + q * (JT * 4));
-      return f;
-    };
-    Rec rc_cur = read_rec(0);
-    Rec rc_nxt = read_rec(NP > 1 ? 1 : 0);
-    Coefs f_cur = fetch(rc_cur);
-#pragma unroll
-    for (int p = 0; p < NP; ++p) {
-      Coefs f_nxt = f_cur;
-      Rec rc_nn = rc_nxt;
-      asm volatile("" ::"v"(f_cur.c[3]), "v"(rc_nxt.n3));                       // first touch of step p's data
-      __builtin_amdgcn_sched_barrier(0);
-      if (p + 2 < NP) rc_nn = read_rec(p + 2);
-      if (p + 1 < NP) f_nxt = fetch(rc_nxt);
-      __builtin_amdgcn_sched_barrier(0);
-      const float n[4] = {__uint_as_float(rc_cur.a.y), __uint_as_float(rc_cur.a.z), __uint_as_float(rc_cur.a.w), rc_cur.n3};
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        acc[p][0] = fmaf(n[q], f_cur.c[q].x, acc[p][0]);
-        acc[p][1] = fmaf(n[q], f_cur.c[q].y, acc[p][1]);
-        acc[p][2] = fmaf(n[q], f_cur.c[q].z, acc[p][2]);
-        acc[p][3] = fmaf(n[q], f_cur.c[q].w, acc[p][3]);
-      }
-      if constexpr (BASE) {
-        acc[p][0] = fmaf(base_gain.x, rc_cur.base, acc[p][0]);
-        acc[p][1] = fmaf(base_gain.y, rc_cur.base, acc[p][1]);
-        acc[p][2] = fmaf(base_gain.z, rc_cur.base, acc[p][2]);
-        acc[p][3] = fmaf(base_gain.w, rc_cur.base, acc[p][3]);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-      rc_cur = rc_nxt;
-      rc_nxt = rc_nn;
-      f_cur = f_nxt;
-    }
-    wait_all_vector_loads();
-    lds_barrier();
-  }
-
-  const int j = t * JT + sub * 4;
-#pragma unroll
-  for (int p = 0; p < NP; ++p) {
-    const int64_t b = b0 + p * RPS + hrow;
-    if (b < a.B) {
-      if (j + 3 < a.m && (a.m & 3) == 0) {
-        *reinterpret_cast<f32x4 *>(yout + b * a.m + j) = f32x4{acc[p][0], acc[p][1], acc[p][2], acc[p][3]};
-      } else {
-#pragma unroll
-        for (int c = 0; c < 4; ++c)
-          if (j + c < a.m) yout[b * a.m + j + c] = acc[p][c];
-      }
-    }
-  }
-}
-
-// Sums the n_split partial outputs of the tiled kernels in ascending chunk order (deterministic): y = sum_s part[s].
-__global__ __launch_bounds__(256) void sum_partials_kernel(const float *part, float *y, int64_t n, int n_split) {
-  const int64_t e = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
-  if (e + 3 < n && (n & 3) == 0) {                   // 16-byte path needs every chunk's base aligned
-    f32x4 acc = *reinterpret_cast<const f32x4 *>(part + e);
-#pragma unroll 8
-    for (int s = 1; s < n_split; ++s) acc += *reinterpret_cast<const f32x4 *>(part + (int64_t)s * n + e);   // loads of 8 chunks in flight
-    *reinterpret_cast<f32x4 *>(y + e) = acc;
-  } else {
-    for (int64_t q = e; q < n && q < e + 4; ++q) {
-      float acc = part[q];
-      for (int s = 1; s < n_split; ++s) acc += part[(int64_t)s * n + q];
-      y[q] = acc;
-    }
-  }
-}
-
-// ------------------------------------------------------------------------------------------------
-// Host launchers.
-// ------------------------------------------------------------------------------------------------
-constexpr int kTileWaves = 16;          // waves per tiled work-group (1024 threads, one work-group per CU)
-constexpr int kMaxTileRows = kTileWaves * 64;   // largest row tile of any tiled variant; Bp is a multiple of it
-constexpr int kMaxTiledLds = 144 * 1024;
-
-inline int64_t round_up(int64_t v, int64_t q) { return (v + q - 1) / q * q; }
-inline int64_t padded_rows(int64_t B) { return round_up(B, kMaxTileRows); }
-inline int lut_record_bytes(int value_repr) { return value_repr == LUTKAN_REPR_SPLINE_COMPONENT ? 16 : 8; }
-inline size_t record_bytes(int d, int64_t Bp, int bytes_per_record) { return (size_t)round_up((int64_t)d * Bp * bytes_per_record, 256); }
-
-int check_launch(const char *what) {
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return fail(LUTKAN_EHIP, "%s: %s", what, hipGetErrorString(e));
-  return LUTKAN_OK;
-}
-
 int validate_layer(const lutkan_dev_layer *l, const char *who) {
   if (!l) return fail(LUTKAN_EINVAL, "%s: null layer", who);
   if (!l->table) return fail(LUTKAN_EINVAL, "%s: layer.table is null", who);
@@ -1123,71 +706,6 @@ int validate_layer(const lutkan_dev_layer *l, const char *who) {
   return LUTKAN_OK;
 }
 
-int gather_jx_log2(int m) {
-  int lg = 2;
-  while ((1 << lg) < m && lg < 8) ++lg;
-  return lg;
-}
-
-// Launch shape of the tiled kernels for B rows: NP row steps per wave (16/8/4/2/1, at most 64 rows per wave) and
-// the number of chunks the d inputs are split into (each with its own work-groups and its own set of partial sums).
-// Chosen by a small cost model, in microseconds, over every (NP, chunk count) pair:
-//   one input of one work-group   max(0.55 + 0.11 * NP, slice bytes at 100 GB/s) + 0.1
-//                                 (barrier and address set-up, NP row steps of 256 edges per wave, the slice's
-//                                 global -> LDS copy when that is the longer of the two)
-//   one work-group                3 + its inputs (pipeline fill, accumulator write-back)
-//   the launch                    rounds of 256 work-groups (one per compute unit), one after the other
-//   the partial sums              4 + their bytes at 3 TB/s, when there is more than one chunk
-// The constants come from the widest workload (2.4 us per input at NP = 16), a 64x1024 layer at NP = 4 (1.1 us) and
-// sweeps over batch sizes of 78x16 ... 4096x256 layers; the model replaced a rule (largest row tile first, split the inputs until 256
-// work-groups, at most 32 chunks) that lost up to 40 % on wide-input, narrow-output layers at a few hundred rows.
-struct TilePlan {
-  int np, n_split, chunk;
-};
-
-TilePlan plan_tiles(int64_t B, int d, int m, int n_tiles, int rps, int slice_bytes) {
-  const int np_max = std::min(16, 64 / rps);
-  const int max_split = std::max(1, std::min(128, d / 8));
-  TilePlan best{np_max, 1, d};
-  double best_cost = 1e300;
-  for (int np = np_max; np >= 1; np >>= 1) {
-    const int64_t rows = (int64_t)kTileWaves * rps * np;
-    const int64_t groups = (B + rows - 1) / rows * n_tiles;
-    const double per_input = std::max(0.55 + 0.11 * np, slice_bytes / 100e3) + 0.1;
-    // candidate chunk counts: 1 .. 8, then the counts that fill whole rounds of 256 work-groups, and the cap
-    int candidates[16];
-    int n_candidates = 0;
-    for (int c = 1; c <= 8; ++c) candidates[n_candidates++] = c;
-    for (int rounds = 1; rounds <= 4; ++rounds) candidates[n_candidates++] = (int)std::min<int64_t>(max_split, (256 * rounds + groups - 1) / groups);
-    candidates[n_candidates++] = max_split;
-    for (int q = 0; q < n_candidates; ++q) {
-      const int want = std::min(candidates[q], max_split);
-      const int chunk = (d + want - 1) / want;
-      const int split = (d + chunk - 1) / chunk;      // no empty trailing chunks
-      const double rounds = (double)((groups * split + 255) / 256);
-      double cost = rounds * (3.0 + chunk * per_input);
-      if (split > 1) cost += 4.0 + (double)split * (double)B * m * 4.0 / 3e6;
-      if (cost < best_cost) { best_cost = cost; best = TilePlan{np, split, chunk}; }
-    }
-  }
-  return best;
-}
-
-// Launch shape of the gather kernel: the d inputs are cut into chunks (at least 4 inputs each, at most 64 chunks)
-// until the launch has about a million threads: a thread's walk over its inputs is a chain of dependent reads,
-// four inputs per round trip, so short chunks matter more than full compute units.
-struct GatherPlan {
-  int n_split, chunk;
-};
-
-GatherPlan plan_gather(int64_t B, int d, int m) {
-  const int64_t threads = B * (int64_t)m;
-  int64_t want = (threads >= (1 << 20)) ? 1 : ((1 << 20) + threads - 1) / threads;
-  want = std::min<int64_t>(want, std::min(64, std::max(1, d / 4)));
-  const int chunk = (int)((d + want - 1) / want);
-  return GatherPlan{(d + chunk - 1) / chunk, chunk};
-}
-
 // True when a batch is so small that reading only the table rows it touches (gather kernel, inputs split over the
 // GPU) moves fewer bytes than the whole table, which the tiled kernel streams once whatever the batch.
 bool prefer_gather_for_small_batch(const lutkan_dev_layer *l, int64_t B) {
@@ -1196,34 +714,6 @@ bool prefer_gather_for_small_batch(const lutkan_dev_layer *l, int64_t B) {
   const double touched = (double)B * l->d * l->n_tiles * (2.0 * l->jt + (double)lay.param_row_bytes);
   const double table = (double)l->n_tiles * l->d * l->blob_bytes;
   return touched <= table;     // measured crossover: 1024x1024 near 100 rows, 256x256 near 200, both where the two are equal
-}
-
-// The default cap on a kernel's dynamic LDS (64 KiB) is below the 160 KiB a gfx950 CU has.  Raising it is a
-// per-kernel, per-device setting: one of these per kernel remembers which devices have it (bit = device ordinal).
-struct LdsCap {
-  std::atomic<uint64_t> devices{0};
-};
-
-template <typename Kern>
-int raise_lds_cap(Kern kern, LdsCap *cap, const char *what) {
-  int dev = 0;
-  hipError_t e = hipGetDevice(&dev);
-  if (e != hipSuccess) return fail(LUTKAN_EHIP, "%s: hipGetDevice: %s", what, hipGetErrorString(e));
-  if (dev < 0 || dev >= 64) return fail(LUTKAN_EUNSUPPORTED, "%s: device ordinal %d", what, dev);
-  const uint64_t bit = 1ull << dev;
-  if (cap->devices.load(std::memory_order_acquire) & bit) return LUTKAN_OK;
-  e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kMaxTiledLds);
-  if (e != hipSuccess) return fail(LUTKAN_EHIP, "%s: hipFuncSetAttribute(LDS): %s", what, hipGetErrorString(e));
-  cap->devices.fetch_or(bit, std::memory_order_release);
-  return LUTKAN_OK;
-}
-
-template <typename Kern, typename Args>
-int launch_with_lds(Kern kern, LdsCap *cap, const dim3 &grid, size_t lds, hipStream_t s, const Args &args, const char *what) {
-  if (lds > (size_t)kMaxTiledLds) return fail(LUTKAN_EUNSUPPORTED, "%s: needs %zu bytes of LDS", what, lds);
-  if (int rc = raise_lds_cap(kern, cap, what)) return rc;
-  hipLaunchKernelGGL(kern, grid, dim3(kTileWaves * 64), lds, s, args);
-  return check_launch(what);
 }
 
 template <int SCHEME, int LPR, int NP>
@@ -1267,7 +757,6 @@ bool tiled_supported(int jt, int blob_bytes) {
   return jt >= 4 && blob_bytes <= lutkan::kLdsSliceBudget;
 }
 
-enum { kLocate = 1, kEdges = 2 };
 
 template <bool BASE, bool PERIN>
 void launch_locate(int cols, dim3 grid, hipStream_t s, const LocateArgs &la) {
@@ -1435,155 +924,11 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   return check_launch("sum_partials_kernel");
 }
 
-template <int LPR, int NP>
-int launch_spline_tiled_np(const SplineEdgeArgs &ea, hipStream_t s) {
-  constexpr int NW = kTileWaves;
-  constexpr int RW = (64 / LPR) * NP;
-  const int bytes = ea.rows * 4 * LPR * 4;
-  const int64_t row_tiles = (ea.B + NW * RW - 1) / (NW * RW);
-  if (row_tiles * ea.n_tiles > 0x7fffffffLL) return fail(LUTKAN_EUNSUPPORTED, "bspline_tiled_kernel: B * m too large for one launch");
-  const dim3 grid((unsigned)(row_tiles * ea.n_tiles), (unsigned)((ea.d + ea.chunk - 1) / ea.chunk));
-  const size_t lds = 2 * (size_t)bytes + (size_t)NW * 2 * RW * 32;
-  static LdsCap raised, raised_base;
-  if (ea.with_base) return launch_with_lds(bspline_tiled_kernel<LPR, NP, NW, true>, &raised_base, grid, lds, s, ea, "bspline_tiled_kernel");
-  return launch_with_lds(bspline_tiled_kernel<LPR, NP, NW, false>, &raised, grid, lds, s, ea, "bspline_tiled_kernel");
-}
-
-template <int LPR>
-int launch_spline_tiled(const SplineEdgeArgs &ea, int np, hipStream_t s) {
-  constexpr int kMaxNp = (64 / (64 / LPR) < 16) ? 64 / (64 / LPR) : 16;
-  if constexpr (kMaxNp >= 16) { if (np >= 16) return launch_spline_tiled_np<LPR, 16>(ea, s); }
-  if constexpr (kMaxNp >= 8) { if (np >= 8) return launch_spline_tiled_np<LPR, 8>(ea, s); }
-  if constexpr (kMaxNp >= 4) { if (np >= 4) return launch_spline_tiled_np<LPR, 4>(ea, s); }
-  if constexpr (kMaxNp >= 2) { if (np >= 2) return launch_spline_tiled_np<LPR, 2>(ea, s); }
-  return launch_spline_tiled_np<LPR, 1>(ea, s);
-}
-
-int launch_spline_tiled_jt(const SplineEdgeArgs &ea, int np, hipStream_t s) {
-  switch (ea.jt) {
-    case 128: return launch_spline_tiled<32>(ea, np, s);
-    case 64: return launch_spline_tiled<16>(ea, np, s);
-    case 32: return launch_spline_tiled<8>(ea, np, s);
-    case 16: return launch_spline_tiled<4>(ea, np, s);
-    case 8: return launch_spline_tiled<2>(ea, np, s);
-    default: return launch_spline_tiled<1>(ea, np, s);
-  }
-}
-
-int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y, void *workspace,
-                 size_t workspace_bytes, void *hip_stream, const char *who, int phases) {
-  if (!l) return fail(LUTKAN_EINVAL, "%s: null layer", who);
-  if (!l->coef_table) return fail(LUTKAN_EINVAL, "%s: layer.coef_table is null", who);
-  if (l->knots_per_input != 0 && l->knots_per_input != 1) return fail(LUTKAN_EINVAL, "%s: bad knots_per_input %d", who, l->knots_per_input);
-  if (l->knots_per_input && (!l->input_ext_knots || (reinterpret_cast<uintptr_t>(l->input_ext_knots) & 3) != 0))
-    return fail(LUTKAN_EINVAL, "%s: knots_per_input needs layer.input_ext_knots (device, 4-byte aligned)", who);
-  if (l->d < 1 || l->m < 1 || l->G < 1 || l->G > LUTKAN_MAX_K) return fail(LUTKAN_EINVAL, "%s: bad d/m/G", who);
-  if (l->degree != 3) return fail(LUTKAN_EUNSUPPORTED, "%s: only cubic splines", who);
-  if (l->boundary != LUTKAN_HALF_OPEN && l->boundary != LUTKAN_CLOSED) return fail(LUTKAN_EINVAL, "%s: bad boundary_mode", who);
-  if (l->oob != LUTKAN_CLIP_X && l->oob != LUTKAN_ZERO_SPLINE) return fail(LUTKAN_EINVAL, "%s: bad oob_policy", who);
-  if (l->algo < LUTKAN_ALGO_AUTO || l->algo > LUTKAN_ALGO_TILED) return fail(LUTKAN_EINVAL, "%s: bad algo", who);
-  if (l->value_repr != LUTKAN_REPR_PHI && l->value_repr != LUTKAN_REPR_SPLINE_COMPONENT) return fail(LUTKAN_EINVAL, "%s: bad value_repr", who);
-  if (l->knot_span != LUTKAN_SPAN_DOMAIN && l->knot_span != LUTKAN_SPAN_EXTENDED) return fail(LUTKAN_EINVAL, "%s: bad knot_span", who);
-  for (int r = 0; r < l->G + 6; ++r)
-    if (!(l->ext_knots[r] < l->ext_knots[r + 1])) return fail(LUTKAN_EINVAL, "%s: knots not strictly increasing at %d", who, r);
-  if (l->jt < 4 || l->jt > 128 || (l->jt & (l->jt - 1))) return fail(LUTKAN_EINVAL, "%s: bad jt", who);
-  if (l->n_tiles != (l->m + l->jt - 1) / l->jt) return fail(LUTKAN_ESHAPE, "%s: n_tiles does not match m and jt", who);
-  if ((reinterpret_cast<uintptr_t>(l->coef_table) & 15) != 0) return fail(LUTKAN_EINVAL, "%s: coef_table must be 16-byte aligned", who);
-  if (l->coef_blob_bytes != lutkan::coef_slice_rows(l->G + 3, l->value_repr) * l->jt * 4) return fail(LUTKAN_ESHAPE, "%s: coef_blob_bytes does not match G, jt, value_repr", who);
-  if (B < 0) return fail(LUTKAN_EINVAL, "%s: B < 0", who);
-  if (B == 0) return LUTKAN_OK;
-  if (((phases & kLocate) && !x) || ((phases & kEdges) && !y) || x == y) return fail(LUTKAN_EINVAL, "%s: null or aliased x / y", who);
-  const size_t need = bspline_forward_workspace_bytes(l, B);
-  if (!workspace || workspace_bytes < need) return fail(LUTKAN_ESHAPE, "%s: workspace of %zu bytes, need %zu", who, workspace_bytes, need);
-  if ((reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return fail(LUTKAN_EINVAL, "%s: workspace must be 256-byte aligned", who);
-  hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  const int64_t Bp = padded_rows(B);
-  const int G = l->G;
-
-  SplineLocateArgs la;
-  la.x = x;
-  la.rec = static_cast<u32x4 *>(workspace);
-  la.B = B; la.Bp = Bp; la.d = l->d; la.G = G; la.jt = l->jt;
-  la.with_base = (l->value_repr == LUTKAN_REPR_SPLINE_COMPONENT);
-  la.closed = (l->boundary == LUTKAN_CLOSED);
-  la.zero_spline = (l->oob == LUTKAN_ZERO_SPLINE);
-  la.extended = (l->knot_span == LUTKAN_SPAN_EXTENDED);
-  const float domain_end = la.extended ? l->ext_knots[G + 6] : l->ext_knots[3 + G];
-  la.tKs = la.closed ? domain_end : std::nextafterf(domain_end, -INFINITY);
-  for (int r = 0; r < G + 7; ++r) la.ext_knots[r] = l->ext_knots[r];
-  la.input_ext_knots = l->knots_per_input ? l->input_ext_knots : nullptr;
-  if (phases & kLocate) {
-    const int cols = ((l->d + 15) / 16 * 16 < (l->d + 31) / 32 * 32) ? 16 : 32;      // the width that pads d least
-    const dim3 lgrid((unsigned)(Bp / (kSplTile / cols)), (unsigned)((l->d + cols - 1) / cols));
-    if (lgrid.y > 65535u) return fail(LUTKAN_EUNSUPPORTED, "%s: d too large", who);
-    if (l->knots_per_input) {
-      if (cols == 32) hipLaunchKernelGGL((bspline_locate_kernel<32, true>), lgrid, dim3(256), 0, s, la);
-      else hipLaunchKernelGGL((bspline_locate_kernel<16, true>), lgrid, dim3(256), 0, s, la);
-    } else {
-      if (cols == 32) hipLaunchKernelGGL((bspline_locate_kernel<32, false>), lgrid, dim3(256), 0, s, la);
-      else hipLaunchKernelGGL((bspline_locate_kernel<16, false>), lgrid, dim3(256), 0, s, la);
-    }
-    if (int rc = check_launch("bspline_locate_kernel")) return rc;
-  }
-  if (!(phases & kEdges)) return LUTKAN_OK;
-
-  SplineEdgeArgs ea;
-  ea.coef_table = l->coef_table; ea.rec = la.rec; ea.y = y;
-  ea.B = B; ea.Bp = Bp; ea.d = l->d; ea.m = l->m; ea.rows = lutkan::coef_slice_rows(G + 3, l->value_repr);
-  ea.with_base = la.with_base; ea.jt = l->jt; ea.n_tiles = l->n_tiles;
-  bool tiled = true;                                   // a coefficient slice always fits LDS (R <= 67)
-  if (l->algo == LUTKAN_ALGO_GATHER) tiled = false;
-  // up to 16 rows the gather kernel with the inputs split over the GPU is the faster one (measured on 256x256 and
-  // 1024x1024 layers): the tiled kernel's walk over all inputs is then a longer chain than the arithmetic
-  if (l->algo == LUTKAN_ALGO_AUTO && B <= 16) tiled = false;
-  if (l->algo == LUTKAN_ALGO_TILED && !tiled) return fail(LUTKAN_EUNSUPPORTED, "%s: tiled kernel unavailable", who);
-  ea.chunk = l->d;
-  ea.split_stride = 0;
-  if (tiled) {
-    const TilePlan tp = plan_tiles(B, l->d, l->m, l->n_tiles, 64 / (l->jt / 4), l->coef_blob_bytes);
-    float *partials = reinterpret_cast<float *>(static_cast<char *>(workspace) + record_bytes(l->d, Bp, 32));
-    ea.chunk = tp.chunk;
-    if (tp.n_split > 1) { ea.y = partials; ea.split_stride = B * l->m; }
-    const int rc = launch_spline_tiled_jt(ea, tp.np, s);
-    if (rc || tp.n_split == 1) return rc;
-    const int64_t n = B * l->m;
-    hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, s, partials, y, n, tp.n_split);
-    return check_launch("sum_partials_kernel");
-  }
-  const int lg = gather_jx_log2(l->m);
-  const GatherPlan gp = plan_gather(B, l->d, l->m);
-  float *partials = reinterpret_cast<float *>(static_cast<char *>(workspace) + record_bytes(l->d, Bp, 32));
-  ea.chunk = gp.chunk;
-  if (gp.n_split > 1) { ea.y = partials; ea.split_stride = B * l->m; }
-  const dim3 grid((unsigned)((B + (256 >> lg) - 1) / (256 >> lg)), (unsigned)((l->m + (1 << lg) - 1) >> lg), (unsigned)gp.n_split);
-  hipLaunchKernelGGL(bspline_gather_kernel, grid, dim3(256), 0, s, ea, lg);
-  if (int rc = check_launch("bspline_gather_kernel")) return rc;
-  if (gp.n_split == 1) return LUTKAN_OK;
-  const int64_t n = B * l->m;
-  hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, s, partials, y, n, gp.n_split);
-  return check_launch("sum_partials_kernel");
-}
-
 }  // namespace
-
-// Records for every (input, padded row), then room for the partial sums when the inputs are split into chunks.
-static size_t tiled_workspace_bytes(int d, int m, int jt, int n_tiles, int64_t B, int bytes_per_record, int slice_bytes) {
-  size_t bytes = record_bytes(d, padded_rows(B), bytes_per_record);
-  const TilePlan tp = plan_tiles(B, d, m, n_tiles, 64 / (jt / 4), slice_bytes);
-  const GatherPlan gp = plan_gather(B, d, m);           // either kernel may run: room for the larger set of partial sums
-  const int n_split = std::max(tp.n_split, gp.n_split);
-  if (n_split > 1) bytes += (size_t)n_split * (size_t)B * (size_t)m * 4;
-  return bytes;
-}
 
 extern "C" size_t lutkan_forward_workspace_bytes(const lutkan_dev_layer *layer, int64_t B) {
   if (!layer || B <= 0 || layer->d < 1 || layer->m < 1 || layer->jt < 4 || layer->n_tiles < 1) return 0;
   return tiled_workspace_bytes(layer->d, layer->m, layer->jt, layer->n_tiles, B, lut_record_bytes(layer->value_repr), layer->blob_bytes);
-}
-
-extern "C" size_t bspline_forward_workspace_bytes(const bspline_dev_layer *layer, int64_t B) {
-  if (!layer || B <= 0 || layer->d < 1 || layer->m < 1 || layer->jt < 4 || layer->n_tiles < 1) return 0;
-  return tiled_workspace_bytes(layer->d, layer->m, layer->jt, layer->n_tiles, B, 32, layer->coef_blob_bytes);
 }
 
 extern "C" int lutkan_forward(const lutkan_dev_layer *layer, const float *x, int64_t B, float *y,
@@ -1609,21 +954,6 @@ extern "C" int lutkan_forward_trace(const lutkan_dev_layer *layer, const float *
                                     void *workspace, size_t workspace_bytes, void *hip_stream) {
   return forward_impl(layer, x, B, y, nullptr, k_out, l0_out, in_out, w_out, q01_out, true, workspace,
                       workspace_bytes, hip_stream, "lutkan_forward_trace");
-}
-
-extern "C" int bspline_kan_forward(const bspline_dev_layer *l, const float *x, int64_t B, float *y,
-                                   void *workspace, size_t workspace_bytes, void *hip_stream) {
-  return bspline_impl(l, x, B, y, workspace, workspace_bytes, hip_stream, "bspline_kan_forward", kLocate | kEdges);
-}
-
-extern "C" int bspline_forward_locate(const bspline_dev_layer *l, const float *x, int64_t B, void *workspace,
-                                      size_t workspace_bytes, void *hip_stream) {
-  return bspline_impl(l, x, B, nullptr, workspace, workspace_bytes, hip_stream, "bspline_forward_locate", kLocate);
-}
-
-extern "C" int bspline_forward_edges(const bspline_dev_layer *l, int64_t B, float *y, void *workspace,
-                                     size_t workspace_bytes, void *hip_stream) {
-  return bspline_impl(l, nullptr, B, y, workspace, workspace_bytes, hip_stream, "bspline_forward_edges", kEdges);
 }
 
 extern "C" size_t lutkan_model_workspace_bytes(const lutkan_dev_layer *layers, int32_t n_layers, int64_t B) {

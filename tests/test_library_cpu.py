@@ -470,14 +470,17 @@ def test_m0_is_only_touched_by_the_lds_dma_helper(tmp_path):
     assembly (every mention of m0 in a tiled kernel lies inside an inline-asm block)."""
     import subprocess
     from paper_2601_03332_amd import build as lib_build
-    out = tmp_path / "kernels.s"
-    src = os.path.join(ROOT, "paper_2601_03332_amd", "csrc", "lutkan_kernels.hip")
-    cmd = [os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")] + lib_build.HIPCC_FLAGS + \
-          ["-I", os.path.join(ROOT, "include"), "-I", os.path.join(ROOT, "paper_2601_03332_amd", "csrc"),
-           "-x", "hip", "--cuda-device-only", "-S", src, "-o", str(out)]
-    subprocess.run(cmd, check=True, capture_output=True)
+    lines = []
+    for name in ("lutkan_kernels", "bspline_kernels"):
+        out = tmp_path / (name + ".s")
+        src = os.path.join(ROOT, "paper_2601_03332_amd", "csrc", name + ".hip")
+        cmd = [os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")] + lib_build.HIPCC_FLAGS + \
+              ["-I", os.path.join(ROOT, "include"), "-I", os.path.join(ROOT, "paper_2601_03332_amd", "csrc"),
+               "-x", "hip", "--cuda-device-only", "-S", src, "-o", str(out)]
+        subprocess.run(cmd, check=True, capture_output=True)
+        lines += open(out).readlines()
     kernels, inside_asm, current = 0, False, None
-    for line in open(out):
+    for line in lines:
         text = line.strip()
         if re.match(r"_Z\S*tiled_kernel\S*:", text):
             current, kernels = text.split(":")[0], kernels + 1
