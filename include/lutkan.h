@@ -249,7 +249,9 @@ int bspline_forward_edges(const bspline_dev_layer *layer, int64_t B, float *y,
 
 /* Per-layer chaining (Sec. 5.1: intermediate activations feed the next layer and may leave its domain):
  * y of layer l is x of layer l+1.  The workspace holds two ping-pong activation buffers plus the largest
- * per-layer scratch.  layers[l].m must equal layers[l+1].d.  stats (nullable) points to n_layers entries. */
+ * per-layer scratch.  layers[l].m must equal layers[l+1].d.  stats (nullable) points to n_layers entries.
+ * The result is bit-identical to calling lutkan_forward layer by layer; when every layer is one that lutkan_forward
+ * runs as a launch of the chain kernel (see lutkan_algo), the whole network runs as ONE launch of it. */
 size_t lutkan_model_workspace_bytes(const lutkan_dev_layer *layers, int32_t n_layers, int64_t B);
 int lutkan_model_forward(const lutkan_dev_layer *layers, int32_t n_layers, const float *x, int64_t B, float *y,
                          lutkan_oob_stats *stats, void *workspace, size_t workspace_bytes, void *hip_stream);

@@ -820,6 +820,12 @@ int chain_impl(const lutkan_dev_layer *layers, int32_t n_layers, const float *x,
   return check_launch("lutkan_chain_kernel");
 }
 
+// The layers that AUTO runs as a launch of the chain kernel (see forward_impl).
+bool small_layer_runs_as_chain(const lutkan_dev_layer *l, int64_t B) {
+  return l->algo == LUTKAN_ALGO_AUTO && l->n_tiles == 1 && l->jt <= kChainMaxColumns && !l->knots_per_input &&
+         l->d * l->jt <= 4096 && B <= 8192;
+}
+
 int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y, lutkan_oob_stats *stats,
                  int32_t *k_out, int32_t *l0_out, uint8_t *in_out, float *w_out, int16_t *q01_out, bool trace,
                  void *workspace, size_t workspace_bytes, void *hip_stream, const char *who, int phases = kLocate | kEdges) {
@@ -835,8 +841,7 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   // A small narrow layer at a moderate batch: the one-launch chain kernel with a single layer beats locate + edge
   // kernel (+ partial sums) by 1.4-2x (78x16, 128x8, 64x32 up to 8192 rows); with more inputs per output column the
   // per-row walk over the inputs gets too long for it (256x64, 1024x64: slower).
-  if (l->algo == LUTKAN_ALGO_AUTO && phases == (kLocate | kEdges) && !trace && !q01_out && l->n_tiles == 1 &&
-      l->jt <= kChainMaxColumns && !l->knots_per_input && l->d * l->jt <= 4096 && B <= 8192)
+  if (phases == (kLocate | kEdges) && !trace && !q01_out && small_layer_runs_as_chain(l, B))
     return chain_impl(l, 1, x, B, y, nullptr, stats, hip_stream, who);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const int64_t Bp = padded_rows(B);
@@ -987,6 +992,11 @@ extern "C" int lutkan_model_forward(const lutkan_dev_layer *layers, int32_t n_la
     if (l + 1 < n_layers) act = std::max(act, (size_t)round_up((int64_t)layers[l].m * B * 4, 256));
     scratch = std::max(scratch, lutkan_forward_workspace_bytes(&layers[l], B));
   }
+  // Every layer would run as its own launch of the chain kernel: run them as one launch of it instead.  The
+  // arithmetic per layer is the same, so the result is bit-identical to the layer-by-layer calls.
+  bool all_small = (n_layers <= kChainMaxLayers);
+  for (int l = 0; l < n_layers && all_small; ++l) all_small = small_layer_runs_as_chain(&layers[l], B);
+  if (all_small && n_layers > 1) return chain_impl(layers, n_layers, x, B, y, nullptr, stats, hip_stream, who);
   char *base = static_cast<char *>(workspace);
   float *ping[2] = {reinterpret_cast<float *>(base), reinterpret_cast<float *>(base + act)};
   void *rec = base + 2 * act;

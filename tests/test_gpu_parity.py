@@ -406,6 +406,13 @@ def test_cfg2_tabular_two_layer_chain_full_size():
     _chain_check(cfg2(), "cfg2")
 
 
+@pytest.mark.parametrize("B", [1, 300, 5000])
+def test_cfg2_tabular_chain_at_small_batches(B):
+    """Up to 8192 rows every layer of this network runs as a launch of the chain kernel, and lutkan_model_forward
+    runs the whole network as one launch of it: same arithmetic, so still bit-identical to the layer-by-layer calls."""
+    _chain_check(cfg2(B=B), f"cfg2 B={B}")
+
+
 @pytest.mark.parametrize("boundary,oob", [(HALF_OPEN, CLIP_X), (HALF_OPEN, ZERO_SPLINE), (CLOSED, CLIP_X), (CLOSED, ZERO_SPLINE)])
 def test_cfg5_deep_chain_robustness_matrix(boundary, oob):
     _chain_check(cfg5(B=16384 + 77, boundary=boundary, oob=oob), f"cfg5 b{boundary} o{oob}")
