@@ -298,7 +298,13 @@ def main():
         ws2 = torch.empty(lk.lutkan_model_workspace_bytes(chain, B2), dtype=torch.uint8, device=dev)
         full_ms = chain_ms(lambda: lk.lutkan_model_forward(chain, x2, y2, workspace=ws2))
         xs256, ys256 = x2[:256].contiguous(), y2[:256].contiguous()
-        layers_ms = chain_ms(lambda: lk.lutkan_model_forward(chain, xs256, ys256, workspace=ws2))
+        hid256 = torch.empty((256, chain[0].m), dtype=torch.float32, device=dev)
+
+        def layer_by_layer():
+            lk.lutkan_forward(chain[0], xs256, hid256, workspace=ws2)
+            lk.lutkan_forward(chain[1], hid256, ys256, workspace=ws2)
+
+        layers_ms = chain_ms(layer_by_layer)
         fused_ms = chain_ms(lambda: lk.lutkan_chain_forward(chain, xs256, ys256))
         chain_edges = sum(c.d * c.m for c in w2.layers)
         extra["tabular_chain_78_16_2"] = {"batch_65536_ms": round(full_ms, 4),

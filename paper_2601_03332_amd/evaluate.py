@@ -180,7 +180,7 @@ def main():
 
         print()
         print("Narrow chains, L = 64, grid 5: ms per forward, synchronised after every call | back to back on the stream")
-        print(f"{'network':>18} {'options':>28} {'batch':>7} {'per-layer launches':>22} {'fused chain':>22}")
+        print(f"{'network':>18} {'options':>28} {'batch':>7} {'lutkan_forward per layer':>26} {'fused chain':>22}")
         for widths, scheme, base, half, label in (((78, 16, 2), ASYM_UINT8, False, False, "uint8 phi fp32"),
                                                   ((78, 32, 16, 1), SYM_INT8, True, False, "int8 spline_component fp32"),
                                                   ((78, 32, 16, 1), ASYM_UINT8, True, True, "uint8 spline_component fp16")):
@@ -189,9 +189,15 @@ def main():
                 x = torch.randn((B, widths[0]), dtype=torch.float32, device=dev)
                 y = torch.empty((B, widths[-1]), dtype=torch.float32, device=dev)
                 ws = torch.empty(lk.lutkan_model_workspace_bytes(layers, B), dtype=torch.uint8, device=dev)
-                a = per_call_ms(lambda: lk.lutkan_model_forward(layers, x, y, workspace=ws), 200)
+                acts = [x] + [torch.empty((B, l.m), dtype=torch.float32, device=dev) for l in layers[:-1]] + [y]
+
+                def layer_by_layer():
+                    for l, src, dst in zip(layers, acts[:-1], acts[1:]):
+                        lk.lutkan_forward(l, src, dst, workspace=ws)
+
+                a = per_call_ms(layer_by_layer, 200)
                 f = per_call_ms(lambda: lk.lutkan_chain_forward(layers, x, y), 200)
-                print(f"{'->'.join(map(str, widths)):>18} {label:>28} {B:>7} {a[0]:>10.4f} | {a[1]:<9.4f} {f[0]:>10.4f} | {f[1]:<9.4f}")
+                print(f"{'->'.join(map(str, widths)):>18} {label:>28} {B:>7} {a[0]:>14.4f} | {a[1]:<9.4f} {f[0]:>10.4f} | {f[1]:<9.4f}")
 
 
 if __name__ == "__main__":
