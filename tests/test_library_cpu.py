@@ -518,3 +518,26 @@ def test_host_compile_matches_the_oracle_on_random_shapes():
                                               edge_scales=art.edge_scales, param_dtype=int(half))
         np.testing.assert_array_equal(back.table, art.table, err_msg=what)
         assert back.info.blob_bytes == art.info.blob_bytes and back.info.jt == art.info.jt
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The measurement script is single-GPU by design and says so (no GPU is touched before the check)."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "single-GPU" in (r.stderr + r.stdout)
+
+
+def test_product_package_does_not_touch_the_oracle():
+    """Nothing under the product package, the input generators or the build script may import or run the oracle."""
+    import glob
+    files = glob.glob(os.path.join(ROOT, "paper_2601_03332_amd", "**", "*"), recursive=True) + \
+        glob.glob(os.path.join(ROOT, "lutkan_inputs", "*.py")) + glob.glob(os.path.join(ROOT, "include", "*.h"))
+    checked = 0
+    for path in files:
+        if not path.endswith((".py", ".hip", ".cpp", ".h")):
+            continue
+        text = open(path).read()
+        checked += 1
+        assert "import oracle" not in text and "from oracle" not in text and "lutkan_oracle" not in text and "lko_" not in text, path
+    assert checked >= 10
