@@ -155,18 +155,17 @@ const float *lutkan_artifact_edge_out_scale(const lutkan_artifact *a);    /* [E]
 /* Device tables (host copies to upload verbatim).  Columns are cut into n_tiles tiles of jt outputs; the
  * last tile is zero padded.  LUT table: for tile t and input i one contiguous slice of blob_bytes bytes
  *     float   base  [jt]                       (spline_component only: s_out * s_base of the edge (i, column))
- *     float   gain  [jt]                       (spline_component with fp16 parameters only: s_out * s_spline)
  *     param   p     [K+1] rows                 (a row is alpha[jt], followed for the asymmetric scheme by y_min[jt] --
  *                                               y_min is elided when it is identically 0, Sec. 7.5; row K is all zero;
- *                                               values are fp32, or binary16 with fp16 parameters)
+ *                                               values are fp32, or binary16 for a phi layer with fp16 parameters)
  *     code    q     [K*L+2][jt]                (one byte per code, row k*L+l, i.e. the [i][segment][sample][j]
  *                                               order per tile: uint8 codes as they are, int8 codes excess-128,
  *                                               byte = q + 128; the two trailing rows are all-zero bytes)
  *     zero padding up to a multiple of 16 bytes
  * The zero rows are where the kernels redirect inputs whose contribution is exactly 0 (oob_policy zero_spline).
- * With spline_component the product s_out * s_spline of the edge is folded into its fp32 alpha and y_min (fp16
- * parameters are stored as they are, rounded, and the product sits in the gain row), and into the coefficients of
- * the B-spline table, whose slices then start with the same base[jt] row.
+ * With spline_component the product s_out * s_spline of the edge is folded into its alpha and y_min, held as fp32
+ * (with fp16 parameters: the products of the rounded values; the canonical arrays keep the rounded values
+ * themselves), and into the coefficients of the B-spline table, whose slices then start with the same base[jt] row.
  * slices ordered [t][i].  B-spline table: slices of float c[R = G+p][jt], ordered [t][i]. */
 const void *lutkan_artifact_table(const lutkan_artifact *a);
 const void *lutkan_artifact_coef_table(const lutkan_artifact *a);

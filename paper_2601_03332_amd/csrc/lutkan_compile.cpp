@@ -149,15 +149,11 @@ struct SlicePacker {
   int jt, L, scheme;
   bool half_params;
 
-  // s_out * s_base of the edge in column jj (spline_component only); with float16 parameters also s_out * s_spline,
-  // which cannot be folded into parameters that are stored rounded
-  void put_base(uint8_t *slice, int jj, float base_gain, float spline_gain) const {
-    reinterpret_cast<float *>(slice)[jj] = base_gain;
-    if (half_params) reinterpret_cast<float *>(slice)[jt + jj] = spline_gain;
-  }
+  // s_out * s_base of the edge in column jj (spline_component only)
+  void put_base(uint8_t *slice, int jj, float base_gain) const { reinterpret_cast<float *>(slice)[jj] = base_gain; }
 
   // Segment k of the edge in column jj: its dequantisation parameters (times gain = s_out * s_spline with
-  // spline_component, else exactly as given; binary16 parameters arrive already rounded) and its L codes.
+  // spline_component, else exactly as given; float16 parameters arrive already rounded) and its L codes.
   void put_segment(uint8_t *slice, int jj, int k, float alpha, float ymin, bool with_gain, float gain, const uint8_t *codes) const {
     // parameter row k: the alpha of every column, then (asymmetric only) the y_min of every column
     uint8_t *row = slice + lay.params_off + (size_t)k * lay.param_row_bytes;
@@ -300,7 +296,7 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
   nt = std::max(1, std::min(nt, 64));
   nt = (int)std::min<size_t>((size_t)nt, (size_t)d);
   std::atomic<long> unrepresentable{0};       // float16 parameters that overflowed
-  const SlicePacker packer{lay, jt, L, scheme, half_params};
+  const SlicePacker packer{lay, jt, L, scheme, half_params && !with_base};
   auto work = [&](int tid) {
     std::vector<float> v((size_t)L);
     std::vector<double> own_basis;
@@ -319,7 +315,7 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
         if (with_base) {
           const float base_gain = desc->edge_out_scale[e] * desc->edge_base_scale[e];
           spline_gain = desc->edge_out_scale[e] * desc->edge_spline_scale[e];
-          packer.put_base(slice, jj, base_gain, spline_gain);
+          packer.put_base(slice, jj, base_gain);
           cslice[jj] = base_gain;
           cslice += jt;
         }
@@ -432,7 +428,7 @@ extern "C" int lutkan_artifact_from_arrays(const lutkan_artifact_arrays *in, lut
     delete a;
     return fail(LUTKAN_ENOMEM, "%s: out of host memory for %zu edges", who, E);
   }
-  const SlicePacker packer{lay, jt, L, scheme, half_params};
+  const SlicePacker packer{lay, jt, L, scheme, half_params && !with_base};
   for (int i = 0; i < d; ++i)
     for (int j = 0; j < m; ++j) {
       const size_t e = (size_t)i * m + j;
@@ -440,7 +436,7 @@ extern "C" int lutkan_artifact_from_arrays(const lutkan_artifact_arrays *in, lut
       float spline_gain = 1.0f;
       if (with_base) {
         spline_gain = a->edge_out[e] * a->edge_spline[e];
-        packer.put_base(slice, j % jt, a->edge_out[e] * a->edge_base[e], spline_gain);
+        packer.put_base(slice, j % jt, a->edge_out[e] * a->edge_base[e]);
       }
       for (int k = 0; k < K; ++k)
         packer.put_segment(slice, j % jt, k, a->scale[e * K + k], a->ymin[e * K + k], with_base, spline_gain, a->q.data() + (e * K + k) * L);

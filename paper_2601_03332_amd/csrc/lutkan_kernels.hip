@@ -196,7 +196,7 @@ struct EdgeArgs {
   int32_t jt, n_tiles, blob_bytes;
   int32_t codes_off, params_off, param_row_bytes;
   int32_t with_base;       // value_repr = spline_component: slices start with a row of s_out*s_base, records carry SiLU(x)
-  int32_t param_fp16;      // dequantisation parameters are binary16 values (Sec. 4.6), else fp32
+  int32_t param_fp16;      // the table's dequantisation parameters are binary16 values (phi layers with float16 parameters), else fp32
   const int32_t *k_out, *l0_out;   // code trace only: the located (k, l0) of every (row, input), [B][d]
   int32_t chunk;           // tiled kernels: inputs per work-group (blockIdx.y selects the chunk of inputs)
   int64_t split_stride;    // tiled kernels: floats between the partial outputs of consecutive chunks (0 if one chunk)
@@ -250,7 +250,7 @@ __global__ __launch_bounds__(256) void lutkan_gather_kernel(const EdgeArgs a, co
       silu_x[u] = a.with_base ? __uint_as_float(r[2]) : 0.0f;
     }
     unsigned c0[U], c1[U];
-    float al[U], ym[U], bg[U], sg[U];      // alpha, y_min, s_out*s_base, s_out*s_spline (1 where it is folded in)
+    float al[U], ym[U], bg[U];             // alpha, y_min, s_out*s_base
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const unsigned char *slice = tile + (size_t)min(i0 + u, i_end - 1) * a.blob_bytes;
@@ -269,7 +269,6 @@ __global__ __launch_bounds__(256) void lutkan_gather_kernel(const EdgeArgs a, co
         ym[u] = (SCHEME == LUTKAN_ASYM_UINT8) ? prm[a.jt + jj] : 0.0f;
       }
       bg[u] = a.with_base ? reinterpret_cast<const float *>(slice)[jj] : 0.0f;
-      sg[u] = (a.with_base && a.param_fp16) ? reinterpret_cast<const float *>(slice)[a.jt + jj] : 1.0f;
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -277,12 +276,8 @@ __global__ __launch_bounds__(256) void lutkan_gather_kernel(const EdgeArgs a, co
         const float w = __uint_as_float(rec[u].y);
         const float f0 = code_to_float<SCHEME>(c0[u]), f1 = code_to_float<SCHEME>(c1[u]);
         const float tq = fmaf(w, f1 - f0, f0);                             // interpolate the codes ...
-        if (a.with_base && a.param_fp16) {                                 // unfolded: s_out*s_spline * (y_min + alpha * t)
-          acc = fmaf(sg[u], fmaf(al[u], tq, ym[u]), acc);
-        } else {
-          acc = fmaf(al[u], tq, acc);                                      // ... then one scale per edge
-          if (SCHEME == LUTKAN_ASYM_UINT8) acc += ym[u];
-        }
+        acc = fmaf(al[u], tq, acc);                                        // ... then one scale per edge
+        if (SCHEME == LUTKAN_ASYM_UINT8) acc += ym[u];
         if (a.with_base) acc = fmaf(bg[u], silu_x[u], acc);                  // + s_out*s_base * SiLU(x)
         if (TRACE && a.q01_out) {
           const int l0 = a.l0_out[b * a.d + i0 + u];
@@ -326,6 +321,7 @@ __global__ __launch_bounds__(256) void lutkan_gather_kernel(const EdgeArgs a, co
 // on the stored values.
 template <int SCHEME, int LPR, int NP, int NW, bool BASE, bool PH>
 __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a) {
+  static_assert(!(BASE && PH), "with the base branch the device table holds fp32 products, never binary16 parameters");
   extern __shared__ __align__(16) unsigned char lds[];
   constexpr int JT = 4 * LPR;
   constexpr int RPS = 64 / LPR;
@@ -384,10 +380,8 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
     // step where the wave waits for its outstanding LDS reads (the first touch of step p's data): what the
     // wave waits for was issued a whole step earlier, what it issues now has a whole step to arrive.
     typedef typename std::conditional<BASE, u32x3, u32x2>::type rec_t;        // 12-byte or 8-byte LDS read
-    f32x4 base_gain = {0.f, 0.f, 0.f, 0.f}, spline_gain = {1.f, 1.f, 1.f, 1.f};
+    f32x4 base_gain = {0.f, 0.f, 0.f, 0.f};
     if (BASE) base_gain = *reinterpret_cast<const f32x4 *>(slice + sub * 16) * kTwoToMinus24;
-    // float16 parameters are stored rounded, so s_out*s_spline cannot be folded into them: it has a row of its own
-    if (BASE && PH) spline_gain = *reinterpret_cast<const f32x4 *>(slice + JT * 4 + sub * 16);
     // parameters of the lane's 4 columns as loaded: pa = the four alphas, pb = the four y_min (asymmetric);
     // binary16 parameters are packed two per word in .x and .y
     struct Fetched { unsigned c0, c1; f32x4 pa, pb; };
@@ -457,24 +451,13 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
       const float t1 = fmaf(w, (float)dlo.y, (float)q0lo.y);
       const float t2 = fmaf(w, (float)dhi.x, (float)q0hi.x);
       const float t3 = fmaf(w, (float)dhi.y, (float)q0hi.y);
-      if constexpr (BASE && PH) {                                              // gain * (alpha * t + y_min * 2^-24)
-        const float u0 = fmaf(al[0], t0, (SCHEME == LUTKAN_ASYM_UINT8) ? ym[0] * kTwoToMinus24 : 0.0f);
-        const float u1 = fmaf(al[1], t1, (SCHEME == LUTKAN_ASYM_UINT8) ? ym[1] * kTwoToMinus24 : 0.0f);
-        const float u2 = fmaf(al[2], t2, (SCHEME == LUTKAN_ASYM_UINT8) ? ym[2] * kTwoToMinus24 : 0.0f);
-        const float u3 = fmaf(al[3], t3, (SCHEME == LUTKAN_ASYM_UINT8) ? ym[3] * kTwoToMinus24 : 0.0f);
-        acc[p][0] = fmaf(spline_gain.x, u0, acc[p][0]);
-        acc[p][1] = fmaf(spline_gain.y, u1, acc[p][1]);
-        acc[p][2] = fmaf(spline_gain.z, u2, acc[p][2]);
-        acc[p][3] = fmaf(spline_gain.w, u3, acc[p][3]);
-      } else {
-        acc[p][0] = fmaf(al[0], t0, acc[p][0]);
-        acc[p][1] = fmaf(al[1], t1, acc[p][1]);
-        acc[p][2] = fmaf(al[2], t2, acc[p][2]);
-        acc[p][3] = fmaf(al[3], t3, acc[p][3]);
-        if (SCHEME == LUTKAN_ASYM_UINT8) {
+      acc[p][0] = fmaf(al[0], t0, acc[p][0]);
+      acc[p][1] = fmaf(al[1], t1, acc[p][1]);
+      acc[p][2] = fmaf(al[2], t2, acc[p][2]);
+      acc[p][3] = fmaf(al[3], t3, acc[p][3]);
+      if (SCHEME == LUTKAN_ASYM_UINT8) {
 #pragma unroll
-          for (int c = 0; c < 4; ++c) acc[p][c] = fmaf(ym[c], kTwoToMinus24, acc[p][c]);
-        }
+        for (int c = 0; c < 4; ++c) acc[p][c] = fmaf(ym[c], kTwoToMinus24, acc[p][c]);
       }
       if constexpr (BASE) {
         const float silu_x = __uint_as_float(rc_cur.z);
@@ -624,7 +607,7 @@ __global__ __launch_bounds__(kChainWaves * 64) void lutkan_chain_kernel(const Ch
     for (int i0 = g; i0 < Y.d; i0 += U * stride) {
       u32x4 rec[U];
       unsigned c0[U], c1[U];
-      float al[U], ym[U], bg[U], sg[U];
+      float al[U], ym[U], bg[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const int i = min(i0 + u * stride, Y.d - 1);
@@ -644,7 +627,6 @@ __global__ __launch_bounds__(kChainWaves * 64) void lutkan_chain_kernel(const Ch
           ym[u] = Y.sym ? 0.0f : prm[jt + jj];
         }
         bg[u] = Y.with_base ? reinterpret_cast<const float *>(slice)[jj] : 0.0f;
-        sg[u] = (Y.with_base && Y.param_fp16) ? reinterpret_cast<const float *>(slice)[jt + jj] : 1.0f;
       }
 #pragma unroll
       for (int u = 0; u < U; ++u) {
@@ -653,12 +635,8 @@ __global__ __launch_bounds__(kChainWaves * 64) void lutkan_chain_kernel(const Ch
           const float bias = Y.sym ? 128.0f : 0.0f;                           // int8 codes are stored excess-128
           const float f0 = (float)c0[u] - bias, f1 = (float)c1[u] - bias;
           const float tq = fmaf(w, f1 - f0, f0);                               // Eq. 17 on the codes ...
-          if (Y.with_base && Y.param_fp16) {
-            acc = fmaf(sg[u], fmaf(al[u], tq, ym[u]), acc);
-          } else {
-            acc = fmaf(al[u], tq, acc);                                        // ... Eq. 10 once per edge
-            if (!Y.sym) acc += ym[u];
-          }
+          acc = fmaf(al[u], tq, acc);                                          // ... Eq. 10 once per edge
+          if (!Y.sym) acc += ym[u];
           if (Y.with_base) acc = fmaf(bg[u], __uint_as_float(rec[u].z), acc);  // + s_out*s_base * SiLU(x)
         }
       }
@@ -724,8 +702,7 @@ int launch_tiled_np(const EdgeArgs &ea, hipStream_t s) {
   if (row_tiles * ea.n_tiles > 0x7fffffffLL) return fail(LUTKAN_EUNSUPPORTED, "lutkan_tiled_kernel: B * m too large for one launch");
   const dim3 grid((unsigned)(row_tiles * ea.n_tiles), (unsigned)((ea.d + ea.chunk - 1) / ea.chunk));
   const size_t lds = 2 * (size_t)ea.blob_bytes + (size_t)NW * 2 * RW * (ea.with_base ? 16 : 8);
-  static LdsCap raised, raised_base, raised_half, raised_base_half;
-  if (ea.with_base && ea.param_fp16) return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, true, true>, &raised_base_half, grid, lds, s, ea, "lutkan_tiled_kernel");
+  static LdsCap raised, raised_base, raised_half;
   if (ea.with_base) return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, true, false>, &raised_base, grid, lds, s, ea, "lutkan_tiled_kernel");
   if (ea.param_fp16) return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, false, true>, &raised_half, grid, lds, s, ea, "lutkan_tiled_kernel");
   return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, false, false>, &raised, grid, lds, s, ea, "lutkan_tiled_kernel");
@@ -789,7 +766,7 @@ int chain_impl(const lutkan_dev_layer *layers, int32_t n_layers, const float *x,
     c.codes_off = lay.codes_off; c.params_off = lay.params_off; c.param_row_bytes = lay.param_row_bytes;
     c.sym = (L->scheme == LUTKAN_SYM_INT8);
     c.with_base = (L->value_repr == LUTKAN_REPR_SPLINE_COMPONENT);
-    c.param_fp16 = (L->param_dtype == LUTKAN_PARAM_FP16);
+    c.param_fp16 = lutkan::device_params_are_half(L->value_repr, L->param_dtype);
     c.closed = (L->boundary == LUTKAN_CLOSED);
     c.zero_spline = (L->oob == LUTKAN_ZERO_SPLINE);
     c.tKs = c.closed ? L->knots[L->K] : std::nextafterf(L->knots[L->K], -INFINITY);
@@ -889,7 +866,7 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   ea.jt = l->jt; ea.n_tiles = l->n_tiles; ea.blob_bytes = l->blob_bytes;
   ea.codes_off = lay.codes_off; ea.params_off = lay.params_off; ea.param_row_bytes = lay.param_row_bytes;
   ea.with_base = with_base; ea.k_out = k_out; ea.l0_out = l0_out;
-  ea.param_fp16 = (l->param_dtype == LUTKAN_PARAM_FP16);
+  ea.param_fp16 = lutkan::device_params_are_half(l->value_repr, l->param_dtype);
 
   bool tiled = tiled_supported(l->jt, l->blob_bytes) && !q01_out;
   if (l->algo == LUTKAN_ALGO_GATHER) tiled = false;

@@ -268,8 +268,9 @@ def test_fp16_parameter_tables(scheme):
 
 @pytest.mark.parametrize("scheme", [SYM_INT8, ASYM_UINT8])
 def test_fp16_parameters_with_spline_component(scheme):
-    """Sec. 4.6 float16 parameters together with Eq. 2's per-edge scalars: the parameters stay the rounded values
-    themselves (what Eq. 10 dequantises with), and s_out*s_spline has a float32 row of its own after the base row."""
+    """Sec. 4.6 float16 parameters together with Eq. 2's per-edge scalars: the canonical parameters are the rounded
+    values (what Eq. 10 dequantises with); the device table holds their fp32 products with s_out*s_spline, in the
+    layout of a float32 spline_component layer."""
     w = random_layer(97, 3, 70, 6, 16, scheme, CLOSED, CLIP_X, 4, with_base=True)
     s = w.layers[0]
     art = lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, scheme, s.boundary, s.oob,
@@ -281,9 +282,11 @@ def test_fp16_parameters_with_spline_component(scheme):
     I = art.info
     K, L, jt, nt = I.K, I.L, I.jt, I.n_tiles
     per = 2 if scheme == ASYM_UINT8 else 1
-    params_off = 2 * jt * 4
-    codes_off = params_off + (K + 1) * jt * 2 * per
+    params_off = jt * 4
+    codes_off = params_off + (K + 1) * jt * 4 * per
     assert I.blob_bytes == (codes_off + (K * L + 2) * jt + 15) // 16 * 16
+    a32 = lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, scheme, s.boundary, s.oob, edge_scales=s.edge_scales)
+    assert (a32.info.jt, a32.info.blob_bytes) == (jt, I.blob_bytes)
     sb, ss, so = (np.asarray(v, np.float32).reshape(-1) for v in s.edge_scales)
     tab = art.table.reshape(nt, s.d, I.blob_bytes)
     for t in range(nt):
@@ -291,14 +294,14 @@ def test_fp16_parameters_with_spline_component(scheme):
         n = cols.size
         for i in range(s.d):
             e = i * s.m + cols
-            head = tab[t, i, :params_off].view(np.float32).reshape(2, jt)
-            np.testing.assert_array_equal(head[0, :n], so[e] * sb[e])
-            np.testing.assert_array_equal(head[1, :n], so[e] * ss[e])
-            assert np.all(head[:, n:] == 0)
-            prm = tab[t, i, params_off:codes_off].view(np.float16).reshape(K + 1, per, jt)
-            np.testing.assert_array_equal(prm[:K, 0, :n].astype(np.float32), art.scale[e].T)
+            head = tab[t, i, :params_off].view(np.float32)
+            np.testing.assert_array_equal(head[:n], so[e] * sb[e])
+            assert np.all(head[n:] == 0)
+            gain = (so[e] * ss[e]).astype(np.float32)
+            prm = tab[t, i, params_off:codes_off].view(np.float32).reshape(K + 1, per, jt)
+            np.testing.assert_array_equal(prm[:K, 0, :n], (gain[None, :] * art.scale[e].T).astype(np.float32))
             if scheme == ASYM_UINT8:
-                np.testing.assert_array_equal(prm[:K, 1, :n].astype(np.float32), art.y_min[e].T)
+                np.testing.assert_array_equal(prm[:K, 1, :n], (gain[None, :] * art.y_min[e].T).astype(np.float32))
             assert np.all(prm[K] == 0)
 
 
