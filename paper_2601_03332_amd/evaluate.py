@@ -13,6 +13,7 @@ the LUT layer against the B-spline layer and the time of both per point: the lat
 With --cold-start it times the tabular chain 78 -> 16 -> 2 (L = 64 asymmetric uint8, batch 65536) twice, as the
 latency metrics of Sec. 6.5 distinguish: steady state (tables resident on the GPU) and cold start (every iteration
 reads the NPZ artifacts, rebuilds the device tables and uploads them before the forward).
+With --variants it times every option combination (scheme x value_repr x parameter dtype) on the widest workload.
 With --latency it times narrow chains at batches 1 .. 65536 as per-layer launches and as the fused one-launch chain.
 Both layers and the error statistics (lutkan_error_stats, Sec. 5.6) run as the library's HIP kernels.  The layers
 are randomly initialised here, so the absolute numbers are not the paper's; the trends are (error halves per
@@ -31,6 +32,7 @@ def main():
     ap.add_argument("--batch", type=int, default=4096)
     ap.add_argument("--sweep", action="store_true", help="also run the 256->256 L x scheme sweep with timings")
     ap.add_argument("--cold-start", action="store_true", help="also time steady-state vs cold-start latency of the 78->16->2 chain")
+    ap.add_argument("--variants", action="store_true", help="also time every option combination on the 1024 -> 1024 layer at batch 32768")
     ap.add_argument("--latency", action="store_true", help="also time narrow chains at small batches: per-layer launches vs the fused chain")
     args = ap.parse_args()
     import torch
@@ -145,6 +147,48 @@ def main():
         print()
         print(f"78 -> 16 -> 2, L = 64 asymmetric uint8, batch {B}: steady state {t_steady:.3f} ms/iter "
               f"({t_steady / B * 1e6:.3f} ns/sample), cold start {t_cold:.3f} ms/iter (NPZ artifacts: {size} bytes)")
+
+    if args.variants:
+        from lutkan_inputs import cfg4, draw_edge_scales
+
+        def event_ms(fn, n=10, warm=3):
+            for _ in range(warm):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(n):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / n
+
+        w = cfg4(B=32768)
+        s = w.layers[0]
+        x = torch.from_numpy(w.x).to(dev)
+        B = x.shape[0]
+        y = torch.empty((B, s.m), dtype=torch.float32, device=dev)
+        scales = draw_edge_scales(np.random.Generator(np.random.PCG64(1)), s.d, s.m)
+        print()
+        print(f"Option combinations on the {s.d} -> {s.m} layer (G = {s.G}, L = {s.L}), batch {B}: ms per forward, 10^12 edge-evaluations/s")
+        for scheme, sn in ((SYM_INT8, "int8"), (ASYM_UINT8, "uint8")):
+            for base in (False, True):
+                for half in (False, True):
+                    art = lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, scheme, s.boundary, s.oob,
+                                            edge_scales=scales if base else None, param_dtype=lk.PARAM_FP16 if half else lk.PARAM_FP32)
+                    layer = art.to_device(dev)
+                    ws = torch.empty(lk.lutkan_forward_workspace_bytes(layer, B), dtype=torch.uint8, device=dev)
+                    t = event_ms(lambda: lk.lutkan_forward(layer, x, y, workspace=ws))
+                    print(f"  LUT {sn:>5} {'spline_component' if base else 'phi':>16} {'float16' if half else 'float32'} parameters: "
+                          f"{t:7.3f} ms {B * s.d * s.m / t / 1e9:6.2f}")
+                    del layer, ws, art
+        for base in (False, True):
+            art = lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, SYM_INT8, s.boundary, s.oob,
+                                    edge_scales=scales if base else None)
+            bl = art.bspline_to_device(dev)
+            wsb = torch.empty(lk.bspline_forward_workspace_bytes(bl, B), dtype=torch.uint8, device=dev)
+            t = event_ms(lambda: lk.bspline_kan_forward(bl, x, y, workspace=wsb))
+            print(f"  B-spline layer {'spline_component' if base else 'phi':>16}: {t:7.3f} ms {B * s.d * s.m / t / 1e9:6.2f}")
+            del bl, wsb, art
 
     if args.latency:
         import time
