@@ -157,7 +157,8 @@ const float *lutkan_artifact_edge_out_scale(const lutkan_artifact *a);    /* [E]
  *     float   base  [jt]                       (spline_component only: s_out * s_base of the edge (i, column))
  *     param   p     [K+1] rows                 (a row is alpha[jt], followed for the asymmetric scheme by y_min[jt] --
  *                                               y_min is elided when it is identically 0, Sec. 7.5; row K is all zero;
- *                                               values are fp32, or binary16 for a phi layer with fp16 parameters)
+ *                                               values are fp32, or binary16 for a phi layer with fp16 parameters
+ *                                               on tiles of at most 32 columns)
  *     code    q     [K*L+2][jt]                (one byte per code, row k*L+l, i.e. the [i][segment][sample][j]
  *                                               order per tile: uint8 codes as they are, int8 codes excess-128,
  *                                               byte = q + 128; the two trailing rows are all-zero bytes)

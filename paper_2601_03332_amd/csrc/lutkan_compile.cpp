@@ -296,7 +296,7 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
   nt = std::max(1, std::min(nt, 64));
   nt = (int)std::min<size_t>((size_t)nt, (size_t)d);
   std::atomic<long> unrepresentable{0};       // float16 parameters that overflowed
-  const SlicePacker packer{lay, jt, L, scheme, half_params && !with_base};
+  const SlicePacker packer{lay, jt, L, scheme, device_params_are_half(repr, half_params ? LUTKAN_PARAM_FP16 : LUTKAN_PARAM_FP32, jt)};
   auto work = [&](int tid) {
     std::vector<float> v((size_t)L);
     std::vector<double> own_basis;
@@ -428,7 +428,7 @@ extern "C" int lutkan_artifact_from_arrays(const lutkan_artifact_arrays *in, lut
     delete a;
     return fail(LUTKAN_ENOMEM, "%s: out of host memory for %zu edges", who, E);
   }
-  const SlicePacker packer{lay, jt, L, scheme, half_params && !with_base};
+  const SlicePacker packer{lay, jt, L, scheme, device_params_are_half(repr, half_params ? LUTKAN_PARAM_FP16 : LUTKAN_PARAM_FP32, jt)};
   for (int i = 0; i < d; ++i)
     for (int j = 0; j < m; ++j) {
       const size_t e = (size_t)i * m + j;

@@ -16,24 +16,25 @@ int fail(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
 
 // Byte offsets inside one (tile, input) slice of the LUT device table:
 //   [base jt f32 (spline_component only)][params (K+1) rows of jt entries][codes (K*L+2) rows of jt bytes][pad to 16 B]
-// A parameter row is alpha[jt], then for the asymmetric scheme y_min[jt]; fp32 values, or binary16 values when the
-// artifact's parameters are float16 and nothing has to be folded into them (value_repr = phi).
+// A parameter row is alpha[jt], then for the asymmetric scheme y_min[jt]; fp32 values, or binary16 values (see
+// device_params_are_half).
 // Parameter row K and code rows K*L, K*L+1 are all zero: the kernels send masked inputs there.
 struct BlobLayout {
   int32_t params_off, param_row_bytes, codes_off, bytes;
 };
 
-// True when the device table holds the parameters as binary16 values: float16 parameters of a phi layer.  With
-// spline_component the table holds the fp32 products s_out*s_spline*alpha (of the rounded alpha) instead: a product
-// cannot be stored in 16 bits without a second rounding, and measured on the device the 16-bit rows save nothing.
-inline bool device_params_are_half(int value_repr, int param_dtype) {
-  return param_dtype == LUTKAN_PARAM_FP16 && value_repr != LUTKAN_REPR_SPLINE_COMPONENT;
+// True when the device table holds the parameters as binary16 values: float16 parameters of a phi layer on tiles
+// of at most 32 columns, where the shorter rows were measured 0-5 % faster; on the widest layer (64-column tiles) they
+// were a repeatable 3 % slower, so on wider tiles the (rounded) values are held as fp32.  With spline_component the table holds the fp32 products
+// s_out*s_spline*alpha of the rounded alpha: a product cannot be stored in 16 bits without a second rounding.
+inline bool device_params_are_half(int value_repr, int param_dtype, int jt) {
+  return param_dtype == LUTKAN_PARAM_FP16 && value_repr != LUTKAN_REPR_SPLINE_COMPONENT && jt <= 32;
 }
 
 inline BlobLayout blob_layout(int K, int L, int jt, int scheme, int value_repr, int param_dtype) {
   BlobLayout b;
   b.params_off = (value_repr == LUTKAN_REPR_SPLINE_COMPONENT) ? jt * 4 : 0;
-  b.param_row_bytes = jt * ((scheme == LUTKAN_ASYM_UINT8) ? 2 : 1) * (device_params_are_half(value_repr, param_dtype) ? 2 : 4);
+  b.param_row_bytes = jt * ((scheme == LUTKAN_ASYM_UINT8) ? 2 : 1) * (device_params_are_half(value_repr, param_dtype, jt) ? 2 : 4);
   b.codes_off = b.params_off + (K + 1) * b.param_row_bytes;
   int raw = b.codes_off + (K * L + 2) * jt;
   b.bytes = (raw + 15) & ~15;

@@ -766,7 +766,7 @@ int chain_impl(const lutkan_dev_layer *layers, int32_t n_layers, const float *x,
     c.codes_off = lay.codes_off; c.params_off = lay.params_off; c.param_row_bytes = lay.param_row_bytes;
     c.sym = (L->scheme == LUTKAN_SYM_INT8);
     c.with_base = (L->value_repr == LUTKAN_REPR_SPLINE_COMPONENT);
-    c.param_fp16 = lutkan::device_params_are_half(L->value_repr, L->param_dtype);
+    c.param_fp16 = lutkan::device_params_are_half(L->value_repr, L->param_dtype, L->jt);
     c.closed = (L->boundary == LUTKAN_CLOSED);
     c.zero_spline = (L->oob == LUTKAN_ZERO_SPLINE);
     c.tKs = c.closed ? L->knots[L->K] : std::nextafterf(L->knots[L->K], -INFINITY);
@@ -866,7 +866,7 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   ea.jt = l->jt; ea.n_tiles = l->n_tiles; ea.blob_bytes = l->blob_bytes;
   ea.codes_off = lay.codes_off; ea.params_off = lay.params_off; ea.param_row_bytes = lay.param_row_bytes;
   ea.with_base = with_base; ea.k_out = k_out; ea.l0_out = l0_out;
-  ea.param_fp16 = lutkan::device_params_are_half(l->value_repr, l->param_dtype);
+  ea.param_fp16 = lutkan::device_params_are_half(l->value_repr, l->param_dtype, l->jt);
 
   bool tiled = tiled_supported(l->jt, l->blob_bytes) && !q01_out;
   if (l->algo == LUTKAN_ALGO_GATHER) tiled = false;

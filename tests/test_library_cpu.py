@@ -228,11 +228,13 @@ def test_spline_component_tables_carry_the_base_row_and_folded_gains():
             np.testing.assert_array_equal(ctab[t, i, 1:, :n], (gain[None, :] * s.coef[i, cols].T).astype(np.float32))
 
 
+@pytest.mark.parametrize("m", [30, 70])
 @pytest.mark.parametrize("scheme", [SYM_INT8, ASYM_UINT8])
-def test_fp16_parameter_tables(scheme):
+def test_fp16_parameter_tables(scheme, m):
     """Sec. 4.6 float16 scale / y_min: codes as with fp32 parameters, parameters bit-identical to the oracle's
-    rounding, device rows hold the binary16 bit patterns, the byte accounting halves the parameter bytes."""
-    w = random_layer(91, 3, 70, 6, 16, scheme, CLOSED, CLIP_X, 4)
+    rounding, the byte accounting halves the parameter bytes; device rows hold the binary16 bit patterns on tiles of
+    up to 32 columns and the same rounded values as fp32 on wider ones."""
+    w = random_layer(91, 3, m, 6, 16, scheme, CLOSED, CLIP_X, 4)
     s = w.layers[0]
     art = lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, scheme, s.boundary, s.oob, param_dtype=lk.PARAM_FP16)
     a32 = lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, scheme, s.boundary, s.oob)
@@ -245,7 +247,9 @@ def test_fp16_parameter_tables(scheme):
     assert I.param_dtype == lk.PARAM_FP16 and a32.info.param_dtype == lk.PARAM_FP32
     K, L, jt, nt = I.K, I.L, I.jt, I.n_tiles
     per = 2 if scheme == ASYM_UINT8 else 1
-    codes_off = (K + 1) * jt * 2 * per
+    assert jt == (32 if m == 30 else 128)
+    pdt = np.float16 if jt <= 32 else np.float32
+    codes_off = (K + 1) * jt * np.dtype(pdt).itemsize * per
     assert I.blob_bytes == (codes_off + (K * L + 2) * jt + 15) // 16 * 16
     assert I.params_canonical_bytes == s.d * s.m * K * 2
     assert I.artifact_bytes == oracle.artifact_bytes(s.d * s.m, K, L, 4)
@@ -255,7 +259,7 @@ def test_fp16_parameter_tables(scheme):
         n = cols.size
         for i in range(s.d):
             e = i * s.m + cols
-            prm = tab[t, i, :codes_off].view(np.float16).reshape(K + 1, per, jt)
+            prm = tab[t, i, :codes_off].view(pdt).reshape(K + 1, per, jt)
             np.testing.assert_array_equal(prm[:K, 0, :n].astype(np.float32), art.scale[e].T)
             if scheme == ASYM_UINT8:
                 np.testing.assert_array_equal(prm[:K, 1, :n].astype(np.float32), art.y_min[e].T)
