@@ -264,8 +264,8 @@ int lutkan_model_forward(const lutkan_dev_layer *layers, int32_t n_layers, const
  *   hidden   device, nullable: receives the activations between the layers, layer after layer, each [B][m_l]
  *            (sum over l < n_layers-1 of B*m_l floats)
  *   stats    device, nullable, n_layers entries, ADDED to
- * EUNSUPPORTED: more than 8 layers, a layer with more than 64 outputs or more than 1024 inputs, or with one knot
- * vector per input (use lutkan_model_forward).  Other errors as lutkan_model_forward. */
+ * EUNSUPPORTED: more than 8 layers, a layer with more than one column tile (more than 64 outputs) or more than 1024
+ * inputs.  Other errors as lutkan_model_forward. */
 int lutkan_chain_forward(const lutkan_dev_layer *layers, int32_t n_layers, const float *x, int64_t B, float *y,
                          float *hidden, lutkan_oob_stats *stats, void *hip_stream);
 

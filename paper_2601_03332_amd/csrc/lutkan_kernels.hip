@@ -517,6 +517,7 @@ constexpr int kChainMaxColumns = 64;      // widest layer output: one lane per c
 
 struct ChainLayer {
   const unsigned char *table;
+  const float *input_knots;        // nullable: [d][K+1], one knot vector per input (read from global memory)
   int32_t d, m, K, L, jt_log2, blob_bytes;
   int32_t codes_off, params_off, param_row_bytes;
   int32_t sym, with_base, param_fp16, closed, zero_spline;
@@ -571,7 +572,7 @@ __global__ __launch_bounds__(kChainWaves * 64) void lutkan_chain_kernel(const Ch
     unsigned outside = 0;
     for (int i = rtid; i < Y.d; i += WPR * 64) {
       const float x = (l == 0) ? a.x[b * Y.d + i] : s_act[i];
-      const Located o = locate_one<false>(Y, T, x);
+      const Located o = Y.input_knots ? locate_one<true>(Y, Y.input_knots + (int64_t)i * (Y.K + 1), x) : locate_one<false>(Y, T, x);
       u32x4 rec = {masked_index, 0u, 0u, 0u};
       const bool masked = Y.zero_spline && !o.inside && !o.is_nan;
       if (!masked) {
@@ -756,10 +757,10 @@ int chain_impl(const lutkan_dev_layer *layers, int32_t n_layers, const float *x,
     if (l + 1 < n_layers && L->m != layers[l + 1].d) return fail(LUTKAN_ESHAPE, "%s: layer %d has m=%d but layer %d has d=%d", who, l, L->m, l + 1, layers[l + 1].d);
     if (L->n_tiles != 1 || L->jt > kChainMaxColumns) return fail(LUTKAN_EUNSUPPORTED, "%s: layer %d has %d outputs in %d column tiles, the fused chain takes one tile of at most %d columns", who, l, L->m, L->n_tiles, kChainMaxColumns);
     if (L->d > kChainMaxInputs) return fail(LUTKAN_EUNSUPPORTED, "%s: layer %d has %d inputs, the fused chain takes at most %d", who, l, L->d, kChainMaxInputs);
-    if (L->knots_per_input) return fail(LUTKAN_EUNSUPPORTED, "%s: layer %d has one knot vector per input; use lutkan_model_forward", who, l);
     const lutkan::BlobLayout lay = lutkan::blob_layout(L->K, L->L, L->jt, L->scheme, L->value_repr, L->param_dtype);
     ChainLayer &c = ca.layer[l];
     c.table = static_cast<const unsigned char *>(L->table);
+    c.input_knots = L->knots_per_input ? L->input_knots : nullptr;
     c.d = L->d; c.m = L->m; c.K = L->K; c.L = L->L; c.blob_bytes = L->blob_bytes;
     c.jt_log2 = 0;
     while ((1 << c.jt_log2) < L->jt) ++c.jt_log2;
@@ -799,8 +800,7 @@ int chain_impl(const lutkan_dev_layer *layers, int32_t n_layers, const float *x,
 
 // The layers that AUTO runs as a launch of the chain kernel (see forward_impl).
 bool small_layer_runs_as_chain(const lutkan_dev_layer *l, int64_t B) {
-  return l->algo == LUTKAN_ALGO_AUTO && l->n_tiles == 1 && l->jt <= kChainMaxColumns && !l->knots_per_input &&
-         l->d * l->jt <= 4096 && B <= 8192;
+  return l->algo == LUTKAN_ALGO_AUTO && l->n_tiles == 1 && l->jt <= kChainMaxColumns && l->d * l->jt <= 4096 && B <= 8192;
 }
 
 int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y, lutkan_oob_stats *stats,

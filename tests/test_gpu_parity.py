@@ -818,6 +818,39 @@ def test_fused_chain(case):
     _fused_chain_check(specs, x, f"fused seed{seed}", half)
 
 
+@pytest.mark.parametrize("B", [3, 300, 3000])
+def test_fused_chain_with_one_knot_vector_per_input(B):
+    """A network whose layers each have per-input knot vectors (the grids of a model after per-feature grid updates):
+    the fused launch locates every input on its own vector, read from global memory."""
+    rng = np.random.Generator(np.random.PCG64(930))
+    widths, G, L = (20, 9, 5, 2), 6, 32
+    specs = []
+    for li, (d, m) in enumerate(zip(widths[:-1], widths[1:])):
+        s = per_input_layer(931 + li, d, m, G, L, ASYM_UINT8 if li % 2 else SYM_INT8, HALF_OPEN, ZERO_SPLINE, 4, with_base=(li == 1)).layers[0]
+        s.coef = (s.coef / np.sqrt(d)).astype(np.float32)
+        specs.append(s)
+    x = per_input_layer(931, widths[0], widths[1], G, L, SYM_INT8, HALF_OPEN, ZERO_SPLINE, B).x     # covers layer 0's own domains
+    compiled = [_compile_both(s) for s in specs]
+    layers = [_device_layer(art, s) for s, (art, _) in zip(specs, compiled)]
+    xg = torch.from_numpy(x).to(DEV)
+    hidden = torch.zeros(B * sum(widths[1:-1]), dtype=torch.float32, device=DEV)
+    stats = torch.zeros((len(specs), 2), dtype=torch.int64, device=DEV)
+    _say(f"case fused chain with per-input knots {widths} B={B}")
+    y = lk.lutkan_chain_forward(layers, xg, stats=stats, hidden=hidden)
+    y_model = lk.lutkan_model_forward(layers, xg)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y_model)                          # every layer is a small one: the same single launch
+    h, cur, off = hidden.cpu().numpy(), x, 0
+    for li, (s, (art, ora)) in enumerate(zip(specs, compiled)):
+        ref = oracle.lut_forward(ora, s.boundary, s.oob, cur, edge_scalars=s.edge_scales)
+        nxt = h[off:off + B * s.m].reshape(B, s.m) if li + 1 < len(specs) else y.cpu().numpy()
+        off += B * s.m
+        _assert_close(nxt, ref, f"per-input chain layer {li}")
+        st = stats[li].cpu().numpy()
+        assert (int(st[0]), int(st[1])) == (ref.oob_count, ref.oob_any_rows)
+        cur = nxt
+
+
 def test_fused_chain_refuses_what_it_cannot_hold():
     specs, x = _narrow_chain(920, (8, 128, 4), 4, 8, SYM_INT8, CLOSED, CLIP_X, 8)
     layers = [_device_layer(_compile_both_uncached(s, False)[0], s) for s in specs]
@@ -828,7 +861,3 @@ def test_fused_chain_refuses_what_it_cannot_hold():
     with pytest.raises(lk.LutKanError) as e:        # widths that do not chain
         lk.lutkan_chain_forward([layers[0], layers[0]], xg)
     assert str(e.value).startswith("[-2]")
-    w = per_input_layer(921, 4, 4, 5, 8, SYM_INT8, CLOSED, CLIP_X, 16)
-    with pytest.raises(lk.LutKanError) as e:        # one knot vector per input
-        lk.lutkan_chain_forward([_device_layer(_compile_both(w.layers[0])[0], w.layers[0])], torch.from_numpy(w.x).to(DEV))
-    assert str(e.value).startswith("[-5]")
