@@ -4,6 +4,8 @@ Bar (stated by the benchmark spec): segment index k, LUT index l0, the domain
 codes bit-exact; outputs within |dy| <= 1e-5 * sum_i |phi_ij(x_i)| + 1e-6 (fp32).  The interpolation weight w is
 produced by the same IEEE fp32 operations on both sides and is compared bit-exactly as well.
 """
+from types import SimpleNamespace
+
 import numpy as np
 import pytest
 
@@ -849,6 +851,39 @@ def test_fused_chain_with_one_knot_vector_per_input(B):
         st = stats[li].cpu().numpy()
         assert (int(st[0]), int(st[1])) == (ref.oob_count, ref.oob_any_rows)
         cur = nxt
+
+
+@pytest.mark.parametrize("boundary", [HALF_OPEN, CLOSED])
+def test_every_kernel_locates_bit_exactly_through_a_revealing_table(boundary):
+    """A one-edge layer whose table makes the output spell out the lookup: codes q[k][l] = l, alpha_k = 2^k, y_min = 0,
+    so y = 2^k * (l0 + w) = 2^k * z exactly (z - l0 = w and l0 + w = z are exact in fp32).  The oracle's (k, l0, w)
+    therefore fix the output of every edge kernel bit for bit -- also of the kernels that have no trace outputs
+    (the tiled kernel and the fused chain)."""
+    G, L, B = 7, 64, 4000
+    rng = np.random.Generator(np.random.PCG64(77 + boundary))
+    knots = np.unique(np.sort(rng.uniform(-2.0, 3.0, size=G + 1)).astype(np.float32))   # no knot at 0: a subnormal x
+    # next to it gives a subnormal z, which the tiled kernel's 2^-24-scaled sums flush (far below the tolerance)
+    K = knots.size - 1
+    q = np.tile(np.arange(L, dtype=np.uint8), (1, K, 1))
+    scale = (2.0 ** np.arange(K)).astype(np.float32).reshape(1, K)
+    art = lk.lutkan_artifact_from_arrays(1, 1, knots, q, scale, np.zeros((1, K), np.float32), boundary, CLIP_X)
+    x = rng.uniform(knots[0] - 0.5, knots[-1] + 0.5, size=(B, 1)).astype(np.float32)
+    special = np.concatenate([knots, np.nextafter(knots, np.float32(-np.inf)), np.nextafter(knots, np.float32(np.inf))])
+    x[:special.size, 0] = special
+    ora = SimpleNamespace(d=1, m=1, K=K, L=L, scheme=ASYM_UINT8, knots=knots, q=q, scale=scale, y_min=np.zeros((1, K), np.float32))
+    ref = oracle.lut_forward(ora, boundary, CLIP_X, x, trace=True)
+    z = ref.l0[:, 0].astype(np.float32) + ref.w[:, 0]
+    want = np.ldexp(z, ref.k[:, 0]).astype(np.float32)
+    xg = torch.from_numpy(x).to(DEV)
+    outs = {"tiled": lk.lutkan_forward(art.to_device(DEV, lk.ALGO_TILED), xg),
+            "gather": lk.lutkan_forward(art.to_device(DEV, lk.ALGO_GATHER), xg),
+            "chain, a work-group per row": lk.lutkan_chain_forward([art.to_device(DEV)], xg[:900].contiguous()),
+            "chain, a wave per row": lk.lutkan_chain_forward([art.to_device(DEV)], xg),
+            "auto": lk.lutkan_forward(art.to_device(DEV), xg)}
+    torch.cuda.synchronize()
+    for name, y in outs.items():
+        got = y.cpu().numpy()[:, 0]
+        np.testing.assert_array_equal(got.view(np.uint32), want[:got.size].view(np.uint32), err_msg=name)
 
 
 def test_fused_chain_refuses_what_it_cannot_hold():
