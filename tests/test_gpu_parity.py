@@ -131,6 +131,8 @@ TILED_CASES = [
     (209, 7, 70, 16, 128, SYM_INT8, CLOSED, CLIP_X, 1500),           # 2048 table rows: 16-column tiles of a wide layer
     (210, 5, 50, 32, 128, ASYM_UINT8, HALF_OPEN, ZERO_SPLINE, 2100), # 4096 table rows: 8-column tiles, ragged last tile
     (211, 3, 21, 64, 200, SYM_INT8, HALF_OPEN, CLIP_X, 300),         # 12800 table rows: 4-column tiles
+    (213, 5000, 4, 3, 8, ASYM_UINT8, HALF_OPEN, ZERO_SPLINE, 50),    # very many inputs: 79 locate tiles, many chunks
+    (214, 2, 5000, 3, 8, SYM_INT8, CLOSED, CLIP_X, 33),              # very many outputs: 40 column tiles
 ]
 
 
