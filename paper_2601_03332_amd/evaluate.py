@@ -14,6 +14,8 @@ With --cold-start it times the tabular chain 78 -> 16 -> 2 (L = 64 asymmetric ui
 latency metrics of Sec. 6.5 distinguish: steady state (tables resident on the GPU) and cold start (every iteration
 reads the NPZ artifacts, rebuilds the device tables and uploads them before the forward).
 With --variants it times every option combination (scheme x value_repr x parameter dtype) on the widest workload.
+With --batches it times LUT and B-spline layers of five shapes from 1 to 65536 rows (which kernel AUTO picks changes
+along the way: one-launch chain, gather with split inputs, tiled).
 With --latency it times narrow chains at batches 1 .. 65536 as per-layer launches and as the fused one-launch chain.
 Both layers and the error statistics (lutkan_error_stats, Sec. 5.6) run as the library's HIP kernels.  The layers
 are randomly initialised here, so the absolute numbers are not the paper's; the trends are (error halves per
@@ -33,6 +35,7 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="also run the 256->256 L x scheme sweep with timings")
     ap.add_argument("--cold-start", action="store_true", help="also time steady-state vs cold-start latency of the 78->16->2 chain")
     ap.add_argument("--variants", action="store_true", help="also time every option combination on the 1024 -> 1024 layer at batch 32768")
+    ap.add_argument("--batches", action="store_true", help="also time LUT and B-spline layers of several shapes from 1 to 65536 rows")
     ap.add_argument("--latency", action="store_true", help="also time narrow chains at small batches: per-layer launches vs the fused chain")
     args = ap.parse_args()
     import torch
@@ -189,6 +192,38 @@ def main():
             t = event_ms(lambda: lk.bspline_kan_forward(bl, x, y, workspace=wsb))
             print(f"  B-spline layer {'spline_component' if base else 'phi':>16}: {t:7.3f} ms {B * s.d * s.m / t / 1e9:6.2f}")
             del bl, wsb, art
+
+    if args.batches:
+        from lutkan_inputs import random_layer
+
+        def event_ms2(fn, n=20, warm=3):
+            for _ in range(warm):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(n):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / n
+
+        print()
+        print("Layer forward over batch sizes (AUTO picks the kernel): ms, 10^9 edge-evaluations/s, B-spline ms, B-spline / LUT")
+        for d, m, G, L, scheme in ((78, 16, 5, 64, ASYM_UINT8), (128, 8, 5, 32, ASYM_UINT8), (256, 256, 8, 64, SYM_INT8),
+                                   (1024, 64, 10, 64, SYM_INT8), (1024, 1024, 10, 64, SYM_INT8)):
+            sp = random_layer(3, d, m, G, L, scheme, CLOSED, CLIP_X, 4).layers[0]
+            art = lk.lutkan_compile(d, m, G, 3, sp.ext_knots, sp.coef, L, scheme, CLOSED, CLIP_X)
+            layer, bl = art.to_device(dev), art.bspline_to_device(dev)
+            print(f"--- {d} -> {m}, G = {G}, L = {L}, {'int8' if scheme == SYM_INT8 else 'uint8'}, {art.info.jt}-column tiles, table {art.info.table_bytes / 2**20:.1f} MiB")
+            for B in (1, 4, 16, 64, 256, 1024, 4096, 16384, 65536):
+                x = torch.rand((B, d), device=dev) * 2.2 - 1.1
+                y = torch.empty((B, m), dtype=torch.float32, device=dev)
+                ws = torch.empty(lk.lutkan_forward_workspace_bytes(layer, B), dtype=torch.uint8, device=dev)
+                t = event_ms2(lambda: lk.lutkan_forward(layer, x, y, workspace=ws))
+                wsb = torch.empty(lk.bspline_forward_workspace_bytes(bl, B), dtype=torch.uint8, device=dev)
+                tb = event_ms2(lambda: lk.bspline_kan_forward(bl, x, y, workspace=wsb))
+                print(f"  B = {B:>6}: {t:8.4f} ms {B * d * m / t / 1e6:9.1f} | {tb:8.4f} ms  {tb / t:5.2f}")
+                del x, y, ws, wsb
 
     if args.latency:
         import time
