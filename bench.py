@@ -231,6 +231,7 @@ def main():
             return work / best
 
         fma_flops = probe(lk.PROBE_VALU_FMA, 2048)
+        mix_rate = probe(lk.PROBE_VALU_MIX, 2048)                # lane-instructions/s of the kernel's own instruction mix
         lds_bps = probe(lk.PROBE_LDS_READ, 512)
         l2_bps = probe(lk.PROBE_L2_READ, 4)
         hbm_bps = probe(lk.PROBE_HBM_READ, 2)
@@ -240,11 +241,14 @@ def main():
         lds_bytes = 8.0 * edges                                  # 32 B per lane and row step: record 8, codes 8, scales 16
         l2_bytes = -(-B // 1024) * art.info.table_bytes + art.info.n_tiles * rec_bytes   # slices and records staged into LDS
         hbm_bytes = MEASURED_TRAFFIC_BYTES.get(B) or (art.info.table_bytes + rec_bytes + 4 * B * m)
-        terms = {"valu": valu_ops / (fma_flops / 2.0), "lds": (lds_bytes + l2_bytes) / lds_bps,
+        # valu: every vector instruction at the FMA issue rate; valu_mix: at the measured rate of the kernel's mix
+        # (permutes, packed-fp16 adds and mixed FMAs issue more slowly than plain FMAs on this chip)
+        terms = {"valu": valu_ops / (fma_flops / 2.0), "valu_mix": valu_ops / mix_rate, "lds": (lds_bytes + l2_bytes) / lds_bps,
                  "l2": l2_bytes / l2_bps, "hbm": hbm_bytes / hbm_bps}
         binding = max(terms, key=terms.get)
         roofline.update({
-            "measured_peaks": {"fp32_fma_TFLOPs": round(fma_flops / 1e12, 2), "lds_read_TBs": round(lds_bps / 1e12, 2),
+            "measured_peaks": {"fp32_fma_TFLOPs": round(fma_flops / 1e12, 2),
+                               "kernel_mix_Tlane_instr_s": round(mix_rate / 1e12, 3), "lds_read_TBs": round(lds_bps / 1e12, 2),
                                "l2_read_TBs": round(l2_bps / 1e12, 2), "hbm_read_TBs": round(hbm_bps / 1e12, 2)},
             "terms_ms": {k: round(v * 1e3, 4) for k, v in terms.items()},
             "binding_term": binding,

@@ -297,12 +297,16 @@ int lutkan_error_stats(const float *y, const float *y_ref, int64_t B, int32_t m,
  *                 LUTKAN_PROBE_LDS_READ  conflict-free 16-byte LDS reads                        work = bytes
  *                 LUTKAN_PROBE_L2_READ   every work-group re-reads the same 2 MiB               work = bytes
  *                 LUTKAN_PROBE_HBM_READ  the whole buffer once per pass (buffer >= 1 GiB)       work = bytes
+ *                 LUTKAN_PROBE_VALU_MIX  the instruction mix of the tiled LUT kernel (per row step 2 16-bit
+ *                                        multiply-adds, 4 byte permutes, 4 packed-fp16 adds, 4 mixed-precision FMAs,
+ *                                        4 fp32 FMAs), one 16-wave work-group per compute unit  work = lane-instructions
  *   buffer        device, 16-byte aligned; the first 16 bytes are a sink, the rest is read (contents irrelevant, but
  *                 finite floats for the LDS probe); needs 16 B / 16 KiB+16 / 2 MiB+16 / >= 1 GiB by kind
  *   iters         repetitions inside the kernel, 1 .. 2^20
  *   work_out      host: the flop or bytes one launch performs
  * Errors: EINVAL (null, misaligned, unknown kind, iters), ESHAPE (buffer too small), EHIP. */
-typedef enum { LUTKAN_PROBE_VALU_FMA = 0, LUTKAN_PROBE_LDS_READ = 1, LUTKAN_PROBE_L2_READ = 2, LUTKAN_PROBE_HBM_READ = 3 } lutkan_probe_kind;
+typedef enum { LUTKAN_PROBE_VALU_FMA = 0, LUTKAN_PROBE_LDS_READ = 1, LUTKAN_PROBE_L2_READ = 2, LUTKAN_PROBE_HBM_READ = 3,
+               LUTKAN_PROBE_VALU_MIX = 4 } lutkan_probe_kind;
 int lutkan_probe_launch(int32_t kind, void *buffer, size_t buffer_bytes, int32_t iters, double *work_out, void *hip_stream);
 
 #ifdef __cplusplus

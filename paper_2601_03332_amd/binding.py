@@ -16,7 +16,7 @@ CLIP_X, ZERO_SPLINE = 0, 1
 ALGO_AUTO, ALGO_GATHER, ALGO_TILED = 0, 1, 2
 PARAM_FP32, PARAM_FP16 = 0, 1
 SPAN_DOMAIN, SPAN_EXTENDED = 0, 1
-PROBE_VALU_FMA, PROBE_LDS_READ, PROBE_L2_READ, PROBE_HBM_READ = 0, 1, 2, 3
+PROBE_VALU_FMA, PROBE_LDS_READ, PROBE_L2_READ, PROBE_HBM_READ, PROBE_VALU_MIX = 0, 1, 2, 3, 4
 REPR_PHI, REPR_SPLINE_COMPONENT = 0, 1
 MAX_K = 64
 

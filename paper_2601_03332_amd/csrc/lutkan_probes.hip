@@ -1,5 +1,6 @@
-// Measurement aids of liblutkan: four kernels of known work, one per resource the LUT layer forward can be bound
-// by (vector-ALU FMA issue, LDS read bandwidth, L2 read bandwidth, HBM read bandwidth).  A caller times a launch
+// Measurement aids of liblutkan: kernels of known work, one per resource the LUT layer forward can be bound by
+// (vector-ALU FMA issue, the issue rate of the tiled kernel's own instruction mix, LDS read bandwidth, L2 read
+// bandwidth, HBM read bandwidth).  A caller times a launch
 // and divides the reported work by the duration to get the rate this machine actually sustains, which is what
 // the roofline terms of the layer kernels are compared with.  They are not part of the method.
 #include <hip/hip_runtime.h>
@@ -32,6 +33,50 @@ __global__ __launch_bounds__(kProbeThreads) void probe_valu_fma_kernel(float *si
 #pragma unroll
   for (int c = 0; c < kFmaChains; ++c) s += x[c];
   if (s == 123456.789f) sink[0] = s;     // keeps the chains alive; practically never taken
+}
+
+// Issue rate of the instruction mix of the tiled LUT kernel (int8 codes, value_repr = phi): per row step a lane
+// issues 2 16-bit multiply-adds (addresses), 4 byte permutes, 4 packed-fp16 adds, 4 mixed-precision FMAs and 4 fp32
+// FMAs, with the data dependences of the kernel (permutes -> packed adds -> mixed FMAs -> FMAs, four columns side by
+// side).  On gfx950 these kinds do not all issue in four cycles per wave, so the rate of the mix, not the FMA rate,
+// is the vector-ALU bound of that kernel.  The probe runs one 16-wave work-group per compute unit, like the kernel
+// (the dynamic LDS it asks for, and never touches, keeps a second work-group off the compute unit).
+constexpr int kMixLdsBytes = 96 * 1024;
+constexpr int kMixInstructionsPerStep = 18;
+
+__global__ __launch_bounds__(kProbeThreads) void probe_valu_mix_kernel(float *sink, int iters, unsigned seed, float w) {
+  unsigned rec = seed + threadIdx.x, c0 = seed * 3u + threadIdx.x, c1 = seed * 7u + threadIdx.x;
+  unsigned base0 = threadIdx.x * 4u, base1 = threadIdx.x * 16u;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  const float alpha[4] = {w, w * 0.5f, w * 0.25f, w * 0.125f};
+  const unsigned bias = 0x00800080u, rows = 64u;
+  for (int it = 0; it < iters; ++it) {
+    unsigned a0, a1, q0lo, q0hi, q1lo, q1hi, dlo, dhi;
+    float t0, t1, t2, t3;
+    asm volatile("v_mad_u32_u16 %0, %1, %2, %3 op_sel:[0,0,0,0]" : "=v"(a0) : "v"(rec), "v"(rows), "v"(base0));
+    asm volatile("v_mad_u32_u16 %0, %1, %2, %3 op_sel:[1,0,0,0]" : "=v"(a1) : "v"(rec), "v"(rows), "v"(base1));
+    asm volatile("v_perm_b32 %0, %1, %1, %2" : "=v"(q0lo) : "v"(c0), "v"(0x0c010c00u));
+    asm volatile("v_perm_b32 %0, %1, %1, %2" : "=v"(q0hi) : "v"(c0), "v"(0x0c030c02u));
+    asm volatile("v_perm_b32 %0, %1, %1, %2" : "=v"(q1lo) : "v"(c1), "v"(0x0c010c00u));
+    asm volatile("v_perm_b32 %0, %1, %1, %2" : "=v"(q1hi) : "v"(c1), "v"(0x0c030c02u));
+    asm volatile("v_pk_add_f16 %0, %1, %2 neg_lo:[0,1] neg_hi:[0,1]" : "=v"(dlo) : "v"(q1lo), "v"(q0lo));
+    asm volatile("v_pk_add_f16 %0, %1, %2 neg_lo:[0,1] neg_hi:[0,1]" : "=v"(dhi) : "v"(q1hi), "v"(q0hi));
+    asm volatile("v_pk_add_f16 %0, %0, %1 neg_lo:[0,1] neg_hi:[0,1]" : "+v"(q0lo) : "v"(bias));
+    asm volatile("v_pk_add_f16 %0, %0, %1 neg_lo:[0,1] neg_hi:[0,1]" : "+v"(q0hi) : "v"(bias));
+    asm volatile("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[0,0,0] op_sel_hi:[0,1,1]" : "=v"(t0) : "v"(w), "v"(dlo), "v"(q0lo));
+    asm volatile("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[0,1,1] op_sel_hi:[0,1,1]" : "=v"(t1) : "v"(w), "v"(dlo), "v"(q0lo));
+    asm volatile("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[0,0,0] op_sel_hi:[0,1,1]" : "=v"(t2) : "v"(w), "v"(dhi), "v"(q0hi));
+    asm volatile("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[0,1,1] op_sel_hi:[0,1,1]" : "=v"(t3) : "v"(w), "v"(dhi), "v"(q0hi));
+    asm volatile("v_fmac_f32 %0, %1, %2" : "+v"(acc[0]) : "v"(alpha[0]), "v"(t0));
+    asm volatile("v_fmac_f32 %0, %1, %2" : "+v"(acc[1]) : "v"(alpha[1]), "v"(t1));
+    asm volatile("v_fmac_f32 %0, %1, %2" : "+v"(acc[2]) : "v"(alpha[2]), "v"(t2));
+    asm volatile("v_fmac_f32 %0, %1, %2" : "+v"(acc[3]) : "v"(alpha[3]), "v"(t3));
+    // the next step's "loads" are this step's addresses: everything above stays live and changes every step
+    c0 = a0;
+    c1 = a1;
+    rec = a0 ^ a1;
+  }
+  if (acc[0] + acc[1] + acc[2] + acc[3] == 123456.789f) sink[0] = acc[0];
 }
 
 // LDS read bandwidth: a work-group fills 64 KiB of LDS once, then every lane reads 16 bytes per step, lanes on
@@ -91,6 +136,19 @@ extern "C" int lutkan_probe_launch(int32_t kind, void *buffer, size_t buffer_byt
       if (buffer_bytes < 16) return fail(LUTKAN_ESHAPE, "%s: buffer too small", who);
       hipLaunchKernelGGL(probe_valu_fma_kernel, dim3(groups), dim3(kProbeThreads), 0, s, fbuf, iters, 0.999f, 0.001f);
       *work_out = 2.0 * kFmaChains * (double)iters * kProbeThreads * groups;            // flop
+      break;
+    }
+    case LUTKAN_PROBE_VALU_MIX: {
+      if (buffer_bytes < 16) return fail(LUTKAN_ESHAPE, "%s: buffer too small", who);
+      static bool raised_mix = false;
+      if (!raised_mix) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(probe_valu_mix_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kMixLdsBytes);
+        if (e != hipSuccess) return fail(LUTKAN_EHIP, "hipFuncSetAttribute(LDS): %s", hipGetErrorString(e));
+        raised_mix = true;
+      }
+      hipLaunchKernelGGL(probe_valu_mix_kernel, dim3(groups), dim3(kProbeThreads), kMixLdsBytes, s, fbuf, iters, 12345u, 0.37f);
+      *work_out = (double)kMixInstructionsPerStep * (double)iters * kProbeThreads * groups;   // lane-instructions
       break;
     }
     case LUTKAN_PROBE_LDS_READ: {
