@@ -898,3 +898,29 @@ def test_fused_chain_refuses_what_it_cannot_hold():
     with pytest.raises(lk.LutKanError) as e:        # widths that do not chain
         lk.lutkan_chain_forward([layers[0], layers[0]], xg)
     assert str(e.value).startswith("[-2]")
+
+
+def test_measurement_probes_report_their_work_and_plausible_rates():
+    """The peak-rate probes behind the roofline terms: each kind launches, reports the work of one launch, and the
+    rate it implies lies in the range the hardware can have (a wrong work count or a kernel the optimiser emptied
+    would not)."""
+    buf = torch.zeros((1 << 30) // 4 + 4, dtype=torch.float32, device=DEV)
+    ranges = {lk.PROBE_VALU_FMA: (2048, 3e13, 1.7e14),      # flop/s: between 30 and 170 TFLOP/s
+              lk.PROBE_VALU_MIX: (2048, 1.5e13, 8e13),      # lane-instructions/s
+              lk.PROBE_LDS_READ: (512, 4e13, 3e14),         # bytes/s
+              lk.PROBE_L2_READ: (4, 5e12, 8e13),
+              lk.PROBE_HBM_READ: (2, 2e12, 8.5e12)}
+    for kind, (iters, lo, hi) in ranges.items():
+        lk.lutkan_probe_launch(kind, buf, iters)             # warm-up
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        work = lk.lutkan_probe_launch(kind, buf, iters)
+        e1.record()
+        torch.cuda.synchronize()
+        rate = work / (e0.elapsed_time(e1) * 1e-3)
+        _say(f"probe kind {kind}: {rate:.3g} per second")
+        assert lo < rate < hi, (kind, rate)
+    with pytest.raises(lk.LutKanError):
+        lk.lutkan_probe_launch(99, buf, 1)
+    with pytest.raises(lk.LutKanError):
+        lk.lutkan_probe_launch(lk.PROBE_HBM_READ, buf[:1024], 1)
