@@ -121,7 +121,7 @@ def main():
     ap.add_argument("--batch", type=int, default=32768)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bspline", action="store_true")
-    ap.add_argument("--no-probes", action="store_true", help="skip the four peak-rate probes (FMA, LDS, L2, HBM)")
+    ap.add_argument("--no-probes", action="store_true", help="skip the peak-rate probes (FMA, instruction mix, LDS, L2, HBM)")
     ap.add_argument("--all-configs", action="store_true",
                     help="also time every workload of the scope table (LUT chain, B-spline chain, bounded oracle sample); "
                          "the results go to extra.configs and, as a table, to stderr")
