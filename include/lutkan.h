@@ -58,6 +58,10 @@ typedef enum { LUTKAN_SPAN_DOMAIN = 0, LUTKAN_SPAN_EXTENDED = 1 } lutkan_knot_sp
 
 const char *lutkan_last_error(void);
 const char *lutkan_version(void);
+/* What the last forward call of this thread launched, for logs and tests: one clause per kernel launch, e.g.
+ * "locate; tiled np=16 split=2; sum; " or "chain layers=2 wpr=4; " or "locate; gather split=16; sum; " (model_forward:
+ * the clauses of all its layers).  Thread-local, overwritten by the next forward call, never null. */
+const char *lutkan_last_plan(void);
 
 /* ------------------------------------------------------------------------------------------------
  * Host side: compile a B-spline KAN layer into a LUT artifact (Sec. 4.2-4.6, Sec. 6.3).

@@ -65,7 +65,7 @@ class _SplineDevLayer(C.Structure):
 
 
 EXPORTS = [
-    "lutkan_last_error", "lutkan_version", "lutkan_compile", "lutkan_artifact_free", "lutkan_artifact_info",
+    "lutkan_last_error", "lutkan_last_plan", "lutkan_version", "lutkan_compile", "lutkan_artifact_free", "lutkan_artifact_info",
     "lutkan_artifact_q", "lutkan_artifact_scale", "lutkan_artifact_ymin", "lutkan_artifact_knots",
     "lutkan_artifact_ext_knots", "lutkan_artifact_table", "lutkan_artifact_coef_table",
     "lutkan_artifact_edge_base_scale", "lutkan_artifact_edge_spline_scale", "lutkan_artifact_edge_out_scale",
@@ -93,6 +93,7 @@ def load_library():
     lib = C.CDLL(_build.LIB)
     vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
     lib.lutkan_last_error.restype = C.c_char_p
+    lib.lutkan_last_plan.restype = C.c_char_p
     lib.lutkan_version.restype = C.c_char_p
     lib.lutkan_compile.argtypes = [C.POINTER(_LayerDesc), i32, C.POINTER(vp)]
     lib.lutkan_artifact_from_arrays.argtypes = [C.POINTER(_ArtifactArrays), C.POINTER(vp)]
@@ -131,6 +132,11 @@ def load_library():
 
 def lutkan_last_error() -> str:
     return load_library().lutkan_last_error().decode()
+
+
+def lutkan_last_plan() -> str:
+    """Which kernels the last forward call of this thread launched (one clause per launch)."""
+    return load_library().lutkan_last_plan().decode()
 
 
 def lutkan_version() -> str:

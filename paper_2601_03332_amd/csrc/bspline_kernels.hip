@@ -409,6 +409,7 @@ int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y
       else hipLaunchKernelGGL((bspline_locate_kernel<16, false>), lgrid, dim3(256), 0, s, la);
     }
     if (int rc = check_launch("bspline_locate_kernel")) return rc;
+    lutkan::plan_note("bspline_locate; ");
   }
   if (!(phases & kEdges)) return LUTKAN_OK;
 
@@ -430,9 +431,12 @@ int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y
     ea.chunk = tp.chunk;
     if (tp.n_split > 1) { ea.y = partials; ea.split_stride = B * l->m; }
     const int rc = launch_spline_tiled_jt(ea, tp.np, s);
-    if (rc || tp.n_split == 1) return rc;
+    if (rc) return rc;
+    lutkan::plan_note("bspline_tiled np=%d split=%d; ", tp.np, tp.n_split);
+    if (tp.n_split == 1) return rc;
     const int64_t n = B * l->m;
     hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, s, partials, y, n, tp.n_split);
+    lutkan::plan_note("sum; ");
     return check_launch("sum_partials_kernel");
   }
   const int lg = gather_jx_log2(l->m);
@@ -443,9 +447,11 @@ int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y
   const dim3 grid((unsigned)((B + (256 >> lg) - 1) / (256 >> lg)), (unsigned)((l->m + (1 << lg) - 1) >> lg), (unsigned)gp.n_split);
   hipLaunchKernelGGL(bspline_gather_kernel, grid, dim3(256), 0, s, ea, lg);
   if (int rc = check_launch("bspline_gather_kernel")) return rc;
+  lutkan::plan_note("bspline_gather split=%d; ", gp.n_split);
   if (gp.n_split == 1) return LUTKAN_OK;
   const int64_t n = B * l->m;
   hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, s, partials, y, n, gp.n_split);
+  lutkan::plan_note("sum; ");
   return check_launch("sum_partials_kernel");
 }
 
@@ -458,16 +464,19 @@ extern "C" size_t bspline_forward_workspace_bytes(const bspline_dev_layer *layer
 
 extern "C" int bspline_kan_forward(const bspline_dev_layer *l, const float *x, int64_t B, float *y,
                                    void *workspace, size_t workspace_bytes, void *hip_stream) {
+  lutkan::plan_clear();
   return bspline_impl(l, x, B, y, workspace, workspace_bytes, hip_stream, "bspline_kan_forward", kLocate | kEdges);
 }
 
 extern "C" int bspline_forward_locate(const bspline_dev_layer *l, const float *x, int64_t B, void *workspace,
                                       size_t workspace_bytes, void *hip_stream) {
+  lutkan::plan_clear();
   return bspline_impl(l, x, B, nullptr, workspace, workspace_bytes, hip_stream, "bspline_forward_locate", kLocate);
 }
 
 extern "C" int bspline_forward_edges(const bspline_dev_layer *l, int64_t B, float *y, void *workspace,
                                      size_t workspace_bytes, void *hip_stream) {
+  lutkan::plan_clear();
   return bspline_impl(l, nullptr, B, y, workspace, workspace_bytes, hip_stream, "bspline_forward_edges", kEdges);
 }
 

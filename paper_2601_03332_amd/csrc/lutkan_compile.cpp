@@ -21,6 +21,22 @@
 namespace lutkan {
 
 static thread_local char g_err[512] = "";
+static thread_local char g_plan[1024] = "";
+static thread_local size_t g_plan_len = 0;
+
+void plan_clear() {
+  g_plan[0] = 0;
+  g_plan_len = 0;
+}
+
+void plan_note(const char *fmt, ...) {
+  if (g_plan_len + 1 >= sizeof(g_plan)) return;
+  va_list ap;
+  va_start(ap, fmt);
+  const int n = vsnprintf(g_plan + g_plan_len, sizeof(g_plan) - g_plan_len, fmt, ap);
+  va_end(ap);
+  if (n > 0) g_plan_len = std::min(sizeof(g_plan) - 1, g_plan_len + (size_t)n);
+}
 
 int fail(int code, const char *fmt, ...) {
   va_list ap;
@@ -199,6 +215,7 @@ void fill_info(lutkan_artifact *a, int d, int m, int K, int L, int G, int scheme
 using namespace lutkan;
 
 extern "C" const char *lutkan_last_error(void) { return g_err; }
+extern "C" const char *lutkan_last_plan(void) { return g_plan; }
 extern "C" const char *lutkan_version(void) { return "lutkan-gfx950 0.1"; }
 
 extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, lutkan_artifact **out) {

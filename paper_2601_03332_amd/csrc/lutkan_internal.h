@@ -13,6 +13,9 @@ namespace lutkan {
 
 // Thread-local error text behind lutkan_last_error().
 int fail(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+// Thread-local text behind lutkan_last_plan(): which kernels the last forward call launched, one clause per launch.
+void plan_clear();
+void plan_note(const char *fmt, ...) __attribute__((format(printf, 1, 2)));
 
 // Byte offsets inside one (tile, input) slice of the LUT device table:
 //   [base jt f32 (spline_component only)][params (K+1) rows of jt entries][codes (K*L+2) rows of jt bytes][pad to 16 B]

@@ -795,6 +795,7 @@ int chain_impl(const lutkan_dev_layer *layers, int32_t n_layers, const float *x,
   } else {
     hipLaunchKernelGGL(lutkan_chain_kernel<kChainWaves>, dim3((unsigned)groups), dim3(kChainWaves * 64), lds, s, ca);
   }
+  lutkan::plan_note("chain layers=%d wpr=%d; ", n_layers, wpr);
   return check_launch("lutkan_chain_kernel");
 }
 
@@ -850,11 +851,13 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
       else launch_locate<false, false>(cols, lgrid, s, la);
     }
     if (int rc = check_launch("lutkan_locate_kernel")) return rc;
+    lutkan::plan_note("locate; ");
     if (stats) {
       const int64_t rows_per_group = 4 * kOobRowsPerWave;
       hipLaunchKernelGGL(oob_count_kernel, dim3((unsigned)((B + rows_per_group - 1) / rows_per_group)), dim3(256), 0, s, x, B, l->d,
                          l->knots[0], l->knots[l->K], la.closed, la.input_knots, l->K, reinterpret_cast<unsigned long long *>(stats));
       if (int rc = check_launch("oob_count_kernel")) return rc;
+      lutkan::plan_note("oob; ");
     }
   }
   if (!(phases & kEdges)) return LUTKAN_OK;
@@ -880,9 +883,12 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
     ea.chunk = tp.chunk;
     if (tp.n_split > 1) { ea.y = partials; ea.split_stride = B * l->m; }
     const int rc = (l->scheme == LUTKAN_SYM_INT8) ? launch_tiled_jt<LUTKAN_SYM_INT8>(ea, tp.np, s) : launch_tiled_jt<LUTKAN_ASYM_UINT8>(ea, tp.np, s);
-    if (rc || tp.n_split == 1) return rc;
+    if (rc) return rc;
+    lutkan::plan_note("tiled np=%d split=%d; ", tp.np, tp.n_split);
+    if (tp.n_split == 1) return rc;
     const int64_t n = B * l->m;
     hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, s, partials, y, n, tp.n_split);
+    lutkan::plan_note("sum; ");
     return check_launch("sum_partials_kernel");
   }
   const int lg = gather_jx_log2(l->m);
@@ -900,9 +906,11 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
     else hipLaunchKernelGGL((lutkan_gather_kernel<LUTKAN_ASYM_UINT8, false>), grid, dim3(256), 0, s, ea, lg);
   }
   if (int rc = check_launch("lutkan_gather_kernel")) return rc;
+  lutkan::plan_note("gather split=%d; ", gp.n_split);
   if (gp.n_split == 1) return LUTKAN_OK;
   const int64_t n = B * l->m;
   hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, s, partials, y, n, gp.n_split);
+  lutkan::plan_note("sum; ");
   return check_launch("sum_partials_kernel");
 }
 
@@ -915,18 +923,21 @@ extern "C" size_t lutkan_forward_workspace_bytes(const lutkan_dev_layer *layer, 
 
 extern "C" int lutkan_forward(const lutkan_dev_layer *layer, const float *x, int64_t B, float *y,
                               lutkan_oob_stats *stats, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  lutkan::plan_clear();
   return forward_impl(layer, x, B, y, stats, nullptr, nullptr, nullptr, nullptr, nullptr, false, workspace,
                       workspace_bytes, hip_stream, "lutkan_forward");
 }
 
 extern "C" int lutkan_forward_locate(const lutkan_dev_layer *layer, const float *x, int64_t B, lutkan_oob_stats *stats,
                                      void *workspace, size_t workspace_bytes, void *hip_stream) {
+  lutkan::plan_clear();
   return forward_impl(layer, x, B, nullptr, stats, nullptr, nullptr, nullptr, nullptr, nullptr, false, workspace,
                       workspace_bytes, hip_stream, "lutkan_forward_locate", kLocate);
 }
 
 extern "C" int lutkan_forward_edges(const lutkan_dev_layer *layer, int64_t B, float *y, void *workspace,
                                     size_t workspace_bytes, void *hip_stream) {
+  lutkan::plan_clear();
   return forward_impl(layer, nullptr, B, y, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, false, workspace,
                       workspace_bytes, hip_stream, "lutkan_forward_edges", kEdges);
 }
@@ -934,6 +945,7 @@ extern "C" int lutkan_forward_edges(const lutkan_dev_layer *layer, int64_t B, fl
 extern "C" int lutkan_forward_trace(const lutkan_dev_layer *layer, const float *x, int64_t B, float *y,
                                     int32_t *k_out, int32_t *l0_out, uint8_t *in_out, float *w_out, int16_t *q01_out,
                                     void *workspace, size_t workspace_bytes, void *hip_stream) {
+  lutkan::plan_clear();
   return forward_impl(layer, x, B, y, nullptr, k_out, l0_out, in_out, w_out, q01_out, true, workspace,
                       workspace_bytes, hip_stream, "lutkan_forward_trace");
 }
@@ -950,12 +962,14 @@ extern "C" size_t lutkan_model_workspace_bytes(const lutkan_dev_layer *layers, i
 
 extern "C" int lutkan_chain_forward(const lutkan_dev_layer *layers, int32_t n_layers, const float *x, int64_t B, float *y,
                                     float *hidden, lutkan_oob_stats *stats, void *hip_stream) {
+  lutkan::plan_clear();
   return chain_impl(layers, n_layers, x, B, y, hidden, stats, hip_stream, "lutkan_chain_forward");
 }
 
 extern "C" int lutkan_model_forward(const lutkan_dev_layer *layers, int32_t n_layers, const float *x, int64_t B, float *y,
                                     lutkan_oob_stats *stats, void *workspace, size_t workspace_bytes, void *hip_stream) {
   const char *who = "lutkan_model_forward";
+  lutkan::plan_clear();
   if (!layers || n_layers < 1 || n_layers > LUTKAN_MAX_LAYERS) return fail(LUTKAN_EINVAL, "%s: need 1..%d layers", who, LUTKAN_MAX_LAYERS);
   for (int l = 0; l + 1 < n_layers; ++l)
     if (layers[l].m != layers[l + 1].d) return fail(LUTKAN_ESHAPE, "%s: layer %d has m=%d but layer %d has d=%d", who, l, layers[l].m, l + 1, layers[l + 1].d);
@@ -980,7 +994,8 @@ extern "C" int lutkan_model_forward(const lutkan_dev_layer *layers, int32_t n_la
   const float *in = x;
   for (int l = 0; l < n_layers; ++l) {
     float *out = (l + 1 == n_layers) ? y : ping[l & 1];
-    int rc = lutkan_forward(&layers[l], in, B, out, stats ? stats + l : nullptr, rec, scratch, hip_stream);
+    int rc = forward_impl(&layers[l], in, B, out, stats ? stats + l : nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, false, rec,
+                          scratch, hip_stream, who);
     if (rc) return rc;
     in = out;
   }

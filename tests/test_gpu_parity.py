@@ -900,6 +900,46 @@ def test_fused_chain_refuses_what_it_cannot_hold():
     assert str(e.value).startswith("[-2]")
 
 
+def test_last_plan_reports_what_auto_dispatch_launched():
+    """lutkan_last_plan names the kernels of the last forward call: the dispatch rules of algo = AUTO, observed."""
+    w = cfg4(B=4096)
+    s = w.layers[0]
+    art, _ = _compile_both(s)
+    layer = _device_layer(art, s)
+    xg = torch.from_numpy(w.x).to(DEV)
+    _say("case last plan: cfg4 at 1, 64 and 4096 rows")
+    lk.lutkan_forward(layer, xg[:1])
+    assert lk.lutkan_last_plan() == "locate; gather split=64; sum; "          # a few rows: only the touched table rows
+    lk.lutkan_forward(layer, xg[:64])
+    assert lk.lutkan_last_plan().startswith("locate; gather split=")
+    lk.lutkan_forward(layer, xg)
+    assert lk.lutkan_last_plan() == "locate; tiled np=16 split=4; sum; "      # 4 row tiles x 16 column tiles x 4 chunks = 256 work-groups
+    stats = torch.zeros(2, dtype=torch.int64, device=DEV)
+    lk.lutkan_forward(layer, xg, stats=stats)
+    assert lk.lutkan_last_plan() == "locate; oob; tiled np=16 split=4; sum; "
+    lk.bspline_kan_forward(art.bspline_to_device(DEV), xg)
+    assert lk.lutkan_last_plan().startswith("bspline_locate; bspline_tiled np=")
+    _say("case last plan: cfg2 at 300, 5000 and 20000 rows")
+    w2 = cfg2(B=20000)
+    layers = []
+    keep = []
+    for s2 in w2.layers:
+        a2, _ = _compile_both(s2)
+        keep.append(a2)
+        layers.append(_device_layer(a2, s2))
+    x2 = torch.from_numpy(w2.x).to(DEV)
+    lk.lutkan_model_forward(layers, x2[:300])
+    assert lk.lutkan_last_plan() == "chain layers=2 wpr=4; "                   # every layer small: one launch, a work-group per row
+    lk.lutkan_model_forward(layers, x2[:5000])
+    assert lk.lutkan_last_plan() == "chain layers=2 wpr=1; "                   # beyond 1024 rows: a wave per row
+    lk.lutkan_forward(layers[0], x2[:300])
+    assert lk.lutkan_last_plan() == "chain layers=1 wpr=4; "                   # a single small layer runs as a one-layer chain
+    lk.lutkan_model_forward(layers, x2)
+    plan = lk.lutkan_last_plan()
+    assert plan.count("locate; tiled np=") == 2 and "chain" not in plan, plan  # beyond 8192 rows: locate + tiled kernel per layer
+    torch.cuda.synchronize()
+
+
 def test_measurement_probes_report_their_work_and_plausible_rates():
     """The peak-rate probes behind the roofline terms: each kind launches, reports the work of one launch, and the
     rate it implies lies in the range the hardware can have (a wrong work count or a kernel the optimiser emptied

@@ -161,6 +161,7 @@ def test_forward_argument_validation_happens_before_any_launch():
     lib.lutkan_dev_layer_init(art._h, C.byref(dl))
     assert lib.lutkan_forward(C.byref(dl), 16, 4, 32, None, 256, 1 << 20, None) == -1      # table is NULL
     assert "table" in lk.lutkan_last_error()
+    assert lk.lutkan_last_plan() == ""                                                       # nothing was launched
     dl.table = 4096
     assert lib.lutkan_forward(C.byref(dl), 16, 0, 32, None, None, 0, None) == 0            # B == 0: no-op
     assert lib.lutkan_forward(C.byref(dl), 16, -1, 32, None, 256, 1 << 20, None) == -1
