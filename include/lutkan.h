@@ -105,15 +105,17 @@ typedef struct lutkan_artifact lutkan_artifact;     /* opaque, host memory */
 
 typedef struct {
   int32_t d, m, K, L, G, degree, scheme, boundary, oob, value_repr, param_dtype, knot_span, knots_per_input;
-  int32_t jt;                /* column-tile width of the device tables: a power of two in 4 .. 128 */
+  int32_t jt;                /* column-tile width of the LUT device table: a power of two in 4 .. 64 */
   int32_t n_tiles;           /* ceil(m / jt) */
   int32_t blob_bytes;        /* bytes of one (tile, input) slice of the LUT device table */
+  int32_t coef_jt;           /* column-tile width of the B-spline device table: a power of two in 4 .. 128 (0 if none) */
+  int32_t coef_n_tiles;      /* ceil(m / coef_jt) */
   int32_t coef_blob_bytes;   /* bytes of one (tile, input) slice of the B-spline device table */
   float t0, tK, tK_star;     /* domain ends and the safe upper clip value of Eq. 13 (of input 0 with knots_per_input) */
   size_t q_canonical_bytes;  /* d*m*K*L */
   size_t params_canonical_bytes; /* d*m*K*4 (d*m*K*2 with fp16 parameters), for scale and for y_min each */
   size_t table_bytes;        /* whole LUT device table = n_tiles*d*blob_bytes */
-  size_t coef_table_bytes;   /* whole B-spline device table = n_tiles*d*coef_blob_bytes */
+  size_t coef_table_bytes;   /* whole B-spline device table = coef_n_tiles*d*coef_blob_bytes */
   size_t artifact_bytes;     /* Sec. 4.6 arrays: q + scale + y_min + knots (what Sec. 6.6 "LUT artifact bytes" counts;
                                 knots are 4*(K+1) bytes, times d with knots_per_input) */
 } lutkan_info;

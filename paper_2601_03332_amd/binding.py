@@ -44,7 +44,7 @@ class _ArtifactArrays(C.Structure):
 class _Info(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("d", "m", "K", "L", "G", "degree", "scheme", "boundary", "oob", "value_repr",
                                          "param_dtype", "knot_span", "knots_per_input", "jt", "n_tiles", "blob_bytes",
-                                         "coef_blob_bytes")] + \
+                                         "coef_jt", "coef_n_tiles", "coef_blob_bytes")] + \
                [("t0", C.c_float), ("tK", C.c_float), ("tK_star", C.c_float)] + \
                [(n, C.c_size_t) for n in ("q_canonical_bytes", "params_canonical_bytes", "table_bytes",
                                           "coef_table_bytes", "artifact_bytes")]

@@ -48,12 +48,17 @@ int fail(int code, const char *fmt, ...) {
 
 int choose_jt(int m, int K, int L, int scheme, int value_repr, int param_dtype) {
   int jt = 4;
-  while (jt < m && jt < 128) jt *= 2;
+  while (jt < m && jt < 64) jt *= 2;
   int fit = jt;
-  while (fit > 4 && blob_layout(K, L, fit, scheme, value_repr, param_dtype).bytes > kLdsSliceBudget) fit /= 2;
-  if (blob_layout(K, L, fit, scheme, value_repr, param_dtype).bytes <= kLdsSliceBudget) return fit;
+  while (fit > 4 && blob_layout(K, L, fit, scheme, value_repr, param_dtype).bytes > lds_slice_budget(value_repr)) fit /= 2;
+  if (blob_layout(K, L, fit, scheme, value_repr, param_dtype).bytes <= lds_slice_budget(value_repr)) return fit;
   return jt < 32 ? jt : 32;   // no width fits: the gather kernel, which is fastest on 32-column tiles
+}
 
+int choose_coef_jt(int m) {
+  int jt = 4;
+  while (jt < m && jt < 128) jt *= 2;
+  return jt;
 }
 
 namespace {
@@ -191,14 +196,15 @@ struct SlicePacker {
 
 // Fills the size and contract fields of an artifact's info once its arrays and tables are in place.
 void fill_info(lutkan_artifact *a, int d, int m, int K, int L, int G, int scheme, int boundary, int oob, int repr,
-               int param_dtype, int knots_per_input, int jt, int n_tiles, const BlobLayout &lay, int coef_blob) {
+               int param_dtype, int knots_per_input, int jt, int n_tiles, const BlobLayout &lay, int coef_jt, int coef_blob) {
   const size_t E = (size_t)d * m;
   lutkan_info &I = a->info;
   std::memset(&I, 0, sizeof(I));
   I.d = d; I.m = m; I.K = K; I.L = L; I.G = G; I.degree = P;
   I.scheme = scheme; I.boundary = boundary; I.oob = oob; I.value_repr = repr; I.param_dtype = param_dtype;
   I.knots_per_input = knots_per_input;
-  I.jt = jt; I.n_tiles = n_tiles; I.blob_bytes = lay.bytes; I.coef_blob_bytes = coef_blob;
+  I.jt = jt; I.n_tiles = n_tiles; I.blob_bytes = lay.bytes;
+  I.coef_jt = coef_blob ? coef_jt : 0; I.coef_n_tiles = coef_blob ? (m + coef_jt - 1) / coef_jt : 0; I.coef_blob_bytes = coef_blob;
   I.t0 = a->knots[0]; I.tK = a->knots[K];
   I.tK_star = (boundary == LUTKAN_CLOSED) ? I.tK : std::nextafterf(I.tK, -INFINITY);  // Eq. 13
   I.q_canonical_bytes = E * K * L;
@@ -267,7 +273,9 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
   const int n_tiles = (m + jt - 1) / jt;
   const BlobLayout lay = blob_layout(K, L, jt, scheme, repr, desc->param_dtype);
   const int coef_rows = coef_slice_rows(R, repr);
-  const int coef_blob = coef_rows * jt * 4;
+  const int cjt = choose_coef_jt(m);
+  const int coef_tiles = (m + cjt - 1) / cjt;
+  const int coef_blob = coef_rows * cjt * 4;
   try {
     a->ext_knots.assign(desc->ext_knots, desc->ext_knots + (size_t)n_vectors * n_knots);
     a->knots.resize((size_t)n_vectors * (K + 1));
@@ -277,7 +285,7 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
     a->scale.resize(E * K);
     a->ymin.resize(E * K);
     a->table.assign((size_t)n_tiles * d * lay.bytes, 0);
-    a->coef_table.assign((size_t)n_tiles * d * coef_rows * jt, 0.0f);
+    a->coef_table.assign((size_t)coef_tiles * d * coef_rows * cjt, 0.0f);
     if (with_base) {
       a->edge_base.assign(desc->edge_base_scale, desc->edge_base_scale + E);
       a->edge_spline.assign(desc->edge_spline_scale, desc->edge_spline_scale + E);
@@ -325,7 +333,8 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
         const float *c = desc->coef + e * R;
         const int t = j / jt, jj = j % jt;
         uint8_t *slice = a->table.data() + ((size_t)t * d + i) * lay.bytes;
-        float *cslice = a->coef_table.data() + ((size_t)t * d + i) * coef_rows * jt;
+        const int cj = j % cjt;
+        float *cslice = a->coef_table.data() + ((size_t)(j / cjt) * d + i) * coef_rows * cjt;
         // spline_component (Eq. 2): the device tables carry s_out*s_base per edge as an extra row and fold
         // s_out*s_spline into the edge's dequantisation parameters / B-spline coefficients.
         float spline_gain = 1.0f;
@@ -333,10 +342,10 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
           const float base_gain = desc->edge_out_scale[e] * desc->edge_base_scale[e];
           spline_gain = desc->edge_out_scale[e] * desc->edge_spline_scale[e];
           packer.put_base(slice, jj, base_gain);
-          cslice[jj] = base_gain;
-          cslice += jt;
+          cslice[cj] = base_gain;
+          cslice += cjt;
         }
-        for (int r = 0; r < R; ++r) cslice[(size_t)r * jt + jj] = with_base ? spline_gain * c[r] : c[r];
+        for (int r = 0; r < R; ++r) cslice[(size_t)r * cjt + cj] = with_base ? spline_gain * c[r] : c[r];
         for (int k = 0; k < K; ++k) {
           const int r0 = first_knot + k - P;               // coefficient of the span's first basis function
           auto coefficient = [&](int r) { return (r >= 0 && r < R) ? (double)c[r] : 0.0; };
@@ -381,7 +390,7 @@ extern "C" int lutkan_compile(const lutkan_layer_desc *desc, int32_t n_threads, 
     return fail(LUTKAN_EUNSUPPORTED, "lutkan_compile: %ld segments have an alpha or y_min too large for float16", n);
   }
 
-  fill_info(a, d, m, K, L, G, scheme, desc->boundary, desc->oob, repr, desc->param_dtype, desc->knots_per_input, jt, n_tiles, lay, coef_blob);
+  fill_info(a, d, m, K, L, G, scheme, desc->boundary, desc->oob, repr, desc->param_dtype, desc->knots_per_input, jt, n_tiles, lay, cjt, coef_blob);
   a->info.knot_span = desc->knot_span;
   *out = a;
   return LUTKAN_OK;
@@ -459,7 +468,7 @@ extern "C" int lutkan_artifact_from_arrays(const lutkan_artifact_arrays *in, lut
         packer.put_segment(slice, j % jt, k, a->scale[e * K + k], a->ymin[e * K + k], with_base, spline_gain, a->q.data() + (e * K + k) * L);
     }
   // a LUT artifact holds no spline coefficients: G = 0 and an empty B-spline table say so
-  fill_info(a, d, m, K, L, 0, scheme, in->boundary, in->oob, repr, in->param_dtype, in->knots_per_input, jt, n_tiles, lay, 0);
+  fill_info(a, d, m, K, L, 0, scheme, in->boundary, in->oob, repr, in->param_dtype, in->knots_per_input, jt, n_tiles, lay, 0, 0);
   *out = a;
   return LUTKAN_OK;
 }
@@ -506,7 +515,7 @@ extern "C" int bspline_dev_layer_init(const lutkan_artifact *a, bspline_dev_laye
   const lutkan_info &I = a->info;
   out->d = I.d; out->m = I.m; out->G = I.G; out->degree = I.degree;
   out->boundary = I.boundary; out->oob = I.oob; out->value_repr = I.value_repr; out->knot_span = I.knot_span;
-  out->jt = I.jt; out->n_tiles = I.n_tiles; out->coef_blob_bytes = I.coef_blob_bytes;
+  out->jt = I.coef_jt; out->n_tiles = I.coef_n_tiles; out->coef_blob_bytes = I.coef_blob_bytes;
   out->algo = LUTKAN_ALGO_AUTO;
   for (int r = 0; r < I.G + 2 * P + 1; ++r) out->ext_knots[r] = a->ext_knots[r];
   out->coef_table = nullptr;

@@ -98,7 +98,7 @@ __global__ __launch_bounds__(256) void sum_partials_kernel(const float *part, fl
 // ------------------------------------------------------------------------------------------------
 constexpr int kTileWaves = 16;          // waves per tiled work-group (1024 threads, one work-group per CU)
 constexpr int kMaxTileRows = kTileWaves * 64;   // largest row tile of any tiled variant; Bp is a multiple of it
-constexpr int kMaxTiledLds = 144 * 1024;
+constexpr int kMaxTiledLds = lutkan::kLdsPerWorkGroup;
 
 inline int64_t round_up(int64_t v, int64_t q) { return (v + q - 1) / q * q; }
 inline int64_t padded_rows(int64_t B) { return round_up(B, kMaxTileRows); }

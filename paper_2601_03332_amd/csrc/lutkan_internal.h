@@ -47,14 +47,24 @@ inline BlobLayout blob_layout(int K, int L, int jt, int scheme, int value_repr, 
 // Rows of one (tile, input) slice of the B-spline device table: [base row (spline_component only)][R coefficient rows].
 inline int coef_slice_rows(int R, int value_repr) { return R + (value_repr == LUTKAN_REPR_SPLINE_COMPONENT ? 1 : 0); }
 
-// Largest table slice of the tiled kernels: two slice buffers plus the per-wave record buffers must fit the
-// 160 KiB of LDS of a gfx950 CU.
-constexpr int kLdsSliceBudget = 56 * 1024;
+// LDS that one work-group of the tiled kernels may use: all 160 KiB of a gfx950 compute unit.
+constexpr int kLdsPerWorkGroup = 160 * 1024;
 
-// Column-tile width for a layer: the widest power of two in 4 .. 128 (not wider than the next power of two >= m)
-// whose slice fits the LDS budget; a table of 4096 rows still runs on the tiled kernel, 8 columns at a time, twice
-// as fast as on the gather kernel.  If not even 4 columns fit: 32 (or the layer's width), for the gather kernel.
+// Largest table slice of the LUT tiled kernel: two slice buffers plus the per-wave record buffers (16 waves x 2 buffers
+// x at most 64 rows of 8-byte records, 16-byte with the base branch) must fit: 72 KiB, 64 KiB with the base branch.
+inline int lds_slice_budget(int value_repr) {
+  const int record_bytes = (value_repr == LUTKAN_REPR_SPLINE_COMPONENT) ? 16 : 8;
+  return (kLdsPerWorkGroup - 16 * 2 * 64 * record_bytes) / 2;
+}
+
+// Column-tile width of a layer's LUT table: the widest power of two in 4 .. 64 (not wider than the next power of two
+// >= m) whose slice fits the LDS budget; a table of 4096 rows still runs on the tiled kernel, 8 columns at a time,
+// twice as fast as on the gather kernel.  If not even 4 columns fit: 32 (or the layer's width), for the gather kernel.
+// 128-column tiles, where they fit, measured 1-6 % slower than 64 from 4096 rows on.
 int choose_jt(int m, int K, int L, int scheme, int value_repr, int param_dtype);
+// Column-tile width of the B-spline coefficient table: a power of two in 4 .. 128 (its slices always fit; that layer
+// measured 1.5-4 % faster on 128 columns than on 64 at the largest batches).
+int choose_coef_jt(int m);
 
 }  // namespace lutkan
 

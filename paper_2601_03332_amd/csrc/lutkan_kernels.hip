@@ -675,7 +675,7 @@ int validate_layer(const lutkan_dev_layer *l, const char *who) {
   if (l->param_dtype != LUTKAN_PARAM_FP32 && l->param_dtype != LUTKAN_PARAM_FP16) return fail(LUTKAN_EINVAL, "%s: bad param_dtype %d", who, l->param_dtype);
   for (int k = 0; k < l->K; ++k)
     if (!(l->knots[k] < l->knots[k + 1])) return fail(LUTKAN_EINVAL, "%s: knots not strictly increasing at %d", who, k);
-  if (l->jt < 4 || l->jt > 128 || (l->jt & (l->jt - 1))) return fail(LUTKAN_EINVAL, "%s: jt=%d is not a power of two in [4,128]", who, l->jt);
+  if (l->jt < 4 || l->jt > 64 || (l->jt & (l->jt - 1))) return fail(LUTKAN_EINVAL, "%s: jt=%d is not a power of two in [4,64]", who, l->jt);
   if (l->n_tiles != (l->m + l->jt - 1) / l->jt) return fail(LUTKAN_ESHAPE, "%s: n_tiles does not match m and jt", who);
   if (l->blob_bytes != lutkan::blob_layout(l->K, l->L, l->jt, l->scheme, l->value_repr, l->param_dtype).bytes) return fail(LUTKAN_ESHAPE, "%s: blob_bytes does not match K, L, jt, scheme, param_dtype", who);
   if ((reinterpret_cast<uintptr_t>(l->table) & 15) != 0) return fail(LUTKAN_EINVAL, "%s: table must be 16-byte aligned", who);
@@ -722,7 +722,6 @@ int launch_tiled(const EdgeArgs &ea, int np, hipStream_t s) {
 template <int SCHEME>
 int launch_tiled_jt(const EdgeArgs &ea, int np, hipStream_t s) {
   switch (ea.jt) {
-    case 128: return launch_tiled<SCHEME, 32>(ea, np, s);
     case 64: return launch_tiled<SCHEME, 16>(ea, np, s);
     case 32: return launch_tiled<SCHEME, 8>(ea, np, s);
     case 16: return launch_tiled<SCHEME, 4>(ea, np, s);
@@ -731,8 +730,8 @@ int launch_tiled_jt(const EdgeArgs &ea, int np, hipStream_t s) {
   }
 }
 
-bool tiled_supported(int jt, int blob_bytes) {
-  return jt >= 4 && blob_bytes <= lutkan::kLdsSliceBudget;
+bool tiled_supported(int jt, int blob_bytes, int value_repr) {
+  return jt >= 4 && blob_bytes <= lutkan::lds_slice_budget(value_repr);
 }
 
 
@@ -871,10 +870,10 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   ea.with_base = with_base; ea.k_out = k_out; ea.l0_out = l0_out;
   ea.param_fp16 = lutkan::device_params_are_half(l->value_repr, l->param_dtype, l->jt);
 
-  bool tiled = tiled_supported(l->jt, l->blob_bytes) && !q01_out;
+  bool tiled = tiled_supported(l->jt, l->blob_bytes, l->value_repr) && !q01_out;
   if (l->algo == LUTKAN_ALGO_GATHER) tiled = false;
   if (l->algo == LUTKAN_ALGO_AUTO && tiled && prefer_gather_for_small_batch(l, B)) tiled = false;
-  if (l->algo == LUTKAN_ALGO_TILED && !tiled) return fail(LUTKAN_EUNSUPPORTED, "%s: tiled kernel needs a table slice <= 56 KiB", who);
+  if (l->algo == LUTKAN_ALGO_TILED && !tiled) return fail(LUTKAN_EUNSUPPORTED, "%s: tiled kernel needs a table slice <= 72 KiB (64 KiB with the base branch)", who);
   ea.chunk = l->d;
   ea.split_stride = 0;
   if (tiled) {

@@ -115,7 +115,7 @@ def test_property_layers_gather_with_codes(case):
     seed, d, m, G, L, scheme, boundary, oob, B, uniform = case
     w = random_layer(seed, d, m, G, L, scheme, boundary, oob, B, uniform=uniform)
     _check_layer(w.layers[0], w.x, lk.ALGO_GATHER, codes=(B * d * m <= 2_000_000), what=w.name)
-    _check_layer(w.layers[0], w.x, lk.ALGO_TILED, what=w.name)          # narrow column tiles: 4..128 columns
+    _check_layer(w.layers[0], w.x, lk.ALGO_TILED, what=w.name)          # narrow column tiles: 4..64 columns
 
 
 TILED_CASES = [
@@ -144,6 +144,30 @@ def test_property_layers_tiled(case):
     _check_layer(w.layers[0], w.x, lk.ALGO_GATHER, what=w.name)
 
 
+@pytest.mark.parametrize("base", [False, True], ids=["phi", "spline_component"])
+def test_largest_slices_with_the_largest_record_buffers_fill_the_lds(base):
+    """The LDS budget at its edge: 64-column slices of 72 KiB (64 KiB with the base branch, whose records are 16 bytes)
+    at a batch large enough for 16 row steps per wave, so that two slice buffers and the record buffers take all but
+    a few hundred bytes of the 160 KiB of a compute unit.  Sampled rows against the oracle."""
+    L = 122 if base else 139         # 8 L + 2 code rows of 64 bytes + parameters: just under the budget
+    B = 262144 + 3
+    w = random_layer(230 + base, 4, 64, 8, L, SYM_INT8, HALF_OPEN, ZERO_SPLINE, B, with_base=base)
+    s = w.layers[0]
+    art, ora = _compile_both(s)
+    budget = (64 if base else 72) * 1024
+    assert art.info.jt == 64 and budget - 1024 < art.info.blob_bytes <= budget
+    layer = _device_layer(art, s)
+    xg = torch.from_numpy(w.x).to(DEV)
+    _say(f"case {w.name} B={B} slice of {art.info.blob_bytes} bytes")
+    y = lk.lutkan_forward(layer, xg)
+    assert lk.lutkan_last_plan().startswith("locate; tiled np=16 "), lk.lutkan_last_plan()
+    lds = 2 * art.info.blob_bytes + 16 * 2 * 64 * (16 if base else 8)
+    assert 160 * 1024 - 1024 < lds <= 160 * 1024
+    rows = np.unique(np.concatenate([np.random.Generator(np.random.PCG64(5)).integers(0, B, size=1500), [0, B - 1]]))
+    ref = oracle.lut_forward(ora, s.boundary, s.oob, w.x[rows], edge_scalars=s.edge_scales)
+    _assert_close(y[torch.from_numpy(rows).to(DEV)].cpu().numpy(), ref, w.name)
+
+
 def test_table_too_large_for_any_tile_runs_on_the_gather_kernel():
     """32768 table rows: not even a 4-column slice fits the LDS budget; AUTO takes the gather kernel on 32-column
     tiles, and asking for the tiled kernel is an error, not a silent fallback."""
@@ -151,7 +175,7 @@ def test_table_too_large_for_any_tile_runs_on_the_gather_kernel():
     s = w.layers[0]
     _check_layer(s, w.x, lk.ALGO_AUTO, what=w.name)
     art = _compile_both(s)[0]
-    assert art.info.jt == 32 and art.info.blob_bytes > 56 * 1024
+    assert art.info.jt == 32 and art.info.blob_bytes > 72 * 1024
     with pytest.raises(lk.LutKanError) as e:
         lk.lutkan_forward(_device_layer(art, s, lk.ALGO_TILED), torch.from_numpy(w.x).to(DEV))
     assert str(e.value).startswith("[-5]")

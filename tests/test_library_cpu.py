@@ -13,7 +13,7 @@ import paper_2601_03332_amd as lk
 from paper_2601_03332_amd import binding
 from lutkan_inputs import (ASYM_UINT8, CLIP_X, CLOSED, HALF_OPEN, SYM_INT8, ZERO_SPLINE, cfg1, cfg2, cfg5,
                            random_layer, uniform_ext_knots)
-from lutkan_inputs import per_input_layer
+from lutkan_inputs import draw_edge_scales, per_input_layer
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -56,14 +56,21 @@ def test_host_compile_is_bit_identical_to_the_oracle_and_tables_follow_the_docum
     np.testing.assert_array_equal(art.knots, ora.knots)
     I = art.info
     K, L, jt, nt = I.K, I.L, I.jt, I.n_tiles
-    assert nt == -(-s.m // jt) and (jt & (jt - 1)) == 0 and 4 <= jt <= 128
+    assert nt == -(-s.m // jt) and (jt & (jt - 1)) == 0 and 4 <= jt <= 64
+    cjt, cnt = I.coef_jt, I.coef_n_tiles                   # the B-spline table has its own tile width, up to 128 columns
+    assert cnt == -(-s.m // cjt) and (cjt & (cjt - 1)) == 0 and jt <= cjt <= 128 and I.coef_blob_bytes == (s.G + 3) * cjt * 4
     asym = s.scheme == ASYM_UINT8
     codes_off = (K + 1) * jt * 4 * (2 if asym else 1)
     assert I.blob_bytes == (codes_off + (K * L + 2) * jt + 15) // 16 * 16
-    assert I.table_bytes == nt * s.d * I.blob_bytes and I.coef_table_bytes == nt * s.d * (s.G + 3) * jt * 4
+    assert I.table_bytes == nt * s.d * I.blob_bytes and I.coef_table_bytes == cnt * s.d * (s.G + 3) * cjt * 4
     assert I.artifact_bytes == oracle.artifact_bytes(s.d * s.m, K, L, 8)
     tab = art.table.reshape(nt, s.d, I.blob_bytes)
-    ctab = art.coef_table.reshape(nt, s.d, s.G + 3, jt)
+    ctab = art.coef_table.reshape(cnt, s.d, s.G + 3, cjt)
+    for t in range(cnt):
+        cols = np.arange(t * cjt, min(s.m, (t + 1) * cjt))
+        for i in range(s.d):
+            np.testing.assert_array_equal(ctab[t, i, :, :cols.size], s.coef[i, cols].T)
+            assert np.all(ctab[t, i, :, cols.size:] == 0)
     qdt = np.uint8 if asym else np.int8
     for t in range(nt):
         cols = np.arange(t * jt, min(s.m, (t + 1) * jt))
@@ -81,7 +88,6 @@ def test_host_compile_is_bit_identical_to_the_oracle_and_tables_follow_the_docum
             want = want.view(np.uint8) if asym else (want.astype(np.int16) + 128).astype(np.uint8)   # int8: excess-128
             np.testing.assert_array_equal(codes[:, :, :n], want)
             assert np.all(codes[:, :, n:] == 0) and np.all(blob[codes_off + K * L * jt:] == 0)
-            np.testing.assert_array_equal(ctab[t, i, :, :n], s.coef[i, cols].T)
 
 
 def test_device_struct_initialisers():
@@ -213,7 +219,15 @@ def test_spline_component_tables_carry_the_base_row_and_folded_gains():
     assert I.blob_bytes == (codes_off + (K * L + 2) * jt + 15) // 16 * 16
     assert I.artifact_bytes == oracle.artifact_bytes(s.d * s.m, K, L, 8) + 12 * s.d * s.m
     tab = art.table.reshape(nt, s.d, I.blob_bytes)
-    ctab = art.coef_table.reshape(nt, s.d, s.G + 4, jt)
+    cjt, cnt = I.coef_jt, I.coef_n_tiles
+    ctab = art.coef_table.reshape(cnt, s.d, s.G + 4, cjt)
+    for t in range(cnt):
+        cols = np.arange(t * cjt, min(s.m, (t + 1) * cjt))
+        for i in range(s.d):
+            e = i * s.m + cols
+            np.testing.assert_array_equal(ctab[t, i, 0, :cols.size], so[e] * sb[e])
+            gain = (so[e] * ss[e]).astype(np.float32)
+            np.testing.assert_array_equal(ctab[t, i, 1:, :cols.size], (gain[None, :] * s.coef[i, cols].T).astype(np.float32))
     for t in range(nt):
         cols = np.arange(t * jt, min(s.m, (t + 1) * jt))
         n = cols.size
@@ -221,12 +235,10 @@ def test_spline_component_tables_carry_the_base_row_and_folded_gains():
             e = i * s.m + cols
             base = tab[t, i, :params_off].view(np.float32)
             np.testing.assert_array_equal(base[:n], so[e] * sb[e])
-            np.testing.assert_array_equal(ctab[t, i, 0, :n], so[e] * sb[e])
             prm = tab[t, i, params_off:codes_off].view(np.float32).reshape(K + 1, 2, jt)
             gain = (so[e] * ss[e]).astype(np.float32)
             np.testing.assert_array_equal(prm[:K, 0, :n], (gain[None, :] * art.scale[e].T).astype(np.float32))
             np.testing.assert_array_equal(prm[:K, 1, :n], (gain[None, :] * art.y_min[e].T).astype(np.float32))
-            np.testing.assert_array_equal(ctab[t, i, 1:, :n], (gain[None, :] * s.coef[i, cols].T).astype(np.float32))
 
 
 @pytest.mark.parametrize("m", [30, 70])
@@ -248,7 +260,7 @@ def test_fp16_parameter_tables(scheme, m):
     assert I.param_dtype == lk.PARAM_FP16 and a32.info.param_dtype == lk.PARAM_FP32
     K, L, jt, nt = I.K, I.L, I.jt, I.n_tiles
     per = 2 if scheme == ASYM_UINT8 else 1
-    assert jt == (32 if m == 30 else 128)
+    assert jt == (32 if m == 30 else 64)
     pdt = np.float16 if jt <= 32 else np.float32
     codes_off = (K + 1) * jt * np.dtype(pdt).itemsize * per
     assert I.blob_bytes == (codes_off + (K * L + 2) * jt + 15) // 16 * 16
@@ -442,16 +454,24 @@ def test_knots_per_input_compile_like_the_oracle(scheme, extended, half, base, t
 
 
 def test_tile_width_follows_the_table_size():
-    """The widest power of two in 4..128 whose slice fits 56 KiB of LDS; 32 (gather kernel) if not even 4 columns fit."""
+    """The widest power of two in 4..64 whose slice fits 72 KiB of LDS (two slices and the record buffers in the 160 KiB
+    of a compute unit; 64 KiB with the base branch, whose records are twice as large); 32 (gather kernel) if not even
+    4 columns fit.  The B-spline table's tiles go up to 128 columns."""
     rng = np.random.Generator(np.random.PCG64(3))
-    for G, L, m, want in ((8, 64, 300, 64), (8, 128, 300, 32), (16, 128, 300, 16), (32, 128, 300, 8), (64, 200, 300, 4),
-                          (64, 512, 300, 32), (64, 512, 10, 16), (8, 16, 300, 128), (8, 16, 5, 8), (32, 128, 3, 4)):
+    for G, L, m, want in ((8, 64, 300, 64), (8, 128, 300, 64), (9, 128, 300, 32), (16, 128, 300, 32), (32, 128, 300, 16), (64, 200, 300, 4),
+                          (64, 512, 300, 32), (64, 512, 10, 16), (8, 16, 300, 64), (8, 16, 5, 8), (32, 128, 3, 4)):
         tau = np.linspace(-1.0, 1.0, G + 7).astype(np.float32)
         art = lk.lutkan_compile(1, m, G, 3, tau, rng.normal(size=(1, m, G + 3)).astype(np.float32), L, SYM_INT8, CLOSED, CLIP_X)
         I = art.info
         assert I.jt == want, (G, L, m, I.jt, want)
         assert I.n_tiles == -(-m // I.jt) and I.table_bytes == I.n_tiles * I.blob_bytes
-        assert (I.blob_bytes <= 56 * 1024) == (not (G == 64 and L == 512))
+        assert I.coef_jt == min(128, max(4, 1 << (m - 1).bit_length())) and I.coef_n_tiles == -(-m // I.coef_jt)
+        assert (I.blob_bytes <= 72 * 1024) == (not (G == 64 and L == 512))
+    # with the base branch the records are 16 bytes: 64 KiB per slice, so the 1026-row table takes 32-column tiles
+    tau = np.linspace(-1.0, 1.0, 8 + 7).astype(np.float32)
+    coef = rng.normal(size=(1, 300, 8 + 3)).astype(np.float32)
+    based = lk.lutkan_compile(1, 300, 8, 3, tau, coef, 128, SYM_INT8, CLOSED, CLIP_X, edge_scales=draw_edge_scales(rng, 1, 300))
+    assert based.info.jt == 32 and 2 * based.info.blob_bytes > 64 * 1024
 
 
 def test_table9_artifact_bytes_from_the_compiler():
