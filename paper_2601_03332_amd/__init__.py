@@ -5,10 +5,12 @@ arguments (torch tensors -> raw device pointers, the current HIP stream) and kee
 There is no CPU fallback: importing works anywhere, calling a forward without a GPU raises.
 """
 from .binding import (  # noqa: F401
-    ALGO_AUTO, ALGO_GATHER, ALGO_TILED, PARAM_FP32, PARAM_FP16, SPAN_DOMAIN, SPAN_EXTENDED, PROBE_VALU_FMA, PROBE_LDS_READ, PROBE_L2_READ, PROBE_HBM_READ, PROBE_VALU_MIX, ASYM_UINT8, CLIP_X, CLOSED, HALF_OPEN, REPR_PHI, REPR_SPLINE_COMPONENT,
-    SYM_INT8, ZERO_SPLINE,
-    Artifact, BsplineLayer, LutKanError, LutLayer, bspline_forward_workspace_bytes, bspline_kan_forward,
-    library_path, lutkan_error_stats, lutkan_artifact_from_arrays, lutkan_artifact_load, lutkan_compile, lutkan_forward, lutkan_forward_edges, lutkan_forward_locate, lutkan_forward_trace,
-    bspline_forward_edges, bspline_forward_locate, lutkan_forward_workspace_bytes,
-    lutkan_last_error, lutkan_last_plan, lutkan_chain_forward, lutkan_model_forward, lutkan_model_workspace_bytes, lutkan_probe_launch, lutkan_version, load_library,
+    ALGO_AUTO, ALGO_GATHER, ALGO_TILED, PARAM_FP32, PARAM_FP16, SPAN_DOMAIN, SPAN_EXTENDED, PROBE_VALU_FMA,
+    PROBE_LDS_READ, PROBE_L2_READ, PROBE_HBM_READ, PROBE_VALU_MIX, ASYM_UINT8, CLIP_X, CLOSED, HALF_OPEN, REPR_PHI,
+    REPR_SPLINE_COMPONENT, SYM_INT8, ZERO_SPLINE, Artifact, BsplineLayer, LutKanError, LutLayer,
+    bspline_forward_workspace_bytes, bspline_kan_forward, library_path, lutkan_error_stats,
+    lutkan_artifact_from_arrays, lutkan_artifact_load, lutkan_compile, lutkan_forward, lutkan_forward_edges,
+    lutkan_forward_locate, lutkan_forward_trace, bspline_forward_edges, bspline_forward_locate,
+    lutkan_forward_workspace_bytes, lutkan_last_error, lutkan_last_plan, lutkan_chain_forward, lutkan_model_forward,
+    lutkan_model_workspace_bytes, lutkan_probe_launch, lutkan_version, load_library,
 )
