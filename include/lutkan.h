@@ -222,6 +222,20 @@ size_t bspline_forward_workspace_bytes(const bspline_dev_layer *layer, int64_t B
 int lutkan_forward(const lutkan_dev_layer *layer, const float *x, int64_t B, float *y,
                    lutkan_oob_stats *stats, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* lutkan_forward for callers that cannot hand over a workspace because they cannot allocate one: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The lookup records and partial sums go to an array
+ * of LUTKAN_STATIC_SCRATCH_BYTES bytes that is part of the library's device code: every GPU the library runs on holds
+ * one copy from the first call on it until the process ends.  The call allocates and frees nothing and launches the
+ * same kernels as lutkan_forward, so y and stats are bit-identical to lutkan_forward's.
+ *   ESHAPE when lutkan_forward_workspace_bytes(layer, B) exceeds LUTKAN_STATIC_SCRATCH_BYTES (the message says by how
+ *   much); other errors as lutkan_forward.
+ * All calls on one GPU share that GPU's array: two calls may be in flight together only on the same stream (or
+ * otherwise ordered one after the other); calls that overlap on one GPU race on the records.  Contents are undefined
+ * between calls and nothing in the array needs clearing. */
+#define LUTKAN_STATIC_SCRATCH_BYTES (64u << 20)
+int lutkan_forward_static_scratch(const lutkan_dev_layer *layer, const float *x, int64_t B, float *y,
+                                  lutkan_oob_stats *stats, void *hip_stream);
+
 /* The two phases of lutkan_forward as separate calls, for callers that time or overlap them:
  *   lutkan_forward_locate   steps 1-4 of Sec. 4.5 and the domain test of Sec. 5.2 for every (row, input);
  *                           fills the workspace with the lookup records (and adds to stats, nullable)

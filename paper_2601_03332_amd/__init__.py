@@ -12,5 +12,6 @@ from .binding import (  # noqa: F401
     lutkan_artifact_from_arrays, lutkan_artifact_load, lutkan_compile, lutkan_forward, lutkan_forward_edges,
     lutkan_forward_locate, lutkan_forward_trace, bspline_forward_edges, bspline_forward_locate,
     lutkan_forward_workspace_bytes, lutkan_last_error, lutkan_last_plan, lutkan_chain_forward, lutkan_model_forward,
-    lutkan_model_workspace_bytes, lutkan_probe_launch, lutkan_version, load_library,
+    lutkan_model_workspace_bytes, lutkan_probe_launch, lutkan_version, load_library, lutkan_forward_static_scratch,
+    STATIC_SCRATCH_BYTES,
 )

@@ -73,7 +73,7 @@ EXPORTS = [
     "bspline_forward_workspace_bytes", "lutkan_forward", "lutkan_forward_trace", "bspline_kan_forward",
     "lutkan_model_workspace_bytes", "lutkan_model_forward", "lutkan_chain_forward", "lutkan_forward_locate", "lutkan_forward_edges",
     "bspline_forward_locate", "bspline_forward_edges", "lutkan_probe_launch", "lutkan_artifact_from_arrays",
-    "lutkan_error_stats_workspace_bytes", "lutkan_error_stats",
+    "lutkan_error_stats_workspace_bytes", "lutkan_error_stats", "lutkan_forward_static_scratch",
 ]
 
 _lib = None
@@ -112,6 +112,7 @@ def load_library():
     lib.bspline_forward_workspace_bytes.argtypes = [C.POINTER(_SplineDevLayer), i64]
     lib.bspline_forward_workspace_bytes.restype = sz
     lib.lutkan_forward.argtypes = [C.POINTER(_DevLayer), vp, i64, vp, vp, vp, sz, vp]
+    lib.lutkan_forward_static_scratch.argtypes = [C.POINTER(_DevLayer), vp, i64, vp, vp, vp]
     lib.lutkan_forward_trace.argtypes = [C.POINTER(_DevLayer), vp, i64, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.bspline_kan_forward.argtypes = [C.POINTER(_SplineDevLayer), vp, i64, vp, vp, sz, vp]
     lib.lutkan_forward_locate.argtypes = [C.POINTER(_DevLayer), vp, i64, vp, vp, sz, vp]
@@ -432,6 +433,26 @@ def lutkan_forward(layer: LutLayer, x, y=None, stats=None, workspace=None):
     _check(load_library().lutkan_forward(C.byref(layer.c), x.data_ptr(), B, y.data_ptr(),
                                          stats.data_ptr() if stats is not None else None,
                                          ws.data_ptr(), ws.numel(), _stream(x.device)))
+    return y
+
+
+STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def lutkan_forward_static_scratch(layer: LutLayer, x, y, stats=None):
+    """lutkan_forward without a workspace: the scratch is an array inside the library (see lutkan.h).  Nothing is
+    allocated, here or in the library, so the caller brings y."""
+    torch = _torch()
+    _require(x, torch.float32, "x")
+    _require(y, torch.float32, "y")
+    B = x.shape[0]
+    if x.dim() != 2 or x.shape[1] != layer.d or tuple(y.shape) != (B, layer.m):
+        raise LutKanError(f"x must be [B,{layer.d}] and y [B,{layer.m}]")
+    if stats is not None:
+        _require(stats, torch.int64, "stats")
+    _check(load_library().lutkan_forward_static_scratch(C.byref(layer.c), x.data_ptr(), B, y.data_ptr(),
+                                                        stats.data_ptr() if stats is not None else None,
+                                                        _stream(x.device)))
     return y
 
 

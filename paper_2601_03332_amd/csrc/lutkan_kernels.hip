@@ -927,6 +927,52 @@ extern "C" int lutkan_forward(const lutkan_dev_layer *layer, const float *x, int
                       workspace_bytes, hip_stream, "lutkan_forward");
 }
 
+// Device memory for lutkan_forward_static_scratch: one array per GPU that loads this library, held until the process
+// ends.  In host code the name is only a handle for hipGetSymbolAddress; what kernels and copies get is the address
+// that call returns on the current device.
+static __device__ __align__(256) unsigned char scratch[LUTKAN_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];     // per device ordinal: the device address of that GPU's copy of `scratch`
+
+// The current device's copy of the scratch array (looked up once per device, with that device current).
+int static_scratch(void **out, const char *who) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(LUTKAN_EHIP, "%s: hipGetDevice: %s", who, hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices) return fail(LUTKAN_EUNSUPPORTED, "%s: device ordinal %d", who, dev);
+  void *ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) return fail(LUTKAN_EHIP, "%s: hipGetSymbolAddress(scratch): %s", who, hipGetErrorString(e));
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+  }
+  *out = ptr;
+  return LUTKAN_OK;
+}
+}  // namespace
+
+extern "C" int lutkan_forward_static_scratch(const lutkan_dev_layer *layer, const float *x, int64_t B, float *y,
+                                             lutkan_oob_stats *stats, void *hip_stream) {
+  const char *who = "lutkan_forward_static_scratch";
+  lutkan::plan_clear();
+  if (int rc = validate_layer(layer, who)) return rc;
+  if (B < 0) return fail(LUTKAN_EINVAL, "%s: B < 0", who);
+  if (B == 0) return LUTKAN_OK;
+  const size_t need = lutkan_forward_workspace_bytes(layer, B);
+  if (need > (size_t)LUTKAN_STATIC_SCRATCH_BYTES)
+    return fail(LUTKAN_ESHAPE, "%s: %lld rows of this %d -> %d layer need %zu bytes of scratch, the built-in array holds %zu; "
+                "use lutkan_forward with a workspace of the caller's", who, (long long)B, layer->d, layer->m, need,
+                (size_t)LUTKAN_STATIC_SCRATCH_BYTES);
+  void *ptr = nullptr;
+  if (int rc = static_scratch(&ptr, who)) return rc;
+  // Nothing in the scratch has to start at zero: the locate kernel writes every record of every padded row, and the
+  // edge kernels write every partial sum that the summing pass reads.
+  return forward_impl(layer, x, B, y, stats, nullptr, nullptr, nullptr, nullptr, nullptr, false, ptr,
+                      (size_t)LUTKAN_STATIC_SCRATCH_BYTES, hip_stream, who);
+}
+
 extern "C" int lutkan_forward_locate(const lutkan_dev_layer *layer, const float *x, int64_t B, lutkan_oob_stats *stats,
                                      void *workspace, size_t workspace_bytes, void *hip_stream) {
   lutkan::plan_clear();

@@ -192,6 +192,18 @@ def test_forward_argument_validation_happens_before_any_launch():
     assert lib.lutkan_chain_forward(one, 0, 16, 4, 32, None, None, None) == -1
     nine = (binding._DevLayer * 9)(*([dl] * 9))
     assert lib.lutkan_chain_forward(nine, 9, 16, 4, 32, None, None, None) == -5             # more than eight layers
+    # the entry point with the built-in scratch array: the same checks, and sizes beyond the array are refused
+    assert lib.lutkan_forward_static_scratch(C.byref(dl), 16, 0, 32, None, None) == 0       # B == 0: no-op
+    assert lib.lutkan_forward_static_scratch(C.byref(dl), 16, -1, 32, None, None) == -1
+    too_many = binding.STATIC_SCRATCH_BYTES // (8 * s.d) + 1024
+    assert lib.lutkan_forward_workspace_bytes(C.byref(dl), too_many) > binding.STATIC_SCRATCH_BYTES
+    assert lib.lutkan_forward_static_scratch(C.byref(dl), 16, too_many, 32, None, None) == -2
+    assert "built-in array holds 67108864" in lk.lutkan_last_error()
+    header = open(os.path.join(ROOT, "include", "lutkan.h")).read()
+    assert re.search(r"#define LUTKAN_STATIC_SCRATCH_BYTES \(64u << 20\)", header) and binding.STATIC_SCRATCH_BYTES == 64 << 20
+    nul = binding._DevLayer.from_buffer_copy(dl)
+    nul.table = None
+    assert lib.lutkan_forward_static_scratch(C.byref(nul), 16, 4, 32, None, None) == -1
     wide = cfg5().layers[1]                                                                  # 128 -> 128
     wl = binding._DevLayer()
     wide_art = _both(wide)[0]                                                               # stays alive across the call
