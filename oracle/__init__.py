@@ -211,8 +211,11 @@ def artifact_bytes(E: int, K: int, L: int, param_bytes_per_segment: int) -> int:
 def error_stats(y, y_ref, x, t0, tK, boundary):
     """OOB evaluation protocol of Sec. 5.6 written out: a sample (row) is in-range when every input satisfies the
     domain predicate In(x) of Sec. 5.2 (half_open: t0 <= x < tK, closed: t0 <= x <= tK; NaN is outside), else it is
-    in the OOB-only subset.  t0 and tK are scalars, or [d] arrays when every input has its own domain.  Per subset: number of rows, sum and maximum of |y - y_ref| over the rows' outputs in
-    fp64, MAE = sum / (number of non-NaN differences); differences that are NaN are counted and left out."""
+    in the OOB-only subset; OOB_any_frac is the share of rows in the second subset.  t0 and tK are scalars, or [d]
+    arrays when every input has its own domain.  Per subset: number of rows, and over the outputs of its rows, in fp64,
+    the sum, the maximum and the mean (MAE, Sec. 6.5) of |y - y_ref|.  A difference that is NaN is counted (nan_in,
+    nan_oob) and left out of all three, so MAE = sum / (rows * m - nan): the mean of the differences that exist, NaN
+    when there is none."""
     x = _f32(x)
     y = np.asarray(y, dtype=np.float32).astype(np.float64)
     y_ref = np.asarray(y_ref, dtype=np.float32).astype(np.float64)
@@ -220,12 +223,12 @@ def error_stats(y, y_ref, x, t0, tK, boundary):
     inside = (x >= t0) & ((x <= tK) if boundary == CLOSED else (x < tK))
     row_in = inside.all(axis=1)
     err = np.abs(y - y_ref)
+    out = {"rows_in": int(row_in.sum()), "rows_oob": int((~row_in).sum()), "oob_any_frac": float((~row_in).sum() / x.shape[0])}
     nan = np.isnan(err)
-    out = {"rows_in": int(row_in.sum()), "rows_oob": int((~row_in).sum()), "nan_outputs": int(nan.sum()),
-           "oob_any_frac": float((~row_in).mean())}
     for name, rows in (("in", row_in), ("oob", ~row_in)):
-        e = err[rows][~nan[rows]]
+        e = err[rows][~nan[rows]]                       # the subset's differences that exist
+        out["nan_" + name] = int(nan[rows].sum())
         out["sum_abs_" + name] = float(e.sum()) if e.size else 0.0
         out["max_abs_" + name] = float(e.max()) if e.size else 0.0
-        out["mae_" + name] = float(e.sum() / (int(rows.sum()) * y.shape[1])) if rows.any() else float("nan")
+        out["mae_" + name] = float(e.sum() / e.size) if e.size else float("nan")
     return out

@@ -543,12 +543,34 @@ def test_error_stats_on_a_hand_made_example():
     y = np.array([[1.0, 2.0], [3.0, 5.0], [0.0, 0.0]], dtype=np.float32)
     r = np.array([[1.5, 2.0], [2.0, 5.5], [4.0, -1.0]], dtype=np.float32)
     c = oracle.error_stats(y, r, x, -1.0, 1.0, CLOSED)            # t_K belongs to the domain: rows 0, 1 in-range
-    assert (c["rows_in"], c["rows_oob"], c["nan_outputs"]) == (2, 1, 0)
+    assert (c["rows_in"], c["rows_oob"], c["nan_in"], c["nan_oob"]) == (2, 1, 0, 0)
     assert c["sum_abs_in"] == 0.5 + 0.0 + 1.0 + 0.5 and c["max_abs_in"] == 1.0 and c["mae_in"] == 2.0 / 4
     assert c["sum_abs_oob"] == 5.0 and c["max_abs_oob"] == 4.0 and c["mae_oob"] == 2.5 and c["oob_any_frac"] == 1 / 3
     h = oracle.error_stats(y, r, x, -1.0, 1.0, HALF_OPEN)         # x = t_K is outside (Sec. 5.5): row 1 moves over
     assert (h["rows_in"], h["rows_oob"]) == (1, 2)
     assert h["sum_abs_in"] == 0.5 and h["sum_abs_oob"] == 6.5 and h["max_abs_oob"] == 4.0 and h["mae_oob"] == 6.5 / 4
+
+
+def test_error_stats_mean_leaves_nan_differences_out_of_the_count():
+    """A NaN output inside each subset: it is counted per subset and left out of that subset's sum, maximum AND of the
+    number the sum is divided by, so the mean is the mean of the differences that exist.  Dividing by rows * m instead
+    (the NaN output still counted as a term) would give 1.5 / 4 and 5.0 / 4 below.  Values by hand."""
+    nan = np.float32(np.nan)
+    x = np.array([[0.0, 0.5], [0.9, -1.0], [0.2, 1.5], [3.0, 0.0]], dtype=np.float32)     # rows 0, 1 inside [-1, 1]
+    y = np.array([[1.0, nan], [3.0, 5.0], [0.0, 0.0], [nan, 2.0]], dtype=np.float32)
+    r = np.array([[1.5, 2.0], [2.5, 5.5], [4.0, -1.0], [1.0, 2.0]], dtype=np.float32)
+    c = oracle.error_stats(y, r, x, -1.0, 1.0, CLOSED)
+    assert (c["rows_in"], c["rows_oob"], c["nan_in"], c["nan_oob"]) == (2, 2, 1, 1)
+    assert c["sum_abs_in"] == 1.5 and c["max_abs_in"] == 0.5 and c["mae_in"] == 1.5 / 3
+    assert c["sum_abs_oob"] == 5.0 and c["max_abs_oob"] == 4.0 and c["mae_oob"] == 5.0 / 3
+    assert c["oob_any_frac"] == 0.5
+    # the library routine for "mean of what is not NaN" on each subset
+    e = np.abs(y.astype(np.float64) - r.astype(np.float64))
+    assert c["mae_in"] == np.nanmean(e[:2]) and c["mae_oob"] == np.nanmean(e[2:])
+    # a subset whose every difference is NaN has no mean
+    allnan = oracle.error_stats(np.full((1, 2), nan), r[:1], x[:1], -1.0, 1.0, CLOSED)
+    assert (allnan["rows_in"], allnan["nan_in"], allnan["sum_abs_in"]) == (1, 2, 0.0) and np.isnan(allnan["mae_in"])
+    assert np.isnan(allnan["mae_oob"]) and allnan["oob_any_frac"] == 0.0
 
 
 def test_error_stats_against_plain_loops_and_nan_rules():
@@ -564,7 +586,7 @@ def test_error_stats_against_plain_loops_and_nan_rules():
         rows = {"in": 0, "oob": 0}
         sums = {"in": 0.0, "oob": 0.0}
         maxs = {"in": 0.0, "oob": 0.0}
-        nans = 0
+        nans = {"in": 0, "oob": 0}
         for b in range(B):
             inside = True
             for i in range(d):
@@ -576,15 +598,17 @@ def test_error_stats_against_plain_loops_and_nan_rules():
             for j in range(m):
                 e = abs(float(y[b, j]) - float(r[b, j]))
                 if e != e:
-                    nans += 1
+                    nans[key] += 1
                     continue
                 sums[key] += e
                 maxs[key] = max(maxs[key], e)
-        assert (got["rows_in"], got["rows_oob"], got["nan_outputs"]) == (rows["in"], rows["oob"], nans) and nans == 1
+        assert (got["rows_in"], got["rows_oob"]) == (rows["in"], rows["oob"])
+        assert (got["nan_in"], got["nan_oob"]) == (nans["in"], nans["oob"]) and nans["in"] + nans["oob"] == 1
+        assert got["oob_any_frac"] == rows["oob"] / B
         for key in ("in", "oob"):
             assert abs(got["sum_abs_" + key] - sums[key]) <= 1e-12 * sums[key]
             assert got["max_abs_" + key] == maxs[key]
-            assert abs(got["mae_" + key] - sums[key] / (rows[key] * m)) <= 1e-15
+            assert abs(got["mae_" + key] - sums[key] / (rows[key] * m - nans[key])) <= 1e-15
 
 
 # ---------------------------------------------------------------------------------------------------
