@@ -293,17 +293,22 @@ int lutkan_chain_forward(const lutkan_dev_layer *layers, int32_t n_layers, const
  * device: |y - y_ref| over the outputs of the in-range samples (rows whose d inputs all satisfy the domain predicate
  * In(x) of Sec. 5.2 under `boundary` on [t0, tK]) and of the OOB-only samples (rows with at least one input outside;
  * NaN counts as outside).  input_domain (device fp32 [d][2], nullable) gives every input its own {t0, tK} instead,
- * for layers with one knot vector per input.  MAE of a subset = sum_abs / (rows * m - its NaN outputs); OOB_any_frac = rows_oob / B.
+ * for layers with one knot vector per input.
  *   y, y_ref   device [B][m] fp32 (e.g. the LUT layer and the B-spline layer on the same x)
  *   x          device [B][d] fp32, the layer input that decides the subset of each row
  *   out        device, 8-byte aligned, overwritten
  *   workspace  device, >= lutkan_error_stats_workspace_bytes(B), 16-byte aligned
  * Differences are taken and summed in fp64; partial sums are combined in a fixed order (the result is reproducible).
- * Outputs whose difference is NaN are counted in nan_outputs and left out of the sums and maxima. */
+ * An output whose difference is NaN is counted in its subset's nan_* and left out of that subset's sum, maximum and
+ * mean:  mae = sum_abs / (rows * m - nan)  per subset, i.e. the mean of the differences that exist (NaN when the
+ * subset has none);  oob_any_frac = rows_oob / B  (Sec. 5.6). */
 typedef struct {
-  unsigned long long rows_in, rows_oob, nan_outputs;
+  unsigned long long rows_in, rows_oob;
+  unsigned long long nan_in, nan_oob;
   double sum_abs_in, sum_abs_oob;
   double max_abs_in, max_abs_oob;
+  double mae_in, mae_oob;
+  double oob_any_frac;
 } lutkan_error_summary;
 size_t lutkan_error_stats_workspace_bytes(int64_t B);
 int lutkan_error_stats(const float *y, const float *y_ref, int64_t B, int32_t m, const float *x, int32_t d,

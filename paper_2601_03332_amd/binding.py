@@ -4,6 +4,7 @@ from __future__ import annotations
 import ctypes as C
 import json
 import os
+from types import SimpleNamespace
 from typing import List, Optional, Sequence
 
 import numpy as np
@@ -396,6 +397,41 @@ def _require(t, dtype, what):
         raise LutKanError(f"{what} must be a contiguous CUDA tensor of dtype {dtype}")
 
 
+def _check_io(who, layer, x=None, y=None, workspace=None, stats=None, n_stats=1):
+    """Shapes, dtypes and devices of the tensors handed to a forward call, checked before any pointer reaches the
+    library: the kernels index x as [B, d] and y as [B, m] on trust.  Returns B."""
+    torch = _torch()
+    B = None
+    for t, what, width in ((x, "x", layer.d), (y, "y", layer.m)):
+        if t is None:
+            continue
+        if not isinstance(t, torch.Tensor) or t.dtype != torch.float32 or t.dim() != 2 or t.shape[1] != width:
+            raise LutKanError(f"{who}: {what} must be a float32 tensor of shape [B, {width}]")
+        if B is not None and t.shape[0] != B:
+            raise LutKanError(f"{who}: y must have as many rows as x ({B})")
+        B = t.shape[0]
+    if stats is not None and (not isinstance(stats, torch.Tensor) or stats.dtype != torch.int64 or stats.numel() != 2 * n_stats):
+        raise LutKanError(f"{who}: stats must be an int64 tensor of {2 * n_stats} elements")
+    if workspace is not None and (not isinstance(workspace, torch.Tensor) or workspace.dtype != torch.uint8):
+        raise LutKanError(f"{who}: workspace must be a uint8 tensor")
+    for t, what in ((x, "x"), (y, "y"), (workspace, "workspace"), (stats, "stats")):
+        if t is None:
+            continue
+        if not t.is_cuda or not t.is_contiguous():
+            raise LutKanError(f"{who}: {what} must be a contiguous CUDA tensor")
+        if t.device != layer.device:
+            raise LutKanError(f"{who}: {what} is on {t.device}, the layer's tables are on {layer.device}")
+    return B
+
+
+def _check_chain(who, layers):
+    if len(layers) < 1:
+        raise LutKanError(f"{who}: need at least one layer")
+    if any(l.device != layers[0].device for l in layers):        # (that the widths chain is the library's own check)
+        raise LutKanError(f"{who}: the layers' tables must be on one device")
+    return SimpleNamespace(d=layers[0].d, m=layers[-1].m, device=layers[0].device)
+
+
 def lutkan_forward_workspace_bytes(layer: LutLayer, B: int) -> int:
     return int(load_library().lutkan_forward_workspace_bytes(C.byref(layer.c), B))
 
@@ -420,15 +456,9 @@ def _workspace(nbytes, device, workspace):
 def lutkan_forward(layer: LutLayer, x, y=None, stats=None, workspace=None):
     """y[B,m] = LUT layer forward of x[B,d] on the current stream.  stats: optional int64[2] CUDA tensor (added to)."""
     torch = _torch()
-    _require(x, torch.float32, "x")
-    B = x.shape[0]
-    if x.dim() != 2 or x.shape[1] != layer.d:
-        raise LutKanError(f"x must be [B,{layer.d}]")
+    B = _check_io("lutkan_forward", layer, x=x, y=y, workspace=workspace, stats=stats)
     if y is None:
         y = torch.empty((B, layer.m), dtype=torch.float32, device=x.device)
-    _require(y, torch.float32, "y")
-    if stats is not None:
-        _require(stats, torch.int64, "stats")
     ws = _workspace(lutkan_forward_workspace_bytes(layer, B), x.device, workspace)
     _check(load_library().lutkan_forward(C.byref(layer.c), x.data_ptr(), B, y.data_ptr(),
                                          stats.data_ptr() if stats is not None else None,
@@ -442,14 +472,9 @@ STATIC_SCRATCH_BYTES = 64 << 20
 def lutkan_forward_static_scratch(layer: LutLayer, x, y, stats=None):
     """lutkan_forward without a workspace: the scratch is an array inside the library (see lutkan.h).  Nothing is
     allocated, here or in the library, so the caller brings y."""
-    torch = _torch()
-    _require(x, torch.float32, "x")
-    _require(y, torch.float32, "y")
-    B = x.shape[0]
-    if x.dim() != 2 or x.shape[1] != layer.d or tuple(y.shape) != (B, layer.m):
-        raise LutKanError(f"x must be [B,{layer.d}] and y [B,{layer.m}]")
-    if stats is not None:
-        _require(stats, torch.int64, "stats")
+    if y is None:
+        raise LutKanError("lutkan_forward_static_scratch: the caller brings y")
+    B = _check_io("lutkan_forward_static_scratch", layer, x=x, y=y, stats=stats)
     _check(load_library().lutkan_forward_static_scratch(C.byref(layer.c), x.data_ptr(), B, y.data_ptr(),
                                                         stats.data_ptr() if stats is not None else None,
                                                         _stream(x.device)))
@@ -458,36 +483,31 @@ def lutkan_forward_static_scratch(layer: LutLayer, x, y, stats=None):
 
 def lutkan_forward_locate(layer: LutLayer, x, workspace, stats=None):
     """Phase 1 of lutkan_forward: fills `workspace` with the per-(row,input) lookup records."""
-    torch = _torch()
-    _require(x, torch.float32, "x")
-    _require(workspace, torch.uint8, "workspace")
-    _check(load_library().lutkan_forward_locate(C.byref(layer.c), x.data_ptr(), x.shape[0],
+    B = _check_io("lutkan_forward_locate", layer, x=x, workspace=workspace, stats=stats)
+    _check(load_library().lutkan_forward_locate(C.byref(layer.c), x.data_ptr(), B,
                                                 stats.data_ptr() if stats is not None else None,
                                                 workspace.data_ptr(), workspace.numel(), _stream(x.device)))
 
 
 def lutkan_forward_edges(layer: LutLayer, B: int, y, workspace):
-    """Phase 2 of lutkan_forward: gathers, dequantises, interpolates and sums from the records in `workspace`."""
-    torch = _torch()
-    _require(y, torch.float32, "y")
-    _require(workspace, torch.uint8, "workspace")
+    """Phase 2 of lutkan_forward: gathers, dequantises, interpolates and sums from the records that
+    lutkan_forward_locate left in `workspace` for the same layer and the same B."""
+    if _check_io("lutkan_forward_edges", layer, y=y, workspace=workspace) != B:
+        raise LutKanError(f"lutkan_forward_edges: y must have B = {B} rows")
     _check(load_library().lutkan_forward_edges(C.byref(layer.c), B, y.data_ptr(), workspace.data_ptr(),
                                                workspace.numel(), _stream(y.device)))
     return y
 
 
 def bspline_forward_locate(layer: "BsplineLayer", x, workspace):
-    torch = _torch()
-    _require(x, torch.float32, "x")
-    _require(workspace, torch.uint8, "workspace")
-    _check(load_library().bspline_forward_locate(C.byref(layer.c), x.data_ptr(), x.shape[0], workspace.data_ptr(),
+    B = _check_io("bspline_forward_locate", layer, x=x, workspace=workspace)
+    _check(load_library().bspline_forward_locate(C.byref(layer.c), x.data_ptr(), B, workspace.data_ptr(),
                                                  workspace.numel(), _stream(x.device)))
 
 
 def bspline_forward_edges(layer: "BsplineLayer", B: int, y, workspace):
-    torch = _torch()
-    _require(y, torch.float32, "y")
-    _require(workspace, torch.uint8, "workspace")
+    if _check_io("bspline_forward_edges", layer, y=y, workspace=workspace) != B:
+        raise LutKanError(f"bspline_forward_edges: y must have B = {B} rows")
     _check(load_library().bspline_forward_edges(C.byref(layer.c), B, y.data_ptr(), workspace.data_ptr(),
                                                 workspace.numel(), _stream(y.device)))
     return y
@@ -496,8 +516,8 @@ def bspline_forward_edges(layer: "BsplineLayer", B: int, y, workspace):
 def lutkan_forward_trace(layer: LutLayer, x, codes: bool = False, workspace=None):
     """Forward plus the bit-exact quantities of the contract: (y, k, l0, inside, w, q01 or None)."""
     torch = _torch()
-    _require(x, torch.float32, "x")
-    B, d, m = x.shape[0], layer.d, layer.m
+    B = _check_io("lutkan_forward_trace", layer, x=x, workspace=workspace)
+    d, m = layer.d, layer.m
     dev = x.device
     y = torch.empty((B, m), dtype=torch.float32, device=dev)
     k = torch.empty((B, d), dtype=torch.int32, device=dev)
@@ -515,13 +535,9 @@ def lutkan_forward_trace(layer: LutLayer, x, codes: bool = False, workspace=None
 
 def bspline_kan_forward(layer: BsplineLayer, x, y=None, workspace=None):
     torch = _torch()
-    _require(x, torch.float32, "x")
-    B = x.shape[0]
-    if x.dim() != 2 or x.shape[1] != layer.d:
-        raise LutKanError(f"x must be [B,{layer.d}]")
+    B = _check_io("bspline_kan_forward", layer, x=x, y=y, workspace=workspace)
     if y is None:
         y = torch.empty((B, layer.m), dtype=torch.float32, device=x.device)
-    _require(y, torch.float32, "y")
     ws = _workspace(bspline_forward_workspace_bytes(layer, B), x.device, workspace)
     _check(load_library().bspline_kan_forward(C.byref(layer.c), x.data_ptr(), B, y.data_ptr(), ws.data_ptr(),
                                               ws.numel(), _stream(x.device)))
@@ -531,14 +547,11 @@ def bspline_kan_forward(layer: BsplineLayer, x, y=None, workspace=None):
 def lutkan_model_forward(layers: List[LutLayer], x, y=None, stats=None, workspace=None):
     """Chained forward: layer l's output is layer l+1's input.  stats: optional int64[n_layers,2] CUDA tensor."""
     torch = _torch()
-    _require(x, torch.float32, "x")
-    B = x.shape[0]
+    ends = _check_chain("lutkan_model_forward", layers)
+    B = _check_io("lutkan_model_forward", ends, x=x, y=y, workspace=workspace, stats=stats, n_stats=len(layers))
     arr = (_DevLayer * len(layers))(*[l.c for l in layers])
     if y is None:
         y = torch.empty((B, layers[-1].m), dtype=torch.float32, device=x.device)
-    _require(y, torch.float32, "y")
-    if stats is not None:
-        _require(stats, torch.int64, "stats")
     need = int(load_library().lutkan_model_workspace_bytes(arr, len(layers), B))
     ws = _workspace(need, x.device, workspace)
     _check(load_library().lutkan_model_forward(arr, len(layers), x.data_ptr(), B, y.data_ptr(),
@@ -551,18 +564,15 @@ def lutkan_chain_forward(layers: List[LutLayer], x, y=None, stats=None, hidden=N
     """The chain in one launch (narrow layers, small batches; see lutkan.h).  hidden: optional float32 CUDA tensor of
     sum_{l < n-1} B*m_l elements that receives the activations between the layers."""
     torch = _torch()
-    _require(x, torch.float32, "x")
-    B = x.shape[0]
+    ends = _check_chain("lutkan_chain_forward", layers)
+    B = _check_io("lutkan_chain_forward", ends, x=x, y=y, stats=stats, n_stats=len(layers))
     arr = (_DevLayer * len(layers))(*[l.c for l in layers])
     if y is None:
         y = torch.empty((B, layers[-1].m), dtype=torch.float32, device=x.device)
-    _require(y, torch.float32, "y")
-    if stats is not None:
-        _require(stats, torch.int64, "stats")
     if hidden is not None:
         _require(hidden, torch.float32, "hidden")
-        if hidden.numel() < B * sum(l.m for l in layers[:-1]):
-            raise LutKanError("lutkan_chain_forward: hidden is too small")
+        if hidden.numel() < B * sum(l.m for l in layers[:-1]) or hidden.device != x.device:
+            raise LutKanError("lutkan_chain_forward: hidden is too small or on another device")
     _check(load_library().lutkan_chain_forward(arr, len(layers), x.data_ptr(), B, y.data_ptr(),
                                                hidden.data_ptr() if hidden is not None else None,
                                                stats.data_ptr() if stats is not None else None, _stream(x.device)))
@@ -583,28 +593,35 @@ def lutkan_probe_launch(kind: int, buffer, iters: int) -> float:
 def lutkan_error_stats(y, y_ref, x, t0: float, tK: float, boundary: int, input_domain=None) -> dict:
     """|y - y_ref| statistics on the in-range and the OOB-only samples (Sec. 5.6), reduced on the device.
     input_domain: optional device tensor [d, 2] fp32 of per-input {t0, tK} (layers with one knot vector per input).
-    Returns rows_in, rows_oob, nan_outputs, sum / max / mae per subset and oob_any_frac."""
+    Returns the fields of lutkan_error_summary as a dict: rows_in, rows_oob, nan_in, nan_oob, sum_abs_*, max_abs_*,
+    mae_* and oob_any_frac, all computed on the device."""
     torch = _torch()
     for t, what in ((y, "y"), (y_ref, "y_ref"), (x, "x")):
         _require(t, torch.float32, what)
+    if y.dim() != 2 or x.dim() != 2:
+        raise LutKanError("lutkan_error_stats: y, y_ref must be [B,m] and x [B,d]")
     B, m, d = y.shape[0], y.shape[1], x.shape[1]
     if y_ref.shape != y.shape or x.shape[0] != B:
         raise LutKanError("lutkan_error_stats: y, y_ref must be [B,m] and x [B,d]")
+    if y_ref.device != y.device or x.device != y.device:
+        raise LutKanError("lutkan_error_stats: y, y_ref and x must be on one device")
     if input_domain is not None:
         _require(input_domain, torch.float32, "input_domain")
-        if tuple(input_domain.shape) != (d, 2):
-            raise LutKanError("lutkan_error_stats: input_domain must be [d, 2]")
+        if tuple(input_domain.shape) != (d, 2) or input_domain.device != y.device:
+            raise LutKanError("lutkan_error_stats: input_domain must be [d, 2] on the device of y")
     lib = load_library()
-    out = torch.zeros(7, dtype=torch.float64, device=y.device)            # 3 x uint64 + 4 x double = 56 bytes
+    out = torch.zeros(_ERROR_SUMMARY_WORDS, dtype=torch.float64, device=y.device)
     ws = torch.empty(max(16, lib.lutkan_error_stats_workspace_bytes(B)), dtype=torch.uint8, device=y.device)
     _check(lib.lutkan_error_stats(y.data_ptr(), y_ref.data_ptr(), B, m, x.data_ptr(), d, float(t0), float(tK),
                                   input_domain.data_ptr() if input_domain is not None else None, boundary,
                                   out.data_ptr(), ws.data_ptr(), ws.numel(), _stream(y.device)))
     raw = out.cpu().numpy()
-    rows_in, rows_oob, nans = (int(v) for v in raw[:3].view(np.uint64))
-    s_in, s_oob, mx_in, mx_oob = (float(v) for v in raw[3:])
-    res = dict(rows_in=rows_in, rows_oob=rows_oob, nan_outputs=nans, sum_abs_in=s_in, sum_abs_oob=s_oob,
-               max_abs_in=mx_in, max_abs_oob=mx_oob, oob_any_frac=rows_oob / B)
-    res["mae_in"] = s_in / (rows_in * m) if rows_in else float("nan")
-    res["mae_oob"] = s_oob / (rows_oob * m) if rows_oob else float("nan")
+    res = {name: int(v) for name, v in zip(_ERROR_SUMMARY_COUNTS, raw[:4].view(np.uint64))}
+    res.update({name: float(v) for name, v in zip(_ERROR_SUMMARY_REALS, raw[4:])})
     return res
+
+
+# lutkan_error_summary: four uint64 counters, then seven doubles
+_ERROR_SUMMARY_COUNTS = ("rows_in", "rows_oob", "nan_in", "nan_oob")
+_ERROR_SUMMARY_REALS = ("sum_abs_in", "sum_abs_oob", "max_abs_in", "max_abs_oob", "mae_in", "mae_oob", "oob_any_frac")
+_ERROR_SUMMARY_WORDS = len(_ERROR_SUMMARY_COUNTS) + len(_ERROR_SUMMARY_REALS)

@@ -458,7 +458,8 @@ int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y
 }  // namespace
 
 extern "C" size_t bspline_forward_workspace_bytes(const bspline_dev_layer *layer, int64_t B) {
-  if (!layer || B <= 0 || layer->d < 1 || layer->m < 1 || layer->jt < 4 || layer->n_tiles < 1) return 0;
+  if (!layer || B <= 0 || layer->d < 1 || layer->m < 1 || layer->n_tiles < 1 || layer->coef_blob_bytes < 1) return 0;
+  if (layer->jt < 4 || layer->jt > 128 || (layer->jt & (layer->jt - 1))) return 0;     // as bspline_kan_forward refuses it
   return tiled_workspace_bytes(layer->d, layer->m, layer->jt, layer->n_tiles, B, 32, layer->coef_blob_bytes);
 }
 

@@ -426,6 +426,10 @@ extern "C" int lutkan_artifact_from_arrays(const lutkan_artifact_arrays *in, lut
   const size_t E = (size_t)d * m;
   for (size_t n = 0; n < E * K; ++n) {
     if (!std::isfinite(in->scale[n]) || !std::isfinite(in->y_min[n])) return fail(LUTKAN_EINVAL, "%s: scale / y_min entry %zu is not finite", who, n);
+    // Eq. 11 fixes y_min = 0 for the symmetric scheme; its device table carries no y_min plane, so any other value
+    // would silently drop out of Eq. 10
+    if (scheme == LUTKAN_SYM_INT8 && in->y_min[n] != 0.0f)
+      return fail(LUTKAN_EINVAL, "%s: y_min entry %zu is %g, but the symmetric int8 scheme has y_min = 0 (Eq. 11)", who, n, (double)in->y_min[n]);
     if (half_params && (to_binary16(in->scale[n]).value != in->scale[n] || to_binary16(in->y_min[n]).value != in->y_min[n]))
       return fail(LUTKAN_EINVAL, "%s: scale / y_min entry %zu is not a float16 value", who, n);
   }

@@ -916,7 +916,10 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
 }  // namespace
 
 extern "C" size_t lutkan_forward_workspace_bytes(const lutkan_dev_layer *layer, int64_t B) {
-  if (!layer || B <= 0 || layer->d < 1 || layer->m < 1 || layer->jt < 4 || layer->n_tiles < 1) return 0;
+  // 0 for anything validate_layer would refuse on these fields (a tile width that is not a power of two in 4 .. 64
+  // would divide by zero in the launch planning)
+  if (!layer || B <= 0 || layer->d < 1 || layer->m < 1 || layer->n_tiles < 1 || layer->blob_bytes < 1) return 0;
+  if (layer->jt < 4 || layer->jt > 64 || (layer->jt & (layer->jt - 1))) return 0;
   return tiled_workspace_bytes(layer->d, layer->m, layer->jt, layer->n_tiles, B, lut_record_bytes(layer->value_repr), layer->blob_bytes);
 }
 
@@ -1016,6 +1019,8 @@ extern "C" int lutkan_model_forward(const lutkan_dev_layer *layers, int32_t n_la
   const char *who = "lutkan_model_forward";
   lutkan::plan_clear();
   if (!layers || n_layers < 1 || n_layers > LUTKAN_MAX_LAYERS) return fail(LUTKAN_EINVAL, "%s: need 1..%d layers", who, LUTKAN_MAX_LAYERS);
+  for (int l = 0; l < n_layers; ++l)                       // before anything is computed from a layer's fields
+    if (int rc = validate_layer(&layers[l], who)) return rc;
   for (int l = 0; l + 1 < n_layers; ++l)
     if (layers[l].m != layers[l + 1].d) return fail(LUTKAN_ESHAPE, "%s: layer %d has m=%d but layer %d has d=%d", who, l, layers[l].m, l + 1, layers[l + 1].d);
   if (B < 0) return fail(LUTKAN_EINVAL, "%s: B < 0", who);

@@ -23,16 +23,16 @@ constexpr int kStatRowsPerGroup = kStatWaves * kStatRowsPerWave;
 
 struct Partial {
   double sum_in, sum_oob, max_in, max_oob;
-  unsigned long long rows_in, rows_oob, nan_outputs, pad;
+  unsigned long long rows_in, rows_oob, nan_in, nan_oob;
 };
 static_assert(sizeof(Partial) == 64, "one partial record is 64 bytes");
 
 struct Acc {
   double sum_in, sum_oob, max_in, max_oob;
-  unsigned long long rows_in, rows_oob, nan_outputs;
+  unsigned long long rows_in, rows_oob, nan_in, nan_oob;
 };
 
-__device__ __forceinline__ Acc empty_acc() { return Acc{0.0, 0.0, 0.0, 0.0, 0ull, 0ull, 0ull}; }
+__device__ __forceinline__ Acc empty_acc() { return Acc{0.0, 0.0, 0.0, 0.0, 0ull, 0ull, 0ull, 0ull}; }
 
 __device__ __forceinline__ void merge(Acc &a, const Acc &b) {
   a.sum_in += b.sum_in;
@@ -41,7 +41,8 @@ __device__ __forceinline__ void merge(Acc &a, const Acc &b) {
   a.max_oob = fmax(a.max_oob, b.max_oob);
   a.rows_in += b.rows_in;
   a.rows_oob += b.rows_oob;
-  a.nan_outputs += b.nan_outputs;
+  a.nan_in += b.nan_in;
+  a.nan_oob += b.nan_oob;
 }
 
 __device__ __forceinline__ Acc shuffle_down(const Acc &a, int off) {
@@ -52,7 +53,8 @@ __device__ __forceinline__ Acc shuffle_down(const Acc &a, int off) {
   o.max_oob = __shfl_down(a.max_oob, off, 64);
   o.rows_in = __shfl_down(a.rows_in, off, 64);
   o.rows_oob = __shfl_down(a.rows_oob, off, 64);
-  o.nan_outputs = __shfl_down(a.nan_outputs, off, 64);
+  o.nan_in = __shfl_down(a.nan_in, off, 64);
+  o.nan_oob = __shfl_down(a.nan_oob, off, 64);
   return o;
 }
 
@@ -85,12 +87,13 @@ __global__ __launch_bounds__(kStatWaves * 64) void error_stats_partial_kernel(co
       sum += e;
       mx = fmax(mx, e);
     }
-    acc.nan_outputs += nans;
     if (row_in) {
+      acc.nan_in += nans;
       acc.sum_in += sum;
       acc.max_in = fmax(acc.max_in, mx);
       if (lane == 0) ++acc.rows_in;
     } else {
+      acc.nan_oob += nans;
       acc.sum_oob += sum;
       acc.max_oob = fmax(acc.max_oob, mx);
       if (lane == 0) ++acc.rows_oob;
@@ -104,19 +107,26 @@ __global__ __launch_bounds__(kStatWaves * 64) void error_stats_partial_kernel(co
     for (int w = 1; w < kStatWaves; ++w) merge(t, s_acc[w]);
     Partial p;
     p.sum_in = t.sum_in; p.sum_oob = t.sum_oob; p.max_in = t.max_in; p.max_oob = t.max_oob;
-    p.rows_in = t.rows_in; p.rows_oob = t.rows_oob; p.nan_outputs = t.nan_outputs; p.pad = 0;
+    p.rows_in = t.rows_in; p.rows_oob = t.rows_oob; p.nan_in = t.nan_in; p.nan_oob = t.nan_oob;
     partials[blockIdx.x] = p;
   }
 }
 
-__global__ __launch_bounds__(256) void error_stats_final_kernel(const Partial *partials, int64_t n, lutkan_error_summary *out) {
+// MAE of a subset (Sec. 6.5 over the subsets of Sec. 5.6): the mean of its differences that are not NaN.
+__device__ __forceinline__ double subset_mae(double sum_abs, unsigned long long rows, int m, unsigned long long nans) {
+  const unsigned long long counted = rows * (unsigned long long)m - nans;
+  return counted ? sum_abs / (double)counted : __builtin_nan("");
+}
+
+__global__ __launch_bounds__(256) void error_stats_final_kernel(const Partial *partials, int64_t n, int64_t B, int m,
+                                                                lutkan_error_summary *out) {
   __shared__ Acc s_acc[256];
   Acc acc = empty_acc();
   for (int64_t q = threadIdx.x; q < n; q += 256) {      // fixed assignment of partials to threads
     const Partial p = partials[q];
     Acc t = empty_acc();
     t.sum_in = p.sum_in; t.sum_oob = p.sum_oob; t.max_in = p.max_in; t.max_oob = p.max_oob;
-    t.rows_in = p.rows_in; t.rows_oob = p.rows_oob; t.nan_outputs = p.nan_outputs;
+    t.rows_in = p.rows_in; t.rows_oob = p.rows_oob; t.nan_in = p.nan_in; t.nan_oob = p.nan_oob;
     merge(acc, t);
   }
   s_acc[threadIdx.x] = acc;
@@ -127,9 +137,12 @@ __global__ __launch_bounds__(256) void error_stats_final_kernel(const Partial *p
   }
   if (threadIdx.x == 0) {
     const Acc t = s_acc[0];
-    out->rows_in = t.rows_in; out->rows_oob = t.rows_oob; out->nan_outputs = t.nan_outputs;
+    out->rows_in = t.rows_in; out->rows_oob = t.rows_oob; out->nan_in = t.nan_in; out->nan_oob = t.nan_oob;
     out->sum_abs_in = t.sum_in; out->sum_abs_oob = t.sum_oob;
     out->max_abs_in = t.max_in; out->max_abs_oob = t.max_oob;
+    out->mae_in = subset_mae(t.sum_in, t.rows_in, m, t.nan_in);
+    out->mae_oob = subset_mae(t.sum_oob, t.rows_oob, m, t.nan_oob);
+    out->oob_any_frac = (double)t.rows_oob / (double)B;
   }
 }
 
@@ -159,7 +172,7 @@ extern "C" int lutkan_error_stats(const float *y, const float *y_ref, int64_t B,
   Partial *partials = static_cast<Partial *>(workspace);
   hipLaunchKernelGGL(error_stats_partial_kernel, dim3((unsigned)groups), dim3(kStatWaves * 64), 0, s, y, y_ref, x, B, m, d, t0, tK,
                      input_domain, boundary == LUTKAN_CLOSED ? 1 : 0, partials);
-  hipLaunchKernelGGL(error_stats_final_kernel, dim3(1), dim3(256), 0, s, partials, groups, out);
+  hipLaunchKernelGGL(error_stats_final_kernel, dim3(1), dim3(256), 0, s, partials, groups, B, (int)m, out);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(LUTKAN_EHIP, "%s: %s", who, hipGetErrorString(e));
   return LUTKAN_OK;

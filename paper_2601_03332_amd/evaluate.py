@@ -10,9 +10,6 @@ spline_component, inputs N(0,1) clipped to the knot domain) it prints
     of rows with any out-of-domain input, error on those rows, error on the in-range rows.
 With --sweep it also prints, for the 256 -> 256 layer of the L x scheme sweep (G = 8, batch 16384), the error of
 the LUT layer against the B-spline layer and the time of both per point: the latency is flat in L (Sec. 7.2).
-With --cold-start it times the tabular chain 78 -> 16 -> 2 (L = 64 asymmetric uint8, batch 65536) twice, as the
-latency metrics of Sec. 6.5 distinguish: steady state (tables resident on the GPU) and cold start (every iteration
-reads the NPZ artifacts, rebuilds the device tables and uploads them before the forward).
 With --variants it times every option combination (scheme x value_repr x parameter dtype) on the widest workload.
 With --batches it times LUT and B-spline layers of five shapes from 1 to 65536 rows (which kernel AUTO picks changes
 along the way: one-launch chain, gather with split inputs, tiled).
@@ -33,7 +30,6 @@ def main():
     ap.add_argument("--seeds", type=int, default=5)
     ap.add_argument("--batch", type=int, default=4096)
     ap.add_argument("--sweep", action="store_true", help="also run the 256->256 L x scheme sweep with timings")
-    ap.add_argument("--cold-start", action="store_true", help="also time steady-state vs cold-start latency of the 78->16->2 chain")
     ap.add_argument("--variants", action="store_true", help="also time every option combination on the 1024 -> 1024 layer at batch 32768")
     ap.add_argument("--batches", action="store_true", help="also time LUT and B-spline layers of several shapes from 1 to 65536 rows")
     ap.add_argument("--latency", action="store_true", help="also time narrow chains at small batches: per-layer launches vs the fused chain")
@@ -109,47 +105,6 @@ def main():
                 st = lk.lutkan_error_stats(y_lut, y_ref, x, float(art.knots[0]), float(art.knots[-1]), s.boundary)
                 print(f"{L:>4} {name:>10} {st['mae_in']:>12.6f} {st['max_abs_in']:>12.6f} {t_lut:>9.3f} {t_spl:>12.3f} "
                       f"{B * s.d * s.m / t_lut / 1e6:>15.1f} {art.info.table_bytes / 2**20:>10.1f}")
-
-
-    if args.cold_start:
-        import os
-        import tempfile
-        import time
-
-        w = cfg2()
-        arts = [lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, s.boundary, s.oob) for s in w.layers]
-        folder = tempfile.mkdtemp(prefix="lutkan_artifacts_")
-        paths = []
-        for n, a in enumerate(arts):
-            paths.append(os.path.join(folder, f"layer{n}.npz"))
-            a.save(paths[-1])
-        x = torch.from_numpy(w.x).to(dev)
-        B = x.shape[0]
-        layers = [a.to_device(dev) for a in arts]
-        ws = torch.empty(lk.lutkan_model_workspace_bytes(layers, B), dtype=torch.uint8, device=dev)
-        y = torch.empty((B, layers[-1].m), dtype=torch.float32, device=dev)
-
-        def steady():
-            lk.lutkan_model_forward(layers, x, y, workspace=ws)
-            torch.cuda.synchronize()
-
-        def cold():
-            fresh = [lk.lutkan_artifact_load(p).to_device(dev) for p in paths]
-            lk.lutkan_model_forward(fresh, x, y, workspace=ws)
-            torch.cuda.synchronize()
-
-        def wall(fn, n):
-            fn()
-            t0 = time.perf_counter()
-            for _ in range(n):
-                fn()
-            return (time.perf_counter() - t0) / n * 1e3
-
-        t_steady, t_cold = wall(steady, 50), wall(cold, 10)
-        size = sum(os.path.getsize(p) for p in paths)
-        print()
-        print(f"78 -> 16 -> 2, L = 64 asymmetric uint8, batch {B}: steady state {t_steady:.3f} ms/iter "
-              f"({t_steady / B * 1e6:.3f} ns/sample), cold start {t_cold:.3f} ms/iter (NPZ artifacts: {size} bytes)")
 
     if args.variants:
         from lutkan_inputs import cfg4, draw_edge_scales

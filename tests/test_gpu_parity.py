@@ -242,10 +242,7 @@ def test_one_knot_vector_per_input(case):
     dom = torch.from_numpy(np.ascontiguousarray(art.knots[:, [0, -1]])).to(DEV)
     got = lk.lutkan_error_stats(y_lut, yb, xg, 0.0, 0.0, boundary, input_domain=dom)
     want = oracle.error_stats(y_lut.cpu().numpy(), yb.cpu().numpy(), w.x, art.knots[:, 0], art.knots[:, -1], boundary)
-    for key in ("rows_in", "rows_oob", "nan_outputs", "max_abs_in", "max_abs_oob"):
-        assert got[key] == want[key], key
-    for key in ("sum_abs_in", "sum_abs_oob"):
-        assert abs(got[key] - want[key]) <= 1e-12 * abs(want[key]) + 1e-300, key
+    _same_error_summary(got, want)
 
 
 def test_per_input_layer_without_its_knot_table_is_refused():
@@ -453,34 +450,56 @@ def test_cfg3_sweep_point_reduced_batch(L, scheme):
     _check_layer(w.layers[0], w.x, lk.ALGO_AUTO, what=w.name)
 
 
+@pytest.mark.parametrize("L", [16, 32, 64, 128])
+@pytest.mark.parametrize("scheme", [SYM_INT8, ASYM_UINT8])
+def test_cfg3_sweep_point_full_batch_every_row(L, scheme):
+    """Every point of the L x scheme sweep at its stated batch (16384 rows, the launch plan a user gets): k, l0, In(x),
+    w and the counters bit-exact and every output within the tolerance, on all rows."""
+    w = cfg3(L=L, scheme=scheme)
+    assert w.x.shape[0] == 16384
+    _check_layer(w.layers[0], w.x, lk.ALGO_AUTO, what=w.name)
+
+
 def _sampled_rows_check(w, n_rows, what, seed=0):
-    """Full-size launch (the configuration the benchmark times); the oracle recomputes a sample of rows."""
+    """Full-size launch (the configuration the benchmark times).  The oracle recomputes a seeded random sample of at
+    least n_rows rows (plus the first and the last one): k, l0, In(x), w bit-exact and the outputs of both the traced
+    and the plain launch within the tolerance on them; the OOB counters are exact over ALL rows."""
     s = w.layers[0]
     art, ora = _compile_both(s)
     layer = _device_layer(art, s)
     xg = torch.from_numpy(w.x).to(DEV)
-    _say(f"case {what} full size B={w.x.shape[0]} sampled rows={n_rows}")
+    B = w.x.shape[0]
+    rng = np.random.Generator(np.random.PCG64(seed))
+    rows = np.unique(np.concatenate([rng.choice(B, size=min(B, n_rows), replace=False), [0, B - 1]]))
+    _say(f"case {what} full size B={B} sampled rows={rows.size}")
     stats = torch.zeros(2, dtype=torch.int64, device=DEV)
     y = lk.lutkan_forward(layer, xg, stats=stats)
+    plan = lk.lutkan_last_plan()
+    y_t, k, l0, inside, wgt, _ = lk.lutkan_forward_trace(layer, xg)
+    assert lk.lutkan_last_plan() == plan.replace("oob; ", "")           # the traced launch is the plain launch's plan
     torch.cuda.synchronize()
-    rng = np.random.Generator(np.random.PCG64(seed))
-    B = w.x.shape[0]
-    rows = np.unique(np.concatenate([rng.integers(0, B, size=n_rows), [0, B - 1]]))
-    ref = oracle.lut_forward(ora, s.boundary, s.oob, w.x[rows])
-    _assert_close(y[torch.from_numpy(rows).to(DEV)].cpu().numpy(), ref, what)
-    T = ora.knots
-    inside = (w.x >= T[0]) & (w.x <= T[-1]) if s.boundary == CLOSED else (w.x >= T[0]) & (w.x < T[-1])
-    st = stats.cpu().numpy()
-    assert int(st[0]) == int((~inside).sum()) and int(st[1]) == int((~inside).any(axis=1).sum())
-
-
-def test_cfg5_full_batch_chain_sampled_rows():
-    """cfg5 at its full batch (131072 rows, the launch shapes a user gets): every layer against the oracle on a
-    sample of rows, fed with the GPU's own activations of the previous layer."""
-    w = cfg5(boundary=HALF_OPEN, oob=ZERO_SPLINE)
-    B = w.x.shape[0]
-    rows = np.unique(np.random.Generator(np.random.PCG64(9)).integers(0, B, size=3000))
     rows_t = torch.from_numpy(rows).to(DEV)
+    ref = oracle.lut_forward(ora, s.boundary, s.oob, w.x[rows], trace=True)
+    np.testing.assert_array_equal(k[rows_t].cpu().numpy(), ref.k)
+    np.testing.assert_array_equal(l0[rows_t].cpu().numpy(), ref.l0)
+    np.testing.assert_array_equal(inside[rows_t].cpu().numpy(), ref.inside)
+    np.testing.assert_array_equal(wgt[rows_t].cpu().numpy().view(np.uint32), ref.w.view(np.uint32))
+    _assert_close(y[rows_t].cpu().numpy(), ref, what)
+    _assert_close(y_t[rows_t].cpu().numpy(), ref, what + " (traced launch)")
+    T = ora.knots
+    inside_all = (w.x >= T[0]) & (w.x <= T[-1]) if s.boundary == CLOSED else (w.x >= T[0]) & (w.x < T[-1])
+    st = stats.cpu().numpy()
+    assert int(st[0]) == int((~inside_all).sum()) and int(st[1]) == int((~inside_all).any(axis=1).sum())
+
+
+@pytest.mark.parametrize("boundary,oob", [(HALF_OPEN, CLIP_X), (HALF_OPEN, ZERO_SPLINE), (CLOSED, CLIP_X), (CLOSED, ZERO_SPLINE)])
+def test_cfg5_full_batch_chain_every_row(boundary, oob):
+    """cfg5 at its full batch (131072 rows, the launch shapes a user gets) under each of the four boundary x policy
+    contracts: every layer against the oracle on ALL rows, fed with the GPU's own activations of the previous layer;
+    the per-layer OOB counters exact; the chained entry point bit-identical to the layer-by-layer calls."""
+    w = cfg5(boundary=boundary, oob=oob)
+    B = w.x.shape[0]
+    assert B == 131072
     layers, oras = [], []
     for s in w.layers:
         art, ora = _compile_both(s)
@@ -490,23 +509,28 @@ def test_cfg5_full_batch_chain_sampled_rows():
     stats = torch.zeros((len(layers), 2), dtype=torch.int64, device=DEV)
     y_model = lk.lutkan_model_forward(layers, cur, stats=stats)
     for li, (s, layer, ora) in enumerate(zip(w.layers, layers, oras)):
-        _say(f"case cfg5 full batch layer {li}: {s.d}->{s.m} B={B}")
+        _say(f"case cfg5 b{boundary} o{oob} full batch layer {li}: {s.d}->{s.m} B={B}")
         nxt = lk.lutkan_forward(layer, cur)
-        ref = oracle.lut_forward(ora, s.boundary, s.oob, cur[rows_t].cpu().numpy())
-        _assert_close(nxt[rows_t].cpu().numpy(), ref, f"cfg5 full layer {li}")
+        ref = oracle.lut_forward(ora, s.boundary, s.oob, cur.cpu().numpy())
+        _assert_close(nxt.cpu().numpy(), ref, f"cfg5 full layer {li}")
+        st = stats[li].cpu().numpy()
+        assert (int(st[0]), int(st[1])) == (ref.oob_count, ref.oob_any_rows)
         cur = nxt
     assert torch.equal(cur, y_model)
 
 
-def test_cfg3_full_batch_sampled_rows():
-    _sampled_rows_check(cfg3(L=64, scheme=SYM_INT8), 512, "cfg3 L64 sym")
+@pytest.mark.parametrize("B", [1, 7, 64, 100, 256, 4096])
+def test_cfg4_wide_layer_every_row(B):
+    """The widest workload at its batches of 256 and 4096 rows, and at batches of a few rows, where AUTO runs the
+    gather kernel with the inputs split into chunks (partial sums added in chunk order): all rows against the oracle."""
+    w = cfg4(B=B)
+    _check_layer(w.layers[0], w.x, lk.ALGO_AUTO, what=f"cfg4 B={B}")
 
 
-@pytest.mark.parametrize("B", [1, 7, 64, 100, 256, 4096, 32768])
-def test_cfg4_wide_layer_full_size_sampled_rows(B):
-    """The widest workload at its three batches, and at batches of a few rows, where AUTO runs the gather kernel
-    with the inputs split into chunks (partial sums added in chunk order)."""
-    _sampled_rows_check(cfg4(B=B), 96, f"cfg4 B={B}")
+def test_cfg4_wide_layer_largest_batch_sampled_rows():
+    """The configuration the benchmark times (1024 -> 1024 at 32768 rows): 4096 random rows against the oracle, the
+    OOB counters exact over all rows."""
+    _sampled_rows_check(cfg4(B=32768), 4096, "cfg4 B=32768")
 
 
 @pytest.mark.parametrize("B", [1, 5, 16, 17])
@@ -524,7 +548,7 @@ def test_two_million_rows_sampled():
     """A batch far beyond the workloads (2^21 rows, 2048 row tiles, 1 GiB of lookup records): 64-bit row indexing in
     every kernel, checked on sampled rows and through the exact OOB counters."""
     w = random_layer(351, 64, 48, 6, 32, ASYM_UINT8, HALF_OPEN, ZERO_SPLINE, 1 << 21)
-    _sampled_rows_check(w, 400, "2^21 rows, 64 -> 48")
+    _sampled_rows_check(w, 4096, "2^21 rows, 64 -> 48")
 
 
 # ---------------------------------------------------------------- B-spline baseline
@@ -562,15 +586,14 @@ def test_bspline_special_inputs():
             _check_bspline(s, x, lk.ALGO_GATHER, "special")
 
 
-def test_bspline_cfg4_sampled_rows():
+def test_bspline_cfg4_every_row():
     w = cfg4(B=4096)
     s = w.layers[0]
     art = lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, s.boundary, s.oob)
     layer = art.bspline_to_device(DEV)
     y = lk.bspline_kan_forward(layer, torch.from_numpy(w.x).to(DEV))
-    rows = np.arange(0, 4096, 64)
-    ref = oracle.bspline_forward(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.boundary, s.oob, w.x[rows])
-    _assert_close(y[torch.from_numpy(rows).to(DEV)].cpu().numpy(), ref, "bspline cfg4")
+    ref = oracle.bspline_forward(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.boundary, s.oob, w.x)
+    _assert_close(y.cpu().numpy(), ref, "bspline cfg4, all 4096 rows")
 
 
 # ---------------------------------------------------------------- value_repr = spline_component (Eq. 2, Sec. 4.3 B)
@@ -644,13 +667,45 @@ def test_error_stats_kernel(case):
     got = lk.lutkan_error_stats(torch.from_numpy(y).to(DEV), torch.from_numpy(r).to(DEV), torch.from_numpy(x).to(DEV),
                                 -1.0, 1.0, boundary)
     want = oracle.error_stats(y, r, x, -1.0, 1.0, boundary)
-    for key in ("rows_in", "rows_oob", "nan_outputs", "max_abs_in", "max_abs_oob", "oob_any_frac"):
+    _same_error_summary(got, want)
+
+
+def _same_error_summary(got, want):
+    """Every field of lutkan_error_summary against the oracle's: counts, maxima and the OOB fraction exact, the fp64
+    sums and means up to the order of summation."""
+    assert set(got) == set(want)
+    for key in ("rows_in", "rows_oob", "nan_in", "nan_oob", "max_abs_in", "max_abs_oob", "oob_any_frac"):
         assert got[key] == want[key], key
     for key in ("sum_abs_in", "sum_abs_oob", "mae_in", "mae_oob"):
         if np.isnan(want[key]):
             assert np.isnan(got[key]), key
         else:
             assert abs(got[key] - want[key]) <= 1e-12 * abs(want[key]) + 1e-300, key
+
+
+def test_error_stats_mean_leaves_nan_outputs_out_of_the_count():
+    """NaN outputs inside both subsets (several per subset, so that rows * m and the number of differences that exist
+    differ visibly): the device divides each sum by the latter, as the oracle does; a subset of NaN outputs only has
+    no mean."""
+    rng = np.random.Generator(np.random.PCG64(720))
+    B, d, m = 500, 6, 10
+    x = rng.uniform(-1.1, 1.1, size=(B, d)).astype(np.float32)
+    y = rng.normal(size=(B, m)).astype(np.float32)
+    r = (y + rng.normal(scale=1e-2, size=(B, m))).astype(np.float32)
+    y.reshape(-1)[rng.choice(B * m, size=B * m // 5, replace=False)] = np.nan
+    _say(f"case stats with NaN outputs in both subsets B={B} d={d} m={m}")
+    got = lk.lutkan_error_stats(torch.from_numpy(y).to(DEV), torch.from_numpy(r).to(DEV), torch.from_numpy(x).to(DEV),
+                                -1.0, 1.0, CLOSED)
+    want = oracle.error_stats(y, r, x, -1.0, 1.0, CLOSED)
+    assert want["nan_in"] > 50 and want["nan_oob"] > 50 and want["rows_in"] > 50 and want["rows_oob"] > 50
+    _same_error_summary(got, want)
+    assert abs(got["mae_in"] - got["sum_abs_in"] / (got["rows_in"] * m - got["nan_in"])) <= 1e-15
+    assert got["mae_in"] > 1.1 * got["sum_abs_in"] / (got["rows_in"] * m)          # the other denominator is 20 % larger
+    y[:] = np.nan
+    got = lk.lutkan_error_stats(torch.from_numpy(y).to(DEV), torch.from_numpy(r).to(DEV), torch.from_numpy(x).to(DEV),
+                                -1.0, 1.0, CLOSED)
+    _same_error_summary(got, oracle.error_stats(y, r, x, -1.0, 1.0, CLOSED))
+    assert np.isnan(got["mae_in"]) and np.isnan(got["mae_oob"]) and got["nan_in"] == got["rows_in"] * m
 
 
 def test_error_stats_of_a_lut_layer_against_its_spline_layer():
@@ -932,15 +987,33 @@ def test_last_plan_reports_what_auto_dispatch_launched():
     layer = _device_layer(art, s)
     xg = torch.from_numpy(w.x).to(DEV)
     _say("case last plan: cfg4 at 1, 64 and 4096 rows")
+    import re
+
+    def tiled_groups(plan, B, jt, n_tiles):
+        """Work-groups of the tiled launch named in `plan`, and its chunk count: the launch shape comes out of a
+        fitted cost model, so only its invariants are asserted -- a legal row-step count, whole rounds' worth of
+        work-groups, and a summing pass exactly when the inputs were split."""
+        mt = re.search(r"tiled np=(\d+) split=(\d+); ", plan)
+        assert mt, plan
+        np_, split = int(mt.group(1)), int(mt.group(2))
+        rows_per_wave = (64 // (jt // 4)) * np_
+        assert np_ in (1, 2, 4, 8, 16) and rows_per_wave <= 64 and 1 <= split <= 128
+        assert plan.endswith("sum; ") == (split > 1), plan
+        return -(-B // (16 * rows_per_wave)) * n_tiles * split, split
+
     lk.lutkan_forward(layer, xg[:1])
-    assert lk.lutkan_last_plan() == "locate; gather split=64; sum; "          # a few rows: only the touched table rows
+    plan = lk.lutkan_last_plan()                                                # a few rows: only the touched table rows,
+    assert re.fullmatch(r"locate; gather split=(\d+); sum; ", plan), plan      # the inputs split over the GPU
     lk.lutkan_forward(layer, xg[:64])
     assert lk.lutkan_last_plan().startswith("locate; gather split=")
     lk.lutkan_forward(layer, xg)
-    assert lk.lutkan_last_plan() == "locate; tiled np=16 split=4; sum; "      # 4 row tiles x 16 column tiles x 4 chunks = 256 work-groups
+    plan = lk.lutkan_last_plan()
+    assert plan.startswith("locate; tiled np="), plan
+    groups, _ = tiled_groups(plan, 4096, art.info.jt, art.info.n_tiles)
+    assert groups >= 256, plan                                                  # at least one work-group per compute unit
     stats = torch.zeros(2, dtype=torch.int64, device=DEV)
     lk.lutkan_forward(layer, xg, stats=stats)
-    assert lk.lutkan_last_plan() == "locate; oob; tiled np=16 split=4; sum; "
+    assert lk.lutkan_last_plan() == plan.replace("locate; ", "locate; oob; ")   # the counters add one launch, nothing else
     lk.bspline_kan_forward(art.bspline_to_device(DEV), xg)
     assert lk.lutkan_last_plan().startswith("bspline_locate; bspline_tiled np=")
     _say("case last plan: cfg2 at 300, 5000 and 20000 rows")
@@ -964,26 +1037,27 @@ def test_last_plan_reports_what_auto_dispatch_launched():
     torch.cuda.synchronize()
 
 
-def test_measurement_probes_report_their_work_and_plausible_rates():
-    """The peak-rate probes behind the roofline terms: each kind launches, reports the work of one launch, and the
-    rate it implies lies in the range the hardware can have (a wrong work count or a kernel the optimiser emptied
-    would not)."""
+def test_measurement_probes_report_their_work():
+    """The peak-rate probes behind the roofline terms: each kind launches and reports the work of one launch (the
+    count the rate is computed from), which follows from the launch shape and the iteration count; the rate itself is
+    only required to be a finite positive number here -- its value belongs to the benchmark's record, not to a test."""
     buf = torch.zeros((1 << 30) // 4 + 4, dtype=torch.float32, device=DEV)
-    ranges = {lk.PROBE_VALU_FMA: (2048, 3e13, 1.7e14),      # flop/s: between 30 and 170 TFLOP/s
-              lk.PROBE_VALU_MIX: (2048, 1.5e13, 8e13),      # lane-instructions/s
-              lk.PROBE_LDS_READ: (512, 4e13, 3e14),         # bytes/s
-              lk.PROBE_L2_READ: (4, 5e12, 8e13),
-              lk.PROBE_HBM_READ: (2, 2e12, 8.5e12)}
-    for kind, (iters, lo, hi) in ranges.items():
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    kinds = {lk.PROBE_VALU_FMA: 2048, lk.PROBE_VALU_MIX: 2048, lk.PROBE_LDS_READ: 512, lk.PROBE_L2_READ: 4, lk.PROBE_HBM_READ: 2}
+    for kind, iters in kinds.items():
         lk.lutkan_probe_launch(kind, buf, iters)             # warm-up
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         work = lk.lutkan_probe_launch(kind, buf, iters)
         e1.record()
         torch.cuda.synchronize()
+        half = lk.lutkan_probe_launch(kind, buf, iters // 2)
+        torch.cuda.synchronize()
         rate = work / (e0.elapsed_time(e1) * 1e-3)
-        _say(f"probe kind {kind}: {rate:.3g} per second")
-        assert lo < rate < hi, (kind, rate)
+        _say(f"probe kind {kind}: work {work:.4g}, {rate:.3g} per second on {cus} compute units")
+        assert work > 0 and work == 2 * half                 # proportional to the iterations inside the kernel
+        assert np.isfinite(rate) and rate > 0
+    assert lk.lutkan_probe_launch(lk.PROBE_HBM_READ, buf, 2) == 2.0 * (buf.numel() * 4 - 16)      # the buffer, once per pass
     with pytest.raises(lk.LutKanError):
         lk.lutkan_probe_launch(99, buf, 1)
     with pytest.raises(lk.LutKanError):

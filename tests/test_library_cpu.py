@@ -180,12 +180,13 @@ def test_forward_argument_validation_happens_before_any_launch():
     dl.knots[2] = dl.knots[1]
     assert lib.lutkan_forward(C.byref(dl), 16, 4, 32, None, 256, 1 << 20, None) == -1
     two = (binding._DevLayer * 2)(dl, dl)
-    assert lib.lutkan_model_forward(two, 2, 16, 4, 32, None, 256, 1 << 20, None) == -2     # m of layer 0 != d of layer 1
+    assert lib.lutkan_model_forward(two, 2, 16, 4, 32, None, 256, 1 << 20, None) == -1     # every layer is validated first
     # the fused chain: same checks, plus the shapes it cannot hold
     assert lib.lutkan_chain_forward(two, 2, 16, 4, 32, None, None, None) == -1             # the knots are still broken
     dl.knots[2] = np.float32(0.5 * (dl.knots[1] + dl.knots[3]))
     two, one = (binding._DevLayer * 2)(dl, dl), (binding._DevLayer * 1)(dl)
     assert lib.lutkan_chain_forward(two, 2, 16, 4, 32, None, None, None) == -2
+    assert lib.lutkan_model_forward(two, 2, 16, 4, 32, None, 256, 1 << 20, None) == -2     # m of layer 0 != d of layer 1
     assert lib.lutkan_chain_forward(one, 1, 16, 0, 32, None, None, None) == 0               # B == 0: no-op
     assert lib.lutkan_chain_forward(one, 1, None, 4, 32, None, None, None) == -1
     assert lib.lutkan_chain_forward(one, 1, 16, 4, 16, None, None, None) == -1              # x and y alias
@@ -211,6 +212,97 @@ def test_forward_argument_validation_happens_before_any_launch():
     wl.table = 4096
     assert lib.lutkan_chain_forward((binding._DevLayer * 1)(wl), 1, 16, 4, 32, None, None, None) == -5
     assert "at most 64 columns" in lk.lutkan_last_error()
+
+
+def test_binding_refuses_tensors_of_the_wrong_shape_dtype_or_device():
+    """The kernels index x as [B, d] and y as [B, m] on trust, so the binding checks every tensor before a pointer
+    reaches the library.  No GPU is needed to see the refusals: the layer below is a host-side stand-in."""
+    import torch
+    s = cfg2(B=4).layers[0]                                     # 78 -> 16
+    art, _ = _both(s)
+    layer = object.__new__(lk.LutLayer)
+    layer.c = binding._DevLayer()
+    lk.load_library().lutkan_dev_layer_init(art._h, C.byref(layer.c))
+    layer.d, layer.m, layer.device = s.d, s.m, torch.device("cpu")
+    spline = object.__new__(lk.BsplineLayer)
+    spline.c = binding._SplineDevLayer()
+    lk.load_library().bspline_dev_layer_init(art._h, C.byref(spline.c))
+    spline.d, spline.m, spline.device = s.d, s.m, torch.device("cpu")
+    x = torch.zeros((8, s.d))
+    y = torch.zeros((8, s.m))
+    ws = torch.zeros(1 << 16, dtype=torch.uint8)
+    bad_calls = [
+        lambda: lk.lutkan_forward(layer, torch.zeros((8, s.d + 1))),                       # wrong width
+        lambda: lk.lutkan_forward(layer, torch.zeros(8 * s.d)),                            # not two-dimensional
+        lambda: lk.lutkan_forward(layer, x.double()),                                       # wrong dtype
+        lambda: lk.lutkan_forward(layer, x, torch.zeros((7, s.m))),                        # y too short
+        lambda: lk.lutkan_forward(layer, x, torch.zeros((8, s.m - 1))),
+        lambda: lk.lutkan_forward(layer, x, y, stats=torch.zeros(3, dtype=torch.int64)),
+        lambda: lk.lutkan_forward(layer, x, y, workspace=ws.float()),
+        lambda: lk.lutkan_forward(layer, x, y),                                             # right shapes, but not on a GPU
+        lambda: lk.lutkan_forward_static_scratch(layer, x, None),
+        lambda: lk.lutkan_forward_static_scratch(layer, x, torch.zeros((9, s.m))),
+        lambda: lk.lutkan_forward_trace(layer, torch.zeros((8, 3))),
+        lambda: lk.lutkan_forward_locate(layer, torch.zeros((8, s.m)), ws),
+        lambda: lk.lutkan_forward_edges(layer, 9, y, ws),                                  # B does not match y
+        lambda: lk.lutkan_forward_edges(layer, 8, torch.zeros((8, s.d)), ws),
+        lambda: lk.bspline_kan_forward(spline, torch.zeros((8, s.d - 1))),
+        lambda: lk.bspline_kan_forward(spline, x, torch.zeros((8, s.m + 1))),
+        lambda: lk.bspline_forward_locate(spline, torch.zeros((s.d, 8)), ws),
+        lambda: lk.bspline_forward_edges(spline, 4, y, ws),
+        lambda: lk.lutkan_model_forward([layer, layer], x),                                # 16 outputs feed 78 inputs
+        lambda: lk.lutkan_model_forward([], x),
+        lambda: lk.lutkan_model_forward([layer], torch.zeros((8, 5))),
+        lambda: lk.lutkan_model_forward([layer], x, torch.zeros((8, s.m)), stats=torch.zeros(4, dtype=torch.int64)),
+        lambda: lk.lutkan_chain_forward([layer], torch.zeros((8, s.d, 1))),
+        lambda: lk.lutkan_chain_forward([layer, layer], x),
+        lambda: lk.lutkan_error_stats(y, torch.zeros((8, s.m + 1)), x, -1.0, 1.0, CLOSED),
+        lambda: lk.lutkan_error_stats(y, y, torch.zeros((7, s.d)), -1.0, 1.0, CLOSED),
+    ]
+    for n, call in enumerate(bad_calls):
+        with pytest.raises(lk.LutKanError):
+            call()
+            pytest.fail(f"call {n} was not refused")
+    assert lk.lutkan_last_plan() == ""                          # nothing reached a launch
+
+
+def test_stored_symmetric_artifact_with_an_offset_is_refused():
+    """Eq. 11 fixes y_min = 0 for symmetric int8 and the device table of that scheme carries no y_min plane: stored
+    arrays that say otherwise are refused instead of silently losing the offset."""
+    s = cfg1().layers[0]
+    art, _ = _both(s)
+    ok = lk.lutkan_artifact_from_arrays(s.d, s.m, art.knots, art.q, art.scale, art.y_min, s.boundary, s.oob)
+    assert np.array_equal(ok.table, art.table)
+    shifted = art.y_min.copy()
+    shifted[5, 2] = np.float32(1e-3)
+    with pytest.raises(lk.LutKanError) as e:
+        lk.lutkan_artifact_from_arrays(s.d, s.m, art.knots, art.q, art.scale, shifted, s.boundary, s.oob)
+    assert str(e.value).startswith("[-1]") and "Eq. 11" in str(e.value)
+    minus_zero = np.full_like(art.y_min, -0.0)                  # -0 is still zero
+    lk.lutkan_artifact_from_arrays(s.d, s.m, art.knots, art.q, art.scale, minus_zero, s.boundary, s.oob)
+
+
+def test_workspace_queries_return_zero_for_tile_widths_no_kernel_has():
+    """The size queries run on structs nobody has validated yet: a tile width outside what the kernels exist for gives
+    0 (and the forward call then refuses the layer), never a division by zero in the launch planning."""
+    s = cfg1().layers[0]
+    art, _ = _both(s)
+    lib = lk.load_library()
+    dl = binding._DevLayer()
+    lib.lutkan_dev_layer_init(art._h, C.byref(dl))
+    bl = binding._SplineDevLayer()
+    lib.bspline_dev_layer_init(art._h, C.byref(bl))
+    assert lib.lutkan_forward_workspace_bytes(C.byref(dl), 100) > 0 and lib.bspline_forward_workspace_bytes(C.byref(bl), 100) > 0
+    for jt in (0, 3, 6, 128, 256, 260, 1024, 1 << 20):
+        dl.jt = jt
+        assert lib.lutkan_forward_workspace_bytes(C.byref(dl), 100) == 0, jt
+        assert lib.lutkan_model_workspace_bytes((binding._DevLayer * 1)(dl), 1, 100) == 0
+        dl.table = 4096
+        assert lib.lutkan_model_forward((binding._DevLayer * 1)(dl), 1, 16, 100, 32, None, 256, 1 << 30, None) == -1
+        assert "jt" in lk.lutkan_last_error()
+    for jt in (0, 3, 12, 256, 512, 1 << 20):
+        bl.jt = jt
+        assert lib.bspline_forward_workspace_bytes(C.byref(bl), 100) == 0, jt
 
 
 def test_spline_component_tables_carry_the_base_row_and_folded_gains():
