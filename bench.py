@@ -1,20 +1,23 @@
 #!/usr/bin/env python3
 """Benchmark of the LUT-KAN layer forward on one MI355X.
 
-One "step" is one pass of the whole hot path (locate kernel + edge kernel, i.e. lutkan_forward) over one batch of
-seeded synthetic input that is already resident in HBM.  The workload is the largest single-GPU configuration:
-one dense layer 1024 -> 1024, G = 10 segments on [-1,1], cubic splines with N(0,1) coefficients compiled to
-L = 64 symmetric int8 tables, batch 32768 rows of x ~ N(0, 0.5) clipped to [-1.2, 1.2], closed + clip_x.
+One "step" is one pass of the whole hot path (lutkan_model_forward: per layer the locate kernel, the edge kernel and,
+where the inputs were split, the summing pass) over one batch of seeded synthetic input that is already resident in
+HBM.  The default workload is the largest single-GPU configuration: one dense layer 1024 -> 1024, G = 10 segments
+on [-1,1], cubic splines with N(0,1) coefficients compiled to L = 64 symmetric int8 tables, batch 32768 rows of
+x ~ N(0, 0.5) clipped to [-1.2, 1.2], closed + clip_x.  --workload names any other workload of the scope table.
 
-Prints ONE JSON line: edge-evaluations/s (batch*d*m per second), the roofline record of the dominant kernel
-(the edge kernel) measured with HIP events on the launch stream, the B-spline baseline ratio, and the CPU
-oracle timed on a bounded sample of the same rows.
+Prints ONE JSON line: edge-evaluations/s (batch*d*m per second, summed over the layers), the roofline record of the
+dominant kernel measured with HIP events on the launch stream, what one forward asks of each resource (HBM, L2, LDS,
+vector ALU) priced at published / derived peaks and at rates measured in the same run, the B-spline baseline ratio,
+and the CPU oracle timed on a bounded random sample of the same rows.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -22,33 +25,385 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# fp32 vector rate without the packed-fp32 forms (this library is built with them disabled):
-# 256 CUs x 4 SIMDs x 16 lanes x 2 flop (FMA) x 2.4 GHz.  The published packed figure is 157.3 TFLOP/s.
+# ---- peaks.  "derived" = from the unit counts and the clock, not a published figure.
+# fp32 vector rate WITHOUT the packed-fp32 forms (this library is built with them disabled):
+# 256 CUs x 4 SIMDs x 16 lanes x 2 flop (FMA) x 2.4 GHz = 78.6 TFLOP/s (derived).  Published, with packed forms: 157.3.
 PEAK_FP32_TFLOPS = 256 * 4 * 16 * 2 * 2.4e9 / 1e12
 PEAK_FP32_PACKED_TFLOPS = 157.3
-PEAK_HBM_GBS = 8000.0
+PEAK_LANE_INSTR = 256 * 4 * 16 * 2.4e9            # vector lane-instructions/s at one wave instruction per 4 cycles (derived)
+PEAK_HBM_BPS = 8.0e12                              # published
+PEAK_LDS_BPS = 256 * 256 * 2.4e9                   # 256 B per clock and compute unit (derived)
 # Algorithmic fp32 operations per edge evaluation (Eq. 10 twice: 2 mul + 2 add; Eq. 17: 2 mul + 1 add;
 # Eq. 1: 1 add).  Integer->float conversions, address arithmetic and the 1-w subtraction are not counted.
 FLOP_PER_EDGE = 8
-# HBM traffic of one edge-kernel launch on the default workload, from rocprofv3 --pmc FETCH_SIZE (x2.0, the factor a
-# plain 1 GiB copy gives) + WRITE_SIZE (x1.0); see profiles/lutkan_tiled_kernel_cfg4_B32768.md.
-MEASURED_TRAFFIC_BYTES = {32768: 3.72e9}
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic_per_launch.md")
 
 
 def log(msg):
     print(msg, file=sys.stderr, flush=True)
 
 
-def time_all_configs(lk, torch, dev, with_oracle):
-    """Every workload of the scope table: one lutkan_model_forward and the chained B-spline layers (events, mean of 20
-    after 3 warm-up runs), and the oracle chain on a bounded sample of rows with all host threads."""
-    import numpy as np
-    from lutkan_inputs import ASYM_UINT8, HALF_OPEN, SYM_INT8, ZERO_SPLINE, cfg1, cfg2, cfg3, cfg4, cfg5
+# ------------------------------------------------------------------------------------------------ workloads
+def workload_names():
+    names = ["cfg1", "cfg2"]
+    names += [f"cfg3_L{L}_{sc}" for sc in ("sym", "asym") for L in (16, 32, 64, 128)]
+    names += ["cfg4_B256", "cfg4_B4096", "cfg4_B32768"]
+    names += [f"cfg5_{b}_{o}" for b in ("closed", "half_open") for o in ("clip_x", "zero_spline")]
+    return names
 
-    def timed(fn, n=20, warm=3):
-        for _ in range(warm):
+
+def make_workload(name, batch=None):
+    """The seeded synthetic workload `name` of the scope table (lutkan_inputs); batch overrides its row count."""
+    import lutkan_inputs as li
+    kw = {} if batch is None else {"B": batch}
+    if name == "cfg1":
+        return li.cfg1(**kw)
+    if name == "cfg2":
+        return li.cfg2(**kw)
+    mt = re.fullmatch(r"cfg3_L(\d+)_(sym|asym)", name)
+    if mt:
+        return li.cfg3(L=int(mt.group(1)), scheme=li.SYM_INT8 if mt.group(2) == "sym" else li.ASYM_UINT8, **kw)
+    mt = re.fullmatch(r"cfg4_B(\d+)", name)
+    if mt:
+        return li.cfg4(B=batch or int(mt.group(1)))
+    mt = re.fullmatch(r"cfg5_(closed|half_open)_(clip_x|zero_spline)", name)
+    if mt:
+        return li.cfg5(boundary=li.CLOSED if mt.group(1) == "closed" else li.HALF_OPEN,
+                       oob=li.CLIP_X if mt.group(2) == "clip_x" else li.ZERO_SPLINE, **kw)
+    sys.exit(f"bench.py: unknown workload {name!r}; known: {', '.join(workload_names())}")
+
+
+# ------------------------------------------------------------------------------------------------ cost model
+def kernel_costs(info, spec, B, plan):
+    """What each kernel launch of one lutkan_forward call must move and compute, from the layer's shape and the launch
+    plan the library reports (lutkan_last_plan): a list of dicts {kernel, hbm, l2, lds, valu} in bytes resp. vector
+    lane-instructions.  hbm = compulsory bytes (every operand once); l2 = bytes staged from L2 into LDS, or read
+    through L2 by the kernels that gather from global memory; lds = bytes the lanes read from LDS plus the staged
+    bytes written into it; valu = lane-instructions of the inner loops (counted for the tiled kernel, estimated for
+    the kernels that are bound by memory latency)."""
+    d, m, K = spec.d, spec.m, info.K
+    asym = (info.scheme == 1)
+    base = (info.value_repr == 1)
+    rec = 16 if base else 8
+    prm = (8 if asym else 4) + (4 if base else 0)               # parameter bytes per edge
+    Bp = -(-B // 1024) * 1024
+    edges = B * d * m
+    out = []
+    last_split = 1
+    for clause in [c.strip() for c in plan.split(";") if c.strip()]:
+        nums = [int(v) for v in re.findall(r"=(\d+)", clause)]
+        if clause == "locate":
+            # about 30 + K vector instructions per (row, input): domain test, clip, K-1 compares, divide, floor, record
+            out.append(dict(kernel="lutkan_locate_kernel", hbm=4 * B * d + rec * Bp * d, l2=0, lds=2 * rec * Bp * d,
+                            valu=(30 + K) * B * d))
+        elif clause.startswith("tiled"):
+            np_, last_split = nums
+            rows_per_group = 16 * (64 // (info.jt // 4)) * np_
+            staged = -(-B // rows_per_group) * info.table_bytes + info.n_tiles * rec * Bp * d
+            per4 = (20 if asym else 18) + (4 if base else 0)            # vector instructions per 4 edges
+            lds_per4 = (12 if base else 8) + 8 + (32 if asym else 16)   # record, two code dwords, alpha (+ y_min) per lane
+            out.append(dict(kernel="lutkan_tiled_kernel", hbm=info.table_bytes + rec * Bp * d + 4 * B * m * last_split,
+                            l2=staged, lds=edges / 4 * lds_per4 + staged, valu=edges / 4 * per4))
+        elif clause.startswith("gather"):
+            last_split = nums[0]
+            touched = min(info.table_bytes, B * d * info.n_tiles * info.jt * (2 + prm))
+            out.append(dict(kernel="lutkan_gather_kernel", hbm=touched + rec * Bp * d + 4 * B * m * last_split,
+                            l2=edges * (2 + prm + rec), lds=0, valu=edges * 14))
+        elif clause == "sum":
+            out.append(dict(kernel="sum_partials_kernel", hbm=4 * B * m * (last_split + 1), l2=0, lds=0, valu=B * m * last_split / 4))
+        elif clause.startswith("chain"):
+            touched = min(info.table_bytes, B * d * info.jt * (2 + prm))
+            out.append(dict(kernel="lutkan_chain_kernel", hbm=touched + 4 * B * (d + m), l2=edges * (2 + prm),
+                            lds=16 * B * d * (1 + max(1, m)), valu=edges * 14 + (30 + K) * B * d))
+    return out
+
+
+def price(costs, rates):
+    """Lower bound of one forward = sum over its kernels of the largest of that kernel's resource times; the binding
+    resource is the one that contributes most to that sum."""
+    total, by_resource, share = 0.0, {r: 0.0 for r in rates}, {r: 0.0 for r in rates}
+    for c in costs:
+        t = {r: c[r] / rates[r] for r in rates}
+        worst = max(t, key=t.get)
+        total += t[worst]
+        share[worst] += t[worst]
+        for r in rates:
+            by_resource[r] += t[r]
+    return total, by_resource, max(share, key=share.get)
+
+
+def traffic_from_profiles(workload, kernel):
+    """HBM bytes per launch of `kernel` on `workload` as rocprofv3 counted them (FETCH_SIZE and WRITE_SIZE, scaled by
+    a plain copy of known size), read from the table of the committed profile summary; None when it has no such row."""
+    try:
+        for line in open(TRAFFIC_TABLE):
+            cells = [c.strip().strip("`") for c in line.strip().strip("|").split("|")]
+            if len(cells) >= 5 and cells[0] == workload and cells[1] == kernel:
+                return float(cells[4]), os.path.relpath(TRAFFIC_TABLE, ROOT) + " (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)"
+    except (OSError, ValueError):
+        pass
+    return None, None
+
+
+# ------------------------------------------------------------------------------------------------ measurement
+class Rig:
+    """Shared state of one bench process: torch, the binding, the device and the measured peak rates."""
+
+    def __init__(self, probes=True):
+        import numpy as np
+        import torch
+
+        import paper_2601_03332_amd as lk
+        assert torch.cuda.is_available(), "bench.py needs a GPU"
+        self.np, self.torch, self.lk, self.dev = np, torch, lk, "cuda:0"
+        self.measured = self.measure_peaks() if probes else None
+
+    def events(self):
+        return self.torch.cuda.Event(enable_timing=True), self.torch.cuda.Event(enable_timing=True)
+
+    def measure_peaks(self):
+        """Rates this GPU sustains on one resource at a time (kernels of known work, best of three, HIP events)."""
+        torch, lk = self.torch, self.lk
+        buf = torch.zeros((1 << 30) // 4 + 4, dtype=torch.float32, device=self.dev)      # 1 GiB + 16 B, finite floats
+
+        def probe(kind, iters):
+            best, work = None, 0.0
+            for _ in range(3):
+                e0, e1 = self.events()
+                e0.record()
+                work = lk.lutkan_probe_launch(kind, buf, iters)
+                e1.record()
+                torch.cuda.synchronize()
+                t = e0.elapsed_time(e1) * 1e-3
+                best = t if best is None else min(best, t)
+            return work / best
+
+        fma = probe(lk.PROBE_VALU_FMA, 2048)
+        rates = {"fp32_fma_flops": fma, "kernel_mix_lane_instr": probe(lk.PROBE_VALU_MIX, 2048),
+                 "lds_read_Bps": probe(lk.PROBE_LDS_READ, 512), "l2_read_Bps": probe(lk.PROBE_L2_READ, 4),
+                 "hbm_read_Bps": probe(lk.PROBE_HBM_READ, 2)}
+        del buf
+        log("[bench] measured peaks: FMA %.1f TFLOP/s, kernel mix %.1f T lane-instr/s, LDS %.1f TB/s, L2 %.1f TB/s, HBM %.2f TB/s"
+            % (fma / 1e12, rates["kernel_mix_lane_instr"] / 1e12, rates["lds_read_Bps"] / 1e12, rates["l2_read_Bps"] / 1e12,
+               rates["hbm_read_Bps"] / 1e12))
+        return rates
+
+
+def run_workload(rig, name, steps, warmup, batch=None, bspline=True, cpu_baseline=True, oracle_seconds=12.0):
+    """Times `name` and returns its record: throughput of the whole forward, per-kernel durations, roofline terms."""
+    np, torch, lk, dev = rig.np, rig.torch, rig.lk, rig.dev
+    t0 = time.time()
+    wl = make_workload(name, batch)
+    B = wl.x.shape[0]
+    arts = [lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, s.boundary, s.oob) for s in wl.layers]
+    layers = [a.to_device(dev) for a in arts]
+    log(f"[bench] {name}: {wl.name}; inputs and tables ready in {time.time() - t0:.1f}s "
+        f"(tables {sum(a.info.table_bytes for a in arts) / 2**20:.1f} MiB)")
+    edges = sum(B * s.d * s.m for s in wl.layers)
+    nbuf = 3                                            # rotate buffers so no step re-reads a cache-warm x / y
+    xs = [torch.from_numpy(wl.x).to(dev)]
+    for r in range(1, nbuf):
+        xs.append(xs[0].roll(r * 977, dims=0).contiguous())
+    ys = [torch.empty((B, layers[-1].m), dtype=torch.float32, device=dev) for _ in range(nbuf)]
+    ws = torch.empty(max(256, lk.lutkan_model_workspace_bytes(layers, B)), dtype=torch.uint8, device=dev)
+
+    def step(n):
+        lk.lutkan_model_forward(layers, xs[n % nbuf], ys[n % nbuf], workspace=ws)
+
+    for n in range(warmup):
+        step(n)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for n in range(steps):
+        step(n)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    model_plan = lk.lutkan_last_plan()
+    # the same steps by HIP events on the launch stream, one pair per step: spread of the step time
+    ev = [rig.events() for _ in range(steps)]
+    for n in range(steps):
+        ev[n][0].record()
+        step(n)
+        ev[n][1].record()
+    torch.cuda.synchronize()
+    per_step = sorted(a.elapsed_time(b) for a, b in ev)
+    mean = sum(per_step) / steps
+    spread = {"median": per_step[steps // 2], "mean": mean, "std": (sum((t - mean) ** 2 for t in per_step) / steps) ** 0.5,
+              "min": per_step[0], "max": per_step[-1]}
+    log(f"[bench] {name}: lutkan_model_forward {dt * 1e3:.4f} ms/step, {edges / dt:.4g} edge-evals/s  [{model_plan.strip()}]")
+
+    # ---- per layer: which kernels a forward launches, and their durations (HIP events around the two phases)
+    acts = [xs[0]] + [torch.empty((B, l.m), dtype=torch.float32, device=dev) for l in layers]
+    kernels, costs = [], []
+    n_ev = max(5, min(steps, 50))
+    for li, (layer, art, spec) in enumerate(zip(layers, arts, wl.layers)):
+        lk.lutkan_forward(layer, acts[li], acts[li + 1], workspace=ws)
+        plan = lk.lutkan_last_plan()
+        costs += kernel_costs(art.info, spec, B, plan)
+        if plan.startswith("chain"):                    # one launch: the whole call is the kernel
+            evs = [rig.events() for _ in range(n_ev)]
+            for a, b in evs:
+                a.record()
+                lk.lutkan_forward(layer, acts[li], acts[li + 1], workspace=ws)
+                b.record()
+            torch.cuda.synchronize()
+            kernels.append({"layer": li, "kernel": "lutkan_chain_kernel", "ms": sum(a.elapsed_time(b) for a, b in evs) / n_ev,
+                            "plan": plan.strip()})
+            continue
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(n_ev)]
+        for e in evs:
+            e[0].record()
+            lk.lutkan_forward_locate(layer, acts[li], ws)
+            e[1].record()
+            lk.lutkan_forward_edges(layer, B, acts[li + 1], ws)
+            e[2].record()
+        torch.cuda.synchronize()
+        edge_plan = lk.lutkan_last_plan()
+        assert edge_plan == plan.replace("locate; ", ""), (plan, edge_plan)
+        edge_name = "lutkan_tiled_kernel" if "tiled" in plan else "lutkan_gather_kernel"
+        kernels.append({"layer": li, "kernel": "lutkan_locate_kernel", "ms": sum(e[0].elapsed_time(e[1]) for e in evs) / n_ev,
+                        "plan": "locate"})
+        kernels.append({"layer": li, "kernel": edge_name + (" + sum_partials_kernel" if "sum" in plan else ""),
+                        "ms": sum(e[1].elapsed_time(e[2]) for e in evs) / n_ev, "plan": edge_plan.strip()})
+    dominant = max(kernels, key=lambda k: k["ms"])
+    dspec, dart = wl.layers[dominant["layer"]], arts[dominant["layer"]]
+    dom_costs = kernel_costs(dart.info, dspec, B, dominant["plan"])
+    dom_edges = B * dspec.d * dspec.m
+
+    # ---- roofline terms of the whole forward
+    published = {"hbm": PEAK_HBM_BPS, "lds": PEAK_LDS_BPS, "valu": PEAK_LANE_INSTR}
+    t_pub, by_pub, bind_pub = price(costs, published)
+    terms = {"at_published_or_derived_peaks_ms": {k: round(v * 1e3, 5) for k, v in by_pub.items()},
+             "lower_bound_at_peaks_ms": round(t_pub * 1e3, 5), "binding_at_peaks": bind_pub,
+             "frac_of_bound_at_peaks": round(t_pub / dt, 4),
+             "work": {r: float(sum(c[r] for c in costs)) for r in ("hbm", "l2", "lds", "valu")},
+             "peaks": {"hbm_Bps_published": PEAK_HBM_BPS, "lds_Bps_derived": PEAK_LDS_BPS, "valu_lane_instr_derived": PEAK_LANE_INSTR}}
+    if rig.measured:
+        ms = rig.measured
+        measured = {"hbm": ms["hbm_read_Bps"], "l2": ms["l2_read_Bps"], "lds": ms["lds_read_Bps"], "valu": ms["fp32_fma_flops"] / 2.0}
+        t_ms, by_ms, bind_ms = price(costs, measured)
+        t_mix, by_mix, _ = price(costs, dict(measured, valu=ms["kernel_mix_lane_instr"]))
+        terms.update({"at_measured_rates_ms": {k: round(v * 1e3, 5) for k, v in by_ms.items()},
+                      "valu_at_kernel_mix_rate_ms": round(by_mix["valu"] * 1e3, 5),
+                      "lower_bound_at_measured_rates_ms": round(t_ms * 1e3, 5), "binding_at_measured_rates": bind_ms,
+                      "frac_of_bound_at_measured_rates": round(t_ms / dt, 4),
+                      "frac_of_bound_with_kernel_mix_rate": round(t_mix / dt, 4),
+                      "measured_rates": {k: float(f"{v:.4g}") for k, v in ms.items()}})
+
+    # ---- roofline record of the dominant kernel
+    k_s = dominant["ms"] * 1e-3
+    hbm_bytes = sum(c["hbm"] for c in dom_costs)
+    t_dom = {"hbm": hbm_bytes / PEAK_HBM_BPS, "valu": sum(c["valu"] for c in dom_costs) / PEAK_LANE_INSTR,
+             "lds": sum(c["lds"] for c in dom_costs) / PEAK_LDS_BPS}
+    traffic, source = traffic_from_profiles(name, dominant["kernel"].split(" + ")[0])
+    if max(t_dom, key=t_dom.get) == "hbm":
+        achieved = hbm_bytes / k_s / 1e9
+        roofline = {"bound": "hbm", "kernel": dominant["kernel"], "achieved": round(achieved, 1), "peak": PEAK_HBM_BPS / 1e9,
+                    "unit": "GB/s", "frac": round(achieved / (PEAK_HBM_BPS / 1e9), 4)}
+    else:
+        achieved = FLOP_PER_EDGE * dom_edges / k_s / 1e12
+        roofline = {"bound": "alu", "kernel": dominant["kernel"], "achieved": round(achieved, 3), "peak": round(PEAK_FP32_TFLOPS, 1),
+                    "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP32_TFLOPS, 4),
+                    "peak_is": "derived: 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz, fp32 FMA without the packed forms",
+                    "peak_published_packed_fp32": PEAK_FP32_PACKED_TFLOPS,
+                    "frac_vs_published_packed_fp32": round(achieved / PEAK_FP32_PACKED_TFLOPS, 4),
+                    "flop_per_edge_eval": FLOP_PER_EDGE}
+    roofline.update({"traffic": traffic, "traffic_source": source, "kernel_ms": round(dominant["ms"], 5), "layer": dominant["layer"],
+                     "launch_plan": dominant["plan"], "compulsory_hbm_bytes": int(hbm_bytes),
+                     "hbm_time_floor_ms": round(hbm_bytes / PEAK_HBM_BPS * 1e3, 5), "terms": terms})
+
+    rec = {"workload": name, "description": wl.name, "batch": B, "layers": [[s.d, s.m] for s in wl.layers],
+           "ms_per_step": round(dt * 1e3, 5), "edge_evals_per_s": round(edges / dt, 1), "rows_per_s": round(B / dt, 1),
+           "launch_plan": model_plan.strip(), "step_ms_by_events": {k: round(v, 5) for k, v in spread.items()},
+           "kernels": [dict(k, ms=round(k["ms"], 5)) for k in kernels], "roofline": roofline}
+
+    if bspline:
+        splines = [a.bspline_to_device(dev) for a in arts]
+        wsb = torch.empty(max(lk.bspline_forward_workspace_bytes(b, B) for b in splines), dtype=torch.uint8, device=dev)
+
+        def spline_chain():
+            for li, b in enumerate(splines):
+                lk.bspline_kan_forward(b, acts[li], acts[li + 1], workspace=wsb)
+
+        n_b = max(3, min(steps, 50))
+        for _ in range(max(2, min(warmup, 10))):
+            spline_chain()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n_b):
+            spline_chain()
+        torch.cuda.synchronize()
+        bs = (time.perf_counter() - t0) / n_b
+        rec.update({"bspline_ms_per_step": round(bs * 1e3, 5), "lut_vs_bspline_speedup": round(bs / dt, 4)})
+        log(f"[bench] {name}: B-spline layers {bs * 1e3:.4f} ms/step -> LUT is {bs / dt:.2f}x the B-spline chain")
+        del splines, wsb
+
+    if cpu_baseline:
+        import oracle
+        oras = [oracle.compile_layer(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme) for s in wl.layers]
+        threads = oracle.default_threads()
+        per_row = sum(s.d * s.m for s in wl.layers)
+
+        def chain(x, nthreads):
+            outs = []
+            for o, s in zip(oras, wl.layers):
+                outs.append(oracle.lut_forward(o, s.boundary, s.oob, x, nthreads=nthreads))
+                x = outs[-1].y
+            return outs
+
+        probe = min(B, 64)
+        t0 = time.perf_counter()
+        chain(wl.x[:probe], threads)
+        rate = probe / (time.perf_counter() - t0)
+        rows = int(min(B, max(probe, rate * oracle_seconds)))
+        # a seeded random sample of the batch (sorted), so that every row tile of the launch is represented
+        pick = np.sort(np.random.Generator(np.random.PCG64(2601)).choice(B, size=rows, replace=False))
+        x_pick = np.ascontiguousarray(wl.x[pick])
+        t0 = time.perf_counter()
+        ref = chain(x_pick, threads)
+        cdt = time.perf_counter() - t0
+        # the same rows on the GPU at the timed batch, layer by layer on the oracle's own activations
+        pick_t = torch.from_numpy(pick).to(dev)
+        ok, cur = True, xs[0]
+        for li, layer in enumerate(layers):
+            if li > 0:
+                cur = torch.zeros((B, layer.d), dtype=torch.float32, device=dev)
+                cur[pick_t] = torch.from_numpy(ref[li - 1].y).to(dev)
+            yg = lk.lutkan_forward(layer, cur, workspace=ws)
+            torch.cuda.synchronize()
+            err = np.abs(yg[pick_t].cpu().numpy().astype(np.float64) - ref[li].y)
+            ok = ok and bool(np.all(err <= 1e-5 * ref[li].A + 1e-6))
+        n1 = max(1, min(rows, probe // 2))              # the paper's protocol is single-threaded (Sec. 6.1)
+        t0 = time.perf_counter()
+        chain(wl.x[:n1], 1)
+        single = n1 * per_row / (time.perf_counter() - t0)
+        rec["cpu_baseline"] = {"value": round(rows * per_row / cdt, 1), "unit": "edge-evals/s", "cores": threads, "kind": "oracle",
+                               "sample": f"{rows} of the {B} rows of the same workload, drawn at random (seeded), {cdt:.1f}s",
+                               "gpu_matches_oracle_on_sample": ok, "single_thread_value": round(single, 1)}
+        log(f"[bench] {name}: oracle {rows} rows in {cdt:.1f}s on {threads} threads ({rows * per_row / cdt:.3g} edge-evals/s); "
+            f"GPU within tolerance on them: {ok}; one thread: {single:.3g} edge-evals/s")
+        del oras, ref
+    del layers, arts, xs, ys, ws, acts
+    torch.cuda.empty_cache()
+    return rec
+
+
+def tabular_chain_latency(rig):
+    """The tabular chain 78 -> 16 -> 2 at batch 256 (the batch of the paper's deployment measurements, Sec. 8): per-layer
+    launches against the fused one-launch chain."""
+    torch, lk, dev = rig.torch, rig.lk, rig.dev
+    w2 = make_workload("cfg2", 256)
+    chain = [lk.lutkan_compile(c.d, c.m, c.G, c.p, c.ext_knots, c.coef, c.L, c.scheme, c.boundary, c.oob).to_device(dev)
+             for c in w2.layers]
+    x = torch.from_numpy(w2.x).to(dev)
+    y = torch.empty((256, 2), dtype=torch.float32, device=dev)
+    hid = torch.empty((256, chain[0].m), dtype=torch.float32, device=dev)
+    ws = torch.empty(max(256, lk.lutkan_model_workspace_bytes(chain, 256)), dtype=torch.uint8, device=dev)
+
+    def ms(fn, n=200):
+        for _ in range(20):
             fn()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0, e1 = rig.events()
         e0.record()
         for _ in range(n):
             fn()
@@ -56,314 +411,81 @@ def time_all_configs(lk, torch, dev, with_oracle):
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / n
 
-    def oracle_rate(wl, budget_s=4.0):
-        import oracle
-        arts = [oracle.compile_layer(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme) for s in wl.layers]
-        per_row = sum(s.d * s.m for s in wl.layers)
-        threads = oracle.default_threads()
+    def layer_by_layer():
+        lk.lutkan_forward(chain[0], x, hid, workspace=ws)
+        lk.lutkan_forward(chain[1], hid, y, workspace=ws)
 
-        def chain(x):
-            for a, s in zip(arts, wl.layers):
-                x = oracle.lut_forward(a, s.boundary, s.oob, x, nthreads=threads).y
-            return x
-
-        rows = min(wl.x.shape[0], 64)
-        t0 = time.perf_counter()
-        chain(wl.x[:rows])
-        rate = rows / (time.perf_counter() - t0)
-        rows = int(min(wl.x.shape[0], max(rows, rate * budget_s)))
-        t0 = time.perf_counter()
-        chain(wl.x[:rows])
-        return rows * per_row / (time.perf_counter() - t0), rows
-
-    workloads = [("cfg1", cfg1()), ("cfg2", cfg2())]
-    workloads += [(f"cfg3 L={L} {'sym' if sc == SYM_INT8 else 'asym'}", cfg3(L=L, scheme=sc)) for sc in (SYM_INT8, ASYM_UINT8)
-                  for L in (16, 32, 64, 128)]
-    workloads += [(f"cfg4 B={B}", cfg4(B=B)) for B in (256, 4096, 32768)]
-    workloads += [("cfg5 closed+clip_x", cfg5()), ("cfg5 half_open+zero_spline", cfg5(boundary=HALF_OPEN, oob=ZERO_SPLINE))]
-    rows_out = []
-    log(f"[bench] {'workload':28s} {'B':>7s} {'LUT ms':>9s} {'G edge-evals/s':>15s} {'B-spline ms':>12s} {'ratio':>6s} {'oracle G/s':>11s}")
-    for name, wl in workloads:
-        arts = [lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, s.boundary, s.oob) for s in wl.layers]
-        layers = [a.to_device(dev) for a in arts]
-        splines = [a.bspline_to_device(dev) for a in arts]
-        x = torch.from_numpy(wl.x).to(dev)
-        B = x.shape[0]
-        ws = torch.empty(lk.lutkan_model_workspace_bytes(layers, B), dtype=torch.uint8, device=dev)
-        y = torch.empty((B, layers[-1].m), dtype=torch.float32, device=dev)
-        ms = timed(lambda: lk.lutkan_model_forward(layers, x, y, workspace=ws))
-        acts = [x] + [torch.empty((B, s.m), dtype=torch.float32, device=dev) for s in wl.layers]
-        wsb = torch.empty(max(lk.bspline_forward_workspace_bytes(b, B) for b in splines), dtype=torch.uint8, device=dev)
-
-        def spline_chain():
-            for li, b in enumerate(splines):
-                lk.bspline_kan_forward(b, acts[li], acts[li + 1], workspace=wsb)
-
-        msb = timed(spline_chain)
-        edges = sum(B * s.d * s.m for s in wl.layers)
-        rec = {"workload": name, "batch": B, "lut_ms": round(ms, 4), "edge_evals_per_s": round(edges / ms * 1e3, 1),
-               "bspline_ms": round(msb, 4), "lut_vs_bspline_speedup": round(msb / ms, 3)}
-        if with_oracle:
-            rate, rows = oracle_rate(wl)
-            rec.update(oracle_edge_evals_per_s=round(rate, 1), oracle_rows=rows)
-        rows_out.append(rec)
-        log(f"[bench] {name:28s} {B:7d} {ms:9.3f} {edges / ms / 1e6:15.1f} {msb:12.3f} {msb / ms:6.2f} "
-            f"{rec.get('oracle_edge_evals_per_s', float('nan')) / 1e9:11.3f}")
-        del arts, layers, splines, x, ws, y, acts, wsb
-    return rows_out
+    return {"batch_256_per_layer_launches_ms": round(ms(layer_by_layer), 5),
+            "batch_256_fused_chain_ms": round(ms(lambda: lk.lutkan_chain_forward(chain, x, y)), 5)}
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--batch", type=int, default=32768)
+    ap.add_argument("--steps", type=int, default=200, help="timed steps (default: the 200 of Sec. 6.4's protocol)")
+    ap.add_argument("--warmup", type=int, default=50, help="untimed warm-up steps (default: the 50 of Sec. 6.4's protocol)")
+    ap.add_argument("--workload", default="cfg4_B32768", help="one of: " + ", ".join(workload_names()))
+    ap.add_argument("--batch", type=int, default=None, help="override the workload's number of rows")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bspline", action="store_true")
     ap.add_argument("--no-probes", action="store_true", help="skip the peak-rate probes (FMA, instruction mix, LDS, L2, HBM)")
     ap.add_argument("--all-configs", action="store_true",
-                    help="also time every workload of the scope table (LUT chain, B-spline chain, bounded oracle sample); "
-                         "the results go to extra.configs and, as a table, to stderr")
+                    help="also run every workload of the scope table; their records (throughput, kernels, roofline terms, "
+                         "B-spline ratio, bounded oracle sample) go to extra.configs and, as a table, to stderr")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy, as a known-size reference for HBM counters")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU by design (rows are independent: more GPUs would each run the "
                  "same kernel on B/N rows with replicated tables); run with --gpus 1")
+    if args.steps < 1 or args.warmup < 0:
+        sys.exit("bench.py: --steps must be >= 1 and --warmup >= 0")
+    if args.workload not in workload_names():
+        sys.exit(f"bench.py: unknown workload {args.workload!r}; known: {', '.join(workload_names())}")
 
-    import numpy as np
-    import torch
-
-    import paper_2601_03332_amd as lk
-    from lutkan_inputs import cfg4
-
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    dev = "cuda:0"
-    t0 = time.time()
-    w = cfg4(seed=0, B=args.batch)
-    s = w.layers[0]
-    B, d, m = w.x.shape[0], s.d, s.m
-    log(f"[bench] inputs generated in {time.time() - t0:.1f}s: {w.name}")
-    t0 = time.time()
-    art = lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, s.boundary, s.oob)
-    log(f"[bench] lutkan_compile: {time.time() - t0:.1f}s, table {art.info.table_bytes / 2**20:.0f} MiB, jt={art.info.jt}")
-    layer = art.to_device(dev)
-    nbuf = 3                                            # rotate buffers so no step re-reads a cache-warm x / y
-    xs = [torch.from_numpy(w.x).to(dev)]
-    for r in range(1, nbuf):
-        xs.append(xs[0].roll(r * 977, dims=0).contiguous())
-    ys = [torch.empty((B, m), dtype=torch.float32, device=dev) for _ in range(nbuf)]
-    ws = torch.empty(lk.lutkan_forward_workspace_bytes(layer, B), dtype=torch.uint8, device=dev)
-    edges = B * d * m
-
-    def step(n):
-        lk.lutkan_forward(layer, xs[n % nbuf], ys[n % nbuf], workspace=ws)
-
+    rig = Rig(probes=not args.no_probes)
+    torch = rig.torch
     if args.copy_calibration:                           # 2^28 floats read + 2^28 floats written = 1 GiB each way
-        ca = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        ca = torch.empty(1 << 28, dtype=torch.float32, device=rig.dev).normal_()
         cb = torch.empty_like(ca)
         for _ in range(3):
             cb.copy_(ca)
         torch.cuda.synchronize()
         del ca, cb
 
-    for n in range(args.warmup):
-        step(n)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for n in range(args.steps):
-        step(n)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt / args.steps * 1e3
-    value = edges / (dt / args.steps)
-    log(f"[bench] lutkan_forward: {ms_per_step:.3f} ms/step, {value:.4g} edge-evals/s")
-
-    # Per-kernel durations with HIP events on the stream the kernels are launched on (torch's current stream).
-    def time_phases(locate, edge_fn, steps):
-        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
-        for n in range(steps):
-            ev[n][0].record()
-            locate(n)
-            ev[n][1].record()
-            edge_fn(n)
-            ev[n][2].record()
-        torch.cuda.synchronize()
-        loc = sorted(e[0].elapsed_time(e[1]) for e in ev)
-        edg = sorted(e[1].elapsed_time(e[2]) for e in ev)
-        tot = sorted(e[0].elapsed_time(e[2]) for e in ev)
-        mean = sum(tot) / len(tot)
-        spread = {"median": tot[len(tot) // 2], "mean": mean, "std": (sum((t - mean) ** 2 for t in tot) / len(tot)) ** 0.5,
-                  "min": tot[0], "max": tot[-1]}
-        return sum(loc) / len(loc), sum(edg) / len(edg), edg[len(edg) // 2], spread
-
-    loc_ms, edge_ms, edge_med, step_spread = time_phases(lambda n: lk.lutkan_forward_locate(layer, xs[n % nbuf], ws),
-                                            lambda n: lk.lutkan_forward_edges(layer, B, ys[n % nbuf], ws), args.steps)
-    log(f"[bench] locate kernel {loc_ms:.3f} ms, edge kernel {edge_ms:.3f} ms (median {edge_med:.3f})")
-    achieved = FLOP_PER_EDGE * edges / (edge_ms * 1e-3) / 1e12
-    roofline = {"bound": "alu", "kernel": "lutkan_tiled_kernel", "achieved": round(achieved, 3),
-                "peak": round(PEAK_FP32_TFLOPS, 1), "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP32_TFLOPS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get(B), "kernel_ms": round(edge_ms, 4),
-                "flop_per_edge_eval": FLOP_PER_EDGE, "peak_packed_fp32": PEAK_FP32_PACKED_TFLOPS,
-                "compulsory_hbm_bytes": int(art.info.table_bytes + 8 * B * d + 4 * B * m),
-                "hbm_time_floor_ms": round((art.info.table_bytes + 8 * B * d + 4 * B * m) / (PEAK_HBM_GBS * 1e9) * 1e3, 4)}
-
-    extra = {"rows_per_s": round(B / (dt / args.steps), 1), "locate_kernel_ms": round(loc_ms, 4),
-             "edge_kernel_edge_evals_per_s": round(edges / (edge_ms * 1e-3), 1),
-             "step_ms_by_events": {k: round(v, 4) for k, v in step_spread.items()}}
-
-    if not args.no_probes:
-        # Rates this GPU sustains on one resource at a time (kernels of known work, timed with events), and what
-        # the edge kernel asks of each resource per launch: the largest term is the bound, the others show the slack.
-        probe_buf = torch.zeros((1 << 30) // 4 + 4, dtype=torch.float32, device=dev)      # 1 GiB + 16 B, finite floats
-
-        def probe(kind, iters):
-            best, work = None, 0.0
-            for _ in range(3):
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
-                work = lk.lutkan_probe_launch(kind, probe_buf, iters)
-                e1.record()
-                torch.cuda.synchronize()
-                t = e0.elapsed_time(e1) * 1e-3
-                best = t if best is None else min(best, t)
-            return work / best
-
-        fma_flops = probe(lk.PROBE_VALU_FMA, 2048)
-        mix_rate = probe(lk.PROBE_VALU_MIX, 2048)                # lane-instructions/s of the kernel's own instruction mix
-        lds_bps = probe(lk.PROBE_LDS_READ, 512)
-        l2_bps = probe(lk.PROBE_L2_READ, 4)
-        hbm_bps = probe(lk.PROBE_HBM_READ, 2)
-        del probe_buf
-        rec_bytes = 8 * (-(-B // 1024) * 1024) * d
-        valu_ops = 4.5 * edges                                   # 18 vector instructions per 4 edges (lane-operations)
-        lds_bytes = 8.0 * edges                                  # 32 B per lane and row step: record 8, codes 8, scales 16
-        l2_bytes = -(-B // 1024) * art.info.table_bytes + art.info.n_tiles * rec_bytes   # slices and records staged into LDS
-        hbm_bytes = MEASURED_TRAFFIC_BYTES.get(B) or (art.info.table_bytes + rec_bytes + 4 * B * m)
-        # valu: every vector instruction at the FMA issue rate; valu_mix: at the measured rate of the kernel's mix
-        # (permutes, packed-fp16 adds and mixed FMAs issue more slowly than plain FMAs on this chip)
-        terms = {"valu": valu_ops / (fma_flops / 2.0), "valu_mix": valu_ops / mix_rate, "lds": (lds_bytes + l2_bytes) / lds_bps,
-                 "l2": l2_bytes / l2_bps, "hbm": hbm_bytes / hbm_bps}
-        binding = max(terms, key=terms.get)
-        roofline.update({
-            "measured_peaks": {"fp32_fma_TFLOPs": round(fma_flops / 1e12, 2),
-                               "kernel_mix_Tlane_instr_s": round(mix_rate / 1e12, 3), "lds_read_TBs": round(lds_bps / 1e12, 2),
-                               "l2_read_TBs": round(l2_bps / 1e12, 2), "hbm_read_TBs": round(hbm_bps / 1e12, 2)},
-            "terms_ms": {k: round(v * 1e3, 4) for k, v in terms.items()},
-            "binding_term": binding,
-            "frac_of_measured_bound": round(terms[binding] / (edge_ms * 1e-3), 4)})
-        log(f"[bench] measured peaks: FMA {fma_flops / 1e12:.1f} TFLOP/s, LDS {lds_bps / 1e12:.1f} TB/s, "
-            f"L2 {l2_bps / 1e12:.1f} TB/s, HBM {hbm_bps / 1e12:.2f} TB/s; edge-kernel terms (ms): "
-            + ", ".join(f"{k} {v * 1e3:.2f}" for k, v in terms.items()) + f" -> bound by {binding}")
-
-    if not args.no_bspline:
-        bl = art.bspline_to_device(dev)
-        wsb = torch.empty(lk.bspline_forward_workspace_bytes(bl, B), dtype=torch.uint8, device=dev)
-        for n in range(max(2, args.warmup // 2)):
-            lk.bspline_kan_forward(bl, xs[n % nbuf], ys[n % nbuf], workspace=wsb)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for n in range(args.steps):
-            lk.bspline_kan_forward(bl, xs[n % nbuf], ys[n % nbuf], workspace=wsb)
-        torch.cuda.synchronize()
-        bs_ms = (time.perf_counter() - t0) / args.steps * 1e3
-        bloc_ms, bedge_ms, _, _ = time_phases(lambda n: lk.bspline_forward_locate(bl, xs[n % nbuf], wsb),
-                                           lambda n: lk.bspline_forward_edges(bl, B, ys[n % nbuf], wsb), args.steps)
-        extra.update({"bspline_ms_per_step": round(bs_ms, 4), "lut_vs_bspline_speedup": round(bs_ms / ms_per_step, 4),
-                      "bspline_locate_kernel_ms": round(bloc_ms, 4), "bspline_edge_kernel_ms": round(bedge_ms, 4),
-                      "paper_cpu_speedup_context": "LUT vs B-spline on a Ryzen 7 7840HS, 1 thread: ~12x NumPy, ~10x Numba (Tables 2-3)"})
-        log(f"[bench] bspline_kan_forward: {bs_ms:.3f} ms/step -> LUT is {bs_ms / ms_per_step:.2f}x the B-spline layer")
-        del wsb
-
-    if not args.no_bspline:
-        # The tabular chain 78 -> 16 -> 2 (L = 64 asymmetric uint8): throughput at batch 65536 through the per-layer
-        # launches, and latency at batch 256 (the batch of the paper's deployment measurements, Sec. 8) through the
-        # per-layer launches and through the fused one-launch chain.
-        from lutkan_inputs import cfg2
-        w2 = cfg2(seed=0)
-        chain = [lk.lutkan_compile(c.d, c.m, c.G, c.p, c.ext_knots, c.coef, c.L, c.scheme, c.boundary, c.oob).to_device(dev)
-                 for c in w2.layers]
-        x2 = torch.from_numpy(w2.x).to(dev)
-
-        def chain_ms(fn, n=50):
-            for _ in range(5):
-                fn()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(n):
-                fn()
-            e1.record()
-            torch.cuda.synchronize()
-            return e0.elapsed_time(e1) / n
-
-        B2 = x2.shape[0]
-        y2 = torch.empty((B2, 2), dtype=torch.float32, device=dev)
-        ws2 = torch.empty(lk.lutkan_model_workspace_bytes(chain, B2), dtype=torch.uint8, device=dev)
-        full_ms = chain_ms(lambda: lk.lutkan_model_forward(chain, x2, y2, workspace=ws2))
-        xs256, ys256 = x2[:256].contiguous(), y2[:256].contiguous()
-        hid256 = torch.empty((256, chain[0].m), dtype=torch.float32, device=dev)
-
-        def layer_by_layer():
-            lk.lutkan_forward(chain[0], xs256, hid256, workspace=ws2)
-            lk.lutkan_forward(chain[1], hid256, ys256, workspace=ws2)
-
-        layers_ms = chain_ms(layer_by_layer)
-        fused_ms = chain_ms(lambda: lk.lutkan_chain_forward(chain, xs256, ys256))
-        chain_edges = sum(c.d * c.m for c in w2.layers)
-        extra["tabular_chain_78_16_2"] = {"batch_65536_ms": round(full_ms, 4),
-                                          "batch_65536_edge_evals_per_s": round(B2 * chain_edges / (full_ms * 1e-3), 1),
-                                          "batch_256_per_layer_launches_ms": round(layers_ms, 4),
-                                          "batch_256_fused_chain_ms": round(fused_ms, 4)}
-        log(f"[bench] 78->16->2: batch {B2} {full_ms:.3f} ms; batch 256: {layers_ms:.4f} ms per-layer launches, "
-            f"{fused_ms:.4f} ms fused chain")
-        del chain, x2, y2, ws2
-
-    cpu = None
-    if not args.no_cpu_baseline:
-        import oracle
-        t0 = time.time()
-        ora = oracle.compile_layer(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme)
-        log(f"[bench] oracle compile (not timed into the baseline): {time.time() - t0:.1f}s")
-        threads = oracle.default_threads()
-        probe = 64
-        t0 = time.perf_counter()
-        oracle.lut_forward(ora, s.boundary, s.oob, w.x[:probe], nthreads=threads)
-        rate = probe / (time.perf_counter() - t0)
-        rows = int(min(B, max(probe, rate * 12.0)))      # about 12 s of CPU work
-        # a seeded random sample of the batch (sorted), so that every row tile of the launch is represented
-        pick = np.sort(np.random.Generator(np.random.PCG64(2601)).choice(B, size=rows, replace=False))
-        x_pick = np.ascontiguousarray(w.x[pick])
-        t0 = time.perf_counter()
-        ref = oracle.lut_forward(ora, s.boundary, s.oob, x_pick, nthreads=threads)
-        cdt = time.perf_counter() - t0
-        # the same rows on the GPU, as a last parity check of the timed configuration
-        yg = ys[0]
-        lk.lutkan_forward(layer, xs[0], yg, workspace=ws)
-        torch.cuda.synchronize()
-        err = np.abs(yg[torch.from_numpy(pick).to(dev)].cpu().numpy().astype(np.float64) - ref.y)
-        ok = bool(np.all(err <= 1e-5 * ref.A + 1e-6))
-        t0 = time.perf_counter()                              # the paper's protocol is single-threaded (Sec. 6.1)
-        oracle.lut_forward(ora, s.boundary, s.oob, w.x[:probe // 2], nthreads=1)
-        single = (probe // 2) * d * m / (time.perf_counter() - t0)
-        cpu = {"value": round(rows * d * m / cdt, 1), "unit": "edge-evals/s", "cores": threads, "kind": "oracle",
-               "sample": f"{rows} of the {B} rows of the same workload, drawn at random (seeded), {cdt:.1f}s", "gpu_matches_oracle_on_sample": ok,
-               "single_thread_value": round(single, 1)}
-        log(f"[bench] oracle: {rows} rows in {cdt:.1f}s on {threads} threads; GPU within tolerance on them: {ok}; "
-            f"one thread: {single:.3g} edge-evals/s")
-        del ora, ref
+    rec = run_workload(rig, args.workload, args.steps, args.warmup, batch=args.batch, bspline=not args.no_bspline,
+                       cpu_baseline=not args.no_cpu_baseline)
+    extra = {k: rec[k] for k in ("rows_per_s", "launch_plan", "step_ms_by_events", "kernels", "bspline_ms_per_step",
+                                 "lut_vs_bspline_speedup") if k in rec}
+    if "lut_vs_bspline_speedup" in rec:
+        extra["paper_cpu_speedup_context"] = "LUT vs B-spline on a Ryzen 7 7840HS, 1 thread: ~12x NumPy, ~10x Numba (Tables 2-3)"
+        extra["tabular_chain_78_16_2"] = tabular_chain_latency(rig)
 
     if args.all_configs:
-        del xs, ys, ws, layer, art
-        extra["configs"] = time_all_configs(lk, torch, dev, with_oracle=not args.no_cpu_baseline)
+        configs = []
+        log(f"[bench] {'workload':26s} {'B':>7s} {'LUT ms':>9s} {'G edge-evals/s':>15s} {'B-spline ms':>12s} {'ratio':>6s} "
+            f"{'bound':>6s} {'frac@peaks':>10s} {'frac@measured':>13s} {'oracle G/s':>11s}")
+        for name in workload_names():
+            r = rec if (name == args.workload and args.batch is None) else run_workload(
+                rig, name, max(5, min(args.steps, 50)), max(2, min(args.warmup, 10)), bspline=not args.no_bspline,
+                cpu_baseline=not args.no_cpu_baseline, oracle_seconds=3.0)
+            configs.append(r)
+            t = r["roofline"]["terms"]
+            log(f"[bench] {name:26s} {r['batch']:7d} {r['ms_per_step']:9.4f} {r['edge_evals_per_s'] / 1e9:15.1f} "
+                f"{r.get('bspline_ms_per_step', float('nan')):12.4f} {r.get('lut_vs_bspline_speedup', float('nan')):6.2f} "
+                f"{t.get('binding_at_measured_rates', t['binding_at_peaks']):>6s} {t['frac_of_bound_at_peaks']:10.3f} "
+                f"{t.get('frac_of_bound_at_measured_rates', float('nan')):13.3f} "
+                f"{r.get('cpu_baseline', {}).get('value', float('nan')) / 1e9:11.3f}")
+        extra["configs"] = configs
 
-    out = {"metric": "lutkan_layer_edge_evals_per_s", "value": round(value, 1), "unit": "edge-evals/s", "n_gpus": 1,
-           "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
-           "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-           "config": {"workload": f"cfg4: dense KAN layer {d}->{m}, G={s.G}, k=3, L={s.L} symmetric int8, batch {B}, "
-                                  f"x~N(0,0.5) clipped to [-1.2,1.2], closed+clip_x, seed 0",
-                      "d": d, "m": m, "K": s.G, "L": s.L, "batch": B, "scheme": "sym_int8"},
-           "roofline": roofline, "cpu_baseline": cpu, "extra": extra}
+    config = {"workload": f"{args.workload}: {rec['description']}, batch {rec['batch']}, seed 0", "layers": rec["layers"], "batch": rec["batch"]}
+    if len(rec["layers"]) == 1:
+        s0 = make_workload(args.workload, 1).layers[0]
+        config.update({"d": s0.d, "m": s0.m, "K": s0.G, "L": s0.L, "scheme": "sym_int8" if s0.scheme == 0 else "asym_uint8"})
+    out = {"metric": "lutkan_layer_edge_evals_per_s", "value": rec["edge_evals_per_s"], "unit": "edge-evals/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": rec["ms_per_step"], "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic", "config": config,
+           "roofline": rec["roofline"], "cpu_baseline": rec.get("cpu_baseline"), "extra": extra}
     print(json.dumps(out), flush=True)
 
 
