@@ -128,18 +128,25 @@ int gather_jx_log2(int m) {
 //   one work-group                3 + its inputs (pipeline fill, accumulator write-back)
 //   the launch                    rounds of 256 work-groups (one per compute unit), one after the other
 //   the partial sums              4 + their bytes at 3 TB/s, when there is more than one chunk
+//   a table of more than 128 MiB  at least its bytes at 21 GB/s per work-group and 5.3 TB/s in all (it streams from
+//                                 HBM on every launch; smaller tables are served by the caches after the first)
 // The constants come from the widest workload (2.4 us per input at NP = 16), a 64x1024 layer at NP = 4 (1.1 us) and
 // sweeps over batch sizes of 78x16 ... 4096x256 layers; the model replaced a rule (largest row tile first, split the inputs until 256
 // work-groups, at most 32 chunks) that lost up to 40 % on wide-input, narrow-output layers at a few hundred rows.
 struct TilePlan {
   int np, n_split, chunk;
+  double cost;       // the model's estimate for the launch (and its summing pass), microseconds
 };
 
 TilePlan plan_tiles(int64_t B, int d, int m, int n_tiles, int rps, int slice_bytes) {
   const int np_max = std::min(16, 64 / rps);
   const int max_split = std::max(1, std::min(128, d / 8));
-  TilePlan best{np_max, 1, d};
+  TilePlan best{np_max, 1, d, 1e300};
   double best_cost = 1e300;
+  // a table beyond what the caches hold streams from HBM once per launch: about 21 GB/s per streaming work-group,
+  // 5.3 TB/s for the whole chip
+  const double table_bytes = (double)n_tiles * d * slice_bytes;
+  const bool streams_from_hbm = table_bytes > 128.0 * 1024 * 1024;
   for (int np = np_max; np >= 1; np >>= 1) {
     const int64_t rows = (int64_t)kTileWaves * rps * np;
     const int64_t groups = (B + rows - 1) / rows * n_tiles;
@@ -156,22 +163,25 @@ TilePlan plan_tiles(int64_t B, int d, int m, int n_tiles, int rps, int slice_byt
       const int split = (d + chunk - 1) / chunk;      // no empty trailing chunks
       const double rounds = (double)((groups * split + 255) / 256);
       double cost = rounds * (3.0 + chunk * per_input);
+      if (streams_from_hbm)           // once per row tile; ties go to the smaller row tile (fewer padding rows)
+        cost = std::max(cost, (double)(groups / n_tiles) * table_bytes / std::min(5.3e6, 21e3 * (double)std::min<int64_t>(256, groups * split))) + 0.01 * np;
       if (split > 1) cost += 4.0 + (double)split * (double)B * m * 4.0 / 3e6;
-      if (cost < best_cost) { best_cost = cost; best = TilePlan{np, split, chunk}; }
+      if (cost < best_cost) { best_cost = cost; best = TilePlan{np, split, chunk, cost}; }
     }
   }
   return best;
 }
 
-// Launch shape of the gather kernel: the d inputs are cut into chunks (at least 4 inputs each, at most 64 chunks)
+// Launch shape of the gather kernels (lanes_per_row = m with one column per lane, a quarter of the padded width with
+// four): the d inputs are cut into chunks (at least 4 inputs each, at most 64 chunks)
 // until the launch has about a million threads: a thread's walk over its inputs is a chain of dependent reads,
 // four inputs per round trip, so short chunks matter more than full compute units.
 struct GatherPlan {
   int n_split, chunk;
 };
 
-GatherPlan plan_gather(int64_t B, int d, int m) {
-  const int64_t threads = B * (int64_t)m;
+GatherPlan plan_gather(int64_t B, int d, int lanes_per_row) {
+  const int64_t threads = B * (int64_t)lanes_per_row;
   int64_t want = (threads >= (1 << 20)) ? 1 : ((1 << 20) + threads - 1) / threads;
   want = std::min<int64_t>(want, std::min(64, std::max(1, d / 4)));
   const int chunk = (int)((d + want - 1) / want);
@@ -210,8 +220,9 @@ int launch_with_lds(Kern kern, LdsCap *cap, const dim3 &grid, size_t lds, hipStr
 size_t tiled_workspace_bytes(int d, int m, int jt, int n_tiles, int64_t B, int bytes_per_record, int slice_bytes) {
   size_t bytes = record_bytes(d, padded_rows(B), bytes_per_record);
   const TilePlan tp = plan_tiles(B, d, m, n_tiles, 64 / (jt / 4), slice_bytes);
-  const GatherPlan gp = plan_gather(B, d, m);           // either kernel may run: room for the larger set of partial sums
-  const int n_split = std::max(tp.n_split, gp.n_split);
+  // any of the kernels may run (tiled, gather with one column per lane, gather with four): room for the largest set
+  const GatherPlan gp = plan_gather(B, d, m), gp4 = plan_gather(B, d, n_tiles * jt / 4);
+  const int n_split = std::max(tp.n_split, std::max(gp.n_split, gp4.n_split));
   if (n_split > 1) bytes += (size_t)n_split * (size_t)B * (size_t)m * 4;
   return bytes;
 }

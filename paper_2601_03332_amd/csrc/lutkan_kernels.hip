@@ -295,6 +295,93 @@ __global__ __launch_bounds__(256) void lutkan_gather_kernel(const EdgeArgs a, co
 }
 
 
+// Gather variant for the plain launch (no code trace): the lane layout of the tiled kernel without its staging.  A lane
+// owns 4 adjacent columns of one row, jt/4 lanes share a row, so per input a lane issues four vector-memory reads for
+// its 4 edges -- the row's record (the same address for the lanes of a row), one dword of code row l0, one of row
+// l0+1, 16 bytes of alpha (plus 16 of y_min for the asymmetric scheme) -- where the kernel above issues five per
+// edge.  Only the table rows a batch touches are read, each as whole 4..64-byte runs of its column tile, which is what
+// makes this the kernel for batches that touch less than the whole table: the tiled kernel streams every slice
+// whatever the batch.  Inputs four at a time (all records, then all codes and parameters: two dependent round trips
+// per four inputs); blockIdx.z selects the chunk of inputs, partial sums as above.  Arithmetic per edge as above.
+template <int SCHEME, bool BASE, bool PH, int U>
+__global__ __launch_bounds__(256) void lutkan_gather4_kernel(const EdgeArgs a, const int lpr_log2) {
+  typedef typename std::conditional<BASE, u32x4, u32x2>::type rec_t;
+  const int sub = threadIdx.x & ((1 << lpr_log2) - 1);                  // which 4-column group of the tile
+  const int64_t b = (int64_t)blockIdx.x * (256 >> lpr_log2) + (threadIdx.x >> lpr_log2);    // < Bp: padding rows carry masked records
+  const int t = blockIdx.y;
+  const unsigned char *tile = a.table + (size_t)t * a.d * a.blob_bytes;
+  const rec_t *recs = static_cast<const rec_t *>(a.rec) + b;
+  const unsigned col_codes = (unsigned)a.codes_off + sub * 4;
+  const unsigned col_params = (unsigned)a.params_off + sub * (PH ? 8 : 16);
+  const unsigned plane = (unsigned)a.jt * (PH ? 2 : 4);
+  const int i_begin = blockIdx.z * a.chunk;
+  const int i_end = min(a.d, i_begin + a.chunk);
+  float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  rec_t rec[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) rec[u] = recs[(int64_t)min(i_begin + u, i_end - 1) * a.Bp];
+  for (int i0 = i_begin; i0 < i_end; i0 += U) {
+    unsigned c0[U], c1[U];
+    f32x4 al[U], ym[U], bg[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const unsigned char *slice = tile + (size_t)min(i0 + u, i_end - 1) * a.blob_bytes;
+      const unsigned char *cp = slice + col_codes + (rec[u].x & 0xffffu) * (unsigned)a.jt;
+      const unsigned char *pp = slice + col_params + (rec[u].x >> 16) * (unsigned)a.param_row_bytes;
+      c0[u] = *reinterpret_cast<const unsigned *>(cp);
+      c1[u] = *reinterpret_cast<const unsigned *>(cp + a.jt);
+      ym[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if constexpr (PH) {
+        const u32x2 ha = *reinterpret_cast<const u32x2 *>(pp);
+        const f16x2 a01 = bits_to_f16x2(ha.x), a23 = bits_to_f16x2(ha.y);
+        al[u] = f32x4{(float)a01.x, (float)a01.y, (float)a23.x, (float)a23.y};
+        if (SCHEME == LUTKAN_ASYM_UINT8) {
+          const u32x2 hy = *reinterpret_cast<const u32x2 *>(pp + plane);
+          const f16x2 y01 = bits_to_f16x2(hy.x), y23 = bits_to_f16x2(hy.y);
+          ym[u] = f32x4{(float)y01.x, (float)y01.y, (float)y23.x, (float)y23.y};
+        }
+      } else {
+        al[u] = *reinterpret_cast<const f32x4 *>(pp);
+        if (SCHEME == LUTKAN_ASYM_UINT8) ym[u] = *reinterpret_cast<const f32x4 *>(pp + plane);
+      }
+      bg[u] = BASE ? *reinterpret_cast<const f32x4 *>(slice + sub * 16) : f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    // the records of the next U inputs travel while this round's codes and parameters do: one exposed round trip per round
+    rec_t rec_next[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) rec_next[u] = recs[(int64_t)min(i0 + U + u, i_end - 1) * a.Bp];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (i0 + u < i_end) {
+        const float w = __uint_as_float(rec[u].y);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const float f0 = code_to_float<SCHEME>(c0[u] >> (8 * c)), f1 = code_to_float<SCHEME>(c1[u] >> (8 * c));
+          const float tq = fmaf(w, f1 - f0, f0);                              // interpolate the codes ...
+          acc[c] = fmaf(al[u][c], tq, acc[c]);                               // ... then one scale per edge
+          if (SCHEME == LUTKAN_ASYM_UINT8) acc[c] += ym[u][c];
+          if constexpr (BASE) acc[c] = fmaf(bg[u][c], __uint_as_float(rec[u].z), acc[c]);    // + s_out*s_base * SiLU(x)
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) rec[u] = rec_next[u];
+  }
+  if (b >= a.B) return;
+  const int j = t * a.jt + sub * 4;
+  float *yout = a.y + (int64_t)blockIdx.z * a.split_stride + b * a.m + j;
+  if (j + 3 < a.m && (a.m & 3) == 0) {
+    *reinterpret_cast<f32x4 *>(yout) = f32x4{acc[0], acc[1], acc[2], acc[3]};
+  } else {
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+      if (j + c < a.m) yout[c] = acc[c];
+  }
+}
+
+
+constexpr int kGather4Inputs = 8;
+
 // Tiled variant.  A work-group of NW waves owns NW*RW rows and one column tile of JT = 4*LPR outputs.
 // A wave works on RPS = 64/LPR rows at a time: LPR lanes share a row and each lane owns 4 adjacent columns,
 // so one dword holds a lane's four codes of a table row and one 16-byte read its four scales.  Each wave owns
@@ -685,14 +772,18 @@ int validate_layer(const lutkan_dev_layer *l, const char *who) {
   return LUTKAN_OK;
 }
 
-// True when a batch is so small that reading only the table rows it touches (gather kernel, inputs split over the
-// GPU) moves fewer bytes than the whole table, which the tiled kernel streams once whatever the batch.
-bool prefer_gather_for_small_batch(const lutkan_dev_layer *l, int64_t B) {
+// True when a batch is so small that gathering only the table rows it touches (gather kernel, inputs split over the
+// GPU) beats the tiled kernel, which streams the whole table once whatever the batch.  A table that the caches hold
+// (up to 128 MiB): when the bytes the lanes request (per row, input and column tile two code rows and one parameter
+// row) stay below the table's (measured: 256x256 near 128 rows).  A larger table streams from HBM on every tiled
+// launch, and scattered reads of it pay off for longer: the gather kernel is priced at 8 us plus the requested bytes
+// at 9.4 TB/s, the tiled launch at the estimate of its launch planning (measured: 1024x1024 between 128 and 256 rows).
+bool prefer_gather_for_small_batch(const lutkan_dev_layer *l, int64_t B, double tiled_cost_us) {
   const lutkan::BlobLayout lay = lutkan::blob_layout(l->K, l->L, l->jt, l->scheme, l->value_repr, l->param_dtype);
-  // per (row, input, column tile): two code rows and one parameter row
   const double touched = (double)B * l->d * l->n_tiles * (2.0 * l->jt + (double)lay.param_row_bytes);
   const double table = (double)l->n_tiles * l->d * l->blob_bytes;
-  return touched <= table;     // measured crossover: 1024x1024 near 100 rows, 256x256 near 200, both where the two are equal
+  if (table <= 128.0 * 1024 * 1024) return touched <= table;
+  return 8.0 + touched / 9.4e6 <= tiled_cost_us;
 }
 
 template <int SCHEME, int LPR, int NP>
@@ -872,12 +963,12 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
 
   bool tiled = tiled_supported(l->jt, l->blob_bytes, l->value_repr) && !q01_out;
   if (l->algo == LUTKAN_ALGO_GATHER) tiled = false;
-  if (l->algo == LUTKAN_ALGO_AUTO && tiled && prefer_gather_for_small_batch(l, B)) tiled = false;
+  const TilePlan tp = tiled ? plan_tiles(B, l->d, l->m, l->n_tiles, 64 / (l->jt / 4), l->blob_bytes) : TilePlan{1, 1, l->d, 0.0};
+  if (l->algo == LUTKAN_ALGO_AUTO && tiled && prefer_gather_for_small_batch(l, B, tp.cost)) tiled = false;
   if (l->algo == LUTKAN_ALGO_TILED && !tiled) return fail(LUTKAN_EUNSUPPORTED, "%s: tiled kernel needs a table slice <= 72 KiB (64 KiB with the base branch)", who);
   ea.chunk = l->d;
   ea.split_stride = 0;
   if (tiled) {
-    const TilePlan tp = plan_tiles(B, l->d, l->m, l->n_tiles, 64 / (l->jt / 4), l->blob_bytes);
     float *partials = reinterpret_cast<float *>(static_cast<char *>(workspace) + record_bytes(l->d, Bp, lut_record_bytes(l->value_repr)));
     ea.chunk = tp.chunk;
     if (tp.n_split > 1) { ea.y = partials; ea.split_stride = B * l->m; }
@@ -890,9 +981,34 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
     lutkan::plan_note("sum; ");
     return check_launch("sum_partials_kernel");
   }
+  float *partials = reinterpret_cast<float *>(static_cast<char *>(workspace) + record_bytes(l->d, Bp, lut_record_bytes(l->value_repr)));
+  if (!q01_out) {
+    // the plain launch: four columns per lane
+    int lpr_log2 = 0;
+    while ((4 << lpr_log2) < l->jt) ++lpr_log2;
+    const GatherPlan gp = plan_gather(B, l->d, (l->n_tiles * l->jt) / 4);
+    ea.chunk = gp.chunk;
+    if (gp.n_split > 1) { ea.y = partials; ea.split_stride = B * l->m; }
+    const int rows_per_group = 256 >> lpr_log2;
+    const dim3 grid((unsigned)((B + rows_per_group - 1) / rows_per_group), (unsigned)l->n_tiles, (unsigned)gp.n_split);
+    if (grid.y > 65535u) return fail(LUTKAN_EUNSUPPORTED, "%s: m too large for the gather kernel", who);
+    const bool sym = (l->scheme == LUTKAN_SYM_INT8);
+#define LUTKAN_LAUNCH_GATHER4(S, BASE, PH) hipLaunchKernelGGL((lutkan_gather4_kernel<S, BASE, PH, kGather4Inputs>), grid, dim3(256), 0, s, ea, lpr_log2)
+    if (with_base) { if (sym) LUTKAN_LAUNCH_GATHER4(LUTKAN_SYM_INT8, true, false); else LUTKAN_LAUNCH_GATHER4(LUTKAN_ASYM_UINT8, true, false); }
+    else if (ea.param_fp16) { if (sym) LUTKAN_LAUNCH_GATHER4(LUTKAN_SYM_INT8, false, true); else LUTKAN_LAUNCH_GATHER4(LUTKAN_ASYM_UINT8, false, true); }
+    else { if (sym) LUTKAN_LAUNCH_GATHER4(LUTKAN_SYM_INT8, false, false); else LUTKAN_LAUNCH_GATHER4(LUTKAN_ASYM_UINT8, false, false); }
+#undef LUTKAN_LAUNCH_GATHER4
+    if (int rc = check_launch("lutkan_gather4_kernel")) return rc;
+    lutkan::plan_note("gather split=%d; ", gp.n_split);
+    if (gp.n_split == 1) return LUTKAN_OK;
+    const int64_t n = B * l->m;
+    hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, s, partials, y, n, gp.n_split);
+    lutkan::plan_note("sum; ");
+    return check_launch("sum_partials_kernel");
+  }
+  // the code trace: one column per lane, so that every edge's two codes can be written out
   const int lg = gather_jx_log2(l->m);
   const GatherPlan gp = plan_gather(B, l->d, l->m);
-  float *partials = reinterpret_cast<float *>(static_cast<char *>(workspace) + record_bytes(l->d, Bp, lut_record_bytes(l->value_repr)));
   ea.chunk = gp.chunk;
   if (gp.n_split > 1) { ea.y = partials; ea.split_stride = B * l->m; }
   const dim3 grid((unsigned)((B + (256 >> lg) - 1) / (256 >> lg)), (unsigned)((l->m + (1 << lg) - 1) >> lg), (unsigned)gp.n_split);
