@@ -10,6 +10,10 @@ spline_component, inputs N(0,1) clipped to the knot domain) it prints
     of rows with any out-of-domain input, error on those rows, error on the in-range rows.
 With --sweep it also prints, for the 256 -> 256 layer of the L x scheme sweep (G = 8, batch 16384), the error of
 the LUT layer against the B-spline layer and the time of both per point: the latency is flat in L (Sec. 7.2).
+With --matrix it runs the deep chain 64 -> 128 -> 128 -> 64 -> 8 (G = 5, L = 32 asymmetric uint8, batch 131072, 30 % of the
+inputs outside the knot domain) under each of the four boundary_mode x oob_policy contracts: per-layer fraction of
+out-of-domain inputs and of rows with any (Sec. 5.5 counters), error of the LUT chain against the B-spline chain under
+the same contract on the in-range and the OOB-only rows (Sec. 5.6), and the time of one forward.
 With --variants it times every option combination (scheme x value_repr x parameter dtype) on the widest workload.
 With --batches it times LUT and B-spline layers of five shapes from 1 to 65536 rows (which kernel AUTO picks changes
 along the way: one-launch chain, gather with split inputs, tiled).
@@ -30,6 +34,7 @@ def main():
     ap.add_argument("--seeds", type=int, default=5)
     ap.add_argument("--batch", type=int, default=4096)
     ap.add_argument("--sweep", action="store_true", help="also run the 256->256 L x scheme sweep with timings")
+    ap.add_argument("--matrix", action="store_true", help="also run the deep chain under the four boundary x policy contracts")
     ap.add_argument("--variants", action="store_true", help="also time every option combination on the 1024 -> 1024 layer at batch 32768")
     ap.add_argument("--batches", action="store_true", help="also time LUT and B-spline layers of several shapes from 1 to 65536 rows")
     ap.add_argument("--latency", action="store_true", help="also time narrow chains at small batches: per-layer launches vs the fused chain")
@@ -105,6 +110,55 @@ def main():
                 st = lk.lutkan_error_stats(y_lut, y_ref, x, float(art.knots[0]), float(art.knots[-1]), s.boundary)
                 print(f"{L:>4} {name:>10} {st['mae_in']:>12.6f} {st['max_abs_in']:>12.6f} {t_lut:>9.3f} {t_spl:>12.3f} "
                       f"{B * s.d * s.m / t_lut / 1e6:>15.1f} {art.info.table_bytes / 2**20:>10.1f}")
+
+    if args.matrix:
+        from lutkan_inputs import cfg5
+
+        def chain_ms(fn, n=30, warm=5):
+            for _ in range(warm):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(n):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / n
+
+        print()
+        print("Deep chain 64 -> 128 -> 128 -> 64 -> 8, G = 5, L = 32 asymmetric uint8, batch 131072, 30 % of the inputs out of domain:")
+        print("LUT chain vs B-spline chain under the same contract; subsets by the first layer's inputs (Sec. 5.6)")
+        print(f"{'boundary':>10} {'policy':>12} {'OOB inputs per layer':>34} {'rows with any OOB per layer':>34} {'OOB_any_frac':>13} "
+              f"{'MAE in-range':>13} {'MaxAbs in':>10} {'MAE OOB rows':>13} {'MaxAbs OOB':>11} {'LUT ms':>8} {'B-spline ms':>12}")
+        for boundary, bn in ((CLOSED, "closed"), (HALF_OPEN, "half_open")):
+            for oob, on in ((CLIP_X, "clip_x"), (ZERO_SPLINE, "zero_spline")):
+                w = cfg5(boundary=boundary, oob=oob)
+                arts = [lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, s.boundary, s.oob) for s in w.layers]
+                layers = [a.to_device(dev) for a in arts]
+                splines = [a.bspline_to_device(dev) for a in arts]
+                x = torch.from_numpy(w.x).to(dev)
+                B = x.shape[0]
+                ws = torch.empty(lk.lutkan_model_workspace_bytes(layers, B), dtype=torch.uint8, device=dev)
+                y = torch.empty((B, layers[-1].m), dtype=torch.float32, device=dev)
+                stats = torch.zeros((len(layers), 2), dtype=torch.int64, device=dev)
+                lk.lutkan_model_forward(layers, x, y, stats=stats, workspace=ws)
+                acts = [x] + [torch.empty((B, s.m), dtype=torch.float32, device=dev) for s in w.layers]
+                wsb = torch.empty(max(lk.bspline_forward_workspace_bytes(b, B) for b in splines), dtype=torch.uint8, device=dev)
+
+                def spline_chain():
+                    for li, b in enumerate(splines):
+                        lk.bspline_kan_forward(b, acts[li], acts[li + 1], workspace=wsb)
+
+                spline_chain()
+                st = lk.lutkan_error_stats(y, acts[-1], x, float(arts[0].knots[0]), float(arts[0].knots[-1]), boundary)
+                counts = stats.cpu().numpy()
+                per_input = " ".join(f"{counts[li, 0] / (B * s.d):.4f}" for li, s in enumerate(w.layers))
+                per_row = " ".join(f"{counts[li, 1] / B:.4f}" for li in range(len(layers)))
+                t_lut = chain_ms(lambda: lk.lutkan_model_forward(layers, x, y, workspace=ws))
+                t_spl = chain_ms(spline_chain)
+                print(f"{bn:>10} {on:>12} {per_input:>34} {per_row:>34} {st['oob_any_frac']:>13.4f} {st['mae_in']:>13.3e} {st['max_abs_in']:>10.3e} "
+                      f"{st['mae_oob']:>13.3e} {st['max_abs_oob']:>11.3e} {t_lut:>8.3f} {t_spl:>12.3f}")
+                del layers, splines, arts, x, ws, y, acts, wsb
 
     if args.variants:
         from lutkan_inputs import cfg4, draw_edge_scales
