@@ -83,7 +83,8 @@ def kernel_costs(info, spec, B, plan):
     the kernels that are bound by memory latency)."""
     d, m, K = spec.d, spec.m, info.K
     asym = (info.scheme == 1)
-    base = (info.value_repr == 1)
+    base_product = "base_product" in plan                       # the base branch runs as a matrix product of its own
+    base = (info.value_repr == 1) and not base_product         # ... else inside the edge kernel
     rec = 16 if base else 8
     prm = (8 if asym else 4) + (4 if base else 0)               # parameter bytes per edge
     Bp = -(-B // 1024) * 1024
@@ -94,7 +95,8 @@ def kernel_costs(info, spec, B, plan):
         nums = [int(v) for v in re.findall(r"=(\d+)", clause)]
         if clause == "locate":
             # about 30 + K vector instructions per (row, input): domain test, clip, K-1 compares, divide, floor, record
-            out.append(dict(kernel="lutkan_locate_kernel", hbm=4 * B * d + rec * Bp * d, l2=0, lds=2 * rec * Bp * d,
+            silu_plane = 4 * B * d if (info.value_repr == 1 and "base_product" in plan) else 0
+            out.append(dict(kernel="lutkan_locate_kernel", hbm=4 * B * d + rec * Bp * d + silu_plane, l2=0, lds=2 * rec * Bp * d,
                             valu=(30 + K) * B * d))
         elif clause.startswith("tiled"):
             np_, last_split = nums
@@ -109,6 +111,12 @@ def kernel_costs(info, spec, B, plan):
             touched = min(info.table_bytes, B * d * info.n_tiles * info.jt * (2 + prm))
             out.append(dict(kernel="lutkan_gather_kernel", hbm=touched + rec * Bp * d + 4 * B * m * last_split,
                             l2=edges * (2 + prm + rec), lds=0, valu=edges * 14))
+        elif clause == "base_product":
+            # SiLU(X) [B, d] times s_out*s_base [d, m] on the matrix cores, fp32 operands as three bf16 pieces each, six
+            # piece products: not priced against the vector ALU (its conversions are, roughly 12 instructions per operand element)
+            tiles = -(-B // 128) * -(-m // 128)
+            out.append(dict(kernel="lutkan_base_gemm_kernel", hbm=4 * B * d + 4 * d * m + 4 * B * m, l2=tiles * 4 * 128 * 2 * d,
+                            lds=tiles * (d / 32) * (2 * 61440), valu=tiles * 2 * 128 * d * 12, mfma_flop=12.0 * B * d * m))
         elif clause == "sum":
             out.append(dict(kernel="sum_partials_kernel", hbm=4 * B * m * (last_split + 1), l2=0, lds=0, valu=B * m * last_split / 4))
         elif clause.startswith("chain"):

@@ -10,8 +10,8 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.environ.get("LUTKAN_LIBRARY", os.path.join(HERE, "liblutkan.so"))
 SOURCES = [os.path.join(CSRC, "lutkan_compile.cpp"), os.path.join(CSRC, "lutkan_kernels.hip"),
            os.path.join(CSRC, "bspline_kernels.hip"), os.path.join(CSRC, "lutkan_probes.hip"),
-           os.path.join(CSRC, "lutkan_stats.hip")]
-HEADERS = [os.path.join(CSRC, "lutkan_internal.h"), os.path.join(CSRC, "lutkan_device.h"),
+           os.path.join(CSRC, "lutkan_stats.hip"), os.path.join(CSRC, "lutkan_base_gemm.hip")]
+HEADERS = [os.path.join(CSRC, "lutkan_internal.h"), os.path.join(CSRC, "lutkan_device.h"), os.path.join(CSRC, "lutkan_pieces.h"),
            os.path.join(ROOT, "include", "lutkan.h")]
 
 # -ffp-contract=off: the index arithmetic of the locate kernel and the host quantiser must round once per

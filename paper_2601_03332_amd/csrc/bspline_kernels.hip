@@ -435,7 +435,7 @@ int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y
     lutkan::plan_note("bspline_tiled np=%d split=%d; ", tp.np, tp.n_split);
     if (tp.n_split == 1) return rc;
     const int64_t n = B * l->m;
-    hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, s, partials, y, n, tp.n_split);
+    hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, s, partials, y, n, tp.n_split, 0);
     lutkan::plan_note("sum; ");
     return check_launch("sum_partials_kernel");
   }
@@ -450,7 +450,7 @@ int bspline_impl(const bspline_dev_layer *l, const float *x, int64_t B, float *y
   lutkan::plan_note("bspline_gather split=%d; ", gp.n_split);
   if (gp.n_split == 1) return LUTKAN_OK;
   const int64_t n = B * l->m;
-  hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, s, partials, y, n, gp.n_split);
+  hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, s, partials, y, n, gp.n_split, 0);
   lutkan::plan_note("sum; ");
   return check_launch("sum_partials_kernel");
 }

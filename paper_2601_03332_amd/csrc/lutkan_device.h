@@ -76,19 +76,21 @@ __device__ __forceinline__ void stage_slice(const u32x4 *gsrc, unsigned char *ld
   }
 }
 
-// Sums the n_split partial outputs of the tiled kernels in ascending chunk order (deterministic): y = sum_s part[s].
-__global__ __launch_bounds__(256) void sum_partials_kernel(const float *part, float *y, int64_t n, int n_split) {
+// Sums the n_split partial outputs of the tiled kernels in ascending chunk order (deterministic): y = sum_s part[s],
+// or y = y + sum_s part[s] with `accumulate` (y then already holds the base branch of the layer).
+__global__ __launch_bounds__(256) void sum_partials_kernel(const float *part, float *y, int64_t n, int n_split, int accumulate) {
   const int64_t e = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
   if (e + 3 < n && (n & 3) == 0) {                   // 16-byte path needs every chunk's base aligned
     f32x4 acc = *reinterpret_cast<const f32x4 *>(part + e);
 #pragma unroll 8
     for (int s = 1; s < n_split; ++s) acc += *reinterpret_cast<const f32x4 *>(part + (int64_t)s * n + e);   // loads of 8 chunks in flight
+    if (accumulate) acc = *reinterpret_cast<const f32x4 *>(y + e) + acc;
     *reinterpret_cast<f32x4 *>(y + e) = acc;
   } else {
     for (int64_t q = e; q < n && q < e + 4; ++q) {
       float acc = part[q];
       for (int s = 1; s < n_split; ++s) acc += part[(int64_t)s * n + q];
-      y[q] = acc;
+      y[q] = accumulate ? y[q] + acc : acc;
     }
   }
 }

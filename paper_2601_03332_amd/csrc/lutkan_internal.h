@@ -66,6 +66,17 @@ int choose_jt(int m, int K, int L, int scheme, int value_repr, int param_dtype);
 // measured 1.5-4 % faster on 128 columns than on 64 at the largest batches).
 int choose_coef_jt(int m);
 
+// The base branch of a spline_component layer as one product on the matrix cores (lutkan_base_gemm.hip):
+// y[B][m] = SiLU(x)[B][d] x (s_out*s_base)[d][m], both operands as three bf16 pieces per fp32 value.
+//   silu_pieces  [3][Bp][d] bf16 bit patterns written by the locate kernel, rows B .. Bp-1 zero, Bp a multiple of 128
+//   w_pieces     scratch of base_product_workspace_bytes(d, m) bytes, filled from the base rows of `table` by the call
+// base_product_fits: the shapes the product exists for (d a multiple of 32, at least 64 columns); for other shapes the
+// scratch size is 0.
+size_t base_product_workspace_bytes(int32_t d, int32_t m);
+bool base_product_fits(int32_t d, int32_t m, int64_t B);
+int launch_base_product(const uint16_t *silu_pieces, int64_t Bp, const void *table, uint16_t *w_pieces, int32_t d, int32_t m, int32_t jt,
+                        int32_t blob_bytes, int64_t B, float *y, void *hip_stream, const char *who);
+
 }  // namespace lutkan
 
 struct lutkan_artifact {

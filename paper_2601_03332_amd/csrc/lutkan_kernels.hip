@@ -15,6 +15,7 @@
 //                      batches, where the launches of 1. and 2. per layer cost more than the arithmetic).
 // The file is compiled with -ffp-contract=off; every fused multiply-add below is written out as fmaf().
 #include "lutkan_device.h"
+#include "lutkan_pieces.h"
 
 namespace {
 
@@ -33,6 +34,8 @@ struct LocateArgs {
   int32_t *k_out, *l0_out;     // nullable trace outputs, [B][d]
   uint8_t *in_out;
   float *w_out;
+  uint16_t *silu_pieces;       // nullable, [3][Bp][d]: SiLU(x) cut into three bf16 pieces (rows B .. Bp-1 zero), the first
+                               // operand of the base branch when it runs as a matrix product of its own
 };
 
 struct Located {
@@ -128,12 +131,26 @@ __global__ __launch_bounds__(256) void lutkan_locate_kernel(const LocateArgs a) 
       }
       // base branch b(x) = SiLU(x) = x / (1 + exp(-x)) at the RAW input (Eq. 2); it is never masked (Sec. 5.4)
       if constexpr (BASE) rec.z = __float_as_uint(__fdiv_rn(x, 1.0f + expf(-x)));
+      else if (a.silu_pieces) {
+        unsigned h, m, lo;
+        lutkan_cut3(__fdiv_rn(x, 1.0f + expf(-x)), h, m, lo);
+        uint16_t *dst = a.silu_pieces + b * a.d + i;
+        dst[0] = (uint16_t)h;
+        dst[a.Bp * a.d] = (uint16_t)m;
+        dst[2 * a.Bp * a.d] = (uint16_t)lo;
+      }
       if (a.k_out) {
         a.k_out[b * a.d + i] = o.k;
         a.l0_out[b * a.d + i] = o.l0;
         a.in_out[b * a.d + i] = o.inside ? 1 : 0;
         a.w_out[b * a.d + i] = o.w;
       }
+    }
+    else if (!BASE && a.silu_pieces && i < a.d) {          // a padding row: zero pieces, so that the product needs no row checks
+      uint16_t *dst = a.silu_pieces + b * a.d + i;
+      dst[0] = 0;
+      dst[a.Bp * a.d] = 0;
+      dst[2 * a.Bp * a.d] = 0;
     }
     s_rec[il][bl] = rec;
   }
@@ -200,6 +217,7 @@ struct EdgeArgs {
   const int32_t *k_out, *l0_out;   // code trace only: the located (k, l0) of every (row, input), [B][d]
   int32_t chunk;           // tiled kernels: inputs per work-group (blockIdx.y selects the chunk of inputs)
   int64_t split_stride;    // tiled kernels: floats between the partial outputs of consecutive chunks (0 if one chunk)
+  int32_t accumulate;      // tiled kernel writing y itself (one chunk): add to what y holds (the base branch) instead of overwriting
 };
 
 // Device-table byte -> code value.  Symmetric int8 codes are stored excess-128 (byte = q + 128).
@@ -381,6 +399,8 @@ __global__ __launch_bounds__(256) void lutkan_gather4_kernel(const EdgeArgs a, c
 
 
 constexpr int kGather4Inputs = 8;
+
+constexpr double kBaseProductMinEdges = 5e8;      // batch * d * m from which the base branch runs as a matrix product
 
 // Tiled variant.  A work-group of NW waves owns NW*RW rows and one column tile of JT = 4*LPR outputs.
 // A wave works on RPS = 64/LPR rows at a time: LPR lanes share a row and each lane owns 4 adjacent columns,
@@ -570,11 +590,13 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
     const int64_t b = b0 + p * RPS + hrow;
     if (b < a.B) {
       if (j + 3 < a.m && (a.m & 3) == 0) {
-        *reinterpret_cast<f32x4 *>(yout + b * a.m + j) = f32x4{acc[p][0], acc[p][1], acc[p][2], acc[p][3]};
+        f32x4 out = f32x4{acc[p][0], acc[p][1], acc[p][2], acc[p][3]};
+        if (a.accumulate) out = *reinterpret_cast<const f32x4 *>(yout + b * a.m + j) + out;
+        *reinterpret_cast<f32x4 *>(yout + b * a.m + j) = out;
       } else {
 #pragma unroll
         for (int c = 0; c < 4; ++c)
-          if (j + c < a.m) yout[b * a.m + j + c] = acc[p][c];
+          if (j + c < a.m) yout[b * a.m + j + c] = a.accumulate ? yout[b * a.m + j + c] + acc[p][c] : acc[p][c];
       }
     }
   }
@@ -915,13 +937,36 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   const int64_t Bp = padded_rows(B);
   const lutkan::BlobLayout lay = lutkan::blob_layout(l->K, l->L, l->jt, l->scheme, l->value_repr, l->param_dtype);
 
+  // Which edge kernel runs, and how the base branch of a spline_component layer is evaluated, follow from the layer
+  // and B alone, so that the two phases agree when they are called separately.
+  const bool with_base = (l->value_repr == LUTKAN_REPR_SPLINE_COMPONENT);
+  bool tiled = tiled_supported(l->jt, l->blob_bytes, l->value_repr) && !q01_out;
+  if (l->algo == LUTKAN_ALGO_GATHER) tiled = false;
+  const TilePlan tp = tiled ? plan_tiles(B, l->d, l->m, l->n_tiles, 64 / (l->jt / 4), l->blob_bytes) : TilePlan{1, 1, l->d, 0.0};
+  if (l->algo == LUTKAN_ALGO_AUTO && tiled && prefer_gather_for_small_batch(l, B, tp.cost)) tiled = false;
+  if (l->algo == LUTKAN_ALGO_TILED && !tiled) return fail(LUTKAN_EUNSUPPORTED, "%s: tiled kernel needs a table slice <= 72 KiB (64 KiB with the base branch)", who);
+  // Base branch as a matrix product of its own (SiLU(X) times the s_out*s_base of the table's base rows, into y) with
+  // the edge kernel of a phi layer adding the spline branch on top.  Measured against the base FMAs inside the edge
+  // kernel (four per four edges, 16-byte records): 1024x1024 at 32768 rows 5.87 -> 5.47 ms (uint8 codes 6.67 -> 5.97),
+  // at 2048 rows 0.55 -> 0.52; 128x128 at 131072 rows 0.59 -> 0.55; 256x256 at 16384 rows 0.260 -> 0.248, but at
+  // 2048 rows 0.056 -> 0.071 (three more launches): hence the floor on the work of the layer.
+  const bool base_by_product = with_base && tiled && (double)B * l->d * l->m >= kBaseProductMinEdges && lutkan::base_product_fits(l->d, l->m, B);
+  const int rec_bytes = (with_base && !base_by_product) ? 16 : 8;
+  // workspace: [records: room for 16 bytes each with the base branch; 8-byte records leave room for the 6 bytes per
+  // (row, input) of the SiLU pieces behind them] [pieces of s_out*s_base, spline_component only] [partial sums]
+  char *const ws_bytes = static_cast<char *>(workspace);
+  uint16_t *silu_pieces = reinterpret_cast<uint16_t *>(ws_bytes + record_bytes(l->d, Bp, 8));
+  const size_t records_end = record_bytes(l->d, Bp, lut_record_bytes(l->value_repr));
+  uint16_t *w_pieces = reinterpret_cast<uint16_t *>(ws_bytes + records_end);
+  float *const partials = reinterpret_cast<float *>(ws_bytes + records_end + (with_base ? lutkan::base_product_workspace_bytes(l->d, l->m) : 0));
+
   LocateArgs la;
   la.x = x;
   la.rec = workspace;
+  la.silu_pieces = base_by_product ? silu_pieces : nullptr;
   la.B = B; la.Bp = Bp; la.d = l->d; la.K = l->K; la.L = l->L;
   la.closed = (l->boundary == LUTKAN_CLOSED);
   la.zero_spline = (l->oob == LUTKAN_ZERO_SPLINE);
-  const bool with_base = (l->value_repr == LUTKAN_REPR_SPLINE_COMPONENT);
   la.tKs = la.closed ? l->knots[l->K] : std::nextafterf(l->knots[l->K], -INFINITY);
   for (int k = 0; k <= l->K; ++k) la.knots[k] = l->knots[k];
   la.input_knots = l->knots_per_input ? l->input_knots : nullptr;
@@ -934,10 +979,10 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
     const dim3 lgrid((unsigned)(Bp / (kLocTile / cols)), (unsigned)((l->d + cols - 1) / cols));
     if (lgrid.y > 65535u) return fail(LUTKAN_EUNSUPPORTED, "%s: d too large", who);
     if (l->knots_per_input) {
-      if (with_base) launch_locate<true, true>(cols, lgrid, s, la);
+      if (rec_bytes == 16) launch_locate<true, true>(cols, lgrid, s, la);
       else launch_locate<false, true>(cols, lgrid, s, la);
     } else {
-      if (with_base) launch_locate<true, false>(cols, lgrid, s, la);
+      if (rec_bytes == 16) launch_locate<true, false>(cols, lgrid, s, la);
       else launch_locate<false, false>(cols, lgrid, s, la);
     }
     if (int rc = check_launch("lutkan_locate_kernel")) return rc;
@@ -958,30 +1003,28 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   ea.B = B; ea.Bp = Bp; ea.d = l->d; ea.m = l->m; ea.K = l->K; ea.L = l->L;
   ea.jt = l->jt; ea.n_tiles = l->n_tiles; ea.blob_bytes = l->blob_bytes;
   ea.codes_off = lay.codes_off; ea.params_off = lay.params_off; ea.param_row_bytes = lay.param_row_bytes;
-  ea.with_base = with_base; ea.k_out = k_out; ea.l0_out = l0_out;
+  ea.with_base = (rec_bytes == 16); ea.k_out = k_out; ea.l0_out = l0_out;
   ea.param_fp16 = lutkan::device_params_are_half(l->value_repr, l->param_dtype, l->jt);
-
-  bool tiled = tiled_supported(l->jt, l->blob_bytes, l->value_repr) && !q01_out;
-  if (l->algo == LUTKAN_ALGO_GATHER) tiled = false;
-  const TilePlan tp = tiled ? plan_tiles(B, l->d, l->m, l->n_tiles, 64 / (l->jt / 4), l->blob_bytes) : TilePlan{1, 1, l->d, 0.0};
-  if (l->algo == LUTKAN_ALGO_AUTO && tiled && prefer_gather_for_small_batch(l, B, tp.cost)) tiled = false;
-  if (l->algo == LUTKAN_ALGO_TILED && !tiled) return fail(LUTKAN_EUNSUPPORTED, "%s: tiled kernel needs a table slice <= 72 KiB (64 KiB with the base branch)", who);
+  ea.accumulate = 0;
   ea.chunk = l->d;
   ea.split_stride = 0;
+  if (base_by_product) {
+    if (int rc = lutkan::launch_base_product(silu_pieces, Bp, l->table, w_pieces, l->d, l->m, l->jt, l->blob_bytes, B, y, hip_stream, who)) return rc;
+    lutkan::plan_note("base_product; ");
+  }
   if (tiled) {
-    float *partials = reinterpret_cast<float *>(static_cast<char *>(workspace) + record_bytes(l->d, Bp, lut_record_bytes(l->value_repr)));
     ea.chunk = tp.chunk;
     if (tp.n_split > 1) { ea.y = partials; ea.split_stride = B * l->m; }
+    ea.accumulate = (base_by_product && tp.n_split == 1) ? 1 : 0;       // with chunks, the summing pass adds to y instead
     const int rc = (l->scheme == LUTKAN_SYM_INT8) ? launch_tiled_jt<LUTKAN_SYM_INT8>(ea, tp.np, s) : launch_tiled_jt<LUTKAN_ASYM_UINT8>(ea, tp.np, s);
     if (rc) return rc;
     lutkan::plan_note("tiled np=%d split=%d; ", tp.np, tp.n_split);
     if (tp.n_split == 1) return rc;
     const int64_t n = B * l->m;
-    hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, s, partials, y, n, tp.n_split);
+    hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, s, partials, y, n, tp.n_split, base_by_product ? 1 : 0);
     lutkan::plan_note("sum; ");
     return check_launch("sum_partials_kernel");
   }
-  float *partials = reinterpret_cast<float *>(static_cast<char *>(workspace) + record_bytes(l->d, Bp, lut_record_bytes(l->value_repr)));
   if (!q01_out) {
     // the plain launch: four columns per lane
     int lpr_log2 = 0;
@@ -1002,7 +1045,7 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
     lutkan::plan_note("gather split=%d; ", gp.n_split);
     if (gp.n_split == 1) return LUTKAN_OK;
     const int64_t n = B * l->m;
-    hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, s, partials, y, n, gp.n_split);
+    hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, s, partials, y, n, gp.n_split, 0);
     lutkan::plan_note("sum; ");
     return check_launch("sum_partials_kernel");
   }
@@ -1024,7 +1067,7 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   lutkan::plan_note("gather split=%d; ", gp.n_split);
   if (gp.n_split == 1) return LUTKAN_OK;
   const int64_t n = B * l->m;
-  hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, s, partials, y, n, gp.n_split);
+  hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, s, partials, y, n, gp.n_split, 0);
   lutkan::plan_note("sum; ");
   return check_launch("sum_partials_kernel");
 }
@@ -1036,7 +1079,8 @@ extern "C" size_t lutkan_forward_workspace_bytes(const lutkan_dev_layer *layer, 
   // would divide by zero in the launch planning)
   if (!layer || B <= 0 || layer->d < 1 || layer->m < 1 || layer->n_tiles < 1 || layer->blob_bytes < 1) return 0;
   if (layer->jt < 4 || layer->jt > 64 || (layer->jt & (layer->jt - 1))) return 0;
-  return tiled_workspace_bytes(layer->d, layer->m, layer->jt, layer->n_tiles, B, lut_record_bytes(layer->value_repr), layer->blob_bytes);
+  return tiled_workspace_bytes(layer->d, layer->m, layer->jt, layer->n_tiles, B, lut_record_bytes(layer->value_repr), layer->blob_bytes) +
+         (layer->value_repr == LUTKAN_REPR_SPLINE_COMPONENT ? lutkan::base_product_workspace_bytes(layer->d, layer->m) : 0);
 }
 
 extern "C" int lutkan_forward(const lutkan_dev_layer *layer, const float *x, int64_t B, float *y,

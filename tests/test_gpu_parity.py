@@ -619,6 +619,49 @@ def test_spline_component_layers(case):
     _check_bspline(s, w.x, lk.ALGO_TILED, w.name)
 
 
+BASE_PRODUCT_CASES = [
+    # seed, d, m, G, L, scheme, boundary, oob, B, per_input, param_fp16      batch * d * m >= 5e8, d a multiple of 32, m >= 64
+    (551, 64, 256, 8, 64, SYM_INT8, CLOSED, ZERO_SPLINE, 32768 + 5, False, False),      # ragged last row tile of the product
+    (552, 96, 130, 6, 16, ASYM_UINT8, HALF_OPEN, CLIP_X, 41000, False, False),          # ragged column tile (130 of 256 columns)
+    (553, 32, 64, 5, 32, SYM_INT8, HALF_OPEN, ZERO_SPLINE, 250001, False, True),        # the narrowest product; float16 parameters
+    (554, 128, 128, 5, 32, ASYM_UINT8, CLOSED, CLIP_X, 33000, True, False),             # one knot vector per input
+    (555, 1024, 1024, 10, 64, SYM_INT8, CLOSED, CLIP_X, 2048, False, False),            # the widest layer: inputs split, summing pass adds to y
+]
+
+
+@pytest.mark.parametrize("case", BASE_PRODUCT_CASES, ids=lambda c: f"seed{c[0]}")
+def test_spline_component_with_the_base_branch_as_a_matrix_product(case):
+    """From about 5e8 edge evaluations per call a spline_component layer evaluates its base branch (Eq. 2: s_out * s_base *
+    SiLU(x), summed over the inputs) as one [B, d] x [d, m] product on the matrix cores, fp32 operands as three bf16
+    pieces, and the LUT edge kernel adds the spline branch on top.  Same bar as every other path: k, l0, In, w bit-exact,
+    outputs within the tolerance, on all rows; a NaN input poisons its own row only."""
+    seed, d, m, G, L, scheme, boundary, oob, B, per_input, half = case
+    if per_input:
+        w = per_input_layer(seed, d, m, G, L, scheme, boundary, oob, B, with_base=True)
+    else:
+        w = random_layer(seed, d, m, G, L, scheme, boundary, oob, B, uniform=(seed % 2 == 0), oob_frac=0.3, with_base=True)
+    s = w.layers[0]
+    x = w.x.copy()
+    x[B // 2, d // 3] = np.nan
+    x[B // 3, :] = 30.0                                 # SiLU(x) ~ x
+    x[B // 5, :] = -90.0                                # SiLU(x) underflows to -0
+    _check_layer(s, x, lk.ALGO_AUTO, what=w.name, param_fp16=half)
+    assert "base_product; tiled" in lk.lutkan_last_plan(), lk.lutkan_last_plan()
+    # the same layer through the entry points that take the two phases apart, and through the built-in scratch
+    art, ora = _compile_both(s, half)
+    layer = _device_layer(art, s)
+    xg = torch.from_numpy(x).to(DEV)
+    y_ref = lk.lutkan_forward(layer, xg)
+    ws = torch.empty(lk.lutkan_forward_workspace_bytes(layer, B), dtype=torch.uint8, device=DEV)
+    lk.lutkan_forward_locate(layer, xg, ws)
+    y_two = lk.lutkan_forward_edges(layer, B, torch.full((B, m), 3.0, dtype=torch.float32, device=DEV), ws)
+    same = lambda p, q: bool(((p == q) | (torch.isnan(p) & torch.isnan(q))).all())
+    assert same(y_two, y_ref)
+    if lk.lutkan_forward_workspace_bytes(layer, B) <= lk.STATIC_SCRATCH_BYTES:
+        y_static = lk.lutkan_forward_static_scratch(layer, xg, torch.full((B, m), -3.0, dtype=torch.float32, device=DEV))
+        assert same(y_static, y_ref)
+
+
 @pytest.mark.parametrize("boundary,oob", [(HALF_OPEN, CLIP_X), (HALF_OPEN, ZERO_SPLINE), (CLOSED, CLIP_X), (CLOSED, ZERO_SPLINE)])
 def test_case_a_sweep_shape_spline_component(boundary, oob):
     """The paper's controlled-sweep layer (10->8, grid 8, spline_component) with inputs clipped onto the domain."""

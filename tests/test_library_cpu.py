@@ -105,6 +105,16 @@ def test_device_struct_initialisers():
     assert 78 * 1024 * 8 <= need <= 78 * 1024 * 8 + 32 * 1000 * 16 * 4
     dl.value_repr = 1                                                 # spline_component: 16-byte records (with SiLU(x))
     assert lib.lutkan_forward_workspace_bytes(C.byref(dl), 1000) == need + 78 * 1024 * 8
+    # a shape whose base branch can run as a matrix product (d a multiple of 32, m >= 64) also needs room for the three
+    # bf16 pieces of s_out * s_base, columns padded to 128
+    wide = random_layer(7, 64, 200, 5, 16, SYM_INT8, CLOSED, CLIP_X, 4, with_base=True).layers[0]
+    wide_art = lk.lutkan_compile(wide.d, wide.m, wide.G, wide.p, wide.ext_knots, wide.coef, wide.L, wide.scheme, wide.boundary,
+                                 wide.oob, edge_scales=wide.edge_scales)
+    wl = binding._DevLayer()
+    assert lib.lutkan_dev_layer_init(wide_art._h, C.byref(wl)) == 0
+    with_pieces = lib.lutkan_forward_workspace_bytes(C.byref(wl), 1000)
+    wl.value_repr = 0
+    assert with_pieces - lib.lutkan_forward_workspace_bytes(C.byref(wl), 1000) == 64 * 1024 * 8 + 6 * 256 * 64
     dl.value_repr = 0
     assert lib.lutkan_forward_workspace_bytes(C.byref(dl), 0) == 0
     assert I_tK_star(art, CLOSED) == art.knots[-1]
