@@ -216,21 +216,22 @@ __global__ __launch_bounds__(NW * 64) void bspline_tiled_kernel(const SplineEdge
 #pragma unroll
     for (int c = 0; c < 4; ++c) acc[p][c] = 0.0f;
 
-  const u32x4 *src = reinterpret_cast<const u32x4 *>(a.coef_table + (size_t)t * a.d * a.rows * JT);
+  const unsigned char *src = reinterpret_cast<const unsigned char *>(a.coef_table + (size_t)t * a.d * a.rows * JT);   // slice (t, 0); wave-uniform
   // a wave's RW 32-byte records are 2*RW consecutive 16-byte vectors: lanes 0..63 take the first 64, then the rest
-  const u32x4 *rec_src = a.rec + b0 * 2;
+  const unsigned char *rec_src = reinterpret_cast<const unsigned char *>(a.rec + b0 * 2);                            // wave-uniform
+  const unsigned lane_off = lane * 16;
   unsigned char *rec_area = lds + 2 * blob_bytes + wave * (2 * RW * 32);
   auto stage_records = [&](int i, unsigned char *dst) {
-    const u32x4 *g = rec_src + (int64_t)i * a.Bp * 2;
-    if (lane < 2 * RW) copy16_global_to_lds(g + lane, dst);
-    if (2 * RW > 64 && lane + 64 < 2 * RW) copy16_global_to_lds(g + 64 + lane, dst + 1024);
+    const unsigned char *g = rec_src + (int64_t)i * a.Bp * 32;
+    if (lane < 2 * RW) copy16_global_to_lds_at(g, lane_off, dst);
+    if (2 * RW > 64 && lane + 64 < 2 * RW) copy16_global_to_lds_at(g + 1024, lane_off, dst + 1024);
   };
 
   const int i_begin = blockIdx.y * a.chunk;
   const int i_end = min(a.d, i_begin + a.chunk);
   float *yout = a.y + (int64_t)blockIdx.y * a.split_stride;
 
-  stage_slice<NW>(src + (size_t)i_begin * nvec, lds, nvec, wave, lane);
+  stage_slice<NW>(src + (size_t)i_begin * blob_bytes, lds, nvec, wave, lane, lane_off);
   stage_records(i_begin, rec_area);
   wait_all_vector_loads();
   __syncthreads();
@@ -238,7 +239,7 @@ __global__ __launch_bounds__(NW * 64) void bspline_tiled_kernel(const SplineEdge
   for (int i = i_begin; i < i_end; ++i) {
     const int cur = (i - i_begin) & 1;
     if (i + 1 < i_end) {
-      stage_slice<NW>(src + (size_t)(i + 1) * nvec, lds + (cur ^ 1) * blob_bytes, nvec, wave, lane);
+      stage_slice<NW>(src + (size_t)(i + 1) * blob_bytes, lds + (cur ^ 1) * blob_bytes, nvec, wave, lane, lane_off);
       stage_records(i + 1, rec_area + (cur ^ 1) * (RW * 32));
     }
     const unsigned char *rec_buf = rec_area + cur * (RW * 32) + hrow * 32;

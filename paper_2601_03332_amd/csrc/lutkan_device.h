@@ -58,6 +58,14 @@ __device__ __forceinline__ void copy16_global_to_lds(const void *gsrc, void *lds
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(gsrc) : "m0", "memory");
 }
 
+// The same copy with the address split the way the instruction can take it: a wave-uniform 64-bit base in scalar
+// registers plus a 32-bit byte offset per lane.  With the lane offsets of a wave fixed (16 * lane) the address of every
+// copy of a walk is scalar arithmetic only: no vector instruction is spent on staging.
+__device__ __forceinline__ void copy16_global_to_lds_at(const void *uniform_base, unsigned lane_byte_offset, void *lds_dst) {
+  const unsigned dst = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(__attribute__((address_space(3))) void *)lds_dst);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(lane_byte_offset), "s"(uniform_base) : "m0", "memory");
+}
+
 __device__ __forceinline__ void wait_all_vector_loads() { __builtin_amdgcn_s_waitcnt(0x0f70); }   // vmcnt(0)
 
 // Work-group barrier that orders LDS traffic only (__syncthreads() also drains the wave's global-memory traffic).
@@ -67,13 +75,15 @@ __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-// Copies n16 16-byte vectors from gsrc to lds_dst with all NW waves of the work-group, 1 KiB per wave step.
+// Copies n16 16-byte vectors from gsrc (wave-uniform) to lds_dst with all NW waves of the work-group, 1 KiB per wave
+// step: wave w takes the whole chunks w, w + NW, ...; the last, partial chunk goes to the wave whose turn it is.
+// lane_off = 16 * lane.
 template <int NW>
-__device__ __forceinline__ void stage_slice(const u32x4 *gsrc, unsigned char *lds_dst, int n16, int wave, int lane) {
-  for (int c = wave; c * 64 < n16; c += NW) {
-    const int v = c * 64 + lane;
-    if (v < n16) copy16_global_to_lds(gsrc + v, lds_dst + c * 1024);
-  }
+__device__ __forceinline__ void stage_slice(const unsigned char *gsrc, unsigned char *lds_dst, int n16, int wave, int lane, unsigned lane_off) {
+  const int whole = n16 >> 6;
+  for (int c = wave; c < whole; c += NW) copy16_global_to_lds_at(gsrc + c * 1024, lane_off, lds_dst + c * 1024);
+  const int tail = n16 & 63;
+  if (tail != 0 && wave == (whole % NW) && lane < tail) copy16_global_to_lds_at(gsrc + whole * 1024, lane_off, lds_dst + whole * 1024);
 }
 
 // Sums the n_split partial outputs of the tiled kernels in ascending chunk order (deterministic): y = sum_s part[s],

@@ -456,8 +456,9 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
 #pragma unroll
     for (int c = 0; c < 4; ++c) acc[p][c] = 0.0f;
 
-  const u32x4 *src = reinterpret_cast<const u32x4 *>(a.table + (size_t)t * a.d * a.blob_bytes);
-  const unsigned char *rec_src = static_cast<const unsigned char *>(a.rec) + b0 * RB + (lane < REC_LANES ? lane : 0) * 16;
+  const unsigned char *src = a.table + (size_t)t * a.d * a.blob_bytes;                   // slice (t, 0); wave-uniform
+  const unsigned char *rec_src = static_cast<const unsigned char *>(a.rec) + b0 * RB;     // this wave's records of input 0; wave-uniform
+  const unsigned lane_off = lane * 16;
   unsigned char *rec_area = lds + 2 * a.blob_bytes + wave * (2 * RW * RB);
 
   // this work-group walks the inputs [i_begin, i_end) and writes one set of (partial) sums
@@ -465,16 +466,16 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
   const int i_end = min(a.d, i_begin + a.chunk);
   float *yout = a.y + (int64_t)blockIdx.y * a.split_stride;
 
-  stage_slice<NW>(src + (size_t)i_begin * nvec, lds, nvec, wave, lane);
-  if (lane < REC_LANES) copy16_global_to_lds(rec_src + (int64_t)i_begin * a.Bp * RB, rec_area);
+  stage_slice<NW>(src + (size_t)i_begin * a.blob_bytes, lds, nvec, wave, lane, lane_off);
+  if (lane < REC_LANES) copy16_global_to_lds_at(rec_src + (int64_t)i_begin * a.Bp * RB, lane_off, rec_area);
   wait_all_vector_loads();
   __syncthreads();
 
   for (int i = i_begin; i < i_end; ++i) {
     const int cur = (i - i_begin) & 1;
     if (i + 1 < i_end) {                               // stream the next input's slice and records
-      stage_slice<NW>(src + (size_t)(i + 1) * nvec, lds + (cur ^ 1) * a.blob_bytes, nvec, wave, lane);
-      if (lane < REC_LANES) copy16_global_to_lds(rec_src + (int64_t)(i + 1) * a.Bp * RB, rec_area + (cur ^ 1) * (RW * RB));
+      stage_slice<NW>(src + (size_t)(i + 1) * a.blob_bytes, lds + (cur ^ 1) * a.blob_bytes, nvec, wave, lane, lane_off);
+      if (lane < REC_LANES) copy16_global_to_lds_at(rec_src + (int64_t)(i + 1) * a.Bp * RB, lane_off, rec_area + (cur ^ 1) * (RW * RB));
     }
     const unsigned char *slice = lds + cur * a.blob_bytes;
     const unsigned char *rec_buf = rec_area + cur * (RW * RB) + hrow * RB;
