@@ -59,8 +59,9 @@ typedef enum { LUTKAN_SPAN_DOMAIN = 0, LUTKAN_SPAN_EXTENDED = 1 } lutkan_knot_sp
 const char *lutkan_last_error(void);
 const char *lutkan_version(void);
 /* What the last forward call of this thread launched, for logs and tests: one clause per kernel launch, e.g.
- * "locate; tiled np=16 split=2; sum; " or "chain layers=2 wpr=4; " or "locate; gather split=16; sum; " (model_forward:
- * the clauses of all its layers).  Thread-local, overwritten by the next forward call, never null. */
+ * "locate; tiled np=16 split=2; sum; " or "chain layers=2 wpr=4; " or "locate; gather split=16; sum; " or, for a large
+ * spline_component layer, "locate; base_product; tiled np=16 split=1; " (model_forward: the clauses of all its layers).
+ * Thread-local, overwritten by the next forward call, never null. */
 const char *lutkan_last_plan(void);
 
 /* ------------------------------------------------------------------------------------------------
@@ -218,6 +219,11 @@ size_t bspline_forward_workspace_bytes(const bspline_dev_layer *layer, int64_t B
  *   x          device [B][d] fp32          y   device [B][m] fp32 (overwritten)
  *   stats      device, nullable; the two counters are ADDED to (the caller zeroes them)
  *   workspace  device, >= lutkan_forward_workspace_bytes(layer, B), 256-byte aligned, contents undefined after
+ * value_repr = spline_component (Eq. 2): the base branch s_out * s_base * SiLU(x), summed over the inputs, is evaluated
+ * inside the edge kernel or, from 5e8 edge evaluations per call (d a multiple of 32, m >= 64, tiled kernel), as one
+ * [B, d] x [d, m] product on the matrix cores with every fp32 operand cut exactly into three bf16 pieces (relative error
+ * per term <= 2^-23), on top of which the edge kernel adds the spline branch; the two ways agree to rounding.  With
+ * the product a row that contains an infinite input comes out NaN (edge by edge it may be +-inf).
  * Errors: EINVAL for null/ill-formed arguments, ESHAPE for a short workspace, EHIP if a launch fails. */
 int lutkan_forward(const lutkan_dev_layer *layer, const float *x, int64_t B, float *y,
                    lutkan_oob_stats *stats, void *workspace, size_t workspace_bytes, void *hip_stream);
