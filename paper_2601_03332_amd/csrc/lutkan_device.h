@@ -44,26 +44,31 @@ __device__ __forceinline__ float next_float_below(float t) {
   return __uint_as_float(0x80000001u);                 // below +-0: the smallest negative subnormal
 }
 
-// Asynchronous global -> LDS copy of 16 bytes per lane (gfx950 LDS-DMA form of the global load): the wave's
-// active lanes each fetch 16 bytes from their own global address and the data lands at lds_dst + 16*lane.
-// lds_dst must be wave-uniform (it travels in M0; one wait state separates the M0 write from the load).  M0 is
-// declared clobbered; nothing else in these kernels may keep a value in M0 (a test checks the generated code:
-// saving and restoring M0 around every copy was measured 1.3 % slower on the widest layer).
+// Asynchronous global -> LDS copy of 16 bytes per lane (gfx950 LDS-DMA form of the global load): the wave's active
+// lanes each fetch 16 bytes from (a wave-uniform 64-bit base in scalar registers) + (their own 32-bit byte offset)
+// and the data lands at lds_dst + 16*lane.  With the lane offsets of a wave fixed (16 * lane) the address of every
+// copy of a walk is scalar arithmetic only: no vector instruction is spent on staging.
+// lds_dst must be wave-uniform (it travels in M0; one wait state separates the M0 write from the load).
 // Completion is tracked by vmcnt like any other vector memory load.  The copy is written out as instructions
 // rather than through the compiler's builtin: for the builtin the compiler makes the wave wait for all its
 // outstanding copies before any later LDS read and before every barrier, because it cannot tell the stage
 // buffers apart; here the kernel waits itself (wait_all_vector_loads) before it reads what a copy wrote.
-__device__ __forceinline__ void copy16_global_to_lds(const void *gsrc, void *lds_dst) {
-  const unsigned dst = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(__attribute__((address_space(3))) void *)lds_dst);
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(gsrc) : "m0", "memory");
-}
+//
+// M0: by default the helper overwrites it and declares it clobbered, which is sound as long as nothing else in these
+// kernels keeps a value in M0 across a copy (a CPU-side test checks the generated code for that).  Should a compiler
+// ever start doing so, set kLdsDmaPreservesM0: the copy then saves M0 in a scalar register and restores it (measured
+// 1.3 % slower on the widest layer).
+constexpr bool kLdsDmaPreservesM0 = false;
 
-// The same copy with the address split the way the instruction can take it: a wave-uniform 64-bit base in scalar
-// registers plus a 32-bit byte offset per lane.  With the lane offsets of a wave fixed (16 * lane) the address of every
-// copy of a walk is scalar arithmetic only: no vector instruction is spent on staging.
 __device__ __forceinline__ void copy16_global_to_lds_at(const void *uniform_base, unsigned lane_byte_offset, void *lds_dst) {
   const unsigned dst = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(__attribute__((address_space(3))) void *)lds_dst);
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(lane_byte_offset), "s"(uniform_base) : "m0", "memory");
+  if constexpr (kLdsDmaPreservesM0) {
+    unsigned saved;
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3\n\ts_mov_b32 m0, %0"
+                 : "=&s"(saved) : "s"(dst), "v"(lane_byte_offset), "s"(uniform_base) : "memory");
+  } else {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(lane_byte_offset), "s"(uniform_base) : "m0", "memory");
+  }
 }
 
 __device__ __forceinline__ void wait_all_vector_loads() { __builtin_amdgcn_s_waitcnt(0x0f70); }   // vmcnt(0)
