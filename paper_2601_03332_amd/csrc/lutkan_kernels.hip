@@ -426,9 +426,19 @@ constexpr double kBaseProductMinEdges = 5e8;      // batch * d * m from which th
 // With PH the dequantisation parameters are binary16 values: half the LDS bytes per edge; they enter the same FMAs
 // through the mixed-precision form (fp16 factor, fp32 product and sum), so the arithmetic is that of the fp32 path
 // on the stored values.
-template <int SCHEME, int LPR, int NP, int NW, bool BASE, bool PH>
+//
+// STAGES = 3 (no BASE, NP >= 2; chosen when three slice buffers fit the LDS) takes the barrier out of the critical
+// path.  With two buffers every input ends in "wait for my copies, barrier", and every wave then refills its
+// read pipeline (record -> addresses -> codes and scales, two LDS round trips) at the same moment, with nothing
+// else on the SIMD to cover it.  With three, the slice of input i+2 is copied while input i is processed; the one
+// barrier per input (before input i: "everyone has finished input i-1", so its buffer may be overwritten, and
+// "everyone's share of slice i+1 has landed", waited for one whole input after the copies were issued) no longer
+// guards the data the wave is about to read, so the read pipeline runs on from the last row steps of input i into
+// the first of input i+1 without a refill.
+template <int SCHEME, int LPR, int NP, int NW, bool BASE, bool PH, int STAGES>
 __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a) {
   static_assert(!(BASE && PH), "with the base branch the device table holds fp32 products, never binary16 parameters");
+  static_assert(STAGES == 2 || (STAGES == 3 && !BASE && NP >= 2), "three stages: no base branch, and the read pipeline needs two row steps of the same input");
   extern __shared__ __align__(16) unsigned char lds[];
   constexpr int JT = 4 * LPR;
   constexpr int RPS = 64 / LPR;
@@ -459,70 +469,109 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
   const unsigned char *src = a.table + (size_t)t * a.d * a.blob_bytes;                   // slice (t, 0); wave-uniform
   const unsigned char *rec_src = static_cast<const unsigned char *>(a.rec) + b0 * RB;     // this wave's records of input 0; wave-uniform
   const unsigned lane_off = lane * 16;
-  unsigned char *rec_area = lds + 2 * a.blob_bytes + wave * (2 * RW * RB);
+  unsigned char *rec_area = lds + STAGES * a.blob_bytes + wave * (STAGES * RW * RB);
 
   // this work-group walks the inputs [i_begin, i_end) and writes one set of (partial) sums
   const int i_begin = blockIdx.y * a.chunk;
   const int i_end = min(a.d, i_begin + a.chunk);
   float *yout = a.y + (int64_t)blockIdx.y * a.split_stride;
 
-  stage_slice<NW>(src + (size_t)i_begin * a.blob_bytes, lds, nvec, wave, lane, lane_off);
-  if (lane < REC_LANES) copy16_global_to_lds_at(rec_src + (int64_t)i_begin * a.Bp * RB, lane_off, rec_area);
+  // copies slice (t, i) and this wave's records of input i into buffer `buf`
+  auto stage_input = [&](int i, int buf) {
+    stage_slice<NW>(src + (size_t)i * a.blob_bytes, lds + buf * a.blob_bytes, nvec, wave, lane, lane_off);
+    if (lane < REC_LANES) copy16_global_to_lds_at(rec_src + (int64_t)i * a.Bp * RB, lane_off, rec_area + buf * (RW * RB));
+  };
+  stage_input(i_begin, 0);
+  if (STAGES == 3 && i_begin + 1 < i_end) stage_input(i_begin + 1, 1);
   wait_all_vector_loads();
   __syncthreads();
 
+  // Software pipeline over the row steps.  The reads of step p+1 (codes, parameters) and the record of
+  // step p+2 are issued before the arithmetic of step p, and they are issued right AFTER the one point per
+  // step where the wave waits for its outstanding LDS reads (the first touch of step p's data): what the
+  // wave waits for was issued a whole step earlier, what it issues now has a whole step to arrive.
+  typedef typename std::conditional<BASE, u32x3, u32x2>::type rec_t;        // 12-byte or 8-byte LDS read
+  // parameters of the lane's 4 columns as loaded: pa = the four alphas, pb = the four y_min (asymmetric);
+  // binary16 parameters are packed two per word in .x and .y
+  struct Fetched { unsigned c0, c1; f32x4 pa, pb; };
+  // col_codes / col_params: LDS byte addresses of this lane's columns in code row 0 and parameter row 0 of a slice
+  auto fetch = [&](const rec_t &rc, unsigned col_codes, unsigned col_params) {
+    Fetched f;
+    // address = column address + (16-bit half of the record word) * (bytes per row): D = S0.u16 * S1.u16 + S2
+    unsigned code_addr, param_addr;
+    asm("v_mad_u32_u16 %0, %1, %2, %3 op_sel:[0,0,0,0]" : "=v"(code_addr) : "v"(rc.x), "s"(JT), "v"(col_codes));
+    asm("v_mad_u32_u16 %0, %1, %2, %3 op_sel:[1,0,0,0]" : "=v"(param_addr) : "v"(rc.x), "s"(a.param_row_bytes), "v"(col_params));
+    lds_bytes cp = (lds_bytes)(uintptr_t)code_addr;
+    lds_bytes pp = (lds_bytes)(uintptr_t)param_addr;
+    typedef const __attribute__((address_space(3))) unsigned *lds_u32;
+    typedef const __attribute__((address_space(3))) f32x4 *lds_f32x4;
+    f.c0 = *(lds_u32)cp;
+    f.c1 = *(lds_u32)(cp + JT);
+    f.pb = f32x4{0.f, 0.f, 0.f, 0.f};
+    if constexpr (PH) {
+      typedef const __attribute__((address_space(3))) f32x2 *lds_f32x2;
+      const f32x2 ha = *(lds_f32x2)pp;
+      f.pa = f32x4{ha.x, ha.y, 0.f, 0.f};
+      if (SCHEME == LUTKAN_ASYM_UINT8) {
+        const f32x2 hy = *(lds_f32x2)(pp + PLANE);
+        f.pb = f32x4{hy.x, hy.y, 0.f, 0.f};
+      }
+    } else {
+      f.pa = *(lds_f32x4)pp;
+      if (SCHEME == LUTKAN_ASYM_UINT8) f.pb = *(lds_f32x4)(pp + PLANE);
+    }
+    return f;
+  };
+  auto columns_of = [&](int buf, unsigned &col_codes, unsigned &col_params) {
+    const unsigned slice_addr = (unsigned)(uintptr_t)(lds_bytes)(lds + buf * a.blob_bytes);
+    col_codes = slice_addr + (unsigned)a.codes_off + sub * 4;
+    col_params = slice_addr + (unsigned)a.params_off + sub * PSZ;
+  };
+
+  // carried from one input to the next with three stages; refilled at the top of every input with two
+  rec_t rc_cur, rc_nxt;
+  Fetched f_cur;
+  int cur = 0;                                         // buffer of input i
+  if (STAGES == 3) {
+    unsigned cc, cp;
+    columns_of(0, cc, cp);
+    const unsigned char *rec_buf = rec_area + hrow * RB;
+    rc_cur = *reinterpret_cast<const rec_t *>(rec_buf);
+    rc_nxt = *reinterpret_cast<const rec_t *>(rec_buf + RPS * RB);
+    f_cur = fetch(rc_cur, cc, cp);
+  }
+
   for (int i = i_begin; i < i_end; ++i) {
-    const int cur = (i - i_begin) & 1;
-    if (i + 1 < i_end) {                               // stream the next input's slice and records
-      stage_slice<NW>(src + (size_t)(i + 1) * a.blob_bytes, lds + (cur ^ 1) * a.blob_bytes, nvec, wave, lane, lane_off);
-      if (lane < REC_LANES) copy16_global_to_lds_at(rec_src + (int64_t)(i + 1) * a.Bp * RB, lane_off, rec_area + (cur ^ 1) * (RW * RB));
+    // two stages: the other buffer; three: the next of the ring, and the one after it for the copies
+    const int nxt = (STAGES == 2) ? (cur ^ 1) : (cur == 2 ? 0 : cur + 1);
+    if (STAGES == 2) {
+      if (i + 1 < i_end) stage_input(i + 1, nxt);                  // stream the next input's slice and records
+    } else {
+      // My share of slice i+1, copied during input i-1, has landed; after the barrier everyone's has, and everyone has
+      // finished input i-1, whose buffer now takes the slice of input i+2.  The reads this wave has in flight (the
+      // first row steps of input i) stay in flight: the barrier is the bare instruction, without the wait for LDS
+      // traffic that a fence would add.
+      wait_all_vector_loads();
+      asm volatile("s_barrier" ::: "memory");
+      if (i + 2 < i_end) stage_input(i + 2, nxt == 2 ? 0 : nxt + 1);
     }
     const unsigned char *slice = lds + cur * a.blob_bytes;
     const unsigned char *rec_buf = rec_area + cur * (RW * RB) + hrow * RB;
-    // LDS byte addresses of this lane's columns in code row 0 and parameter row 0 of the slice
-    const unsigned slice_addr = (unsigned)(uintptr_t)(lds_bytes)slice;
-    const unsigned col_codes = slice_addr + (unsigned)a.codes_off + sub * 4;
-    const unsigned col_params = slice_addr + (unsigned)a.params_off + sub * PSZ;
-    // Software pipeline over the NP row steps.  The reads of step p+1 (codes, parameters) and the record of
-    // step p+2 are issued before the arithmetic of step p, and they are issued right AFTER the one point per
-    // step where the wave waits for its outstanding LDS reads (the first touch of step p's data): what the
-    // wave waits for was issued a whole step earlier, what it issues now has a whole step to arrive.
-    typedef typename std::conditional<BASE, u32x3, u32x2>::type rec_t;        // 12-byte or 8-byte LDS read
+    unsigned col_codes, col_params;
+    columns_of(cur, col_codes, col_params);
+    // three stages: where the reads for the next input's first row steps go.  After the last input they re-read this
+    // input's buffers (valid records and rows, results unused).
+    const int ahead = (STAGES == 3 && i + 1 < i_end) ? nxt : cur;
+    const unsigned char *rec_ahead = rec_area + ahead * (RW * RB) + hrow * RB;
+    unsigned ahead_codes = col_codes, ahead_params = col_params;
+    if (STAGES == 3) columns_of(ahead, ahead_codes, ahead_params);
     f32x4 base_gain = {0.f, 0.f, 0.f, 0.f};
     if (BASE) base_gain = *reinterpret_cast<const f32x4 *>(slice + sub * 16) * kTwoToMinus24;
-    // parameters of the lane's 4 columns as loaded: pa = the four alphas, pb = the four y_min (asymmetric);
-    // binary16 parameters are packed two per word in .x and .y
-    struct Fetched { unsigned c0, c1; f32x4 pa, pb; };
-    auto fetch = [&](const rec_t &rc) {
-      Fetched f;
-      // address = column address + (16-bit half of the record word) * (bytes per row): D = S0.u16 * S1.u16 + S2
-      unsigned code_addr, param_addr;
-      asm("v_mad_u32_u16 %0, %1, %2, %3 op_sel:[0,0,0,0]" : "=v"(code_addr) : "v"(rc.x), "s"(JT), "v"(col_codes));
-      asm("v_mad_u32_u16 %0, %1, %2, %3 op_sel:[1,0,0,0]" : "=v"(param_addr) : "v"(rc.x), "s"(a.param_row_bytes), "v"(col_params));
-      lds_bytes cp = (lds_bytes)(uintptr_t)code_addr;
-      lds_bytes pp = (lds_bytes)(uintptr_t)param_addr;
-      typedef const __attribute__((address_space(3))) unsigned *lds_u32;
-      typedef const __attribute__((address_space(3))) f32x4 *lds_f32x4;
-      f.c0 = *(lds_u32)cp;
-      f.c1 = *(lds_u32)(cp + JT);
-      f.pb = f32x4{0.f, 0.f, 0.f, 0.f};
-      if constexpr (PH) {
-        typedef const __attribute__((address_space(3))) f32x2 *lds_f32x2;
-        const f32x2 ha = *(lds_f32x2)pp;
-        f.pa = f32x4{ha.x, ha.y, 0.f, 0.f};
-        if (SCHEME == LUTKAN_ASYM_UINT8) {
-          const f32x2 hy = *(lds_f32x2)(pp + PLANE);
-          f.pb = f32x4{hy.x, hy.y, 0.f, 0.f};
-        }
-      } else {
-        f.pa = *(lds_f32x4)pp;
-        if (SCHEME == LUTKAN_ASYM_UINT8) f.pb = *(lds_f32x4)(pp + PLANE);
-      }
-      return f;
-    };
-    rec_t rc_cur = *reinterpret_cast<const rec_t *>(rec_buf);
-    rec_t rc_nxt = *reinterpret_cast<const rec_t *>(rec_buf + (NP > 1 ? RPS * RB : 0));
-    Fetched f_cur = fetch(rc_cur);
+    if (STAGES == 2) {
+      rc_cur = *reinterpret_cast<const rec_t *>(rec_buf);
+      rc_nxt = *reinterpret_cast<const rec_t *>(rec_buf + (NP > 1 ? RPS * RB : 0));
+      f_cur = fetch(rc_cur, col_codes, col_params);
+    }
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
       Fetched f_nxt = f_cur;
@@ -531,7 +580,9 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
       asm volatile("" ::"v"(f_cur.pa.x), "v"(f_cur.c1), "v"(rc_nxt.y));        // first touch of step p's data
       __builtin_amdgcn_sched_barrier(0);
       if (p + 2 < NP) rc_nn = *reinterpret_cast<const rec_t *>(rec_buf + (p + 2) * (RPS * RB));
-      if (p + 1 < NP) f_nxt = fetch(rc_nxt);
+      else if (STAGES == 3) rc_nn = *reinterpret_cast<const rec_t *>(rec_ahead + (p + 2 - NP) * (RPS * RB));
+      if (p + 1 < NP) f_nxt = fetch(rc_nxt, col_codes, col_params);
+      else if (STAGES == 3) f_nxt = fetch(rc_nxt, ahead_codes, ahead_params);
       __builtin_amdgcn_sched_barrier(0);
       const float w = __uint_as_float(rc_cur.y);
       float al[4], ym[4];
@@ -579,8 +630,11 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
       rc_nxt = rc_nn;
       f_cur = f_nxt;
     }
-    wait_all_vector_loads();                           // my share of the next slice has landed ...
-    lds_barrier();                                     // ... everyone's has, and everyone is done with this one
+    if (STAGES == 2) {
+      wait_all_vector_loads();                         // my share of the next slice has landed ...
+      lds_barrier();                                   // ... everyone's has, and everyone is done with this one
+    }
+    cur = nxt;
   }
 
   const int j = t * JT + sub * 4;
@@ -816,11 +870,19 @@ int launch_tiled_np(const EdgeArgs &ea, hipStream_t s) {
   const int64_t row_tiles = (ea.B + NW * RW - 1) / (NW * RW);
   if (row_tiles * ea.n_tiles > 0x7fffffffLL) return fail(LUTKAN_EUNSUPPORTED, "lutkan_tiled_kernel: B * m too large for one launch");
   const dim3 grid((unsigned)(row_tiles * ea.n_tiles), (unsigned)((ea.d + ea.chunk - 1) / ea.chunk));
+  static LdsCap raised, raised_base, raised_half, raised3, raised3_half;
+  // three slice and record buffers where they fit (and the kernel has that form): the barrier leaves the critical path
+  const size_t lds3 = 3 * (size_t)ea.blob_bytes + (size_t)NW * 3 * RW * 8;
+  if constexpr (NP >= 2) {
+    if (!ea.with_base && lds3 <= (size_t)kMaxTiledLds) {
+      if (ea.param_fp16) return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, false, true, 3>, &raised3_half, grid, lds3, s, ea, "lutkan_tiled_kernel");
+      return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, false, false, 3>, &raised3, grid, lds3, s, ea, "lutkan_tiled_kernel");
+    }
+  }
   const size_t lds = 2 * (size_t)ea.blob_bytes + (size_t)NW * 2 * RW * (ea.with_base ? 16 : 8);
-  static LdsCap raised, raised_base, raised_half;
-  if (ea.with_base) return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, true, false>, &raised_base, grid, lds, s, ea, "lutkan_tiled_kernel");
-  if (ea.param_fp16) return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, false, true>, &raised_half, grid, lds, s, ea, "lutkan_tiled_kernel");
-  return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, false, false>, &raised, grid, lds, s, ea, "lutkan_tiled_kernel");
+  if (ea.with_base) return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, true, false, 2>, &raised_base, grid, lds, s, ea, "lutkan_tiled_kernel");
+  if (ea.param_fp16) return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, false, true, 2>, &raised_half, grid, lds, s, ea, "lutkan_tiled_kernel");
+  return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, false, false, 2>, &raised, grid, lds, s, ea, "lutkan_tiled_kernel");
 }
 
 template <int SCHEME, int LPR>
