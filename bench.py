@@ -100,11 +100,15 @@ def kernel_costs(info, spec, B, plan):
                             valu=(30 + K) * B * d))
         elif clause.startswith("tiled"):
             np_, last_split = nums
+            wide = clause.startswith("tiled wide")                      # the table form with 16-bit codes: its code rows are twice as long
             rows_per_group = 16 * (64 // (info.jt // 4)) * np_
-            staged = -(-B // rows_per_group) * info.table_bytes + info.n_tiles * rec * Bp * d
-            per4 = (20 if asym else 18) + (4 if base else 0)            # vector instructions per 4 edges
-            lds_per4 = (12 if base else 8) + 8 + (32 if asym else 16)   # record, two code dwords, alpha (+ y_min) per lane
-            out.append(dict(kernel="lutkan_tiled_kernel", hbm=info.table_bytes + rec * Bp * d + 4 * B * m * last_split,
+            table_bytes = info.table_bytes + (info.n_tiles * d * (K * info.L + 2) * info.jt if wide else 0)
+            staged = -(-B // rows_per_group) * table_bytes + info.n_tiles * rec * Bp * d
+            # vector instructions per 4 edges: two addresses, [four byte permutes, two bias removals (int8)], two code
+            # differences, four interpolations, four scalings [, four y_min] [, four base products]
+            per4 = ((16 if asym else 12) if wide else (20 if asym else 18)) + (4 if base else 0)
+            lds_per4 = (12 if base else 8) + (16 if wide else 8) + (32 if asym else 16)   # record, two code rows, alpha (+ y_min) per lane
+            out.append(dict(kernel="lutkan_tiled_kernel", hbm=table_bytes + rec * Bp * d + 4 * B * m * last_split,
                             l2=staged, lds=edges / 4 * lds_per4 + staged, valu=edges / 4 * per4))
         elif clause.startswith("gather"):
             last_split = nums[0]

@@ -43,8 +43,10 @@ typedef enum { LUTKAN_CLIP_X = 0, LUTKAN_ZERO_SPLINE = 1 } lutkan_oob;          
  * from global memory and splits the inputs over the GPU.  AUTO: tiled when a slice fits LDS, except for batches of so
  * few rows that they touch less than the whole table (then gather), and except for a small narrow layer (one column
  * tile, d * jt <= 4096) at up to 8192 rows, which lutkan_forward runs as a one-layer launch of the fused chain kernel;
- * results agree to rounding, not bit for bit. */
-typedef enum { LUTKAN_ALGO_AUTO = 0, LUTKAN_ALGO_GATHER = 1, LUTKAN_ALGO_TILED = 2 } lutkan_algo;
+ * results agree to rounding, not bit for bit.  TILED (and AUTO) take the table's wide form, where the layer holds one
+ * (lutkan_wide_table_build), when the launch planning prices it lower; TILED_WIDE takes it whatever the price and is
+ * an error for a layer without one or a call it does not serve (16-byte records).  LUT layers only. */
+typedef enum { LUTKAN_ALGO_AUTO = 0, LUTKAN_ALGO_GATHER = 1, LUTKAN_ALGO_TILED = 2, LUTKAN_ALGO_TILED_WIDE = 3 } lutkan_algo;
 typedef enum { LUTKAN_REPR_PHI = 0, LUTKAN_REPR_SPLINE_COMPONENT = 1 } lutkan_value_repr;  /* Sec. 4.3 A / B */
 typedef enum { LUTKAN_PARAM_FP32 = 0, LUTKAN_PARAM_FP16 = 1 } lutkan_param_dtype;   /* Sec. 4.6: dtype of scale, y_min */
 /* Which knots are the LUT's "knot grid" (Sec. 4.2): the G+1 breakpoints of the domain [ext_knots[p], ext_knots[p+G]]
@@ -189,6 +191,9 @@ typedef struct {
   const void *table;                  /* device, lutkan_info.table_bytes bytes, 16-byte aligned */
   int32_t knots_per_input;            /* 1: every input is located on its own row of input_knots */
   const float *input_knots;           /* device fp32 [d][K+1], a verbatim copy of lutkan_artifact_knots; NULL if shared */
+  /* Optional second copy of the LUT table with 16-bit codes (see lutkan_wide_table_build); NULL / 0: none. */
+  const void *wide_table;             /* device, lutkan_wide_table_bytes() bytes, 16-byte aligned */
+  int32_t wide_blob_bytes;            /* bytes of one (tile, input) slice of the wide table */
 } lutkan_dev_layer;
 
 typedef struct {
@@ -204,6 +209,24 @@ typedef struct {
 /* Fills every field of the device structs from an artifact except the device pointers (set to NULL). */
 int lutkan_dev_layer_init(const lutkan_artifact *a, lutkan_dev_layer *out);
 int bspline_dev_layer_init(const lutkan_artifact *a, bspline_dev_layer *out);
+
+/* The wide form of the LUT device table: the same slices ([base][parameter rows][code rows], the same tiles, ordered
+ * [t][i]) with every code held as the binary16 value q * 2^-24 (sign and magnitude; a subnormal, whose bit pattern is
+ * the magnitude of the code) instead of one byte.  The tiled kernel then reads a lane's codes as packed binary16 pairs
+ * and spends no instruction on unpacking bytes or on the excess-128 bias: 12 vector instructions per four edges
+ * instead of 18 (16 instead of 20 with y_min), on the same arithmetic, bit for bit (Eq. 10 + Eq. 17).  The codes stay
+ * 8-bit values; the form costs device memory (two bytes per code beside the byte table, which the other kernels keep
+ * using) and more LDS traffic per edge.  It exists for layers on 64-column tiles whose wide slice still fits the
+ * LDS twice (K*L up to about 540 rows): on narrower tiles the LDS reads, not the instructions, bound the kernel and
+ * the form is slower.  A forward call uses it on the tiled kernel when its launch planning prices it below the byte
+ * form (which it does unless the table streams from HBM and the batch is small).
+ * lutkan_wide_table_bytes: size of the wide table, 0 for a layer that has none.
+ * lutkan_wide_table_build: fills `wide_table` (device, 16-byte aligned, at least that many bytes) from layer->table on
+ * `hip_stream` and sets layer->wide_table and wide_blob_bytes; the layer may be used on that stream right away, on
+ * others after the stream has been synchronised.  The memory stays the caller's.  Errors: EINVAL (null / misaligned
+ * pointers, bad layer), ESHAPE (bytes too small), EUNSUPPORTED (no wide form), EHIP. */
+size_t lutkan_wide_table_bytes(const lutkan_dev_layer *layer);
+int lutkan_wide_table_build(lutkan_dev_layer *layer, void *wide_table, size_t bytes, void *hip_stream);
 
 /* Sec. 5.5 / 5.6 counters: inputs (b,i) with In(x) = 0, and rows with at least one such input. */
 typedef struct { unsigned long long oob_count, oob_any_rows; } lutkan_oob_stats;

@@ -14,7 +14,7 @@ from . import build as _build
 SYM_INT8, ASYM_UINT8 = 0, 1
 HALF_OPEN, CLOSED = 0, 1
 CLIP_X, ZERO_SPLINE = 0, 1
-ALGO_AUTO, ALGO_GATHER, ALGO_TILED = 0, 1, 2
+ALGO_AUTO, ALGO_GATHER, ALGO_TILED, ALGO_TILED_WIDE = 0, 1, 2, 3
 PARAM_FP32, PARAM_FP16 = 0, 1
 SPAN_DOMAIN, SPAN_EXTENDED = 0, 1
 PROBE_VALU_FMA, PROBE_LDS_READ, PROBE_L2_READ, PROBE_HBM_READ, PROBE_VALU_MIX = 0, 1, 2, 3, 4
@@ -55,7 +55,7 @@ class _DevLayer(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("d", "m", "K", "L", "scheme", "boundary", "oob", "value_repr", "param_dtype",
                                          "jt", "n_tiles", "blob_bytes", "algo")] + \
                [("knots", C.c_float * (MAX_K + 1)), ("table", C.c_void_p), ("knots_per_input", C.c_int32),
-                ("input_knots", C.c_void_p)]
+                ("input_knots", C.c_void_p), ("wide_table", C.c_void_p), ("wide_blob_bytes", C.c_int32)]
 
 
 class _SplineDevLayer(C.Structure):
@@ -75,6 +75,7 @@ EXPORTS = [
     "lutkan_model_workspace_bytes", "lutkan_model_forward", "lutkan_chain_forward", "lutkan_forward_locate", "lutkan_forward_edges",
     "bspline_forward_locate", "bspline_forward_edges", "lutkan_probe_launch", "lutkan_artifact_from_arrays",
     "lutkan_error_stats_workspace_bytes", "lutkan_error_stats", "lutkan_forward_static_scratch",
+    "lutkan_wide_table_bytes", "lutkan_wide_table_build",
 ]
 
 _lib = None
@@ -108,6 +109,9 @@ def load_library():
         f.restype = vp
     lib.lutkan_dev_layer_init.argtypes = [vp, C.POINTER(_DevLayer)]
     lib.bspline_dev_layer_init.argtypes = [vp, C.POINTER(_SplineDevLayer)]
+    lib.lutkan_wide_table_bytes.argtypes = [C.POINTER(_DevLayer)]
+    lib.lutkan_wide_table_bytes.restype = sz
+    lib.lutkan_wide_table_build.argtypes = [C.POINTER(_DevLayer), vp, sz, vp]
     lib.lutkan_forward_workspace_bytes.argtypes = [C.POINTER(_DevLayer), i64]
     lib.lutkan_forward_workspace_bytes.restype = sz
     lib.bspline_forward_workspace_bytes.argtypes = [C.POINTER(_SplineDevLayer), i64]
@@ -244,8 +248,10 @@ class Artifact:
             np.savez_compressed(f, manifest=np.frombuffer(json.dumps(manifest, sort_keys=True).encode(), dtype=np.uint8),
                                 **arrays)
 
-    def to_device(self, device="cuda:0", algo: int = ALGO_AUTO) -> "LutLayer":
-        return LutLayer(self, device, algo)
+    def to_device(self, device="cuda:0", algo: int = ALGO_AUTO, wide: Optional[bool] = None) -> "LutLayer":
+        """wide: also hold the table's wide form (16-bit codes; lutkan_wide_table_build).  None: for layers of at
+        least 4096 edges that have one."""
+        return LutLayer(self, device, algo, wide)
 
     def bspline_to_device(self, device="cuda:0", algo: int = ALGO_AUTO) -> "BsplineLayer":
         return BsplineLayer(self, device, algo)
@@ -341,9 +347,10 @@ def _upload(arr: np.ndarray, device):
 class LutLayer:
     """Device-side LUT layer: the lutkan_dev_layer struct plus the torch tensor that owns its table."""
 
-    def __init__(self, art: Artifact, device, algo: int = ALGO_AUTO):
+    def __init__(self, art: Artifact, device, algo: int = ALGO_AUTO, wide: Optional[bool] = None):
+        lib = load_library()
         self.c = _DevLayer()
-        _check(load_library().lutkan_dev_layer_init(art._h, C.byref(self.c)))
+        _check(lib.lutkan_dev_layer_init(art._h, C.byref(self.c)))
         self.c.algo = algo
         self.table = _upload(art.table, device)
         self.c.table = self.table.data_ptr()
@@ -351,6 +358,17 @@ class LutLayer:
         self.c.input_knots = self.input_knots.data_ptr() if self.input_knots is not None else None
         self.device = self.table.device
         self.d, self.m = self.c.d, self.c.m
+        self.wide_table = None
+        n_wide = lib.lutkan_wide_table_bytes(C.byref(self.c))
+        if wide is None:
+            wide = n_wide > 0 and self.d * self.m >= 4096
+        if wide:
+            torch = _torch()
+            if n_wide == 0:
+                raise LutKanError("this layer has no wide table form")
+            self.wide_table = torch.empty(n_wide, dtype=torch.uint8, device=self.device)
+            with torch.cuda.device(self.device):
+                _check(lib.lutkan_wide_table_build(C.byref(self.c), self.wide_table.data_ptr(), n_wide, _stream(self.device)))
 
     def with_contract(self, boundary: int, oob: int, algo: Optional[int] = None) -> "LutLayer":
         """Same tables under another boundary_mode / oob_policy (the contract is not baked into the codes)."""
@@ -360,7 +378,7 @@ class LutLayer:
         if algo is not None:
             other.c.algo = algo
         other.table, other.device, other.d, other.m = self.table, self.device, self.d, self.m
-        other.input_knots = self.input_knots
+        other.input_knots, other.wide_table = self.input_knots, self.wide_table
         return other
 
 

@@ -142,7 +142,8 @@ int gather_jx_log2(int m) {
 //   one input of one work-group   max(0.55 + 0.11 * NP, slice bytes at 100 GB/s) + 0.1
 //                                 (barrier and address set-up, NP row steps of 256 edges per wave, the slice's
 //                                 global -> LDS copy when that is the longer of the two)
-//   one work-group                3 + its inputs (pipeline fill, accumulator write-back)
+//   one work-group                3 + its inputs (pipeline fill, accumulator write-back); the wide form of the table
+//                                 (16-bit codes: 0.095 * NP per input) adds half its slice at 21 GB/s to the fill
 //   the launch                    rounds of 256 work-groups (one per compute unit), one after the other
 //   the partial sums              4 + their bytes at 3 TB/s, when there is more than one chunk
 //   a table of more than 128 MiB  at least its bytes at 21 GB/s per work-group and 5.3 TB/s in all (it streams from
@@ -155,7 +156,8 @@ struct TilePlan {
   double cost;       // the model's estimate for the launch (and its summing pass), microseconds
 };
 
-TilePlan plan_tiles(int64_t B, int d, int m, int n_tiles, int rps, int slice_bytes) {
+// wide: the slices are those of the table's wide form (16-bit codes), whose row steps take fewer instructions.
+TilePlan plan_tiles(int64_t B, int d, int m, int n_tiles, int rps, int slice_bytes, bool wide = false) {
   const int np_max = std::min(16, 64 / rps);
   const int max_split = std::max(1, std::min(128, d / 8));
   TilePlan best{np_max, 1, d, 1e300};
@@ -164,10 +166,13 @@ TilePlan plan_tiles(int64_t B, int d, int m, int n_tiles, int rps, int slice_byt
   // 5.3 TB/s for the whole chip
   const double table_bytes = (double)n_tiles * d * slice_bytes;
   const bool streams_from_hbm = table_bytes > 128.0 * 1024 * 1024;
+  // a work-group's first slice arrives before it computes anything; the wide form's is twice as long (measured on a
+  // 256x256 layer at 512 rows, 8 inputs per work-group: 0.030 -> 0.037 ms on the wide form)
+  const double fill = 3.0 + (wide ? 0.5 * slice_bytes / 21e3 : 0.0);
   for (int np = np_max; np >= 1; np >>= 1) {
     const int64_t rows = (int64_t)kTileWaves * rps * np;
     const int64_t groups = (B + rows - 1) / rows * n_tiles;
-    const double per_input = std::max(0.55 + 0.11 * np, slice_bytes / 100e3) + 0.1;
+    const double per_input = std::max(0.55 + (wide ? 0.095 : 0.11) * np, slice_bytes / 100e3) + 0.1;
     // candidate chunk counts: 1 .. 8, then the counts that fill whole rounds of 256 work-groups, and the cap
     int candidates[16];
     int n_candidates = 0;
@@ -179,9 +184,14 @@ TilePlan plan_tiles(int64_t B, int d, int m, int n_tiles, int rps, int slice_byt
       const int chunk = (d + want - 1) / want;
       const int split = (d + chunk - 1) / chunk;      // no empty trailing chunks
       const double rounds = (double)((groups * split + 255) / 256);
-      double cost = rounds * (3.0 + chunk * per_input);
-      if (streams_from_hbm)           // once per row tile; ties go to the smaller row tile (fewer padding rows)
-        cost = std::max(cost, (double)(groups / n_tiles) * table_bytes / std::min(5.3e6, 21e3 * (double)std::min<int64_t>(256, groups * split))) + 0.01 * np;
+      double cost = rounds * (fill + chunk * per_input);
+      if (streams_from_hbm) {         // ties go to the smaller row tile (fewer padding rows)
+        // within one round of work-groups: once per row tile (measured at a few hundred to a few thousand rows);
+        // over several rounds: once per round, the row tiles of a round walk the inputs together and share what
+        // they read through the caches
+        const double passes = rounds > 1.0 ? rounds : (double)(groups / n_tiles);
+        cost = std::max(cost, passes * table_bytes / std::min(5.3e6, 21e3 * (double)std::min<int64_t>(256, groups * split))) + 0.01 * np;
+      }
       if (split > 1) cost += 4.0 + (double)split * (double)B * m * 4.0 / 3e6;
       if (cost < best_cost) { best_cost = cost; best = TilePlan{np, split, chunk, cost}; }
     }
@@ -234,9 +244,9 @@ int launch_with_lds(Kern kern, LdsCap *cap, const dim3 &grid, size_t lds, hipStr
 }
 
 // Records for every (input, padded row), then room for the partial sums when the inputs are split into chunks.
-size_t tiled_workspace_bytes(int d, int m, int jt, int n_tiles, int64_t B, int bytes_per_record, int slice_bytes) {
+size_t tiled_workspace_bytes(int d, int m, int jt, int n_tiles, int64_t B, int bytes_per_record, int slice_bytes, bool wide = false) {
   size_t bytes = record_bytes(d, padded_rows(B), bytes_per_record);
-  const TilePlan tp = plan_tiles(B, d, m, n_tiles, 64 / (jt / 4), slice_bytes);
+  const TilePlan tp = plan_tiles(B, d, m, n_tiles, 64 / (jt / 4), slice_bytes, wide);
   // any of the kernels may run (tiled, gather with one column per lane, gather with four): room for the largest set
   const GatherPlan gp = plan_gather(B, d, m), gp4 = plan_gather(B, d, n_tiles * jt / 4);
   const int n_split = std::max(tp.n_split, std::max(gp.n_split, gp4.n_split));

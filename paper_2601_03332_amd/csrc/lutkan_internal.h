@@ -57,6 +57,21 @@ inline int lds_slice_budget(int value_repr) {
   return (kLdsPerWorkGroup - 16 * 2 * 64 * record_bytes) / 2;
 }
 
+// The wide form of the LUT table (two bytes per code, see lutkan_wide_table_build): the same slice layout with code
+// rows of jw binary16 values.
+inline BlobLayout wide_blob_layout(int K, int L, int jw, int scheme, int value_repr, int param_dtype) {
+  BlobLayout b = blob_layout(K, L, jw, scheme, value_repr, param_dtype);
+  b.bytes = (b.codes_off + (K * L + 2) * jw * 2 + 15) & ~15;
+  return b;
+}
+// A layer has a wide form when its table is on 64-column tiles and the wide slice fits twice into the LDS beside the
+// record buffers of the 8-byte records it is used with.  (On 32-column tiles the kernel's LDS reads come in eight
+// short runs per wave and bound it: measured 12 % slower than the byte form on the 1024x1024 layer, whose wide
+// slices only fit at that width.)
+inline bool has_wide_form(int jt, int K, int L, int scheme, int value_repr, int param_dtype) {
+  return jt == 64 && wide_blob_layout(K, L, jt, scheme, value_repr, param_dtype).bytes <= lds_slice_budget(LUTKAN_REPR_PHI);
+}
+
 // Column-tile width of a layer's LUT table: the widest power of two in 4 .. 64 (not wider than the next power of two
 // >= m) whose slice fits the LDS budget; a table of 4096 rows still runs on the tiled kernel, 8 columns at a time,
 // twice as fast as on the gather kernel.  If not even 4 columns fit: 32 (or the layer's width), for the gather kernel.

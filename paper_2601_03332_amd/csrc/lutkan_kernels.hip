@@ -218,6 +218,7 @@ struct EdgeArgs {
   int32_t chunk;           // tiled kernels: inputs per work-group (blockIdx.y selects the chunk of inputs)
   int64_t split_stride;    // tiled kernels: floats between the partial outputs of consecutive chunks (0 if one chunk)
   int32_t accumulate;      // tiled kernel writing y itself (one chunk): add to what y holds (the base branch) instead of overwriting
+  int32_t wide;            // tiled kernel: table, jt, n_tiles, blob_bytes and the offsets describe the wide form (16-bit codes)
 };
 
 // Device-table byte -> code value.  Symmetric int8 codes are stored excess-128 (byte = q + 128).
@@ -435,18 +436,25 @@ constexpr double kBaseProductMinEdges = 5e8;      // batch * d * m from which th
 // "everyone's share of slice i+1 has landed", waited for one whole input after the copies were issued) no longer
 // guards the data the wave is about to read, so the read pipeline runs on from the last row steps of input i into
 // the first of input i+1 without a refill.
-template <int SCHEME, int LPR, int NP, int NW, bool BASE, bool PH, int STAGES>
+//
+// WIDE: the slices come from the wide form of the table, whose codes are binary16 values already (q * 2^-24, signed):
+// a lane reads its four codes of a row as two packed pairs, and the permutes and the bias removal fall away; the
+// arithmetic after them is the same.
+template <int SCHEME, int LPR, int NP, int NW, bool BASE, bool PH, int STAGES, bool WIDE>
 __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a) {
   static_assert(!(BASE && PH), "with the base branch the device table holds fp32 products, never binary16 parameters");
+  static_assert(!(BASE && WIDE), "the wide form is used with 8-byte records only");
+  constexpr int CB = WIDE ? 2 : 1;         // bytes per code
   static_assert(STAGES == 2 || (STAGES == 3 && !BASE && NP >= 2), "three stages: no base branch, and the read pipeline needs two row steps of the same input");
   extern __shared__ __align__(16) unsigned char lds[];
   constexpr int JT = 4 * LPR;
   constexpr int RPS = 64 / LPR;
   constexpr int RW = RPS * NP;
-  static_assert(RW <= 64, "a wave's records for one input must fit one 1 KiB copy step");
+
   constexpr int PSZ = PH ? 8 : 16;         // bytes of a lane's four alphas (and of its four y_min, one plane further)
   constexpr int PLANE = JT * (PH ? 2 : 4); // a parameter row is the alpha plane, then (asymmetric) the y_min plane
   constexpr int RB = BASE ? 16 : 8;                              // bytes per record
+  static_assert(RW <= 64, "a wave's records for one input must fit one 1 KiB copy step");
   constexpr int REC_LANES = RW * RB / 16;                        // lanes that copy 16 bytes of the wave's records
   static_assert((RW * RB) % 16 == 0, "a wave's records are whole 16-byte vectors");
   typedef const __attribute__((address_space(3))) unsigned char *lds_bytes;
@@ -493,20 +501,27 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
   typedef typename std::conditional<BASE, u32x3, u32x2>::type rec_t;        // 12-byte or 8-byte LDS read
   // parameters of the lane's 4 columns as loaded: pa = the four alphas, pb = the four y_min (asymmetric);
   // binary16 parameters are packed two per word in .x and .y
-  struct Fetched { unsigned c0, c1; f32x4 pa, pb; };
+  struct Fetched { unsigned c0, c1, c0b, c1b; f32x4 pa, pb; };                // c0b, c1b: columns 2 and 3 of a wide row
   // col_codes / col_params: LDS byte addresses of this lane's columns in code row 0 and parameter row 0 of a slice
   auto fetch = [&](const rec_t &rc, unsigned col_codes, unsigned col_params) {
     Fetched f;
     // address = column address + (16-bit half of the record word) * (bytes per row): D = S0.u16 * S1.u16 + S2
     unsigned code_addr, param_addr;
-    asm("v_mad_u32_u16 %0, %1, %2, %3 op_sel:[0,0,0,0]" : "=v"(code_addr) : "v"(rc.x), "s"(JT), "v"(col_codes));
+    asm("v_mad_u32_u16 %0, %1, %2, %3 op_sel:[0,0,0,0]" : "=v"(code_addr) : "v"(rc.x), "s"(JT * CB), "v"(col_codes));
     asm("v_mad_u32_u16 %0, %1, %2, %3 op_sel:[1,0,0,0]" : "=v"(param_addr) : "v"(rc.x), "s"(a.param_row_bytes), "v"(col_params));
     lds_bytes cp = (lds_bytes)(uintptr_t)code_addr;
     lds_bytes pp = (lds_bytes)(uintptr_t)param_addr;
     typedef const __attribute__((address_space(3))) unsigned *lds_u32;
     typedef const __attribute__((address_space(3))) f32x4 *lds_f32x4;
-    f.c0 = *(lds_u32)cp;
-    f.c1 = *(lds_u32)(cp + JT);
+    if constexpr (WIDE) {
+      typedef const __attribute__((address_space(3))) u32x2 *lds_u32x2;
+      const u32x2 r0 = *(lds_u32x2)cp, r1 = *(lds_u32x2)(cp + JT * CB);
+      f.c0 = r0.x; f.c0b = r0.y; f.c1 = r1.x; f.c1b = r1.y;
+    } else {
+      f.c0 = *(lds_u32)cp;
+      f.c1 = *(lds_u32)(cp + JT);
+      f.c0b = 0; f.c1b = 0;
+    }
     f.pb = f32x4{0.f, 0.f, 0.f, 0.f};
     if constexpr (PH) {
       typedef const __attribute__((address_space(3))) f32x2 *lds_f32x2;
@@ -524,7 +539,7 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
   };
   auto columns_of = [&](int buf, unsigned &col_codes, unsigned &col_params) {
     const unsigned slice_addr = (unsigned)(uintptr_t)(lds_bytes)(lds + buf * a.blob_bytes);
-    col_codes = slice_addr + (unsigned)a.codes_off + sub * 4;
+    col_codes = slice_addr + (unsigned)a.codes_off + sub * (4 * CB);
     col_params = slice_addr + (unsigned)a.params_off + sub * PSZ;
   };
 
@@ -595,13 +610,19 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
         al[0] = f_cur.pa.x; al[1] = f_cur.pa.y; al[2] = f_cur.pa.z; al[3] = f_cur.pa.w;
         ym[0] = f_cur.pb.x; ym[1] = f_cur.pb.y; ym[2] = f_cur.pb.z; ym[3] = f_cur.pb.w;
       }
-      // bytes {b3,b2,b1,b0} -> packed fp16 denormals {b1,b0} and {b3,b2}, each worth byte * 2^-24
-      f16x2 q0lo = bits_to_f16x2(__builtin_amdgcn_perm(f_cur.c0, f_cur.c0, 0x0c010c00u));
-      f16x2 q0hi = bits_to_f16x2(__builtin_amdgcn_perm(f_cur.c0, f_cur.c0, 0x0c030c02u));
-      const f16x2 q1lo = bits_to_f16x2(__builtin_amdgcn_perm(f_cur.c1, f_cur.c1, 0x0c010c00u));
-      const f16x2 q1hi = bits_to_f16x2(__builtin_amdgcn_perm(f_cur.c1, f_cur.c1, 0x0c030c02u));
+      f16x2 q0lo, q0hi, q1lo, q1hi;
+      if constexpr (WIDE) {                                                    // the table holds q * 2^-24 as it is needed
+        q0lo = bits_to_f16x2(f_cur.c0); q0hi = bits_to_f16x2(f_cur.c0b);
+        q1lo = bits_to_f16x2(f_cur.c1); q1hi = bits_to_f16x2(f_cur.c1b);
+      } else {
+        // bytes {b3,b2,b1,b0} -> packed fp16 denormals {b1,b0} and {b3,b2}, each worth byte * 2^-24
+        q0lo = bits_to_f16x2(__builtin_amdgcn_perm(f_cur.c0, f_cur.c0, 0x0c010c00u));
+        q0hi = bits_to_f16x2(__builtin_amdgcn_perm(f_cur.c0, f_cur.c0, 0x0c030c02u));
+        q1lo = bits_to_f16x2(__builtin_amdgcn_perm(f_cur.c1, f_cur.c1, 0x0c010c00u));
+        q1hi = bits_to_f16x2(__builtin_amdgcn_perm(f_cur.c1, f_cur.c1, 0x0c030c02u));
+      }
       const f16x2 dlo = q1lo - q0lo, dhi = q1hi - q0hi;                        // (q1 - q0) * 2^-24, exact
-      if (SCHEME == LUTKAN_SYM_INT8) {                                         // remove the excess-128 bias, exact
+      if (SCHEME == LUTKAN_SYM_INT8 && !WIDE) {                                // remove the excess-128 bias, exact
         const f16x2 bias = bits_to_f16x2(0x00800080u);
         q0lo = q0lo - bias;
         q0hi = q0hi - bias;
@@ -834,7 +855,7 @@ int validate_layer(const lutkan_dev_layer *l, const char *who) {
   if (l->scheme != LUTKAN_SYM_INT8 && l->scheme != LUTKAN_ASYM_UINT8) return fail(LUTKAN_EINVAL, "%s: bad scheme %d", who, l->scheme);
   if (l->boundary != LUTKAN_HALF_OPEN && l->boundary != LUTKAN_CLOSED) return fail(LUTKAN_EINVAL, "%s: bad boundary_mode %d", who, l->boundary);
   if (l->oob != LUTKAN_CLIP_X && l->oob != LUTKAN_ZERO_SPLINE) return fail(LUTKAN_EINVAL, "%s: bad oob_policy %d", who, l->oob);
-  if (l->algo < LUTKAN_ALGO_AUTO || l->algo > LUTKAN_ALGO_TILED) return fail(LUTKAN_EINVAL, "%s: bad algo %d", who, l->algo);
+  if (l->algo < LUTKAN_ALGO_AUTO || l->algo > LUTKAN_ALGO_TILED_WIDE) return fail(LUTKAN_EINVAL, "%s: bad algo %d", who, l->algo);
   if (l->value_repr != LUTKAN_REPR_PHI && l->value_repr != LUTKAN_REPR_SPLINE_COMPONENT) return fail(LUTKAN_EINVAL, "%s: bad value_repr %d", who, l->value_repr);
   if (l->param_dtype != LUTKAN_PARAM_FP32 && l->param_dtype != LUTKAN_PARAM_FP16) return fail(LUTKAN_EINVAL, "%s: bad param_dtype %d", who, l->param_dtype);
   for (int k = 0; k < l->K; ++k)
@@ -843,6 +864,11 @@ int validate_layer(const lutkan_dev_layer *l, const char *who) {
   if (l->n_tiles != (l->m + l->jt - 1) / l->jt) return fail(LUTKAN_ESHAPE, "%s: n_tiles does not match m and jt", who);
   if (l->blob_bytes != lutkan::blob_layout(l->K, l->L, l->jt, l->scheme, l->value_repr, l->param_dtype).bytes) return fail(LUTKAN_ESHAPE, "%s: blob_bytes does not match K, L, jt, scheme, param_dtype", who);
   if ((reinterpret_cast<uintptr_t>(l->table) & 15) != 0) return fail(LUTKAN_EINVAL, "%s: table must be 16-byte aligned", who);
+  if (l->wide_table) {
+    if (!lutkan::has_wide_form(l->jt, l->K, l->L, l->scheme, l->value_repr, l->param_dtype)) return fail(LUTKAN_EINVAL, "%s: wide_table set on a layer that has no wide form", who);
+    if (l->wide_blob_bytes != lutkan::wide_blob_layout(l->K, l->L, l->jt, l->scheme, l->value_repr, l->param_dtype).bytes) return fail(LUTKAN_ESHAPE, "%s: wide_blob_bytes does not match K, L, jt, scheme, param_dtype", who);
+    if ((reinterpret_cast<uintptr_t>(l->wide_table) & 15) != 0) return fail(LUTKAN_EINVAL, "%s: wide_table must be 16-byte aligned", who);
+  }
   if (l->knots_per_input != 0 && l->knots_per_input != 1) return fail(LUTKAN_EINVAL, "%s: bad knots_per_input %d", who, l->knots_per_input);
   if (l->knots_per_input && (!l->input_knots || (reinterpret_cast<uintptr_t>(l->input_knots) & 3) != 0))
     return fail(LUTKAN_EINVAL, "%s: knots_per_input needs layer.input_knots (device, 4-byte aligned)", who);
@@ -870,19 +896,28 @@ int launch_tiled_np(const EdgeArgs &ea, hipStream_t s) {
   const int64_t row_tiles = (ea.B + NW * RW - 1) / (NW * RW);
   if (row_tiles * ea.n_tiles > 0x7fffffffLL) return fail(LUTKAN_EUNSUPPORTED, "lutkan_tiled_kernel: B * m too large for one launch");
   const dim3 grid((unsigned)(row_tiles * ea.n_tiles), (unsigned)((ea.d + ea.chunk - 1) / ea.chunk));
-  static LdsCap raised, raised_base, raised_half, raised3, raised3_half;
   // three slice and record buffers where they fit (and the kernel has that form): the barrier leaves the critical path
   const size_t lds3 = 3 * (size_t)ea.blob_bytes + (size_t)NW * 3 * RW * 8;
+  const size_t lds = 2 * (size_t)ea.blob_bytes + (size_t)NW * 2 * RW * (ea.with_base ? 16 : 8);
+#define LUTKAN_LAUNCH_TILED(BASE, PH, STAGES, WIDE, BYTES)                                                                       \
+  do {                                                                                                                           \
+    static LdsCap raised;                                                                                                        \
+    return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, BASE, PH, STAGES, WIDE>, &raised, grid, BYTES, s, ea, "lutkan_tiled_kernel"); \
+  } while (0)
+  if (ea.with_base) {
+    if (ea.wide) return fail(LUTKAN_EINVAL, "lutkan_tiled_kernel: the wide table goes with 8-byte records");
+    LUTKAN_LAUNCH_TILED(true, false, 2, false, lds);
+  }
   if constexpr (NP >= 2) {
-    if (!ea.with_base && lds3 <= (size_t)kMaxTiledLds) {
-      if (ea.param_fp16) return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, false, true, 3>, &raised3_half, grid, lds3, s, ea, "lutkan_tiled_kernel");
-      return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, false, false, 3>, &raised3, grid, lds3, s, ea, "lutkan_tiled_kernel");
+    if (lds3 <= (size_t)kMaxTiledLds) {
+      if (ea.wide) { if (ea.param_fp16) LUTKAN_LAUNCH_TILED(false, true, 3, true, lds3); else LUTKAN_LAUNCH_TILED(false, false, 3, true, lds3); }
+      if (ea.param_fp16) LUTKAN_LAUNCH_TILED(false, true, 3, false, lds3); else LUTKAN_LAUNCH_TILED(false, false, 3, false, lds3);
     }
   }
-  const size_t lds = 2 * (size_t)ea.blob_bytes + (size_t)NW * 2 * RW * (ea.with_base ? 16 : 8);
-  if (ea.with_base) return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, true, false, 2>, &raised_base, grid, lds, s, ea, "lutkan_tiled_kernel");
-  if (ea.param_fp16) return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, false, true, 2>, &raised_half, grid, lds, s, ea, "lutkan_tiled_kernel");
-  return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, false, false, 2>, &raised, grid, lds, s, ea, "lutkan_tiled_kernel");
+  if (ea.wide) { if (ea.param_fp16) LUTKAN_LAUNCH_TILED(false, true, 2, true, lds); else LUTKAN_LAUNCH_TILED(false, false, 2, true, lds); }
+  if (ea.param_fp16) LUTKAN_LAUNCH_TILED(false, true, 2, false, lds);
+  LUTKAN_LAUNCH_TILED(false, false, 2, false, lds);
+#undef LUTKAN_LAUNCH_TILED
 }
 
 template <int SCHEME, int LPR>
@@ -1007,7 +1042,8 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   if (l->algo == LUTKAN_ALGO_GATHER) tiled = false;
   const TilePlan tp = tiled ? plan_tiles(B, l->d, l->m, l->n_tiles, 64 / (l->jt / 4), l->blob_bytes) : TilePlan{1, 1, l->d, 0.0};
   if (l->algo == LUTKAN_ALGO_AUTO && tiled && prefer_gather_for_small_batch(l, B, tp.cost)) tiled = false;
-  if (l->algo == LUTKAN_ALGO_TILED && !tiled) return fail(LUTKAN_EUNSUPPORTED, "%s: tiled kernel needs a table slice <= 72 KiB (64 KiB with the base branch)", who);
+  const bool tiled_asked_for = (l->algo == LUTKAN_ALGO_TILED || l->algo == LUTKAN_ALGO_TILED_WIDE);
+  if (tiled_asked_for && !tiled) return fail(LUTKAN_EUNSUPPORTED, "%s: tiled kernel needs a table slice <= 72 KiB (64 KiB with the base branch)%s", who, q01_out ? " and writes no code trace" : "");
   // Base branch as a matrix product of its own (SiLU(X) times the s_out*s_base of the table's base rows, into y) with
   // the edge kernel of a phi layer adding the spline branch on top.  Measured against the base FMAs inside the edge
   // kernel (four per four edges, 16-byte records): 1024x1024 at 32768 rows 5.87 -> 5.47 ms (uint8 codes 6.67 -> 5.97),
@@ -1015,6 +1051,13 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   // 2048 rows 0.056 -> 0.071 (three more launches): hence the floor on the work of the layer.
   const bool base_by_product = with_base && tiled && (double)B * l->d * l->m >= kBaseProductMinEdges && lutkan::base_product_fits(l->d, l->m, B);
   const int rec_bytes = (with_base && !base_by_product) ? 16 : 8;
+  // The wide form of the table (16-bit codes, a third fewer vector instructions per edge, twice the table bytes),
+  // where the layer has one and the launch planning prices it lower.
+  const bool can_wide = tiled && l->wide_table != nullptr && rec_bytes == 8;
+  const TilePlan tpw = can_wide ? plan_tiles(B, l->d, l->m, l->n_tiles, 64 / (l->jt / 4), l->wide_blob_bytes, true) : tp;
+  const bool wide = can_wide && (tpw.cost < tp.cost || l->algo == LUTKAN_ALGO_TILED_WIDE);
+  if (l->algo == LUTKAN_ALGO_TILED_WIDE && !wide)
+    return fail(LUTKAN_EUNSUPPORTED, "%s: algo TILED_WIDE on a layer %s", who, l->wide_table ? "whose base branch runs inside the edge kernel (16-byte records)" : "without a wide table");
   // workspace: [records: room for 16 bytes each with the base branch; 8-byte records leave room for the 6 bytes per
   // (row, input) of the SiLU pieces behind them] [pieces of s_out*s_base, spline_component only] [partial sums]
   char *const ws_bytes = static_cast<char *>(workspace);
@@ -1069,6 +1112,7 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   ea.with_base = (rec_bytes == 16); ea.k_out = k_out; ea.l0_out = l0_out;
   ea.param_fp16 = lutkan::device_params_are_half(l->value_repr, l->param_dtype, l->jt);
   ea.accumulate = 0;
+  ea.wide = 0;
   ea.chunk = l->d;
   ea.split_stride = 0;
   if (base_by_product) {
@@ -1076,15 +1120,21 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
     lutkan::plan_note("base_product; ");
   }
   if (tiled) {
-    ea.chunk = tp.chunk;
-    if (tp.n_split > 1) { ea.y = partials; ea.split_stride = B * l->m; }
-    ea.accumulate = (base_by_product && tp.n_split == 1) ? 1 : 0;       // with chunks, the summing pass adds to y instead
-    const int rc = (l->scheme == LUTKAN_SYM_INT8) ? launch_tiled_jt<LUTKAN_SYM_INT8>(ea, tp.np, s) : launch_tiled_jt<LUTKAN_ASYM_UINT8>(ea, tp.np, s);
+    const TilePlan &plan = wide ? tpw : tp;
+    if (wide) {
+      ea.table = static_cast<const unsigned char *>(l->wide_table);       // same tiles, offsets and parameters, longer code rows
+      ea.blob_bytes = l->wide_blob_bytes;
+      ea.wide = 1;
+    }
+    ea.chunk = plan.chunk;
+    if (plan.n_split > 1) { ea.y = partials; ea.split_stride = B * l->m; }
+    ea.accumulate = (base_by_product && plan.n_split == 1) ? 1 : 0;     // with chunks, the summing pass adds to y instead
+    const int rc = (l->scheme == LUTKAN_SYM_INT8) ? launch_tiled_jt<LUTKAN_SYM_INT8>(ea, plan.np, s) : launch_tiled_jt<LUTKAN_ASYM_UINT8>(ea, plan.np, s);
     if (rc) return rc;
-    lutkan::plan_note("tiled np=%d split=%d; ", tp.np, tp.n_split);
-    if (tp.n_split == 1) return rc;
+    lutkan::plan_note("tiled%s np=%d split=%d; ", wide ? " wide" : "", plan.np, plan.n_split);
+    if (plan.n_split == 1) return rc;
     const int64_t n = B * l->m;
-    hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, s, partials, y, n, tp.n_split, base_by_product ? 1 : 0);
+    hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, s, partials, y, n, plan.n_split, base_by_product ? 1 : 0);
     lutkan::plan_note("sum; ");
     return check_launch("sum_partials_kernel");
   }
@@ -1142,8 +1192,73 @@ extern "C" size_t lutkan_forward_workspace_bytes(const lutkan_dev_layer *layer, 
   // would divide by zero in the launch planning)
   if (!layer || B <= 0 || layer->d < 1 || layer->m < 1 || layer->n_tiles < 1 || layer->blob_bytes < 1) return 0;
   if (layer->jt < 4 || layer->jt > 64 || (layer->jt & (layer->jt - 1))) return 0;
-  return tiled_workspace_bytes(layer->d, layer->m, layer->jt, layer->n_tiles, B, lut_record_bytes(layer->value_repr), layer->blob_bytes) +
-         (layer->value_repr == LUTKAN_REPR_SPLINE_COMPONENT ? lutkan::base_product_workspace_bytes(layer->d, layer->m) : 0);
+  size_t bytes = tiled_workspace_bytes(layer->d, layer->m, layer->jt, layer->n_tiles, B, lut_record_bytes(layer->value_repr), layer->blob_bytes);
+  if (layer->wide_table && layer->wide_blob_bytes >= 1)
+    bytes = std::max(bytes, tiled_workspace_bytes(layer->d, layer->m, layer->jt, layer->n_tiles, B, lut_record_bytes(layer->value_repr), layer->wide_blob_bytes, true));
+  return bytes + (layer->value_repr == LUTKAN_REPR_SPLINE_COMPONENT ? lutkan::base_product_workspace_bytes(layer->d, layer->m) : 0);
+}
+
+// ------------------------------------------------------------------------------------------------
+// The wide form of the table.
+// ------------------------------------------------------------------------------------------------
+namespace {
+
+struct WidenArgs {
+  const unsigned char *src;          // byte table, slices [t][i]
+  unsigned char *dst;                // wide table, slices [t][i]
+  int32_t jt, src_blob, dst_blob, codes_off, n_code_rows;
+  int32_t sym;
+};
+
+// One work-group per slice (t, i).  Base row and parameter rows are copied as they are (16 bytes per thread and
+// step: codes_off is a multiple of 16); a code byte becomes the binary16 bit pattern of q * 2^-24: sign bit and, as
+// the subnormal's significand, the magnitude of q.
+__global__ __launch_bounds__(256) void lutkan_widen_kernel(const WidenArgs a) {
+  const unsigned char *src = a.src + (size_t)blockIdx.x * a.src_blob;
+  unsigned char *dst = a.dst + (size_t)blockIdx.x * a.dst_blob;
+  for (int e = threadIdx.x * 16; e < a.codes_off; e += 256 * 16) *reinterpret_cast<u32x4 *>(dst + e) = *reinterpret_cast<const u32x4 *>(src + e);
+  const int n_codes = a.n_code_rows * a.jt;
+  uint16_t *dc = reinterpret_cast<uint16_t *>(dst + a.codes_off);
+  for (int e = threadIdx.x; e < n_codes; e += 256) {
+    const int byte = src[a.codes_off + e];
+    const int q = a.sym ? byte - 128 : byte;
+    dc[e] = (uint16_t)(q < 0 ? (0x8000 | -q) : q);
+  }
+  for (int e = a.codes_off + n_codes * 2 + threadIdx.x; e < a.dst_blob; e += 256) dst[e] = 0;      // padding to 16 bytes
+}
+
+}  // namespace
+
+extern "C" size_t lutkan_wide_table_bytes(const lutkan_dev_layer *layer) {
+  if (!layer || layer->d < 1 || layer->m < 1 || layer->n_tiles < 1 || layer->K < 1 || layer->L < 2 || layer->K > LUTKAN_MAX_K) return 0;
+  if (!lutkan::has_wide_form(layer->jt, layer->K, layer->L, layer->scheme, layer->value_repr, layer->param_dtype)) return 0;
+  return (size_t)layer->n_tiles * layer->d * lutkan::wide_blob_layout(layer->K, layer->L, layer->jt, layer->scheme, layer->value_repr, layer->param_dtype).bytes;
+}
+
+extern "C" int lutkan_wide_table_build(lutkan_dev_layer *layer, void *wide_table, size_t bytes, void *hip_stream) {
+  const char *who = "lutkan_wide_table_build";
+  if (layer) { layer->wide_table = nullptr; layer->wide_blob_bytes = 0; }
+  if (int rc = validate_layer(layer, who)) return rc;
+  const size_t need = lutkan_wide_table_bytes(layer);
+  if (!need) return fail(LUTKAN_EUNSUPPORTED, "%s: the layer has no wide form (64-column tiles whose wide slice fits the LDS twice; jt = %d, K*L = %d)", who, layer->jt, layer->K * layer->L);
+  if (!wide_table || (reinterpret_cast<uintptr_t>(wide_table) & 15) != 0) return fail(LUTKAN_EINVAL, "%s: wide_table must be a 16-byte aligned device pointer", who);
+  if (bytes < need) return fail(LUTKAN_ESHAPE, "%s: %zu bytes, need %zu", who, bytes, need);
+  if ((int64_t)layer->n_tiles * layer->d > 0x7fffffffLL) return fail(LUTKAN_EUNSUPPORTED, "%s: too many slices", who);
+  const lutkan::BlobLayout lay = lutkan::blob_layout(layer->K, layer->L, layer->jt, layer->scheme, layer->value_repr, layer->param_dtype);
+  WidenArgs a;
+  a.src = static_cast<const unsigned char *>(layer->table);
+  a.dst = static_cast<unsigned char *>(wide_table);
+  a.jt = layer->jt;
+  a.src_blob = layer->blob_bytes;
+  a.dst_blob = lutkan::wide_blob_layout(layer->K, layer->L, layer->jt, layer->scheme, layer->value_repr, layer->param_dtype).bytes;
+  a.codes_off = lay.codes_off;
+  a.n_code_rows = layer->K * layer->L + 2;
+  a.sym = (layer->scheme == LUTKAN_SYM_INT8);
+  hipLaunchKernelGGL(lutkan_widen_kernel, dim3((unsigned)((int64_t)layer->n_tiles * layer->d)), dim3(256), 0, static_cast<hipStream_t>(hip_stream), a);
+  if (int rc = check_launch("lutkan_widen_kernel")) return rc;
+  layer->wide_table = wide_table;
+  layer->wide_blob_bytes = a.dst_blob;
+  return LUTKAN_OK;
 }
 
 extern "C" int lutkan_forward(const lutkan_dev_layer *layer, const float *x, int64_t B, float *y,

@@ -48,8 +48,8 @@ def _compile_both(s, param_fp16=False):
     return _COMPILED[key]
 
 
-def _device_layer(art, s, algo=lk.ALGO_AUTO):
-    return art.to_device(DEV, algo).with_contract(s.boundary, s.oob)
+def _device_layer(art, s, algo=lk.ALGO_AUTO, wide=None):
+    return art.to_device(DEV, algo, wide=wide).with_contract(s.boundary, s.oob)
 
 
 def _assert_close(y_gpu, ref, what):
@@ -62,12 +62,12 @@ def _assert_close(y_gpu, ref, what):
     return float(np.nanmax(err / tol))
 
 
-def _check_layer(s, x, algo, codes=False, what="", param_fp16=False):
+def _check_layer(s, x, algo, codes=False, what="", param_fp16=False, wide=None):
     art, ora = _compile_both(s, param_fp16)
-    layer = _device_layer(art, s, algo)
+    layer = _device_layer(art, s, algo, wide)
     xg = torch.from_numpy(x).to(DEV)
     _say(f"case {what} d={s.d} m={s.m} K={s.G} L={s.L} scheme={s.scheme} boundary={s.boundary} oob={s.oob} "
-         f"B={x.shape[0]} algo={algo} jt={art.info.jt} param_fp16={param_fp16}")
+         f"B={x.shape[0]} algo={algo} jt={art.info.jt} param_fp16={param_fp16} wide={wide}")
     y, k, l0, inside, w, q01 = lk.lutkan_forward_trace(layer, xg, codes=codes)
     stats = torch.zeros(2, dtype=torch.int64, device=DEV)
     y2 = lk.lutkan_forward(layer, xg, stats=stats)
@@ -142,6 +142,80 @@ def test_property_layers_tiled(case):
     w = random_layer(seed, d, m, G, L, scheme, boundary, oob, B, uniform=(seed % 2 == 0))
     _check_layer(w.layers[0], w.x, lk.ALGO_TILED, what=w.name)
     _check_layer(w.layers[0], w.x, lk.ALGO_GATHER, what=w.name)
+
+
+WIDE_CASES = [
+    # seed, d, m, G, L, scheme, boundary, oob, B, with_base     64-column tiles whose wide slice (2 bytes per code) fits the LDS twice
+    (701, 17, 128, 5, 32, SYM_INT8, CLOSED, CLIP_X, 700, False),
+    (702, 33, 130, 8, 64, ASYM_UINT8, HALF_OPEN, ZERO_SPLINE, 1025, False),     # 514 code rows: the largest wide slices; ragged last tile
+    (703, 64, 256, 8, 64, SYM_INT8, CLOSED, ZERO_SPLINE, 2500, False),
+    (704, 40, 300, 6, 16, ASYM_UINT8, CLOSED, CLIP_X, 4099, False),
+    (705, 1, 64, 2, 2, ASYM_UINT8, CLOSED, CLIP_X, 1, False),
+    (706, 300, 64, 5, 32, SYM_INT8, HALF_OPEN, CLIP_X, 9000, False),            # many inputs: chunks and the summing pass
+    (707, 3, 1000, 10, 50, SYM_INT8, HALF_OPEN, ZERO_SPLINE, 20000, False),     # 16 column tiles, three slice buffers
+    (708, 64, 128, 5, 32, ASYM_UINT8, CLOSED, CLIP_X, 70000, True),             # spline_component: base branch as a product, 8-byte records
+    (709, 24, 70, 6, 16, SYM_INT8, CLOSED, ZERO_SPLINE, 3000, True),            # spline_component with 16-byte records: the byte form runs
+]
+
+
+@pytest.mark.parametrize("case", WIDE_CASES, ids=lambda c: f"seed{c[0]}")
+def test_wide_table_form(case):
+    """The second form of the device table (16-bit codes: no byte unpacking in the tiled kernel) against the oracle,
+    to the bar of every other path, and against the byte form: the arithmetic after the unpacking is the same, so
+    with the same launch plan the outputs agree bit for bit."""
+    seed, d, m, G, L, scheme, boundary, oob, B, with_base = case
+    w = random_layer(seed, d, m, G, L, scheme, boundary, oob, B, uniform=(seed % 2 == 0), oob_frac=0.3, with_base=with_base)
+    s = w.layers[0]
+    x = w.x.copy()
+    if B > 1:
+        x[B // 2, d // 3] = np.nan
+    art, ora = _compile_both(s)
+    assert art.info.jt == 64
+    wide, byte = _device_layer(art, s, lk.ALGO_TILED_WIDE, wide=True), _device_layer(art, s, lk.ALGO_TILED, wide=False)
+    assert wide.wide_table is not None and byte.wide_table is None
+    assert wide.wide_table.numel() == art.info.table_bytes + art.info.n_tiles * d * (art.info.K * L + 2) * 64
+    xg = torch.from_numpy(x).to(DEV)
+    if with_base and B * d * m < 5e8:
+        # 16-byte records (the base branch inside the edge kernel) go with the byte form only
+        with pytest.raises(lk.LutKanError) as e:
+            lk.lutkan_forward(wide, xg)
+        assert str(e.value).startswith("[-5]") and "16-byte records" in str(e.value)
+        _check_layer(s, x, lk.ALGO_TILED, what=w.name + " (wide table present, byte form runs)", wide=True)
+        assert "tiled np=" in lk.lutkan_last_plan()
+        return
+    worst = _check_layer(s, x, lk.ALGO_TILED_WIDE, what=w.name + " (wide form)", wide=True)
+    y_wide = lk.lutkan_forward(wide, xg)
+    plan_wide = lk.lutkan_last_plan()
+    y_byte = lk.lutkan_forward(byte, xg)
+    plan_byte = lk.lutkan_last_plan()
+    _say(f"wide: {plan_wide!r}  byte: {plan_byte!r}  worst error / tolerance {worst:.3g}")
+    assert "tiled wide np=" in plan_wide and " wide" not in plan_byte
+    if plan_wide.replace("tiled wide", "tiled") == plan_byte:
+        assert bool(((y_wide == y_byte) | (torch.isnan(y_wide) & torch.isnan(y_byte))).all())
+    # the two phases apart, and the entry point with the built-in scratch, take the same form
+    ws = torch.empty(lk.lutkan_forward_workspace_bytes(wide, B), dtype=torch.uint8, device=DEV)
+    lk.lutkan_forward_locate(wide, xg, ws)
+    y_two = lk.lutkan_forward_edges(wide, B, torch.full((B, m), 3.0, dtype=torch.float32, device=DEV), ws)
+    assert bool(((y_two == y_wide) | (torch.isnan(y_two) & torch.isnan(y_wide))).all())
+    if lk.lutkan_forward_workspace_bytes(wide, B) <= lk.STATIC_SCRATCH_BYTES:
+        y_static = lk.lutkan_forward_static_scratch(wide, xg, torch.full((B, m), -3.0, dtype=torch.float32, device=DEV))
+        assert bool(((y_static == y_wide) | (torch.isnan(y_static) & torch.isnan(y_wide))).all())
+    # left to the launch planning, the wide form runs on large batches
+    auto = _device_layer(art, s, lk.ALGO_AUTO, wide=True)
+    lk.lutkan_forward(auto, xg)
+    if B * d * m >= 2e8:
+        assert "tiled wide np=" in lk.lutkan_last_plan(), lk.lutkan_last_plan()
+
+
+def test_wide_table_form_exists_only_where_it_pays():
+    """No wide form on tiles narrower than 64 columns or when two wide slices do not fit the LDS (the widest layer:
+    642 code rows); asking for one is an error, the default upload simply goes without."""
+    for d, m, G, L in ((8, 32, 5, 16), (4, 1024, 10, 64), (4, 256, 8, 128)):
+        w = random_layer(720, d, m, G, L, SYM_INT8, CLOSED, CLIP_X, 8)
+        art, _ = _compile_both(w.layers[0])
+        assert art.to_device(DEV).wide_table is None
+        with pytest.raises(lk.LutKanError):
+            art.to_device(DEV, wide=True)
 
 
 @pytest.mark.parametrize("base", [False, True], ids=["phi", "spline_component"])

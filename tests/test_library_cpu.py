@@ -315,6 +315,58 @@ def test_workspace_queries_return_zero_for_tile_widths_no_kernel_has():
         assert lib.bspline_forward_workspace_bytes(C.byref(bl), 100) == 0, jt
 
 
+def test_wide_table_form_sizes_and_refusals():
+    """The second form of the device table (two bytes per code): which layers have one, how large it is, and what the
+    build call and the forward calls refuse before anything reaches the GPU (the pointers below are stand-ins)."""
+    lib = lk.load_library()
+    rng = np.random.Generator(np.random.PCG64(12))
+
+    def dev_layer(m, G, L, scheme, scales=False):
+        tau = np.linspace(-1.0, 1.0, G + 7).astype(np.float32)
+        art = lk.lutkan_compile(3, m, G, 3, tau, rng.normal(size=(3, m, G + 3)).astype(np.float32), L, scheme, CLOSED, CLIP_X,
+                                edge_scales=draw_edge_scales(rng, 3, m) if scales else None)
+        dl = binding._DevLayer()
+        assert lib.lutkan_dev_layer_init(art._h, C.byref(dl)) == 0
+        assert not dl.wide_table and dl.wide_blob_bytes == 0
+        return art, dl
+
+    for m, G, L, scheme, scales in ((130, 8, 64, SYM_INT8, False), (64, 5, 32, ASYM_UINT8, False), (300, 8, 64, ASYM_UINT8, True)):
+        art, dl = dev_layer(m, G, L, scheme, scales)
+        I = art.info
+        assert I.jt == 64
+        wide_blob = I.blob_bytes + (I.K * L + 2) * 64               # every code one byte longer, the rest of the slice as it is
+        assert wide_blob % 16 == 0 and 2 * wide_blob + 16 * 2 * 64 * 8 <= 160 * 1024
+        assert lib.lutkan_wide_table_bytes(C.byref(dl)) == I.n_tiles * 3 * wide_blob
+    # no wide form: tiles narrower than 64 columns; slices that do not fit the LDS twice (642 and 1026 code rows)
+    for m, G, L in ((32, 5, 16), (16, 8, 64), (128, 10, 64), (128, 8, 128)):
+        art, dl = dev_layer(m, G, L, SYM_INT8)
+        assert lib.lutkan_wide_table_bytes(C.byref(dl)) == 0
+        dl.table = 4096
+        assert lib.lutkan_wide_table_build(C.byref(dl), 8192, 1 << 30, None) == -5 and "no wide form" in lk.lutkan_last_error()
+    assert lib.lutkan_wide_table_bytes(None) == 0
+
+    art, dl = dev_layer(130, 8, 64, SYM_INT8)
+    need = lib.lutkan_wide_table_bytes(C.byref(dl))
+    assert lib.lutkan_wide_table_build(C.byref(dl), 8192, need, None) == -1 and "table is null" in lk.lutkan_last_error()
+    dl.table = 4096
+    assert lib.lutkan_wide_table_build(C.byref(dl), None, need, None) == -1
+    assert lib.lutkan_wide_table_build(C.byref(dl), 8192 + 8, need, None) == -1 and "aligned" in lk.lutkan_last_error()
+    assert lib.lutkan_wide_table_build(C.byref(dl), 8192, need - 1, None) == -2 and str(need) in lk.lutkan_last_error()
+    assert lib.lutkan_wide_table_build(None, 8192, need, None) == -1
+    assert not dl.wide_table and dl.wide_blob_bytes == 0             # a refused build leaves the layer without
+    # a layer whose wide fields do not fit its shape is refused by every forward call
+    ws_bytes = lib.lutkan_forward_workspace_bytes(C.byref(dl), 64)
+    dl.wide_table, dl.wide_blob_bytes = 8192, art.info.blob_bytes
+    assert lib.lutkan_forward(C.byref(dl), 16, 64, 32, None, 256, 1 << 30, None) == -2 and "wide_blob_bytes" in lk.lutkan_last_error()
+    dl.wide_table, dl.wide_blob_bytes = 8192 + 4, art.info.blob_bytes + (art.info.K * 64 + 2) * 64
+    assert lib.lutkan_forward(C.byref(dl), 16, 64, 32, None, 256, 1 << 30, None) == -1 and "wide_table" in lk.lutkan_last_error()
+    dl.wide_table = 8192
+    assert lib.lutkan_forward_workspace_bytes(C.byref(dl), 64) >= ws_bytes
+    _, narrow = dev_layer(32, 5, 16, SYM_INT8)
+    narrow.table, narrow.wide_table, narrow.wide_blob_bytes = 4096, 8192, 4096
+    assert lib.lutkan_forward(C.byref(narrow), 16, 64, 32, None, 256, 1 << 30, None) == -1 and "no wide form" in lk.lutkan_last_error()
+
+
 def test_spline_component_tables_carry_the_base_row_and_folded_gains():
     w = random_layer(77, 3, 70, 5, 16, ASYM_UINT8, CLOSED, ZERO_SPLINE, 4, with_base=True)
     s = w.layers[0]
