@@ -72,6 +72,20 @@ __device__ __forceinline__ void copy16_global_to_lds_at(const void *uniform_base
 }
 
 __device__ __forceinline__ void wait_all_vector_loads() { __builtin_amdgcn_s_waitcnt(0x0f70); }   // vmcnt(0)
+// Waits until at most n (wave-uniform, 0..7; more counts as 0) of the wave's vector memory loads are outstanding.  The
+// count is an immediate of the wait instruction, hence the switch.
+__device__ __forceinline__ void wait_until_vector_loads_outstanding(int n) {
+  switch (n) {
+    case 1: __builtin_amdgcn_s_waitcnt(0x0f71); break;
+    case 2: __builtin_amdgcn_s_waitcnt(0x0f72); break;
+    case 3: __builtin_amdgcn_s_waitcnt(0x0f73); break;
+    case 4: __builtin_amdgcn_s_waitcnt(0x0f74); break;
+    case 5: __builtin_amdgcn_s_waitcnt(0x0f75); break;
+    case 6: __builtin_amdgcn_s_waitcnt(0x0f76); break;
+    case 7: __builtin_amdgcn_s_waitcnt(0x0f77); break;
+    default: __builtin_amdgcn_s_waitcnt(0x0f70); break;
+  }
+}
 
 // Work-group barrier that orders LDS traffic only (__syncthreads() also drains the wave's global-memory traffic).
 __device__ __forceinline__ void lds_barrier() {
@@ -154,13 +168,14 @@ int gather_jx_log2(int m) {
 struct TilePlan {
   int np, n_split, chunk;
   double cost;       // the model's estimate for the launch (and its summing pass), microseconds
+  bool hbm_bound;    // the estimate is the time the table takes to stream from HBM, not the work-groups' own time
 };
 
 // wide: the slices are those of the table's wide form (16-bit codes), whose row steps take fewer instructions.
 TilePlan plan_tiles(int64_t B, int d, int m, int n_tiles, int rps, int slice_bytes, bool wide = false) {
   const int np_max = std::min(16, 64 / rps);
   const int max_split = std::max(1, std::min(128, d / 8));
-  TilePlan best{np_max, 1, d, 1e300};
+  TilePlan best{np_max, 1, d, 1e300, false};
   double best_cost = 1e300;
   // a table beyond what the caches hold streams from HBM once per launch: about 21 GB/s per streaming work-group,
   // 5.3 TB/s for the whole chip
@@ -185,15 +200,18 @@ TilePlan plan_tiles(int64_t B, int d, int m, int n_tiles, int rps, int slice_byt
       const int split = (d + chunk - 1) / chunk;      // no empty trailing chunks
       const double rounds = (double)((groups * split + 255) / 256);
       double cost = rounds * (fill + chunk * per_input);
+      bool hbm_bound = false;
       if (streams_from_hbm) {         // ties go to the smaller row tile (fewer padding rows)
         // within one round of work-groups: once per row tile (measured at a few hundred to a few thousand rows);
         // over several rounds: once per round, the row tiles of a round walk the inputs together and share what
         // they read through the caches
         const double passes = rounds > 1.0 ? rounds : (double)(groups / n_tiles);
-        cost = std::max(cost, passes * table_bytes / std::min(5.3e6, 21e3 * (double)std::min<int64_t>(256, groups * split))) + 0.01 * np;
+        const double stream = passes * table_bytes / std::min(5.3e6, 21e3 * (double)std::min<int64_t>(256, groups * split));
+        hbm_bound = stream > cost;
+        cost = std::max(cost, stream) + 0.01 * np;
       }
       if (split > 1) cost += 4.0 + (double)split * (double)B * m * 4.0 / 3e6;
-      if (cost < best_cost) { best_cost = cost; best = TilePlan{np, split, chunk, cost}; }
+      if (cost < best_cost) { best_cost = cost; best = TilePlan{np, split, chunk, cost, hbm_bound}; }
     }
   }
   return best;

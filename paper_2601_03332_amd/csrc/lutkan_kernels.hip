@@ -219,6 +219,7 @@ struct EdgeArgs {
   int64_t split_stride;    // tiled kernels: floats between the partial outputs of consecutive chunks (0 if one chunk)
   int32_t accumulate;      // tiled kernel writing y itself (one chunk): add to what y holds (the base branch) instead of overwriting
   int32_t wide;            // tiled kernel: table, jt, n_tiles, blob_bytes and the offsets describe the wide form (16-bit codes)
+  int32_t deep;            // tiled kernel: the launch waits for the table to stream from HBM; keep two slices in flight
 };
 
 // Device-table byte -> code value.  Symmetric int8 codes are stored excess-128 (byte = q + 128).
@@ -428,24 +429,33 @@ constexpr double kBaseProductMinEdges = 5e8;      // batch * d * m from which th
 // through the mixed-precision form (fp16 factor, fp32 product and sum), so the arithmetic is that of the fp32 path
 // on the stored values.
 //
-// STAGES = 3 (no BASE, NP >= 2; chosen when three slice buffers fit the LDS) takes the barrier out of the critical
-// path.  With two buffers every input ends in "wait for my copies, barrier", and every wave then refills its
-// read pipeline (record -> addresses -> codes and scales, two LDS round trips) at the same moment, with nothing
-// else on the SIMD to cover it.  With three, the slice of input i+2 is copied while input i is processed; the one
-// barrier per input (before input i: "everyone has finished input i-1", so its buffer may be overwritten, and
-// "everyone's share of slice i+1 has landed", waited for one whole input after the copies were issued) no longer
-// guards the data the wave is about to read, so the read pipeline runs on from the last row steps of input i into
-// the first of input i+1 without a refill.
+// PIPE: how the copies, the barrier and the LDS reads of consecutive inputs overlap.
+//   2  two buffers.  Every input ends in "wait for my copies of the next slice, barrier", and every wave then refills
+//      its read pipeline (record -> addresses -> codes and scales, two LDS round trips) at the same moment, with
+//      nothing else on the SIMD to cover it.
+//   3  three buffers, reads carried across inputs (no BASE, NP >= 2; where three buffers fit the LDS).  The slice of
+//      input i+2 is copied while input i is processed; the one barrier per input (before input i: "everyone has
+//      finished input i-1", so its buffer may be overwritten, and "everyone's share of slice i+1 has landed", waited
+//      for one whole input after the copies were issued) no longer guards the data the wave is about to read, so the
+//      read pipeline runs on from the last row steps of input i into the first of input i+1 without a refill.
+//   4  three buffers, two slices in flight (no BASE), for launches that wait for the table to stream from HBM: a
+//      work-group with one 44 KiB slice in flight draws about 21 GB/s, 256 of them 5.4 TB/s.  Before input i a wave
+//      waits only until its copies of slice i have landed -- those of slice i+1, issued one input ago, stay in flight
+//      -- and after the barrier it issues the copies of slice i+2; the read pipeline is refilled per input as with 2.
+//      (vmcnt counts a wave's copies in issue order: with n0 = the fewest copies any wave issues per input, "at
+//      most n0 outstanding" implies that everything older than the newest input's copies has landed.)
 //
 // WIDE: the slices come from the wide form of the table, whose codes are binary16 values already (q * 2^-24, signed):
 // a lane reads its four codes of a row as two packed pairs, and the permutes and the bias removal fall away; the
 // arithmetic after them is the same.
-template <int SCHEME, int LPR, int NP, int NW, bool BASE, bool PH, int STAGES, bool WIDE>
+template <int SCHEME, int LPR, int NP, int NW, bool BASE, bool PH, int PIPE, bool WIDE>
 __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a) {
   static_assert(!(BASE && PH), "with the base branch the device table holds fp32 products, never binary16 parameters");
   static_assert(!(BASE && WIDE), "the wide form is used with 8-byte records only");
   constexpr int CB = WIDE ? 2 : 1;         // bytes per code
-  static_assert(STAGES == 2 || (STAGES == 3 && !BASE && NP >= 2), "three stages: no base branch, and the read pipeline needs two row steps of the same input");
+  static_assert(PIPE == 2 || (PIPE == 3 && !BASE && NP >= 2) || (PIPE == 4 && !BASE), "carried reads need two row steps of the same input; three buffers go with 8-byte records");
+  constexpr int NBUF = (PIPE == 2) ? 2 : 3;
+  constexpr bool CARRY = (PIPE == 3), DEEP = (PIPE == 4);
   extern __shared__ __align__(16) unsigned char lds[];
   constexpr int JT = 4 * LPR;
   constexpr int RPS = 64 / LPR;
@@ -477,7 +487,7 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
   const unsigned char *src = a.table + (size_t)t * a.d * a.blob_bytes;                   // slice (t, 0); wave-uniform
   const unsigned char *rec_src = static_cast<const unsigned char *>(a.rec) + b0 * RB;     // this wave's records of input 0; wave-uniform
   const unsigned lane_off = lane * 16;
-  unsigned char *rec_area = lds + STAGES * a.blob_bytes + wave * (STAGES * RW * RB);
+  unsigned char *rec_area = lds + NBUF * a.blob_bytes + wave * (NBUF * RW * RB);
 
   // this work-group walks the inputs [i_begin, i_end) and writes one set of (partial) sums
   const int i_begin = blockIdx.y * a.chunk;
@@ -490,9 +500,12 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
     if (lane < REC_LANES) copy16_global_to_lds_at(rec_src + (int64_t)i * a.Bp * RB, lane_off, rec_area + buf * (RW * RB));
   };
   stage_input(i_begin, 0);
-  if (STAGES == 3 && i_begin + 1 < i_end) stage_input(i_begin + 1, 1);
-  wait_all_vector_loads();
-  __syncthreads();
+  if (NBUF == 3 && i_begin + 1 < i_end) stage_input(i_begin + 1, 1);
+  if (!DEEP) {                                         // (DEEP waits at the top of every input)
+    wait_all_vector_loads();
+    __syncthreads();
+  }
+  const int fewest_copies = (nvec >> 6) / NW + 1;      // per wave and input: its whole 1 KiB chunks of the slice, its records
 
   // Software pipeline over the row steps.  The reads of step p+1 (codes, parameters) and the record of
   // step p+2 are issued before the arithmetic of step p, and they are issued right AFTER the one point per
@@ -543,11 +556,11 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
     col_params = slice_addr + (unsigned)a.params_off + sub * PSZ;
   };
 
-  // carried from one input to the next with three stages; refilled at the top of every input with two
+  // carried from one input to the next (PIPE 3), else refilled at the top of every input
   rec_t rc_cur, rc_nxt;
   Fetched f_cur;
   int cur = 0;                                         // buffer of input i
-  if (STAGES == 3) {
+  if (CARRY) {
     unsigned cc, cp;
     columns_of(0, cc, cp);
     const unsigned char *rec_buf = rec_area + hrow * RB;
@@ -557,11 +570,11 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
   }
 
   for (int i = i_begin; i < i_end; ++i) {
-    // two stages: the other buffer; three: the next of the ring, and the one after it for the copies
-    const int nxt = (STAGES == 2) ? (cur ^ 1) : (cur == 2 ? 0 : cur + 1);
-    if (STAGES == 2) {
+    // two buffers: the other one; three: the next of the ring, and the one after it for the copies
+    const int nxt = (NBUF == 2) ? (cur ^ 1) : (cur == 2 ? 0 : cur + 1);
+    if (PIPE == 2) {
       if (i + 1 < i_end) stage_input(i + 1, nxt);                  // stream the next input's slice and records
-    } else {
+    } else if (CARRY) {
       // My share of slice i+1, copied during input i-1, has landed; after the barrier everyone's has, and everyone has
       // finished input i-1, whose buffer now takes the slice of input i+2.  The reads this wave has in flight (the
       // first row steps of input i) stay in flight: the barrier is the bare instruction, without the wait for LDS
@@ -569,20 +582,26 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
       wait_all_vector_loads();
       asm volatile("s_barrier" ::: "memory");
       if (i + 2 < i_end) stage_input(i + 2, nxt == 2 ? 0 : nxt + 1);
+    } else {
+      // My copies of slice i have landed (those of slice i+1 may still be in flight); after the barrier everyone's
+      // have, and everyone has finished input i-1, whose buffer now takes the slice of input i+2.
+      if (i + 1 < i_end) wait_until_vector_loads_outstanding(fewest_copies); else wait_all_vector_loads();
+      lds_barrier();
+      if (i + 2 < i_end) stage_input(i + 2, nxt == 2 ? 0 : nxt + 1);
     }
     const unsigned char *slice = lds + cur * a.blob_bytes;
     const unsigned char *rec_buf = rec_area + cur * (RW * RB) + hrow * RB;
     unsigned col_codes, col_params;
     columns_of(cur, col_codes, col_params);
-    // three stages: where the reads for the next input's first row steps go.  After the last input they re-read this
+    // carried reads: where the reads for the next input's first row steps go.  After the last input they re-read this
     // input's buffers (valid records and rows, results unused).
-    const int ahead = (STAGES == 3 && i + 1 < i_end) ? nxt : cur;
+    const int ahead = (CARRY && i + 1 < i_end) ? nxt : cur;
     const unsigned char *rec_ahead = rec_area + ahead * (RW * RB) + hrow * RB;
     unsigned ahead_codes = col_codes, ahead_params = col_params;
-    if (STAGES == 3) columns_of(ahead, ahead_codes, ahead_params);
+    if (CARRY) columns_of(ahead, ahead_codes, ahead_params);
     f32x4 base_gain = {0.f, 0.f, 0.f, 0.f};
     if (BASE) base_gain = *reinterpret_cast<const f32x4 *>(slice + sub * 16) * kTwoToMinus24;
-    if (STAGES == 2) {
+    if (!CARRY) {
       rc_cur = *reinterpret_cast<const rec_t *>(rec_buf);
       rc_nxt = *reinterpret_cast<const rec_t *>(rec_buf + (NP > 1 ? RPS * RB : 0));
       f_cur = fetch(rc_cur, col_codes, col_params);
@@ -595,9 +614,9 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
       asm volatile("" ::"v"(f_cur.pa.x), "v"(f_cur.c1), "v"(rc_nxt.y));        // first touch of step p's data
       __builtin_amdgcn_sched_barrier(0);
       if (p + 2 < NP) rc_nn = *reinterpret_cast<const rec_t *>(rec_buf + (p + 2) * (RPS * RB));
-      else if (STAGES == 3) rc_nn = *reinterpret_cast<const rec_t *>(rec_ahead + (p + 2 - NP) * (RPS * RB));
+      else if (CARRY) rc_nn = *reinterpret_cast<const rec_t *>(rec_ahead + (p + 2 - NP) * (RPS * RB));
       if (p + 1 < NP) f_nxt = fetch(rc_nxt, col_codes, col_params);
-      else if (STAGES == 3) f_nxt = fetch(rc_nxt, ahead_codes, ahead_params);
+      else if (CARRY) f_nxt = fetch(rc_nxt, ahead_codes, ahead_params);
       __builtin_amdgcn_sched_barrier(0);
       const float w = __uint_as_float(rc_cur.y);
       float al[4], ym[4];
@@ -651,7 +670,7 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
       rc_nxt = rc_nn;
       f_cur = f_nxt;
     }
-    if (STAGES == 2) {
+    if (PIPE == 2) {
       wait_all_vector_loads();                         // my share of the next slice has landed ...
       lds_barrier();                                   // ... everyone's has, and everyone is done with this one
     }
@@ -897,16 +916,20 @@ int launch_tiled_np(const EdgeArgs &ea, hipStream_t s) {
   if (row_tiles * ea.n_tiles > 0x7fffffffLL) return fail(LUTKAN_EUNSUPPORTED, "lutkan_tiled_kernel: B * m too large for one launch");
   const dim3 grid((unsigned)(row_tiles * ea.n_tiles), (unsigned)((ea.d + ea.chunk - 1) / ea.chunk));
   // three slice and record buffers where they fit (and the kernel has that form): the barrier leaves the critical path
+  // (PIPE 3), or, for a launch that waits for the table to stream from HBM, two slices are in flight (PIPE 4)
   const size_t lds3 = 3 * (size_t)ea.blob_bytes + (size_t)NW * 3 * RW * 8;
   const size_t lds = 2 * (size_t)ea.blob_bytes + (size_t)NW * 2 * RW * (ea.with_base ? 16 : 8);
-#define LUTKAN_LAUNCH_TILED(BASE, PH, STAGES, WIDE, BYTES)                                                                       \
+#define LUTKAN_LAUNCH_TILED(BASE, PH, PIPE, WIDE, BYTES)                                                                         \
   do {                                                                                                                           \
     static LdsCap raised;                                                                                                        \
-    return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, BASE, PH, STAGES, WIDE>, &raised, grid, BYTES, s, ea, "lutkan_tiled_kernel"); \
+    return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, BASE, PH, PIPE, WIDE>, &raised, grid, BYTES, s, ea, "lutkan_tiled_kernel"); \
   } while (0)
   if (ea.with_base) {
     if (ea.wide) return fail(LUTKAN_EINVAL, "lutkan_tiled_kernel: the wide table goes with 8-byte records");
     LUTKAN_LAUNCH_TILED(true, false, 2, false, lds);
+  }
+  if (ea.deep && !ea.wide && lds3 <= (size_t)kMaxTiledLds) {
+    if (ea.param_fp16) LUTKAN_LAUNCH_TILED(false, true, 4, false, lds3); else LUTKAN_LAUNCH_TILED(false, false, 4, false, lds3);
   }
   if constexpr (NP >= 2) {
     if (lds3 <= (size_t)kMaxTiledLds) {
@@ -1040,7 +1063,7 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   const bool with_base = (l->value_repr == LUTKAN_REPR_SPLINE_COMPONENT);
   bool tiled = tiled_supported(l->jt, l->blob_bytes, l->value_repr) && !q01_out;
   if (l->algo == LUTKAN_ALGO_GATHER) tiled = false;
-  const TilePlan tp = tiled ? plan_tiles(B, l->d, l->m, l->n_tiles, 64 / (l->jt / 4), l->blob_bytes) : TilePlan{1, 1, l->d, 0.0};
+  const TilePlan tp = tiled ? plan_tiles(B, l->d, l->m, l->n_tiles, 64 / (l->jt / 4), l->blob_bytes) : TilePlan{1, 1, l->d, 0.0, false};
   if (l->algo == LUTKAN_ALGO_AUTO && tiled && prefer_gather_for_small_batch(l, B, tp.cost)) tiled = false;
   const bool tiled_asked_for = (l->algo == LUTKAN_ALGO_TILED || l->algo == LUTKAN_ALGO_TILED_WIDE);
   if (tiled_asked_for && !tiled) return fail(LUTKAN_EUNSUPPORTED, "%s: tiled kernel needs a table slice <= 72 KiB (64 KiB with the base branch)%s", who, q01_out ? " and writes no code trace" : "");
@@ -1113,6 +1136,7 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   ea.param_fp16 = lutkan::device_params_are_half(l->value_repr, l->param_dtype, l->jt);
   ea.accumulate = 0;
   ea.wide = 0;
+  ea.deep = 0;
   ea.chunk = l->d;
   ea.split_stride = 0;
   if (base_by_product) {
@@ -1127,6 +1151,7 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
       ea.wide = 1;
     }
     ea.chunk = plan.chunk;
+    ea.deep = plan.hbm_bound ? 1 : 0;
     if (plan.n_split > 1) { ea.y = partials; ea.split_stride = B * l->m; }
     ea.accumulate = (base_by_product && plan.n_split == 1) ? 1 : 0;     // with chunks, the summing pass adds to y instead
     const int rc = (l->scheme == LUTKAN_SYM_INT8) ? launch_tiled_jt<LUTKAN_SYM_INT8>(ea, plan.np, s) : launch_tiled_jt<LUTKAN_ASYM_UINT8>(ea, plan.np, s);
