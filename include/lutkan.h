@@ -42,7 +42,8 @@ typedef enum { LUTKAN_CLIP_X = 0, LUTKAN_ZERO_SPLINE = 1 } lutkan_oob;          
 /* Which edge kernel runs.  TILED stages each (tile, input) table slice in LDS; GATHER reads the touched table rows
  * from global memory and splits the inputs over the GPU.  AUTO: tiled when a slice fits LDS, except for batches of so
  * few rows that they touch less than the whole table (then gather), and except for a small narrow layer (one column
- * tile, d * jt <= 4096) at up to 8192 rows, which lutkan_forward runs as a one-layer launch of the fused chain kernel;
+ * tile, d * jt <= 4096) at up to 10000 / (0.30 + 0.00053 d jt) rows (30000 for a 16x2 layer, 4000 for 256x16), which
+ * lutkan_forward runs as a one-layer launch of the fused chain kernel;
  * results agree to rounding, not bit for bit.  TILED (and AUTO) take the table's wide form, where the layer holds one
  * (lutkan_wide_table_build), when the launch planning prices it lower; TILED_WIDE takes it whatever the price and is
  * an error for a layer without one or a call it does not serve (16-byte records).  LUT layers only. */

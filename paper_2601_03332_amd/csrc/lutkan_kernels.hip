@@ -1032,9 +1032,14 @@ int chain_impl(const lutkan_dev_layer *layers, int32_t n_layers, const float *x,
   return check_launch("lutkan_chain_kernel");
 }
 
-// The layers that AUTO runs as a launch of the chain kernel (see forward_impl).
+// The layers that AUTO runs as a launch of the chain kernel (see forward_impl): one column tile, d * jt <= 4096, and
+// few enough rows.  Measured on 16x2 ... 256x16 layers between 8192 and 131072 rows: the chain kernel takes about
+// 4 us + (0.35 + 0.00088 d jt) us per 1000 rows, locate + tiled kernel + summing pass about 17 us + (0.05 + 0.00035 d jt)
+// us per 1000 rows; the chain kernel wins below their crossing, taken a little low (16x2: up to 30000 rows, 78x16:
+// 10000, 64x32: 7000, 256x16: 4000).
 bool small_layer_runs_as_chain(const lutkan_dev_layer *l, int64_t B) {
-  return l->algo == LUTKAN_ALGO_AUTO && l->n_tiles == 1 && l->jt <= kChainMaxColumns && l->d * l->jt <= 4096 && B <= 8192;
+  if (l->algo != LUTKAN_ALGO_AUTO || l->n_tiles != 1 || l->jt > kChainMaxColumns || l->d * l->jt > 4096) return false;
+  return (double)B * (0.30 + 0.00053 * l->d * l->jt) <= 10000.0;
 }
 
 int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y, lutkan_oob_stats *stats,

@@ -507,7 +507,7 @@ def test_cfg2_tabular_two_layer_chain_full_size():
 
 @pytest.mark.parametrize("B", [1, 300, 5000])
 def test_cfg2_tabular_chain_at_small_batches(B):
-    """Up to 8192 rows every layer of this network runs as a launch of the chain kernel, and lutkan_model_forward
+    """Up to about 10000 rows every layer of this network runs as a launch of the chain kernel, and lutkan_model_forward
     runs the whole network as one launch of it: same arithmetic, so still bit-identical to the layer-by-layer calls."""
     _chain_check(cfg2(B=B), f"cfg2 B={B}")
 
@@ -1133,8 +1133,8 @@ def test_last_plan_reports_what_auto_dispatch_launched():
     assert lk.lutkan_last_plan() == plan.replace("locate; ", "locate; oob; ")   # the counters add one launch, nothing else
     lk.bspline_kan_forward(art.bspline_to_device(DEV), xg)
     assert lk.lutkan_last_plan().startswith("bspline_locate; bspline_tiled np=")
-    _say("case last plan: cfg2 at 300, 5000 and 20000 rows")
-    w2 = cfg2(B=20000)
+    _say("case last plan: cfg2 at 300, 5000, 20000 and 40000 rows")
+    w2 = cfg2(B=40000)
     layers = []
     keep = []
     for s2 in w2.layers:
@@ -1148,9 +1148,12 @@ def test_last_plan_reports_what_auto_dispatch_launched():
     assert lk.lutkan_last_plan() == "chain layers=2 wpr=1; "                   # beyond 1024 rows: a wave per row
     lk.lutkan_forward(layers[0], x2[:300])
     assert lk.lutkan_last_plan() == "chain layers=1 wpr=4; "                   # a single small layer runs as a one-layer chain
+    lk.lutkan_model_forward(layers, x2[:20000])
+    plan = lk.lutkan_last_plan()                                               # 78x16 has outgrown the chain kernel, 16x2 has not yet
+    assert plan.count("locate; tiled np=") == 1 and plan.endswith("chain layers=1 wpr=1; "), plan
     lk.lutkan_model_forward(layers, x2)
     plan = lk.lutkan_last_plan()
-    assert plan.count("locate; tiled np=") == 2 and "chain" not in plan, plan  # beyond 8192 rows: locate + tiled kernel per layer
+    assert plan.count("locate; tiled np=") == 2 and "chain" not in plan, plan  # large batches: locate + tiled kernel per layer
     torch.cuda.synchronize()
 
 
