@@ -219,8 +219,9 @@ int bspline_dev_layer_init(const lutkan_artifact *a, bspline_dev_layer *out);
  * 8-bit values; the form costs device memory (two bytes per code beside the byte table, which the other kernels keep
  * using) and more LDS traffic per edge.  It exists for layers on 64-column tiles whose wide slice still fits the
  * LDS twice (K*L up to about 540 rows): on narrower tiles the LDS reads, not the instructions, bound the kernel and
- * the form is slower.  A forward call uses it on the tiled kernel when its launch planning prices it below the byte
- * form (which it does unless the table streams from HBM and the batch is small).
+ * the form is slower.  A forward call uses it on the tiled kernel when the layer's codes are symmetric int8 and its
+ * launch planning prices it below the byte form (large batches; with y_min the two forms measured within 3 % of each
+ * other, so asymmetric layers stay on the byte form unless algo = TILED_WIDE asks for the wide one).
  * lutkan_wide_table_bytes: size of the wide table, 0 for a layer that has none.
  * lutkan_wide_table_build: fills `wide_table` (device, 16-byte aligned, at least that many bytes) from layer->table on
  * `hip_stream` and sets layer->wide_table and wide_blob_bytes; the layer may be used on that stream right away, on

@@ -249,8 +249,8 @@ class Artifact:
                                 **arrays)
 
     def to_device(self, device="cuda:0", algo: int = ALGO_AUTO, wide: Optional[bool] = None) -> "LutLayer":
-        """wide: also hold the table's wide form (16-bit codes; lutkan_wide_table_build).  None: for layers of at
-        least 4096 edges that have one."""
+        """wide: also hold the table's wide form (16-bit codes; lutkan_wide_table_build).  None: for symmetric-int8
+        layers of at least 4096 edges that have one."""
         return LutLayer(self, device, algo, wide)
 
     def bspline_to_device(self, device="cuda:0", algo: int = ALGO_AUTO) -> "BsplineLayer":
@@ -360,8 +360,8 @@ class LutLayer:
         self.d, self.m = self.c.d, self.c.m
         self.wide_table = None
         n_wide = lib.lutkan_wide_table_bytes(C.byref(self.c))
-        if wide is None:
-            wide = n_wide > 0 and self.d * self.m >= 4096
+        if wide is None:                # what the launch planning would ever pick: symmetric codes, a layer of some size
+            wide = n_wide > 0 and self.d * self.m >= 4096 and self.c.scheme == SYM_INT8
         if wide:
             torch = _torch()
             if n_wide == 0:

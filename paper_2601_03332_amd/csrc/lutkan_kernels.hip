@@ -1083,7 +1083,9 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   // where the layer has one and the launch planning prices it lower.
   const bool can_wide = tiled && l->wide_table != nullptr && rec_bytes == 8;
   const TilePlan tpw = can_wide ? plan_tiles(B, l->d, l->m, l->n_tiles, 64 / (l->jt / 4), l->wide_blob_bytes, true) : tp;
-  const bool wide = can_wide && (tpw.cost < tp.cost || l->algo == LUTKAN_ALGO_TILED_WIDE);
+  // (with y_min the wide row step reads 56 bytes per lane from LDS and measured within 3 % of the byte form either
+  // way on 256x256 and 128x128 layers: left to the byte form unless asked for)
+  const bool wide = can_wide && ((tpw.cost < tp.cost && l->scheme == LUTKAN_SYM_INT8) || l->algo == LUTKAN_ALGO_TILED_WIDE);
   if (l->algo == LUTKAN_ALGO_TILED_WIDE && !wide)
     return fail(LUTKAN_EUNSUPPORTED, "%s: algo TILED_WIDE on a layer %s", who, l->wide_table ? "whose base branch runs inside the edge kernel (16-byte records)" : "without a wide table");
   // workspace: [records: room for 16 bytes each with the base branch; 8-byte records leave room for the 6 bytes per

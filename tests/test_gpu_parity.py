@@ -155,6 +155,7 @@ WIDE_CASES = [
     (707, 3, 1000, 10, 50, SYM_INT8, HALF_OPEN, ZERO_SPLINE, 20000, False),     # 16 column tiles, three slice buffers
     (708, 64, 128, 5, 32, ASYM_UINT8, CLOSED, CLIP_X, 70000, True),             # spline_component: base branch as a product, 8-byte records
     (709, 24, 70, 6, 16, SYM_INT8, CLOSED, ZERO_SPLINE, 3000, True),            # spline_component with 16-byte records: the byte form runs
+    (710, 64, 256, 8, 32, SYM_INT8, HALF_OPEN, CLIP_X, 16384 + 3, False),       # large enough for the launch planning to pick the wide form
 ]
 
 
@@ -200,11 +201,14 @@ def test_wide_table_form(case):
     if lk.lutkan_forward_workspace_bytes(wide, B) <= lk.STATIC_SCRATCH_BYTES:
         y_static = lk.lutkan_forward_static_scratch(wide, xg, torch.full((B, m), -3.0, dtype=torch.float32, device=DEV))
         assert bool(((y_static == y_wide) | (torch.isnan(y_static) & torch.isnan(y_wide))).all())
-    # left to the launch planning, the wide form runs on large batches
+    # left to the launch planning, the wide form runs on large batches of symmetric layers
     auto = _device_layer(art, s, lk.ALGO_AUTO, wide=True)
     lk.lutkan_forward(auto, xg)
-    if B * d * m >= 2e8:
+    if scheme == ASYM_UINT8:
+        assert " wide" not in lk.lutkan_last_plan(), lk.lutkan_last_plan()
+    elif B * d * m >= 2e8:
         assert "tiled wide np=" in lk.lutkan_last_plan(), lk.lutkan_last_plan()
+    assert (art.to_device(DEV).wide_table is not None) == (scheme == SYM_INT8 and d * m >= 4096)    # the default upload
 
 
 def test_wide_table_form_exists_only_where_it_pays():
