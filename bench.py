@@ -99,7 +99,7 @@ def kernel_costs(info, spec, B, plan):
             out.append(dict(kernel="lutkan_locate_kernel", hbm=4 * B * d + rec * Bp * d + silu_plane, l2=0, lds=2 * rec * Bp * d,
                             valu=(30 + K) * B * d))
         elif clause.startswith("tiled"):
-            np_, last_split = nums
+            np_, last_split = nums[:2]                                   # (the third number is the pipeline mode)
             wide = clause.startswith("tiled wide")                      # the table form with 16-bit codes: its code rows are twice as long
             rows_per_group = 16 * (64 // (info.jt // 4)) * np_
             table_bytes = info.table_bytes + (info.n_tiles * d * (K * info.L + 2) * info.jt if wide else 0)

@@ -908,6 +908,17 @@ bool prefer_gather_for_small_batch(const lutkan_dev_layer *l, int64_t B, double 
   return 8.0 + touched / 9.4e6 <= tiled_cost_us;
 }
 
+// Which pipeline mode of the tiled kernel a launch runs in (its PIPE parameter): three slice and record buffers where
+// they fit and the kernel has that form -- the barrier leaves the critical path (3), or, for a launch that waits for
+// the table to stream from HBM, two slices are in flight (4) -- else two buffers (2).
+int tiled_pipe(const EdgeArgs &ea, int np) {
+  const int rows_per_wave = 64 / (ea.jt / 4) * np;
+  const size_t lds3 = 3 * (size_t)ea.blob_bytes + (size_t)kTileWaves * 3 * rows_per_wave * 8;
+  if (ea.with_base || lds3 > (size_t)kMaxTiledLds) return 2;
+  if (ea.deep && !ea.wide) return 4;
+  return np >= 2 ? 3 : 2;
+}
+
 template <int SCHEME, int LPR, int NP>
 int launch_tiled_np(const EdgeArgs &ea, hipStream_t s) {
   constexpr int NW = kTileWaves;
@@ -915,31 +926,28 @@ int launch_tiled_np(const EdgeArgs &ea, hipStream_t s) {
   const int64_t row_tiles = (ea.B + NW * RW - 1) / (NW * RW);
   if (row_tiles * ea.n_tiles > 0x7fffffffLL) return fail(LUTKAN_EUNSUPPORTED, "lutkan_tiled_kernel: B * m too large for one launch");
   const dim3 grid((unsigned)(row_tiles * ea.n_tiles), (unsigned)((ea.d + ea.chunk - 1) / ea.chunk));
-  // three slice and record buffers where they fit (and the kernel has that form): the barrier leaves the critical path
-  // (PIPE 3), or, for a launch that waits for the table to stream from HBM, two slices are in flight (PIPE 4)
-  const size_t lds3 = 3 * (size_t)ea.blob_bytes + (size_t)NW * 3 * RW * 8;
-  const size_t lds = 2 * (size_t)ea.blob_bytes + (size_t)NW * 2 * RW * (ea.with_base ? 16 : 8);
-#define LUTKAN_LAUNCH_TILED(BASE, PH, PIPE, WIDE, BYTES)                                                                         \
+  const int pipe = tiled_pipe(ea, NP);
+  const size_t lds = (pipe == 2) ? 2 * (size_t)ea.blob_bytes + (size_t)NW * 2 * RW * (ea.with_base ? 16 : 8)
+                                 : 3 * (size_t)ea.blob_bytes + (size_t)NW * 3 * RW * 8;
+#define LUTKAN_LAUNCH_TILED(BASE, PH, PIPE, WIDE)                                                                                \
   do {                                                                                                                           \
     static LdsCap raised;                                                                                                        \
-    return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, BASE, PH, PIPE, WIDE>, &raised, grid, BYTES, s, ea, "lutkan_tiled_kernel"); \
+    return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, BASE, PH, PIPE, WIDE>, &raised, grid, lds, s, ea, "lutkan_tiled_kernel"); \
   } while (0)
   if (ea.with_base) {
     if (ea.wide) return fail(LUTKAN_EINVAL, "lutkan_tiled_kernel: the wide table goes with 8-byte records");
-    LUTKAN_LAUNCH_TILED(true, false, 2, false, lds);
+    LUTKAN_LAUNCH_TILED(true, false, 2, false);
   }
-  if (ea.deep && !ea.wide && lds3 <= (size_t)kMaxTiledLds) {
-    if (ea.param_fp16) LUTKAN_LAUNCH_TILED(false, true, 4, false, lds3); else LUTKAN_LAUNCH_TILED(false, false, 4, false, lds3);
-  }
+  if (pipe == 4) { if (ea.param_fp16) LUTKAN_LAUNCH_TILED(false, true, 4, false); else LUTKAN_LAUNCH_TILED(false, false, 4, false); }
   if constexpr (NP >= 2) {
-    if (lds3 <= (size_t)kMaxTiledLds) {
-      if (ea.wide) { if (ea.param_fp16) LUTKAN_LAUNCH_TILED(false, true, 3, true, lds3); else LUTKAN_LAUNCH_TILED(false, false, 3, true, lds3); }
-      if (ea.param_fp16) LUTKAN_LAUNCH_TILED(false, true, 3, false, lds3); else LUTKAN_LAUNCH_TILED(false, false, 3, false, lds3);
+    if (pipe == 3) {
+      if (ea.wide) { if (ea.param_fp16) LUTKAN_LAUNCH_TILED(false, true, 3, true); else LUTKAN_LAUNCH_TILED(false, false, 3, true); }
+      if (ea.param_fp16) LUTKAN_LAUNCH_TILED(false, true, 3, false); else LUTKAN_LAUNCH_TILED(false, false, 3, false);
     }
   }
-  if (ea.wide) { if (ea.param_fp16) LUTKAN_LAUNCH_TILED(false, true, 2, true, lds); else LUTKAN_LAUNCH_TILED(false, false, 2, true, lds); }
-  if (ea.param_fp16) LUTKAN_LAUNCH_TILED(false, true, 2, false, lds);
-  LUTKAN_LAUNCH_TILED(false, false, 2, false, lds);
+  if (ea.wide) { if (ea.param_fp16) LUTKAN_LAUNCH_TILED(false, true, 2, true); else LUTKAN_LAUNCH_TILED(false, false, 2, true); }
+  if (ea.param_fp16) LUTKAN_LAUNCH_TILED(false, true, 2, false);
+  LUTKAN_LAUNCH_TILED(false, false, 2, false);
 #undef LUTKAN_LAUNCH_TILED
 }
 
@@ -1163,7 +1171,7 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
     ea.accumulate = (base_by_product && plan.n_split == 1) ? 1 : 0;     // with chunks, the summing pass adds to y instead
     const int rc = (l->scheme == LUTKAN_SYM_INT8) ? launch_tiled_jt<LUTKAN_SYM_INT8>(ea, plan.np, s) : launch_tiled_jt<LUTKAN_ASYM_UINT8>(ea, plan.np, s);
     if (rc) return rc;
-    lutkan::plan_note("tiled%s np=%d split=%d; ", wide ? " wide" : "", plan.np, plan.n_split);
+    lutkan::plan_note("tiled%s np=%d split=%d pipe=%d; ", wide ? " wide" : "", plan.np, plan.n_split, tiled_pipe(ea, plan.np));
     if (plan.n_split == 1) return rc;
     const int64_t n = B * l->m;
     hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, s, partials, y, n, plan.n_split, base_by_product ? 1 : 0);

@@ -1114,11 +1114,11 @@ def test_last_plan_reports_what_auto_dispatch_launched():
         """Work-groups of the tiled launch named in `plan`, and its chunk count: the launch shape comes out of a
         fitted cost model, so only its invariants are asserted -- a legal row-step count, whole rounds' worth of
         work-groups, and a summing pass exactly when the inputs were split."""
-        mt = re.search(r"tiled np=(\d+) split=(\d+); ", plan)
+        mt = re.search(r"tiled np=(\d+) split=(\d+) pipe=(\d); ", plan)
         assert mt, plan
-        np_, split = int(mt.group(1)), int(mt.group(2))
+        np_, split, pipe = int(mt.group(1)), int(mt.group(2)), int(mt.group(3))
         rows_per_wave = (64 // (jt // 4)) * np_
-        assert np_ in (1, 2, 4, 8, 16) and rows_per_wave <= 64 and 1 <= split <= 128
+        assert np_ in (1, 2, 4, 8, 16) and rows_per_wave <= 64 and 1 <= split <= 128 and pipe in (2, 3, 4)
         assert plan.endswith("sum; ") == (split > 1), plan
         return -(-B // (16 * rows_per_wave)) * n_tiles * split, split
 
@@ -1132,6 +1132,10 @@ def test_last_plan_reports_what_auto_dispatch_launched():
     assert plan.startswith("locate; tiled np="), plan
     groups, _ = tiled_groups(plan, 4096, art.info.jt, art.info.n_tiles)
     assert groups >= 256, plan                                                  # at least one work-group per compute unit
+    assert " pipe=3; " in plan, plan                                            # three slice buffers fit: reads carried across inputs
+    lk.lutkan_forward(layer, xg[:256])                                          # the 686 MiB table streaming from HBM is the launch's time:
+    assert re.search(r"tiled np=\d+ split=\d+ pipe=4; ", lk.lutkan_last_plan()), lk.lutkan_last_plan()      # two slices in flight
+    lk.lutkan_forward(layer, xg)
     stats = torch.zeros(2, dtype=torch.int64, device=DEV)
     lk.lutkan_forward(layer, xg, stats=stats)
     assert lk.lutkan_last_plan() == plan.replace("locate; ", "locate; oob; ")   # the counters add one launch, nothing else
