@@ -201,14 +201,14 @@ class Rig:
         return rates
 
 
-def run_workload(rig, name, steps, warmup, batch=None, bspline=True, cpu_baseline=True, oracle_seconds=12.0):
+def run_workload(rig, name, steps, warmup, batch=None, bspline=True, cpu_baseline=True, oracle_seconds=12.0, wide=None):
     """Times `name` and returns its record: throughput of the whole forward, per-kernel durations, roofline terms."""
     np, torch, lk, dev = rig.np, rig.torch, rig.lk, rig.dev
     t0 = time.time()
     wl = make_workload(name, batch)
     B = wl.x.shape[0]
     arts = [lk.lutkan_compile(s.d, s.m, s.G, s.p, s.ext_knots, s.coef, s.L, s.scheme, s.boundary, s.oob) for s in wl.layers]
-    layers = [a.to_device(dev) for a in arts]
+    layers = [a.to_device(dev, wide=wide) for a in arts]
     log(f"[bench] {name}: {wl.name}; inputs and tables ready in {time.time() - t0:.1f}s "
         f"(tables {sum(a.info.table_bytes for a in arts) / 2**20:.1f} MiB)")
     edges = sum(B * s.d * s.m for s in wl.layers)
@@ -440,6 +440,7 @@ def main():
     ap.add_argument("--batch", type=int, default=None, help="override the workload's number of rows")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bspline", action="store_true")
+    ap.add_argument("--no-wide-tables", action="store_true", help="byte form of the LUT table only (no second copy with 16-bit codes)")
     ap.add_argument("--no-probes", action="store_true", help="skip the peak-rate probes (FMA, instruction mix, LDS, L2, HBM)")
     ap.add_argument("--all-configs", action="store_true",
                     help="also run every workload of the scope table; their records (throughput, kernels, roofline terms, "
@@ -465,7 +466,8 @@ def main():
         torch.cuda.synchronize()
         del ca, cb
 
-    rec = run_workload(rig, args.workload, args.steps, args.warmup, batch=args.batch, bspline=not args.no_bspline,
+    wide = False if args.no_wide_tables else None      # None: the binding's default (symmetric layers that have the form)
+    rec = run_workload(rig, args.workload, args.steps, args.warmup, batch=args.batch, wide=wide, bspline=not args.no_bspline,
                        cpu_baseline=not args.no_cpu_baseline)
     extra = {k: rec[k] for k in ("rows_per_s", "launch_plan", "step_ms_by_events", "kernels", "bspline_ms_per_step",
                                  "lut_vs_bspline_speedup") if k in rec}
@@ -479,7 +481,7 @@ def main():
             f"{'bound':>6s} {'frac@peaks':>10s} {'frac@measured':>13s} {'oracle G/s':>11s}")
         for name in workload_names():
             r = rec if (name == args.workload and args.batch is None) else run_workload(
-                rig, name, max(5, min(args.steps, 50)), max(2, min(args.warmup, 10)), bspline=not args.no_bspline,
+                rig, name, args.steps, args.warmup, wide=wide, bspline=not args.no_bspline,       # the same protocol for every workload
                 cpu_baseline=not args.no_cpu_baseline, oracle_seconds=3.0)
             configs.append(r)
             t = r["roofline"]["terms"]

@@ -220,6 +220,7 @@ struct EdgeArgs {
   int32_t accumulate;      // tiled kernel writing y itself (one chunk): add to what y holds (the base branch) instead of overwriting
   int32_t wide;            // tiled kernel: table, jt, n_tiles, blob_bytes and the offsets describe the wide form (16-bit codes)
   int32_t deep;            // tiled kernel: the launch waits for the table to stream from HBM; keep two slices in flight
+  int32_t asym;            // the layer's scheme is asymmetric uint8 (a second parameter plane)
 };
 
 // Device-table byte -> code value.  Symmetric int8 codes are stored excess-128 (byte = q + 128).
@@ -456,6 +457,11 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
   static_assert(PIPE == 2 || (PIPE == 3 && !BASE && NP >= 2) || (PIPE == 4 && !BASE), "carried reads need two row steps of the same input; three buffers go with 8-byte records");
   constexpr int NBUF = (PIPE == 2) ? 2 : 3;
   constexpr bool CARRY = (PIPE == 3), DEEP = (PIPE == 4);
+  // Row steps between the issue of a step's code and parameter reads and their use.  One step of the byte form (18
+  // vector instructions on each of a SIMD's four waves) covers the LDS latency; one of the wide form (12) does not:
+  // its waves spent 13 % of their cycles waiting for LDS reads, so it reads two steps ahead.
+  constexpr int AHEAD = WIDE ? 2 : 1;
+  static_assert(!CARRY || NP > AHEAD, "carried reads: the pipeline must fit into one input's row steps");
   extern __shared__ __align__(16) unsigned char lds[];
   constexpr int JT = 4 * LPR;
   constexpr int RPS = 64 / LPR;
@@ -556,17 +562,21 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
     col_params = slice_addr + (unsigned)a.params_off + sub * PSZ;
   };
 
-  // carried from one input to the next (PIPE 3), else refilled at the top of every input
-  rec_t rc_cur, rc_nxt;
-  Fetched f_cur;
+  // The read pipeline: rcq[k] is the record of row step p+k, fq[k] the codes and parameters of row step p+k, for the
+  // current step p.  Carried from one input to the next (PIPE 3), else refilled at the top of every input.
+  rec_t rcq[AHEAD + 1];
+  Fetched fq[AHEAD];
+  auto fill_read_pipeline = [&](const unsigned char *rec_buf, unsigned col_codes, unsigned col_params) {
+#pragma unroll
+    for (int k = 0; k <= AHEAD; ++k) rcq[k] = *reinterpret_cast<const rec_t *>(rec_buf + (k < NP ? k : NP - 1) * (RPS * RB));
+#pragma unroll
+    for (int k = 0; k < AHEAD; ++k) fq[k] = fetch(rcq[k], col_codes, col_params);
+  };
   int cur = 0;                                         // buffer of input i
   if (CARRY) {
     unsigned cc, cp;
     columns_of(0, cc, cp);
-    const unsigned char *rec_buf = rec_area + hrow * RB;
-    rc_cur = *reinterpret_cast<const rec_t *>(rec_buf);
-    rc_nxt = *reinterpret_cast<const rec_t *>(rec_buf + RPS * RB);
-    f_cur = fetch(rc_cur, cc, cp);
+    fill_read_pipeline(rec_area + hrow * RB, cc, cp);
   }
 
   for (int i = i_begin; i < i_end; ++i) {
@@ -601,22 +611,22 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
     if (CARRY) columns_of(ahead, ahead_codes, ahead_params);
     f32x4 base_gain = {0.f, 0.f, 0.f, 0.f};
     if (BASE) base_gain = *reinterpret_cast<const f32x4 *>(slice + sub * 16) * kTwoToMinus24;
-    if (!CARRY) {
-      rc_cur = *reinterpret_cast<const rec_t *>(rec_buf);
-      rc_nxt = *reinterpret_cast<const rec_t *>(rec_buf + (NP > 1 ? RPS * RB : 0));
-      f_cur = fetch(rc_cur, col_codes, col_params);
-    }
+    if (!CARRY) fill_read_pipeline(rec_buf, col_codes, col_params);
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
-      Fetched f_nxt = f_cur;
-      rec_t rc_nn = rc_nxt;
+      const Fetched f_cur = fq[0];
+      const rec_t rc_cur = rcq[0];
+      Fetched f_new = fq[AHEAD - 1];
+      rec_t rc_new = rcq[AHEAD];
+      // first touch of step p's data, and of the record whose addresses are computed next (everything older has
+      // arrived then: LDS reads return in order)
       if (SCHEME == LUTKAN_ASYM_UINT8) asm volatile("" ::"v"(f_cur.pb.x));
-      asm volatile("" ::"v"(f_cur.pa.x), "v"(f_cur.c1), "v"(rc_nxt.y));        // first touch of step p's data
+      asm volatile("" ::"v"(f_cur.pa.x), "v"(f_cur.c1), "v"(rcq[AHEAD].y));
       __builtin_amdgcn_sched_barrier(0);
-      if (p + 2 < NP) rc_nn = *reinterpret_cast<const rec_t *>(rec_buf + (p + 2) * (RPS * RB));
-      else if (CARRY) rc_nn = *reinterpret_cast<const rec_t *>(rec_ahead + (p + 2 - NP) * (RPS * RB));
-      if (p + 1 < NP) f_nxt = fetch(rc_nxt, col_codes, col_params);
-      else if (CARRY) f_nxt = fetch(rc_nxt, ahead_codes, ahead_params);
+      if (p + AHEAD + 1 < NP) rc_new = *reinterpret_cast<const rec_t *>(rec_buf + (p + AHEAD + 1) * (RPS * RB));
+      else if (CARRY) rc_new = *reinterpret_cast<const rec_t *>(rec_ahead + (p + AHEAD + 1 - NP) * (RPS * RB));
+      if (p + AHEAD < NP) f_new = fetch(rcq[AHEAD], col_codes, col_params);
+      else if (CARRY) f_new = fetch(rcq[AHEAD], ahead_codes, ahead_params);
       __builtin_amdgcn_sched_barrier(0);
       const float w = __uint_as_float(rc_cur.y);
       float al[4], ym[4];
@@ -666,9 +676,12 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
         acc[p][3] = fmaf(base_gain.w, silu_x, acc[p][3]);
       }
       __builtin_amdgcn_sched_barrier(0);
-      rc_cur = rc_nxt;
-      rc_nxt = rc_nn;
-      f_cur = f_nxt;
+#pragma unroll
+      for (int k = 0; k < AHEAD; ++k) rcq[k] = rcq[k + 1];
+      rcq[AHEAD] = rc_new;
+#pragma unroll
+      for (int k = 0; k + 1 < AHEAD; ++k) fq[k] = fq[k + 1];
+      fq[AHEAD - 1] = f_new;
     }
     if (PIPE == 2) {
       wait_all_vector_loads();                         // my share of the next slice has landed ...
@@ -916,7 +929,8 @@ int tiled_pipe(const EdgeArgs &ea, int np) {
   const size_t lds3 = 3 * (size_t)ea.blob_bytes + (size_t)kTileWaves * 3 * rows_per_wave * 8;
   if (ea.with_base || lds3 > (size_t)kMaxTiledLds) return 2;
   if (ea.deep && !ea.wide) return 4;
-  return np >= 2 ? 3 : 2;
+  if (ea.wide && ea.asym && np == 16) return 2;         // (what that variant carries across inputs no longer fits 128 registers)
+  return np >= (ea.wide ? 4 : 2) ? 3 : 2;             // carried reads: more row steps per input than the kernel reads ahead
 }
 
 template <int SCHEME, int LPR, int NP>
@@ -939,11 +953,11 @@ int launch_tiled_np(const EdgeArgs &ea, hipStream_t s) {
     LUTKAN_LAUNCH_TILED(true, false, 2, false);
   }
   if (pipe == 4) { if (ea.param_fp16) LUTKAN_LAUNCH_TILED(false, true, 4, false); else LUTKAN_LAUNCH_TILED(false, false, 4, false); }
+  if constexpr (NP >= 4) {
+    if (pipe == 3 && ea.wide) { if (ea.param_fp16) LUTKAN_LAUNCH_TILED(false, true, 3, true); else LUTKAN_LAUNCH_TILED(false, false, 3, true); }
+  }
   if constexpr (NP >= 2) {
-    if (pipe == 3) {
-      if (ea.wide) { if (ea.param_fp16) LUTKAN_LAUNCH_TILED(false, true, 3, true); else LUTKAN_LAUNCH_TILED(false, false, 3, true); }
-      if (ea.param_fp16) LUTKAN_LAUNCH_TILED(false, true, 3, false); else LUTKAN_LAUNCH_TILED(false, false, 3, false);
-    }
+    if (pipe == 3 && !ea.wide) { if (ea.param_fp16) LUTKAN_LAUNCH_TILED(false, true, 3, false); else LUTKAN_LAUNCH_TILED(false, false, 3, false); }
   }
   if (ea.wide) { if (ea.param_fp16) LUTKAN_LAUNCH_TILED(false, true, 2, true); else LUTKAN_LAUNCH_TILED(false, false, 2, true); }
   if (ea.param_fp16) LUTKAN_LAUNCH_TILED(false, true, 2, false);
@@ -1152,6 +1166,7 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   ea.accumulate = 0;
   ea.wide = 0;
   ea.deep = 0;
+  ea.asym = (l->scheme == LUTKAN_ASYM_UINT8);
   ea.chunk = l->d;
   ea.split_stride = 0;
   if (base_by_product) {
