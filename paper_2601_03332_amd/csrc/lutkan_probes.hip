@@ -20,7 +20,10 @@ constexpr int kFmaChains = 16;          // independent FMA chains per thread (hi
 constexpr int kLdsProbeBytes = 64 * 1024;
 constexpr int kL2ProbeBytes = 2 * 1024 * 1024;   // per pass; fits every XCD's L2, exceeds every CU's L1
 
-// fp32 FMA issue rate: every lane runs kFmaChains dependent chains of `iters` FMAs (non-packed form).
+// fp32 FMA issue rate: every lane runs kFmaChains dependent chains of `iters` FMAs (non-packed form).  The compiler
+// emits the three-operand encoding with one scalar operand (x = x * a + b), which issues every 4.1-4.3 cycles per wave
+// and SIMD like the permutes, packed-fp16 and mixed-precision instructions of the layer kernels: the yardstick for
+// their vector-instruction count.  (The two-operand v_fmac_f32 on registers alone issues every 2.8 cycles.)
 __global__ __launch_bounds__(kProbeThreads) void probe_valu_fma_kernel(float *sink, int iters, float a, float b) {
   float x[kFmaChains];
 #pragma unroll
