@@ -605,6 +605,20 @@ def test_cfg4_wide_layer_every_row(B):
     _check_layer(w.layers[0], w.x, lk.ALGO_AUTO, what=f"cfg4 B={B}")
 
 
+@pytest.mark.parametrize("L,scheme,B", [(32, ASYM_UINT8, 200), (48, SYM_INT8, 300)], ids=["L32_uint8_200rows", "L48_int8_300rows"])
+def test_table_streaming_from_hbm_runs_with_two_slices_in_flight(L, scheme, B):
+    """A table of more than 128 MiB at a few hundred rows: the launch waits for the table to stream from HBM and the
+    tiled kernel keeps two slices in flight, waiting on a count of its own outstanding copies.  Other slice sizes than
+    the widest workload's (two resp. three copies per wave and input at least), both schemes, every row against the oracle."""
+    w = random_layer(810 + L, 1024, 1024, 10, L, scheme, CLOSED, ZERO_SPLINE, B, oob_frac=0.1)
+    art, _ = _compile_both(w.layers[0])
+    assert art.info.table_bytes > 128 << 20
+    _check_layer(w.layers[0], w.x, lk.ALGO_TILED, what=w.name)
+    layer = _device_layer(art, w.layers[0], lk.ALGO_TILED)
+    lk.lutkan_forward(layer, torch.from_numpy(w.x).to(DEV))
+    assert " pipe=4; " in lk.lutkan_last_plan(), lk.lutkan_last_plan()
+
+
 def test_cfg4_wide_layer_largest_batch_sampled_rows():
     """The configuration the benchmark times (1024 -> 1024 at 32768 rows): 4096 random rows against the oracle, the
     OOB counters exact over all rows."""
