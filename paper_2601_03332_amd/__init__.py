@@ -6,7 +6,7 @@ There is no CPU fallback: importing works anywhere, calling a forward without a 
 """
 from .binding import (  # noqa: F401
     ALGO_AUTO, ALGO_GATHER, ALGO_TILED, ALGO_TILED_WIDE, PARAM_FP32, PARAM_FP16, SPAN_DOMAIN, SPAN_EXTENDED, PROBE_VALU_FMA,
-    PROBE_LDS_READ, PROBE_L2_READ, PROBE_HBM_READ, PROBE_VALU_MIX, ASYM_UINT8, CLIP_X, CLOSED, HALF_OPEN, REPR_PHI,
+    PROBE_LDS_READ, PROBE_L2_READ, PROBE_HBM_READ, PROBE_VALU_MIX, PROBE_VALU_FMAC, ASYM_UINT8, CLIP_X, CLOSED, HALF_OPEN, REPR_PHI,
     REPR_SPLINE_COMPONENT, SYM_INT8, ZERO_SPLINE, Artifact, BsplineLayer, LutKanError, LutLayer,
     bspline_forward_workspace_bytes, bspline_kan_forward, library_path, lutkan_error_stats,
     lutkan_artifact_from_arrays, lutkan_artifact_load, lutkan_compile, lutkan_forward, lutkan_forward_edges,

@@ -17,7 +17,7 @@ CLIP_X, ZERO_SPLINE = 0, 1
 ALGO_AUTO, ALGO_GATHER, ALGO_TILED, ALGO_TILED_WIDE = 0, 1, 2, 3
 PARAM_FP32, PARAM_FP16 = 0, 1
 SPAN_DOMAIN, SPAN_EXTENDED = 0, 1
-PROBE_VALU_FMA, PROBE_LDS_READ, PROBE_L2_READ, PROBE_HBM_READ, PROBE_VALU_MIX = 0, 1, 2, 3, 4
+PROBE_VALU_FMA, PROBE_LDS_READ, PROBE_L2_READ, PROBE_HBM_READ, PROBE_VALU_MIX, PROBE_VALU_FMAC = 0, 1, 2, 3, 4, 5
 REPR_PHI, REPR_SPLINE_COMPONENT = 0, 1
 MAX_K = 64
 

@@ -38,6 +38,26 @@ __global__ __launch_bounds__(kProbeThreads) void probe_valu_fma_kernel(float *si
   if (s == 123456.789f) sink[0] = s;     // keeps the chains alive; practically never taken
 }
 
+// The same count of fp32 FMAs in the two-operand encoding on registers only (x += b * y, y another running value):
+// on gfx950 this form issues every 2.8 cycles per wave and SIMD, i.e. above the 4-cycle rate that every other
+// instruction of the layer kernels has.  Reported beside the rate above so that nobody takes the 4-cycle figure for
+// the ceiling of the fp32 units.
+__global__ __launch_bounds__(kProbeThreads) void probe_valu_fmac_kernel(float *sink, int iters, float b) {
+  float x[kFmaChains];
+#pragma unroll
+  for (int c = 0; c < kFmaChains; ++c) x[c] = (float)(threadIdx.x + c) * 1e-3f;
+  float bv = b;
+  asm volatile("" : "+v"(bv));                         // the multiplier in a vector register
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int c = 0; c < kFmaChains; ++c) asm volatile("v_fmac_f32 %0, %1, %2" : "+v"(x[c]) : "v"(bv), "v"(x[(c + 1) % kFmaChains]));
+  }
+  float s = 0.0f;
+#pragma unroll
+  for (int c = 0; c < kFmaChains; ++c) s += x[c];
+  if (s == 123456.789f) sink[0] = s;
+}
+
 // Issue rate of the instruction mix of the tiled LUT kernel (int8 codes, value_repr = phi): per row step a lane
 // issues 2 16-bit multiply-adds (addresses), 4 byte permutes, 4 packed-fp16 adds, 4 mixed-precision FMAs and 4 fp32
 // FMAs, with the data dependences of the kernel (permutes -> packed adds -> mixed FMAs -> FMAs, four columns side by
@@ -138,6 +158,12 @@ extern "C" int lutkan_probe_launch(int32_t kind, void *buffer, size_t buffer_byt
     case LUTKAN_PROBE_VALU_FMA: {
       if (buffer_bytes < 16) return fail(LUTKAN_ESHAPE, "%s: buffer too small", who);
       hipLaunchKernelGGL(probe_valu_fma_kernel, dim3(groups), dim3(kProbeThreads), 0, s, fbuf, iters, 0.999f, 0.001f);
+      *work_out = 2.0 * kFmaChains * (double)iters * kProbeThreads * groups;            // flop
+      break;
+    }
+    case LUTKAN_PROBE_VALU_FMAC: {
+      if (buffer_bytes < 16) return fail(LUTKAN_ESHAPE, "%s: buffer too small", who);
+      hipLaunchKernelGGL(probe_valu_fmac_kernel, dim3(groups), dim3(kProbeThreads), 0, s, fbuf, iters, 1e-9f);
       *work_out = 2.0 * kFmaChains * (double)iters * kProbeThreads * groups;            // flop
       break;
     }

@@ -1185,7 +1185,8 @@ def test_measurement_probes_report_their_work():
     only required to be a finite positive number here -- its value belongs to the benchmark's record, not to a test."""
     buf = torch.zeros((1 << 30) // 4 + 4, dtype=torch.float32, device=DEV)
     cus = torch.cuda.get_device_properties(0).multi_processor_count
-    kinds = {lk.PROBE_VALU_FMA: 2048, lk.PROBE_VALU_MIX: 2048, lk.PROBE_LDS_READ: 512, lk.PROBE_L2_READ: 4, lk.PROBE_HBM_READ: 2}
+    kinds = {lk.PROBE_VALU_FMA: 2048, lk.PROBE_VALU_FMAC: 2048, lk.PROBE_VALU_MIX: 2048, lk.PROBE_LDS_READ: 512, lk.PROBE_L2_READ: 4,
+             lk.PROBE_HBM_READ: 2}
     for kind, iters in kinds.items():
         lk.lutkan_probe_launch(kind, buf, iters)             # warm-up
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
