@@ -100,14 +100,19 @@ def kernel_costs(info, spec, B, plan):
                             valu=(30 + K) * B * d))
         elif clause.startswith("tiled"):
             np_, last_split = nums[:2]                                   # (the third number is the pipeline mode)
-            wide = clause.startswith("tiled wide")                      # the table form with 16-bit codes: its code rows are twice as long
+            # a wide form of the table: 16-bit codes (code rows twice as long), or fp32 values (four times, no parameter rows)
+            wide = 4 if clause.startswith("tiled wide32") else 2 if clause.startswith("tiled wide") else 0
             rows_per_group = 16 * (64 // (info.jt // 4)) * np_
-            table_bytes = info.table_bytes + (info.n_tiles * d * (K * info.L + 2) * info.jt if wide else 0)
+            code_bytes_all = info.n_tiles * d * (K * info.L + 2) * info.jt
+            param_bytes_all = info.n_tiles * d * (K + 1) * info.jt * (8 if asym else 4)
+            table_bytes = info.table_bytes + (3 * code_bytes_all - param_bytes_all if wide == 4 else code_bytes_all if wide else 0)
             staged = -(-B // rows_per_group) * table_bytes + info.n_tiles * rec * Bp * d
             # vector instructions per 4 edges: two addresses, [four byte permutes, two bias removals (int8)], two code
-            # differences, four interpolations, four scalings [, four y_min] [, four base products]
-            per4 = ((16 if asym else 12) if wide else (20 if asym else 18)) + (4 if base else 0)
-            lds_per4 = (12 if base else 8) + (16 if wide else 8) + (32 if asym else 16)   # record, two code rows, alpha (+ y_min) per lane
+            # differences, four interpolations, four scalings [, four y_min] [, four base products]; on fp32 values one
+            # address, four differences, four interpolations, four additions
+            per4 = (13 if wide == 4 else (16 if asym else 12) if wide else (20 if asym else 18)) + (4 if base else 0)
+            # record, two code rows, alpha (+ y_min) per lane
+            lds_per4 = (12 if base else 8) + (32 if wide == 4 else (16 if wide else 8) + (32 if asym else 16))
             out.append(dict(kernel="lutkan_tiled_kernel", hbm=table_bytes + rec * Bp * d + 4 * B * m * last_split,
                             l2=staged, lds=edges / 4 * lds_per4 + staged, valu=edges / 4 * per4))
         elif clause.startswith("gather"):

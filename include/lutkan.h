@@ -197,6 +197,7 @@ typedef struct {
   /* Optional second copy of the LUT table with 16-bit codes (see lutkan_wide_table_build); NULL / 0: none. */
   const void *wide_table;             /* device, lutkan_wide_table_bytes() bytes, 16-byte aligned */
   int32_t wide_blob_bytes;            /* bytes of one (tile, input) slice of the wide table */
+  int32_t wide_code_bytes;            /* 2: binary16 codes; 4: dequantised fp32 values */
 } lutkan_dev_layer;
 
 typedef struct {
@@ -213,24 +214,30 @@ typedef struct {
 int lutkan_dev_layer_init(const lutkan_artifact *a, lutkan_dev_layer *out);
 int bspline_dev_layer_init(const lutkan_artifact *a, bspline_dev_layer *out);
 
-/* The wide form of the LUT device table: the same slices ([base][parameter rows][code rows], the same tiles, ordered
- * [t][i]) with every code held as the binary16 value q * 2^-24 (sign and magnitude; a subnormal, whose bit pattern is
- * the magnitude of the code) instead of one byte.  The tiled kernel then reads a lane's codes as packed binary16 pairs
- * and spends no instruction on unpacking bytes or on the excess-128 bias: 12 vector instructions per four edges
- * instead of 18 (16 instead of 20 with y_min), on the same arithmetic, bit for bit (Eq. 10 + Eq. 17).  The codes stay
- * 8-bit values; the form costs device memory (two bytes per code beside the byte table, which the other kernels keep
- * using) and more LDS traffic per edge.  It exists for layers on 64-column tiles whose wide slice still fits the
- * LDS twice (K*L up to about 540 rows): on narrower tiles the LDS reads, not the instructions, bound the kernel and
- * the form is slower.  A forward call uses it on the tiled kernel when the layer's codes are symmetric int8 and its
- * launch planning prices it below the byte form (large batches; with y_min the two forms measured within 3 % of each
- * other, so asymmetric layers stay on the byte form unless algo = TILED_WIDE asks for the wide one).
- * lutkan_wide_table_bytes: size of the wide table, 0 for a layer that has none.
+/* A wide form of the LUT device table: the same tiles and slice order ([t][i]) with more than a byte per code, so that
+ * the tiled kernel spends fewer vector instructions per edge.  The codes stay 8-bit values and the artifact is what it
+ * was; a wide form is a second, larger copy on the device (the byte table stays: the other kernels keep using it).
+ *   code_bytes = 2  every code as the binary16 value q * 2^-24 (sign and magnitude; a subnormal whose bit pattern is
+ *                   the magnitude of the code); the slice is otherwise the byte form's ([base][parameter rows][code
+ *                   rows]).  A lane reads its codes as packed binary16 pairs and spends nothing on unpacking bytes or on
+ *                   the excess-128 bias: 12 vector instructions per four edges instead of 18 (16 instead of 20 with
+ *                   y_min), on the same arithmetic, bit for bit (Eq. 10 + Eq. 17).
+ *   code_bytes = 4  every code dequantised: the fp32 value y_min + alpha * q of Eq. 10 (one rounding per operation; with
+ *                   spline_component the folded parameters), slices [base][value rows], no parameter rows.  Per edge
+ *                   the kernel then does Eq. 17 on the stored values, v0 + w * (v1 - v0): three plain fp32 instructions,
+ *                   no scale or y_min to read, the same for both schemes.
+ * Both cost device memory and LDS traffic per edge, and exist only for layers on 64-column tiles whose wide slice still
+ * fits the LDS twice (K*L up to about 540 rows with 2 bytes per code, 285 with 4): on narrower tiles the LDS reads, not
+ * the instructions, bound the kernel.  A forward call uses the form a layer holds on the tiled kernel when its launch
+ * planning prices it below the byte form (large batches; the 2-byte form only for symmetric codes -- with y_min it
+ * measured on par with the byte form); algo = TILED_WIDE takes it whatever the price.
+ * lutkan_wide_table_bytes: size of that form of the layer's table, 0 if the layer has none.
  * lutkan_wide_table_build: fills `wide_table` (device, 16-byte aligned, at least that many bytes) from layer->table on
- * `hip_stream` and sets layer->wide_table and wide_blob_bytes; the layer may be used on that stream right away, on
- * others after the stream has been synchronised.  The memory stays the caller's.  Errors: EINVAL (null / misaligned
- * pointers, bad layer), ESHAPE (bytes too small), EUNSUPPORTED (no wide form), EHIP. */
-size_t lutkan_wide_table_bytes(const lutkan_dev_layer *layer);
-int lutkan_wide_table_build(lutkan_dev_layer *layer, void *wide_table, size_t bytes, void *hip_stream);
+ * `hip_stream` and sets layer->wide_table, wide_blob_bytes and wide_code_bytes; the layer may be used on that stream
+ * right away, on others after the stream has been synchronised.  The memory stays the caller's.  Errors: EINVAL (null /
+ * misaligned pointers, bad layer, code_bytes not 2 or 4), ESHAPE (bytes too small), EUNSUPPORTED (no such form), EHIP. */
+size_t lutkan_wide_table_bytes(const lutkan_dev_layer *layer, int32_t code_bytes);
+int lutkan_wide_table_build(lutkan_dev_layer *layer, int32_t code_bytes, void *wide_table, size_t bytes, void *hip_stream);
 
 /* Sec. 5.5 / 5.6 counters: inputs (b,i) with In(x) = 0, and rows with at least one such input. */
 typedef struct { unsigned long long oob_count, oob_any_rows; } lutkan_oob_stats;

@@ -55,7 +55,8 @@ class _DevLayer(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("d", "m", "K", "L", "scheme", "boundary", "oob", "value_repr", "param_dtype",
                                          "jt", "n_tiles", "blob_bytes", "algo")] + \
                [("knots", C.c_float * (MAX_K + 1)), ("table", C.c_void_p), ("knots_per_input", C.c_int32),
-                ("input_knots", C.c_void_p), ("wide_table", C.c_void_p), ("wide_blob_bytes", C.c_int32)]
+                ("input_knots", C.c_void_p), ("wide_table", C.c_void_p), ("wide_blob_bytes", C.c_int32),
+                ("wide_code_bytes", C.c_int32)]
 
 
 class _SplineDevLayer(C.Structure):
@@ -109,9 +110,9 @@ def load_library():
         f.restype = vp
     lib.lutkan_dev_layer_init.argtypes = [vp, C.POINTER(_DevLayer)]
     lib.bspline_dev_layer_init.argtypes = [vp, C.POINTER(_SplineDevLayer)]
-    lib.lutkan_wide_table_bytes.argtypes = [C.POINTER(_DevLayer)]
+    lib.lutkan_wide_table_bytes.argtypes = [C.POINTER(_DevLayer), C.c_int32]
     lib.lutkan_wide_table_bytes.restype = sz
-    lib.lutkan_wide_table_build.argtypes = [C.POINTER(_DevLayer), vp, sz, vp]
+    lib.lutkan_wide_table_build.argtypes = [C.POINTER(_DevLayer), C.c_int32, vp, sz, vp]
     lib.lutkan_forward_workspace_bytes.argtypes = [C.POINTER(_DevLayer), i64]
     lib.lutkan_forward_workspace_bytes.restype = sz
     lib.bspline_forward_workspace_bytes.argtypes = [C.POINTER(_SplineDevLayer), i64]
@@ -248,9 +249,10 @@ class Artifact:
             np.savez_compressed(f, manifest=np.frombuffer(json.dumps(manifest, sort_keys=True).encode(), dtype=np.uint8),
                                 **arrays)
 
-    def to_device(self, device="cuda:0", algo: int = ALGO_AUTO, wide: Optional[bool] = None) -> "LutLayer":
-        """wide: also hold the table's wide form (16-bit codes; lutkan_wide_table_build).  None: for symmetric-int8
-        layers of at least 4096 edges that have one."""
+    def to_device(self, device="cuda:0", algo: int = ALGO_AUTO, wide=None) -> "LutLayer":
+        """wide: also hold a wide form of the table (lutkan_wide_table_build).  2: binary16 codes; 4: fp32 values;
+        True: fp32 values if the layer has that form, else binary16 codes; False: none.  None: for layers of at
+        least 4096 edges, fp32 values if the layer has that form, else (symmetric int8 only) binary16 codes."""
         return LutLayer(self, device, algo, wide)
 
     def bspline_to_device(self, device="cuda:0", algo: int = ALGO_AUTO) -> "BsplineLayer":
@@ -347,7 +349,7 @@ def _upload(arr: np.ndarray, device):
 class LutLayer:
     """Device-side LUT layer: the lutkan_dev_layer struct plus the torch tensor that owns its table."""
 
-    def __init__(self, art: Artifact, device, algo: int = ALGO_AUTO, wide: Optional[bool] = None):
+    def __init__(self, art: Artifact, device, algo: int = ALGO_AUTO, wide=None):
         lib = load_library()
         self.c = _DevLayer()
         _check(lib.lutkan_dev_layer_init(art._h, C.byref(self.c)))
@@ -359,16 +361,24 @@ class LutLayer:
         self.device = self.table.device
         self.d, self.m = self.c.d, self.c.m
         self.wide_table = None
-        n_wide = lib.lutkan_wide_table_bytes(C.byref(self.c))
-        if wide is None:                # what the launch planning would ever pick: symmetric codes, a layer of some size
-            wide = n_wide > 0 and self.d * self.m >= 4096 and self.c.scheme == SYM_INT8
+        n_wide = {cb: lib.lutkan_wide_table_bytes(C.byref(self.c), cb) for cb in (2, 4)}
+        if wide is None or wide is True:
+            asked = wide is True
+            wide = 4 if n_wide[4] else 2 if n_wide[2] else 0
+            if not asked:               # what the launch planning would ever pick, on a layer of some size
+                if self.d * self.m < 4096 or (wide == 2 and self.c.scheme != SYM_INT8):
+                    wide = 0
+            elif not wide:
+                raise LutKanError("this layer has no wide table form")
         if wide:
             torch = _torch()
-            if n_wide == 0:
-                raise LutKanError("this layer has no wide table form")
-            self.wide_table = torch.empty(n_wide, dtype=torch.uint8, device=self.device)
+            if wide not in (2, 4):
+                raise LutKanError("wide: 2 (binary16 codes) or 4 (fp32 values)")
+            if n_wide[wide] == 0:
+                raise LutKanError("this layer has no wide table form of %d bytes per code" % wide)
+            self.wide_table = torch.empty(n_wide[wide], dtype=torch.uint8, device=self.device)
             with torch.cuda.device(self.device):
-                _check(lib.lutkan_wide_table_build(C.byref(self.c), self.wide_table.data_ptr(), n_wide, _stream(self.device)))
+                _check(lib.lutkan_wide_table_build(C.byref(self.c), wide, self.wide_table.data_ptr(), n_wide[wide], _stream(self.device)))
 
     def with_contract(self, boundary: int, oob: int, algo: Optional[int] = None) -> "LutLayer":
         """Same tables under another boundary_mode / oob_policy (the contract is not baked into the codes)."""

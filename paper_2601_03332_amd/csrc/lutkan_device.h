@@ -156,8 +156,9 @@ int gather_jx_log2(int m) {
 //   one input of one work-group   max(0.55 + 0.11 * NP, slice bytes at 100 GB/s) + 0.1
 //                                 (barrier and address set-up, NP row steps of 256 edges per wave, the slice's
 //                                 global -> LDS copy when that is the longer of the two)
-//   one work-group                3 + its inputs (pipeline fill, accumulator write-back); the wide form of the table
-//                                 (16-bit codes: 0.095 * NP per input) adds half its slice at 21 GB/s to the fill
+//   one work-group                3 + its inputs (pipeline fill, accumulator write-back); a wide form of the table
+//                                 (16-bit codes: 0.095 * NP per input, fp32 values: 0.070 * NP) adds half its slice
+//                                 at 21 GB/s to the fill
 //   the launch                    rounds of 256 work-groups (one per compute unit), one after the other
 //   the partial sums              4 + their bytes at 3 TB/s, when there is more than one chunk
 //   a table of more than 128 MiB  at least its bytes at 21 GB/s per work-group and 5.3 TB/s in all (it streams from
@@ -171,8 +172,10 @@ struct TilePlan {
   bool hbm_bound;    // the estimate is the time the table takes to stream from HBM, not the work-groups' own time
 };
 
-// wide: the slices are those of the table's wide form (16-bit codes), whose row steps take fewer instructions.
-TilePlan plan_tiles(int64_t B, int d, int m, int n_tiles, int rps, int slice_bytes, bool wide = false) {
+// code_bytes: 1 for the table as compiled; 2 or 4 when the slices are those of a wide form of the table, whose row
+// steps take fewer instructions.
+inline double row_step_us(int code_bytes) { return code_bytes == 4 ? 0.070 : code_bytes == 2 ? 0.095 : 0.11; }
+TilePlan plan_tiles(int64_t B, int d, int m, int n_tiles, int rps, int slice_bytes, int code_bytes = 1) {
   const int np_max = std::min(16, 64 / rps);
   const int max_split = std::max(1, std::min(128, d / 8));
   TilePlan best{np_max, 1, d, 1e300, false};
@@ -183,11 +186,11 @@ TilePlan plan_tiles(int64_t B, int d, int m, int n_tiles, int rps, int slice_byt
   const bool streams_from_hbm = table_bytes > 128.0 * 1024 * 1024;
   // a work-group's first slice arrives before it computes anything; the wide form's is twice as long (measured on a
   // 256x256 layer at 512 rows, 8 inputs per work-group: 0.030 -> 0.037 ms on the wide form)
-  const double fill = 3.0 + (wide ? 0.5 * slice_bytes / 21e3 : 0.0);
+  const double fill = 3.0 + (code_bytes > 1 ? 0.5 * slice_bytes / 21e3 : 0.0);
   for (int np = np_max; np >= 1; np >>= 1) {
     const int64_t rows = (int64_t)kTileWaves * rps * np;
     const int64_t groups = (B + rows - 1) / rows * n_tiles;
-    const double per_input = std::max(0.55 + (wide ? 0.095 : 0.11) * np, slice_bytes / 100e3) + 0.1;
+    const double per_input = std::max(0.55 + row_step_us(code_bytes) * np, slice_bytes / 100e3) + 0.1;
     // candidate chunk counts: 1 .. 8, then the counts that fill whole rounds of 256 work-groups, and the cap
     int candidates[16];
     int n_candidates = 0;
@@ -262,9 +265,9 @@ int launch_with_lds(Kern kern, LdsCap *cap, const dim3 &grid, size_t lds, hipStr
 }
 
 // Records for every (input, padded row), then room for the partial sums when the inputs are split into chunks.
-size_t tiled_workspace_bytes(int d, int m, int jt, int n_tiles, int64_t B, int bytes_per_record, int slice_bytes, bool wide = false) {
+size_t tiled_workspace_bytes(int d, int m, int jt, int n_tiles, int64_t B, int bytes_per_record, int slice_bytes, int code_bytes = 1) {
   size_t bytes = record_bytes(d, padded_rows(B), bytes_per_record);
-  const TilePlan tp = plan_tiles(B, d, m, n_tiles, 64 / (jt / 4), slice_bytes, wide);
+  const TilePlan tp = plan_tiles(B, d, m, n_tiles, 64 / (jt / 4), slice_bytes, code_bytes);
   // any of the kernels may run (tiled, gather with one column per lane, gather with four): room for the largest set
   const GatherPlan gp = plan_gather(B, d, m), gp4 = plan_gather(B, d, n_tiles * jt / 4);
   const int n_split = std::max(tp.n_split, std::max(gp.n_split, gp4.n_split));

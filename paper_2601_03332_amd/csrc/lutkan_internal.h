@@ -57,19 +57,25 @@ inline int lds_slice_budget(int value_repr) {
   return (kLdsPerWorkGroup - 16 * 2 * 64 * record_bytes) / 2;
 }
 
-// The wide form of the LUT table (two bytes per code, see lutkan_wide_table_build): the same slice layout with code
-// rows of jw binary16 values.
-inline BlobLayout wide_blob_layout(int K, int L, int jw, int scheme, int value_repr, int param_dtype) {
-  BlobLayout b = blob_layout(K, L, jw, scheme, value_repr, param_dtype);
-  b.bytes = (b.codes_off + (K * L + 2) * jw * 2 + 15) & ~15;
+// The wide forms of the LUT table (see lutkan_wide_table_build).  code_bytes = 2: the same slice layout with code
+// rows of jt binary16 values.  code_bytes = 4: [base jt f32 (spline_component only)][(K*L+2) rows of jt fp32 values
+// y_min + alpha * q, the last two rows zero]; there are no parameter rows (params_off = codes_off, param_row_bytes 0).
+inline BlobLayout wide_blob_layout(int K, int L, int jt, int scheme, int value_repr, int param_dtype, int code_bytes) {
+  BlobLayout b = blob_layout(K, L, jt, scheme, value_repr, param_dtype);
+  if (code_bytes == 4) {
+    b.param_row_bytes = 0;
+    b.codes_off = b.params_off;
+  }
+  b.bytes = (b.codes_off + (K * L + 2) * jt * code_bytes + 15) & ~15;
   return b;
 }
 // A layer has a wide form when its table is on 64-column tiles and the wide slice fits twice into the LDS beside the
 // record buffers of the 8-byte records it is used with.  (On 32-column tiles the kernel's LDS reads come in eight
 // short runs per wave and bound it: measured 12 % slower than the byte form on the 1024x1024 layer, whose wide
 // slices only fit at that width.)
-inline bool has_wide_form(int jt, int K, int L, int scheme, int value_repr, int param_dtype) {
-  return jt == 64 && wide_blob_layout(K, L, jt, scheme, value_repr, param_dtype).bytes <= lds_slice_budget(LUTKAN_REPR_PHI);
+inline bool has_wide_form(int jt, int K, int L, int scheme, int value_repr, int param_dtype, int code_bytes) {
+  if (code_bytes != 2 && code_bytes != 4) return false;
+  return jt == 64 && wide_blob_layout(K, L, jt, scheme, value_repr, param_dtype, code_bytes).bytes <= lds_slice_budget(LUTKAN_REPR_PHI);
 }
 
 // Column-tile width of a layer's LUT table: the widest power of two in 4 .. 64 (not wider than the next power of two

@@ -218,7 +218,7 @@ struct EdgeArgs {
   int32_t chunk;           // tiled kernels: inputs per work-group (blockIdx.y selects the chunk of inputs)
   int64_t split_stride;    // tiled kernels: floats between the partial outputs of consecutive chunks (0 if one chunk)
   int32_t accumulate;      // tiled kernel writing y itself (one chunk): add to what y holds (the base branch) instead of overwriting
-  int32_t wide;            // tiled kernel: table, jt, n_tiles, blob_bytes and the offsets describe the wide form (16-bit codes)
+  int32_t wide;            // tiled kernel: 2 or 4 when table, blob_bytes and the offsets describe a wide form (bytes per code), else 0
   int32_t deep;            // tiled kernel: the launch waits for the table to stream from HBM; keep two slices in flight
   int32_t asym;            // the layer's scheme is asymmetric uint8 (a second parameter plane)
 };
@@ -446,21 +446,25 @@ constexpr double kBaseProductMinEdges = 5e8;      // batch * d * m from which th
 //      (vmcnt counts a wave's copies in issue order: with n0 = the fewest copies any wave issues per input, "at
 //      most n0 outstanding" implies that everything older than the newest input's copies has landed.)
 //
-// WIDE: the slices come from the wide form of the table, whose codes are binary16 values already (q * 2^-24, signed):
-// a lane reads its four codes of a row as two packed pairs, and the permutes and the bias removal fall away; the
-// arithmetic after them is the same.
-template <int SCHEME, int LPR, int NP, int NW, bool BASE, bool PH, int PIPE, bool WIDE>
+// CB: bytes per code of the slices.  1: the table as compiled.  2: the wide form whose codes are binary16 values
+// already (q * 2^-24, signed): a lane reads its four codes of a row as two packed pairs, and the permutes and the
+// bias removal fall away; the arithmetic after them is the same.  4: the wide form that holds the dequantised values
+// of Eq. 10 as fp32: a lane reads its four values of both rows, nothing of the parameters, and interpolates them
+// (Sec. 4.5 step 5) with a subtraction, a multiply-add and the addition to the sum.
+template <int SCHEME, int LPR, int NP, int NW, bool BASE, bool PH, int PIPE, int CB>
 __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a) {
   static_assert(!(BASE && PH), "with the base branch the device table holds fp32 products, never binary16 parameters");
-  static_assert(!(BASE && WIDE), "the wide form is used with 8-byte records only");
-  constexpr int CB = WIDE ? 2 : 1;         // bytes per code
+  static_assert(CB == 1 || CB == 2 || CB == 4, "bytes per code");
+  constexpr bool WIDE = (CB == 2), VALUES = (CB == 4);
+  static_assert(!(BASE && CB != 1), "the wide forms are used with 8-byte records only");
+  static_assert(!(VALUES && (PH || SCHEME != 0)), "the fp32 values are the same for both schemes and any parameter type: one instance");
   static_assert(PIPE == 2 || (PIPE == 3 && !BASE && NP >= 2) || (PIPE == 4 && !BASE), "carried reads need two row steps of the same input; three buffers go with 8-byte records");
   constexpr int NBUF = (PIPE == 2) ? 2 : 3;
   constexpr bool CARRY = (PIPE == 3), DEEP = (PIPE == 4);
   // Row steps between the issue of a step's code and parameter reads and their use.  One step of the byte form (18
-  // vector instructions on each of a SIMD's four waves) covers the LDS latency; one of the wide form (12) does not:
-  // its waves spent 13 % of their cycles waiting for LDS reads, so it reads two steps ahead.
-  constexpr int AHEAD = WIDE ? 2 : 1;
+  // vector instructions on each of a SIMD's four waves) covers the LDS latency; one of the wide forms (12 or 13) does
+  // not: the waves of the binary16 form spent 13 % of their cycles waiting for LDS reads, so they read two steps ahead.
+  constexpr int AHEAD = (CB > 1) ? 2 : 1;
   static_assert(!CARRY || NP > AHEAD, "carried reads: the pipeline must fit into one input's row steps");
   extern __shared__ __align__(16) unsigned char lds[];
   constexpr int JT = 4 * LPR;
@@ -519,7 +523,8 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
   // wave waits for was issued a whole step earlier, what it issues now has a whole step to arrive.
   typedef typename std::conditional<BASE, u32x3, u32x2>::type rec_t;        // 12-byte or 8-byte LDS read
   // parameters of the lane's 4 columns as loaded: pa = the four alphas, pb = the four y_min (asymmetric);
-  // binary16 parameters are packed two per word in .x and .y
+  // binary16 parameters are packed two per word in .x and .y.  With fp32 values: pa = the row's four values, pb =
+  // the next row's.
   struct Fetched { unsigned c0, c1, c0b, c1b; f32x4 pa, pb; };                // c0b, c1b: columns 2 and 3 of a wide row
   // col_codes / col_params: LDS byte addresses of this lane's columns in code row 0 and parameter row 0 of a slice
   auto fetch = [&](const rec_t &rc, unsigned col_codes, unsigned col_params) {
@@ -527,11 +532,17 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
     // address = column address + (16-bit half of the record word) * (bytes per row): D = S0.u16 * S1.u16 + S2
     unsigned code_addr, param_addr;
     asm("v_mad_u32_u16 %0, %1, %2, %3 op_sel:[0,0,0,0]" : "=v"(code_addr) : "v"(rc.x), "s"(JT * CB), "v"(col_codes));
-    asm("v_mad_u32_u16 %0, %1, %2, %3 op_sel:[1,0,0,0]" : "=v"(param_addr) : "v"(rc.x), "s"(a.param_row_bytes), "v"(col_params));
     lds_bytes cp = (lds_bytes)(uintptr_t)code_addr;
-    lds_bytes pp = (lds_bytes)(uintptr_t)param_addr;
     typedef const __attribute__((address_space(3))) unsigned *lds_u32;
     typedef const __attribute__((address_space(3))) f32x4 *lds_f32x4;
+    if constexpr (VALUES) {
+      f.c0 = 0; f.c1 = 0; f.c0b = 0; f.c1b = 0;
+      f.pa = *(lds_f32x4)cp;
+      f.pb = *(lds_f32x4)(cp + JT * CB);
+      return f;
+    }
+    asm("v_mad_u32_u16 %0, %1, %2, %3 op_sel:[1,0,0,0]" : "=v"(param_addr) : "v"(rc.x), "s"(a.param_row_bytes), "v"(col_params));
+    lds_bytes pp = (lds_bytes)(uintptr_t)param_addr;
     if constexpr (WIDE) {
       typedef const __attribute__((address_space(3))) u32x2 *lds_u32x2;
       const u32x2 r0 = *(lds_u32x2)cp, r1 = *(lds_u32x2)(cp + JT * CB);
@@ -620,8 +631,9 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
       rec_t rc_new = rcq[AHEAD];
       // first touch of step p's data, and of the record whose addresses are computed next (everything older has
       // arrived then: LDS reads return in order)
-      if (SCHEME == LUTKAN_ASYM_UINT8) asm volatile("" ::"v"(f_cur.pb.x));
-      asm volatile("" ::"v"(f_cur.pa.x), "v"(f_cur.c1), "v"(rcq[AHEAD].y));
+      if (SCHEME == LUTKAN_ASYM_UINT8 || VALUES) asm volatile("" ::"v"(f_cur.pb.x));
+      if (VALUES) asm volatile("" ::"v"(f_cur.pa.x), "v"(rcq[AHEAD].y));
+      else asm volatile("" ::"v"(f_cur.pa.x), "v"(f_cur.c1), "v"(rcq[AHEAD].y));
       __builtin_amdgcn_sched_barrier(0);
       if (p + AHEAD + 1 < NP) rc_new = *reinterpret_cast<const rec_t *>(rec_buf + (p + AHEAD + 1) * (RPS * RB));
       else if (CARRY) rc_new = *reinterpret_cast<const rec_t *>(rec_ahead + (p + AHEAD + 1 - NP) * (RPS * RB));
@@ -629,6 +641,18 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
       else if (CARRY) f_new = fetch(rcq[AHEAD], ahead_codes, ahead_params);
       __builtin_amdgcn_sched_barrier(0);
       const float w = __uint_as_float(rc_cur.y);
+      if constexpr (VALUES) {
+        // v0 + w * (v1 - v0) of the two dequantised values: three roundings, then the one of the sum.  The multiply-add
+        // is written in its two-operand encoding, which issues faster than the three-operand one the compiler
+        // picks here (v0 is dead afterwards, so it may be overwritten).
+        float v[4] = {f_cur.pa.x, f_cur.pa.y, f_cur.pa.z, f_cur.pa.w};
+        const float dv[4] = {f_cur.pb.x - f_cur.pa.x, f_cur.pb.y - f_cur.pa.y, f_cur.pb.z - f_cur.pa.z, f_cur.pb.w - f_cur.pa.w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          asm("v_fmac_f32 %0, %1, %2" : "+v"(v[c]) : "v"(w), "v"(dv[c]));
+          acc[p][c] += v[c];
+        }
+      } else {
       float al[4], ym[4];
       if constexpr (PH) {
         const f16x2 a01 = bits_to_f16x2(__float_as_uint(f_cur.pa.x)), a23 = bits_to_f16x2(__float_as_uint(f_cur.pa.y));
@@ -675,6 +699,7 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
         acc[p][2] = fmaf(base_gain.z, silu_x, acc[p][2]);
         acc[p][3] = fmaf(base_gain.w, silu_x, acc[p][3]);
       }
+      }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int k = 0; k < AHEAD; ++k) rcq[k] = rcq[k + 1];
@@ -694,7 +719,8 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
 #pragma unroll
   for (int p = 0; p < NP; ++p) {
 #pragma unroll
-    for (int c = 0; c < 4; ++c) acc[p][c] *= kTwoTo24;                         // exact: undo the 2^-24 of the codes
+    for (int c = 0; c < 4; ++c)
+      if (!VALUES) acc[p][c] *= kTwoTo24;                                      // exact: undo the 2^-24 of the codes
     const int64_t b = b0 + p * RPS + hrow;
     if (b < a.B) {
       if (j + 3 < a.m && (a.m & 3) == 0) {
@@ -897,8 +923,9 @@ int validate_layer(const lutkan_dev_layer *l, const char *who) {
   if (l->blob_bytes != lutkan::blob_layout(l->K, l->L, l->jt, l->scheme, l->value_repr, l->param_dtype).bytes) return fail(LUTKAN_ESHAPE, "%s: blob_bytes does not match K, L, jt, scheme, param_dtype", who);
   if ((reinterpret_cast<uintptr_t>(l->table) & 15) != 0) return fail(LUTKAN_EINVAL, "%s: table must be 16-byte aligned", who);
   if (l->wide_table) {
-    if (!lutkan::has_wide_form(l->jt, l->K, l->L, l->scheme, l->value_repr, l->param_dtype)) return fail(LUTKAN_EINVAL, "%s: wide_table set on a layer that has no wide form", who);
-    if (l->wide_blob_bytes != lutkan::wide_blob_layout(l->K, l->L, l->jt, l->scheme, l->value_repr, l->param_dtype).bytes) return fail(LUTKAN_ESHAPE, "%s: wide_blob_bytes does not match K, L, jt, scheme, param_dtype", who);
+    const int cb = l->wide_code_bytes;
+    if (!lutkan::has_wide_form(l->jt, l->K, l->L, l->scheme, l->value_repr, l->param_dtype, cb)) return fail(LUTKAN_EINVAL, "%s: wide_table set on a layer that has no wide form with wide_code_bytes = %d", who, cb);
+    if (l->wide_blob_bytes != lutkan::wide_blob_layout(l->K, l->L, l->jt, l->scheme, l->value_repr, l->param_dtype, cb).bytes) return fail(LUTKAN_ESHAPE, "%s: wide_blob_bytes does not match K, L, jt, scheme, param_dtype, wide_code_bytes", who);
     if ((reinterpret_cast<uintptr_t>(l->wide_table) & 15) != 0) return fail(LUTKAN_EINVAL, "%s: wide_table must be 16-byte aligned", who);
   }
   if (l->knots_per_input != 0 && l->knots_per_input != 1) return fail(LUTKAN_EINVAL, "%s: bad knots_per_input %d", who, l->knots_per_input);
@@ -929,7 +956,7 @@ int tiled_pipe(const EdgeArgs &ea, int np) {
   const size_t lds3 = 3 * (size_t)ea.blob_bytes + (size_t)kTileWaves * 3 * rows_per_wave * 8;
   if (ea.with_base || lds3 > (size_t)kMaxTiledLds) return 2;
   if (ea.deep && !ea.wide) return 4;
-  if (ea.wide && ea.asym && np == 16) return 2;         // (what that variant carries across inputs no longer fits 128 registers)
+  if (ea.wide == 2 && ea.asym && np == 16) return 2;    // (what that variant carries across inputs no longer fits 128 registers)
   return np >= (ea.wide ? 4 : 2) ? 3 : 2;             // carried reads: more row steps per input than the kernel reads ahead
 }
 
@@ -943,25 +970,30 @@ int launch_tiled_np(const EdgeArgs &ea, hipStream_t s) {
   const int pipe = tiled_pipe(ea, NP);
   const size_t lds = (pipe == 2) ? 2 * (size_t)ea.blob_bytes + (size_t)NW * 2 * RW * (ea.with_base ? 16 : 8)
                                  : 3 * (size_t)ea.blob_bytes + (size_t)NW * 3 * RW * 8;
-#define LUTKAN_LAUNCH_TILED(BASE, PH, PIPE, WIDE)                                                                                \
+#define LUTKAN_LAUNCH_TILED(SCH, BASE, PH, PIPE, CB)                                                                             \
   do {                                                                                                                           \
     static LdsCap raised;                                                                                                        \
-    return launch_with_lds(lutkan_tiled_kernel<SCHEME, LPR, NP, NW, BASE, PH, PIPE, WIDE>, &raised, grid, lds, s, ea, "lutkan_tiled_kernel"); \
+    return launch_with_lds(lutkan_tiled_kernel<SCH, LPR, NP, NW, BASE, PH, PIPE, CB>, &raised, grid, lds, s, ea, "lutkan_tiled_kernel"); \
   } while (0)
   if (ea.with_base) {
     if (ea.wide) return fail(LUTKAN_EINVAL, "lutkan_tiled_kernel: the wide table goes with 8-byte records");
-    LUTKAN_LAUNCH_TILED(true, false, 2, false);
+    LUTKAN_LAUNCH_TILED(SCHEME, true, false, 2, 1);
   }
-  if (pipe == 4) { if (ea.param_fp16) LUTKAN_LAUNCH_TILED(false, true, 4, false); else LUTKAN_LAUNCH_TILED(false, false, 4, false); }
-  if constexpr (NP >= 4) {
-    if (pipe == 3 && ea.wide) { if (ea.param_fp16) LUTKAN_LAUNCH_TILED(false, true, 3, true); else LUTKAN_LAUNCH_TILED(false, false, 3, true); }
+  if (ea.wide && LPR != 16) return fail(LUTKAN_EINVAL, "lutkan_tiled_kernel: the wide table goes with 64-column tiles");
+  if (pipe == 4) { if (ea.param_fp16) LUTKAN_LAUNCH_TILED(SCHEME, false, true, 4, 1); else LUTKAN_LAUNCH_TILED(SCHEME, false, false, 4, 1); }
+  if constexpr (LPR == 16) {
+    if constexpr (NP >= 4) {
+      if (pipe == 3 && ea.wide == 4) LUTKAN_LAUNCH_TILED(0, false, false, 3, 4);
+      if (pipe == 3 && ea.wide == 2) { if (ea.param_fp16) LUTKAN_LAUNCH_TILED(SCHEME, false, true, 3, 2); else LUTKAN_LAUNCH_TILED(SCHEME, false, false, 3, 2); }
+    }
+    if (ea.wide == 4) LUTKAN_LAUNCH_TILED(0, false, false, 2, 4);
+    if (ea.wide == 2) { if (ea.param_fp16) LUTKAN_LAUNCH_TILED(SCHEME, false, true, 2, 2); else LUTKAN_LAUNCH_TILED(SCHEME, false, false, 2, 2); }
   }
   if constexpr (NP >= 2) {
-    if (pipe == 3 && !ea.wide) { if (ea.param_fp16) LUTKAN_LAUNCH_TILED(false, true, 3, false); else LUTKAN_LAUNCH_TILED(false, false, 3, false); }
+    if (pipe == 3) { if (ea.param_fp16) LUTKAN_LAUNCH_TILED(SCHEME, false, true, 3, 1); else LUTKAN_LAUNCH_TILED(SCHEME, false, false, 3, 1); }
   }
-  if (ea.wide) { if (ea.param_fp16) LUTKAN_LAUNCH_TILED(false, true, 2, true); else LUTKAN_LAUNCH_TILED(false, false, 2, true); }
-  if (ea.param_fp16) LUTKAN_LAUNCH_TILED(false, true, 2, false);
-  LUTKAN_LAUNCH_TILED(false, false, 2, false);
+  if (ea.param_fp16) LUTKAN_LAUNCH_TILED(SCHEME, false, true, 2, 1);
+  LUTKAN_LAUNCH_TILED(SCHEME, false, false, 2, 1);
 #undef LUTKAN_LAUNCH_TILED
 }
 
@@ -1101,13 +1133,14 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   // 2048 rows 0.056 -> 0.071 (three more launches): hence the floor on the work of the layer.
   const bool base_by_product = with_base && tiled && (double)B * l->d * l->m >= kBaseProductMinEdges && lutkan::base_product_fits(l->d, l->m, B);
   const int rec_bytes = (with_base && !base_by_product) ? 16 : 8;
-  // The wide form of the table (16-bit codes, a third fewer vector instructions per edge, twice the table bytes),
-  // where the layer has one and the launch planning prices it lower.
+  // A wide form of the table (16-bit codes or fp32 values: fewer vector instructions per edge, two or four times the
+  // table bytes), where the layer has one and the launch planning prices it lower.
   const bool can_wide = tiled && l->wide_table != nullptr && rec_bytes == 8;
-  const TilePlan tpw = can_wide ? plan_tiles(B, l->d, l->m, l->n_tiles, 64 / (l->jt / 4), l->wide_blob_bytes, true) : tp;
-  // (with y_min the wide row step reads 56 bytes per lane from LDS and measured within 3 % of the byte form either
-  // way on 256x256 and 128x128 layers: left to the byte form unless asked for)
-  const bool wide = can_wide && ((tpw.cost < tp.cost && l->scheme == LUTKAN_SYM_INT8) || l->algo == LUTKAN_ALGO_TILED_WIDE);
+  const int wide_cb = l->wide_code_bytes;
+  const TilePlan tpw = can_wide ? plan_tiles(B, l->d, l->m, l->n_tiles, 64 / (l->jt / 4), l->wide_blob_bytes, wide_cb) : tp;
+  // (with y_min the row step on 16-bit codes reads 56 bytes per lane from LDS and measured within 3 % of the byte form
+  // either way on 256x256 and 128x128 layers: left to the byte form unless asked for)
+  const bool wide = can_wide && ((tpw.cost < tp.cost && (wide_cb == 4 || l->scheme == LUTKAN_SYM_INT8)) || l->algo == LUTKAN_ALGO_TILED_WIDE);
   if (l->algo == LUTKAN_ALGO_TILED_WIDE && !wide)
     return fail(LUTKAN_EUNSUPPORTED, "%s: algo TILED_WIDE on a layer %s", who, l->wide_table ? "whose base branch runs inside the edge kernel (16-byte records)" : "without a wide table");
   // workspace: [records: room for 16 bytes each with the base branch; 8-byte records leave room for the 6 bytes per
@@ -1176,9 +1209,13 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   if (tiled) {
     const TilePlan &plan = wide ? tpw : tp;
     if (wide) {
-      ea.table = static_cast<const unsigned char *>(l->wide_table);       // same tiles, offsets and parameters, longer code rows
+      ea.table = static_cast<const unsigned char *>(l->wide_table);       // same tiles, longer code rows
       ea.blob_bytes = l->wide_blob_bytes;
-      ea.wide = 1;
+      ea.wide = wide_cb;
+      if (wide_cb == 4) {                                                   // no parameter rows: the value rows follow the base row
+        ea.codes_off = lay.params_off; ea.params_off = lay.params_off; ea.param_row_bytes = 0;
+        ea.param_fp16 = 0;
+      }
     }
     ea.chunk = plan.chunk;
     ea.deep = plan.hbm_bound ? 1 : 0;
@@ -1186,7 +1223,7 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
     ea.accumulate = (base_by_product && plan.n_split == 1) ? 1 : 0;     // with chunks, the summing pass adds to y instead
     const int rc = (l->scheme == LUTKAN_SYM_INT8) ? launch_tiled_jt<LUTKAN_SYM_INT8>(ea, plan.np, s) : launch_tiled_jt<LUTKAN_ASYM_UINT8>(ea, plan.np, s);
     if (rc) return rc;
-    lutkan::plan_note("tiled%s np=%d split=%d pipe=%d; ", wide ? " wide" : "", plan.np, plan.n_split, tiled_pipe(ea, plan.np));
+    lutkan::plan_note("tiled%s np=%d split=%d pipe=%d; ", !wide ? "" : wide_cb == 4 ? " wide32" : " wide", plan.np, plan.n_split, tiled_pipe(ea, plan.np));
     if (plan.n_split == 1) return rc;
     const int64_t n = B * l->m;
     hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, s, partials, y, n, plan.n_split, base_by_product ? 1 : 0);
@@ -1249,7 +1286,7 @@ extern "C" size_t lutkan_forward_workspace_bytes(const lutkan_dev_layer *layer, 
   if (layer->jt < 4 || layer->jt > 64 || (layer->jt & (layer->jt - 1))) return 0;
   size_t bytes = tiled_workspace_bytes(layer->d, layer->m, layer->jt, layer->n_tiles, B, lut_record_bytes(layer->value_repr), layer->blob_bytes);
   if (layer->wide_table && layer->wide_blob_bytes >= 1)
-    bytes = std::max(bytes, tiled_workspace_bytes(layer->d, layer->m, layer->jt, layer->n_tiles, B, lut_record_bytes(layer->value_repr), layer->wide_blob_bytes, true));
+    bytes = std::max(bytes, tiled_workspace_bytes(layer->d, layer->m, layer->jt, layer->n_tiles, B, lut_record_bytes(layer->value_repr), layer->wide_blob_bytes, layer->wide_code_bytes));
   return bytes + (layer->value_repr == LUTKAN_REPR_SPLINE_COMPONENT ? lutkan::base_product_workspace_bytes(layer->d, layer->m) : 0);
 }
 
@@ -1263,6 +1300,8 @@ struct WidenArgs {
   unsigned char *dst;                // wide table, slices [t][i]
   int32_t jt, src_blob, dst_blob, codes_off, n_code_rows;
   int32_t sym;
+  // fp32 values only
+  int32_t params_off, param_row_bytes, L, K, param_fp16;
 };
 
 // One work-group per slice (t, i).  Base row and parameter rows are copied as they are (16 bytes per thread and
@@ -1282,20 +1321,48 @@ __global__ __launch_bounds__(256) void lutkan_widen_kernel(const WidenArgs a) {
   for (int e = a.codes_off + n_codes * 2 + threadIdx.x; e < a.dst_blob; e += 256) dst[e] = 0;      // padding to 16 bytes
 }
 
-}  // namespace
-
-extern "C" size_t lutkan_wide_table_bytes(const lutkan_dev_layer *layer) {
-  if (!layer || layer->d < 1 || layer->m < 1 || layer->n_tiles < 1 || layer->K < 1 || layer->L < 2 || layer->K > LUTKAN_MAX_K) return 0;
-  if (!lutkan::has_wide_form(layer->jt, layer->K, layer->L, layer->scheme, layer->value_repr, layer->param_dtype)) return 0;
-  return (size_t)layer->n_tiles * layer->d * lutkan::wide_blob_layout(layer->K, layer->L, layer->jt, layer->scheme, layer->value_repr, layer->param_dtype).bytes;
+// One work-group per slice (t, i).  The base row is copied; every code becomes the value of Eq. 10 in fp32 arithmetic,
+// fl(y_min + fl(alpha * q)) with the parameters of its segment (row / L; the rows past K*L take the all-zero
+// parameter row K and come out zero).  The value rows start where the parameter rows of the byte table do.
+__global__ __launch_bounds__(256) void lutkan_dequantise_kernel(const WidenArgs a) {
+  const unsigned char *src = a.src + (size_t)blockIdx.x * a.src_blob;
+  unsigned char *dst = a.dst + (size_t)blockIdx.x * a.dst_blob;
+  for (int e = threadIdx.x * 16; e < a.params_off; e += 256 * 16) *reinterpret_cast<u32x4 *>(dst + e) = *reinterpret_cast<const u32x4 *>(src + e);
+  const int n_codes = a.n_code_rows * a.jt;
+  float *dv = reinterpret_cast<float *>(dst + a.params_off);
+  for (int e = threadIdx.x; e < n_codes; e += 256) {
+    const int row = e / a.jt, col = e - row * a.jt;
+    const int byte = src[a.codes_off + e];
+    const int q = a.sym ? byte - 128 : byte;
+    const unsigned char *prow = src + a.params_off + (size_t)min(row / a.L, a.K) * a.param_row_bytes;
+    float alpha, y_min = 0.0f;
+    if (a.param_fp16) {
+      alpha = (float)reinterpret_cast<const _Float16 *>(prow)[col];
+      if (!a.sym) y_min = (float)reinterpret_cast<const _Float16 *>(prow)[a.jt + col];
+    } else {
+      alpha = reinterpret_cast<const float *>(prow)[col];
+      if (!a.sym) y_min = reinterpret_cast<const float *>(prow)[a.jt + col];
+    }
+    dv[e] = __fadd_rn(y_min, __fmul_rn(alpha, (float)q));
+  }
+  for (int e = a.params_off + n_codes * 4 + threadIdx.x; e < a.dst_blob; e += 256) dst[e] = 0;     // padding to 16 bytes
 }
 
-extern "C" int lutkan_wide_table_build(lutkan_dev_layer *layer, void *wide_table, size_t bytes, void *hip_stream) {
+}  // namespace
+
+extern "C" size_t lutkan_wide_table_bytes(const lutkan_dev_layer *layer, int32_t code_bytes) {
+  if (!layer || layer->d < 1 || layer->m < 1 || layer->n_tiles < 1 || layer->K < 1 || layer->L < 2 || layer->K > LUTKAN_MAX_K) return 0;
+  if (!lutkan::has_wide_form(layer->jt, layer->K, layer->L, layer->scheme, layer->value_repr, layer->param_dtype, code_bytes)) return 0;
+  return (size_t)layer->n_tiles * layer->d * lutkan::wide_blob_layout(layer->K, layer->L, layer->jt, layer->scheme, layer->value_repr, layer->param_dtype, code_bytes).bytes;
+}
+
+extern "C" int lutkan_wide_table_build(lutkan_dev_layer *layer, int32_t code_bytes, void *wide_table, size_t bytes, void *hip_stream) {
   const char *who = "lutkan_wide_table_build";
-  if (layer) { layer->wide_table = nullptr; layer->wide_blob_bytes = 0; }
+  if (layer) { layer->wide_table = nullptr; layer->wide_blob_bytes = 0; layer->wide_code_bytes = 0; }
   if (int rc = validate_layer(layer, who)) return rc;
-  const size_t need = lutkan_wide_table_bytes(layer);
-  if (!need) return fail(LUTKAN_EUNSUPPORTED, "%s: the layer has no wide form (64-column tiles whose wide slice fits the LDS twice; jt = %d, K*L = %d)", who, layer->jt, layer->K * layer->L);
+  if (code_bytes != 2 && code_bytes != 4) return fail(LUTKAN_EINVAL, "%s: code_bytes %d (2: binary16 codes, 4: fp32 values)", who, code_bytes);
+  const size_t need = lutkan_wide_table_bytes(layer, code_bytes);
+  if (!need) return fail(LUTKAN_EUNSUPPORTED, "%s: the layer has no wide form of %d bytes per code (64-column tiles whose wide slice fits the LDS twice; jt = %d, K*L = %d)", who, code_bytes, layer->jt, layer->K * layer->L);
   if (!wide_table || (reinterpret_cast<uintptr_t>(wide_table) & 15) != 0) return fail(LUTKAN_EINVAL, "%s: wide_table must be a 16-byte aligned device pointer", who);
   if (bytes < need) return fail(LUTKAN_ESHAPE, "%s: %zu bytes, need %zu", who, bytes, need);
   if ((int64_t)layer->n_tiles * layer->d > 0x7fffffffLL) return fail(LUTKAN_EUNSUPPORTED, "%s: too many slices", who);
@@ -1305,14 +1372,19 @@ extern "C" int lutkan_wide_table_build(lutkan_dev_layer *layer, void *wide_table
   a.dst = static_cast<unsigned char *>(wide_table);
   a.jt = layer->jt;
   a.src_blob = layer->blob_bytes;
-  a.dst_blob = lutkan::wide_blob_layout(layer->K, layer->L, layer->jt, layer->scheme, layer->value_repr, layer->param_dtype).bytes;
+  a.dst_blob = lutkan::wide_blob_layout(layer->K, layer->L, layer->jt, layer->scheme, layer->value_repr, layer->param_dtype, code_bytes).bytes;
   a.codes_off = lay.codes_off;
   a.n_code_rows = layer->K * layer->L + 2;
   a.sym = (layer->scheme == LUTKAN_SYM_INT8);
-  hipLaunchKernelGGL(lutkan_widen_kernel, dim3((unsigned)((int64_t)layer->n_tiles * layer->d)), dim3(256), 0, static_cast<hipStream_t>(hip_stream), a);
-  if (int rc = check_launch("lutkan_widen_kernel")) return rc;
+  a.params_off = lay.params_off; a.param_row_bytes = lay.param_row_bytes; a.L = layer->L; a.K = layer->K;
+  a.param_fp16 = lutkan::device_params_are_half(layer->value_repr, layer->param_dtype, layer->jt);
+  const dim3 grid((unsigned)((int64_t)layer->n_tiles * layer->d));
+  if (code_bytes == 2) hipLaunchKernelGGL(lutkan_widen_kernel, grid, dim3(256), 0, static_cast<hipStream_t>(hip_stream), a);
+  else hipLaunchKernelGGL(lutkan_dequantise_kernel, grid, dim3(256), 0, static_cast<hipStream_t>(hip_stream), a);
+  if (int rc = check_launch(code_bytes == 2 ? "lutkan_widen_kernel" : "lutkan_dequantise_kernel")) return rc;
   layer->wide_table = wide_table;
   layer->wide_blob_bytes = a.dst_blob;
+  layer->wide_code_bytes = code_bytes;
   return LUTKAN_OK;
 }
 

@@ -159,11 +159,13 @@ WIDE_CASES = [
 ]
 
 
+@pytest.mark.parametrize("cb", [2, 4], ids=["binary16_codes", "fp32_values"])
 @pytest.mark.parametrize("case", WIDE_CASES, ids=lambda c: f"seed{c[0]}")
-def test_wide_table_form(case):
-    """The second form of the device table (16-bit codes: no byte unpacking in the tiled kernel) against the oracle,
-    to the bar of every other path, and against the byte form: the arithmetic after the unpacking is the same, so
-    with the same launch plan the outputs agree bit for bit."""
+def test_wide_table_form(case, cb):
+    """The wide forms of the device table against the oracle, to the bar of every other path.  16-bit codes (no byte
+    unpacking in the tiled kernel): the arithmetic after the unpacking is that of the byte form, so with the same launch
+    plan the outputs agree bit for bit.  fp32 values (Eq. 10 applied when the table is built, the kernel interpolates
+    the values): a different rounding order, so only the oracle is the measure."""
     seed, d, m, G, L, scheme, boundary, oob, B, with_base = case
     w = random_layer(seed, d, m, G, L, scheme, boundary, oob, B, uniform=(seed % 2 == 0), oob_frac=0.3, with_base=with_base)
     s = w.layers[0]
@@ -172,26 +174,38 @@ def test_wide_table_form(case):
         x[B // 2, d // 3] = np.nan
     art, ora = _compile_both(s)
     assert art.info.jt == 64
-    wide, byte = _device_layer(art, s, lk.ALGO_TILED_WIDE, wide=True), _device_layer(art, s, lk.ALGO_TILED, wide=False)
-    assert wide.wide_table is not None and byte.wide_table is None
-    assert wide.wide_table.numel() == art.info.table_bytes + art.info.n_tiles * d * (art.info.K * L + 2) * 64
+    value_rows_fit = (art.info.K * L + 2 + with_base) * 256 <= 72 * 1024
+    if cb == 4 and not value_rows_fit:
+        with pytest.raises(lk.LutKanError) as e:
+            art.to_device(DEV, wide=4)
+        assert "no wide table form of 4 bytes" in str(e.value)
+        assert art.to_device(DEV, wide=True).c.wide_code_bytes == 2           # "any": the form the layer has
+        return
+    wide, byte = _device_layer(art, s, lk.ALGO_TILED_WIDE, wide=cb), _device_layer(art, s, lk.ALGO_TILED, wide=False)
+    assert wide.wide_table is not None and byte.wide_table is None and wide.c.wide_code_bytes == cb
+    if cb == 2:
+        assert wide.wide_table.numel() == art.info.table_bytes + art.info.n_tiles * d * (art.info.K * L + 2) * 64
+    else:
+        assert wide.wide_table.numel() == art.info.n_tiles * d * (art.info.K * L + 2 + with_base) * 256
+        assert art.to_device(DEV, wide=True).c.wide_code_bytes == 4
     xg = torch.from_numpy(x).to(DEV)
     if with_base and B * d * m < 5e8:
         # 16-byte records (the base branch inside the edge kernel) go with the byte form only
         with pytest.raises(lk.LutKanError) as e:
             lk.lutkan_forward(wide, xg)
         assert str(e.value).startswith("[-5]") and "16-byte records" in str(e.value)
-        _check_layer(s, x, lk.ALGO_TILED, what=w.name + " (wide table present, byte form runs)", wide=True)
+        _check_layer(s, x, lk.ALGO_TILED, what=w.name + " (wide table present, byte form runs)", wide=cb)
         assert "tiled np=" in lk.lutkan_last_plan()
         return
-    worst = _check_layer(s, x, lk.ALGO_TILED_WIDE, what=w.name + " (wide form)", wide=True)
+    tag = "tiled wide np=" if cb == 2 else "tiled wide32 np="
+    worst = _check_layer(s, x, lk.ALGO_TILED_WIDE, what=w.name + f" (wide form, {cb} bytes per code)", wide=cb)
     y_wide = lk.lutkan_forward(wide, xg)
     plan_wide = lk.lutkan_last_plan()
     y_byte = lk.lutkan_forward(byte, xg)
     plan_byte = lk.lutkan_last_plan()
     _say(f"wide: {plan_wide!r}  byte: {plan_byte!r}  worst error / tolerance {worst:.3g}")
-    assert "tiled wide np=" in plan_wide and " wide" not in plan_byte
-    if plan_wide.replace("tiled wide", "tiled") == plan_byte:
+    assert tag in plan_wide and " wide" not in plan_byte
+    if cb == 2 and plan_wide.replace("tiled wide", "tiled") == plan_byte:
         assert bool(((y_wide == y_byte) | (torch.isnan(y_wide) & torch.isnan(y_byte))).all())
     # the two phases apart, and the entry point with the built-in scratch, take the same form
     ws = torch.empty(lk.lutkan_forward_workspace_bytes(wide, B), dtype=torch.uint8, device=DEV)
@@ -201,14 +215,16 @@ def test_wide_table_form(case):
     if lk.lutkan_forward_workspace_bytes(wide, B) <= lk.STATIC_SCRATCH_BYTES:
         y_static = lk.lutkan_forward_static_scratch(wide, xg, torch.full((B, m), -3.0, dtype=torch.float32, device=DEV))
         assert bool(((y_static == y_wide) | (torch.isnan(y_static) & torch.isnan(y_wide))).all())
-    # left to the launch planning, the wide form runs on large batches of symmetric layers
-    auto = _device_layer(art, s, lk.ALGO_AUTO, wide=True)
+    # left to the launch planning: 16-bit codes run on large batches of symmetric layers, fp32 values with both schemes
+    auto = _device_layer(art, s, lk.ALGO_AUTO, wide=cb)
     lk.lutkan_forward(auto, xg)
-    if scheme == ASYM_UINT8:
+    if cb == 2 and scheme == ASYM_UINT8:
         assert " wide" not in lk.lutkan_last_plan(), lk.lutkan_last_plan()
     elif B * d * m >= 2e8:
-        assert "tiled wide np=" in lk.lutkan_last_plan(), lk.lutkan_last_plan()
-    assert (art.to_device(DEV).wide_table is not None) == (scheme == SYM_INT8 and d * m >= 4096)    # the default upload
+        assert tag in lk.lutkan_last_plan(), lk.lutkan_last_plan()
+    # the default upload: fp32 values where they fit, else 16-bit codes for symmetric layers; layers of some size only
+    default = art.to_device(DEV).c.wide_code_bytes
+    assert default == (0 if d * m < 4096 else 4 if value_rows_fit else 2 if scheme == SYM_INT8 else 0)
 
 
 def test_wide_table_form_exists_only_where_it_pays():

@@ -336,35 +336,55 @@ def test_wide_table_form_sizes_and_refusals():
         assert I.jt == 64
         wide_blob = I.blob_bytes + (I.K * L + 2) * 64               # every code one byte longer, the rest of the slice as it is
         assert wide_blob % 16 == 0 and 2 * wide_blob + 16 * 2 * 64 * 8 <= 160 * 1024
-        assert lib.lutkan_wide_table_bytes(C.byref(dl)) == I.n_tiles * 3 * wide_blob
+        assert lib.lutkan_wide_table_bytes(C.byref(dl), 2) == I.n_tiles * 3 * wide_blob
+        # fp32 values: the base row (with edge scales), then one 256-byte row per code row and no parameter rows
+        values_blob = (256 if scales else 0) + (I.K * L + 2) * 256
+        fits = 2 * values_blob + 16 * 2 * 64 * 8 <= 160 * 1024
+        assert fits == (L == 32)
+        assert lib.lutkan_wide_table_bytes(C.byref(dl), 4) == (I.n_tiles * 3 * values_blob if fits else 0)
+        for cb in (0, 1, 3, 8):
+            assert lib.lutkan_wide_table_bytes(C.byref(dl), cb) == 0
     # no wide form: tiles narrower than 64 columns; slices that do not fit the LDS twice (642 and 1026 code rows)
     for m, G, L in ((32, 5, 16), (16, 8, 64), (128, 10, 64), (128, 8, 128)):
         art, dl = dev_layer(m, G, L, SYM_INT8)
-        assert lib.lutkan_wide_table_bytes(C.byref(dl)) == 0
         dl.table = 4096
-        assert lib.lutkan_wide_table_build(C.byref(dl), 8192, 1 << 30, None) == -5 and "no wide form" in lk.lutkan_last_error()
-    assert lib.lutkan_wide_table_bytes(None) == 0
+        for cb in (2, 4):
+            assert lib.lutkan_wide_table_bytes(C.byref(dl), cb) == 0
+            assert lib.lutkan_wide_table_build(C.byref(dl), cb, 8192, 1 << 30, None) == -5 and "no wide form" in lk.lutkan_last_error()
+    assert lib.lutkan_wide_table_bytes(None, 2) == 0
 
     art, dl = dev_layer(130, 8, 64, SYM_INT8)
-    need = lib.lutkan_wide_table_bytes(C.byref(dl))
-    assert lib.lutkan_wide_table_build(C.byref(dl), 8192, need, None) == -1 and "table is null" in lk.lutkan_last_error()
+    need = lib.lutkan_wide_table_bytes(C.byref(dl), 2)
+    assert lib.lutkan_wide_table_build(C.byref(dl), 2, 8192, need, None) == -1 and "table is null" in lk.lutkan_last_error()
     dl.table = 4096
-    assert lib.lutkan_wide_table_build(C.byref(dl), None, need, None) == -1
-    assert lib.lutkan_wide_table_build(C.byref(dl), 8192 + 8, need, None) == -1 and "aligned" in lk.lutkan_last_error()
-    assert lib.lutkan_wide_table_build(C.byref(dl), 8192, need - 1, None) == -2 and str(need) in lk.lutkan_last_error()
-    assert lib.lutkan_wide_table_build(None, 8192, need, None) == -1
-    assert not dl.wide_table and dl.wide_blob_bytes == 0             # a refused build leaves the layer without
+    assert lib.lutkan_wide_table_build(C.byref(dl), 2, None, need, None) == -1
+    assert lib.lutkan_wide_table_build(C.byref(dl), 2, 8192 + 8, need, None) == -1 and "aligned" in lk.lutkan_last_error()
+    assert lib.lutkan_wide_table_build(C.byref(dl), 2, 8192, need - 1, None) == -2 and str(need) in lk.lutkan_last_error()
+    assert lib.lutkan_wide_table_build(C.byref(dl), 3, 8192, need, None) == -1 and "code_bytes" in lk.lutkan_last_error()
+    assert lib.lutkan_wide_table_build(C.byref(dl), 4, 8192, 1 << 30, None) == -5       # 514 rows of 256 bytes do not fit twice
+    assert lib.lutkan_wide_table_build(None, 2, 8192, need, None) == -1
+    assert not dl.wide_table and dl.wide_blob_bytes == 0 and dl.wide_code_bytes == 0      # a refused build leaves the layer without
     # a layer whose wide fields do not fit its shape is refused by every forward call
     ws_bytes = lib.lutkan_forward_workspace_bytes(C.byref(dl), 64)
-    dl.wide_table, dl.wide_blob_bytes = 8192, art.info.blob_bytes
+    dl.wide_table, dl.wide_blob_bytes, dl.wide_code_bytes = 8192, art.info.blob_bytes, 2
     assert lib.lutkan_forward(C.byref(dl), 16, 64, 32, None, 256, 1 << 30, None) == -2 and "wide_blob_bytes" in lk.lutkan_last_error()
     dl.wide_table, dl.wide_blob_bytes = 8192 + 4, art.info.blob_bytes + (art.info.K * 64 + 2) * 64
     assert lib.lutkan_forward(C.byref(dl), 16, 64, 32, None, 256, 1 << 30, None) == -1 and "wide_table" in lk.lutkan_last_error()
     dl.wide_table = 8192
     assert lib.lutkan_forward_workspace_bytes(C.byref(dl), 64) >= ws_bytes
+    for cb in (0, 1, 4):                                             # no such form, or none of this layer
+        dl.wide_code_bytes = cb
+        assert lib.lutkan_forward(C.byref(dl), 16, 64, 32, None, 256, 1 << 30, None) == -1 and "no wide form" in lk.lutkan_last_error()
     _, narrow = dev_layer(32, 5, 16, SYM_INT8)
-    narrow.table, narrow.wide_table, narrow.wide_blob_bytes = 4096, 8192, 4096
+    narrow.table, narrow.wide_table, narrow.wide_blob_bytes, narrow.wide_code_bytes = 4096, 8192, 4096, 2
     assert lib.lutkan_forward(C.byref(narrow), 16, 64, 32, None, 256, 1 << 30, None) == -1 and "no wide form" in lk.lutkan_last_error()
+    # the fp32 form of a small asymmetric layer: its size is checked the same way
+    art, small = dev_layer(64, 5, 32, ASYM_UINT8)
+    small.table, small.wide_table, small.wide_code_bytes = 4096, 8192, 4
+    small.wide_blob_bytes = (art.info.K * 32 + 2) * 256
+    assert lib.lutkan_forward(C.byref(small), 16, 0, 32, None, 256, 1 << 30, None) == 0   # B = 0: validated, nothing launched
+    small.wide_blob_bytes += 16
+    assert lib.lutkan_forward(C.byref(small), 16, 0, 32, None, 256, 1 << 30, None) == -2 and "wide_blob_bytes" in lk.lutkan_last_error()
 
 
 def test_spline_component_tables_carry_the_base_row_and_folded_gains():
