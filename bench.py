@@ -329,6 +329,10 @@ def run_workload(rig, name, steps, warmup, batch=None, bspline=True, cpu_baselin
                     "peak_published_packed_fp32": PEAK_FP32_PACKED_TFLOPS,
                     "frac_vs_published_packed_fp32": round(achieved / PEAK_FP32_PACKED_TFLOPS, 4),
                     "flop_per_edge_eval": FLOP_PER_EDGE}
+    if "wide32" in dominant["plan"]:
+        roofline["note"] = ("this launch reads the table's fp32-value form: Eq. 10 was applied when that table was built, so 5 of the "
+                            "8 algorithmic flops per edge evaluation execute in the kernel (13 vector instructions per 4 edges); "
+                            "'achieved' counts all 8")
     roofline.update({"traffic": traffic, "traffic_source": source, "kernel_ms": round(dominant["ms"], 5), "layer": dominant["layer"],
                      "launch_plan": dominant["plan"], "compulsory_hbm_bytes": int(hbm_bytes),
                      "hbm_time_floor_ms": round(hbm_bytes / PEAK_HBM_BPS * 1e3, 5), "terms": terms})
@@ -449,7 +453,7 @@ def main():
     ap.add_argument("--batch", type=int, default=None, help="override the workload's number of rows")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bspline", action="store_true")
-    ap.add_argument("--no-wide-tables", action="store_true", help="byte form of the LUT table only (no second copy with 16-bit codes)")
+    ap.add_argument("--no-wide-tables", action="store_true", help="byte form of the LUT table only (no second copy with 16-bit codes or fp32 values)")
     ap.add_argument("--no-probes", action="store_true", help="skip the peak-rate probes (FMA, instruction mix, LDS, L2, HBM)")
     ap.add_argument("--all-configs", action="store_true",
                     help="also run every workload of the scope table; their records (throughput, kernels, roofline terms, "
@@ -475,7 +479,7 @@ def main():
         torch.cuda.synchronize()
         del ca, cb
 
-    wide = False if args.no_wide_tables else None      # None: the binding's default (symmetric layers that have the form)
+    wide = False if args.no_wide_tables else None      # None: the binding's default (layers of some size that have a wide form)
     rec = run_workload(rig, args.workload, args.steps, args.warmup, batch=args.batch, wide=wide, bspline=not args.no_bspline,
                        cpu_baseline=not args.no_cpu_baseline)
     extra = {k: rec[k] for k in ("rows_per_s", "launch_plan", "step_ms_by_events", "kernels", "bspline_ms_per_step",
