@@ -64,7 +64,7 @@ const char *lutkan_version(void);
 /* What the last forward call of this thread launched, for logs and tests: one clause per kernel launch, e.g.
  * "locate; tiled np=16 split=2 pipe=3; sum; " (row steps per wave, chunks of inputs, pipeline mode: 2 = two slice
  * buffers, 3 = three with the reads carried across inputs, 4 = three with two slices in flight; "tiled wide" on the
- * wide form of the table) or "chain layers=2 wpr=4; " or "locate; gather split=16; sum; " or, for a large
+ * table's form with 16-bit codes, "tiled wide32" on the one with fp32 values) or "chain layers=2 wpr=4; " or "locate; gather split=16; sum; " or, for a large
  * spline_component layer, "locate; base_product; tiled np=16 split=1 pipe=3; " (model_forward: the clauses of all its
  * layers).  Thread-local, overwritten by the next forward call, never null. */
 const char *lutkan_last_plan(void);
