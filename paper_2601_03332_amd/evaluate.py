@@ -17,7 +17,8 @@ the same contract on the in-range and the OOB-only rows (Sec. 5.6), and the time
 With --variants it times every option combination (scheme x value_repr x parameter dtype) on the widest workload.
 With --batches it times LUT and B-spline layers of five shapes from 1 to 65536 rows (which kernel AUTO picks changes
 along the way: one-launch chain, gather with split inputs, tiled).
-With --latency it times narrow chains at batches 1 .. 65536 as per-layer launches and as the fused one-launch chain.
+With --latency it times narrow chains at batches 1 .. 65536 as per-layer launches (eager, and replayed from a HIP
+graph) and as the fused one-launch chain.
 Both layers and the error statistics (lutkan_error_stats, Sec. 5.6) run as the library's HIP kernels.  The layers
 are randomly initialised here, so the absolute numbers are not the paper's; the trends are (error halves per
 doubling of L; in-range error independent of the contract; half_open counts inputs clipped onto t_K as OOB).
@@ -268,7 +269,8 @@ def main():
 
         print()
         print("Narrow chains, L = 64, grid 5: ms per forward, synchronised after every call | back to back on the stream")
-        print(f"{'network':>18} {'options':>28} {'batch':>7} {'lutkan_forward per layer':>26} {'fused chain':>22}")
+        print("(HIP graph: the per-layer launches captured once and replayed; checked against the eager result)")
+        print(f"{'network':>18} {'options':>28} {'batch':>7} {'lutkan_forward per layer':>26} {'same, from a HIP graph':>24} {'fused chain':>22}")
         for widths, scheme, base, half, label in (((78, 16, 2), ASYM_UINT8, False, False, "uint8 phi fp32"),
                                                   ((78, 32, 16, 1), SYM_INT8, True, False, "int8 spline_component fp32"),
                                                   ((78, 32, 16, 1), ASYM_UINT8, True, True, "uint8 spline_component fp16")):
@@ -284,8 +286,19 @@ def main():
                         lk.lutkan_forward(l, src, dst, workspace=ws)
 
                 a = per_call_ms(layer_by_layer, 200)
+                y_eager = y.clone()
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph):              # (the warm-up calls above ran every launch once already)
+                    layer_by_layer()
+                y.fill_(7.0)
+                graph.replay()
+                torch.cuda.synchronize()
+                if not bool(((y == y_eager) | (torch.isnan(y) & torch.isnan(y_eager))).all()):
+                    raise SystemExit("evaluate: the graph replay differs from the eager forward")
+                g = per_call_ms(graph.replay, 200)
                 f = per_call_ms(lambda: lk.lutkan_chain_forward(layers, x, y), 200)
-                print(f"{'->'.join(map(str, widths)):>18} {label:>28} {B:>7} {a[0]:>14.4f} | {a[1]:<9.4f} {f[0]:>10.4f} | {f[1]:<9.4f}")
+                print(f"{'->'.join(map(str, widths)):>18} {label:>28} {B:>7} {a[0]:>14.4f} | {a[1]:<9.4f} {g[0]:>12.4f} | {g[1]:<9.4f} {f[0]:>10.4f} | {f[1]:<9.4f}")
+                del graph
 
 
 if __name__ == "__main__":
