@@ -238,6 +238,52 @@ def test_wide_table_form_exists_only_where_it_pays():
             art.to_device(DEV, wide=True)
 
 
+@pytest.mark.parametrize("case", [(731, 5, 130, 6, 16, SYM_INT8, False), (732, 3, 64, 5, 32, ASYM_UINT8, False),
+                                  (733, 4, 200, 8, 8, ASYM_UINT8, True), (734, 2, 70, 4, 64, SYM_INT8, True)],
+                         ids=lambda c: f"seed{c[0]}")
+def test_wide_tables_hold_exactly_what_the_codes_stand_for(case):
+    """The two wide forms as built on the device, read back and compared bit for bit with what the oracle's artifact
+    arrays say they must hold: the binary16 pattern of q * 2^-24 (sign and magnitude) resp. the fp32 value of Eq. 10,
+    fl(y_min + fl(alpha * q)), for every (tile, input, code row, column); the two rows after the last code row and
+    the columns past m are zero."""
+    seed, d, m, G, L, scheme, half = case
+    w = random_layer(seed, d, m, G, L, scheme, CLOSED, CLIP_X, 4)
+    s = w.layers[0]
+    art, ora = _compile_both(s, param_fp16=half)
+    K, jt, n_tiles = art.info.K, art.info.jt, art.info.n_tiles
+    assert jt == 64 and K == ora.K
+    rows = K * L + 2
+    q = ora.q.reshape(d, m, K * L).astype(np.int32)                  # [i][j][row]
+    alpha = np.repeat(ora.scale.reshape(d, m, K), L, axis=2)         # the parameters of each row's segment
+    y_min = np.repeat(ora.y_min.reshape(d, m, K), L, axis=2)
+    values = (y_min + (alpha * q.astype(np.float32)).astype(np.float32)).astype(np.float32)        # two fp32 roundings
+    bits16 = np.where(q < 0, 0x8000 | -q, q).astype(np.uint16)
+    _say(f"case {w.name} wide table contents, param_fp16={half}")
+    for cb, want, dtype in ((2, bits16, np.uint16), (4, values, np.float32)):
+        layer = art.to_device(DEV, wide=cb)
+        blob = layer.c.wide_blob_bytes
+        host = layer.wide_table.cpu().numpy().reshape(n_tiles, d, blob)
+        codes_off = blob - (-(-rows * jt * cb // 16) * 16)             # the code rows end the slice (padded to 16 bytes)
+        if cb == 4:
+            assert codes_off == 0                                    # phi layer: no base row, no parameter rows
+        got = np.ascontiguousarray(host[:, :, codes_off:codes_off + rows * jt * cb]).view(dtype).reshape(n_tiles, d, rows, jt)
+        full = np.zeros((n_tiles * jt, d, rows), dtype=dtype)
+        full[:m, :, :K * L] = np.transpose(want, (1, 0, 2))          # [j][i][row]
+        expect = np.transpose(full.reshape(n_tiles, jt, d, rows), (0, 2, 3, 1))                   # [t][i][row][column]
+        if cb == 4:
+            assert np.array_equal(got, expect)                       # (padding: 0 * -128 under y_min = 0 is +0)
+        else:
+            pad = np.zeros(expect.shape, dtype=bool)
+            pad[:, :, K * L:, :] = True
+            pad |= (np.arange(n_tiles * jt).reshape(n_tiles, jt) >= m)[:, None, None, :]
+            assert np.array_equal(got[~pad], expect[~pad])
+            # padding holds a code byte of 0 or the code 0 (excess-128: byte 0 reads as -128, under alpha = 0)
+            assert np.isin(got[pad], (0, 0x8080)).all()
+        if cb == 2:                                                  # everything before the code rows is the byte table's
+            byte = np.asarray(art.table).reshape(n_tiles, d, art.info.blob_bytes)
+            assert np.array_equal(host[:, :, :codes_off], byte[:, :, :codes_off])
+
+
 @pytest.mark.parametrize("base", [False, True], ids=["phi", "spline_component"])
 def test_largest_slices_with_the_largest_record_buffers_fill_the_lds(base):
     """The LDS budget at its edge: 64-column slices of 72 KiB (64 KiB with the base branch, whose records are 16 bytes)
