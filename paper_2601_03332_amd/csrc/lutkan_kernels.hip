@@ -975,24 +975,32 @@ int launch_tiled_np(const EdgeArgs &ea, hipStream_t s) {
     static LdsCap raised;                                                                                                        \
     return launch_with_lds(lutkan_tiled_kernel<SCH, LPR, NP, NW, BASE, PH, PIPE, CB>, &raised, grid, lds, s, ea, "lutkan_tiled_kernel"); \
   } while (0)
+  // binary16 parameter rows exist on tiles of at most 32 columns only (device_params_are_half), the wide forms of the
+  // table on 64-column tiles only: neither kernel variant is built for the other tile widths
+  constexpr bool kHalfParams = (LPR <= 8), kWideForms = (LPR == 16);
+  if (ea.param_fp16 && !kHalfParams) return fail(LUTKAN_EINVAL, "lutkan_tiled_kernel: binary16 parameter rows go with tiles of at most 32 columns");
+  if (ea.wide && !kWideForms) return fail(LUTKAN_EINVAL, "lutkan_tiled_kernel: the wide table goes with 64-column tiles");
   if (ea.with_base) {
     if (ea.wide) return fail(LUTKAN_EINVAL, "lutkan_tiled_kernel: the wide table goes with 8-byte records");
     LUTKAN_LAUNCH_TILED(SCHEME, true, false, 2, 1);
   }
-  if (ea.wide && LPR != 16) return fail(LUTKAN_EINVAL, "lutkan_tiled_kernel: the wide table goes with 64-column tiles");
-  if (pipe == 4) { if (ea.param_fp16) LUTKAN_LAUNCH_TILED(SCHEME, false, true, 4, 1); else LUTKAN_LAUNCH_TILED(SCHEME, false, false, 4, 1); }
-  if constexpr (LPR == 16) {
+  if constexpr (kHalfParams) {
+    if (ea.param_fp16) {
+      if (pipe == 4) LUTKAN_LAUNCH_TILED(SCHEME, false, true, 4, 1);
+      if constexpr (NP >= 2) { if (pipe == 3) LUTKAN_LAUNCH_TILED(SCHEME, false, true, 3, 1); }
+      LUTKAN_LAUNCH_TILED(SCHEME, false, true, 2, 1);
+    }
+  }
+  if constexpr (kWideForms) {
     if constexpr (NP >= 4) {
       if (pipe == 3 && ea.wide == 4) LUTKAN_LAUNCH_TILED(0, false, false, 3, 4);
-      if (pipe == 3 && ea.wide == 2) { if (ea.param_fp16) LUTKAN_LAUNCH_TILED(SCHEME, false, true, 3, 2); else LUTKAN_LAUNCH_TILED(SCHEME, false, false, 3, 2); }
+      if (pipe == 3 && ea.wide == 2) LUTKAN_LAUNCH_TILED(SCHEME, false, false, 3, 2);
     }
     if (ea.wide == 4) LUTKAN_LAUNCH_TILED(0, false, false, 2, 4);
-    if (ea.wide == 2) { if (ea.param_fp16) LUTKAN_LAUNCH_TILED(SCHEME, false, true, 2, 2); else LUTKAN_LAUNCH_TILED(SCHEME, false, false, 2, 2); }
+    if (ea.wide == 2) LUTKAN_LAUNCH_TILED(SCHEME, false, false, 2, 2);
   }
-  if constexpr (NP >= 2) {
-    if (pipe == 3) { if (ea.param_fp16) LUTKAN_LAUNCH_TILED(SCHEME, false, true, 3, 1); else LUTKAN_LAUNCH_TILED(SCHEME, false, false, 3, 1); }
-  }
-  if (ea.param_fp16) LUTKAN_LAUNCH_TILED(SCHEME, false, true, 2, 1);
+  if (pipe == 4) LUTKAN_LAUNCH_TILED(SCHEME, false, false, 4, 1);
+  if constexpr (NP >= 2) { if (pipe == 3) LUTKAN_LAUNCH_TILED(SCHEME, false, false, 3, 1); }
   LUTKAN_LAUNCH_TILED(SCHEME, false, false, 2, 1);
 #undef LUTKAN_LAUNCH_TILED
 }
@@ -1301,7 +1309,7 @@ struct WidenArgs {
   int32_t jt, src_blob, dst_blob, codes_off, n_code_rows;
   int32_t sym;
   // fp32 values only
-  int32_t params_off, param_row_bytes, L, K, param_fp16;
+  int32_t params_off, param_row_bytes, L, K;
 };
 
 // One work-group per slice (t, i).  Base row and parameter rows are copied as they are (16 bytes per thread and
@@ -1335,14 +1343,8 @@ __global__ __launch_bounds__(256) void lutkan_dequantise_kernel(const WidenArgs 
     const int byte = src[a.codes_off + e];
     const int q = a.sym ? byte - 128 : byte;
     const unsigned char *prow = src + a.params_off + (size_t)min(row / a.L, a.K) * a.param_row_bytes;
-    float alpha, y_min = 0.0f;
-    if (a.param_fp16) {
-      alpha = (float)reinterpret_cast<const _Float16 *>(prow)[col];
-      if (!a.sym) y_min = (float)reinterpret_cast<const _Float16 *>(prow)[a.jt + col];
-    } else {
-      alpha = reinterpret_cast<const float *>(prow)[col];
-      if (!a.sym) y_min = reinterpret_cast<const float *>(prow)[a.jt + col];
-    }
+    const float alpha = reinterpret_cast<const float *>(prow)[col];                   // (64-column tiles hold fp32 parameters)
+    const float y_min = a.sym ? 0.0f : reinterpret_cast<const float *>(prow)[a.jt + col];
     dv[e] = __fadd_rn(y_min, __fmul_rn(alpha, (float)q));
   }
   for (int e = a.params_off + n_codes * 4 + threadIdx.x; e < a.dst_blob; e += 256) dst[e] = 0;     // padding to 16 bytes
@@ -1377,7 +1379,7 @@ extern "C" int lutkan_wide_table_build(lutkan_dev_layer *layer, int32_t code_byt
   a.n_code_rows = layer->K * layer->L + 2;
   a.sym = (layer->scheme == LUTKAN_SYM_INT8);
   a.params_off = lay.params_off; a.param_row_bytes = lay.param_row_bytes; a.L = layer->L; a.K = layer->K;
-  a.param_fp16 = lutkan::device_params_are_half(layer->value_repr, layer->param_dtype, layer->jt);
+  if (lutkan::device_params_are_half(layer->value_repr, layer->param_dtype, layer->jt)) return fail(LUTKAN_EUNSUPPORTED, "%s: binary16 parameter rows", who);   // (not on 64-column tiles)
   const dim3 grid((unsigned)((int64_t)layer->n_tiles * layer->d));
   if (code_bytes == 2) hipLaunchKernelGGL(lutkan_widen_kernel, grid, dim3(256), 0, static_cast<hipStream_t>(hip_stream), a);
   else hipLaunchKernelGGL(lutkan_dequantise_kernel, grid, dim3(256), 0, static_cast<hipStream_t>(hip_stream), a);
