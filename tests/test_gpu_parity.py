@@ -156,6 +156,8 @@ WIDE_CASES = [
     (708, 64, 128, 5, 32, ASYM_UINT8, CLOSED, CLIP_X, 70000, True),             # spline_component: base branch as a product, 8-byte records
     (709, 24, 70, 6, 16, SYM_INT8, CLOSED, ZERO_SPLINE, 3000, True),            # spline_component with 16-byte records: the byte form runs
     (710, 64, 256, 8, 32, SYM_INT8, HALF_OPEN, CLIP_X, 16384 + 3, False),       # large enough for the launch planning to pick the wide form
+    (711, 20, 192, 5, 32, ASYM_UINT8, HALF_OPEN, ZERO_SPLINE, 5001, False),     # masked inputs on a layer that has both wide forms
+    (712, 96, 64, 3, 90, SYM_INT8, HALF_OPEN, ZERO_SPLINE, 33000, False),       # 272 value rows: the largest fp32 slices (two buffers)
 ]
 
 
