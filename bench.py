@@ -76,8 +76,8 @@ def make_workload(name, batch=None):
 # ------------------------------------------------------------------------------------------------ cost model
 def kernel_costs(info, spec, B, plan):
     """What each kernel launch of one lutkan_forward call must move and compute, from the layer's shape and the launch
-    plan the library reports (lutkan_last_plan): a list of dicts {kernel, hbm, l2, lds, valu} in bytes resp. vector
-    lane-instructions.  hbm = compulsory bytes (every operand once); l2 = bytes staged from L2 into LDS, or read
+    plan the library reports (lutkan_last_plan): a list of dicts {kernel, hbm, l2, lds, valu[, valu2]} in bytes resp. vector
+    lane-instructions (valu2: those in the two-operand fp32 encoding on registers, priced at their own rate).  hbm = compulsory bytes (every operand once); l2 = bytes staged from L2 into LDS, or read
     through L2 by the kernels that gather from global memory; lds = bytes the lanes read from LDS plus the staged
     bytes written into it; valu = lane-instructions of the inner loops (counted for the tiled kernel, estimated for
     the kernels that are bound by memory latency)."""
@@ -113,8 +113,11 @@ def kernel_costs(info, spec, B, plan):
             per4 = (13 if wide == 4 else (16 if asym else 12) if wide else (20 if asym else 18)) + (4 if base else 0)
             # record, two code rows, alpha (+ y_min) per lane
             lds_per4 = (12 if base else 8) + (32 if wide == 4 else (16 if wide else 8) + (32 if asym else 16))
+            # on fp32 values all but the address instruction are two-operand fp32 instructions on registers, which
+            # issue about twice as fast as the rest: counted apart (valu2) and priced at their own rate
+            valu2 = edges / 4 * 12 if wide == 4 else 0
             out.append(dict(kernel="lutkan_tiled_kernel", hbm=table_bytes + rec * Bp * d + 4 * B * m * last_split,
-                            l2=staged, lds=edges / 4 * lds_per4 + staged, valu=edges / 4 * per4))
+                            l2=staged, lds=edges / 4 * lds_per4 + staged, valu=edges / 4 * per4 - valu2, valu2=valu2))
         elif clause.startswith("gather"):
             last_split = nums[0]
             touched = min(info.table_bytes, B * d * info.n_tiles * info.jt * (2 + prm))
@@ -138,9 +141,12 @@ def kernel_costs(info, spec, B, plan):
 def price(costs, rates):
     """Lower bound of one forward = sum over its kernels of the largest of that kernel's resource times; the binding
     resource is the one that contributes most to that sum."""
+    rates = dict(rates)
+    rate2 = rates.pop("valu2")
     total, by_resource, share = 0.0, {r: 0.0 for r in rates}, {r: 0.0 for r in rates}
     for c in costs:
         t = {r: c[r] / rates[r] for r in rates}
+        t["valu"] += c.get("valu2", 0) / rate2                # the same issue port: the two classes add up
         worst = max(t, key=t.get)
         total += t[worst]
         share[worst] += t[worst]
@@ -290,16 +296,18 @@ def run_workload(rig, name, steps, warmup, batch=None, bspline=True, cpu_baselin
     dom_edges = B * dspec.d * dspec.m
 
     # ---- roofline terms of the whole forward
-    published = {"hbm": PEAK_HBM_BPS, "lds": PEAK_LDS_BPS, "valu": PEAK_LANE_INSTR}
+    published = {"hbm": PEAK_HBM_BPS, "lds": PEAK_LDS_BPS, "valu": PEAK_LANE_INSTR, "valu2": 2 * PEAK_LANE_INSTR}
     t_pub, by_pub, bind_pub = price(costs, published)
     terms = {"at_published_or_derived_peaks_ms": {k: round(v * 1e3, 5) for k, v in by_pub.items()},
              "lower_bound_at_peaks_ms": round(t_pub * 1e3, 5), "binding_at_peaks": bind_pub,
              "frac_of_bound_at_peaks": round(t_pub / dt, 4),
-             "work": {r: float(sum(c[r] for c in costs)) for r in ("hbm", "l2", "lds", "valu")},
-             "peaks": {"hbm_Bps_published": PEAK_HBM_BPS, "lds_Bps_derived": PEAK_LDS_BPS, "valu_lane_instr_derived": PEAK_LANE_INSTR}}
+             "work": {r: float(sum(c.get(r, 0) for c in costs)) for r in ("hbm", "l2", "lds", "valu", "valu2")},
+             "peaks": {"hbm_Bps_published": PEAK_HBM_BPS, "lds_Bps_derived": PEAK_LDS_BPS, "valu_lane_instr_derived": PEAK_LANE_INSTR,
+                       "valu2_lane_instr_derived": 2 * PEAK_LANE_INSTR}}
     if rig.measured:
         ms = rig.measured
-        measured = {"hbm": ms["hbm_read_Bps"], "l2": ms["l2_read_Bps"], "lds": ms["lds_read_Bps"], "valu": ms["fp32_fma_flops"] / 2.0}
+        measured = {"hbm": ms["hbm_read_Bps"], "l2": ms["l2_read_Bps"], "lds": ms["lds_read_Bps"], "valu": ms["fp32_fma_flops"] / 2.0,
+                    "valu2": ms["fp32_fmac_two_operand_flops"] / 2.0}
         t_ms, by_ms, bind_ms = price(costs, measured)
         t_mix, by_mix, _ = price(costs, dict(measured, valu=ms["kernel_mix_lane_instr"]))
         terms.update({"at_measured_rates_ms": {k: round(v * 1e3, 5) for k, v in by_ms.items()},
@@ -312,7 +320,8 @@ def run_workload(rig, name, steps, warmup, batch=None, bspline=True, cpu_baselin
     # ---- roofline record of the dominant kernel
     k_s = dominant["ms"] * 1e-3
     hbm_bytes = sum(c["hbm"] for c in dom_costs)
-    t_dom = {"hbm": hbm_bytes / PEAK_HBM_BPS, "valu": sum(c["valu"] for c in dom_costs) / PEAK_LANE_INSTR,
+    t_dom = {"hbm": hbm_bytes / PEAK_HBM_BPS,
+             "valu": sum(c["valu"] + c.get("valu2", 0) / 2 for c in dom_costs) / PEAK_LANE_INSTR,
              "lds": sum(c["lds"] for c in dom_costs) / PEAK_LDS_BPS}
     traffic, source = traffic_from_profiles(name, dominant["kernel"].split(" + ")[0])
     if max(t_dom, key=t_dom.get) == "hbm":
@@ -332,7 +341,8 @@ def run_workload(rig, name, steps, warmup, batch=None, bspline=True, cpu_baselin
     if "wide32" in dominant["plan"]:
         roofline["note"] = ("this launch reads the table's fp32-value form: Eq. 10 was applied when that table was built, so 5 of the "
                             "8 algorithmic flops per edge evaluation execute in the kernel (13 vector instructions per 4 edges); "
-                            "'achieved' counts all 8")
+                            "'achieved' counts all 8; at derived peaks the model gives this launch %.4f ms of vector instructions "
+                            "and %.4f ms of LDS traffic: the LDS is its nearest bound" % (t_dom["valu"] * 1e3, t_dom["lds"] * 1e3))
     roofline.update({"traffic": traffic, "traffic_source": source, "kernel_ms": round(dominant["ms"], 5), "layer": dominant["layer"],
                      "launch_plan": dominant["plan"], "compulsory_hbm_bytes": int(hbm_bytes),
                      "hbm_time_floor_ms": round(hbm_bytes / PEAK_HBM_BPS * 1e3, 5), "terms": terms})
