@@ -219,8 +219,8 @@ def main():
 
         print()
         print("Layer forward over batch sizes (AUTO picks the kernel): ms, 10^9 edge-evaluations/s, B-spline ms, B-spline / LUT")
-        for d, m, G, L, scheme in ((78, 16, 5, 64, ASYM_UINT8), (128, 8, 5, 32, ASYM_UINT8), (256, 256, 8, 64, SYM_INT8),
-                                   (1024, 64, 10, 64, SYM_INT8), (1024, 1024, 10, 64, SYM_INT8)):
+        for d, m, G, L, scheme in ((78, 16, 5, 64, ASYM_UINT8), (128, 8, 5, 32, ASYM_UINT8), (128, 128, 5, 32, ASYM_UINT8),
+                                   (256, 256, 8, 64, SYM_INT8), (1024, 64, 10, 64, SYM_INT8), (1024, 1024, 10, 64, SYM_INT8)):
             sp = random_layer(3, d, m, G, L, scheme, CLOSED, CLIP_X, 4).layers[0]
             art = lk.lutkan_compile(d, m, G, 3, sp.ext_knots, sp.coef, L, scheme, CLOSED, CLIP_X)
             layer, bl = art.to_device(dev), art.bspline_to_device(dev)
@@ -232,7 +232,8 @@ def main():
                 t = event_ms2(lambda: lk.lutkan_forward(layer, x, y, workspace=ws))
                 wsb = torch.empty(lk.bspline_forward_workspace_bytes(bl, B), dtype=torch.uint8, device=dev)
                 tb = event_ms2(lambda: lk.bspline_kan_forward(bl, x, y, workspace=wsb))
-                print(f"  B = {B:>6}: {t:8.4f} ms {B * d * m / t / 1e6:9.1f} | {tb:8.4f} ms  {tb / t:5.2f}")
+                lk.lutkan_forward(layer, x, y, workspace=ws)
+                print(f"  B = {B:>6}: {t:8.4f} ms {B * d * m / t / 1e6:9.1f} | {tb:8.4f} ms  {tb / t:5.2f}   [{lk.lutkan_last_plan().strip()}]")
                 del x, y, ws, wsb
 
     if args.latency:
