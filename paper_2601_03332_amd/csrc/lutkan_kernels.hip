@@ -653,52 +653,52 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
           acc[p][c] += v[c];
         }
       } else {
-      float al[4], ym[4];
-      if constexpr (PH) {
-        const f16x2 a01 = bits_to_f16x2(__float_as_uint(f_cur.pa.x)), a23 = bits_to_f16x2(__float_as_uint(f_cur.pa.y));
-        const f16x2 y01 = bits_to_f16x2(__float_as_uint(f_cur.pb.x)), y23 = bits_to_f16x2(__float_as_uint(f_cur.pb.y));
-        al[0] = (float)a01.x; al[1] = (float)a01.y; al[2] = (float)a23.x; al[3] = (float)a23.y;
-        ym[0] = (float)y01.x; ym[1] = (float)y01.y; ym[2] = (float)y23.x; ym[3] = (float)y23.y;
-      } else {
-        al[0] = f_cur.pa.x; al[1] = f_cur.pa.y; al[2] = f_cur.pa.z; al[3] = f_cur.pa.w;
-        ym[0] = f_cur.pb.x; ym[1] = f_cur.pb.y; ym[2] = f_cur.pb.z; ym[3] = f_cur.pb.w;
-      }
-      f16x2 q0lo, q0hi, q1lo, q1hi;
-      if constexpr (WIDE) {                                                    // the table holds q * 2^-24 as it is needed
-        q0lo = bits_to_f16x2(f_cur.c0); q0hi = bits_to_f16x2(f_cur.c0b);
-        q1lo = bits_to_f16x2(f_cur.c1); q1hi = bits_to_f16x2(f_cur.c1b);
-      } else {
-        // bytes {b3,b2,b1,b0} -> packed fp16 denormals {b1,b0} and {b3,b2}, each worth byte * 2^-24
-        q0lo = bits_to_f16x2(__builtin_amdgcn_perm(f_cur.c0, f_cur.c0, 0x0c010c00u));
-        q0hi = bits_to_f16x2(__builtin_amdgcn_perm(f_cur.c0, f_cur.c0, 0x0c030c02u));
-        q1lo = bits_to_f16x2(__builtin_amdgcn_perm(f_cur.c1, f_cur.c1, 0x0c010c00u));
-        q1hi = bits_to_f16x2(__builtin_amdgcn_perm(f_cur.c1, f_cur.c1, 0x0c030c02u));
-      }
-      const f16x2 dlo = q1lo - q0lo, dhi = q1hi - q0hi;                        // (q1 - q0) * 2^-24, exact
-      if (SCHEME == LUTKAN_SYM_INT8 && !WIDE) {                                // remove the excess-128 bias, exact
-        const f16x2 bias = bits_to_f16x2(0x00800080u);
-        q0lo = q0lo - bias;
-        q0hi = q0hi - bias;
-      }
-      const float t0 = fmaf(w, (float)dlo.x, (float)q0lo.x);                   // one rounding each
-      const float t1 = fmaf(w, (float)dlo.y, (float)q0lo.y);
-      const float t2 = fmaf(w, (float)dhi.x, (float)q0hi.x);
-      const float t3 = fmaf(w, (float)dhi.y, (float)q0hi.y);
-      acc[p][0] = fmaf(al[0], t0, acc[p][0]);
-      acc[p][1] = fmaf(al[1], t1, acc[p][1]);
-      acc[p][2] = fmaf(al[2], t2, acc[p][2]);
-      acc[p][3] = fmaf(al[3], t3, acc[p][3]);
-      if (SCHEME == LUTKAN_ASYM_UINT8) {
+        float al[4], ym[4];
+        if constexpr (PH) {
+          const f16x2 a01 = bits_to_f16x2(__float_as_uint(f_cur.pa.x)), a23 = bits_to_f16x2(__float_as_uint(f_cur.pa.y));
+          const f16x2 y01 = bits_to_f16x2(__float_as_uint(f_cur.pb.x)), y23 = bits_to_f16x2(__float_as_uint(f_cur.pb.y));
+          al[0] = (float)a01.x; al[1] = (float)a01.y; al[2] = (float)a23.x; al[3] = (float)a23.y;
+          ym[0] = (float)y01.x; ym[1] = (float)y01.y; ym[2] = (float)y23.x; ym[3] = (float)y23.y;
+        } else {
+          al[0] = f_cur.pa.x; al[1] = f_cur.pa.y; al[2] = f_cur.pa.z; al[3] = f_cur.pa.w;
+          ym[0] = f_cur.pb.x; ym[1] = f_cur.pb.y; ym[2] = f_cur.pb.z; ym[3] = f_cur.pb.w;
+        }
+        f16x2 q0lo, q0hi, q1lo, q1hi;
+        if constexpr (WIDE) {                                                    // the table holds q * 2^-24 as it is needed
+          q0lo = bits_to_f16x2(f_cur.c0); q0hi = bits_to_f16x2(f_cur.c0b);
+          q1lo = bits_to_f16x2(f_cur.c1); q1hi = bits_to_f16x2(f_cur.c1b);
+        } else {
+          // bytes {b3,b2,b1,b0} -> packed fp16 denormals {b1,b0} and {b3,b2}, each worth byte * 2^-24
+          q0lo = bits_to_f16x2(__builtin_amdgcn_perm(f_cur.c0, f_cur.c0, 0x0c010c00u));
+          q0hi = bits_to_f16x2(__builtin_amdgcn_perm(f_cur.c0, f_cur.c0, 0x0c030c02u));
+          q1lo = bits_to_f16x2(__builtin_amdgcn_perm(f_cur.c1, f_cur.c1, 0x0c010c00u));
+          q1hi = bits_to_f16x2(__builtin_amdgcn_perm(f_cur.c1, f_cur.c1, 0x0c030c02u));
+        }
+        const f16x2 dlo = q1lo - q0lo, dhi = q1hi - q0hi;                        // (q1 - q0) * 2^-24, exact
+        if (SCHEME == LUTKAN_SYM_INT8 && !WIDE) {                                // remove the excess-128 bias, exact
+          const f16x2 bias = bits_to_f16x2(0x00800080u);
+          q0lo = q0lo - bias;
+          q0hi = q0hi - bias;
+        }
+        const float t0 = fmaf(w, (float)dlo.x, (float)q0lo.x);                   // one rounding each
+        const float t1 = fmaf(w, (float)dlo.y, (float)q0lo.y);
+        const float t2 = fmaf(w, (float)dhi.x, (float)q0hi.x);
+        const float t3 = fmaf(w, (float)dhi.y, (float)q0hi.y);
+        acc[p][0] = fmaf(al[0], t0, acc[p][0]);
+        acc[p][1] = fmaf(al[1], t1, acc[p][1]);
+        acc[p][2] = fmaf(al[2], t2, acc[p][2]);
+        acc[p][3] = fmaf(al[3], t3, acc[p][3]);
+        if (SCHEME == LUTKAN_ASYM_UINT8) {
 #pragma unroll
-        for (int c = 0; c < 4; ++c) acc[p][c] = fmaf(ym[c], kTwoToMinus24, acc[p][c]);
-      }
-      if constexpr (BASE) {
-        const float silu_x = __uint_as_float(rc_cur.z);
-        acc[p][0] = fmaf(base_gain.x, silu_x, acc[p][0]);
-        acc[p][1] = fmaf(base_gain.y, silu_x, acc[p][1]);
-        acc[p][2] = fmaf(base_gain.z, silu_x, acc[p][2]);
-        acc[p][3] = fmaf(base_gain.w, silu_x, acc[p][3]);
-      }
+          for (int c = 0; c < 4; ++c) acc[p][c] = fmaf(ym[c], kTwoToMinus24, acc[p][c]);
+        }
+        if constexpr (BASE) {
+          const float silu_x = __uint_as_float(rc_cur.z);
+          acc[p][0] = fmaf(base_gain.x, silu_x, acc[p][0]);
+          acc[p][1] = fmaf(base_gain.y, silu_x, acc[p][1]);
+          acc[p][2] = fmaf(base_gain.z, silu_x, acc[p][2]);
+          acc[p][3] = fmaf(base_gain.w, silu_x, acc[p][3]);
+        }
       }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
