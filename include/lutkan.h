@@ -46,7 +46,7 @@ typedef enum { LUTKAN_CLIP_X = 0, LUTKAN_ZERO_SPLINE = 1 } lutkan_oob;          
  * lutkan_forward runs as a one-layer launch of the fused chain kernel;
  * results agree to rounding, not bit for bit.  TILED (and AUTO) take the table's wide form, where the layer holds one
  * (lutkan_wide_table_build), when the launch planning prices it lower; TILED_WIDE takes it whatever the price and is
- * an error for a layer without one or a call it does not serve (16-byte records).  LUT layers only. */
+ * an error for a layer without one or a call it does not serve (16-bit codes with 16-byte records).  LUT layers only. */
 typedef enum { LUTKAN_ALGO_AUTO = 0, LUTKAN_ALGO_GATHER = 1, LUTKAN_ALGO_TILED = 2, LUTKAN_ALGO_TILED_WIDE = 3 } lutkan_algo;
 typedef enum { LUTKAN_REPR_PHI = 0, LUTKAN_REPR_SPLINE_COMPONENT = 1 } lutkan_value_repr;  /* Sec. 4.3 A / B */
 typedef enum { LUTKAN_PARAM_FP32 = 0, LUTKAN_PARAM_FP16 = 1 } lutkan_param_dtype;   /* Sec. 4.6: dtype of scale, y_min */
@@ -230,7 +230,9 @@ int bspline_dev_layer_init(const lutkan_artifact *a, bspline_dev_layer *out);
  * fits the LDS twice (K*L up to about 540 rows with 2 bytes per code, 285 with 4): on narrower tiles the LDS reads, not
  * the instructions, bound the kernel.  A forward call uses the form a layer holds on the tiled kernel when its launch
  * planning prices it below the byte form (large batches; the 2-byte form only for symmetric codes -- with y_min it
- * measured on par with the byte form); algo = TILED_WIDE takes it whatever the price.
+ * measured on par with the byte form); algo = TILED_WIDE takes it whatever the price.  A spline_component layer whose
+ * base branch runs inside the edge kernel (16-byte records: calls below 5e8 edges) can use only the fp32 values, and
+ * only if a slice of them is at most 64 KiB.
  * lutkan_wide_table_bytes: size of that form of the layer's table, 0 if the layer has none.
  * lutkan_wide_table_build: fills `wide_table` (device, 16-byte aligned, at least that many bytes) from layer->table on
  * `hip_stream` and sets layer->wide_table, wide_blob_bytes and wide_code_bytes; the layer may be used on that stream

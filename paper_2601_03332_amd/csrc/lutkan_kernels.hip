@@ -456,7 +456,7 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
   static_assert(!(BASE && PH), "with the base branch the device table holds fp32 products, never binary16 parameters");
   static_assert(CB == 1 || CB == 2 || CB == 4, "bytes per code");
   constexpr bool WIDE = (CB == 2), VALUES = (CB == 4);
-  static_assert(!(BASE && CB != 1), "the wide forms are used with 8-byte records only");
+  static_assert(!(BASE && CB == 2), "the form with 16-bit codes is used with 8-byte records only");
   static_assert(!(VALUES && (PH || SCHEME != 0)), "the fp32 values are the same for both schemes and any parameter type: one instance");
   static_assert(PIPE == 2 || (PIPE == 3 && !BASE && NP >= 2) || (PIPE == 4 && !BASE), "carried reads need two row steps of the same input; three buffers go with 8-byte records");
   constexpr int NBUF = (PIPE == 2) ? 2 : 3;
@@ -621,7 +621,7 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
     unsigned ahead_codes = col_codes, ahead_params = col_params;
     if (CARRY) columns_of(ahead, ahead_codes, ahead_params);
     f32x4 base_gain = {0.f, 0.f, 0.f, 0.f};
-    if (BASE) base_gain = *reinterpret_cast<const f32x4 *>(slice + sub * 16) * kTwoToMinus24;
+    if (BASE) base_gain = *reinterpret_cast<const f32x4 *>(slice + sub * 16) * (VALUES ? 1.0f : kTwoToMinus24);   // (the sums on fp32 values are not scaled)
     if (!CARRY) fill_read_pipeline(rec_buf, col_codes, col_params);
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
@@ -651,6 +651,13 @@ __global__ __launch_bounds__(NW * 64) void lutkan_tiled_kernel(const EdgeArgs a)
         for (int c = 0; c < 4; ++c) {
           asm("v_fmac_f32 %0, %1, %2" : "+v"(v[c]) : "v"(w), "v"(dv[c]));
           acc[p][c] += v[c];
+        }
+        if constexpr (BASE) {
+          const float silu_x = __uint_as_float(rc_cur.z);
+          acc[p][0] = fmaf(base_gain.x, silu_x, acc[p][0]);
+          acc[p][1] = fmaf(base_gain.y, silu_x, acc[p][1]);
+          acc[p][2] = fmaf(base_gain.z, silu_x, acc[p][2]);
+          acc[p][3] = fmaf(base_gain.w, silu_x, acc[p][3]);
         }
       } else {
         float al[4], ym[4];
@@ -981,7 +988,8 @@ int launch_tiled_np(const EdgeArgs &ea, hipStream_t s) {
   if (ea.param_fp16 && !kHalfParams) return fail(LUTKAN_EINVAL, "lutkan_tiled_kernel: binary16 parameter rows go with tiles of at most 32 columns");
   if (ea.wide && !kWideForms) return fail(LUTKAN_EINVAL, "lutkan_tiled_kernel: the wide table goes with 64-column tiles");
   if (ea.with_base) {
-    if (ea.wide) return fail(LUTKAN_EINVAL, "lutkan_tiled_kernel: the wide table goes with 8-byte records");
+    if (ea.wide == 2) return fail(LUTKAN_EINVAL, "lutkan_tiled_kernel: the table with 16-bit codes goes with 8-byte records");
+    if constexpr (kWideForms) { if (ea.wide == 4) LUTKAN_LAUNCH_TILED(0, true, false, 2, 4); }
     LUTKAN_LAUNCH_TILED(SCHEME, true, false, 2, 1);
   }
   if constexpr (kHalfParams) {
@@ -1145,14 +1153,17 @@ int forward_impl(const lutkan_dev_layer *l, const float *x, int64_t B, float *y,
   const int rec_bytes = (with_base && !base_by_product) ? 16 : 8;
   // A wide form of the table (16-bit codes or fp32 values: fewer vector instructions per edge, two or four times the
   // table bytes), where the layer has one and the launch planning prices it lower.
-  const bool can_wide = tiled && l->wide_table != nullptr && rec_bytes == 8;
+  // With 16-byte records (the base branch inside the edge kernel) only the fp32 values can be used, and their slice
+  // must leave room for the larger record buffers.
   const int wide_cb = l->wide_code_bytes;
+  const bool can_wide = tiled && l->wide_table != nullptr &&
+                        (rec_bytes == 8 || (wide_cb == 4 && l->wide_blob_bytes <= lutkan::lds_slice_budget(LUTKAN_REPR_SPLINE_COMPONENT)));
   const TilePlan tpw = can_wide ? plan_tiles(B, l->d, l->m, l->n_tiles, 64 / (l->jt / 4), l->wide_blob_bytes, wide_cb) : tp;
   // (with y_min the row step on 16-bit codes reads 56 bytes per lane from LDS and measured within 3 % of the byte form
   // either way on 256x256 and 128x128 layers: left to the byte form unless asked for)
   const bool wide = can_wide && ((tpw.cost < tp.cost && (wide_cb == 4 || l->scheme == LUTKAN_SYM_INT8)) || l->algo == LUTKAN_ALGO_TILED_WIDE);
   if (l->algo == LUTKAN_ALGO_TILED_WIDE && !wide)
-    return fail(LUTKAN_EUNSUPPORTED, "%s: algo TILED_WIDE on a layer %s", who, l->wide_table ? "whose base branch runs inside the edge kernel (16-byte records)" : "without a wide table");
+    return fail(LUTKAN_EUNSUPPORTED, "%s: algo TILED_WIDE on a layer %s", who, l->wide_table ? "whose base branch runs inside the edge kernel (16-byte records: fp32 values of at most 64 KiB per slice only)" : "without a wide table");
   // workspace: [records: room for 16 bytes each with the base branch; 8-byte records leave room for the 6 bytes per
   // (row, input) of the SiLU pieces behind them] [pieces of s_out*s_base, spline_component only] [partial sums]
   char *const ws_bytes = static_cast<char *>(workspace);

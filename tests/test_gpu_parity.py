@@ -154,7 +154,8 @@ WIDE_CASES = [
     (706, 300, 64, 5, 32, SYM_INT8, HALF_OPEN, CLIP_X, 9000, False),            # many inputs: chunks and the summing pass
     (707, 3, 1000, 10, 50, SYM_INT8, HALF_OPEN, ZERO_SPLINE, 20000, False),     # 16 column tiles, three slice buffers
     (708, 64, 128, 5, 32, ASYM_UINT8, CLOSED, CLIP_X, 70000, True),             # spline_component: base branch as a product, 8-byte records
-    (709, 24, 70, 6, 16, SYM_INT8, CLOSED, ZERO_SPLINE, 3000, True),            # spline_component with 16-byte records: the byte form runs
+    (709, 24, 70, 6, 16, SYM_INT8, CLOSED, ZERO_SPLINE, 3000, True),            # spline_component with 16-byte records: byte form or fp32 values
+    (713, 40, 128, 5, 32, ASYM_UINT8, HALF_OPEN, CLIP_X, 20000, True),          # the same at 16 row steps per wave
     (710, 64, 256, 8, 32, SYM_INT8, HALF_OPEN, CLIP_X, 16384 + 3, False),       # large enough for the launch planning to pick the wide form
     (711, 20, 192, 5, 32, ASYM_UINT8, HALF_OPEN, ZERO_SPLINE, 5001, False),     # masked inputs on a layer that has both wide forms
     (712, 96, 64, 3, 90, SYM_INT8, HALF_OPEN, ZERO_SPLINE, 33000, False),       # 272 value rows: the largest fp32 slices (two buffers)
@@ -191,8 +192,8 @@ def test_wide_table_form(case, cb):
         assert wide.wide_table.numel() == art.info.n_tiles * d * (art.info.K * L + 2 + with_base) * 256
         assert art.to_device(DEV, wide=True).c.wide_code_bytes == 4
     xg = torch.from_numpy(x).to(DEV)
-    if with_base and B * d * m < 5e8:
-        # 16-byte records (the base branch inside the edge kernel) go with the byte form only
+    if with_base and B * d * m < 5e8 and cb == 2:
+        # 16-byte records (the base branch inside the edge kernel) go with the byte form or with fp32 values
         with pytest.raises(lk.LutKanError) as e:
             lk.lutkan_forward(wide, xg)
         assert str(e.value).startswith("[-5]") and "16-byte records" in str(e.value)
